@@ -1,0 +1,339 @@
+/*
+ * CPU oracle for native quantization-aware training's quantized dense layer
+ * (arxiv 2203.15952).  TEST INFRASTRUCTURE ONLY: it is the slow, plain
+ * statement of what the method computes, used to check the HIP library and to
+ * serve as the timed CPU baseline.  It shares no code with the HIP library and
+ * the product path never calls it.
+ *
+ * What each function follows:
+ *   oracle_quantize*      Fig. 2 (abs-max -> scale -> divide_no_nan -> +0.5 ->
+ *                         floor -> cast) and Sec. 2.2 (divide the maximum by 127
+ *                         for int8, by 7 for int4; channel-wise via the reduced
+ *                         axis; no zero point).
+ *   oracle_pack_int4      int4 storage implied by the model sizes of Table 1
+ *                         (half a byte per quantized parameter); the nibble
+ *                         order is this build's choice.
+ *   oracle_dense_fwd*     Sec. 1 and Sec. 2.2: quantize both operands, multiply
+ *                         as integers, de-quantize by multiplying with the
+ *                         scales.
+ *   oracle_dense_bwd      Fig. 2's stop_gradient on the scale; the rounding is
+ *                         passed straight through (the paper does not state it,
+ *                         straight-through is the standard reading of QAT).
+ *
+ * Arithmetic: the quantizer is binary32, one rounding per operation, because
+ * the paper's listing is float32 TensorFlow and the codes depend on it.  The
+ * contraction accumulates in int64 (and reports whether it would have fitted
+ * int32).  De-quantization, epilogues and gradients are evaluated in binary64.
+ * Build with -O2 -ffp-contract=off and without -ffast-math.
+ *
+ * Parity pins: every function here is pinned by tests that do not call it to
+ * produce their expected values (tie table, range, half-step error bound,
+ * integer-valued special case against an int64 library matmul, power-of-two
+ * equivariance, an independent binary32-emulating brute force, the method's
+ * error bound against the float product, gradients against a library float64
+ * matmul of the de-quantized operands, hand-packed bytes).  The paper prints
+ * no worked numeric example, so no pin comes from printed values.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_AXIS_ALL (-1)
+#define ORACLE_EPI_NONE 0
+#define ORACLE_EPI_SWISH 1
+#define ORACLE_EPI_GLU 2
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+static int qmax_of(int bits) { return (1 << (bits - 1)) - 1; }
+
+/* One element of Fig. 2 given its group's scale.  Returns the code; *pass is 1
+ * when the rounded value needed no saturation and the scale is non-zero. */
+static int8_t quantize_one(float x, float s, int qmax, uint8_t *pass) {
+  float t = (s == 0.0f) ? 0.0f : x / s; /* divide_no_nan */
+  float u = t + 0.5f;
+  float r = floorf(u);
+  int in_range = (r >= (float)(-qmax)) && (r <= (float)qmax);
+  float c = r;
+  if (c > (float)qmax) c = (float)qmax;
+  if (c < (float)(-qmax)) c = (float)(-qmax);
+  if (pass) *pass = (uint8_t)(in_range && (s != 0.0f));
+  return (int8_t)c;
+}
+
+/* Scale of one reduction group: maximum magnitude divided by qmax (Sec. 2.2). */
+static float scale_of(float m, int qmax) { return m / (float)qmax; }
+
+/*
+ * Fig. 2 with the bit-width rule of Sec. 2.2.  x is [rows, cols] row-major.
+ * axis names the REDUCED axes: ORACLE_AXIS_ALL -> one scale; 0 -> reduce over
+ * rows, one scale per column; 1 -> reduce over columns, one scale per row.
+ * q: [rows, cols] codes.  scale: 1, cols or rows floats.  mask: nullable,
+ * one byte per element (1 = gradient passes).
+ * Returns 0, or 1 if a group's maximum is not finite (outputs then unspecified).
+ */
+int oracle_quantize(const float *x, int64_t rows, int64_t cols, int bits, int axis,
+                    int8_t *q, float *scale, uint8_t *mask) {
+  const int qmax = qmax_of(bits);
+  int bad = 0;
+  if (axis == ORACLE_AXIS_ALL) {
+    float m = 0.0f;
+    for (int64_t i = 0; i < rows * cols; ++i) {
+      float a = fabsf(x[i]);
+      if (!isfinite(a)) return 1;
+      if (a > m) m = a;
+    }
+    float s = scale_of(m, qmax);
+    scale[0] = s;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows * cols; ++i)
+      q[i] = quantize_one(x[i], s, qmax, mask ? &mask[i] : NULL);
+  } else if (axis == 0) {
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t c = 0; c < cols; ++c) {
+      float m = 0.0f;
+      int nonfinite = 0;
+      for (int64_t r = 0; r < rows; ++r) {
+        float a = fabsf(x[r * cols + c]);
+        if (!isfinite(a)) nonfinite = 1;
+        if (a > m) m = a;
+      }
+      if (nonfinite) { bad |= 1; continue; }
+      float s = scale_of(m, qmax);
+      scale[c] = s;
+      for (int64_t r = 0; r < rows; ++r)
+        q[r * cols + c] = quantize_one(x[r * cols + c], s, qmax, mask ? &mask[r * cols + c] : NULL);
+    }
+  } else if (axis == 1) {
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t r = 0; r < rows; ++r) {
+      float m = 0.0f;
+      int nonfinite = 0;
+      for (int64_t c = 0; c < cols; ++c) {
+        float a = fabsf(x[r * cols + c]);
+        if (!isfinite(a)) nonfinite = 1;
+        if (a > m) m = a;
+      }
+      if (nonfinite) { bad |= 1; continue; }
+      float s = scale_of(m, qmax);
+      scale[r] = s;
+      for (int64_t c = 0; c < cols; ++c)
+        q[r * cols + c] = quantize_one(x[r * cols + c], s, qmax, mask ? &mask[r * cols + c] : NULL);
+    }
+  } else {
+    return 2;
+  }
+  return bad;
+}
+
+/*
+ * The element-wise half of Fig. 2 with scales supplied by the caller instead of
+ * derived from the data.  Only this form can saturate, so it is what exercises
+ * a clip mask that is not all ones.  Same layout and axis meaning as above.
+ */
+int oracle_quantize_with_scale(const float *x, int64_t rows, int64_t cols, int bits, int axis,
+                               const float *scale, int8_t *q, uint8_t *mask) {
+  const int qmax = qmax_of(bits);
+  if (axis != ORACLE_AXIS_ALL && axis != 0 && axis != 1) return 2;
+  for (int64_t r = 0; r < rows; ++r)
+    for (int64_t c = 0; c < cols; ++c) {
+      float s = (axis == ORACLE_AXIS_ALL) ? scale[0] : (axis == 0 ? scale[c] : scale[r]);
+      int64_t i = r * cols + c;
+      q[i] = quantize_one(x[i], s, qmax, mask ? &mask[i] : NULL);
+    }
+  return 0;
+}
+
+/*
+ * int4 storage: codes [K, N] (K = fan-in) -> bytes [N][ceil(K/2)], fan-in
+ * contiguous.  Byte j of channel n holds k = 2j in its low nibble and k = 2j+1
+ * in its high nibble, both two's complement; an odd K leaves the last high
+ * nibble zero.
+ */
+void oracle_pack_int4(const int8_t *codes_kn, int64_t K, int64_t N, uint8_t *bytes) {
+  const int64_t kb = (K + 1) / 2;
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t j = 0; j < kb; ++j) {
+      uint8_t lo = (uint8_t)codes_kn[(2 * j) * N + n] & 0xF;
+      uint8_t hi = (2 * j + 1 < K) ? ((uint8_t)codes_kn[(2 * j + 1) * N + n] & 0xF) : 0;
+      bytes[n * kb + j] = (uint8_t)(lo | (hi << 4));
+    }
+}
+
+static double sigmoid64(double v) { return 1.0 / (1.0 + exp(-v)); }
+
+/*
+ * Integer contraction and de-quantization on already-quantized operands
+ * (Sec. 2.2: de-quantize by multiplying with the scales).
+ * xq [M,K] codes, s_x scalar, wq_kn [K,N] codes, s_w [N], bias nullable [N].
+ * acc (nullable) [M,N] receives the integer sums as int32; y is [M,N] doubles,
+ * or [M,N/2] for GLU (first half of the channels is the value, second half the
+ * gate).  pre (nullable) [M,N] receives the de-quantized value before the
+ * activation.  Returns 0, or 3 if any integer sum does not fit int32.
+ */
+int oracle_dense_fwd_q(const int8_t *xq, float s_x, const int8_t *wq_kn, const float *s_w,
+                       int64_t M, int64_t K, int64_t N, const float *bias, int epilogue,
+                       int32_t *acc, double *y, double *pre) {
+  int overflow = 0;
+  if (epilogue == ORACLE_EPI_GLU && (N % 2)) return 2;
+#pragma omp parallel for schedule(static) reduction(| : overflow)
+  for (int64_t m = 0; m < M; ++m) {
+    double *v = (double *)malloc((size_t)N * sizeof(double));
+    for (int64_t n = 0; n < N; ++n) {
+      int64_t a = 0;
+      for (int64_t k = 0; k < K; ++k) a += (int64_t)xq[m * K + k] * (int64_t)wq_kn[k * N + n];
+      if (a > INT32_MAX || a < INT32_MIN) overflow |= 1;
+      if (acc) acc[m * N + n] = (int32_t)a;
+      double d = (double)a * (double)s_x * (double)s_w[n];
+      if (bias) d += (double)bias[n];
+      v[n] = d;
+      if (pre) pre[m * N + n] = d;
+    }
+    if (epilogue == ORACLE_EPI_NONE) {
+      for (int64_t n = 0; n < N; ++n) y[m * N + n] = v[n];
+    } else if (epilogue == ORACLE_EPI_SWISH) {
+      for (int64_t n = 0; n < N; ++n) y[m * N + n] = v[n] * sigmoid64(v[n]);
+    } else {
+      const int64_t h = N / 2;
+      for (int64_t j = 0; j < h; ++j) y[m * h + j] = v[j] * sigmoid64(v[j + h]);
+    }
+    free(v);
+  }
+  return overflow ? 3 : 0;
+}
+
+/*
+ * The whole forward layer: quantize x per tensor and w per output channel,
+ * contract as integers, de-quantize.  x [M,K], w [K,N] (fan-in major).
+ * Outputs xq [M,K], s_x[1], wq_kn [K,N], s_w [N] are caller buffers; the rest
+ * as oracle_dense_fwd_q.
+ */
+int oracle_dense_fwd(const float *x, const float *w, int64_t M, int64_t K, int64_t N,
+                     int bits_x, int bits_w, const float *bias, int epilogue,
+                     int8_t *xq, float *s_x, int8_t *wq_kn, float *s_w,
+                     int32_t *acc, double *y, double *pre) {
+  int rc = oracle_quantize(x, M, K, bits_x, ORACLE_AXIS_ALL, xq, s_x, NULL);
+  if (rc) return rc;
+  rc = oracle_quantize(w, K, N, bits_w, 0, wq_kn, s_w, NULL);
+  if (rc) return rc;
+  return oracle_dense_fwd_q(xq, s_x[0], wq_kn, s_w, M, K, N, bias, epilogue, acc, y, pre);
+}
+
+/*
+ * Straight-through backward of y = (s_x xq)(s_w wq) (+ bias), scales held
+ * constant (Fig. 2, stop_gradient):
+ *   dx[m,k] = mask_x[m,k] * sum_n dy[m,n] * s_w[n] * wq[k,n]
+ *   dw[k,n] = mask_w[k,n] * s_x * sum_m xq[m,k] * dy[m,n]
+ *   dbias[n] = sum_m dy[m,n]
+ * mask_x / mask_w: nullable byte masks (NULL = all ones).  Any of dx, dw, dbias
+ * may be NULL.  dx_abs / dw_abs (nullable) receive the sum of the magnitudes
+ * of the terms, the yardstick a condition-aware comparison needs.
+ */
+void oracle_dense_bwd(const float *dy, const int8_t *xq, float s_x, const uint8_t *mask_x,
+                      const int8_t *wq_kn, const float *s_w, const uint8_t *mask_w,
+                      int64_t M, int64_t K, int64_t N,
+                      double *dx, double *dw, double *dbias, double *dx_abs, double *dw_abs) {
+  if (dx) {
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+      for (int64_t k = 0; k < K; ++k) {
+        double s = 0.0, sa = 0.0;
+        for (int64_t n = 0; n < N; ++n) {
+          double t = (double)dy[m * N + n] * (double)s_w[n] * (double)wq_kn[k * N + n];
+          s += t;
+          sa += fabs(t);
+        }
+        double g = (mask_x && !mask_x[m * K + k]) ? 0.0 : 1.0;
+        dx[m * K + k] = g * s;
+        if (dx_abs) dx_abs[m * K + k] = sa;
+      }
+  }
+  if (dw) {
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < K; ++k)
+      for (int64_t n = 0; n < N; ++n) {
+        double s = 0.0, sa = 0.0;
+        for (int64_t m = 0; m < M; ++m) {
+          double t = (double)xq[m * K + k] * (double)dy[m * N + n];
+          s += t;
+          sa += fabs(t);
+        }
+        double g = (mask_w && !mask_w[k * N + n]) ? 0.0 : 1.0;
+        dw[k * N + n] = g * (double)s_x * s;
+        if (dw_abs) dw_abs[k * N + n] = fabs((double)s_x) * sa;
+      }
+  }
+  if (dbias) {
+    for (int64_t n = 0; n < N; ++n) {
+      double s = 0.0;
+      for (int64_t m = 0; m < M; ++m) s += (double)dy[m * N + n];
+      dbias[n] = s;
+    }
+  }
+}
+
+/*
+ * Sampled variants for full-size checks: the same definitions evaluated only
+ * at listed output positions, so a test can afford the benchmark shapes.
+ * idx_m/idx_n (or idx_m/idx_k, idx_k/idx_n) have `count` entries each.
+ */
+void oracle_dense_fwd_q_sampled(const int8_t *xq, float s_x, const int8_t *wq_kn, const float *s_w,
+                                int64_t K, int64_t N, const float *bias,
+                                const int64_t *idx_m, const int64_t *idx_n, int64_t count,
+                                int64_t *acc, double *pre) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < count; ++i) {
+    int64_t m = idx_m[i], n = idx_n[i], a = 0;
+    for (int64_t k = 0; k < K; ++k) a += (int64_t)xq[m * K + k] * (int64_t)wq_kn[k * N + n];
+    acc[i] = a;
+    double d = (double)a * (double)s_x * (double)s_w[n];
+    if (bias) d += (double)bias[n];
+    pre[i] = d;
+  }
+}
+
+void oracle_dense_bwd_dx_sampled(const float *dy, const int8_t *wq_kn, const float *s_w,
+                                 int64_t K, int64_t N, const int64_t *idx_m, const int64_t *idx_k,
+                                 int64_t count, double *dx, double *dx_abs) {
+  (void)K;
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < count; ++i) {
+    int64_t m = idx_m[i], k = idx_k[i];
+    double s = 0.0, sa = 0.0;
+    for (int64_t n = 0; n < N; ++n) {
+      double t = (double)dy[m * N + n] * (double)s_w[n] * (double)wq_kn[k * N + n];
+      s += t;
+      sa += fabs(t);
+    }
+    dx[i] = s;
+    dx_abs[i] = sa;
+  }
+}
+
+void oracle_dense_bwd_dw_sampled(const float *dy, const int8_t *xq, float s_x,
+                                 int64_t M, int64_t K, int64_t N, const int64_t *idx_k,
+                                 const int64_t *idx_n, int64_t count, double *dw, double *dw_abs) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < count; ++i) {
+    int64_t k = idx_k[i], n = idx_n[i];
+    double s = 0.0, sa = 0.0;
+    for (int64_t m = 0; m < M; ++m) {
+      double t = (double)xq[m * K + k] * (double)dy[m * N + n];
+      s += t;
+      sa += fabs(t);
+    }
+    dw[i] = (double)s_x * s;
+    dw_abs[i] = fabs((double)s_x) * sa;
+  }
+}

@@ -1,0 +1,448 @@
+"""Pins for the CPU oracle: every expected value here comes from the paper's
+definition worked by hand, a closed form, an invariant, a library routine used
+on a special case, or an independent brute force -- never from the oracle.
+
+Citations: Fig. 2 (quantizer listing), Sec. 2.2 (127 / 7 rule, de-quantization
+by multiplying with the scale, no zero point), Sec. 1 (integer matmul; training
+forward equals serving forward), Table 1 (model sizes => half a byte per int4
+parameter).
+"""
+import numpy as np
+import pytest
+from scipy.special import expit
+
+import oracle
+from paper_2203_15952_amd import inputs
+
+F = np.float32
+
+
+# ----------------------------------------------------------------------------
+# An independent second implementation: python loops over numpy.float32 scalars
+# (each operator is one binary32 rounding), python ints for the contraction.
+# ----------------------------------------------------------------------------
+def bf_quantize_group(vals, bits):
+    qmax = (1 << (bits - 1)) - 1
+    m = F(0)
+    for v in vals:
+        a = abs(F(v))
+        if a > m:
+            m = a
+    s = F(m) / F(qmax)
+    codes = []
+    for v in vals:
+        t = F(0) if s == 0 else F(v) / s
+        u = F(t) + F(0.5)
+        r = int(np.floor(u))
+        assert -qmax <= r <= qmax
+        codes.append(r)
+    return codes, F(s)
+
+
+def bf_dense(x, w, bits_x, bits_w):
+    M, K = x.shape
+    N = w.shape[1]
+    cx, sx = bf_quantize_group(list(x.reshape(-1)), bits_x)
+    xq = [[cx[m * K + k] for k in range(K)] for m in range(M)]
+    wq = [[0] * N for _ in range(K)]
+    sw = []
+    for n in range(N):
+        c, s = bf_quantize_group([w[k, n] for k in range(K)], bits_w)
+        sw.append(s)
+        for k in range(K):
+            wq[k][n] = c[k]
+    acc = [[sum(xq[m][k] * wq[k][n] for k in range(K)) for n in range(N)] for m in range(M)]
+    return xq, sx, wq, sw, acc
+
+
+# ----------------------------------------------------------------------------
+# Quantizer: rounding, range, accuracy, equivariance, degenerate groups
+# ----------------------------------------------------------------------------
+def test_tie_table_round_half_up():
+    # floor(t + 0.5) with scale exactly 1 (the 127 forces max/127 == 1): halves go up,
+    # towards +inf, for both signs.  Worked by hand from Fig. 2.
+    x = np.array([[127.0, 0.5, -0.5, 1.5, -1.5, 2.5, -2.5, 0.25, -0.75, -127.0]], F)
+    q, s = oracle.quantize(x, 8, oracle.AXIS_ALL)
+    assert s[0] == F(1.0)
+    assert q.tolist() == [[127, 1, 0, 2, -1, 3, -2, 0, -1, -127]]
+
+
+def test_tie_table_int4():
+    x = np.array([[7.0, 0.5, -0.5, 6.5, -6.5, 3.49, -7.0]], F)
+    q, s = oracle.quantize(x, 4, oracle.AXIS_ALL)
+    assert s[0] == F(1.0)
+    assert q.tolist() == [[7, 1, 0, 7, -6, 3, -7]]
+
+
+def test_add_half_is_a_float32_add():
+    # 0.49999997f + 0.5f rounds to 1.0f in binary32, so the code is 1, not 0:
+    # the listing adds in float32, it does not compare against a half.
+    t = np.nextafter(F(0.5), F(0))
+    assert F(t) + F(0.5) == F(1.0)
+    x = np.array([[127.0, t, -t]], F)
+    q, _ = oracle.quantize(x, 8, oracle.AXIS_ALL)
+    assert q.tolist() == [[127, 1, 0]]
+
+
+@pytest.mark.parametrize("bits", [8, 4, 2, 5])
+@pytest.mark.parametrize("axis", [oracle.AXIS_ALL, 0, 1])
+def test_range_and_argmax(bits, axis):
+    rng = np.random.default_rng(10 + bits)
+    x = (rng.standard_normal((37, 53)) * rng.uniform(0.01, 100.0)).astype(F)
+    q, s, mask = oracle.quantize(x, bits, axis, want_mask=True)
+    qmax = (1 << (bits - 1)) - 1
+    assert q.min() >= -qmax and q.max() <= qmax
+    assert mask.all()          # abs-max scaling never saturates: every gradient passes
+    a = np.abs(x)
+    if axis == oracle.AXIS_ALL:
+        i = np.unravel_index(np.argmax(a), a.shape)
+        assert abs(int(q[i])) == qmax and s[0] == F(a.max()) / F(qmax)
+    elif axis == 0:
+        j = np.argmax(a, axis=0)
+        assert (np.abs(q[j, np.arange(x.shape[1])]) == qmax).all()
+        np.testing.assert_array_equal(s, a.max(axis=0) / F(qmax))
+    else:
+        j = np.argmax(a, axis=1)
+        assert (np.abs(q[np.arange(x.shape[0]), j]) == qmax).all()
+        np.testing.assert_array_equal(s, a.max(axis=1) / F(qmax))
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_half_step_error_bound(bits):
+    # |s*q - x| <= s/2 inside the clip range (slack for the two float32 roundings).
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((64, 200)).astype(F)
+    q, s = oracle.quantize(x, bits, oracle.AXIS_ALL)
+    sd = float(s[0])
+    err = np.abs(sd * q.astype(np.float64) - x.astype(np.float64))
+    assert err.max() <= sd / 2 + sd * 2.0 ** -16
+    # and the bound is tight: some element must use a good part of the half step
+    assert err.max() > 0.45 * sd
+    q0, s0 = oracle.quantize(x, bits, 0)
+    err0 = np.abs(s0.astype(np.float64)[None, :] * q0 - x.astype(np.float64))
+    assert (err0 <= s0[None, :] / 2 * (1 + 2.0 ** -15)).all()
+
+
+@pytest.mark.parametrize("e", [-20, -3, 5, 40])
+def test_power_of_two_equivariance(e):
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal((16, 33)).astype(F)
+    q1, s1 = oracle.quantize(x, 8, 0)
+    q2, s2 = oracle.quantize(np.ldexp(x, e).astype(F), 8, 0)
+    np.testing.assert_array_equal(q1, q2)
+    np.testing.assert_array_equal(np.ldexp(s1, e).astype(F), s2)
+
+
+def test_zero_group_and_tiny_scale():
+    x = np.zeros((4, 5), F)
+    x[:, 1] = [1, -2, 3, -4]
+    x[:, 3] = [1e-45, 0, -1e-45, 0]     # max/7 underflows to 0: divide_no_nan path
+    q, s, mask = oracle.quantize(x, 4, 0, want_mask=True)
+    assert s[0] == 0 and s[3] == 0 and s[1] == F(4) / F(7)
+    assert (q[:, [0, 2, 3, 4]] == 0).all()
+    assert (mask[:, [0, 2, 3, 4]] == 0).all() and mask[:, 1].all()
+    assert q[:, 1].tolist() == [2, -3, 5, -7]   # 1.75->2, -3.5->-3 (half up), 5.25->5
+    qa, sa = oracle.quantize(np.zeros((3, 3), F), 8, oracle.AXIS_ALL)
+    assert sa[0] == 0 and not qa.any()
+
+
+def test_denormal_range_is_gradual():
+    # maxima near the bottom of the normal range: the scale is subnormal, the
+    # divide still resolves codes (no flush to zero on the host).
+    x = np.array([[1.0e-38, 0.5e-38, -0.25e-38, 3.0e-39]], F)
+    q, s = oracle.quantize(x, 8, oracle.AXIS_ALL)
+    assert 0 < s[0] < np.finfo(F).tiny
+    codes, s_bf = bf_quantize_group(list(x[0]), 8)
+    assert s[0] == s_bf and q[0].tolist() == codes
+    assert q[0, 0] == 127 and abs(int(q[0, 1]) - 64) <= 1
+
+
+def test_nonfinite_is_reported():
+    x = np.ones((2, 3), F)
+    x[1, 1] = np.inf
+    with pytest.raises(FloatingPointError):
+        oracle.quantize(x, 8, oracle.AXIS_ALL)
+    x[1, 1] = np.nan
+    with pytest.raises(FloatingPointError):
+        oracle.quantize(x, 8, 0)
+
+
+def test_external_scale_saturates_and_masks():
+    # hand-worked: scale 1, int4 -> values beyond +-7 saturate and are masked out.
+    x = np.array([[0.4, 7.4, 7.5, -7.5, -7.6, 100.0, -100.0, 6.5]], F)
+    q, mask = oracle.quantize_with_scale(x, 4, oracle.AXIS_ALL, [1.0])
+    assert q.tolist() == [[0, 7, 7, -7, -7, 7, -7, 7]]
+    assert mask.tolist() == [[1, 1, 0, 1, 0, 0, 0, 1]]
+    q, mask = oracle.quantize_with_scale(x, 4, oracle.AXIS_ALL, [0.0])
+    assert not q.any() and not mask.any()
+    # per-column (axis 0) and per-row (axis 1) scales, non-square so they cannot be swapped
+    x2 = np.array([[1.0, 4.0, 30.0], [-2.0, 8.0, -9.0]], F)
+    q, mask = oracle.quantize_with_scale(x2, 4, 0, [1.0, 2.0, 4.0])
+    assert q.tolist() == [[1, 2, 7], [-2, 4, -2]] and mask.tolist() == [[1, 1, 0], [1, 1, 1]]
+    q, mask = oracle.quantize_with_scale(x2, 4, 1, [1.0, 2.0])
+    assert q.tolist() == [[1, 4, 7], [-1, 4, -4]] and mask.tolist() == [[1, 1, 0], [1, 1, 1]]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_brute_force_quantizer(seed):
+    rng = np.random.default_rng(100 + seed)
+    rows, cols = rng.integers(1, 9, 2)
+    x = (rng.standard_normal((rows, cols)) * 10.0 ** rng.integers(-3, 4)).astype(F)
+    for bits in (8, 4):
+        q, s = oracle.quantize(x, bits, oracle.AXIS_ALL)
+        c, sb = bf_quantize_group(list(x.reshape(-1)), bits)
+        assert s[0] == sb and q.reshape(-1).tolist() == c
+        q, s = oracle.quantize(x, bits, 0)
+        for n in range(cols):
+            c, sb = bf_quantize_group(list(x[:, n]), bits)
+            assert s[n] == sb and q[:, n].tolist() == c
+        q, s = oracle.quantize(x, bits, 1)
+        for r in range(rows):
+            c, sb = bf_quantize_group(list(x[r]), bits)
+            assert s[r] == sb and q[r].tolist() == c
+
+
+# ----------------------------------------------------------------------------
+# int4 packing
+# ----------------------------------------------------------------------------
+def test_pack_int4_hand_bytes():
+    # channel 0: k=0..4 codes 1,-1,7,-7,3  -> bytes 0xF1, 0x97, 0x03
+    # channel 1: 0,2,-2,5,-5               -> bytes 0x20, 0x5E, 0x0B
+    codes = np.array([[1, 0], [-1, 2], [7, -2], [-7, 5], [3, -5]], np.int8)
+    b = oracle.pack_int4(codes)
+    assert b.shape == (2, 3)
+    assert b.tolist() == [[0xF1, 0x97, 0x03], [0x20, 0x5E, 0x0B]]
+
+
+def test_pack_int4_never_emits_minus_eight_and_size():
+    rng = np.random.default_rng(5)
+    w = rng.standard_normal((66, 19)).astype(F)
+    q, s = oracle.quantize(w, 4, 0)
+    b = oracle.pack_int4(q)
+    assert ((b & 0xF) != 0x8).all() and ((b >> 4) != 0x8).all()
+    # half a byte per parameter plus one float32 scale per output channel
+    K, N = w.shape
+    assert b.nbytes + s.nbytes == N * ((K + 1) // 2) + 4 * N
+    # round trip through sign extension
+    lo = ((b & 0xF).astype(np.int8) ^ 8) - 8
+    hi = ((b >> 4).astype(np.int8) ^ 8) - 8
+    back = np.empty((N, 2 * b.shape[1]), np.int8)
+    back[:, 0::2], back[:, 1::2] = lo, hi
+    np.testing.assert_array_equal(back[:, :K].T, q)
+
+
+def test_model_size_accounting_matches_table1():
+    # Table 1, Conformer (L): 475 MB float, 139 MB int8, 82 MB int4.  If n MB of
+    # parameters (at 1 B each) are quantized, float->int8 saves 3n and int4 stores
+    # half a byte per parameter: 475 - 3.5 n must land on the int4 row.
+    n = (475 - 139) / 3.0
+    assert abs((475 - 3.5 * n) - 82) <= 1.5
+
+
+# ----------------------------------------------------------------------------
+# Forward contraction and de-quantization
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("bits_w", [8, 4])
+def test_integer_valued_special_case(bits_w):
+    # Integer inputs whose maxima are exactly qmax make every scale 1.0: the layer
+    # must reproduce a plain integer matrix product (checked with numpy int64 @).
+    rng = np.random.default_rng(6)
+    qw = (1 << (bits_w - 1)) - 1
+    M, K, N = 19, 45, 23
+    x = rng.integers(-127, 128, (M, K))
+    x[0, 0] = 127
+    w = rng.integers(-qw, qw + 1, (K, N))
+    w[0, :] = qw
+    r = oracle.dense_fwd(x.astype(F), w.astype(F), 8, bits_w)
+    assert r["s_x"][0] == 1 and (r["s_w"] == 1).all()
+    np.testing.assert_array_equal(r["xq"], x)
+    np.testing.assert_array_equal(r["wq"], w)
+    ref = x.astype(np.int64) @ w.astype(np.int64)
+    np.testing.assert_array_equal(r["acc"], ref)
+    np.testing.assert_array_equal(r["y"], ref.astype(np.float64))
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_brute_force_dense(seed):
+    rng = np.random.default_rng(200 + seed)
+    M, K, N = rng.integers(1, 9, 3)
+    x = rng.standard_normal((M, K)).astype(F)
+    w = (rng.standard_normal((K, N)) / np.sqrt(K)).astype(F)
+    for bx, bw in ((8, 4), (8, 8), (4, 4)):
+        r = oracle.dense_fwd(x, w, bx, bw)
+        xq, sx, wq, sw, acc = bf_dense(x, w, bx, bw)
+        assert r["xq"].tolist() == xq and r["wq"].tolist() == wq
+        assert r["s_x"][0] == sx and r["s_w"].tolist() == [float(s) for s in sw]
+        assert r["acc"].tolist() == acc
+        for m in range(M):
+            for n in range(N):
+                exact = acc[m][n] * float(sx) * float(sw[n])
+                assert r["y"][m, n] == pytest.approx(exact, rel=1e-15, abs=0)
+
+
+def test_transposed_operand_would_fail():
+    # Guard against an index mix-up that a square symmetric test would hide:
+    # non-square, non-symmetric, against int64 matmul of the oracle's own codes
+    # re-derived by the brute force quantizer.
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal((5, 7)).astype(F)
+    w = rng.standard_normal((7, 3)).astype(F)
+    r = oracle.dense_fwd(x, w, 8, 8)
+    xq, _, wq, _, _ = bf_dense(x, w, 8, 8)
+    ref = np.array(xq, np.int64) @ np.array(wq, np.int64)
+    np.testing.assert_array_equal(r["acc"], ref)
+    assert not np.array_equal(ref, (np.array(wq, np.int64).T @ np.array(xq, np.int64).T))
+
+
+def test_accumulator_bound_and_overflow_flag():
+    # K * qmax_x * qmax_w < 2^31 for every layer shape used here ...
+    assert 2048 * 127 * 127 < 2 ** 31 and 16 * 131072 * 127 * 7 < 2 ** 31
+    # ... and the oracle notices when a sum does not fit: 140000 * 127 * 127 > 2^31
+    K = 140000
+    xq = np.full((1, K), 127, np.int8)
+    wq = np.full((K, 1), 127, np.int8)
+    with pytest.raises(OverflowError):
+        oracle.dense_fwd_q(xq, 1.0, wq, np.ones(1, F))
+    r = oracle.dense_fwd_q(xq[:, :2048], 1.0, wq[:2048], np.ones(1, F))
+    assert r["acc"][0, 0] == 2048 * 127 * 127
+
+
+@pytest.mark.parametrize("bx,bw,lo,hi", [(8, 4, 0.06, 0.20), (8, 8, 0.005, 0.03)])
+def test_method_error_bound_against_float_product(bx, bw, lo, hi):
+    # The layer approximates X @ W.  Each operand is off by at most half a step,
+    # so |y - XW|_mn <= sum_k |x| s_w/2 + |w| s_x/2 + s_x s_w/4  (plus float slack).
+    c = inputs.small_case(11, 48, 256, 40, bx, bw)
+    r = oracle.dense_fwd(c.x, c.w, bx, bw)
+    x64, w64 = c.x.astype(np.float64), c.w.astype(np.float64)
+    exact = x64 @ w64
+    sx, sw = float(r["s_x"][0]), r["s_w"].astype(np.float64)
+    bound = (np.abs(x64).sum(1)[:, None] * sw[None, :] / 2
+             + np.abs(w64).sum(0)[None, :] * sx / 2 + c.K * sx * sw[None, :] / 4)
+    assert (np.abs(r["y"] - exact) <= bound * (1 + 1e-4)).all()
+    rel = np.linalg.norm(r["y"] - exact) / np.linalg.norm(exact)
+    assert lo < rel < hi
+
+
+def test_bias_and_epilogues_closed_forms():
+    rng = np.random.default_rng(8)
+    M, K, N = 6, 12, 8
+    xq = rng.integers(-127, 128, (M, K)).astype(np.int8)
+    wq = rng.integers(-7, 8, (K, N)).astype(np.int8)
+    s_x, s_w = F(0.01), rng.uniform(0.01, 0.1, N).astype(F)
+    bias = rng.standard_normal(N).astype(F)
+    acc = xq.astype(np.int64) @ wq.astype(np.int64)
+    pre = acc * float(s_x) * s_w.astype(np.float64)[None, :] + bias.astype(np.float64)[None, :]
+    r = oracle.dense_fwd_q(xq, s_x, wq, s_w, bias, oracle.EPI_NONE)
+    np.testing.assert_allclose(r["y"], pre, rtol=1e-14)
+    np.testing.assert_allclose(r["pre"], pre, rtol=1e-14)
+    r = oracle.dense_fwd_q(xq, s_x, wq, s_w, bias, oracle.EPI_SWISH)
+    np.testing.assert_allclose(r["y"], pre * expit(pre), rtol=1e-13)
+    r = oracle.dense_fwd_q(xq, s_x, wq, s_w, bias, oracle.EPI_GLU)
+    assert r["y"].shape == (M, N // 2)
+    np.testing.assert_allclose(r["y"], pre[:, :N // 2] * expit(pre[:, N // 2:]), rtol=1e-13)
+    # swish limits: 0 at 0, identity for large positive, vanishing for large negative
+    one = np.ones((1, 1), np.int8)
+    for a, want in ((0, 0.0), (40, 40.0), (-40, -40 * np.exp(-40.0))):
+        v = oracle.dense_fwd_q(one * a, 1.0, one, np.ones(1, F), None, oracle.EPI_SWISH)["y"][0, 0]
+        assert v == pytest.approx(want, rel=1e-12, abs=1e-300)
+
+
+def test_training_forward_equals_serving_forward():
+    # Sec. 1: no numerical difference between the training forward (quantize W in
+    # the call) and serving (W quantized beforehand).
+    c = inputs.small_case(12, 33, 70, 21, 8, 4, with_bias=True)
+    full = oracle.dense_fwd(c.x, c.w, 8, 4, c.bias, oracle.EPI_SWISH)
+    xq, s_x = oracle.quantize(c.x, 8, oracle.AXIS_ALL)
+    wq, s_w = oracle.quantize(c.w, 4, 0)
+    served = oracle.dense_fwd_q(xq, s_x[0], wq, s_w, c.bias, oracle.EPI_SWISH)
+    np.testing.assert_array_equal(full["acc"], served["acc"])
+    np.testing.assert_array_equal(full["y"], served["y"])
+
+
+def test_fake_float32_matmul_equals_integer_matmul_while_it_fits():
+    # Sec. 1: float-emulated integers agree with native integers as long as the
+    # sums fit the float32 significand: K * 127 * 7 < 2^24 for K <= 18000.
+    c = inputs.small_case(13, 16, 512, 24, 8, 4)
+    r = oracle.dense_fwd(c.x, c.w, 8, 4)
+    fake = r["xq"].astype(F) @ r["wq"].astype(F)
+    np.testing.assert_array_equal(fake.astype(np.int64), r["acc"].astype(np.int64))
+
+
+# ----------------------------------------------------------------------------
+# Straight-through backward
+# ----------------------------------------------------------------------------
+def test_ste_gradients_against_float64_matmul():
+    c = inputs.small_case(14, 40, 36, 28, 8, 4)
+    f = oracle.dense_fwd(c.x, c.w, 8, 4)
+    g = oracle.dense_bwd(c.dy, f["xq"], f["s_x"][0], f["wq"], f["s_w"])
+    xh = f["xq"].astype(np.float64) * float(f["s_x"][0])
+    wh = f["wq"].astype(np.float64) * f["s_w"].astype(np.float64)[None, :]
+    dy = c.dy.astype(np.float64)
+    np.testing.assert_allclose(g["dx"], dy @ wh.T, rtol=1e-11, atol=1e-15)
+    np.testing.assert_allclose(g["dw"], xh.T @ dy, rtol=1e-11, atol=1e-15)
+    np.testing.assert_allclose(g["dbias"], dy.sum(0), rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(g["dx_abs"], np.abs(dy) @ np.abs(wh).T, rtol=1e-11)
+    np.testing.assert_allclose(g["dw_abs"], np.abs(xh).T @ np.abs(dy), rtol=1e-11)
+    # shapes are all different, so a transposed operand cannot pass
+    assert g["dx"].shape == (40, 36) and g["dw"].shape == (36, 28)
+
+
+def test_ste_is_the_gradient_of_the_dequantized_bilinear_form():
+    # With the codes frozen (straight-through) the layer is y = (s_x xq)(s_w wq);
+    # perturbing the de-quantized operands gives the same directional derivative.
+    c = inputs.small_case(15, 9, 11, 7, 8, 8)
+    f = oracle.dense_fwd(c.x, c.w, 8, 8)
+    g = oracle.dense_bwd(c.dy, f["xq"], f["s_x"][0], f["wq"], f["s_w"])
+    xh = f["xq"].astype(np.float64) * float(f["s_x"][0])
+    wh = f["wq"].astype(np.float64) * f["s_w"].astype(np.float64)[None, :]
+    rng = np.random.default_rng(0)
+    dxh, dwh = rng.standard_normal(xh.shape), rng.standard_normal(wh.shape)
+    dy = c.dy.astype(np.float64)
+    lin = ((dxh @ wh + xh @ dwh) * dy).sum()        # exact: the form is bilinear
+    assert (g["dx"] * dxh).sum() + (g["dw"] * dwh).sum() == pytest.approx(lin, rel=1e-10)
+
+
+def test_masks_gate_gradients_and_zero_groups():
+    rng = np.random.default_rng(16)
+    M, K, N = 6, 5, 4
+    x = rng.standard_normal((M, K)).astype(F)
+    w = rng.standard_normal((K, N)).astype(F)
+    w[:, 2] = 0                                    # an all-zero output channel
+    dy = rng.standard_normal((M, N)).astype(F)
+    xq, s_x, mx = oracle.quantize(x, 8, oracle.AXIS_ALL, want_mask=True)
+    wq, s_w, mw = oracle.quantize(w, 4, 0, want_mask=True)
+    assert mx.all() and mw[:, [0, 1, 3]].all() and not mw[:, 2].any()
+    g = oracle.dense_bwd(dy, xq, s_x[0], wq, s_w, mx, mw)
+    assert (g["dw"][:, 2] == 0).all() and (g["dw"][:, 0] != 0).any()
+    # an explicit mask zeroes exactly the masked entries and nothing else
+    mx2 = mx.copy()
+    mx2[1, 3] = 0
+    g2 = oracle.dense_bwd(dy, xq, s_x[0], wq, s_w, mx2, mw)
+    assert g2["dx"][1, 3] == 0
+    keep = mx2.astype(bool)
+    np.testing.assert_array_equal(g2["dx"][keep], g["dx"][keep])
+
+
+# ----------------------------------------------------------------------------
+# Sampled variants used at benchmark sizes
+# ----------------------------------------------------------------------------
+def test_sampled_variants_against_library_matmul():
+    rng = np.random.default_rng(17)
+    M, K, N = 50, 64, 30
+    xq = rng.integers(-127, 128, (M, K)).astype(np.int8)
+    wq = rng.integers(-7, 8, (K, N)).astype(np.int8)
+    s_x, s_w = F(0.02), rng.uniform(0.01, 0.1, N).astype(F)
+    dy = rng.standard_normal((M, N)).astype(F)
+    im, ik, inn = rng.integers(0, M, 40), rng.integers(0, K, 40), rng.integers(0, N, 40)
+    acc, pre = oracle.dense_fwd_q_sampled(xq, s_x, wq, s_w, im, inn)
+    full = xq.astype(np.int64) @ wq.astype(np.int64)
+    np.testing.assert_array_equal(acc, full[im, inn])
+    np.testing.assert_allclose(pre, full[im, inn] * float(s_x) * s_w.astype(np.float64)[inn], rtol=1e-14)
+    wh = wq.astype(np.float64) * s_w.astype(np.float64)[None, :]
+    dx, dxa = oracle.dense_bwd_dx_sampled(dy, wq, s_w, im, ik)
+    np.testing.assert_allclose(dx, (dy.astype(np.float64) @ wh.T)[im, ik], rtol=1e-11, atol=1e-15)
+    np.testing.assert_allclose(dxa, (np.abs(dy.astype(np.float64)) @ np.abs(wh).T)[im, ik], rtol=1e-11)
+    dw, dwa = oracle.dense_bwd_dw_sampled(dy, xq, s_x, ik, inn)
+    xh = xq.astype(np.float64) * float(s_x)
+    np.testing.assert_allclose(dw, (xh.T @ dy.astype(np.float64))[ik, inn], rtol=1e-11, atol=1e-15)
+    np.testing.assert_allclose(dwa, (np.abs(xh).T @ np.abs(dy.astype(np.float64)))[ik, inn], rtol=1e-11)
