@@ -1,0 +1,252 @@
+"""Thin ctypes binding over libaqt.so (the C ABI in include/aqt.h).
+
+Argument marshalling only: torch supplies device memory and the current HIP
+stream, every step of the computation runs in the library's kernels.  There is
+no CPU or PyTorch fallback: if the library is missing, importing a function here
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libaqt.so")
+
+AQT_OK, AQT_ERR_INVALID_ARG, AQT_ERR_UNSUPPORTED, AQT_ERR_WORKSPACE, AQT_ERR_HIP, AQT_ERR_NONFINITE = range(6)
+AQT_AXIS_ALL, AQT_AXIS_ROWS, AQT_AXIS_COLS = -1, 0, 1
+AQT_EPI_NONE, AQT_EPI_SWISH, AQT_EPI_GLU = 0, 1, 2
+AQT_OP_QUANTIZE, AQT_OP_QUANTIZE_WEIGHTS, AQT_OP_DENSE_FWD, AQT_OP_DENSE_FWD_Q, AQT_OP_DENSE_BWD = range(5)
+
+# every symbol include/aqt.h declares
+SYMBOLS = ["aqt_status_string", "aqt_last_hip_error", "aqt_version", "aqt_workspace_bytes",
+           "aqt_packed_weight_bytes", "aqt_quantize", "aqt_quantize_with_scale", "aqt_quantize_weights",
+           "aqt_unpack_weights", "aqt_dense_fwd_q", "aqt_dense_fwd", "aqt_dense_bwd"]
+
+
+class AqtError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().aqt_status_string(status).decode()
+        if status == AQT_ERR_HIP:
+            msg += f" (hipError {lib().aqt_last_hip_error()})"
+        super().__init__(f"{where}: {msg}")
+
+
+class aqt_saved(ctypes.Structure):
+    _fields_ = [("xq", ctypes.c_void_p), ("s_x", ctypes.c_void_p), ("mask_x", ctypes.c_void_p),
+                ("wq_packed", ctypes.c_void_p), ("wq_kn", ctypes.c_void_p), ("s_w", ctypes.c_void_p),
+                ("mask_w", ctypes.c_void_p)]
+
+
+_lib = None
+_i64, _int, _vp, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+
+
+def lib() -> ctypes.CDLL:
+    """Load libaqt.so; fail loudly when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with "
+                              "`python -m paper_2203_15952_amd.build` (there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        L.aqt_status_string.restype = ctypes.c_char_p
+        L.aqt_status_string.argtypes = [_int]
+        L.aqt_last_hip_error.restype = _int
+        L.aqt_version.restype = _int
+        L.aqt_workspace_bytes.restype = _sz
+        L.aqt_workspace_bytes.argtypes = [_int, _i64, _i64, _i64, _int, _int]
+        L.aqt_packed_weight_bytes.restype = _sz
+        L.aqt_packed_weight_bytes.argtypes = [_i64, _i64, _int]
+        L.aqt_quantize.argtypes = [_vp, _i64, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp, _sz, _vp, _vp]
+        L.aqt_quantize_with_scale.argtypes = [_vp, _i64, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp]
+        L.aqt_quantize_weights.argtypes = [_vp, _i64, _i64, _int, _vp, _vp, _vp, _vp, _vp, _sz, _vp, _vp]
+        L.aqt_unpack_weights.argtypes = [_vp, _i64, _i64, _int, _vp, _vp]
+        L.aqt_dense_fwd_q.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _vp,
+                                      _vp, _sz, _vp]
+        L.aqt_dense_fwd.argtypes = [_vp, _vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp,
+                                    ctypes.POINTER(aqt_saved), _vp, _sz, _vp, _vp]
+        L.aqt_dense_bwd.argtypes = [_vp, ctypes.POINTER(aqt_saved), _i64, _i64, _i64, _int, _int, _vp, _vp, _vp,
+                                    _vp, _sz, _vp]
+        for name in SYMBOLS:
+            getattr(L, name)  # AttributeError if the library lacks a declared entry point
+        _lib = L
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != AQT_OK:
+        raise AqtError(status, where)
+
+
+def _dev(t: torch.Tensor, dtype, name: str):
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name}: expected a contiguous {dtype} device tensor")
+    return t
+
+
+def _words(n: int) -> int:
+    return (n + 31) // 32
+
+
+def aqt_workspace_bytes(op: int, M: int, K: int, N: int, bits_x: int = 8, bits_w: int = 4) -> int:
+    return int(lib().aqt_workspace_bytes(op, M, K, N, bits_x, bits_w))
+
+
+def aqt_packed_weight_bytes(K: int, N: int, bits_w: int) -> int:
+    return int(lib().aqt_packed_weight_bytes(K, N, bits_w))
+
+
+def workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def new_status(device="cuda") -> torch.Tensor:
+    return torch.zeros(1, dtype=torch.int32, device=device)
+
+
+def aqt_quantize(x, bits: int, axis: int, *, q=None, scale=None, clip_mask=None, want_mask=False,
+                 ws=None, dev_status=None, ldx: Optional[int] = None, cols: Optional[int] = None):
+    """aqt_quantize: returns (q int8 [rows, cols], scale float32, clip_mask or None)."""
+    _dev(x, torch.float32, "x")
+    rows = x.shape[0]
+    cols = x.shape[1] if cols is None else cols
+    ldx = x.shape[1] if ldx is None else ldx
+    n_scale = 1 if axis == AQT_AXIS_ALL else (cols if axis == AQT_AXIS_ROWS else rows)
+    q = torch.empty((rows, cols), dtype=torch.int8, device=x.device) if q is None else q
+    scale = torch.empty(n_scale, dtype=torch.float32, device=x.device) if scale is None else scale
+    if want_mask and clip_mask is None:
+        clip_mask = torch.empty(_words(rows * cols), dtype=torch.int32, device=x.device)
+    ws = workspace(aqt_workspace_bytes(AQT_OP_QUANTIZE, rows, cols, 1), x.device) if ws is None else ws
+    st = lib().aqt_quantize(_ptr(x), rows, cols, ldx, bits, axis, _ptr(q), _ptr(scale), _ptr(clip_mask),
+                            _ptr(ws), ws.numel(), _stream(), _ptr(dev_status))
+    _check(st, "aqt_quantize")
+    return q, scale, clip_mask
+
+
+def aqt_quantize_with_scale(x, bits: int, axis: int, scale, *, q=None, clip_mask=None, want_mask=True):
+    """aqt_quantize_with_scale: returns (q, clip_mask or None)."""
+    _dev(x, torch.float32, "x")
+    _dev(scale, torch.float32, "scale")
+    rows, cols = x.shape
+    q = torch.empty((rows, cols), dtype=torch.int8, device=x.device) if q is None else q
+    if want_mask and clip_mask is None:
+        clip_mask = torch.empty(_words(rows * cols), dtype=torch.int32, device=x.device)
+    st = lib().aqt_quantize_with_scale(_ptr(x), rows, cols, cols, bits, axis, _ptr(scale), _ptr(q),
+                                       _ptr(clip_mask), _stream())
+    _check(st, "aqt_quantize_with_scale")
+    return q, clip_mask
+
+
+def aqt_quantize_weights(w, bits_w: int, *, wq_packed=None, s_w=None, wq_kn=None, clip_mask_w=None,
+                         want_kn=True, want_mask=False, dev_status=None):
+    """aqt_quantize_weights: returns (wq_packed uint8, s_w float32 [N], wq_kn int8 [K,N] or None, mask or None)."""
+    _dev(w, torch.float32, "w")
+    K, N = w.shape
+    if wq_packed is None:
+        wq_packed = torch.empty(aqt_packed_weight_bytes(K, N, bits_w), dtype=torch.uint8, device=w.device)
+    s_w = torch.empty(N, dtype=torch.float32, device=w.device) if s_w is None else s_w
+    if want_kn and wq_kn is None:
+        wq_kn = torch.empty((K, N), dtype=torch.int8, device=w.device)
+    if want_mask and clip_mask_w is None:
+        clip_mask_w = torch.empty(_words(K * N), dtype=torch.int32, device=w.device)
+    st = lib().aqt_quantize_weights(_ptr(w), K, N, bits_w, _ptr(wq_packed), _ptr(s_w), _ptr(wq_kn),
+                                    _ptr(clip_mask_w), None, 0, _stream(), _ptr(dev_status))
+    _check(st, "aqt_quantize_weights")
+    return wq_packed, s_w, wq_kn, clip_mask_w
+
+
+def aqt_unpack_weights(wq_packed, K: int, N: int, bits_w: int):
+    codes = torch.empty((K, N), dtype=torch.int8, device=wq_packed.device)
+    st = lib().aqt_unpack_weights(_ptr(wq_packed), K, N, bits_w, _ptr(codes), _stream())
+    _check(st, "aqt_unpack_weights")
+    return codes
+
+
+def _out_cols(N: int, epilogue: int) -> int:
+    return N // 2 if epilogue == AQT_EPI_GLU else N
+
+
+def aqt_dense_fwd_q(xq, s_x, wq_packed, s_w, N: int, bits_x: int, bits_w: int, *, bias=None,
+                    epilogue: int = AQT_EPI_NONE, y=None, acc_out=None, want_acc=False):
+    """aqt_dense_fwd_q: returns (y float32, acc int32 or None)."""
+    _dev(xq, torch.int8, "xq")
+    M, K = xq.shape
+    y = torch.empty((M, _out_cols(N, epilogue)), dtype=torch.float32, device=xq.device) if y is None else y
+    if want_acc and acc_out is None:
+        acc_out = torch.empty((M, N), dtype=torch.int32, device=xq.device)
+    st = lib().aqt_dense_fwd_q(_ptr(xq), _ptr(s_x), _ptr(wq_packed), _ptr(s_w), M, K, N, bits_x, bits_w,
+                               _ptr(bias), epilogue, _ptr(y), _ptr(acc_out), None, 0, _stream())
+    _check(st, "aqt_dense_fwd_q")
+    return y, acc_out
+
+
+class Saved:
+    """Device buffers the forward keeps for the backward, plus their aqt_saved view."""
+
+    def __init__(self, M: int, K: int, N: int, bits_w: int, device="cuda", masks: bool = False):
+        self.M, self.K, self.N, self.bits_w = M, K, N, bits_w
+        self.xq = torch.empty((M, K), dtype=torch.int8, device=device)
+        self.s_x = torch.empty(1, dtype=torch.float32, device=device)
+        self.wq_packed = torch.empty(aqt_packed_weight_bytes(K, N, bits_w), dtype=torch.uint8, device=device)
+        self.wq_kn = torch.empty((K, N), dtype=torch.int8, device=device)
+        self.s_w = torch.empty(N, dtype=torch.float32, device=device)
+        self.mask_x = torch.empty(_words(M * K), dtype=torch.int32, device=device) if masks else None
+        self.mask_w = torch.empty(_words(K * N), dtype=torch.int32, device=device) if masks else None
+        self.refresh()
+
+    def refresh(self):
+        def a(t):
+            return None if t is None else t.data_ptr()
+        self.c = aqt_saved(a(self.xq), a(self.s_x), a(self.mask_x), a(self.wq_packed), a(self.wq_kn),
+                           a(self.s_w), a(self.mask_w))
+        return self
+
+
+def aqt_dense_fwd(x, w, bits_x: int, bits_w: int, *, bias=None, epilogue: int = AQT_EPI_NONE, y=None,
+                  saved: Optional[Saved] = None, ws=None, dev_status=None):
+    """aqt_dense_fwd: returns y float32 [M,N] ([M,N/2] for GLU)."""
+    _dev(x, torch.float32, "x")
+    _dev(w, torch.float32, "w")
+    M, K = x.shape
+    N = w.shape[1]
+    y = torch.empty((M, _out_cols(N, epilogue)), dtype=torch.float32, device=x.device) if y is None else y
+    if ws is None:
+        ws = workspace(aqt_workspace_bytes(AQT_OP_DENSE_FWD, M, K, N, bits_x, bits_w), x.device)
+    sp = ctypes.byref(saved.c) if saved is not None else None
+    st = lib().aqt_dense_fwd(_ptr(x), _ptr(w), M, K, N, bits_x, bits_w, _ptr(bias), epilogue, _ptr(y), sp,
+                             _ptr(ws), ws.numel(), _stream(), _ptr(dev_status))
+    _check(st, "aqt_dense_fwd")
+    return y
+
+
+def aqt_dense_bwd(dy, saved: Saved, bits_x: int, bits_w: int, *, dx=None, dw=None, dbias=None,
+                  want_dx=True, want_dw=True, want_dbias=False, ws=None):
+    """aqt_dense_bwd: returns (dx [M,K], dw [K,N], dbias [N]); skipped outputs are None."""
+    _dev(dy, torch.float32, "dy")
+    M, N = dy.shape
+    K = saved.K
+    if want_dx and dx is None:
+        dx = torch.empty((M, K), dtype=torch.float32, device=dy.device)
+    if want_dw and dw is None:
+        dw = torch.empty((K, N), dtype=torch.float32, device=dy.device)
+    if want_dbias and dbias is None:
+        dbias = torch.empty(N, dtype=torch.float32, device=dy.device)
+    if ws is None:
+        ws = workspace(aqt_workspace_bytes(AQT_OP_DENSE_BWD, M, K, N, bits_x, bits_w), dy.device)
+    st = lib().aqt_dense_bwd(_ptr(dy), ctypes.byref(saved.c), M, K, N, bits_x, bits_w, _ptr(dx), _ptr(dw),
+                             _ptr(dbias), _ptr(ws), ws.numel(), _stream())
+    _check(st, "aqt_dense_bwd")
+    return dx, dw, dbias

@@ -1,0 +1,61 @@
+// Internal declarations shared by the HIP translation units of libaqt.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "aqt.h"
+
+namespace aqt {
+
+extern thread_local int g_last_hip_error;
+
+#define AQT_HIP(expr)                                   \
+  do {                                                  \
+    hipError_t e__ = (expr);                            \
+    if (e__ != hipSuccess) {                            \
+      aqt::g_last_hip_error = static_cast<int>(e__);    \
+      return AQT_ERR_HIP;                               \
+    }                                                   \
+  } while (0)
+
+#define AQT_TRY(expr)                 \
+  do {                                \
+    aqt_status s__ = (expr);          \
+    if (s__ != AQT_OK) return s__;    \
+  } while (0)
+
+constexpr int kMaxPartials = 4096;  // per-block abs-max slots at the head of a quantize workspace
+
+inline int qmax_of(int bits) { return (1 << (bits - 1)) - 1; }
+inline bool bits_ok(int bits) { return bits >= 2 && bits <= 8; }
+inline bool packed4(int bits_w) { return bits_w <= 4; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+__host__ __device__ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---- quantizers (quantize.hip) ------------------------------------------------
+aqt_status launch_quantize(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bits, int axis,
+                           int8_t *q, float *scale, uint32_t *mask, float *partials, hipStream_t st,
+                           int32_t *dev_status);
+aqt_status launch_quantize_with_scale(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bits,
+                                      int axis, const float *scale, int8_t *q, uint32_t *mask,
+                                      hipStream_t st);
+aqt_status launch_quantize_weights(const float *w, int64_t K, int64_t N, int bits_w, void *wq_packed,
+                                   float *s_w, int8_t *wq_kn, uint32_t *mask_w, hipStream_t st,
+                                   int32_t *dev_status);
+aqt_status launch_unpack_weights(const void *wq_packed, int64_t K, int64_t N, int bits_w,
+                                 int8_t *codes_kn, hipStream_t st);
+
+// ---- forward contraction (gemm_fwd.hip) -----------------------------------------
+aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq_packed,
+                              const float *s_w, int64_t M, int64_t K, int64_t N, int bits_w,
+                              const float *bias, int epilogue, float *y, int32_t *acc_out,
+                              hipStream_t st);
+
+// ---- straight-through backward (gemm_bwd.hip) -------------------------------------
+size_t bwd_workspace_bytes(int64_t M, int64_t K, int64_t N);
+aqt_status launch_dense_bwd(const float *dy, const aqt_saved *sv, int64_t M, int64_t K, int64_t N,
+                            float *dx, float *dw, float *dbias, void *ws, size_t ws_bytes,
+                            hipStream_t st);
+
+}  // namespace aqt

@@ -1,0 +1,391 @@
+// Abs-max quantizers of native QAT (arxiv 2203.15952, Fig. 2 and Sec. 2.2) for gfx950.
+//
+// Per reduction group: m = max|x|, scale = m / qmax, code = floor(x / scale + 0.5)
+// with x / scale replaced by 0 when scale is 0.  Every operation is a single
+// float32 rounding (IEEE divide, separate add), so codes and scales are
+// reproducible bit for bit.  The kernels are bound by HBM traffic: the
+// per-tensor path reads the tensor twice (reduce, then quantize; the second pass
+// walks the tensor backwards so that the tail still sitting in the last-level
+// cache is served from there) and writes one byte per element.
+#include "aqt_internal.h"
+
+namespace aqt {
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ uint32_t abs_bits(float v) { return __float_as_uint(v) & 0x7FFFFFFFu; }
+
+// For non-negative floats the unsigned order of the bit patterns is the numeric
+// order, with +Inf and NaN above every finite value: one integer max both
+// reduces and detects non-finite input.
+__device__ __forceinline__ uint32_t wave_max(uint32_t v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    uint32_t o = static_cast<uint32_t>(__shfl_xor(static_cast<int>(v), off, 64));
+    v = v > o ? v : o;
+  }
+  return v;
+}
+
+// Max over a 256-thread block, result valid in every thread.
+__device__ __forceinline__ uint32_t block_max(uint32_t v, uint32_t *sm /*[4]*/) {
+  v = wave_max(v);
+  const int wave = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sm[wave] = v;
+  __syncthreads();
+  uint32_t a = sm[0], b = sm[1], c = sm[2], d = sm[3];
+  a = a > b ? a : b;
+  c = c > d ? c : d;
+  return a > c ? a : c;
+}
+
+// The element-wise part of Fig. 2.  fq = (float)qmax.
+__device__ __forceinline__ int quant_code(float x, float s, float fq, bool &pass) {
+  float t = (s == 0.0f) ? 0.0f : x / s;
+  float u = t + 0.5f;
+  float r = floorf(u);
+  pass = (r >= -fq) && (r <= fq) && (s != 0.0f);
+  r = fminf(fmaxf(r, -fq), fq);
+  return static_cast<int>(r);
+}
+
+__device__ __forceinline__ int quant_code(float x, float s, float fq) {
+  bool p;
+  return quant_code(x, s, fq, p);
+}
+
+// ---- per-tensor, contiguous: pass 1 -------------------------------------------
+__global__ __launch_bounds__(kThreads) void absmax_flat_kernel(const float *__restrict__ x, int64_t n,
+                                                               uint32_t *__restrict__ partial) {
+  __shared__ uint32_t sm[4];
+  const int64_t n4 = n >> 2;
+  const float4 *x4 = reinterpret_cast<const float4 *>(x);
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+  const int64_t gid = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  uint32_t m = 0;
+  int64_t i = gid;
+  for (; i + 3 * stride < n4; i += 4 * stride) {
+    float4 a = x4[i], b = x4[i + stride], c = x4[i + 2 * stride], d = x4[i + 3 * stride];
+    uint32_t ma = max(max(abs_bits(a.x), abs_bits(a.y)), max(abs_bits(a.z), abs_bits(a.w)));
+    uint32_t mb = max(max(abs_bits(b.x), abs_bits(b.y)), max(abs_bits(b.z), abs_bits(b.w)));
+    uint32_t mc = max(max(abs_bits(c.x), abs_bits(c.y)), max(abs_bits(c.z), abs_bits(c.w)));
+    uint32_t md = max(max(abs_bits(d.x), abs_bits(d.y)), max(abs_bits(d.z), abs_bits(d.w)));
+    m = max(m, max(max(ma, mb), max(mc, md)));
+  }
+  for (; i < n4; i += stride) {
+    float4 a = x4[i];
+    m = max(m, max(max(abs_bits(a.x), abs_bits(a.y)), max(abs_bits(a.z), abs_bits(a.w))));
+  }
+  for (int64_t j = (n4 << 2) + gid; j < n; j += stride) m = max(m, abs_bits(x[j]));
+  m = block_max(m, sm);
+  if (threadIdx.x == 0) partial[blockIdx.x] = m;
+}
+
+__device__ __forceinline__ uint32_t pack4(float4 v, float s, float fq) {
+  uint32_t c0 = static_cast<uint32_t>(quant_code(v.x, s, fq)) & 0xFFu;
+  uint32_t c1 = static_cast<uint32_t>(quant_code(v.y, s, fq)) & 0xFFu;
+  uint32_t c2 = static_cast<uint32_t>(quant_code(v.z, s, fq)) & 0xFFu;
+  uint32_t c3 = static_cast<uint32_t>(quant_code(v.w, s, fq)) & 0xFFu;
+  return c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+}
+
+// ---- per-tensor, contiguous: pass 2 -------------------------------------------
+__global__ __launch_bounds__(kThreads) void quantize_flat_kernel(
+    const float *__restrict__ x, int64_t n, const uint32_t *__restrict__ partial, int nparts, int qmax,
+    int8_t *__restrict__ q, float *__restrict__ scale, int32_t *dev_status) {
+  __shared__ uint32_t sm[4];
+  uint32_t m = 0;
+  for (int i = threadIdx.x; i < nparts; i += kThreads) m = max(m, partial[i]);
+  m = block_max(m, sm);
+  const float fq = static_cast<float>(qmax);
+  const float s = __uint_as_float(m) / fq;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    scale[0] = s;
+    if (m >= 0x7F800000u && dev_status) *dev_status = AQT_ERR_NONFINITE;
+  }
+  const int64_t n4 = n >> 2;
+  const float4 *x4 = reinterpret_cast<const float4 *>(x);
+  uint32_t *q4 = reinterpret_cast<uint32_t *>(q);
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+  const int64_t gid = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  int64_t i = n4 - 1 - gid;  // descending: the end of the tensor was read last by pass 1
+  for (; i - 3 * stride >= 0; i -= 4 * stride) {
+    float4 a = x4[i], b = x4[i - stride], c = x4[i - 2 * stride], d = x4[i - 3 * stride];
+    q4[i] = pack4(a, s, fq);
+    q4[i - stride] = pack4(b, s, fq);
+    q4[i - 2 * stride] = pack4(c, s, fq);
+    q4[i - 3 * stride] = pack4(d, s, fq);
+  }
+  for (; i >= 0; i -= stride) q4[i] = pack4(x4[i], s, fq);
+  for (int64_t j = (n4 << 2) + gid; j < n; j += stride) q[j] = static_cast<int8_t>(quant_code(x[j], s, fq));
+}
+
+// ---- general shapes: abs-max per tensor / column / row ---------------------------
+__global__ __launch_bounds__(kThreads) void absmax_strided_kernel(const float *__restrict__ x, int64_t rows,
+                                                                  int64_t cols, int64_t ldx,
+                                                                  uint32_t *__restrict__ partial) {
+  __shared__ uint32_t sm[4];
+  uint32_t m = 0;
+  const int64_t n = rows * cols;
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < n; i += stride) {
+    const int64_t r = i / cols, c = i - r * cols;
+    m = max(m, abs_bits(x[r * ldx + c]));
+  }
+  m = block_max(m, sm);
+  if (threadIdx.x == 0) partial[blockIdx.x] = m;
+}
+
+// Reduce the per-block maxima into the single scale (and the non-finite flag).
+__global__ __launch_bounds__(kThreads) void finish_scale_all_kernel(const uint32_t *__restrict__ partial,
+                                                                    int nparts, int qmax,
+                                                                    float *__restrict__ scale,
+                                                                    int32_t *dev_status) {
+  __shared__ uint32_t sm[4];
+  uint32_t m = 0;
+  for (int i = threadIdx.x; i < nparts; i += kThreads) m = max(m, partial[i]);
+  m = block_max(m, sm);
+  if (threadIdx.x == 0) {
+    scale[0] = __uint_as_float(m) / static_cast<float>(qmax);
+    if (m >= 0x7F800000u && dev_status) *dev_status = AQT_ERR_NONFINITE;
+  }
+}
+
+// One scale per column: 64 columns per block, 4 row lanes.
+__global__ __launch_bounds__(kThreads) void scale_cols_kernel(const float *__restrict__ x, int64_t rows,
+                                                              int64_t cols, int64_t ldx, int qmax,
+                                                              float *__restrict__ scale,
+                                                              int32_t *dev_status) {
+  __shared__ uint32_t sm[4][64];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int64_t c = static_cast<int64_t>(blockIdx.x) * 64 + tx;
+  uint32_t m = 0;
+  if (c < cols)
+    for (int64_t r = ty; r < rows; r += 4) m = max(m, abs_bits(x[r * ldx + c]));
+  sm[ty][tx] = m;
+  __syncthreads();
+  if (ty == 0 && c < cols) {
+    m = max(max(sm[0][tx], sm[1][tx]), max(sm[2][tx], sm[3][tx]));
+    scale[c] = __uint_as_float(m) / static_cast<float>(qmax);
+    if (m >= 0x7F800000u && dev_status) *dev_status = AQT_ERR_NONFINITE;
+  }
+}
+
+// One scale per row: one wavefront per row.
+__global__ __launch_bounds__(kThreads) void scale_rows_kernel(const float *__restrict__ x, int64_t rows,
+                                                              int64_t cols, int64_t ldx, int qmax,
+                                                              float *__restrict__ scale,
+                                                              int32_t *dev_status) {
+  const int lane = threadIdx.x & 63;
+  const int64_t r = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  uint32_t m = 0;
+  for (int64_t c = lane; c < cols; c += 64) m = max(m, abs_bits(x[r * ldx + c]));
+  m = wave_max(m);
+  if (lane == 0) {
+    scale[r] = __uint_as_float(m) / static_cast<float>(qmax);
+    if (m >= 0x7F800000u && dev_status) *dev_status = AQT_ERR_NONFINITE;
+  }
+}
+
+// Element-wise half for any axis / stride / mask: one thread per 32 consecutive
+// elements (one mask word).
+__global__ __launch_bounds__(kThreads) void quantize_elem_kernel(const float *__restrict__ x, int64_t rows,
+                                                                 int64_t cols, int64_t ldx, int qmax,
+                                                                 int axis, const float *__restrict__ scale,
+                                                                 int8_t *__restrict__ q,
+                                                                 uint32_t *__restrict__ mask) {
+  const int64_t n = rows * cols;
+  const int64_t w = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  const int64_t i0 = w * 32;
+  if (i0 >= n) return;
+  const float fq = static_cast<float>(qmax);
+  int64_t r = i0 / cols, c = i0 - r * cols;
+  uint32_t bits = 0;
+  const int cnt = static_cast<int>(min(static_cast<int64_t>(32), n - i0));
+  for (int j = 0; j < cnt; ++j) {
+    const float s = (axis == AQT_AXIS_ALL) ? scale[0] : (axis == AQT_AXIS_ROWS ? scale[c] : scale[r]);
+    bool pass;
+    q[i0 + j] = static_cast<int8_t>(quant_code(x[r * ldx + c], s, fq, pass));
+    bits |= static_cast<uint32_t>(pass) << j;
+    if (++c == cols) { c = 0; ++r; }
+  }
+  if (mask) mask[w] = bits;
+}
+
+// ---- weights: per output channel, emit the forward operand ------------------------
+// Block = 32 output channels x 8 fan-in lanes.  Phase 1 reduces |w| down each
+// column; phase 2 re-reads W (from L2) in 32 x 64 tiles, quantizes, writes the
+// [K,N] codes, transposes the tile through LDS and writes fan-in-contiguous rows,
+// packed two codes per byte when bits_w <= 4.
+constexpr int kWCols = 32;
+constexpr int kWChunk = 64;
+
+__global__ __launch_bounds__(kThreads) void quantize_weights_kernel(
+    const float *__restrict__ w, int64_t K, int64_t N, int qmax, int packed, uint8_t *__restrict__ wq_packed,
+    float *__restrict__ s_w, int8_t *__restrict__ wq_kn, uint32_t *__restrict__ mask_w, int32_t *dev_status) {
+  __shared__ uint32_t red[8][kWCols];
+  __shared__ int8_t tile[kWCols][kWChunk + 4];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int64_t n0 = static_cast<int64_t>(blockIdx.x) * kWCols;
+  const int64_t n = n0 + tx;
+  const bool live = n < N;
+  uint32_t m = 0;
+  if (live)
+    for (int64_t k = ty; k < K; k += 8) m = max(m, abs_bits(w[k * N + n]));
+  red[ty][tx] = m;
+  __syncthreads();
+  m = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) m = max(m, red[j][tx]);
+  const float fq = static_cast<float>(qmax);
+  const float s = __uint_as_float(m) / fq;
+  if (ty == 0 && live) {
+    s_w[n] = s;
+    if (m >= 0x7F800000u && dev_status) *dev_status = AQT_ERR_NONFINITE;
+  }
+  const int64_t row_bytes = packed ? (K + 1) / 2 : K;
+  for (int64_t k0 = 0; k0 < K; k0 += kWChunk) {
+#pragma unroll
+    for (int j = 0; j < kWChunk / 8; ++j) {
+      const int kk = ty + 8 * j;
+      const int64_t k = k0 + kk;
+      int code = 0;
+      if (live && k < K) {
+        bool pass;
+        code = quant_code(w[k * N + n], s, fq, pass);
+        if (wq_kn) wq_kn[k * N + n] = static_cast<int8_t>(code);
+        // Mask words straddle threads here; bits are set with an atomic OR on a
+        // buffer the launcher has zeroed.
+        if (mask_w && pass) atomicOr(&mask_w[(k * N + n) >> 5], 1u << ((k * N + n) & 31));
+      }
+      tile[tx][kk] = static_cast<int8_t>(code);
+    }
+    __syncthreads();
+    // 32 rows x (64 | 32) output bytes per chunk; thread t handles bytes t, t+256, ...
+    const int bytes_per_row = packed ? kWChunk / 2 : kWChunk;
+    for (int b = threadIdx.x; b < kWCols * bytes_per_row; b += kThreads) {
+      const int rn = b / bytes_per_row, jb = b - rn * bytes_per_row;
+      const int64_t nn = n0 + rn;
+      if (nn >= N) continue;
+      if (packed) {
+        const int64_t kb = (k0 >> 1) + jb;
+        if (kb < row_bytes) {
+          const uint32_t lo = static_cast<uint32_t>(tile[rn][2 * jb]) & 0xFu;
+          const uint32_t hi = static_cast<uint32_t>(tile[rn][2 * jb + 1]) & 0xFu;  // 0 beyond K
+          wq_packed[nn * row_bytes + kb] = static_cast<uint8_t>(lo | (hi << 4));
+        }
+      } else {
+        const int64_t k = k0 + jb;
+        if (k < K) wq_packed[nn * row_bytes + k] = static_cast<uint8_t>(tile[rn][jb]);
+      }
+    }
+    __syncthreads();
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void zero_words_kernel(uint32_t *p, int64_t n) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < n; i += stride) p[i] = 0;
+}
+
+__global__ __launch_bounds__(kThreads) void unpack_weights_kernel(const uint8_t *__restrict__ wq_packed,
+                                                                  int64_t K, int64_t N, int packed,
+                                                                  int8_t *__restrict__ codes_kn) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  if (i >= K * N) return;
+  const int64_t k = i / N, n = i - k * N;
+  int code;
+  if (packed) {
+    const uint32_t b = wq_packed[n * ((K + 1) / 2) + (k >> 1)];
+    const uint32_t nib = (k & 1) ? (b >> 4) : (b & 0xFu);
+    code = static_cast<int>(nib ^ 8u) - 8;  // sign-extend the nibble
+  } else {
+    code = static_cast<int8_t>(wq_packed[n * K + k]);
+  }
+  codes_kn[i] = static_cast<int8_t>(code);
+}
+
+int grid_for(int64_t work_items, int per_block, int cap) {
+  int64_t g = cdiv(work_items, per_block);
+  if (g < 1) g = 1;
+  if (g > cap) g = cap;
+  return static_cast<int>(g);
+}
+
+}  // namespace
+
+aqt_status launch_quantize(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bits, int axis,
+                           int8_t *q, float *scale, uint32_t *mask, float *partials, hipStream_t st,
+                           int32_t *dev_status) {
+  const int qmax = qmax_of(bits);
+  const int64_t n = rows * cols;
+  uint32_t *part = reinterpret_cast<uint32_t *>(partials);
+  if (axis == AQT_AXIS_ALL) {
+    const bool flat = (ldx == cols) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) &&
+                      (reinterpret_cast<uintptr_t>(q) % 4 == 0);
+    if (flat && !mask) {
+      // 2048 blocks = 8 per CU; every thread keeps four 16-byte loads in flight.
+      const int g = grid_for(n / 4, kThreads * 4, 2048);
+      absmax_flat_kernel<<<g, kThreads, 0, st>>>(x, n, part);
+      AQT_HIP(hipGetLastError());
+      quantize_flat_kernel<<<g, kThreads, 0, st>>>(x, n, part, g, qmax, q, scale, dev_status);
+      AQT_HIP(hipGetLastError());
+      return AQT_OK;
+    }
+    const int g = grid_for(n, kThreads * 8, 2048);
+    if (flat)
+      absmax_flat_kernel<<<g, kThreads, 0, st>>>(x, n, part);
+    else
+      absmax_strided_kernel<<<g, kThreads, 0, st>>>(x, rows, cols, ldx, part);
+    AQT_HIP(hipGetLastError());
+    finish_scale_all_kernel<<<1, kThreads, 0, st>>>(part, g, qmax, scale, dev_status);
+    AQT_HIP(hipGetLastError());
+  } else if (axis == AQT_AXIS_ROWS) {
+    scale_cols_kernel<<<static_cast<int>(cdiv(cols, 64)), kThreads, 0, st>>>(x, rows, cols, ldx, qmax, scale,
+                                                                             dev_status);
+    AQT_HIP(hipGetLastError());
+  } else {
+    scale_rows_kernel<<<static_cast<int>(cdiv(rows, 4)), kThreads, 0, st>>>(x, rows, cols, ldx, qmax, scale,
+                                                                            dev_status);
+    AQT_HIP(hipGetLastError());
+  }
+  return launch_quantize_with_scale(x, rows, cols, ldx, bits, axis, scale, q, mask, st);
+}
+
+aqt_status launch_quantize_with_scale(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bits,
+                                      int axis, const float *scale, int8_t *q, uint32_t *mask,
+                                      hipStream_t st) {
+  const int64_t words = cdiv(rows * cols, 32);
+  quantize_elem_kernel<<<static_cast<int>(cdiv(words, kThreads)), kThreads, 0, st>>>(
+      x, rows, cols, ldx, qmax_of(bits), axis, scale, q, mask);
+  AQT_HIP(hipGetLastError());
+  return AQT_OK;
+}
+
+aqt_status launch_quantize_weights(const float *w, int64_t K, int64_t N, int bits_w, void *wq_packed,
+                                   float *s_w, int8_t *wq_kn, uint32_t *mask_w, hipStream_t st,
+                                   int32_t *dev_status) {
+  if (mask_w) {
+    const int64_t words = cdiv(K * N, 32);
+    zero_words_kernel<<<grid_for(words, kThreads, 1024), kThreads, 0, st>>>(mask_w, words);
+    AQT_HIP(hipGetLastError());
+  }
+  quantize_weights_kernel<<<static_cast<int>(cdiv(N, kWCols)), kThreads, 0, st>>>(
+      w, K, N, qmax_of(bits_w), packed4(bits_w) ? 1 : 0, static_cast<uint8_t *>(wq_packed), s_w, wq_kn,
+      mask_w, dev_status);
+  AQT_HIP(hipGetLastError());
+  return AQT_OK;
+}
+
+aqt_status launch_unpack_weights(const void *wq_packed, int64_t K, int64_t N, int bits_w, int8_t *codes_kn,
+                                 hipStream_t st) {
+  unpack_weights_kernel<<<static_cast<int>(cdiv(K * N, kThreads)), kThreads, 0, st>>>(
+      static_cast<const uint8_t *>(wq_packed), K, N, packed4(bits_w) ? 1 : 0, codes_kn);
+  AQT_HIP(hipGetLastError());
+  return AQT_OK;
+}
+
+}  // namespace aqt
