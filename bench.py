@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized dense training step on one MI355X.
+
+A step is one pass of the whole hot path over one batch: for each of the two
+feed-forward layers of the training-step configuration (65536 tokens, 512->2048
+and 2048->512, int8 activations x int4 weights), quantize the activations per
+tensor, quantize and pack the weights per output channel, run the int8 MFMA
+contraction with fused de-quantization, then the straight-through backward
+(dX and dW).  Inputs are seeded synthetic tensors already resident in HBM.
+
+Prints ONE JSON line.  `value` is 6 GEMMs x 2MNK integer/float operations per
+step over the step time.  `roofline` describes the kernel that takes the most
+time in the step, timed live with HIP events on the launch stream.
+`cpu_baseline` is the CPU oracle timed on a bounded row sample of the same
+workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
+PEAK_INT8_TOPS = 5000.0      # dense int8 MFMA
+PEAK_BF16_TFLOPS = 2500.0    # dense bf16 MFMA
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--tokens", type=int, default=65536, help="rows of the activation tensors")
+    ap.add_argument("--cpu-rows", type=int, default=8192, help="row sample the CPU oracle is timed on (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2203_15952_amd import binding as B
+    from paper_2203_15952_amd import inputs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    B.lib()
+
+    cases = inputs.config5(seed=1, tokens=args.tokens)
+    layers = []
+    for c in cases:
+        L = dict(c=c, x=torch.from_numpy(c.x).cuda(), w=torch.from_numpy(c.w).cuda(),
+                 dy=torch.from_numpy(c.dy).cuda())
+        L["sv"] = B.Saved(c.M, c.K, c.N, c.bits_w)
+        L["y"] = torch.empty((c.M, c.N), dtype=torch.float32, device="cuda")
+        L["dx"] = torch.empty((c.M, c.K), dtype=torch.float32, device="cuda")
+        L["dw"] = torch.empty((c.K, c.N), dtype=torch.float32, device="cuda")
+        L["ws_q"] = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_QUANTIZE, c.M, c.K, 1))
+        L["ws_b"] = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_DENSE_BWD, c.M, c.K, c.N))
+        layers.append(L)
+    status = B.new_status()
+
+    # One step = these segments, each a C-ABI call that launches one kernel family.
+    seg_names = ["quantize_x", "quantize_w", "fwd_gemm", "bwd_dx", "bwd_dw"]
+
+    def run_step(events=None):
+        for li, L in enumerate(layers):
+            c, sv = L["c"], L["sv"]
+            def mark(i):
+                if events is not None:
+                    events[li][i].record()
+            mark(0)
+            B.aqt_quantize(L["x"], c.bits_x, B.AQT_AXIS_ALL, q=sv.xq, scale=sv.s_x, ws=L["ws_q"], dev_status=status)
+            mark(1)
+            B.aqt_quantize_weights(L["w"], c.bits_w, wq_packed=sv.wq_packed, s_w=sv.s_w, wq_kn=sv.wq_kn,
+                                   dev_status=status)
+            mark(2)
+            B.aqt_dense_fwd_q(sv.xq, sv.s_x, sv.wq_packed, sv.s_w, c.N, c.bits_x, c.bits_w, y=L["y"])
+            mark(3)
+            B.aqt_dense_bwd(L["dy"], sv, c.bits_x, c.bits_w, dx=L["dx"], want_dw=False, ws=L["ws_b"])
+            mark(4)
+            B.aqt_dense_bwd(L["dy"], sv, c.bits_x, c.bits_w, dw=L["dw"], want_dx=False, ws=L["ws_b"])
+            mark(5)
+
+    for _ in range(args.warmup):
+        run_step()
+    torch.cuda.synchronize()
+
+    ev = [[[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in layers] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        run_step(ev[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    assert int(status.item()) == 0, "non-finite input reported by the library"
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    gemm_ops = sum(2.0 * L["c"].M * L["c"].K * L["c"].N for L in layers)      # one GEMM per layer
+    total_ops = 3.0 * gemm_ops                                                  # fwd + dX + dW
+    value = total_ops / (ms_per_step * 1e-3) / 1e12
+
+    # per-segment average durations (ms) from the HIP events
+    seg_ms = {}
+    for li, L in enumerate(layers):
+        for i, name in enumerate(seg_names):
+            tot = sum(ev[s][li][i].elapsed_time(ev[s][li][i + 1]) for s in range(args.steps))
+            seg_ms[(li, name)] = tot / args.steps
+
+    def seg_roofline(li, name):
+        c = layers[li]["c"]
+        ms = seg_ms[(li, name)]
+        mnk2 = 2.0 * c.M * c.K * c.N
+        pk = 0.5 if c.bits_w <= 4 else 1.0
+        if name == "quantize_x":
+            by = c.M * c.K * 5.0                      # 4 B read + 1 B code written per element
+            return dict(bound="hbm", achieved=by / ms / 1e6, peak=PEAK_HBM_GBS, unit="GB/s")
+        if name == "quantize_w":
+            by = c.K * c.N * (4.0 + 1.0 + pk) + 4.0 * c.N
+            return dict(bound="hbm", achieved=by / ms / 1e6, peak=PEAK_HBM_GBS, unit="GB/s")
+        if name == "fwd_gemm":
+            # int8 MFMA work; whether HBM or MFMA bounds it depends on K (fp32 output)
+            by = c.M * c.K + c.K * c.N * pk + 4.0 * c.M * c.N
+            t_hbm, t_mfma = by / (PEAK_HBM_GBS * 1e9), mnk2 / (PEAK_INT8_TOPS * 1e12)
+            if t_hbm >= t_mfma:
+                return dict(bound="hbm", achieved=by / ms / 1e6, peak=PEAK_HBM_GBS, unit="GB/s")
+            return dict(bound="mfma", achieved=mnk2 / ms / 1e9, peak=PEAK_INT8_TOPS, unit="TOP/s")
+        # backward contractions run on bf16 MFMA (codes exact in bf16, float operand split hi/lo)
+        return dict(bound="mfma", achieved=mnk2 / ms / 1e9, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s")
+
+    kernels = {}
+    for (li, name), ms in seg_ms.items():
+        r = seg_roofline(li, name)
+        r["frac"] = r["achieved"] / r["peak"]
+        r["ms"] = ms
+        kernels[f"{layers[li]['c'].name}.{name}"] = r
+    dom_key = max(seg_ms, key=lambda k: seg_ms[k])
+    roof = dict(seg_roofline(*dom_key))
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = f"{layers[dom_key[0]]['c'].name}.{dom_key[1]}"
+    roof["avg_ms"] = seg_ms[dom_key]
+
+    cpu = None
+    if args.cpu_rows > 0:
+        import oracle
+        rows = min(args.cpu_rows, args.tokens)
+        t_cpu, ops_cpu = 0.0, 0.0
+        for L in layers:
+            c = L["c"]
+            xs, dys = c.x[:rows], c.dy[:rows]
+            t = time.perf_counter()
+            f = oracle.dense_fwd(xs, c.w, c.bits_x, c.bits_w)
+            oracle.dense_bwd(dys, f["xq"], f["s_x"][0], f["wq"], f["s_w"], want_dbias=False)
+            t_cpu += time.perf_counter() - t
+            ops_cpu += 3 * 2.0 * rows * c.K * c.N
+        cpu = dict(value=ops_cpu / t_cpu / 1e12, unit="TOPS", cores=oracle.num_threads(), kind="oracle",
+                   sample=f"first {rows} of {args.tokens} rows of both layers: quantize + int64 forward + "
+                          f"float64 dX and dW, {t_cpu:.1f} s", seconds=t_cpu)
+
+    out = {
+        "metric": "quantized dense fwd+bwd TOPS (int8 x int4, int32 acc)",
+        "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8 x int4 -> int32 (forward), bf16x2 -> f32 (backward)", "data": "synthetic",
+        "config": {"workload": "training step, forward + straight-through backward, "
+                               f"{args.tokens} tokens, Linear 512->2048 and 2048->512, int4 weights per channel, "
+                               "int8 activations per tensor, seed 1 (the fwd+bwd configuration of the metric)",
+                   "tokens": args.tokens, "layers": [[c.K, c.N] for c in cases]},
+        "pct_of_int8_mfma_peak": 100.0 * value / PEAK_INT8_TOPS,
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "kernels": kernels,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

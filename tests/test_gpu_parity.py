@@ -218,8 +218,13 @@ def test_dense_fwd_big_tiles_sampled():
 # ----------------------------------------------------------------------------
 # backward
 # ----------------------------------------------------------------------------
-BWD_CASES = [(256, 256, 1024, 8, 4), (300, 128, 256, 8, 8), (37, 50, 23, 8, 4), (5, 7, 3, 8, 8),
-             (1024, 512, 384, 8, 4)]
+BWD_CASES = [(256, 256, 1024, 8, 4),    # MFMA kernels, 128 x 128 tiles
+             (300, 128, 256, 8, 8),     # ragged M: clamped loads (dX), zero-filled tail (dW)
+             (37, 50, 23, 8, 4),        # general kernels
+             (5, 7, 3, 8, 8),
+             (1024, 512, 384, 8, 4),
+             (1000, 1024, 1024, 8, 4),  # dW on 256 x 256 tiles, several slabs, ragged M
+             (70, 128, 96, 8, 4)]       # dX on MFMA, dW on the general kernel
 
 
 @pytest.mark.parametrize("M,K,N,bx,bw", BWD_CASES)
@@ -280,3 +285,75 @@ def test_argument_errors_on_device_buffers():
     with pytest.raises(B.AqtError) as e:
         B.aqt_dense_fwd(x, x, 8, 4, ws=B.workspace(256))
     assert e.value.status == B.AQT_ERR_WORKSPACE
+
+
+# ----------------------------------------------------------------------------
+# the paper-shaped configurations at full size, in the launch configuration the
+# benchmark times: quantizers compared in full, contractions on sampled outputs
+# ----------------------------------------------------------------------------
+def run_full_size_case(c, n_samples=3000, backward=False):
+    say("full size", c.name, c.M, c.K, c.N, c.bits_x, c.bits_w, c.epilogue)
+    xq_ref, sx_ref = oracle.quantize(c.x, c.bits_x, oracle.AXIS_ALL)
+    wq_ref, sw_ref = oracle.quantize(c.w, c.bits_w, 0)
+    sv = B.Saved(c.M, c.K, c.N, c.bits_w)
+    status = B.new_status()
+    x_d, w_d = dev(c.x), dev(c.w)
+    y = B.aqt_dense_fwd(x_d, w_d, c.bits_x, c.bits_w, epilogue=c.epilogue, saved=sv, dev_status=status)
+    assert host(status)[0] == 0
+    np.testing.assert_array_equal(host(sv.s_x), sx_ref)
+    np.testing.assert_array_equal(host(sv.s_w), sw_ref)
+    np.testing.assert_array_equal(host(sv.xq), xq_ref)
+    np.testing.assert_array_equal(host(sv.wq_kn), wq_ref)
+    if c.bits_w <= 4:
+        np.testing.assert_array_equal(host(sv.wq_packed).reshape(c.N, -1), oracle.pack_int4(wq_ref))
+    else:
+        np.testing.assert_array_equal(host(sv.wq_packed).view(np.int8).reshape(c.N, c.K), wq_ref.T)
+    _, acc = B.aqt_dense_fwd_q(sv.xq, sv.s_x, sv.wq_packed, sv.s_w, c.N, c.bits_x, c.bits_w, want_acc=True)
+    acc_h, y_h = host(acc), host(y)
+    del acc
+    rng = np.random.default_rng(7)
+    im = np.r_[rng.integers(0, c.M, n_samples), [0, c.M - 1]]
+    out_cols = c.N // 2 if c.epilogue == 2 else c.N
+    ij = np.r_[rng.integers(0, out_cols, n_samples), [0, out_cols - 1]]
+    a, pre = oracle.dense_fwd_q_sampled(xq_ref, sx_ref[0], wq_ref, sw_ref, im, ij)
+    np.testing.assert_array_equal(acc_h[im, ij], a)
+    got = y_h[im, ij].astype(np.float64)
+    tol_v = 1e-6 * np.abs(pre) + 1e-37
+    if c.epilogue == 0:
+        assert (np.abs(got - pre) <= tol_v).all()
+    elif c.epilogue == 1:
+        ref = pre / (1 + np.exp(-pre))
+        assert (np.abs(got - ref) <= 1e-6 * np.abs(ref) + 1.1 * tol_v).all()
+    else:
+        a2, gate = oracle.dense_fwd_q_sampled(xq_ref, sx_ref[0], wq_ref, sw_ref, im, ij + out_cols)
+        np.testing.assert_array_equal(acc_h[im, ij + out_cols], a2)
+        sg = 1 / (1 + np.exp(-gate))
+        ref = pre * sg
+        tol = 1e-6 * np.abs(ref) + sg * tol_v + 0.25 * np.abs(pre) * (1e-6 * np.abs(gate)) + 1e-37
+        assert (np.abs(got - ref) <= tol).all()
+    if backward:
+        dy_d = dev(c.dy)
+        dx, dw, _ = B.aqt_dense_bwd(dy_d, sv, c.bits_x, c.bits_w)
+        dx_h, dw_h = host(dx), host(dw)
+        ik = np.r_[rng.integers(0, c.K, n_samples), [0, c.K - 1]]
+        r, ra = oracle.dense_bwd_dx_sampled(c.dy, wq_ref, sw_ref, im, ik)
+        err = np.abs(dx_h[im, ik] - r)
+        assert (err <= 1e-4 * ra + 1e-37).all() and err.max() <= 1e-4 * np.abs(r).max()
+        n_dw = 400
+        ik2, in2 = rng.integers(0, c.K, n_dw), rng.integers(0, c.N, n_dw)
+        r, ra = oracle.dense_bwd_dw_sampled(c.dy, xq_ref, sx_ref[0], ik2, in2)
+        err = np.abs(dw_h[ik2, in2] - r)
+        assert (err <= 1e-4 * ra + 1e-37).all() and err.max() <= 1e-4 * np.abs(r).max()
+        say("   bwd max err / 1e-4 bound:", float((err / (1e-4 * ra + 1e-37)).max()))
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4])
+def test_conformer_configs_full_size(cfg):
+    for c in inputs.CONFIGS[cfg]():
+        run_full_size_case(c)
+
+
+def test_training_step_full_size():
+    for c in inputs.config5():
+        run_full_size_case(c, backward=True)
+        torch.cuda.empty_cache()
