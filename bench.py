@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--tokens", type=int, default=65536, help="rows of the activation tensors")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="row sample the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a plain elementwise copy of 1 GiB (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -64,6 +66,7 @@ def main():
         L["dw"] = torch.empty((c.K, c.N), dtype=torch.float32, device="cuda")
         L["ws_q"] = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_QUANTIZE, c.M, c.K, 1))
         L["ws_b"] = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_DENSE_BWD, c.M, c.K, c.N))
+        L["ws_w"] = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_QUANTIZE_WEIGHTS, 1, c.K, c.N))
         layers.append(L)
     status = B.new_status()
 
@@ -80,7 +83,7 @@ def main():
             B.aqt_quantize(L["x"], c.bits_x, B.AQT_AXIS_ALL, q=sv.xq, scale=sv.s_x, ws=L["ws_q"], dev_status=status)
             mark(1)
             B.aqt_quantize_weights(L["w"], c.bits_w, wq_packed=sv.wq_packed, s_w=sv.s_w, wq_kn=sv.wq_kn,
-                                   dev_status=status)
+                                   ws=L["ws_w"], dev_status=status)
             mark(2)
             B.aqt_dense_fwd_q(sv.xq, sv.s_x, sv.wq_packed, sv.s_w, c.N, c.bits_x, c.bits_w, y=L["y"])
             mark(3)
@@ -101,6 +104,15 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     assert int(status.item()) == 0, "non-finite input reported by the library"
+
+    if args.calibrate_copy:
+        # known traffic: 2^28 floats read (1 GiB) and written (1 GiB) by one elementwise kernel
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     gemm_ops = sum(2.0 * L["c"].M * L["c"].K * L["c"].N for L in layers)      # one GEMM per layer

@@ -122,7 +122,8 @@ aqt_status aqt_quantize_with_scale(const float *x, int64_t rows, int64_t cols, i
  * over K) and emit the forward operand in the layout of
  * aqt_packed_weight_bytes().  wq_kn (nullable) also receives the codes as int8
  * in W's own [K,N] layout, which is what the backward contracts with;
- * clip_mask_w nullable, bit order of W[K,N].
+ * clip_mask_w nullable, bit order of W[K,N].  Needs
+ * aqt_workspace_bytes(AQT_OP_QUANTIZE_WEIGHTS, ., K, N, ., bits_w) of workspace.
  */
 aqt_status aqt_quantize_weights(const float *w, int64_t K, int64_t N, int bits_w, void *wq_packed,
                                 float *s_w, int8_t *wq_kn, uint32_t *clip_mask_w, void *ws,

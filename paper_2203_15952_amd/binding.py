@@ -151,7 +151,7 @@ def aqt_quantize_with_scale(x, bits: int, axis: int, scale, *, q=None, clip_mask
 
 
 def aqt_quantize_weights(w, bits_w: int, *, wq_packed=None, s_w=None, wq_kn=None, clip_mask_w=None,
-                         want_kn=True, want_mask=False, dev_status=None):
+                         want_kn=True, want_mask=False, ws=None, dev_status=None):
     """aqt_quantize_weights: returns (wq_packed uint8, s_w float32 [N], wq_kn int8 [K,N] or None, mask or None)."""
     _dev(w, torch.float32, "w")
     K, N = w.shape
@@ -162,8 +162,9 @@ def aqt_quantize_weights(w, bits_w: int, *, wq_packed=None, s_w=None, wq_kn=None
         wq_kn = torch.empty((K, N), dtype=torch.int8, device=w.device)
     if want_mask and clip_mask_w is None:
         clip_mask_w = torch.empty(_words(K * N), dtype=torch.int32, device=w.device)
+    ws = workspace(aqt_workspace_bytes(AQT_OP_QUANTIZE_WEIGHTS, 1, K, N), w.device) if ws is None else ws
     st = lib().aqt_quantize_weights(_ptr(w), K, N, bits_w, _ptr(wq_packed), _ptr(s_w), _ptr(wq_kn),
-                                    _ptr(clip_mask_w), None, 0, _stream(), _ptr(dev_status))
+                                    _ptr(clip_mask_w), _ptr(ws), ws.numel(), _stream(), _ptr(dev_status))
     _check(st, "aqt_quantize_weights")
     return wq_packed, s_w, wq_kn, clip_mask_w
 

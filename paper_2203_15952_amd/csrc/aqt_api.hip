@@ -9,6 +9,7 @@ namespace {
 
 struct FwdWorkspace {
   float *partials;   // kMaxPartials abs-max slots
+  uint32_t *wpart;   // kWeightSlabs x N per-channel slab maxima
   float *s_x;        // 1
   float *s_w;        // N
   int8_t *xq;        // M*K
@@ -27,6 +28,7 @@ FwdWorkspace carve_fwd(void *ws, int64_t M, int64_t K, int64_t N, int bits_w) {
     return p;
   };
   f.partials = reinterpret_cast<float *>(take(kMaxPartials * sizeof(float)));
+  f.wpart = reinterpret_cast<uint32_t *>(take(weight_ws_bytes(N)));
   f.s_x = reinterpret_cast<float *>(take(sizeof(float)));
   f.s_w = reinterpret_cast<float *>(take(static_cast<size_t>(N) * sizeof(float)));
   f.xq = reinterpret_cast<int8_t *>(take(static_cast<size_t>(M) * K));
@@ -75,7 +77,7 @@ size_t aqt_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int bits_x, 
   (void)bits_x;
   switch (op) {
     case AQT_OP_QUANTIZE: return kMaxPartials * sizeof(float);
-    case AQT_OP_QUANTIZE_WEIGHTS: return 256;
+    case AQT_OP_QUANTIZE_WEIGHTS: return N >= 1 ? weight_ws_bytes(N) : 0;
     case AQT_OP_DENSE_FWD_Q: return 256;
     case AQT_OP_DENSE_FWD:
       if (!shape_ok(M, K) || N < 1 || !bits_ok(bits_w)) return 0;
@@ -110,12 +112,11 @@ aqt_status aqt_quantize_with_scale(const float *x, int64_t rows, int64_t cols, i
 aqt_status aqt_quantize_weights(const float *w, int64_t K, int64_t N, int bits_w, void *wq_packed, float *s_w,
                                 int8_t *wq_kn, uint32_t *clip_mask_w, void *ws, size_t ws_bytes, void *stream,
                                 int32_t *dev_status) {
-  (void)ws;
-  (void)ws_bytes;
   if (!w || !wq_packed || !s_w || !shape_ok(K, N)) return AQT_ERR_INVALID_ARG;
   if (!bits_ok(bits_w)) return AQT_ERR_UNSUPPORTED;
+  if (!ws || ws_bytes < weight_ws_bytes(N)) return AQT_ERR_WORKSPACE;
   return launch_quantize_weights(w, K, N, bits_w, wq_packed, s_w, wq_kn, clip_mask_w,
-                                 static_cast<hipStream_t>(stream), dev_status);
+                                 static_cast<uint32_t *>(ws), static_cast<hipStream_t>(stream), dev_status);
 }
 
 aqt_status aqt_unpack_weights(const void *wq_packed, int64_t K, int64_t N, int bits_w, int8_t *codes_kn,
@@ -157,7 +158,7 @@ aqt_status aqt_dense_fwd(const float *x, const float *w, int64_t M, int64_t K, i
   AQT_TRY(launch_quantize(x, M, K, K, bits_x, AQT_AXIS_ALL, xq, s_x, saved ? saved->mask_x : nullptr,
                           f.partials, st, dev_status));
   AQT_TRY(launch_quantize_weights(w, K, N, bits_w, wq, s_w, saved ? saved->wq_kn : nullptr,
-                                  saved ? saved->mask_w : nullptr, st, dev_status));
+                                  saved ? saved->mask_w : nullptr, f.wpart, st, dev_status));
   return launch_dense_fwd_q(xq, s_x, wq, s_w, M, K, N, bits_w, bias, epilogue, y, nullptr, st);
 }
 

@@ -26,6 +26,7 @@ extern thread_local int g_last_hip_error;
   } while (0)
 
 constexpr int kMaxPartials = 4096;  // per-block abs-max slots at the head of a quantize workspace
+constexpr int kWeightSlabs = 16;    // fan-in slabs whose per-channel maxima the weight quantizer folds
 
 inline int qmax_of(int bits) { return (1 << (bits - 1)) - 1; }
 inline bool bits_ok(int bits) { return bits >= 2 && bits <= 8; }
@@ -41,8 +42,9 @@ aqt_status launch_quantize_with_scale(const float *x, int64_t rows, int64_t cols
                                       int axis, const float *scale, int8_t *q, uint32_t *mask,
                                       hipStream_t st);
 aqt_status launch_quantize_weights(const float *w, int64_t K, int64_t N, int bits_w, void *wq_packed,
-                                   float *s_w, int8_t *wq_kn, uint32_t *mask_w, hipStream_t st,
-                                   int32_t *dev_status);
+                                   float *s_w, int8_t *wq_kn, uint32_t *mask_w, uint32_t *part,
+                                   hipStream_t st, int32_t *dev_status);
+inline size_t weight_ws_bytes(int64_t N) { return align_up(static_cast<size_t>(kWeightSlabs) * N * 4, 256); }
 aqt_status launch_unpack_weights(const void *wq_packed, int64_t K, int64_t N, int bits_w,
                                  int8_t *codes_kn, hipStream_t st);
 

@@ -122,19 +122,42 @@ __global__ __launch_bounds__(kThreads) void codes_to_bf16_kernel(const int8_t *_
 // =====================================================================================
 // dX = (dy * s_w) . wq^T       rows m, columns k, contraction over n
 // Both operands are contraction-contiguous in memory (dy is [M,N], the bf16 codes
-// are [K,N]).  Workgroup = 2 x 2 wavefronts, tile (64*TM) x (64*TN); 32 n per
-// LDS stage; dy is scaled and split on its way into LDS.
+// are [K,N]).  Workgroup = 2 x 2 wavefronts, tile (64*TM) x (64*TN), 32 n per LDS
+// stage, two LDS slots, two workgroups per CU.  The split operand sits on the
+// short side of the wavefront tile (TM < TN) to keep LDS reads per MFMA low.
+//
+// Software pipeline of one stage (per wavefront), written so that the MFMA pipe
+// never waits for the other units.  A stage has two MFMA groups, one per 16-deep
+// fragment set f0 / f1:
+//   first half : MFMA(f0) while f1 is fetched from LDS and the NEXT stage is
+//                staged (dy scaled, split to bf16 hi/lo, stored to the other slot)
+//                in small pieces slotted between MFMA pairs;
+//   barrier    : the next stage is now complete in LDS;
+//   second half: MFMA(f1) while f0 of the next stage is fetched from LDS and the
+//                global loads for the stage after next are issued.
+// Loads past the last stage are clamped to it (harmless re-reads), so the loop
+// body is branch-free and the interleaving below is what the hardware issues.
+// LDS rows are 64 bytes without padding; their four 16-byte chunks are XOR-swizzled
+// with bits 1..2 of the row so that 8 consecutive rows hit 8 different bank groups.
 // =====================================================================================
-constexpr int kSN = 32;              // contraction elements per stage
-constexpr int kPitch = kSN * 2 + 16; // LDS row pitch in bytes (bf16 rows of 32, padded)
+constexpr int kSN = 32;      // contraction elements per stage
+constexpr int kRowB = 64;    // LDS row: 32 bf16
+constexpr int kPitch = 80;   // padded row pitch used by the dW kernel
+
+__device__ __forceinline__ int swz(int row) { return (row >> 1) & 3; }
+
+#define AQT_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 template <int TM, int TN>
-__global__ __launch_bounds__(kThreads) void bwd_dx_mfma_kernel(
+__global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
     const float *__restrict__ dy, const uint16_t *__restrict__ wq_bf, const float *__restrict__ s_w,
     const float *__restrict__ s_x, const uint32_t *__restrict__ mask_x, int M, int K, int N,
     float *__restrict__ dx, int tiles_m, int tiles_c) {
   constexpr int BM = 64 * TM, BC = 64 * TN;
-  constexpr int kStage = (2 * BM + BC) * kPitch;
+  constexpr int kStage = (2 * BM + BC) * kRowB;
+  constexpr int NA = 2 * TM;          // float4 of dy per thread per stage
+  constexpr int NB = TN;              // 16-byte pieces of codes per thread per stage
+  constexpr int P = TM * TN;          // MFMA pairs per half stage
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
   int id = blockIdx.x;
@@ -148,47 +171,48 @@ __global__ __launch_bounds__(kThreads) void bwd_dx_mfma_kernel(
   const int wm = wave >> 1, wn = wave & 1;
   const int lr = lane & 31, lk = lane >> 5;
 
-  float4 ra[2 * TM];
+  float4 ra[NA];
   float4 rs;
-  v4i rb[TN];
+  v4i rb[NB];
+
+  // Addresses: a tile-uniform base (moves with the stage) plus small per-thread
+  // byte offsets that stay fixed, so the loads can use scalar-base addressing.
+  const char *a_base = reinterpret_cast<const char *>(dy + static_cast<int64_t>(m0) * N);
+  const char *b_base = reinterpret_cast<const char *>(wq_bf + static_cast<int64_t>(c0) * N);
+  const char *s_base = reinterpret_cast<const char *>(s_w);
+  uint32_t ga[NA];
+#pragma unroll
+  for (int i = 0; i < NA; ++i) {
+    int row = (t >> 3) + 32 * i;                       // tile-local row of piece i
+    row = (m0 + row < M) ? row : (M - 1 - m0);         // ragged last tile: re-read the last row
+    ga[i] = static_cast<uint32_t>(row * N + (t & 7) * 4) * 4u;
+  }
+  const uint32_t gb0 = static_cast<uint32_t>((t >> 2) * N + (t & 3) * 8) * 2u;
+  const uint32_t gb_step = static_cast<uint32_t>(64 * N) * 2u;
+  const uint32_t gs = (t & 7) * 16u;
+  // LDS offsets: piece i of a thread sits 32 (dy) or 64 (codes) rows below piece 0,
+  // which leaves the swizzle bits of the row unchanged.
+  const int ra0 = t >> 3, qa = t & 7;
+  const int offa0 = ra0 * kRowB + (((qa >> 1) ^ swz(ra0)) << 4) + (qa & 1) * 8;
+  const int rb0 = t >> 2;
+  const int offb0 = (2 * BM + rb0) * kRowB + (((t & 3) ^ swz(rb0)) << 4);
 
   auto load_global = [&](int n0) {
-    rs = *reinterpret_cast<const float4 *>(s_w + n0 + (t & 7) * 4);
+    rs = *reinterpret_cast<const float4 *>(s_base + n0 * 4 + gs);
 #pragma unroll
-    for (int i = 0; i < 2 * TM; ++i) {
-      const int c = t + kThreads * i;
-      int row = m0 + (c >> 3);
-      row = row < M ? row : M - 1;
-      ra[i] = *reinterpret_cast<const float4 *>(dy + static_cast<int64_t>(row) * N + n0 + (c & 7) * 4);
-    }
+    for (int i = 0; i < NA; ++i) ra[i] = *reinterpret_cast<const float4 *>(a_base + n0 * 4 + ga[i]);
 #pragma unroll
-    for (int i = 0; i < TN; ++i) {
-      const int c = t + kThreads * i;
-      rb[i] = *reinterpret_cast<const v4i *>(wq_bf + static_cast<int64_t>(c0 + (c >> 2)) * N + n0 + (c & 3) * 8);
-    }
+    for (int i = 0; i < NB; ++i) rb[i] = *reinterpret_cast<const v4i *>(b_base + n0 * 2 + gb0 + i * gb_step);
   };
-
-  auto store_lds = [&](int buf) {
-    uint8_t *Ahi = lds + buf * kStage;
-    uint8_t *Alo = Ahi + BM * kPitch;
-    uint8_t *B = Alo + BM * kPitch;
-#pragma unroll
-    for (int i = 0; i < 2 * TM; ++i) {
-      const int c = t + kThreads * i;
-      const int off = (c >> 3) * kPitch + (c & 7) * 8;
-      v2i hi, lo;
-      uint32_t h, l;
-      split_bf16(ra[i].x * rs.x, ra[i].y * rs.y, h, l); hi.x = h; lo.x = l;
-      split_bf16(ra[i].z * rs.z, ra[i].w * rs.w, h, l); hi.y = h; lo.y = l;
-      *reinterpret_cast<v2i *>(Ahi + off) = hi;
-      *reinterpret_cast<v2i *>(Alo + off) = lo;
-    }
-#pragma unroll
-    for (int i = 0; i < TN; ++i) {
-      const int c = t + kThreads * i;
-      *reinterpret_cast<v4i *>(B + (c >> 2) * kPitch + (c & 3) * 16) = rb[i];
-    }
+  auto store_a = [&](int i, uint8_t *slot) {
+    v2i hi, lo;
+    uint32_t h, l;
+    split_bf16(ra[i].x * rs.x, ra[i].y * rs.y, h, l); hi.x = h; lo.x = l;
+    split_bf16(ra[i].z * rs.z, ra[i].w * rs.w, h, l); hi.y = h; lo.y = l;
+    *reinterpret_cast<v2i *>(slot + offa0 + i * 32 * kRowB) = hi;
+    *reinterpret_cast<v2i *>(slot + BM * kRowB + offa0 + i * 32 * kRowB) = lo;
   };
+  auto store_b = [&](int i, uint8_t *slot) { *reinterpret_cast<v4i *>(slot + offb0 + i * 64 * kRowB) = rb[i]; };
 
   v16f acc[TM][TN];
 #pragma unroll
@@ -198,36 +222,74 @@ __global__ __launch_bounds__(kThreads) void bwd_dx_mfma_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  const int NT = N / kSN;
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
-  for (int nt = 0; nt < NT; ++nt) {
-    const int buf = nt & 1;
-    if (nt + 1 < NT) load_global((nt + 1) * kSN);
-    const uint8_t *Ahi = lds + buf * kStage + (wm * 32 * TM + lr) * kPitch + lk * 16;
-    const uint8_t *Alo = Ahi + BM * kPitch;
-    const uint8_t *B = lds + buf * kStage + 2 * BM * kPitch + (wn * 32 * TN + lr) * kPitch + lk * 16;
+  // This lane's fragment addresses: tile rows are multiples of 32 apart, so the
+  // swizzle term depends on the lane only.
+  const int sw = swz(lr);
+  const int offk[2] = {((0 + lk) ^ sw) << 4, ((2 + lk) ^ sw) << 4};
+  const int a_row = (wm * 32 * TM + lr) * kRowB;
+  const int b_row = (2 * BM + wn * 32 * TN + lr) * kRowB;
+
+  struct Frags {
+    v4i ah[TM], al[TM], b[TN];
+  };
+  auto read_frags = [&](const uint8_t *slot, int kk, Frags &f) {
 #pragma unroll
-    for (int kk = 0; kk < kSN / 16; ++kk) {
-      v4i ah[TM], al[TM], b[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        ah[i] = *reinterpret_cast<const v4i *>(Ahi + i * 32 * kPitch + kk * 32);
-        al[i] = *reinterpret_cast<const v4i *>(Alo + i * 32 * kPitch + kk * 32);
-      }
-#pragma unroll
-      for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const v4i *>(B + j * 32 * kPitch + kk * 32);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          acc[i][j] = mfma_bf16(ah[i], b[j], acc[i][j]);
-          acc[i][j] = mfma_bf16(al[i], b[j], acc[i][j]);
-        }
+    for (int i = 0; i < TM; ++i) {
+      f.ah[i] = *reinterpret_cast<const v4i *>(slot + a_row + i * 32 * kRowB + offk[kk]);
+      f.al[i] = *reinterpret_cast<const v4i *>(slot + BM * kRowB + a_row + i * 32 * kRowB + offk[kk]);
     }
-    if (nt + 1 < NT) store_lds(buf ^ 1);
-    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < TN; ++j) f.b[j] = *reinterpret_cast<const v4i *>(slot + b_row + j * 32 * kRowB + offk[kk]);
+  };
+  // MFMA number q of a half stage, q in [0, 2*P): all hi products first, then all
+  // lo products, so that consecutive MFMAs never share an accumulator.
+  auto mfma_q = [&](const Frags &f, int q) {
+    const int tile = q % P, i = tile / TN, j = tile % TN;
+    acc[i][j] = mfma_bf16(q < P ? f.ah[i] : f.al[i], f.b[j], acc[i][j]);
+  };
+
+  const int NT = N / kSN;
+  const int last = (NT - 1) * kSN;
+  load_global(0);
+#pragma unroll
+  for (int i = 0; i < NA; ++i) store_a(i, lds);
+#pragma unroll
+  for (int i = 0; i < NB; ++i) store_b(i, lds);
+  load_global(kSN < last ? kSN : last);
+  __syncthreads();
+  Frags f0, f1;
+  read_frags(lds, 0, f0);
+
+  constexpr int C = NA + NB;  // staging pieces to slot between the P MFMA pairs of the first half
+  for (int nt = 0; nt < NT; ++nt) {
+    uint8_t *cur = lds + (nt & 1) * kStage;
+    uint8_t *nxt = lds + ((nt & 1) ^ 1) * kStage;
+    // ---- first half ----
+    read_frags(cur, 1, f1);
+    AQT_SCHED_FENCE();
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+      mfma_q(f0, 2 * p);
+      mfma_q(f0, 2 * p + 1);
+      AQT_SCHED_FENCE();
+#pragma unroll
+      for (int c = (p * C) / P; c < ((p + 1) * C) / P; ++c) {
+        if (c < NA) store_a(c, nxt);
+        else store_b(c - NA, nxt);
+      }
+      AQT_SCHED_FENCE();
+    }
+    __syncthreads();  // stage nt + 1 is complete in `nxt`; nobody reads `cur`'s f1 any more
+    // ---- second half ----
+    read_frags(nxt, 0, f0);
+    AQT_SCHED_FENCE();
+    {
+      const int n2 = (nt + 2) * kSN;
+      load_global(n2 < last ? n2 : last);
+    }
+    AQT_SCHED_FENCE();
+#pragma unroll
+    for (int q = 0; q < 2 * P; ++q) mfma_q(f1, q);
   }
 
   const bool pass_all = mask_x ? true : (s_x[0] != 0.0f);
@@ -251,30 +313,34 @@ __global__ __launch_bounds__(kThreads) void bwd_dx_mfma_kernel(
 // =====================================================================================
 // dW = s_x * xq^T . dy         rows k, columns n, contraction over m
 // Neither operand is contraction-contiguous in memory, so each thread gathers a
-// 4 (k or n) x 8 (m) block with coalesced row-wise loads, transposes it in
-// registers and writes 16-byte, m-contiguous pieces into LDS.  Tile-local row
-// index rho of the LDS images is de-interleaved, column 4*g + b lives in row
-// b*(B/4) + g, so that the 64 lanes of a wavefront write 64 consecutive rows.
-// The contraction is split over row slabs of M; each workgroup writes a float32
-// partial tile and a second kernel folds the slabs in a fixed order (run-to-run
-// reproducible), applies s_x and the mask.
+// small block (4 k x 8 m of codes, 4 n x 4 m of gradients) with coalesced row-wise
+// loads, transposes it in registers and writes m-contiguous pieces into LDS.
+// The tile-local row index of the LDS images is de-interleaved, column 4*g + b
+// lives in row b*(B/4) + g, so that the lanes of a wavefront write consecutive
+// rows.  The contraction is split over row slabs of M; each workgroup writes a
+// float32 partial tile and a second kernel folds the slabs in a fixed order
+// (run-to-run reproducible), applies s_x and the mask.  The split operand (dy)
+// sits on the short side of the wavefront tile (TC <= TR).
 // =====================================================================================
-template <int T>  // tile is (64*T) x (64*T); SM = 128/T rows of m per stage
-__global__ __launch_bounds__(kThreads) void bwd_dw_mfma_kernel(
+template <int TR, int TC>  // tile is (64*TR) k-rows x (64*TC) n-columns; 32 m per stage
+__global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_kernel(
     const int8_t *__restrict__ xq, const float *__restrict__ dy, int M, int K, int N, int m_per_slab,
     float *__restrict__ partial, int tiles_r, int tiles_c) {
-  constexpr int BT = 64 * T;             // tile edge (k rows, n columns)
-  constexpr int SM = 128 / T;            // m per stage: 32 (T=4) or 64 (T=2)
-  constexpr int G = BT / 4;              // 4-column groups per tile edge
-  constexpr int kP = SM * 2 + 16;        // LDS row pitch in bytes
-  constexpr int kStage = 3 * BT * kP;    // codes, dy hi, dy lo
+  constexpr int BR = 64 * TR, BC = 64 * TC;
+  constexpr int SM = 32;
+  constexpr int GA = BR / 4, GB = BC / 4;  // 4-column groups per tile edge
+  constexpr int UA = (BR + kThreads - 1) / kThreads;      // code units (4 k x 8 m) per thread
+  constexpr int UB = (2 * BC + kThreads - 1) / kThreads;  // gradient units (4 n x 4 m) per thread
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  uint8_t *const A_base = lds;
+  uint8_t *const Bhi_base = lds + BR * kPitch;
+  uint8_t *const Blo_base = Bhi_base + BC * kPitch;
 
   const int tiles = tiles_r * tiles_c;
   const int slab = blockIdx.x / tiles;
   const int tile = blockIdx.x - slab * tiles;
   const int br = tile / tiles_c, bc = tile - br * tiles_c;
-  const int r0 = br * BT, c0 = bc * BT;
+  const int r0 = br * BR, c0 = bc * BC;
   const int m_begin = slab * m_per_slab;
   const int m_end = min(M, m_begin + m_per_slab);
 
@@ -282,108 +348,135 @@ __global__ __launch_bounds__(kThreads) void bwd_dw_mfma_kernel(
   const int wave = t >> 6, lane = t & 63;
   const int wm = wave >> 1, wn = wave & 1;
   const int lr = lane & 31, lk = lane >> 5;
-  const int g = t % G, mg = t / G;       // this thread's column group and m group (8 rows of m)
 
-  uint32_t rx[8];
-  float4 ry[8];
+  uint32_t rx[UA][8];
+  float4 ry[UB][4];
 
   auto load_global = [&](int mbase) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int m = mbase + mg * 8 + i;
-      if (m < m_end) {
-        rx[i] = *reinterpret_cast<const uint32_t *>(xq + static_cast<int64_t>(m) * K + r0 + 4 * g);
-        ry[i] = *reinterpret_cast<const float4 *>(dy + static_cast<int64_t>(m) * N + c0 + 4 * g);
-      } else {
-        rx[i] = 0;
-        ry[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int u = 0; u < UA; ++u) {
+      const int unit = t + kThreads * u;
+      const int g = unit % GA, mg = unit / GA;
+      if (unit < BR) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int m = mbase + mg * 8 + i;
+          rx[u][i] = (m < m_end) ? *reinterpret_cast<const uint32_t *>(xq + static_cast<int64_t>(m) * K + r0 + 4 * g) : 0u;
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+      const int unit = t + kThreads * u;
+      const int g = unit % GB, ms = unit / GB;
+      if (unit < 2 * BC) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int m = mbase + ms * 4 + i;
+          ry[u][i] = (m < m_end) ? *reinterpret_cast<const float4 *>(dy + static_cast<int64_t>(m) * N + c0 + 4 * g)
+                                 : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
       }
     }
   };
 
-  auto store_lds = [&](int buf) {
-    uint8_t *A = lds + buf * kStage;
-    uint8_t *Bhi = A + BT * kP;
-    uint8_t *Blo = Bhi + BT * kP;
+  auto store_lds = [&]() {
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      // codes: byte b of the eight dwords -> eight bf16 along m
-      float f[8];
+    for (int u = 0; u < UA; ++u) {
+      const int unit = t + kThreads * u;
+      const int g = unit % GA, mg = unit / GA;
+      if (unit < BR) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) f[i] = static_cast<float>(static_cast<int8_t>(rx[i] >> (8 * b)));
-      v4i a;
-      a.x = pack_bf16(f[0], f[1]); a.y = pack_bf16(f[2], f[3]);
-      a.z = pack_bf16(f[4], f[5]); a.w = pack_bf16(f[6], f[7]);
-      const int row = b * G + g;
-      *reinterpret_cast<v4i *>(A + row * kP + mg * 16) = a;
-      // gradients: component b of the eight float4 -> hi/lo bf16 along m
-      float y[8];
+        for (int b = 0; b < 4; ++b) {
+          // byte b of the eight dwords -> eight bf16 along m
+          float f[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) y[i] = b == 0 ? ry[i].x : (b == 1 ? ry[i].y : (b == 2 ? ry[i].z : ry[i].w));
-      v4i hi, lo;
-      uint32_t h, l;
-      split_bf16(y[0], y[1], h, l); hi.x = h; lo.x = l;
-      split_bf16(y[2], y[3], h, l); hi.y = h; lo.y = l;
-      split_bf16(y[4], y[5], h, l); hi.z = h; lo.z = l;
-      split_bf16(y[6], y[7], h, l); hi.w = h; lo.w = l;
-      *reinterpret_cast<v4i *>(Bhi + row * kP + mg * 16) = hi;
-      *reinterpret_cast<v4i *>(Blo + row * kP + mg * 16) = lo;
+          for (int i = 0; i < 8; ++i) f[i] = static_cast<float>(static_cast<int8_t>(rx[u][i] >> (8 * b)));
+          v4i a;
+          a.x = pack_bf16(f[0], f[1]); a.y = pack_bf16(f[2], f[3]);
+          a.z = pack_bf16(f[4], f[5]); a.w = pack_bf16(f[6], f[7]);
+          *reinterpret_cast<v4i *>(A_base + (b * GA + g) * kPitch + mg * 16) = a;
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+      const int unit = t + kThreads * u;
+      const int g = unit % GB, ms = unit / GB;
+      if (unit < 2 * BC) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          // component b of the four float4 -> hi/lo bf16 along m
+          float y[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            y[i] = b == 0 ? ry[u][i].x : (b == 1 ? ry[u][i].y : (b == 2 ? ry[u][i].z : ry[u][i].w));
+          v2i hi, lo;
+          uint32_t h, l;
+          split_bf16(y[0], y[1], h, l); hi.x = h; lo.x = l;
+          split_bf16(y[2], y[3], h, l); hi.y = h; lo.y = l;
+          const int off = (b * GB + g) * kPitch + ms * 8;
+          *reinterpret_cast<v2i *>(Bhi_base + off) = hi;
+          *reinterpret_cast<v2i *>(Blo_base + off) = lo;
+        }
+      }
     }
   };
 
-  v16f acc[T][T];
+  v16f acc[TR][TC];
 #pragma unroll
-  for (int i = 0; i < T; ++i)
+  for (int i = 0; i < TR; ++i)
 #pragma unroll
-    for (int j = 0; j < T; ++j)
+    for (int j = 0; j < TC; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
   const int stages = (m_end - m_begin + SM - 1) / SM;
   if (stages > 0) {
     load_global(m_begin);
-    store_lds(0);
+    store_lds();
   }
   __syncthreads();
+  const uint8_t *A = A_base + (wm * 32 * TR + lr) * kPitch + lk * 16;
+  const uint8_t *Bhi = Bhi_base + (wn * 32 * TC + lr) * kPitch + lk * 16;
+  const uint8_t *Blo = Blo_base + (wn * 32 * TC + lr) * kPitch + lk * 16;
   for (int s = 0; s < stages; ++s) {
-    const int buf = s & 1;
-    if (s + 1 < stages) load_global(m_begin + (s + 1) * SM);
-    const uint8_t *A = lds + buf * kStage + (wm * 32 * T + lr) * kP + lk * 16;
-    const uint8_t *Bhi = lds + buf * kStage + BT * kP + (wn * 32 * T + lr) * kP + lk * 16;
-    const uint8_t *Blo = Bhi + BT * kP;
+    const bool more = s + 1 < stages;
+    if (more) load_global(m_begin + (s + 1) * SM);
 #pragma unroll
     for (int kk = 0; kk < SM / 16; ++kk) {
-      v4i a[T], bh[T], bl[T];
+      v4i a[TR], bh[TC], bl[TC];
 #pragma unroll
-      for (int i = 0; i < T; ++i) a[i] = *reinterpret_cast<const v4i *>(A + i * 32 * kP + kk * 32);
+      for (int i = 0; i < TR; ++i) a[i] = *reinterpret_cast<const v4i *>(A + i * 32 * kPitch + kk * 32);
 #pragma unroll
-      for (int j = 0; j < T; ++j) {
-        bh[j] = *reinterpret_cast<const v4i *>(Bhi + j * 32 * kP + kk * 32);
-        bl[j] = *reinterpret_cast<const v4i *>(Blo + j * 32 * kP + kk * 32);
+      for (int j = 0; j < TC; ++j) {
+        bh[j] = *reinterpret_cast<const v4i *>(Bhi + j * 32 * kPitch + kk * 32);
+        bl[j] = *reinterpret_cast<const v4i *>(Blo + j * 32 * kPitch + kk * 32);
       }
 #pragma unroll
-      for (int i = 0; i < T; ++i)
+      for (int i = 0; i < TR; ++i)
 #pragma unroll
-        for (int j = 0; j < T; ++j) {
+        for (int j = 0; j < TC; ++j) {
           acc[i][j] = mfma_bf16(a[i], bh[j], acc[i][j]);
           acc[i][j] = mfma_bf16(a[i], bl[j], acc[i][j]);
         }
     }
-    if (s + 1 < stages) store_lds(buf ^ 1);
+    __syncthreads();  // every wavefront is done reading this stage
+    if (more) store_lds();
     __syncthreads();
   }
 
   float *out = partial + static_cast<int64_t>(slab) * K * N;
 #pragma unroll
-  for (int j = 0; j < T; ++j) {
-    const int rho_c = wn * 32 * T + j * 32 + lr;
-    const int n = c0 + 4 * (rho_c % G) + rho_c / G;
+  for (int j = 0; j < TC; ++j) {
+    const int rho_c = wn * 32 * TC + j * 32 + lr;
+    const int n = c0 + 4 * (rho_c % GB) + rho_c / GB;
 #pragma unroll
-    for (int i = 0; i < T; ++i)
+    for (int i = 0; i < TR; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int rho_r = wm * 32 * T + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
-        const int k = r0 + 4 * (rho_r % G) + rho_r / G;
+        const int rho_r = wm * 32 * TR + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+        const int k = r0 + 4 * (rho_r % GA) + rho_r / GA;
         out[static_cast<int64_t>(k) * N + n] = acc[i][j][r];
       }
   }
@@ -416,8 +509,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dw_fold_kernel(const float *__re
 
 struct BwdPlan {
   bool dx_mfma, dw_mfma;
-  int dx_t;        // 4 or 2: tile edge 256 or 128
-  int dw_t;
+  bool dx_wide;    // 128 x 256 tiles (else 128 x 128)
+  bool dw_wide;    // 256 x 128 tiles (else 128 x 128)
   int slabs;
   int m_per_slab;
   size_t off_bf, off_part, off_bias, total;
@@ -428,16 +521,15 @@ BwdPlan plan_bwd(int64_t M, int64_t K, int64_t N) {
   const bool fits32 = M < (int64_t(1) << 31) / (K > N ? K : N);
   // dX: columns are K, contraction N in stages of 32
   p.dx_mfma = fits32 && (N % kSN == 0) && (K % 128 == 0);
-  p.dx_t = (K % 256 == 0 && cdiv(M, 256) * (K / 256) >= 512) ? 4 : 2;
+  p.dx_wide = (K % 256 == 0) && cdiv(M, 128) * (K / 256) >= 512;
   // dW: tiles over K x N, slabs over M
   p.dw_mfma = fits32 && (K % 128 == 0) && (N % 128 == 0);
-  p.dw_t = (K % 256 == 0 && N % 256 == 0 && (K / 256) * (N / 256) >= 16) ? 4 : 2;
-  const int edge = 64 * p.dw_t;
-  const int64_t tiles = (K / edge) * (N / edge);
+  p.dw_wide = (K % 256 == 0) && (K / 256) * (N / 128) >= 32;
+  const int64_t tiles = (K / (p.dw_wide ? 256 : 128)) * (N / 128);
   int64_t slabs = p.dw_mfma ? cdiv(512, tiles) : 1;
   if (slabs > 64) slabs = 64;
   int64_t per = cdiv(M, slabs);
-  per = cdiv(per, 64) * 64;            // whole stages
+  per = cdiv(per, 32) * 32;            // whole stages
   slabs = cdiv(M, per);
   p.slabs = static_cast<int>(slabs);
   p.m_per_slab = static_cast<int>(per);
@@ -453,7 +545,7 @@ template <int TM, int TN>
 aqt_status launch_dx(const float *dy, const uint16_t *wq_bf, const aqt_saved *sv, int64_t M, int64_t K, int64_t N,
                      float *dx, hipStream_t st) {
   constexpr int BM = 64 * TM, BC = 64 * TN;
-  constexpr int smem = 2 * (2 * BM + BC) * kPitch;
+  constexpr int smem = 2 * (2 * BM + BC) * kRowB;
   auto kern = bwd_dx_mfma_kernel<TM, TN>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -467,18 +559,18 @@ aqt_status launch_dx(const float *dy, const uint16_t *wq_bf, const aqt_saved *sv
   return AQT_OK;
 }
 
-template <int T>
+template <int TR, int TC>
 aqt_status launch_dw(const float *dy, const aqt_saved *sv, int64_t M, int64_t K, int64_t N, const BwdPlan &p,
                      float *partial, hipStream_t st) {
-  constexpr int BT = 64 * T, SM = 128 / T;
-  constexpr int smem = 2 * 3 * BT * (SM * 2 + 16);
-  auto kern = bwd_dw_mfma_kernel<T>;
+  constexpr int BR = 64 * TR, BC = 64 * TC;
+  constexpr int smem = (BR + 2 * BC) * kPitch;
+  auto kern = bwd_dw_mfma_kernel<TR, TC>;
   static bool attr_set = false;
   if (!attr_set) {
     AQT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem));
     attr_set = true;
   }
-  const int tiles_r = static_cast<int>(K / BT), tiles_c = static_cast<int>(N / BT);
+  const int tiles_r = static_cast<int>(K / BR), tiles_c = static_cast<int>(N / BC);
   kern<<<tiles_r * tiles_c * p.slabs, kThreads, smem, st>>>(sv->xq, dy, static_cast<int>(M), static_cast<int>(K),
                                                             static_cast<int>(N), p.m_per_slab, partial, tiles_r,
                                                             tiles_c);
@@ -504,7 +596,7 @@ aqt_status launch_dense_bwd(const float *dy, const aqt_saved *sv, int64_t M, int
       if (g > 2048) g = 2048;
       codes_to_bf16_kernel<<<g, kThreads, 0, st>>>(sv->wq_kn, n4, reinterpret_cast<uint32_t *>(wq_bf));
       AQT_HIP(hipGetLastError());
-      if (p.dx_t == 4) AQT_TRY((launch_dx<4, 4>(dy, wq_bf, sv, M, K, N, dx, st)));
+      if (p.dx_wide) AQT_TRY((launch_dx<2, 4>(dy, wq_bf, sv, M, K, N, dx, st)));
       else AQT_TRY((launch_dx<2, 2>(dy, wq_bf, sv, M, K, N, dx, st)));
     } else {
       bwd_dx_general_kernel<<<static_cast<int>(cdiv(M * K, kThreads)), kThreads, 0, st>>>(
@@ -516,8 +608,8 @@ aqt_status launch_dense_bwd(const float *dy, const aqt_saved *sv, int64_t M, int
     if (p.dw_mfma && dy_aligned && reinterpret_cast<uintptr_t>(sv->xq) % 4 == 0 &&
         reinterpret_cast<uintptr_t>(dw) % 16 == 0) {
       float *partial = reinterpret_cast<float *>(base + p.off_part);
-      if (p.dw_t == 4) AQT_TRY(launch_dw<4>(dy, sv, M, K, N, p, partial, st));
-      else AQT_TRY(launch_dw<2>(dy, sv, M, K, N, p, partial, st));
+      if (p.dw_wide) AQT_TRY((launch_dw<4, 2>(dy, sv, M, K, N, p, partial, st)));
+      else AQT_TRY((launch_dw<2, 2>(dy, sv, M, K, N, p, partial, st)));
       bwd_dw_fold_kernel<<<static_cast<int>(cdiv(K * N / 4, kThreads)), kThreads, 0, st>>>(
           partial, p.slabs, K * N, N, sv->s_x, sv->s_w, sv->mask_w, dw);
       AQT_HIP(hipGetLastError());

@@ -69,12 +69,13 @@ __global__ __launch_bounds__(kThreads) void dense_fwd_general_kernel(
 __device__ __forceinline__ void unpack8(uint32_t w, uint32_t &d0, uint32_t &d1) {
   const uint32_t lo = (w << 4) & 0xF0F0F0F0u;  // bytes: c0 c2 c4 c6 (each times 16)
   const uint32_t hi = w & 0xF0F0F0F0u;         // bytes: c1 c3 c5 c7
-  d0 = (lo & 0xFFu) | ((hi & 0xFFu) << 8) | ((lo & 0xFF00u) << 8) | ((hi & 0xFF00u) << 16);
-  d1 = ((lo >> 16) & 0xFFu) | (((hi >> 16) & 0xFFu) << 8) | ((lo >> 8) & 0xFF0000u) | (hi & 0xFF000000u);
+  // v_perm_b32 picks bytes out of {hi (selectors 4..7), lo (selectors 0..3)}
+  d0 = __builtin_amdgcn_perm(hi, lo, 0x05010400u);  // lo.b0 hi.b0 lo.b1 hi.b1
+  d1 = __builtin_amdgcn_perm(hi, lo, 0x07030602u);  // lo.b2 hi.b2 lo.b3 hi.b3
 }
 
 template <int TM, int TN, bool PACKED, int EPI>
-__global__ __launch_bounds__(kThreads) void dense_fwd_mfma_kernel(
+__global__ __launch_bounds__(kThreads, (TM * TN <= 8) ? 2 : 1) void dense_fwd_mfma_kernel(
     const int8_t *__restrict__ xq, const float *__restrict__ s_x, const uint8_t *__restrict__ wq,
     const float *__restrict__ s_w, int M, int K, int N, const float *__restrict__ bias,
     float *__restrict__ y, int32_t *__restrict__ acc_out, int tiles_m, int tiles_n) {
@@ -291,18 +292,17 @@ aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq
   const bool sizes_fit = M < (int64_t(1) << 31) / (K > N ? K : N);  // 32-bit tile arithmetic inside
   if (aligned && sizes_fit && K % kBK == 0) {
     // The column tile must divide N (N/2 for GLU, whose tile holds value and gate halves).
+    // 256 x 128 tiles (wavefront tile 128 x 64, two workgroups per CU so that one
+    // workgroup's epilogue and staging overlap the other's MFMA work) once there
+    // are enough of them to fill the chip, else 128 x 128.
     const int64_t nn = (epilogue == AQT_EPI_GLU) ? N / 2 : N;
-    const int64_t unit_big = (epilogue == AQT_EPI_GLU) ? 128 : 256;
-    const int64_t unit_small = (epilogue == AQT_EPI_GLU) ? 64 : 128;
-    const bool big_ok = nn % unit_big == 0;
-    const bool small_ok = nn % unit_small == 0;
-    // Prefer 256 x 256 tiles when they still give every CU a few workgroups.
-    const int64_t big_tiles = cdiv(M, 256) * (N / 256);
-    if (big_ok && big_tiles >= 512) {
-      return packed ? launch_mfma_epi<4, 4, true>(epilogue, xq, s_x, wq_packed, s_w, M, K, N, bias, y, acc_out, st)
-                    : launch_mfma_epi<4, 4, false>(epilogue, xq, s_x, wq_packed, s_w, M, K, N, bias, y, acc_out, st);
-    }
-    if (small_ok) {
+    const int64_t unit = (epilogue == AQT_EPI_GLU) ? 64 : 128;
+    if (nn % unit == 0) {
+      const int64_t wide_tiles = cdiv(M, 256) * (N / 128);
+      if (wide_tiles >= 512) {
+        return packed ? launch_mfma_epi<4, 2, true>(epilogue, xq, s_x, wq_packed, s_w, M, K, N, bias, y, acc_out, st)
+                      : launch_mfma_epi<4, 2, false>(epilogue, xq, s_x, wq_packed, s_w, M, K, N, bias, y, acc_out, st);
+      }
       return packed ? launch_mfma_epi<2, 2, true>(epilogue, xq, s_x, wq_packed, s_w, M, K, N, bias, y, acc_out, st)
                     : launch_mfma_epi<2, 2, false>(epilogue, xq, s_x, wq_packed, s_w, M, K, N, bias, y, acc_out, st);
     }

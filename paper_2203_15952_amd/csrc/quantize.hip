@@ -216,73 +216,84 @@ __global__ __launch_bounds__(kThreads) void quantize_elem_kernel(const float *__
 }
 
 // ---- weights: per output channel, emit the forward operand ------------------------
-// Block = 32 output channels x 8 fan-in lanes.  Phase 1 reduces |w| down each
-// column; phase 2 re-reads W (from L2) in 32 x 64 tiles, quantizes, writes the
-// [K,N] codes, transposes the tile through LDS and writes fan-in-contiguous rows,
-// packed two codes per byte when bits_w <= 4.
+// Two launches.  (1) abs-max of every column over a slab of fan-in rows: 64
+// columns x 4 row lanes per block, grid (column blocks, slabs).  (2) one block per
+// 32-channel x 64-fan-in tile folds the slab maxima of its channels into the scale,
+// quantizes the tile, writes the [K,N] codes, transposes the tile through LDS and
+// writes fan-in-contiguous rows, packed two codes per byte when bits_w <= 4.
 constexpr int kWCols = 32;
 constexpr int kWChunk = 64;
 
+__global__ __launch_bounds__(kThreads) void wabsmax_partial_kernel(const float *__restrict__ w, int64_t K,
+                                                                   int64_t N, int64_t rows_per_slab,
+                                                                   uint32_t *__restrict__ part) {
+  __shared__ uint32_t sm[4][64];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int64_t n = static_cast<int64_t>(blockIdx.x) * 64 + tx;
+  const int64_t k0 = static_cast<int64_t>(blockIdx.y) * rows_per_slab;
+  const int64_t k1 = min(K, k0 + rows_per_slab);
+  uint32_t m = 0;
+  if (n < N)
+    for (int64_t k = k0 + ty; k < k1; k += 4) m = max(m, abs_bits(w[k * N + n]));
+  sm[ty][tx] = m;
+  __syncthreads();
+  if (ty == 0 && n < N)
+    part[static_cast<int64_t>(blockIdx.y) * N + n] = max(max(sm[0][tx], sm[1][tx]), max(sm[2][tx], sm[3][tx]));
+}
+
 __global__ __launch_bounds__(kThreads) void quantize_weights_kernel(
-    const float *__restrict__ w, int64_t K, int64_t N, int qmax, int packed, uint8_t *__restrict__ wq_packed,
-    float *__restrict__ s_w, int8_t *__restrict__ wq_kn, uint32_t *__restrict__ mask_w, int32_t *dev_status) {
-  __shared__ uint32_t red[8][kWCols];
+    const float *__restrict__ w, int64_t K, int64_t N, int qmax, int packed, const uint32_t *__restrict__ part,
+    int slabs, uint8_t *__restrict__ wq_packed, float *__restrict__ s_w, int8_t *__restrict__ wq_kn,
+    uint32_t *__restrict__ mask_w, int32_t *dev_status) {
   __shared__ int8_t tile[kWCols][kWChunk + 4];
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
   const int64_t n0 = static_cast<int64_t>(blockIdx.x) * kWCols;
+  const int64_t k0 = static_cast<int64_t>(blockIdx.y) * kWChunk;
   const int64_t n = n0 + tx;
   const bool live = n < N;
   uint32_t m = 0;
   if (live)
-    for (int64_t k = ty; k < K; k += 8) m = max(m, abs_bits(w[k * N + n]));
-  red[ty][tx] = m;
-  __syncthreads();
-  m = 0;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) m = max(m, red[j][tx]);
+    for (int j = 0; j < slabs; ++j) m = max(m, part[static_cast<int64_t>(j) * N + n]);
   const float fq = static_cast<float>(qmax);
   const float s = __uint_as_float(m) / fq;
-  if (ty == 0 && live) {
+  if (blockIdx.y == 0 && ty == 0 && live) {
     s_w[n] = s;
     if (m >= 0x7F800000u && dev_status) *dev_status = AQT_ERR_NONFINITE;
   }
   const int64_t row_bytes = packed ? (K + 1) / 2 : K;
-  for (int64_t k0 = 0; k0 < K; k0 += kWChunk) {
 #pragma unroll
-    for (int j = 0; j < kWChunk / 8; ++j) {
-      const int kk = ty + 8 * j;
-      const int64_t k = k0 + kk;
-      int code = 0;
-      if (live && k < K) {
-        bool pass;
-        code = quant_code(w[k * N + n], s, fq, pass);
-        if (wq_kn) wq_kn[k * N + n] = static_cast<int8_t>(code);
-        // Mask words straddle threads here; bits are set with an atomic OR on a
-        // buffer the launcher has zeroed.
-        if (mask_w && pass) atomicOr(&mask_w[(k * N + n) >> 5], 1u << ((k * N + n) & 31));
-      }
-      tile[tx][kk] = static_cast<int8_t>(code);
+  for (int j = 0; j < kWChunk / 8; ++j) {
+    const int kk = ty + 8 * j;
+    const int64_t k = k0 + kk;
+    int code = 0;
+    if (live && k < K) {
+      bool pass;
+      code = quant_code(w[k * N + n], s, fq, pass);
+      if (wq_kn) wq_kn[k * N + n] = static_cast<int8_t>(code);
+      // Mask words straddle threads here; bits are set with an atomic OR on a
+      // buffer the launcher has zeroed.
+      if (mask_w && pass) atomicOr(&mask_w[(k * N + n) >> 5], 1u << ((k * N + n) & 31));
     }
-    __syncthreads();
-    // 32 rows x (64 | 32) output bytes per chunk; thread t handles bytes t, t+256, ...
-    const int bytes_per_row = packed ? kWChunk / 2 : kWChunk;
-    for (int b = threadIdx.x; b < kWCols * bytes_per_row; b += kThreads) {
-      const int rn = b / bytes_per_row, jb = b - rn * bytes_per_row;
-      const int64_t nn = n0 + rn;
-      if (nn >= N) continue;
-      if (packed) {
-        const int64_t kb = (k0 >> 1) + jb;
-        if (kb < row_bytes) {
-          const uint32_t lo = static_cast<uint32_t>(tile[rn][2 * jb]) & 0xFu;
-          const uint32_t hi = static_cast<uint32_t>(tile[rn][2 * jb + 1]) & 0xFu;  // 0 beyond K
-          wq_packed[nn * row_bytes + kb] = static_cast<uint8_t>(lo | (hi << 4));
-        }
-      } else {
-        const int64_t k = k0 + jb;
-        if (k < K) wq_packed[nn * row_bytes + k] = static_cast<uint8_t>(tile[rn][jb]);
+    tile[tx][kk] = static_cast<int8_t>(code);
+  }
+  __syncthreads();
+  // 32 rows x (64 | 32) output bytes; thread t handles bytes t, t+256, ...
+  const int bytes_per_row = packed ? kWChunk / 2 : kWChunk;
+  for (int b = threadIdx.x; b < kWCols * bytes_per_row; b += kThreads) {
+    const int rn = b / bytes_per_row, jb = b - rn * bytes_per_row;
+    const int64_t nn = n0 + rn;
+    if (nn >= N) continue;
+    if (packed) {
+      const int64_t kb = (k0 >> 1) + jb;
+      if (kb < row_bytes) {
+        const uint32_t lo = static_cast<uint32_t>(tile[rn][2 * jb]) & 0xFu;
+        const uint32_t hi = static_cast<uint32_t>(tile[rn][2 * jb + 1]) & 0xFu;  // 0 beyond K
+        wq_packed[nn * row_bytes + kb] = static_cast<uint8_t>(lo | (hi << 4));
       }
+    } else {
+      const int64_t k = k0 + jb;
+      if (k < K) wq_packed[nn * row_bytes + k] = static_cast<uint8_t>(tile[rn][jb]);
     }
-    __syncthreads();
   }
 }
 
@@ -366,16 +377,24 @@ aqt_status launch_quantize_with_scale(const float *x, int64_t rows, int64_t cols
 }
 
 aqt_status launch_quantize_weights(const float *w, int64_t K, int64_t N, int bits_w, void *wq_packed,
-                                   float *s_w, int8_t *wq_kn, uint32_t *mask_w, hipStream_t st,
+                                   float *s_w, int8_t *wq_kn, uint32_t *mask_w, uint32_t *part, hipStream_t st,
                                    int32_t *dev_status) {
   if (mask_w) {
     const int64_t words = cdiv(K * N, 32);
     zero_words_kernel<<<grid_for(words, kThreads, 1024), kThreads, 0, st>>>(mask_w, words);
     AQT_HIP(hipGetLastError());
   }
-  quantize_weights_kernel<<<static_cast<int>(cdiv(N, kWCols)), kThreads, 0, st>>>(
-      w, K, N, qmax_of(bits_w), packed4(bits_w) ? 1 : 0, static_cast<uint8_t *>(wq_packed), s_w, wq_kn,
-      mask_w, dev_status);
+  int64_t slabs = cdiv(K, 32);
+  if (slabs > kWeightSlabs) slabs = kWeightSlabs;
+  const int64_t rows_per_slab = cdiv(K, slabs);
+  slabs = cdiv(K, rows_per_slab);
+  dim3 g1(static_cast<unsigned>(cdiv(N, 64)), static_cast<unsigned>(slabs));
+  wabsmax_partial_kernel<<<g1, kThreads, 0, st>>>(w, K, N, rows_per_slab, part);
+  AQT_HIP(hipGetLastError());
+  dim3 g2(static_cast<unsigned>(cdiv(N, kWCols)), static_cast<unsigned>(cdiv(K, kWChunk)));
+  quantize_weights_kernel<<<g2, kThreads, 0, st>>>(w, K, N, qmax_of(bits_w), packed4(bits_w) ? 1 : 0, part,
+                                                   static_cast<int>(slabs), static_cast<uint8_t *>(wq_packed),
+                                                   s_w, wq_kn, mask_w, dev_status);
   AQT_HIP(hipGetLastError());
   return AQT_OK;
 }

@@ -71,6 +71,7 @@ def test_argument_errors_are_synchronous_and_touch_no_gpu(L):
     assert L.aqt_quantize(one, 4, 4, 4, 8, -1, one, one, none, one, 16, none, none) == B.AQT_ERR_WORKSPACE
     assert L.aqt_quantize_with_scale(one, 4, 4, 4, 8, -1, none, one, none, none) == B.AQT_ERR_INVALID_ARG
     assert L.aqt_quantize_weights(one, 4, 4, 12, one, one, none, none, none, 0, none, none) == B.AQT_ERR_UNSUPPORTED
+    assert L.aqt_quantize_weights(one, 4, 4, 4, one, one, none, none, none, 0, none, none) == B.AQT_ERR_WORKSPACE
     assert L.aqt_quantize_weights(one, 4, 4, 4, none, one, none, none, none, 0, none, none) == B.AQT_ERR_INVALID_ARG
     assert L.aqt_unpack_weights(none, 4, 4, 4, one, none) == B.AQT_ERR_INVALID_ARG
     # GLU needs an even N; epilogue must be known; K must keep 16*K*qmax_x*qmax_w inside int32
