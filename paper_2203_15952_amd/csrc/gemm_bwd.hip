@@ -13,6 +13,8 @@
 // v_mfma_f32_32x32x16_bf16 passes accumulate code*hi + code*lo in float32.
 // Every product is exact in float32, so the only other error is the float32
 // accumulation itself.
+#include <type_traits>
+
 #include "aqt_internal.h"
 
 namespace aqt {
@@ -126,15 +128,23 @@ __global__ __launch_bounds__(kThreads) void codes_to_bf16_kernel(const int8_t *_
 // stage, two LDS slots, two workgroups per CU.  The split operand sits on the
 // short side of the wavefront tile (TM < TN) to keep LDS reads per MFMA low.
 //
-// Software pipeline of one stage (per wavefront), written so that the MFMA pipe
-// never waits for the other units.  A stage has two MFMA groups, one per 16-deep
-// fragment set f0 / f1:
-//   first half : MFMA(f0) while f1 is fetched from LDS and the NEXT stage is
-//                staged (dy scaled, split to bf16 hi/lo, stored to the other slot)
-//                in small pieces slotted between MFMA pairs;
-//   barrier    : the next stage is now complete in LDS;
-//   second half: MFMA(f1) while f0 of the next stage is fetched from LDS and the
-//                global loads for the stage after next are issued.
+// Data movement.  The bf16 codes need no conversion: they go straight from global
+// memory into LDS (global_load_lds, 16 bytes per lane, each wavefront instruction
+// fills 1 KB of LDS in lane order; the swizzle is applied by choosing which global
+// piece a lane fetches).  dy has to be scaled and split, so it passes through
+// registers; two register sets alternate so that about two stages of the HBM
+// stream are always in flight per workgroup.
+//
+// Software pipeline of one stage (per wavefront).  A stage has two MFMA groups,
+// one per 16-deep fragment set f0 / f1:
+//   first half : MFMA(f0) while f1 is fetched from LDS and dy of the NEXT stage is
+//                scaled, split to bf16 hi/lo and stored to the other slot in
+//                pieces slotted between MFMA pairs; then the registers just freed
+//                are refilled with the loads for three stages ahead;
+//   barrier    : the next stage is complete in LDS (own LDS traffic drained, the
+//                code DMA issued one stage earlier has landed);
+//   second half: MFMA(f1) while f0 of the next stage is fetched and the code DMA
+//                for the stage after next is issued into the slot just vacated.
 // Loads past the last stage are clamped to it (harmless re-reads), so the loop
 // body is branch-free and the interleaving below is what the hardware issues.
 // LDS rows are 64 bytes without padding; their four 16-byte chunks are XOR-swizzled
@@ -148,71 +158,86 @@ __device__ __forceinline__ int swz(int row) { return (row >> 1) & 3; }
 
 #define AQT_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-template <int TM, int TN>
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+typedef __attribute__((address_space(1))) const void *global_void_ptr;
+
+// s_waitcnt immediate (gfx9 layout): at most `vm` vector-memory and `lgkm` LDS
+// operations of this wavefront may still be outstanding afterwards.
+constexpr int waitcnt_imm(int vm, int lgkm) {
+  return (vm & 0xF) | ((vm >> 4) << 14) | (7 << 4) | ((lgkm & 0xF) << 8);
+}
+
+template <int TM, int TN, bool MASKED>
 __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
     const float *__restrict__ dy, const uint16_t *__restrict__ wq_bf, const float *__restrict__ s_w,
     const float *__restrict__ s_x, const uint32_t *__restrict__ mask_x, int M, int K, int N,
     float *__restrict__ dx, int tiles_m, int tiles_c) {
   constexpr int BM = 64 * TM, BC = 64 * TN;
-  constexpr int kStage = (2 * BM + BC) * kRowB;
-  constexpr int NA = 2 * TM;          // float4 of dy per thread per stage
-  constexpr int NB = TN;              // 16-byte pieces of codes per thread per stage
-  constexpr int P = TM * TN;          // MFMA pairs per half stage
-  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  constexpr int kABytes = 2 * BM * kRowB;  // dy hi image, then dy lo image
+  constexpr int kBBytes = BC * kRowB;      // codes image
+  constexpr int NA = 2 * TM;              // float4 of dy per thread per stage
+  constexpr int NB = TN;                  // DMA instructions per wavefront per stage (1 KB each)
+  constexpr int P = TM * TN;              // MFMA pairs per half stage
+  // Two slots, each a dy image pair and a codes image.  They are four separate LDS
+  // variables on purpose: the compiler orders LDS accesses against in-flight
+  // global-to-LDS transfers only when they may touch the same variable.
+  __shared__ __attribute__((aligned(1024))) uint8_t sA0[kABytes], sA1[kABytes], sB0[kBBytes], sB1[kBBytes];
 
   int id = blockIdx.x;
   const int total = tiles_m * tiles_c;
   if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);  // one run of tiles per XCD
   const int bm = id / tiles_c, bc = id - bm * tiles_c;
-  const int m0 = bm * BM, c0 = bc * BC;
+  // A ragged last row tile is shifted up to end at row M: it recomputes a few rows
+  // of its neighbour (same values, same addresses) instead of clamping loads.
+  const int m0 = min(bm * BM, M - BM), c0 = bc * BC;
 
   const int t = threadIdx.x;
-  const int wave = t >> 6, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63;
   const int wm = wave >> 1, wn = wave & 1;
   const int lr = lane & 31, lk = lane >> 5;
 
-  float4 ra[NA];
+  float4 ra[2][NA];
   float4 rs;
-  v4i rb[NB];
 
-  // Addresses: a tile-uniform base (moves with the stage) plus small per-thread
-  // byte offsets that stay fixed, so the loads can use scalar-base addressing.
+  // dy: a tile-uniform base (moves with the stage) plus small per-thread byte
+  // offsets that stay fixed, so the loads can use scalar-base addressing.
   const char *a_base = reinterpret_cast<const char *>(dy + static_cast<int64_t>(m0) * N);
-  const char *b_base = reinterpret_cast<const char *>(wq_bf + static_cast<int64_t>(c0) * N);
   const char *s_base = reinterpret_cast<const char *>(s_w);
-  uint32_t ga[NA];
-#pragma unroll
-  for (int i = 0; i < NA; ++i) {
-    int row = (t >> 3) + 32 * i;                       // tile-local row of piece i
-    row = (m0 + row < M) ? row : (M - 1 - m0);         // ragged last tile: re-read the last row
-    ga[i] = static_cast<uint32_t>(row * N + (t & 7) * 4) * 4u;
-  }
-  const uint32_t gb0 = static_cast<uint32_t>((t >> 2) * N + (t & 3) * 8) * 2u;
-  const uint32_t gb_step = static_cast<uint32_t>(64 * N) * 2u;
+  const uint32_t ga0 = static_cast<uint32_t>((t >> 3) * N + (t & 7) * 4) * 4u;  // piece i: + i * 32 rows
+  const uint32_t ga_step = static_cast<uint32_t>(32 * N) * 4u;
   const uint32_t gs = (t & 7) * 16u;
-  // LDS offsets: piece i of a thread sits 32 (dy) or 64 (codes) rows below piece 0,
-  // which leaves the swizzle bits of the row unchanged.
+  // LDS offsets: piece i of a thread sits 32 rows below piece 0, which leaves the
+  // swizzle bits of the row unchanged.
   const int ra0 = t >> 3, qa = t & 7;
   const int offa0 = ra0 * kRowB + (((qa >> 1) ^ swz(ra0)) << 4) + (qa & 1) * 8;
-  const int rb0 = t >> 2;
-  const int offb0 = (2 * BM + rb0) * kRowB + (((t & 3) ^ swz(rb0)) << 4);
 
-  auto load_global = [&](int n0) {
-    rs = *reinterpret_cast<const float4 *>(s_base + n0 * 4 + gs);
+  // codes: DMA instruction i of this wavefront fills LDS rows (wave*NB + i)*16 .. +15
+  // of the codes image; lane p lands in row p/4, physical chunk p%4, and therefore
+  // fetches logical chunk (p%4) ^ swz(row) (the swizzle bits come from the lane only).
+  const char *b_base = reinterpret_cast<const char *>(wq_bf + static_cast<int64_t>(c0 + wave * NB * 16) * N);
+  const uint32_t gb0 = static_cast<uint32_t>((lane >> 2) * N + (((lane & 3) ^ swz(lane >> 2)) << 3)) * 2u;
+  const uint32_t gb_step = static_cast<uint32_t>(16 * N) * 2u;
+
+  auto load_s = [&](int n0) { rs = *reinterpret_cast<const float4 *>(s_base + n0 * 4 + gs); };
+  auto load_a = [&](int set, int n0) {
 #pragma unroll
-    for (int i = 0; i < NA; ++i) ra[i] = *reinterpret_cast<const float4 *>(a_base + n0 * 4 + ga[i]);
-#pragma unroll
-    for (int i = 0; i < NB; ++i) rb[i] = *reinterpret_cast<const v4i *>(b_base + n0 * 2 + gb0 + i * gb_step);
+    for (int i = 0; i < NA; ++i)
+      ra[set][i] = *reinterpret_cast<const float4 *>(a_base + n0 * 4 + ga0 + i * ga_step);
   };
-  auto store_a = [&](int i, uint8_t *slot) {
+  auto dma_b = [&](uint8_t *sB, int n0) {
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(b_base + n0 * 2 + gb0 + i * gb_step),
+                                       (lds_void_ptr)(sB + (wave * NB + i) * 1024), 16, 0, 0);
+  };
+  auto store_a = [&](int set, int i, uint8_t *slot) {
     v2i hi, lo;
     uint32_t h, l;
-    split_bf16(ra[i].x * rs.x, ra[i].y * rs.y, h, l); hi.x = h; lo.x = l;
-    split_bf16(ra[i].z * rs.z, ra[i].w * rs.w, h, l); hi.y = h; lo.y = l;
+    split_bf16(ra[set][i].x * rs.x, ra[set][i].y * rs.y, h, l); hi.x = h; lo.x = l;
+    split_bf16(ra[set][i].z * rs.z, ra[set][i].w * rs.w, h, l); hi.y = h; lo.y = l;
     *reinterpret_cast<v2i *>(slot + offa0 + i * 32 * kRowB) = hi;
     *reinterpret_cast<v2i *>(slot + BM * kRowB + offa0 + i * 32 * kRowB) = lo;
   };
-  auto store_b = [&](int i, uint8_t *slot) { *reinterpret_cast<v4i *>(slot + offb0 + i * 64 * kRowB) = rb[i]; };
 
   v16f acc[TM][TN];
 #pragma unroll
@@ -227,19 +252,19 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
   const int sw = swz(lr);
   const int offk[2] = {((0 + lk) ^ sw) << 4, ((2 + lk) ^ sw) << 4};
   const int a_row = (wm * 32 * TM + lr) * kRowB;
-  const int b_row = (2 * BM + wn * 32 * TN + lr) * kRowB;
+  const int b_row = (wn * 32 * TN + lr) * kRowB;
 
   struct Frags {
     v4i ah[TM], al[TM], b[TN];
   };
-  auto read_frags = [&](const uint8_t *slot, int kk, Frags &f) {
+  auto read_frags = [&](const uint8_t *sA, const uint8_t *sB, int kk, Frags &f) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-      f.ah[i] = *reinterpret_cast<const v4i *>(slot + a_row + i * 32 * kRowB + offk[kk]);
-      f.al[i] = *reinterpret_cast<const v4i *>(slot + BM * kRowB + a_row + i * 32 * kRowB + offk[kk]);
+      f.ah[i] = *reinterpret_cast<const v4i *>(sA + a_row + i * 32 * kRowB + offk[kk]);
+      f.al[i] = *reinterpret_cast<const v4i *>(sA + BM * kRowB + a_row + i * 32 * kRowB + offk[kk]);
     }
 #pragma unroll
-    for (int j = 0; j < TN; ++j) f.b[j] = *reinterpret_cast<const v4i *>(slot + b_row + j * 32 * kRowB + offk[kk]);
+    for (int j = 0; j < TN; ++j) f.b[j] = *reinterpret_cast<const v4i *>(sB + b_row + j * 32 * kRowB + offk[kk]);
   };
   // MFMA number q of a half stage, q in [0, 2*P): all hi products first, then all
   // lo products, so that consecutive MFMAs never share an accumulator.
@@ -250,22 +275,35 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
 
   const int NT = N / kSN;
   const int last = (NT - 1) * kSN;
-  load_global(0);
-#pragma unroll
-  for (int i = 0; i < NA; ++i) store_a(i, lds);
-#pragma unroll
-  for (int i = 0; i < NB; ++i) store_b(i, lds);
-  load_global(kSN < last ? kSN : last);
-  __syncthreads();
-  Frags f0, f1;
-  read_frags(lds, 0, f0);
+  auto stage_n0 = [&](int s) { const int n0 = s * kSN; return n0 < last ? n0 : last; };
 
-  constexpr int C = NA + NB;  // staging pieces to slot between the P MFMA pairs of the first half
-  for (int nt = 0; nt < NT; ++nt) {
-    uint8_t *cur = lds + (nt & 1) * kStage;
-    uint8_t *nxt = lds + ((nt & 1) ^ 1) * kStage;
+  // ---- prologue: stage 0 into slot 0, dy of stage 1 into register set 1, codes of
+  //      stage 1 on their way into slot 1 ----
+  load_s(0);
+  load_a(0, 0);
+  dma_b(sB0, 0);
+#pragma unroll
+  for (int i = 0; i < NA; ++i) store_a(0, i, sA0);
+  load_s(stage_n0(1));
+  load_a(1, stage_n0(1));
+  dma_b(sB1, stage_n0(1));
+  // codes of stage 0 landed: everything younger (scales, set 1, codes of stage 1) may stay in flight
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(1 + NA + NB, 0));
+  __builtin_amdgcn_s_barrier();
+  Frags f0, f1;
+  read_frags(sA0, sB0, 0, f0);
+
+  // One stage.  PAR = nt % 2 is a compile-time constant so that the register set
+  // (stage s lives in set s % 2) is addressed statically.
+  auto stage = [&](auto par, int nt) {
+    constexpr int PAR = decltype(par)::value;
+    uint8_t *curA = PAR ? sA1 : sA0, *curB = PAR ? sB1 : sB0;
+    uint8_t *nxtA = PAR ? sA0 : sA1, *nxtB = PAR ? sB0 : sB1;
     // ---- first half ----
-    read_frags(cur, 1, f1);
+    read_frags(curA, curB, 1, f1);
+    // Set PAR (emptied one stage ago) is refilled with stage nt + 2 while set PAR^1
+    // (stage nt + 1, a full stage in flight by now) is consumed below.
+    load_a(PAR, stage_n0(nt + 2));
     AQT_SCHED_FENCE();
 #pragma unroll
     for (int p = 0; p < P; ++p) {
@@ -273,39 +311,65 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
       mfma_q(f0, 2 * p + 1);
       AQT_SCHED_FENCE();
 #pragma unroll
-      for (int c = (p * C) / P; c < ((p + 1) * C) / P; ++c) {
-        if (c < NA) store_a(c, nxt);
-        else store_b(c - NA, nxt);
-      }
+      for (int c = (p * NA) / P; c < ((p + 1) * NA) / P; ++c) store_a(PAR ^ 1, c, nxtA);  // stage nt + 1
       AQT_SCHED_FENCE();
     }
-    __syncthreads();  // stage nt + 1 is complete in `nxt`; nobody reads `cur`'s f1 any more
+    load_s(stage_n0(nt + 2));   // scales for the staging done one stage from now
+    AQT_SCHED_FENCE();
+    // own LDS traffic drained; the code DMA for stage nt + 1 (issued half a stage ago) landed;
+    // only the loads issued in this half stay in flight
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(NA + 1, 0));
+    __builtin_amdgcn_s_barrier();
     // ---- second half ----
-    read_frags(nxt, 0, f0);
-    AQT_SCHED_FENCE();
-    {
-      const int n2 = (nt + 2) * kSN;
-      load_global(n2 < last ? n2 : last);
-    }
+    dma_b(curB, stage_n0(nt + 2));   // every wavefront is past its reads of the current slot
     AQT_SCHED_FENCE();
 #pragma unroll
-    for (int q = 0; q < 2 * P; ++q) mfma_q(f1, q);
-  }
+    for (int q = 0; q < P; ++q) mfma_q(f1, q);
+    AQT_SCHED_FENCE();
+    read_frags(nxtA, nxtB, 0, f0);
+    AQT_SCHED_FENCE();
+#pragma unroll
+    for (int q = P; q < 2 * P; ++q) mfma_q(f1, q);
+  };
 
-  const bool pass_all = mask_x ? true : (s_x[0] != 0.0f);
-#pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int k = c0 + wn * 32 * TN + j * 32 + lr;
+  int nt = 0;
+  for (; nt + 1 < NT; nt += 2) {
+    stage(std::integral_constant<int, 0>{}, nt);
+    stage(std::integral_constant<int, 1>{}, nt + 1);
+  }
+  if (nt < NT) stage(std::integral_constant<int, 0>{}, nt);
+  // drain the clamped prefetches before the registers and LDS are reused
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
+
+  // ---- epilogue: registers -> HBM.  Lane holds column (lane % 32) of each 32 x 32
+  // tile, register r holds row 8*(r/4) + 4*(lane/32) + r%4; 32 lanes write 128
+  // contiguous bytes.  Addresses are a uniform tile base plus one 32-bit lane offset;
+  // the row and tile steps are compile-time multiples of K folded into the base.
+  float *obase = dx + static_cast<int64_t>(m0) * K + c0;
+  const int lane_off = (wm * 32 * TM + 4 * lk) * K + wn * 32 * TN + lr;
+  if (MASKED) {
+    const int64_t tile0 = static_cast<int64_t>(m0) * K + c0;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * 32 * TM + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
-        if (m >= M) continue;
-        const int64_t idx = static_cast<int64_t>(m) * K + k;
-        bool pass = pass_all;
-        if (mask_x) pass = mask_bit(mask_x, idx);
-        dx[idx] = pass ? acc[i][j][r] : 0.0f;
+        const int row_off = (i * 32 + 8 * (r >> 2) + (r & 3)) * K;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int off = row_off + j * 32 + lane_off;
+          obase[off] = mask_bit(mask_x, tile0 + off) ? acc[i][j][r] : 0.0f;
+        }
+      }
+  } else {
+    const float keep = (s_x[0] != 0.0f) ? 1.0f : 0.0f;   // NULL mask: "the scale is non-zero"
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row_off = (i * 32 + 8 * (r >> 2) + (r & 3)) * K;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          obase[row_off + j * 32 + lane_off] = (keep != 0.0f) ? acc[i][j][r] : 0.0f;
       }
   }
 }
@@ -466,18 +530,23 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_kernel(
     __syncthreads();
   }
 
-  float *out = partial + static_cast<int64_t>(slab) * K * N;
+  // ---- epilogue: partial tile -> workspace.  Undo the de-interleaving of rows and
+  // columns; addresses are a uniform base plus a 32-bit lane offset plus
+  // compile-time multiples of N.
+  float *out = partial + static_cast<int64_t>(slab) * K * N + static_cast<int64_t>(r0) * N + c0;
 #pragma unroll
   for (int j = 0; j < TC; ++j) {
     const int rho_c = wn * 32 * TC + j * 32 + lr;
-    const int n = c0 + 4 * (rho_c % GB) + rho_c / GB;
+    const int n_l = 4 * (rho_c % GB) + rho_c / GB;
 #pragma unroll
     for (int i = 0; i < TR; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int rho_r = wm * 32 * TR + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
-        const int k = r0 + 4 * (rho_r % GA) + rho_r / GA;
-        out[static_cast<int64_t>(k) * N + n] = acc[i][j][r];
+        // rho_r = wm*32*TR + i*32 + 8*(r/4) + 4*lk + r%4 ; k_l = 4*(rho_r % GA) + rho_r / GA
+        const int rho_u = wm * 32 * TR + i * 32 + 8 * (r >> 2) + (r & 3);   // uniform part
+        const int rho_r = rho_u + 4 * lk;
+        const int k_l = 4 * (rho_r % GA) + rho_r / GA;
+        out[k_l * N + n_l] = acc[i][j][r];
       }
   }
 }
@@ -519,8 +588,8 @@ struct BwdPlan {
 BwdPlan plan_bwd(int64_t M, int64_t K, int64_t N) {
   BwdPlan p{};
   const bool fits32 = M < (int64_t(1) << 31) / (K > N ? K : N);
-  // dX: columns are K, contraction N in stages of 32
-  p.dx_mfma = fits32 && (N % kSN == 0) && (K % 128 == 0);
+  // dX: columns are K, contraction N in stages of 32; row tiles of 128 (the last one may be shifted)
+  p.dx_mfma = fits32 && (N % kSN == 0) && (K % 128 == 0) && (M >= 128);
   p.dx_wide = (K % 256 == 0) && cdiv(M, 128) * (K / 256) >= 512;
   // dW: tiles over K x N, slabs over M
   p.dw_mfma = fits32 && (K % 128 == 0) && (N % 128 == 0);
@@ -545,15 +614,9 @@ template <int TM, int TN>
 aqt_status launch_dx(const float *dy, const uint16_t *wq_bf, const aqt_saved *sv, int64_t M, int64_t K, int64_t N,
                      float *dx, hipStream_t st) {
   constexpr int BM = 64 * TM, BC = 64 * TN;
-  constexpr int smem = 2 * (2 * BM + BC) * kRowB;
-  auto kern = bwd_dx_mfma_kernel<TM, TN>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    AQT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem));
-    attr_set = true;
-  }
+  auto kern = sv->mask_x ? bwd_dx_mfma_kernel<TM, TN, true> : bwd_dx_mfma_kernel<TM, TN, false>;
   const int tiles_m = static_cast<int>(cdiv(M, BM)), tiles_c = static_cast<int>(K / BC);
-  kern<<<tiles_m * tiles_c, kThreads, smem, st>>>(dy, wq_bf, sv->s_w, sv->s_x, sv->mask_x, static_cast<int>(M),
+  kern<<<tiles_m * tiles_c, kThreads, 0, st>>>(dy, wq_bf, sv->s_w, sv->s_x, sv->mask_x, static_cast<int>(M),
                                                   static_cast<int>(K), static_cast<int>(N), dx, tiles_m, tiles_c);
   AQT_HIP(hipGetLastError());
   return AQT_OK;

@@ -90,7 +90,9 @@ __global__ __launch_bounds__(kThreads, (TM * TN <= 8) ? 2 : 1) void dense_fwd_mf
   const int total = tiles_m * tiles_n;
   if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
   const int bm = id / tiles_n, bn = id - bm * tiles_n;
-  const int m0 = bm * BM;
+  // A ragged last row tile is shifted up to end at row M: it recomputes a few rows
+  // of its neighbour (same values, same addresses) instead of predicating.
+  const int m0 = min(bm * BM, M - BM);
 
   const int t = threadIdx.x;
   const int wave = t >> 6, lane = t & 63;
@@ -115,8 +117,7 @@ __global__ __launch_bounds__(kThreads, (TM * TN <= 8) ? 2 : 1) void dense_fwd_mf
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       const int c = t + kThreads * i;
-      int row = m0 + (c >> 2);
-      row = row < M ? row : M - 1;
+      const int row = m0 + (c >> 2);
       ra[i] = *reinterpret_cast<const v4i *>(xq + static_cast<int64_t>(row) * K + k0 + (c & 3) * 16);
     }
     if (PACKED) {
@@ -205,46 +206,56 @@ __global__ __launch_bounds__(kThreads, (TM * TN <= 8) ? 2 : 1) void dense_fwd_mf
   // ---- epilogue: registers -> HBM ----
   // Lane holds output column (lane % 32) of each 32 x 32 tile; register r holds
   // row 8*(r/4) + 4*(lane/32) + r%4.  32 lanes write 128 contiguous bytes.
+  // Addresses are a uniform tile base plus one 32-bit lane offset; row and tile
+  // steps are compile-time multiples of the row length folded into the base.
   const float sx = s_x[0];
   const int out_cols = (EPI == AQT_EPI_GLU) ? (N >> 1) : N;
   constexpr int JS = (EPI == AQT_EPI_GLU) ? 2 : 1;
+  const int row_l = wm * 32 * TM + 4 * lk;
+  if (acc_out) {
+    int32_t *abase = acc_out + static_cast<int64_t>(m0) * N;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int lane_off = row_l * N + chan_of(wn * 32 * TN + j * 32 + lr);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int a0 = PACKED ? (acc[i][j][r] >> 4) : acc[i][j][r];
+          abase[(i * 32 + 8 * (r >> 2) + (r & 3)) * N + lane_off] = a0;
+        }
+    }
+  }
+  float *ybase = y + static_cast<int64_t>(m0) * out_cols;
 #pragma unroll
   for (int j = 0; j < TN; j += JS) {
-    const int n_a = chan_of(wn * 32 * TN + j * 32 + lr);
+    const int n_a = chan_of(wn * 32 * TN + j * 32 + lr);   // for GLU: the value channel = output column
     const float sc_a = sx * s_w[n_a];
     const float bias_a = bias ? bias[n_a] : 0.0f;
-    int n_b = 0;
     float sc_b = 0.0f, bias_b = 0.0f;
     if (EPI == AQT_EPI_GLU) {
-      n_b = chan_of(wn * 32 * TN + (j + 1) * 32 + lr);
+      const int n_b = chan_of(wn * 32 * TN + (j + 1) * 32 + lr);
       sc_b = sx * s_w[n_b];
       bias_b = bias ? bias[n_b] : 0.0f;
     }
+    const int lane_off = row_l * out_cols + n_a;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * 32 * TM + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
-        if (m >= M) continue;
-        int a0 = acc[i][j][r];
-        if (PACKED) a0 >>= 4;
-        if (acc_out) acc_out[static_cast<int64_t>(m) * N + n_a] = a0;
-        float v = dequant_f32(a0, sc_a);
-        if (bias) v = v + bias_a;
+        const int a0 = PACKED ? (acc[i][j][r] >> 4) : acc[i][j][r];
+        const float v = dequant_f32(a0, sc_a) + bias_a;   // adding a zero bias changes nothing
         float out;
         if (EPI == AQT_EPI_NONE) {
           out = v;
         } else if (EPI == AQT_EPI_SWISH) {
           out = swish_f32(v);
         } else {
-          int a1 = acc[i][j + (JS - 1)][r];
-          if (PACKED) a1 >>= 4;
-          if (acc_out) acc_out[static_cast<int64_t>(m) * N + n_b] = a1;
-          float g = dequant_f32(a1, sc_b);
-          if (bias) g = g + bias_b;
+          const int a1 = PACKED ? (acc[i][j + (JS - 1)][r] >> 4) : acc[i][j + (JS - 1)][r];
+          const float g = dequant_f32(a1, sc_b) + bias_b;
           out = v * sigmoid_f32(g);
         }
-        y[static_cast<int64_t>(m) * out_cols + n_a] = out;
+        ybase[(i * 32 + 8 * (r >> 2) + (r & 3)) * out_cols + lane_off] = out;
       }
     }
   }
@@ -297,9 +308,9 @@ aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq
     // are enough of them to fill the chip, else 128 x 128.
     const int64_t nn = (epilogue == AQT_EPI_GLU) ? N / 2 : N;
     const int64_t unit = (epilogue == AQT_EPI_GLU) ? 64 : 128;
-    if (nn % unit == 0) {
+    if (nn % unit == 0 && M >= 128) {
       const int64_t wide_tiles = cdiv(M, 256) * (N / 128);
-      if (wide_tiles >= 512) {
+      if (M >= 256 && wide_tiles >= 512) {
         return packed ? launch_mfma_epi<4, 2, true>(epilogue, xq, s_x, wq_packed, s_w, M, K, N, bias, y, acc_out, st)
                       : launch_mfma_epi<4, 2, false>(epilogue, xq, s_x, wq_packed, s_w, M, K, N, bias, y, acc_out, st);
       }
