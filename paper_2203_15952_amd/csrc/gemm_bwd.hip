@@ -107,44 +107,63 @@ __global__ __launch_bounds__(kThreads) void bwd_dbias_fold_kernel(const double *
   dbias[n] = static_cast<float>(s);
 }
 
-// int8 codes [K,N] -> bf16 [K,N] (exact), the dX kernel's second operand.
-__global__ __launch_bounds__(kThreads) void codes_to_bf16_kernel(const int8_t *__restrict__ codes, int64_t n4,
-                                                                 uint32_t *__restrict__ out) {
+// int8 codes [K,N] -> bf16 (exact) in MFMA-fragment order, the dX kernel's second
+// operand.  Fragment (jb, ks) covers fan-in rows 32*jb .. +31 and channels
+// 16*ks .. +15; inside it lane (lk*32 + lr) owns the 8 consecutive channels
+// 16*ks + 8*lk .. +7 of row 32*jb + lr, i.e. exactly what that lane feeds to
+// v_mfma_f32_32x32x16_bf16.  A fragment is 1 KB, fragments are ordered
+// [jb][ks], so a wavefront fetches one with a single fully coalesced 16-byte-per-lane load.
+__global__ __launch_bounds__(kThreads) void codes_to_bf16_frag_kernel(const int8_t *__restrict__ codes, int K,
+                                                                      int N, v4i *__restrict__ out) {
+  const int64_t pieces = static_cast<int64_t>(K) * (N / 8);   // one 16-byte piece per (row, 8 channels)
   const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
-  const uint32_t *c4 = reinterpret_cast<const uint32_t *>(codes);
-  for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < n4; i += stride) {
-    const uint32_t w = c4[i];
-    const float f0 = static_cast<float>(static_cast<int8_t>(w)), f1 = static_cast<float>(static_cast<int8_t>(w >> 8));
-    const float f2 = static_cast<float>(static_cast<int8_t>(w >> 16)), f3 = static_cast<float>(static_cast<int8_t>(w >> 24));
-    out[2 * i] = pack_bf16(f0, f1);
-    out[2 * i + 1] = pack_bf16(f2, f3);
+  const int ksteps = N / 16;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < pieces; i += stride) {
+    // i enumerates the output in order: ((jb * ksteps + ks) * 64 + lane)
+    const int lane = static_cast<int>(i & 63);
+    const int64_t frag = i >> 6;
+    const int ks = static_cast<int>(frag % ksteps), jb = static_cast<int>(frag / ksteps);
+    const int k = 32 * jb + (lane & 31), n = 16 * ks + 8 * (lane >> 5);
+    const v2i c = *reinterpret_cast<const v2i *>(codes + static_cast<int64_t>(k) * N + n);
+    float f[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      f[e] = static_cast<float>(static_cast<int8_t>(static_cast<uint32_t>(c.x) >> (8 * e)));
+      f[4 + e] = static_cast<float>(static_cast<int8_t>(static_cast<uint32_t>(c.y) >> (8 * e)));
+    }
+    v4i o;
+    o.x = pack_bf16(f[0], f[1]); o.y = pack_bf16(f[2], f[3]);
+    o.z = pack_bf16(f[4], f[5]); o.w = pack_bf16(f[6], f[7]);
+    out[i] = o;
   }
 }
 
 // =====================================================================================
 // dX = (dy * s_w) . wq^T       rows m, columns k, contraction over n
-// Both operands are contraction-contiguous in memory (dy is [M,N], the bf16 codes
-// are [K,N]).  Workgroup = 2 x 2 wavefronts, tile (64*TM) x (64*TN), 32 n per LDS
-// stage, two LDS slots, two workgroups per CU.  The split operand sits on the
-// short side of the wavefront tile (TM < TN) to keep LDS reads per MFMA low.
+// Workgroup = 2 x 2 wavefronts, tile (64*TM) x (64*TN), 32 n per stage, two
+// workgroups per CU.  The split operand sits on the short side of the wavefront
+// tile (TM < TN).
 //
-// Data movement.  The bf16 codes need no conversion: they go straight from global
-// memory into LDS (global_load_lds, 16 bytes per lane, each wavefront instruction
-// fills 1 KB of LDS in lane order; the swizzle is applied by choosing which global
-// piece a lane fetches).  dy has to be scaled and split, so it passes through
-// registers; two register sets alternate so that about two stages of the HBM
-// stream are always in flight per workgroup.
+// Data movement, chosen around what bounds this kernel on gfx950: LDS bandwidth
+// (about 64 bytes per clock and CU for 16-byte reads), not the matrix cores.
+//   * The bf16 codes never touch LDS.  They are stored in MFMA-fragment order
+//     (codes_to_bf16_frag_kernel), so each wavefront pulls its 1 KB fragments
+//     straight from L2 into registers with fully coalesced loads, one stage ahead.
+//   * dy has to be scaled and split, so it is staged: global -> registers (two
+//     alternating sets, a full stage in flight) -> bf16 hi/lo images in LDS (two
+//     slots) -> MFMA fragments.  Its fragments live in one register set that is
+//     refilled in place, each piece as soon as its last MFMA has issued.
 //
-// Software pipeline of one stage (per wavefront).  A stage has two MFMA groups,
-// one per 16-deep fragment set f0 / f1:
-//   first half : MFMA(f0) while f1 is fetched from LDS and dy of the NEXT stage is
-//                scaled, split to bf16 hi/lo and stored to the other slot in
-//                pieces slotted between MFMA pairs; then the registers just freed
-//                are refilled with the loads for three stages ahead;
-//   barrier    : the next stage is complete in LDS (own LDS traffic drained, the
-//                code DMA issued one stage earlier has landed);
-//   second half: MFMA(f1) while f0 of the next stage is fetched and the code DMA
-//                for the stage after next is issued into the slot just vacated.
+// Software pipeline of one stage (per wavefront): two MFMA groups of 2*TM*TN, one
+// per 16-deep fragment step.  Every other kind of work is cut into small pieces
+// slotted between MFMA pairs, so that the LDS, vector-memory and VALU traffic of
+// the next steps runs under the current MFMAs:
+//   first half : MFMA(step 0) | refill dy fragments for step 1 | stage dy of the
+//                next stage into the other LDS slot | fetch the codes of the next
+//                stage, step 0
+//   barrier    : the next stage's dy images are complete
+//   second half: MFMA(step 1) | refill dy fragments for the next stage, step 0 |
+//                fetch the codes of the next stage, step 1
 // Loads past the last stage are clamped to it (harmless re-reads), so the loop
 // body is branch-free and the interleaving below is what the hardware issues.
 // LDS rows are 64 bytes without padding; their four 16-byte chunks are XOR-swizzled
@@ -158,9 +177,6 @@ __device__ __forceinline__ int swz(int row) { return (row >> 1) & 3; }
 
 #define AQT_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-typedef __attribute__((address_space(3))) void *lds_void_ptr;
-typedef __attribute__((address_space(1))) const void *global_void_ptr;
-
 // s_waitcnt immediate (gfx9 layout): at most `vm` vector-memory and `lgkm` LDS
 // operations of this wavefront may still be outstanding afterwards.
 constexpr int waitcnt_imm(int vm, int lgkm) {
@@ -169,19 +185,14 @@ constexpr int waitcnt_imm(int vm, int lgkm) {
 
 template <int TM, int TN, bool MASKED>
 __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
-    const float *__restrict__ dy, const uint16_t *__restrict__ wq_bf, const float *__restrict__ s_w,
+    const float *__restrict__ dy, const v4i *__restrict__ wq_frag, const float *__restrict__ s_w,
     const float *__restrict__ s_x, const uint32_t *__restrict__ mask_x, int M, int K, int N,
     float *__restrict__ dx, int tiles_m, int tiles_c) {
   constexpr int BM = 64 * TM, BC = 64 * TN;
   constexpr int kABytes = 2 * BM * kRowB;  // dy hi image, then dy lo image
-  constexpr int kBBytes = BC * kRowB;      // codes image
-  constexpr int NA = 2 * TM;              // float4 of dy per thread per stage
-  constexpr int NB = TN;                  // DMA instructions per wavefront per stage (1 KB each)
-  constexpr int P = TM * TN;              // MFMA pairs per half stage
-  // Two slots, each a dy image pair and a codes image.  They are four separate LDS
-  // variables on purpose: the compiler orders LDS accesses against in-flight
-  // global-to-LDS transfers only when they may touch the same variable.
-  __shared__ __attribute__((aligned(1024))) uint8_t sA0[kABytes], sA1[kABytes], sB0[kBBytes], sB1[kBBytes];
+  constexpr int NA = 2 * TM;               // float4 of dy per thread per stage
+  constexpr int P = TM * TN;               // MFMA pairs per half stage
+  __shared__ __attribute__((aligned(1024))) uint8_t sA0[kABytes], sA1[kABytes];
 
   int id = blockIdx.x;
   const int total = tiles_m * tiles_c;
@@ -192,7 +203,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
   const int m0 = min(bm * BM, M - BM), c0 = bc * BC;
 
   const int t = threadIdx.x;
-  const int wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63;
+  const int wave = t >> 6, lane = t & 63;
   const int wm = wave >> 1, wn = wave & 1;
   const int lr = lane & 31, lk = lane >> 5;
 
@@ -211,24 +222,17 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
   const int ra0 = t >> 3, qa = t & 7;
   const int offa0 = ra0 * kRowB + (((qa >> 1) ^ swz(ra0)) << 4) + (qa & 1) * 8;
 
-  // codes: DMA instruction i of this wavefront fills LDS rows (wave*NB + i)*16 .. +15
-  // of the codes image; lane p lands in row p/4, physical chunk p%4, and therefore
-  // fetches logical chunk (p%4) ^ swz(row) (the swizzle bits come from the lane only).
-  const char *b_base = reinterpret_cast<const char *>(wq_bf + static_cast<int64_t>(c0 + wave * NB * 16) * N);
-  const uint32_t gb0 = static_cast<uint32_t>((lane >> 2) * N + (((lane & 3) ^ swz(lane >> 2)) << 3)) * 2u;
-  const uint32_t gb_step = static_cast<uint32_t>(16 * N) * 2u;
+  // codes: fragment (jb, ks) starts at ((jb * N/16) + ks) * 64 pieces of 16 bytes;
+  // this wavefront's column j-block is jb0 + j, a stage covers ks = 2*stage, 2*stage + 1.
+  const int ksteps = N / 16;
+  const v4i *b_lane = wq_frag + (static_cast<int64_t>(c0 / 32 + wn * TN) * ksteps) * 64 + lane;
+  const int b_jstep = ksteps * 64;
 
   auto load_s = [&](int n0) { rs = *reinterpret_cast<const float4 *>(s_base + n0 * 4 + gs); };
   auto load_a = [&](int set, int n0) {
 #pragma unroll
     for (int i = 0; i < NA; ++i)
       ra[set][i] = *reinterpret_cast<const float4 *>(a_base + n0 * 4 + ga0 + i * ga_step);
-  };
-  auto dma_b = [&](uint8_t *sB, int n0) {
-#pragma unroll
-    for (int i = 0; i < NB; ++i)
-      __builtin_amdgcn_global_load_lds((global_void_ptr)(b_base + n0 * 2 + gb0 + i * gb_step),
-                                       (lds_void_ptr)(sB + (wave * NB + i) * 1024), 16, 0, 0);
   };
   auto store_a = [&](int set, int i, uint8_t *slot) {
     v2i hi, lo;
@@ -247,89 +251,91 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  // This lane's fragment addresses: tile rows are multiples of 32 apart, so the
-  // swizzle term depends on the lane only.
+  // dy fragments: this lane's addresses.  Tile rows are multiples of 32 apart, so
+  // the swizzle term depends on the lane only.
   const int sw = swz(lr);
   const int offk[2] = {((0 + lk) ^ sw) << 4, ((2 + lk) ^ sw) << 4};
   const int a_row = (wm * 32 * TM + lr) * kRowB;
-  const int b_row = (wn * 32 * TN + lr) * kRowB;
-
-  struct Frags {
-    v4i ah[TM], al[TM], b[TN];
+  v4i fa[2 * TM];   // ah[0..TM-1], al[0..TM-1] of the fragment step in flight
+  auto read_a = [&](const uint8_t *sA, int kk, int idx) {
+    const int i = idx % TM, img = idx / TM;
+    fa[idx] = *reinterpret_cast<const v4i *>(sA + img * BM * kRowB + a_row + i * 32 * kRowB + offk[kk]);
   };
-  auto read_frags = [&](const uint8_t *sA, const uint8_t *sB, int kk, Frags &f) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      f.ah[i] = *reinterpret_cast<const v4i *>(sA + a_row + i * 32 * kRowB + offk[kk]);
-      f.al[i] = *reinterpret_cast<const v4i *>(sA + BM * kRowB + a_row + i * 32 * kRowB + offk[kk]);
-    }
-#pragma unroll
-    for (int j = 0; j < TN; ++j) f.b[j] = *reinterpret_cast<const v4i *>(sB + b_row + j * 32 * kRowB + offk[kk]);
+  // codes fragments: one register set per (stage parity, fragment step)
+  v4i fb[2][2][TN];
+  auto load_b = [&](int par, int kk, int j, int stage) {
+    fb[par][kk][j] = b_lane[static_cast<int64_t>(j) * b_jstep + (2 * stage + kk) * 64];
   };
   // MFMA number q of a half stage, q in [0, 2*P): all hi products first, then all
-  // lo products, so that consecutive MFMAs never share an accumulator.
-  auto mfma_q = [&](const Frags &f, int q) {
+  // lo products, so that consecutive MFMAs never share an accumulator and each dy
+  // fragment is used by TN consecutive MFMAs.
+  auto mfma_q = [&](int par, int kk, int q) {
     const int tile = q % P, i = tile / TN, j = tile % TN;
-    acc[i][j] = mfma_bf16(q < P ? f.ah[i] : f.al[i], f.b[j], acc[i][j]);
+    acc[i][j] = mfma_bf16(fa[(q < P ? 0 : TM) + i], fb[par][kk][j], acc[i][j]);
   };
 
   const int NT = N / kSN;
   const int last = (NT - 1) * kSN;
-  auto stage_n0 = [&](int s) { const int n0 = s * kSN; return n0 < last ? n0 : last; };
+  auto stage_idx = [&](int s) { return s < NT - 1 ? s : NT - 1; };
+  auto stage_n0 = [&](int s) { return stage_idx(s) * kSN; };
 
-  // ---- prologue: stage 0 into slot 0, dy of stage 1 into register set 1, codes of
-  //      stage 1 on their way into slot 1 ----
+  // ---- prologue: stage 0 staged into slot 0, dy of stage 1 into register set 1,
+  //      codes of stage 0 into their register sets ----
   load_s(0);
   load_a(0, 0);
-  dma_b(sB0, 0);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) { load_b(0, 0, j, 0); load_b(0, 1, j, 0); }
 #pragma unroll
   for (int i = 0; i < NA; ++i) store_a(0, i, sA0);
   load_s(stage_n0(1));
   load_a(1, stage_n0(1));
-  dma_b(sB1, stage_n0(1));
-  // codes of stage 0 landed: everything younger (scales, set 1, codes of stage 1) may stay in flight
-  __builtin_amdgcn_s_waitcnt(waitcnt_imm(1 + NA + NB, 0));
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
   __builtin_amdgcn_s_barrier();
-  Frags f0, f1;
-  read_frags(sA0, sB0, 0, f0);
+#pragma unroll
+  for (int idx = 0; idx < 2 * TM; ++idx) read_a(sA0, 0, idx);
 
-  // One stage.  PAR = nt % 2 is a compile-time constant so that the register set
-  // (stage s lives in set s % 2) is addressed statically.
+  // One stage.  PAR = nt % 2 is a compile-time constant so that register sets
+  // (stage s lives in set s % 2) are addressed statically.
   auto stage = [&](auto par, int nt) {
     constexpr int PAR = decltype(par)::value;
-    uint8_t *curA = PAR ? sA1 : sA0, *curB = PAR ? sB1 : sB0;
-    uint8_t *nxtA = PAR ? sA0 : sA1, *nxtB = PAR ? sB0 : sB1;
-    // ---- first half ----
-    read_frags(curA, curB, 1, f1);
-    // Set PAR (emptied one stage ago) is refilled with stage nt + 2 while set PAR^1
-    // (stage nt + 1, a full stage in flight by now) is consumed below.
+    uint8_t *curA = PAR ? sA1 : sA0;
+    uint8_t *nxtA = PAR ? sA0 : sA1;
+    const int s1 = stage_idx(nt + 1);
+    // ---- first half: fragment step 0 ----
+    // dy set PAR (emptied one stage ago) is refilled with stage nt + 2 while set PAR^1
+    // (stage nt + 1, a full stage in flight by now) is staged below.
     load_a(PAR, stage_n0(nt + 2));
     AQT_SCHED_FENCE();
 #pragma unroll
     for (int p = 0; p < P; ++p) {
-      mfma_q(f0, 2 * p);
-      mfma_q(f0, 2 * p + 1);
+      mfma_q(PAR, 0, 2 * p);
+      mfma_q(PAR, 0, 2 * p + 1);
       AQT_SCHED_FENCE();
+      // dy fragment idx is free once MFMA TN*(idx+1) - 1 has issued: refill it for step 1
+#pragma unroll
+      for (int idx = 0; idx < 2 * TM; ++idx)
+        if (2 * p + 1 == TN * (idx + 1) - 1) read_a(curA, 1, idx);
 #pragma unroll
       for (int c = (p * NA) / P; c < ((p + 1) * NA) / P; ++c) store_a(PAR ^ 1, c, nxtA);  // stage nt + 1
+      if (p < TN) load_b(PAR ^ 1, 0, p, s1);
       AQT_SCHED_FENCE();
     }
     load_s(stage_n0(nt + 2));   // scales for the staging done one stage from now
     AQT_SCHED_FENCE();
-    // own LDS traffic drained; the code DMA for stage nt + 1 (issued half a stage ago) landed;
-    // only the loads issued in this half stay in flight
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(NA + 1, 0));
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));   // own LDS traffic drained
     __builtin_amdgcn_s_barrier();
-    // ---- second half ----
-    dma_b(curB, stage_n0(nt + 2));   // every wavefront is past its reads of the current slot
-    AQT_SCHED_FENCE();
+    // ---- second half: fragment step 1 ----
 #pragma unroll
-    for (int q = 0; q < P; ++q) mfma_q(f1, q);
-    AQT_SCHED_FENCE();
-    read_frags(nxtA, nxtB, 0, f0);
-    AQT_SCHED_FENCE();
+    for (int p = 0; p < P; ++p) {
+      mfma_q(PAR, 1, 2 * p);
+      mfma_q(PAR, 1, 2 * p + 1);
+      AQT_SCHED_FENCE();
 #pragma unroll
-    for (int q = P; q < 2 * P; ++q) mfma_q(f1, q);
+      for (int idx = 0; idx < 2 * TM; ++idx)
+        if (2 * p + 1 == TN * (idx + 1) - 1) read_a(nxtA, 0, idx);   // stage nt + 1, step 0
+      if (p < TN) load_b(PAR ^ 1, 1, p, s1);
+      AQT_SCHED_FENCE();
+    }
   };
 
   int nt = 0;
@@ -338,8 +344,6 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
     stage(std::integral_constant<int, 1>{}, nt + 1);
   }
   if (nt < NT) stage(std::integral_constant<int, 0>{}, nt);
-  // drain the clamped prefetches before the registers and LDS are reused
-  __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
 
   // ---- epilogue: registers -> HBM.  Lane holds column (lane % 32) of each 32 x 32
   // tile, register r holds row 8*(r/4) + 4*(lane/32) + r%4; 32 lanes write 128
@@ -611,12 +615,12 @@ BwdPlan plan_bwd(int64_t M, int64_t K, int64_t N) {
 }
 
 template <int TM, int TN>
-aqt_status launch_dx(const float *dy, const uint16_t *wq_bf, const aqt_saved *sv, int64_t M, int64_t K, int64_t N,
+aqt_status launch_dx(const float *dy, const v4i *wq_frag, const aqt_saved *sv, int64_t M, int64_t K, int64_t N,
                      float *dx, hipStream_t st) {
   constexpr int BM = 64 * TM, BC = 64 * TN;
   auto kern = sv->mask_x ? bwd_dx_mfma_kernel<TM, TN, true> : bwd_dx_mfma_kernel<TM, TN, false>;
   const int tiles_m = static_cast<int>(cdiv(M, BM)), tiles_c = static_cast<int>(K / BC);
-  kern<<<tiles_m * tiles_c, kThreads, 0, st>>>(dy, wq_bf, sv->s_w, sv->s_x, sv->mask_x, static_cast<int>(M),
+  kern<<<tiles_m * tiles_c, kThreads, 0, st>>>(dy, wq_frag, sv->s_w, sv->s_x, sv->mask_x, static_cast<int>(M),
                                                   static_cast<int>(K), static_cast<int>(N), dx, tiles_m, tiles_c);
   AQT_HIP(hipGetLastError());
   return AQT_OK;
@@ -652,15 +656,16 @@ aqt_status launch_dense_bwd(const float *dy, const aqt_saved *sv, int64_t M, int
   uint8_t *base = static_cast<uint8_t *>(ws);
   const bool dy_aligned = reinterpret_cast<uintptr_t>(dy) % 16 == 0;
   if (dx) {
-    if (p.dx_mfma && dy_aligned && reinterpret_cast<uintptr_t>(sv->s_w) % 16 == 0) {
-      uint16_t *wq_bf = reinterpret_cast<uint16_t *>(base + p.off_bf);
-      const int64_t n4 = K * N / 4;
-      int g = static_cast<int>(cdiv(n4, kThreads));
+    if (p.dx_mfma && dy_aligned && reinterpret_cast<uintptr_t>(sv->s_w) % 16 == 0 &&
+        reinterpret_cast<uintptr_t>(sv->wq_kn) % 8 == 0) {
+      v4i *wq_frag = reinterpret_cast<v4i *>(base + p.off_bf);
+      const int64_t pieces = K * (N / 8);
+      int g = static_cast<int>(cdiv(pieces, kThreads));
       if (g > 2048) g = 2048;
-      codes_to_bf16_kernel<<<g, kThreads, 0, st>>>(sv->wq_kn, n4, reinterpret_cast<uint32_t *>(wq_bf));
+      codes_to_bf16_frag_kernel<<<g, kThreads, 0, st>>>(sv->wq_kn, static_cast<int>(K), static_cast<int>(N), wq_frag);
       AQT_HIP(hipGetLastError());
-      if (p.dx_wide) AQT_TRY((launch_dx<2, 4>(dy, wq_bf, sv, M, K, N, dx, st)));
-      else AQT_TRY((launch_dx<2, 2>(dy, wq_bf, sv, M, K, N, dx, st)));
+      if (p.dx_wide) AQT_TRY((launch_dx<2, 4>(dy, wq_frag, sv, M, K, N, dx, st)));
+      else AQT_TRY((launch_dx<2, 2>(dy, wq_frag, sv, M, K, N, dx, st)));
     } else {
       bwd_dx_general_kernel<<<static_cast<int>(cdiv(M * K, kThreads)), kThreads, 0, st>>>(
           dy, sv->wq_kn, sv->s_w, sv->s_x, sv->mask_x, M, K, N, dx);
