@@ -56,29 +56,41 @@ __device__ __forceinline__ int quant_code(float x, float s, float fq) {
   return quant_code(x, s, fq, p);
 }
 
+// Streaming 16-byte accesses.  The non-temporal hint keeps a tensor that is read
+// once per pass from displacing everything else in the caches; on this part it is
+// also what lets a pure stream reach its best HBM rate.
+typedef float v4f __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_stream(const float4 *p) {
+  const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_stream(uint32_t *p, uint32_t v) { __builtin_nontemporal_store(v, p); }
+
+__device__ __forceinline__ uint32_t absmax4(float4 a) {
+  return max(max(abs_bits(a.x), abs_bits(a.y)), max(abs_bits(a.z), abs_bits(a.w)));
+}
+
 // ---- per-tensor, contiguous: pass 1 -------------------------------------------
+// Each block owns one contiguous run of the tensor (per4 float4 per block).
+template <bool STREAM>
 __global__ __launch_bounds__(kThreads) void absmax_flat_kernel(const float *__restrict__ x, int64_t n,
-                                                               uint32_t *__restrict__ partial) {
+                                                               int64_t per4, uint32_t *__restrict__ partial) {
+  auto ld = [](const float4 *p) { return STREAM ? load_stream(p) : *p; };
   __shared__ uint32_t sm[4];
   const int64_t n4 = n >> 2;
   const float4 *x4 = reinterpret_cast<const float4 *>(x);
-  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
-  const int64_t gid = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  const int64_t i0 = static_cast<int64_t>(blockIdx.x) * per4;
+  const int64_t i1 = min(n4, i0 + per4);
   uint32_t m = 0;
-  int64_t i = gid;
-  for (; i + 3 * stride < n4; i += 4 * stride) {
-    float4 a = x4[i], b = x4[i + stride], c = x4[i + 2 * stride], d = x4[i + 3 * stride];
-    uint32_t ma = max(max(abs_bits(a.x), abs_bits(a.y)), max(abs_bits(a.z), abs_bits(a.w)));
-    uint32_t mb = max(max(abs_bits(b.x), abs_bits(b.y)), max(abs_bits(b.z), abs_bits(b.w)));
-    uint32_t mc = max(max(abs_bits(c.x), abs_bits(c.y)), max(abs_bits(c.z), abs_bits(c.w)));
-    uint32_t md = max(max(abs_bits(d.x), abs_bits(d.y)), max(abs_bits(d.z), abs_bits(d.w)));
-    m = max(m, max(max(ma, mb), max(mc, md)));
+  int64_t i = i0 + threadIdx.x;
+  for (; i + 3 * kThreads < i1; i += 4 * kThreads) {
+    const float4 a = ld(x4 + i), b = ld(x4 + i + kThreads);
+    const float4 c = ld(x4 + i + 2 * kThreads), d = ld(x4 + i + 3 * kThreads);
+    m = max(m, max(max(absmax4(a), absmax4(b)), max(absmax4(c), absmax4(d))));
   }
-  for (; i < n4; i += stride) {
-    float4 a = x4[i];
-    m = max(m, max(max(abs_bits(a.x), abs_bits(a.y)), max(abs_bits(a.z), abs_bits(a.w))));
-  }
-  for (int64_t j = (n4 << 2) + gid; j < n; j += stride) m = max(m, abs_bits(x[j]));
+  for (; i < i1; i += kThreads) m = max(m, absmax4(ld(x4 + i)));
+  if (blockIdx.x == 0)
+    for (int64_t j = (n4 << 2) + threadIdx.x; j < n; j += kThreads) m = max(m, abs_bits(x[j]));
   m = block_max(m, sm);
   if (threadIdx.x == 0) partial[blockIdx.x] = m;
 }
@@ -92,9 +104,11 @@ __device__ __forceinline__ uint32_t pack4(float4 v, float s, float fq) {
 }
 
 // ---- per-tensor, contiguous: pass 2 -------------------------------------------
+// Same block -> run mapping as pass 1, but blocks are visited in reverse so that
+// the part of the tensor pass 1 touched last is read first.
 __global__ __launch_bounds__(kThreads) void quantize_flat_kernel(
-    const float *__restrict__ x, int64_t n, const uint32_t *__restrict__ partial, int nparts, int qmax,
-    int8_t *__restrict__ q, float *__restrict__ scale, int32_t *dev_status) {
+    const float *__restrict__ x, int64_t n, int64_t per4, const uint32_t *__restrict__ partial, int nparts,
+    int qmax, int8_t *__restrict__ q, float *__restrict__ scale, int32_t *dev_status) {
   __shared__ uint32_t sm[4];
   uint32_t m = 0;
   for (int i = threadIdx.x; i < nparts; i += kThreads) m = max(m, partial[i]);
@@ -108,18 +122,21 @@ __global__ __launch_bounds__(kThreads) void quantize_flat_kernel(
   const int64_t n4 = n >> 2;
   const float4 *x4 = reinterpret_cast<const float4 *>(x);
   uint32_t *q4 = reinterpret_cast<uint32_t *>(q);
-  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
-  const int64_t gid = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
-  int64_t i = n4 - 1 - gid;  // descending: the end of the tensor was read last by pass 1
-  for (; i - 3 * stride >= 0; i -= 4 * stride) {
-    float4 a = x4[i], b = x4[i - stride], c = x4[i - 2 * stride], d = x4[i - 3 * stride];
-    q4[i] = pack4(a, s, fq);
-    q4[i - stride] = pack4(b, s, fq);
-    q4[i - 2 * stride] = pack4(c, s, fq);
-    q4[i - 3 * stride] = pack4(d, s, fq);
+  const int64_t blk = static_cast<int64_t>(gridDim.x) - 1 - blockIdx.x;
+  const int64_t i0 = blk * per4;
+  const int64_t i1 = min(n4, i0 + per4);
+  int64_t i = i0 + threadIdx.x;
+  for (; i + 3 * kThreads < i1; i += 4 * kThreads) {
+    const float4 a = load_stream(x4 + i), b = load_stream(x4 + i + kThreads);
+    const float4 c = load_stream(x4 + i + 2 * kThreads), d = load_stream(x4 + i + 3 * kThreads);
+    store_stream(q4 + i, pack4(a, s, fq));
+    store_stream(q4 + i + kThreads, pack4(b, s, fq));
+    store_stream(q4 + i + 2 * kThreads, pack4(c, s, fq));
+    store_stream(q4 + i + 3 * kThreads, pack4(d, s, fq));
   }
-  for (; i >= 0; i -= stride) q4[i] = pack4(x4[i], s, fq);
-  for (int64_t j = (n4 << 2) + gid; j < n; j += stride) q[j] = static_cast<int8_t>(quant_code(x[j], s, fq));
+  for (; i < i1; i += kThreads) store_stream(q4 + i, pack4(load_stream(x4 + i), s, fq));
+  if (blockIdx.x == 0)
+    for (int64_t j = (n4 << 2) + threadIdx.x; j < n; j += kThreads) q[j] = static_cast<int8_t>(quant_code(x[j], s, fq));
 }
 
 // ---- general shapes: abs-max per tensor / column / row ---------------------------
@@ -338,18 +355,27 @@ aqt_status launch_quantize(const float *x, int64_t rows, int64_t cols, int64_t l
     const bool flat = (ldx == cols) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) &&
                       (reinterpret_cast<uintptr_t>(q) % 4 == 0);
     if (flat && !mask) {
-      // 2048 blocks = 8 per CU; every thread keeps four 16-byte loads in flight.
-      const int g = grid_for(n / 4, kThreads * 4, 2048);
-      absmax_flat_kernel<<<g, kThreads, 0, st>>>(x, n, part);
+      // up to 2048 blocks = 8 per CU, each on its own contiguous run of the tensor;
+      // every thread keeps four 16-byte loads in flight.
+      int g = grid_for(n / 4, kThreads * 4, 2048);
+      const int64_t per4 = cdiv(cdiv(n / 4, g), kThreads) * kThreads;
+      g = static_cast<int>(per4 > 0 ? cdiv(n / 4, per4) : 1);
+      if (g < 1) g = 1;
+      // A tensor that fits the last-level cache (256 MB) is read with ordinary loads so
+      // that pass 2 can find it there; a larger one is streamed past the caches.
+      if (n * 4 <= (int64_t(192) << 20)) absmax_flat_kernel<false><<<g, kThreads, 0, st>>>(x, n, per4, part);
+      else absmax_flat_kernel<true><<<g, kThreads, 0, st>>>(x, n, per4, part);
       AQT_HIP(hipGetLastError());
-      quantize_flat_kernel<<<g, kThreads, 0, st>>>(x, n, part, g, qmax, q, scale, dev_status);
+      quantize_flat_kernel<<<g, kThreads, 0, st>>>(x, n, per4, part, g, qmax, q, scale, dev_status);
       AQT_HIP(hipGetLastError());
       return AQT_OK;
     }
-    const int g = grid_for(n, kThreads * 8, 2048);
-    if (flat)
-      absmax_flat_kernel<<<g, kThreads, 0, st>>>(x, n, part);
-    else
+    int g = grid_for(n, kThreads * 8, 2048);
+    if (flat) {
+      const int64_t per4 = cdiv(cdiv(n / 4 > 0 ? n / 4 : 1, g), kThreads) * kThreads;
+      g = static_cast<int>(cdiv(n / 4 > 0 ? n / 4 : 1, per4));
+      absmax_flat_kernel<true><<<g, kThreads, 0, st>>>(x, n, per4, part);
+    } else
       absmax_strided_kernel<<<g, kThreads, 0, st>>>(x, rows, cols, ldx, part);
     AQT_HIP(hipGetLastError());
     finish_scale_all_kernel<<<1, kThreads, 0, st>>>(part, g, qmax, scale, dev_status);
