@@ -361,7 +361,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           const int off = row_off + j * 32 + lane_off;
-          obase[off] = mask_bit(mask_x, tile0 + off) ? acc[i][j][r] : 0.0f;
+          __builtin_nontemporal_store(mask_bit(mask_x, tile0 + off) ? acc[i][j][r] : 0.0f, obase + off);
         }
       }
   } else {
@@ -373,7 +373,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
         const int row_off = (i * 32 + 8 * (r >> 2) + (r & 3)) * K;
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          obase[row_off + j * 32 + lane_off] = (keep != 0.0f) ? acc[i][j][r] : 0.0f;
+          __builtin_nontemporal_store((keep != 0.0f) ? acc[i][j][r] : 0.0f, obase + row_off + j * 32 + lane_off);
       }
   }
 }
@@ -404,10 +404,17 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_kernel(
   uint8_t *const Bhi_base = lds + BR * kPitch;
   uint8_t *const Blo_base = Bhi_base + BC * kPitch;
 
+  // Workgroup -> (slab, tile).  All tiles of a slab read the same rows of xq and dy,
+  // so a slab should live on one XCD (one L2) at one time: consecutive workgroup ids
+  // are spread round-robin over the 8 XCDs, hence the remap to one contiguous run
+  // of (slab, tile) pairs per XCD.
   const int tiles = tiles_r * tiles_c;
-  const int slab = blockIdx.x / tiles;
-  const int tile = blockIdx.x - slab * tiles;
-  const int br = tile / tiles_c, bc = tile - br * tiles_c;
+  int id = blockIdx.x;
+  const int total = gridDim.x;
+  if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+  const int slab = id / tiles;
+  const int tile = id - slab * tiles;
+  const int br = tile % tiles_r, bc = tile / tiles_r;   // row tiles of one column tile are neighbours
   const int r0 = br * BR, c0 = bc * BC;
   const int m_begin = slab * m_per_slab;
   const int m_end = min(M, m_begin + m_per_slab);

@@ -255,7 +255,8 @@ __global__ __launch_bounds__(kThreads, (TM * TN <= 8) ? 2 : 1) void dense_fwd_mf
           const float g = dequant_f32(a1, sc_b) + bias_b;
           out = v * sigmoid_f32(g);
         }
-        ybase[(i * 32 + 8 * (r >> 2) + (r & 3)) * out_cols + lane_off] = out;
+        // written once, read by another kernel much later: stream it past the caches
+        __builtin_nontemporal_store(out, ybase + (i * 32 + 8 * (r >> 2) + (r & 3)) * out_cols + lane_off);
       }
     }
   }
