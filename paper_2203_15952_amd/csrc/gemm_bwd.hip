@@ -389,6 +389,17 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
 // float32 partial tile and a second kernel folds the slabs in a fixed order
 // (run-to-run reproducible), applies s_x and the mask.  The split operand (dy)
 // sits on the short side of the wavefront tile (TC <= TR).
+//
+// Pipeline: as in the dX kernel.  Two LDS slots, one barrier per 32-row stage,
+// two register sets so that every global load has a full stage in flight, and
+// every other kind of work cut into pieces slotted between MFMA pairs:
+//   first half : MFMA(step 0) | refill the code fragments in place for step 1,
+//                fetch the dy fragments for step 1 | convert and stage the next
+//                stage into the other LDS slot
+//   barrier
+//   second half: MFMA(step 1) | fragments of the next stage, step 0
+// Rows past M (only in the last slab) are read from row M-1 and their codes are
+// zeroed, so the loop body stays branch-free.
 // =====================================================================================
 template <int TR, int TC>  // tile is (64*TR) k-rows x (64*TC) n-columns; 32 m per stage
 __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_kernel(
@@ -396,13 +407,12 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_kernel(
     float *__restrict__ partial, int tiles_r, int tiles_c) {
   constexpr int BR = 64 * TR, BC = 64 * TC;
   constexpr int SM = 32;
-  constexpr int GA = BR / 4, GB = BC / 4;  // 4-column groups per tile edge
-  constexpr int UA = (BR + kThreads - 1) / kThreads;      // code units (4 k x 8 m) per thread
-  constexpr int UB = (2 * BC + kThreads - 1) / kThreads;  // gradient units (4 n x 4 m) per thread
-  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-  uint8_t *const A_base = lds;
-  uint8_t *const Bhi_base = lds + BR * kPitch;
-  uint8_t *const Blo_base = Bhi_base + BC * kPitch;
+  constexpr int GA = BR / 4, GB = BC / 4;   // 4-column groups per tile edge
+  constexpr int P = TR * TC;                // MFMA pairs per half stage (2*TR*TC MFMAs)
+  static_assert(BR == 256 && BC == 128, "the gather pattern below is written for 256 x 128 tiles");
+  // Two slots, each a codes image and a dy hi/lo image pair.
+  __shared__ __attribute__((aligned(1024))) uint8_t sC0[BR * kRowB], sC1[BR * kRowB];
+  __shared__ __attribute__((aligned(1024))) uint8_t sD0[2 * BC * kRowB], sD1[2 * BC * kRowB];
 
   // Workgroup -> (slab, tile).  All tiles of a slab read the same rows of xq and dy,
   // so a slab should live on one XCD (one L2) at one time: consecutive workgroup ids
@@ -424,78 +434,56 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_kernel(
   const int wm = wave >> 1, wn = wave & 1;
   const int lr = lane & 31, lk = lane >> 5;
 
-  uint32_t rx[UA][8];
-  float4 ry[UB][4];
+  // gather units: codes (g = t % 64: 4 k, mg = t / 64: 8 m); gradients (h = t % 32: 4 n, ms = t / 32: 4 m)
+  const int g = t & 63, mg = t >> 6;
+  const int h = t & 31, ms = t >> 5;
+  uint32_t rx[2][8];
+  float4 ry[2][4];
 
-  auto load_global = [&](int mbase) {
+  // Slab-uniform bases plus 32-bit offsets (a slab spans at most m_per_slab rows).
+  const char *x_slab = reinterpret_cast<const char *>(xq + static_cast<int64_t>(m_begin) * K + r0);
+  const char *y_slab = reinterpret_cast<const char *>(dy + static_cast<int64_t>(m_begin) * N + c0);
+  const int m_last = M - 1 - m_begin;      // last valid row, slab-relative
+  auto load_global = [&](int set, int mrel0) {
 #pragma unroll
-    for (int u = 0; u < UA; ++u) {
-      const int unit = t + kThreads * u;
-      const int g = unit % GA, mg = unit / GA;
-      if (unit < BR) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const int m = mbase + mg * 8 + i;
-          rx[u][i] = (m < m_end) ? *reinterpret_cast<const uint32_t *>(xq + static_cast<int64_t>(m) * K + r0 + 4 * g) : 0u;
-        }
-      }
+    for (int i = 0; i < 8; ++i) {
+      const int mrel = mrel0 + mg * 8 + i;
+      const int mc = min(mrel, m_last);
+      const uint32_t v = *reinterpret_cast<const uint32_t *>(x_slab + static_cast<uint32_t>(mc * K + 4 * g));
+      rx[set][i] = mrel <= m_last ? v : 0u;
     }
 #pragma unroll
-    for (int u = 0; u < UB; ++u) {
-      const int unit = t + kThreads * u;
-      const int g = unit % GB, ms = unit / GB;
-      if (unit < 2 * BC) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int m = mbase + ms * 4 + i;
-          ry[u][i] = (m < m_end) ? *reinterpret_cast<const float4 *>(dy + static_cast<int64_t>(m) * N + c0 + 4 * g)
-                                 : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-      }
+    for (int i = 0; i < 4; ++i) {
+      const int mc = min(mrel0 + ms * 4 + i, m_last);
+      ry[set][i] = *reinterpret_cast<const float4 *>(y_slab + static_cast<uint32_t>(mc * N + 4 * h) * 4u);
     }
   };
-
-  auto store_lds = [&]() {
+  // LDS write offsets (row rho = b*G + g, swizzled 16-byte chunk); b adds whole multiples of
+  // 32 rows, which leaves the swizzle bits unchanged.
+  const int offc0 = g * kRowB + ((mg ^ swz(g)) << 4);
+  const int offd0 = h * kRowB + (((ms >> 1) ^ swz(h)) << 4) + (ms & 1) * 8;
+  auto store_codes = [&](int set, int b, uint8_t *sC) {
+    // byte b of the eight dwords -> eight bf16 along m
+    float f[8];
 #pragma unroll
-    for (int u = 0; u < UA; ++u) {
-      const int unit = t + kThreads * u;
-      const int g = unit % GA, mg = unit / GA;
-      if (unit < BR) {
+    for (int i = 0; i < 8; ++i) f[i] = static_cast<float>(static_cast<int8_t>(rx[set][i] >> (8 * b)));
+    v4i a;
+    a.x = pack_bf16(f[0], f[1]); a.y = pack_bf16(f[2], f[3]);
+    a.z = pack_bf16(f[4], f[5]); a.w = pack_bf16(f[6], f[7]);
+    *reinterpret_cast<v4i *>(sC + offc0 + b * GA * kRowB) = a;
+  };
+  auto store_dy = [&](int set, int b, uint8_t *sD) {
+    // component b of the four float4 -> hi/lo bf16 along m
+    float y[4];
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          // byte b of the eight dwords -> eight bf16 along m
-          float f[8];
-#pragma unroll
-          for (int i = 0; i < 8; ++i) f[i] = static_cast<float>(static_cast<int8_t>(rx[u][i] >> (8 * b)));
-          v4i a;
-          a.x = pack_bf16(f[0], f[1]); a.y = pack_bf16(f[2], f[3]);
-          a.z = pack_bf16(f[4], f[5]); a.w = pack_bf16(f[6], f[7]);
-          *reinterpret_cast<v4i *>(A_base + (b * GA + g) * kPitch + mg * 16) = a;
-        }
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < UB; ++u) {
-      const int unit = t + kThreads * u;
-      const int g = unit % GB, ms = unit / GB;
-      if (unit < 2 * BC) {
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          // component b of the four float4 -> hi/lo bf16 along m
-          float y[4];
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            y[i] = b == 0 ? ry[u][i].x : (b == 1 ? ry[u][i].y : (b == 2 ? ry[u][i].z : ry[u][i].w));
-          v2i hi, lo;
-          uint32_t h, l;
-          split_bf16(y[0], y[1], h, l); hi.x = h; lo.x = l;
-          split_bf16(y[2], y[3], h, l); hi.y = h; lo.y = l;
-          const int off = (b * GB + g) * kPitch + ms * 8;
-          *reinterpret_cast<v2i *>(Bhi_base + off) = hi;
-          *reinterpret_cast<v2i *>(Blo_base + off) = lo;
-        }
-      }
-    }
+    for (int i = 0; i < 4; ++i)
+      y[i] = b == 0 ? ry[set][i].x : (b == 1 ? ry[set][i].y : (b == 2 ? ry[set][i].z : ry[set][i].w));
+    v2i hi, lo;
+    uint32_t hh, ll;
+    split_bf16(y[0], y[1], hh, ll); hi.x = hh; lo.x = ll;
+    split_bf16(y[2], y[3], hh, ll); hi.y = hh; lo.y = ll;
+    *reinterpret_cast<v2i *>(sD + offd0 + b * GB * kRowB) = hi;
+    *reinterpret_cast<v2i *>(sD + BC * kRowB + offd0 + b * GB * kRowB) = lo;
   };
 
   v16f acc[TR][TC];
@@ -506,40 +494,83 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
+  // fragments: this lane's addresses (tile rows are multiples of 32 apart)
+  const int sw = swz(lr);
+  const int offk[2] = {((0 + lk) ^ sw) << 4, ((2 + lk) ^ sw) << 4};
+  const int a_row = (wm * 32 * TR + lr) * kRowB;
+  const int b_row = (wn * 32 * TC + lr) * kRowB;
+  v4i fa[TR];            // code fragments of the step in flight, refilled in place
+  v4i fb[2][2 * TC];     // dy fragments: [set][hi j..., lo j...]
+  auto read_a = [&](const uint8_t *sC, int kk, int i) {
+    fa[i] = *reinterpret_cast<const v4i *>(sC + a_row + i * 32 * kRowB + offk[kk]);
+  };
+  auto read_b = [&](const uint8_t *sD, int kk, int set, int idx) {
+    const int j = idx % TC, img = idx / TC;
+    fb[set][idx] = *reinterpret_cast<const v4i *>(sD + img * BC * kRowB + b_row + j * 32 * kRowB + offk[kk]);
+  };
+  // MFMA number q of a half stage, q in [0, 4*TR*TC/2... ): row tile i uses its code
+  // fragment in 2*TC consecutive MFMAs (hi j0.., lo j0..), so it can be refilled right after.
+  auto mfma_q = [&](int set, int q) {
+    const int i = q / (2 * TC), w = q % (2 * TC), j = w % TC;
+    acc[i][j] = mfma_bf16(fa[i], fb[set][w], acc[i][j]);
+  };
+
   const int stages = (m_end - m_begin + SM - 1) / SM;
-  if (stages > 0) {
-    load_global(m_begin);
-    store_lds();
-  }
-  __syncthreads();
-  const uint8_t *A = A_base + (wm * 32 * TR + lr) * kPitch + lk * 16;
-  const uint8_t *Bhi = Bhi_base + (wn * 32 * TC + lr) * kPitch + lk * 16;
-  const uint8_t *Blo = Blo_base + (wn * 32 * TC + lr) * kPitch + lk * 16;
-  for (int s = 0; s < stages; ++s) {
-    const bool more = s + 1 < stages;
-    if (more) load_global(m_begin + (s + 1) * SM);
+  auto stage_m = [&](int s) { return (s < stages - 1 ? s : stages - 1) * SM; };   // slab-relative
+
+  // ---- prologue ----
+  load_global(0, stage_m(0));
 #pragma unroll
-    for (int kk = 0; kk < SM / 16; ++kk) {
-      v4i a[TR], bh[TC], bl[TC];
+  for (int b = 0; b < 4; ++b) { store_codes(0, b, sC0); store_dy(0, b, sD0); }
+  load_global(1, stage_m(1));
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
+  __builtin_amdgcn_s_barrier();
 #pragma unroll
-      for (int i = 0; i < TR; ++i) a[i] = *reinterpret_cast<const v4i *>(A + i * 32 * kPitch + kk * 32);
+  for (int i = 0; i < TR; ++i) read_a(sC0, 0, i);
 #pragma unroll
-      for (int j = 0; j < TC; ++j) {
-        bh[j] = *reinterpret_cast<const v4i *>(Bhi + j * 32 * kPitch + kk * 32);
-        bl[j] = *reinterpret_cast<const v4i *>(Blo + j * 32 * kPitch + kk * 32);
-      }
+  for (int idx = 0; idx < 2 * TC; ++idx) read_b(sD0, 0, 0, idx);
+
+  // One stage; PAR = s % 2 is a compile-time constant (register sets, LDS slots).
+  // dy fragment sets alternate per half stage: step 0 uses fb[0], step 1 uses fb[1].
+  auto stage = [&](auto par, int s) {
+    constexpr int PAR = decltype(par)::value;
+    uint8_t *curC = PAR ? sC1 : sC0, *curD = PAR ? sD1 : sD0;
+    uint8_t *nxtC = PAR ? sC0 : sC1, *nxtD = PAR ? sD0 : sD1;
+    // ---- first half: step 0 ----
+    load_global(PAR, stage_m(s + 2));   // set PAR was consumed one stage ago
+    AQT_SCHED_FENCE();
 #pragma unroll
-      for (int i = 0; i < TR; ++i)
-#pragma unroll
-        for (int j = 0; j < TC; ++j) {
-          acc[i][j] = mfma_bf16(a[i], bh[j], acc[i][j]);
-          acc[i][j] = mfma_bf16(a[i], bl[j], acc[i][j]);
-        }
+    for (int p = 0; p < P; ++p) {
+      mfma_q(0, 2 * p);
+      mfma_q(0, 2 * p + 1);
+      AQT_SCHED_FENCE();
+      if (p < 2 * TC) read_b(curD, 1, 1, p);                       // dy fragments for step 1
+      if ((2 * p + 2) % (2 * TC) == 0) read_a(curC, 1, (2 * p + 1) / (2 * TC));   // row tile done: refill
+      // stage s + 1 (register set PAR^1) into the other slot: 4 code pieces, 4 dy pieces
+      if (p < 4) store_codes(PAR ^ 1, p, nxtC);
+      else store_dy(PAR ^ 1, p - 4, nxtD);
+      AQT_SCHED_FENCE();
     }
-    __syncthreads();  // every wavefront is done reading this stage
-    if (more) store_lds();
-    __syncthreads();
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));   // own LDS traffic drained
+    __builtin_amdgcn_s_barrier();
+    // ---- second half: step 1 ----
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+      mfma_q(1, 2 * p);
+      mfma_q(1, 2 * p + 1);
+      AQT_SCHED_FENCE();
+      if (p < 2 * TC) read_b(nxtD, 0, 0, p);                       // next stage, step 0
+      if ((2 * p + 2) % (2 * TC) == 0) read_a(nxtC, 0, (2 * p + 1) / (2 * TC));
+      AQT_SCHED_FENCE();
+    }
+  };
+
+  int s = 0;
+  for (; s + 1 < stages; s += 2) {
+    stage(std::integral_constant<int, 0>{}, s);
+    stage(std::integral_constant<int, 1>{}, s + 1);
   }
+  if (s < stages) stage(std::integral_constant<int, 0>{}, s);
 
   // ---- epilogue: partial tile -> workspace.  Undo the de-interleaving of rows and
   // columns; addresses are a uniform base plus a 32-bit lane offset plus
@@ -553,9 +584,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_kernel(
     for (int i = 0; i < TR; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        // rho_r = wm*32*TR + i*32 + 8*(r/4) + 4*lk + r%4 ; k_l = 4*(rho_r % GA) + rho_r / GA
-        const int rho_u = wm * 32 * TR + i * 32 + 8 * (r >> 2) + (r & 3);   // uniform part
-        const int rho_r = rho_u + 4 * lk;
+        const int rho_r = wm * 32 * TR + i * 32 + 8 * (r >> 2) + (r & 3) + 4 * lk;
         const int k_l = 4 * (rho_r % GA) + rho_r / GA;
         out[k_l * N + n_l] = acc[i][j][r];
       }
@@ -603,14 +632,15 @@ BwdPlan plan_bwd(int64_t M, int64_t K, int64_t N) {
   p.dx_mfma = fits32 && (N % kSN == 0) && (K % 128 == 0) && (M >= 128);
   p.dx_wide = (K % 256 == 0) && cdiv(M, 128) * (K / 256) >= 512;
   // dW: tiles over K x N, slabs over M
-  p.dw_mfma = fits32 && (K % 128 == 0) && (N % 128 == 0);
-  p.dw_wide = (K % 256 == 0) && (K / 256) * (N / 128) >= 32;
-  const int64_t tiles = (K / (p.dw_wide ? 256 : 128)) * (N / 128);
+  p.dw_mfma = fits32 && (K % 256 == 0) && (N % 128 == 0);
+  p.dw_wide = true;
+  const int64_t tiles = p.dw_mfma ? (K / 256) * (N / 128) : 1;
   int64_t slabs = p.dw_mfma ? cdiv(512, tiles) : 1;
   if (slabs > 64) slabs = 64;
   int64_t per = cdiv(M, slabs);
   per = cdiv(per, 32) * 32;            // whole stages
   slabs = cdiv(M, per);
+  if (per * (K > N ? K : N) >= (int64_t(1) << 30)) p.dw_mfma = false;   // 32-bit byte offsets inside a slab
   p.slabs = static_cast<int>(slabs);
   p.m_per_slab = static_cast<int>(per);
   size_t off = 0;
@@ -637,17 +667,11 @@ template <int TR, int TC>
 aqt_status launch_dw(const float *dy, const aqt_saved *sv, int64_t M, int64_t K, int64_t N, const BwdPlan &p,
                      float *partial, hipStream_t st) {
   constexpr int BR = 64 * TR, BC = 64 * TC;
-  constexpr int smem = (BR + 2 * BC) * kPitch;
   auto kern = bwd_dw_mfma_kernel<TR, TC>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    AQT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem));
-    attr_set = true;
-  }
   const int tiles_r = static_cast<int>(K / BR), tiles_c = static_cast<int>(N / BC);
-  kern<<<tiles_r * tiles_c * p.slabs, kThreads, smem, st>>>(sv->xq, dy, static_cast<int>(M), static_cast<int>(K),
-                                                            static_cast<int>(N), p.m_per_slab, partial, tiles_r,
-                                                            tiles_c);
+  kern<<<tiles_r * tiles_c * p.slabs, kThreads, 0, st>>>(sv->xq, dy, static_cast<int>(M), static_cast<int>(K),
+                                                         static_cast<int>(N), p.m_per_slab, partial, tiles_r,
+                                                         tiles_c);
   AQT_HIP(hipGetLastError());
   return AQT_OK;
 }
@@ -683,8 +707,7 @@ aqt_status launch_dense_bwd(const float *dy, const aqt_saved *sv, int64_t M, int
     if (p.dw_mfma && dy_aligned && reinterpret_cast<uintptr_t>(sv->xq) % 4 == 0 &&
         reinterpret_cast<uintptr_t>(dw) % 16 == 0) {
       float *partial = reinterpret_cast<float *>(base + p.off_part);
-      if (p.dw_wide) AQT_TRY((launch_dw<4, 2>(dy, sv, M, K, N, p, partial, st)));
-      else AQT_TRY((launch_dw<2, 2>(dy, sv, M, K, N, p, partial, st)));
+      AQT_TRY((launch_dw<4, 2>(dy, sv, M, K, N, p, partial, st)));
       bwd_dw_fold_kernel<<<static_cast<int>(cdiv(K * N / 4, kThreads)), kThreads, 0, st>>>(
           partial, p.slabs, K * N, N, sv->s_x, sv->s_w, sv->mask_w, dw);
       AQT_HIP(hipGetLastError());
