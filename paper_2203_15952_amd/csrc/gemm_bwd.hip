@@ -401,7 +401,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
 // Rows past M (only in the last slab) are read from row M-1 and their codes are
 // zeroed, so the loop body stays branch-free.
 // =====================================================================================
-template <int TR, int TC>  // tile is (64*TR) k-rows x (64*TC) n-columns; 32 m per stage
+template <int TR, int TC, bool RAGGED>  // tile is (64*TR) k-rows x (64*TC) n-columns; 32 m per stage
 __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_kernel(
     const int8_t *__restrict__ xq, const float *__restrict__ dy, int M, int K, int N, int m_per_slab,
     float *__restrict__ partial, int tiles_r, int tiles_c) {
@@ -444,18 +444,29 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_kernel(
   const char *x_slab = reinterpret_cast<const char *>(xq + static_cast<int64_t>(m_begin) * K + r0);
   const char *y_slab = reinterpret_cast<const char *>(dy + static_cast<int64_t>(m_begin) * N + c0);
   const int m_last = M - 1 - m_begin;      // last valid row, slab-relative
+  // RAGGED (M not a multiple of 32): rows past M are read from row M-1 and their codes zeroed.
+  const uint32_t gx0 = static_cast<uint32_t>(mg * 8 * K + 4 * g);
+  const uint32_t gy0 = static_cast<uint32_t>(ms * 4 * N + 4 * h) * 4u;
   auto load_global = [&](int set, int mrel0) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int mrel = mrel0 + mg * 8 + i;
-      const int mc = min(mrel, m_last);
-      const uint32_t v = *reinterpret_cast<const uint32_t *>(x_slab + static_cast<uint32_t>(mc * K + 4 * g));
-      rx[set][i] = mrel <= m_last ? v : 0u;
+      if (RAGGED) {
+        const int mrel = mrel0 + mg * 8 + i;
+        const int mc = min(mrel, m_last);
+        const uint32_t v = *reinterpret_cast<const uint32_t *>(x_slab + static_cast<uint32_t>(mc * K + 4 * g));
+        rx[set][i] = mrel <= m_last ? v : 0u;
+      } else {
+        rx[set][i] = *reinterpret_cast<const uint32_t *>(x_slab + static_cast<uint32_t>((mrel0 + i) * K) + gx0);
+      }
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int mc = min(mrel0 + ms * 4 + i, m_last);
-      ry[set][i] = *reinterpret_cast<const float4 *>(y_slab + static_cast<uint32_t>(mc * N + 4 * h) * 4u);
+      if (RAGGED) {
+        const int mc = min(mrel0 + ms * 4 + i, m_last);
+        ry[set][i] = *reinterpret_cast<const float4 *>(y_slab + static_cast<uint32_t>(mc * N + 4 * h) * 4u);
+      } else {
+        ry[set][i] = *reinterpret_cast<const float4 *>(y_slab + static_cast<uint32_t>((mrel0 + i) * N) * 4u + gy0);
+      }
     }
   };
   // LDS write offsets (row rho = b*G + g, swizzled 16-byte chunk); b adds whole multiples of
@@ -667,7 +678,7 @@ template <int TR, int TC>
 aqt_status launch_dw(const float *dy, const aqt_saved *sv, int64_t M, int64_t K, int64_t N, const BwdPlan &p,
                      float *partial, hipStream_t st) {
   constexpr int BR = 64 * TR, BC = 64 * TC;
-  auto kern = bwd_dw_mfma_kernel<TR, TC>;
+  auto kern = (M % 32 == 0) ? bwd_dw_mfma_kernel<TR, TC, false> : bwd_dw_mfma_kernel<TR, TC, true>;
   const int tiles_r = static_cast<int>(K / BR), tiles_c = static_cast<int>(N / BC);
   kern<<<tiles_r * tiles_c * p.slabs, kThreads, 0, st>>>(sv->xq, dy, static_cast<int>(M), static_cast<int>(K),
                                                          static_cast<int>(N), p.m_per_slab, partial, tiles_r,
