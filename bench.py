@@ -34,8 +34,9 @@ PEAK_BF16_TFLOPS = 2500.0    # dense bf16 MFMA
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50,
+                    help="untimed steps; the card needs a few tens of milliseconds of load to reach its steady clocks")
     ap.add_argument("--tokens", type=int, default=65536, help="rows of the activation tensors")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="row sample the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -67,6 +68,7 @@ def main():
         L["ws_q"] = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_QUANTIZE, c.M, c.K, 1))
         L["ws_b"] = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_DENSE_BWD, c.M, c.K, c.N))
         L["ws_w"] = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_QUANTIZE_WEIGHTS, 1, c.K, c.N))
+        L["ws_f"] = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_DENSE_FWD_Q, c.M, c.K, c.N))
         layers.append(L)
     status = B.new_status()
 
@@ -85,7 +87,7 @@ def main():
             B.aqt_quantize_weights(L["w"], c.bits_w, wq_packed=sv.wq_packed, s_w=sv.s_w, wq_kn=sv.wq_kn,
                                    ws=L["ws_w"], dev_status=status)
             mark(2)
-            B.aqt_dense_fwd_q(sv.xq, sv.s_x, sv.wq_packed, sv.s_w, c.N, c.bits_x, c.bits_w, y=L["y"])
+            B.aqt_dense_fwd_q(sv.xq, sv.s_x, sv.wq_packed, sv.s_w, c.N, c.bits_x, c.bits_w, y=L["y"], ws=L["ws_f"])
             mark(3)
             B.aqt_dense_bwd(L["dy"], sv, c.bits_x, c.bits_w, dx=L["dx"], want_dw=False, ws=L["ws_b"])
             mark(4)

@@ -144,6 +144,8 @@ aqt_status aqt_unpack_weights(const void *wq_packed, int64_t K, int64_t N, int b
  *   s_w [N]; bias nullable [N]; y [M,N] float32 ([M,N/2] for GLU);
  *   acc_out nullable [M,N] int32, the raw accumulators.
  * Requires K * qmax_x * qmax_w < 2^31 / 16 (else AQT_ERR_UNSUPPORTED).
+ * Needs aqt_workspace_bytes(AQT_OP_DENSE_FWD_Q, M, K, N, ., .) of workspace (K*N
+ * bytes: the weight codes re-ordered for the matrix cores, rewritten per call).
  */
 aqt_status aqt_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq_packed, const float *s_w,
                            int64_t M, int64_t K, int64_t N, int bits_x, int bits_w, const float *bias,

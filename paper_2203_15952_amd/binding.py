@@ -181,15 +181,17 @@ def _out_cols(N: int, epilogue: int) -> int:
 
 
 def aqt_dense_fwd_q(xq, s_x, wq_packed, s_w, N: int, bits_x: int, bits_w: int, *, bias=None,
-                    epilogue: int = AQT_EPI_NONE, y=None, acc_out=None, want_acc=False):
+                    epilogue: int = AQT_EPI_NONE, y=None, acc_out=None, want_acc=False, ws=None):
     """aqt_dense_fwd_q: returns (y float32, acc int32 or None)."""
     _dev(xq, torch.int8, "xq")
     M, K = xq.shape
+    if ws is None:
+        ws = workspace(aqt_workspace_bytes(AQT_OP_DENSE_FWD_Q, M, K, N, bits_x, bits_w))
     y = torch.empty((M, _out_cols(N, epilogue)), dtype=torch.float32, device=xq.device) if y is None else y
     if want_acc and acc_out is None:
         acc_out = torch.empty((M, N), dtype=torch.int32, device=xq.device)
     st = lib().aqt_dense_fwd_q(_ptr(xq), _ptr(s_x), _ptr(wq_packed), _ptr(s_w), M, K, N, bits_x, bits_w,
-                               _ptr(bias), epilogue, _ptr(y), _ptr(acc_out), None, 0, _stream())
+                               _ptr(bias), epilogue, _ptr(y), _ptr(acc_out), _ptr(ws), ws.numel(), _stream())
     _check(st, "aqt_dense_fwd_q")
     return y, acc_out
 

@@ -14,6 +14,7 @@ struct FwdWorkspace {
   float *s_w;        // N
   int8_t *xq;        // M*K
   uint8_t *wq;       // packed weight operand
+  uint8_t *wfrag;    // weights in MFMA-fragment order (scratch of the contraction)
   size_t total;
 };
 
@@ -33,6 +34,7 @@ FwdWorkspace carve_fwd(void *ws, int64_t M, int64_t K, int64_t N, int bits_w) {
   f.s_w = reinterpret_cast<float *>(take(static_cast<size_t>(N) * sizeof(float)));
   f.xq = reinterpret_cast<int8_t *>(take(static_cast<size_t>(M) * K));
   f.wq = take(aqt_packed_weight_bytes(K, N, bits_w));
+  f.wfrag = take(fwd_q_workspace_bytes(K, N));
   f.total = off;
   return f;
 }
@@ -78,7 +80,7 @@ size_t aqt_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int bits_x, 
   switch (op) {
     case AQT_OP_QUANTIZE: return kMaxPartials * sizeof(float);
     case AQT_OP_QUANTIZE_WEIGHTS: return N >= 1 ? weight_ws_bytes(N) : 0;
-    case AQT_OP_DENSE_FWD_Q: return 256;
+    case AQT_OP_DENSE_FWD_Q: return (K >= 1 && N >= 1) ? fwd_q_workspace_bytes(K, N) : 0;
     case AQT_OP_DENSE_FWD:
       if (!shape_ok(M, K) || N < 1 || !bits_ok(bits_w)) return 0;
       return carve_fwd(nullptr, M, K, N, bits_w).total;
@@ -129,14 +131,13 @@ aqt_status aqt_unpack_weights(const void *wq_packed, int64_t K, int64_t N, int b
 aqt_status aqt_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq_packed, const float *s_w,
                            int64_t M, int64_t K, int64_t N, int bits_x, int bits_w, const float *bias,
                            int epilogue, float *y, int32_t *acc_out, void *ws, size_t ws_bytes, void *stream) {
-  (void)ws;
-  (void)ws_bytes;
   if (!xq || !s_x || !wq_packed || !s_w || !y || !shape_ok(M, K) || N < 1) return AQT_ERR_INVALID_ARG;
   if (epilogue != AQT_EPI_NONE && epilogue != AQT_EPI_SWISH && epilogue != AQT_EPI_GLU) return AQT_ERR_INVALID_ARG;
   if (!bits_ok(bits_x) || !bits_ok(bits_w)) return AQT_ERR_UNSUPPORTED;
   if (epilogue == AQT_EPI_GLU && (N % 2)) return AQT_ERR_UNSUPPORTED;
   if (!acc_fits(K, bits_x, bits_w)) return AQT_ERR_UNSUPPORTED;
-  return launch_dense_fwd_q(xq, s_x, wq_packed, s_w, M, K, N, bits_w, bias, epilogue, y, acc_out,
+  if (!ws || ws_bytes < fwd_q_workspace_bytes(K, N)) return AQT_ERR_WORKSPACE;
+  return launch_dense_fwd_q(xq, s_x, wq_packed, s_w, M, K, N, bits_w, bias, epilogue, y, acc_out, ws,
                             static_cast<hipStream_t>(stream));
 }
 
@@ -159,7 +160,7 @@ aqt_status aqt_dense_fwd(const float *x, const float *w, int64_t M, int64_t K, i
                           f.partials, st, dev_status));
   AQT_TRY(launch_quantize_weights(w, K, N, bits_w, wq, s_w, saved ? saved->wq_kn : nullptr,
                                   saved ? saved->mask_w : nullptr, f.wpart, st, dev_status));
-  return launch_dense_fwd_q(xq, s_x, wq, s_w, M, K, N, bits_w, bias, epilogue, y, nullptr, st);
+  return launch_dense_fwd_q(xq, s_x, wq, s_w, M, K, N, bits_w, bias, epilogue, y, nullptr, f.wfrag, st);
 }
 
 aqt_status aqt_dense_bwd(const float *dy, const aqt_saved *saved, int64_t M, int64_t K, int64_t N, int bits_x,

@@ -51,8 +51,9 @@ aqt_status launch_unpack_weights(const void *wq_packed, int64_t K, int64_t N, in
 // ---- forward contraction (gemm_fwd.hip) -----------------------------------------
 aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq_packed,
                               const float *s_w, int64_t M, int64_t K, int64_t N, int bits_w,
-                              const float *bias, int epilogue, float *y, int32_t *acc_out,
+                              const float *bias, int epilogue, float *y, int32_t *acc_out, void *ws,
                               hipStream_t st);
+size_t fwd_q_workspace_bytes(int64_t K, int64_t N);
 
 // ---- straight-through backward (gemm_bwd.hip) -------------------------------------
 size_t bwd_workspace_bytes(int64_t M, int64_t K, int64_t N);

@@ -3,14 +3,10 @@
 // for gfx950:  acc = xq . wq in int32 on the int8 matrix cores, then
 // v = float(acc) * (s_x * s_w[n]) (+ bias), then none / Swish / GLU.
 //
-// Tuned kernel: a workgroup of four wavefronts (2 x 2) owns a BM x BN output tile;
-// each wavefront owns TM x TN tiles of 32 x 32 driven by v_mfma_i32_32x32x32_i8.
-// Both operands are fan-in contiguous (xq is [M,K]; the weight operand is [N][K]
-// or [N][K/2] packed), are staged through LDS in 64-byte K slices with register
-// prefetch of the next slice, and int4 weights are expanded to int8 on their way
-// into LDS.  The nibble c is expanded to the byte 16*c (a shift and a mask, the
-// sign comes for free) and the accumulator is shifted back by 4 at the end, which
-// is exact because every partial sum is a multiple of 16.
+// The tuned kernel is described where it is defined; shapes it does not cover take
+// a one-thread-per-output kernel with identical results.
+#include <type_traits>
+
 #include "aqt_internal.h"
 #include "epilogue.h"
 
@@ -21,8 +17,6 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
-constexpr int kBK = 64;            // bytes (= int8 codes) of fan-in per LDS stage
-constexpr int kRow = kBK + 16;     // LDS row pitch: 80 B keeps 16-byte reads of 8 rows on distinct banks
 
 // ---- general kernel: one thread per output, any shape -----------------------------
 __device__ __forceinline__ int weight_code(const uint8_t *__restrict__ wq, int64_t row_bytes, int packed,
@@ -64,6 +58,34 @@ __global__ __launch_bounds__(kThreads) void dense_fwd_general_kernel(
 }
 
 // ---- tuned MFMA kernel --------------------------------------------------------------
+// What bounds this kernel on gfx950 is operand delivery, not the matrix cores: an
+// int8 32x32x32 MFMA eats 2 KB of operands per 32 cycles, LDS delivers about 64
+// bytes per clock and CU for 16-byte reads, and the K=512 layers are bound by
+// writing their float32 output anyway.  Hence:
+//   * The weights never touch LDS.  A small pre-kernel rewrites the forward weight
+//     operand ([N][K] int8 or [N][K/2] packed int4) into MFMA-fragment order --
+//     expanding int4 nibbles c to the byte 16*c on the way (a shift and a mask, the
+//     sign comes for free) -- and every wavefront pulls its 1 KB fragments straight
+//     from L2 with one coalesced load each, one stage ahead, into registers that
+//     are refilled in place.  The accumulator is shifted back by 4 at the end,
+//     which is exact because every partial sum is a multiple of 16.
+//   * The activations (the HBM stream) go global -> registers (two alternating
+//     sets, a full stage in flight) -> LDS (two slots, 128-byte rows, 16-byte chunks
+//     XOR-swizzled with the row) -> fragments refilled in place.
+//   * Workgroup = 2 x 2 wavefronts, tile (64*TM) x (64*TN) with TM < TN so that LDS
+//     reads per MFMA are 1/TN KB; 128 fan-in bytes per stage = 4 MFMA steps; one
+//     barrier per stage; two workgroups per CU.  All non-MFMA work is cut into
+//     pieces slotted between MFMAs; the loop body is branch-free (loads past the
+//     end are clamped to the last stage).
+constexpr int kBK = 128;     // fan-in bytes per stage
+constexpr int kKK = 4;       // MFMA steps (32 fan-in each) per stage
+
+#define AQT_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+constexpr int waitcnt_imm(int vm, int lgkm) {   // s_waitcnt immediate, gfx9 layout
+  return (vm & 0xF) | ((vm >> 4) << 14) | (7 << 4) | ((lgkm & 0xF) << 8);
+}
+
 // int4 -> int8 (times 16): eight nibbles of one dword, fan-in order c0..c7, become
 // the two dwords {16c0,16c1,16c2,16c3} and {16c4,..,16c7}.
 __device__ __forceinline__ void unpack8(uint32_t w, uint32_t &d0, uint32_t &d1) {
@@ -74,14 +96,41 @@ __device__ __forceinline__ void unpack8(uint32_t w, uint32_t &d0, uint32_t &d1) 
   d1 = __builtin_amdgcn_perm(hi, lo, 0x07030602u);  // lo.b2 hi.b2 lo.b3 hi.b3
 }
 
-template <int TM, int TN, bool PACKED, int EPI>
-__global__ __launch_bounds__(kThreads, (TM * TN <= 8) ? 2 : 1) void dense_fwd_mfma_kernel(
-    const int8_t *__restrict__ xq, const float *__restrict__ s_x, const uint8_t *__restrict__ wq,
+// Forward weight operand -> MFMA-fragment order.  Fragment (nb, ks) covers channels
+// 32*nb .. +31 and fan-in 32*ks .. +31; inside it lane (lk*32 + lr) owns the 16
+// consecutive fan-in positions 32*ks + 16*lk .. +15 of channel 32*nb + lr, i.e.
+// what that lane feeds to v_mfma_i32_32x32x32_i8.  Fragments are ordered [nb][ks].
+__global__ __launch_bounds__(kThreads) void weights_to_frag_kernel(const uint8_t *__restrict__ wq, int K, int N,
+                                                                   int packed, v4i *__restrict__ out) {
+  const int64_t pieces = static_cast<int64_t>(N) * (K / 16);
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+  const int ksteps = K / 32;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < pieces; i += stride) {
+    const int lane = static_cast<int>(i & 63);
+    const int64_t frag = i >> 6;
+    const int ks = static_cast<int>(frag % ksteps), nb = static_cast<int>(frag / ksteps);
+    const int n = 32 * nb + (lane & 31), k = 32 * ks + 16 * (lane >> 5);
+    v4i o;
+    if (packed) {
+      const uint2 w = *reinterpret_cast<const uint2 *>(wq + static_cast<int64_t>(n) * (K >> 1) + (k >> 1));
+      uint32_t d0, d1;
+      unpack8(w.x, d0, d1); o.x = d0; o.y = d1;
+      unpack8(w.y, d0, d1); o.z = d0; o.w = d1;
+    } else {
+      o = *reinterpret_cast<const v4i *>(wq + static_cast<int64_t>(n) * K + k);
+    }
+    out[i] = o;
+  }
+}
+
+template <int TM, int TN, bool SHIFT4, int EPI>
+__global__ __launch_bounds__(kThreads, 2) void dense_fwd_mfma_kernel(
+    const int8_t *__restrict__ xq, const float *__restrict__ s_x, const v4i *__restrict__ wfrag,
     const float *__restrict__ s_w, int M, int K, int N, const float *__restrict__ bias,
     float *__restrict__ y, int32_t *__restrict__ acc_out, int tiles_m, int tiles_n) {
   constexpr int BM = 64 * TM, BN = 64 * TN;
-  constexpr int kStage = (BM + BN) * kRow;
-  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  constexpr int NA = BM * (kBK / 16) / kThreads;   // 16-byte pieces of activations per thread per stage
+  __shared__ __attribute__((aligned(1024))) uint8_t sA0[BM * kBK], sA1[BM * kBK];
 
   // Workgroup -> tile.  Consecutive workgroup ids land on different XCDs (8 of
   // them, each with its own L2); give each XCD a contiguous run of tiles so the
@@ -95,78 +144,46 @@ __global__ __launch_bounds__(kThreads, (TM * TN <= 8) ? 2 : 1) void dense_fwd_mf
   const int m0 = min(bm * BM, M - BM);
 
   const int t = threadIdx.x;
-  const int wave = t >> 6, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63;   // wave index is uniform
   const int wm = wave >> 1, wn = wave & 1;
   const int lr = lane & 31, lk = lane >> 5;
 
-  // LDS row rr of the weight tile <- output channel
-  auto chan_of = [&](int rr) -> int {
-    if (EPI == AQT_EPI_GLU) {
-      const int blk = rr >> 5;
-      return ((blk & 1) ? (N >> 1) : 0) + bn * (BN / 2) + (blk >> 1) * 32 + (rr & 31);
-    }
-    return bn * BN + rr;
+  // Tile-local column block cb (32 columns) -> output channel of its first column.
+  // GLU tiles pair value and gate blocks: even blocks are values, odd blocks gates.
+  auto chan_of_block = [&](int cb) -> int {
+    if (EPI == AQT_EPI_GLU) return ((cb & 1) ? (N >> 1) : 0) + bn * (BN / 2) + (cb >> 1) * 32;
+    return bn * BN + cb * 32;
   };
 
-  // ---- global -> register staging ----
-  v4i ra[TM];
-  v4i rb[PACKED ? (TN / 2) : TN];
-  const int64_t wrow = PACKED ? (K >> 1) : K;
-
-  auto load_global = [&](int k0) {
+  // ---- activations: global -> registers -> LDS ----
+  v4i ra[2][NA];
+  const char *a_base = reinterpret_cast<const char *>(xq + static_cast<int64_t>(m0) * K);
+  const uint32_t ga0 = static_cast<uint32_t>((t >> 3) * K + (t & 7) * 16);   // piece i: + i * 32 rows
+  const uint32_t ga_step = static_cast<uint32_t>(32 * K);
+  const int rowa = t >> 3;
+  const int offa0 = rowa * kBK + (((t & 7) ^ (rowa & 7)) << 4);             // + i * 32 rows keeps row & 7
+  auto load_a = [&](int set, int k0) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int c = t + kThreads * i;
-      const int row = m0 + (c >> 2);
-      ra[i] = *reinterpret_cast<const v4i *>(xq + static_cast<int64_t>(row) * K + k0 + (c & 3) * 16);
-    }
-    if (PACKED) {
-#pragma unroll
-      for (int i = 0; i < TN / 2; ++i) {
-        const int c = t + kThreads * i;
-        const int n = chan_of(c >> 1);
-        rb[i] = *reinterpret_cast<const v4i *>(wq + static_cast<int64_t>(n) * wrow + (k0 >> 1) + (c & 1) * 16);
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < TN; ++i) {
-        const int c = t + kThreads * i;
-        const int n = chan_of(c >> 2);
-        rb[i] = *reinterpret_cast<const v4i *>(wq + static_cast<int64_t>(n) * wrow + k0 + (c & 3) * 16);
-      }
-    }
+    for (int i = 0; i < NA; ++i) ra[set][i] = *reinterpret_cast<const v4i *>(a_base + k0 + ga0 + i * ga_step);
+  };
+  auto store_a = [&](int set, int i, uint8_t *slot) {
+    *reinterpret_cast<v4i *>(slot + offa0 + i * 32 * kBK) = ra[set][i];
+  };
+  // fragments of the activations: row lr of row tile i, 16-byte chunk (2*kk + lk) ^ (lr & 7)
+  const int a_row = (wm * 32 * TM + lr) * kBK;
+  v4i fa[TM];
+  auto read_a = [&](const uint8_t *slot, int kk, int i) {
+    fa[i] = *reinterpret_cast<const v4i *>(slot + a_row + i * 32 * kBK + (((2 * kk + lk) ^ (lr & 7)) << 4));
   };
 
-  auto store_lds = [&](int buf) {
-    uint8_t *A = lds + buf * kStage;
-    uint8_t *B = A + BM * kRow;
+  // ---- weights: fragments straight from L2 ----
+  const int ksteps = K / 32;
+  const v4i *b_blk[TN];   // uniform: fragment row of column block j
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int c = t + kThreads * i;
-      *reinterpret_cast<v4i *>(A + (c >> 2) * kRow + (c & 3) * 16) = ra[i];
-    }
-    if (PACKED) {
-#pragma unroll
-      for (int i = 0; i < TN / 2; ++i) {
-        const int c = t + kThreads * i;
-        v4i lo, hi;
-        uint32_t d0, d1;
-        unpack8(static_cast<uint32_t>(rb[i].x), d0, d1); lo.x = d0; lo.y = d1;
-        unpack8(static_cast<uint32_t>(rb[i].y), d0, d1); lo.z = d0; lo.w = d1;
-        unpack8(static_cast<uint32_t>(rb[i].z), d0, d1); hi.x = d0; hi.y = d1;
-        unpack8(static_cast<uint32_t>(rb[i].w), d0, d1); hi.z = d0; hi.w = d1;
-        uint8_t *dst = B + (c >> 1) * kRow + (c & 1) * 32;
-        *reinterpret_cast<v4i *>(dst) = lo;
-        *reinterpret_cast<v4i *>(dst + 16) = hi;
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < TN; ++i) {
-        const int c = t + kThreads * i;
-        *reinterpret_cast<v4i *>(B + (c >> 2) * kRow + (c & 3) * 16) = rb[i];
-      }
-    }
-  };
+  for (int j = 0; j < TN; ++j)
+    b_blk[j] = wfrag + static_cast<int64_t>(chan_of_block(wn * TN + j) / 32) * ksteps * 64;
+  v4i fb[kKK][TN];
+  auto load_b = [&](int kk, int j, int stage) { fb[kk][j] = (b_blk[j] + (stage * kKK + kk) * 64)[lane]; };
 
   v16i acc[TM][TN];
 #pragma unroll
@@ -176,32 +193,73 @@ __global__ __launch_bounds__(kThreads, (TM * TN <= 8) ? 2 : 1) void dense_fwd_mf
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-  const int KT = K / kBK;
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
+  const int NS = K / kBK;
+  auto stage_idx = [&](int s) { return s < NS - 1 ? s : NS - 1; };
 
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < KT) load_global((kt + 1) * kBK);
-    const uint8_t *A = lds + buf * kStage + (wm * 32 * TM + lr) * kRow + lk * 16;
-    const uint8_t *B = lds + buf * kStage + BM * kRow + (wn * 32 * TN + lr) * kRow + lk * 16;
+  // ---- prologue ----
+  load_a(0, 0);
 #pragma unroll
-    for (int kk = 0; kk < kBK / 32; ++kk) {
-      v4i a[TM], b[TN];
+  for (int kk = 0; kk < kKK; ++kk)
 #pragma unroll
-      for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const v4i *>(A + i * 32 * kRow + kk * 32);
+    for (int j = 0; j < TN; ++j) load_b(kk, j, 0);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const v4i *>(B + j * 32 * kRow + kk * 32);
+  for (int i = 0; i < NA; ++i) store_a(0, i, sA0);
+  load_a(1, stage_idx(1) * kBK);
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
+  __builtin_amdgcn_s_barrier();
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < TM; ++i) read_a(sA0, 0, i);
+
+  // One stage; PAR = s % 2 is a compile-time constant (register sets, LDS slots).
+  // MFMA q = i*TN + j of a step: row tile i uses its activation fragment in TN
+  // consecutive MFMAs and is refilled right after; weight fragment j is last used
+  // by row tile TM-1 and is refilled (for the next stage, same step) right after.
+  auto stage = [&](auto par, int s) {
+    constexpr int PAR = decltype(par)::value;
+    uint8_t *cur = PAR ? sA1 : sA0;
+    uint8_t *nxt = PAR ? sA0 : sA1;
+    const int s1 = stage_idx(s + 1);
+    load_a(PAR, stage_idx(s + 2) * kBK);   // set PAR was written to LDS one stage ago
+    AQT_SCHED_FENCE();
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+    for (int kk = 0; kk < kKK; ++kk) {
+      if (kk == kKK - 1) {
+        // next stage fully staged by everybody before its first fragments are read
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
+        __builtin_amdgcn_s_barrier();
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[kk][j], acc[i][j], 0, 0, 0);
+          if (j & 1) {
+            AQT_SCHED_FENCE();
+            if (i == TM - 1) { load_b(kk, j - 1, s1); load_b(kk, j, s1); }
+            // stage s + 1 into the other slot during steps 0 and 1
+            if (kk < 2) {
+              constexpr int PER = (NA + 2 * TM * TN / 2 - 1) / (2 * TM * TN / 2);
+              const int slot_no = (kk * TM + i) * (TN / 2) + (j >> 1);
+#pragma unroll
+              for (int c = slot_no * PER; c < (slot_no + 1) * PER && c < NA; ++c) store_a(PAR ^ 1, c, nxt);
+            }
+            AQT_SCHED_FENCE();
+          }
+        }
+        // row tile i done for this step: refill its fragment for the next step
+        if (kk < kKK - 1) read_a(cur, kk + 1, i);
+        else read_a(nxt, 0, i);
+        AQT_SCHED_FENCE();
+      }
     }
-    if (kt + 1 < KT) store_lds(buf ^ 1);
-    __syncthreads();
+  };
+
+  int s = 0;
+  for (; s + 1 < NS; s += 2) {
+    stage(std::integral_constant<int, 0>{}, s);
+    stage(std::integral_constant<int, 1>{}, s + 1);
   }
+  if (s < NS) stage(std::integral_constant<int, 0>{}, s);
 
   // ---- epilogue: registers -> HBM ----
   // Lane holds output column (lane % 32) of each 32 x 32 tile; register r holds
@@ -216,12 +274,12 @@ __global__ __launch_bounds__(kThreads, (TM * TN <= 8) ? 2 : 1) void dense_fwd_mf
     int32_t *abase = acc_out + static_cast<int64_t>(m0) * N;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      const int lane_off = row_l * N + chan_of(wn * 32 * TN + j * 32 + lr);
+      const int lane_off = row_l * N + chan_of_block(wn * TN + j) + lr;
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int a0 = PACKED ? (acc[i][j][r] >> 4) : acc[i][j][r];
+          const int a0 = SHIFT4 ? (acc[i][j][r] >> 4) : acc[i][j][r];
           abase[(i * 32 + 8 * (r >> 2) + (r & 3)) * N + lane_off] = a0;
         }
     }
@@ -229,12 +287,12 @@ __global__ __launch_bounds__(kThreads, (TM * TN <= 8) ? 2 : 1) void dense_fwd_mf
   float *ybase = y + static_cast<int64_t>(m0) * out_cols;
 #pragma unroll
   for (int j = 0; j < TN; j += JS) {
-    const int n_a = chan_of(wn * 32 * TN + j * 32 + lr);   // for GLU: the value channel = output column
+    const int n_a = chan_of_block(wn * TN + j) + lr;   // for GLU: the value channel = output column
     const float sc_a = sx * s_w[n_a];
     const float bias_a = bias ? bias[n_a] : 0.0f;
     float sc_b = 0.0f, bias_b = 0.0f;
     if (EPI == AQT_EPI_GLU) {
-      const int n_b = chan_of(wn * 32 * TN + (j + 1) * 32 + lr);
+      const int n_b = chan_of_block(wn * TN + j + 1) + lr;
       sc_b = sx * s_w[n_b];
       bias_b = bias ? bias[n_b] : 0.0f;
     }
@@ -243,7 +301,7 @@ __global__ __launch_bounds__(kThreads, (TM * TN <= 8) ? 2 : 1) void dense_fwd_mf
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int a0 = PACKED ? (acc[i][j][r] >> 4) : acc[i][j][r];
+        const int a0 = SHIFT4 ? (acc[i][j][r] >> 4) : acc[i][j][r];
         const float v = dequant_f32(a0, sc_a) + bias_a;   // adding a zero bias changes nothing
         float out;
         if (EPI == AQT_EPI_NONE) {
@@ -251,7 +309,7 @@ __global__ __launch_bounds__(kThreads, (TM * TN <= 8) ? 2 : 1) void dense_fwd_mf
         } else if (EPI == AQT_EPI_SWISH) {
           out = swish_f32(v);
         } else {
-          const int a1 = PACKED ? (acc[i][j + (JS - 1)][r] >> 4) : acc[i][j + (JS - 1)][r];
+          const int a1 = SHIFT4 ? (acc[i][j + (JS - 1)][r] >> 4) : acc[i][j + (JS - 1)][r];
           const float g = dequant_f32(a1, sc_b) + bias_b;
           out = v * sigmoid_f32(g);
         }
@@ -262,61 +320,62 @@ __global__ __launch_bounds__(kThreads, (TM * TN <= 8) ? 2 : 1) void dense_fwd_mf
   }
 }
 
-template <int TM, int TN, bool PACKED, int EPI>
-aqt_status launch_mfma(const int8_t *xq, const float *s_x, const void *wq, const float *s_w, int64_t M,
+template <int TM, int TN, bool SHIFT4, int EPI>
+aqt_status launch_mfma(const int8_t *xq, const float *s_x, const v4i *wfrag, const float *s_w, int64_t M,
                        int64_t K, int64_t N, const float *bias, float *y, int32_t *acc_out, hipStream_t st) {
   constexpr int BM = 64 * TM, BN = 64 * TN;
-  constexpr int smem = 2 * (BM + BN) * kRow;
-  auto kern = dense_fwd_mfma_kernel<TM, TN, PACKED, EPI>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    AQT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, smem));
-    attr_set = true;
-  }
+  auto kern = dense_fwd_mfma_kernel<TM, TN, SHIFT4, EPI>;
   const int tiles_m = static_cast<int>(cdiv(M, BM)), tiles_n = static_cast<int>(N / BN);
-  kern<<<tiles_m * tiles_n, kThreads, smem, st>>>(xq, s_x, static_cast<const uint8_t *>(wq), s_w,
-                                                  static_cast<int>(M), static_cast<int>(K),
-                                                  static_cast<int>(N), bias, y, acc_out, tiles_m, tiles_n);
+  kern<<<tiles_m * tiles_n, kThreads, 0, st>>>(xq, s_x, wfrag, s_w, static_cast<int>(M), static_cast<int>(K),
+                                               static_cast<int>(N), bias, y, acc_out, tiles_m, tiles_n);
   AQT_HIP(hipGetLastError());
   return AQT_OK;
 }
 
-template <int TM, int TN, bool PACKED>
-aqt_status launch_mfma_epi(int epilogue, const int8_t *xq, const float *s_x, const void *wq, const float *s_w,
+template <int TM, int TN, bool SHIFT4>
+aqt_status launch_mfma_epi(int epilogue, const int8_t *xq, const float *s_x, const v4i *wfrag, const float *s_w,
                            int64_t M, int64_t K, int64_t N, const float *bias, float *y, int32_t *acc_out,
                            hipStream_t st) {
   switch (epilogue) {
-    case AQT_EPI_NONE: return launch_mfma<TM, TN, PACKED, AQT_EPI_NONE>(xq, s_x, wq, s_w, M, K, N, bias, y, acc_out, st);
-    case AQT_EPI_SWISH: return launch_mfma<TM, TN, PACKED, AQT_EPI_SWISH>(xq, s_x, wq, s_w, M, K, N, bias, y, acc_out, st);
-    default: return launch_mfma<TM, TN, PACKED, AQT_EPI_GLU>(xq, s_x, wq, s_w, M, K, N, bias, y, acc_out, st);
+    case AQT_EPI_NONE: return launch_mfma<TM, TN, SHIFT4, AQT_EPI_NONE>(xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, st);
+    case AQT_EPI_SWISH: return launch_mfma<TM, TN, SHIFT4, AQT_EPI_SWISH>(xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, st);
+    default: return launch_mfma<TM, TN, SHIFT4, AQT_EPI_GLU>(xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, st);
   }
 }
 
 }  // namespace
 
+size_t fwd_q_workspace_bytes(int64_t K, int64_t N) { return align_up(static_cast<size_t>(K) * N, 256); }
+
 aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq_packed, const float *s_w,
                               int64_t M, int64_t K, int64_t N, int bits_w, const float *bias, int epilogue,
-                              float *y, int32_t *acc_out, hipStream_t st) {
+                              float *y, int32_t *acc_out, void *ws, hipStream_t st) {
   const bool packed = packed4(bits_w);
   const bool aligned = (reinterpret_cast<uintptr_t>(xq) % 16 == 0) &&
-                       (reinterpret_cast<uintptr_t>(wq_packed) % 16 == 0);
+                       (reinterpret_cast<uintptr_t>(wq_packed) % 16 == 0) && ws &&
+                       (reinterpret_cast<uintptr_t>(ws) % 16 == 0);
   const bool sizes_fit = M < (int64_t(1) << 31) / (K > N ? K : N);  // 32-bit tile arithmetic inside
-  if (aligned && sizes_fit && K % kBK == 0) {
+  if (aligned && sizes_fit && K % kBK == 0 && M >= 128) {
     // The column tile must divide N (N/2 for GLU, whose tile holds value and gate halves).
-    // 256 x 128 tiles (wavefront tile 128 x 64, two workgroups per CU so that one
-    // workgroup's epilogue and staging overlap the other's MFMA work) once there
-    // are enough of them to fill the chip, else 128 x 128.
+    // 128 x 256 tiles once there are enough of them to fill the chip, else 128 x 128.
     const int64_t nn = (epilogue == AQT_EPI_GLU) ? N / 2 : N;
+    const int64_t unit_wide = (epilogue == AQT_EPI_GLU) ? 128 : 256;
     const int64_t unit = (epilogue == AQT_EPI_GLU) ? 64 : 128;
-    if (nn % unit == 0 && M >= 128) {
-      const int64_t wide_tiles = cdiv(M, 256) * (N / 128);
-      if (M >= 256 && wide_tiles >= 512) {
-        return packed ? launch_mfma_epi<4, 2, true>(epilogue, xq, s_x, wq_packed, s_w, M, K, N, bias, y, acc_out, st)
-                      : launch_mfma_epi<4, 2, false>(epilogue, xq, s_x, wq_packed, s_w, M, K, N, bias, y, acc_out, st);
+    if (nn % unit == 0) {
+      v4i *wfrag = static_cast<v4i *>(ws);
+      const int64_t pieces = N * (K / 16);
+      int g = static_cast<int>(cdiv(pieces, kThreads));
+      if (g > 2048) g = 2048;
+      weights_to_frag_kernel<<<g, kThreads, 0, st>>>(static_cast<const uint8_t *>(wq_packed), static_cast<int>(K),
+                                                     static_cast<int>(N), packed ? 1 : 0, wfrag);
+      AQT_HIP(hipGetLastError());
+      const bool wide = (nn % unit_wide == 0) && cdiv(M, 128) * (N / 256) >= 512;
+      if (wide) {
+        return packed ? launch_mfma_epi<2, 4, true>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, st)
+                      : launch_mfma_epi<2, 4, false>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, st);
       }
-      return packed ? launch_mfma_epi<2, 2, true>(epilogue, xq, s_x, wq_packed, s_w, M, K, N, bias, y, acc_out, st)
-                    : launch_mfma_epi<2, 2, false>(epilogue, xq, s_x, wq_packed, s_w, M, K, N, bias, y, acc_out, st);
+      return packed ? launch_mfma_epi<2, 2, true>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, st)
+                    : launch_mfma_epi<2, 2, false>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, st);
     }
   }
   const int64_t ncols = (epilogue == AQT_EPI_GLU) ? N / 2 : N;

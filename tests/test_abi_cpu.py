@@ -79,6 +79,8 @@ def test_argument_errors_are_synchronous_and_touch_no_gpu(L):
     assert L.aqt_dense_fwd_q(one, one, one, one, 4, 4, 4, 8, 4, none, 3, one, none, none, 0, none) == B.AQT_ERR_INVALID_ARG
     assert L.aqt_dense_fwd_q(one, one, one, one, 4, 200000, 4, 8, 4, none, 0, one, none, none, 0, none) == B.AQT_ERR_UNSUPPORTED
     assert L.aqt_dense_fwd_q(one, one, one, one, 4, 9000, 4, 8, 8, none, 0, one, none, none, 0, none) == B.AQT_ERR_UNSUPPORTED
+    assert L.aqt_dense_fwd_q(one, one, one, one, 4, 4, 4, 8, 4, none, 0, one, none, none, 0, none) == B.AQT_ERR_WORKSPACE
+    assert L.aqt_dense_fwd_q(one, one, one, one, 4, 4, 4, 8, 4, none, 0, one, none, one, 8, none) == B.AQT_ERR_WORKSPACE
     assert L.aqt_dense_fwd(one, one, 4, 4, 4, 8, 4, none, 0, one, None, none, 0, none, none) == B.AQT_ERR_WORKSPACE
     assert L.aqt_dense_fwd(one, none, 4, 4, 4, 8, 4, none, 0, one, None, one, 1 << 30, none, none) == B.AQT_ERR_INVALID_ARG
     sv = B.aqt_saved(None, None, None, None, None, None, None)

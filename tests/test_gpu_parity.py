@@ -160,9 +160,10 @@ FWD_CASES = [
     (256, 256, 1024, 8, 4, 0, False),    # the single-layer config: tuned kernel, 128 x 128 tiles
     (300, 128, 256, 8, 4, 0, True),      # ragged M on the tuned kernel
     (300, 128, 256, 8, 8, 1, True),      # int8 weights, Swish
-    (200, 192, 512, 8, 4, 2, True),      # GLU on the tuned kernel
-    (200, 192, 512, 8, 8, 2, False),
-    (1100, 64, 128, 4, 4, 1, False),     # int4 activations
+    (200, 256, 512, 8, 4, 2, True),      # GLU on the tuned kernel
+    (200, 384, 512, 8, 8, 2, False),     # odd number of fan-in stages
+    (1100, 128, 128, 4, 4, 1, False),    # int4 activations, a single stage
+    (130, 192, 256, 8, 4, 0, True),      # fan-in not a multiple of the stage: general kernel
     (37, 50, 23, 8, 4, 0, True),         # general kernel, odd K
     (37, 51, 24, 8, 8, 2, True),         # general kernel, GLU
     (5, 7, 3, 8, 4, 1, False),
@@ -285,6 +286,21 @@ def test_argument_errors_on_device_buffers():
     with pytest.raises(B.AqtError) as e:
         B.aqt_dense_fwd(x, x, 8, 4, ws=B.workspace(256))
     assert e.value.status == B.AQT_ERR_WORKSPACE
+
+
+# 128 x 256 tiles are used once there are at least 512 of them
+WIDE_TILE_CASES = [
+    # M, K, N, bits_x, bits_w, epilogue
+    (16384, 128, 1024, 8, 8, 2),     # GLU, value and gate halves in one tile, a single stage
+    (16500, 384, 1024, 8, 4, 1),     # ragged M (shifted last row tile), Swish, three stages
+    (16384, 256, 2048, 4, 4, 0),     # int4 x int4
+]
+
+
+@pytest.mark.parametrize("M,K,N,bx,bw,epi", WIDE_TILE_CASES)
+def test_dense_fwd_wide_tiles_sampled(M, K, N, bx, bw, epi):
+    c = inputs.small_case(53 + K + N, M, K, N, bx, bw, epi, with_dy=False)
+    run_full_size_case(c, n_samples=2000)
 
 
 # ----------------------------------------------------------------------------
