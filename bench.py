@@ -30,6 +30,22 @@ PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
 PEAK_INT8_TOPS = 5000.0      # dense int8 MFMA
 PEAK_BF16_TFLOPS = 2500.0    # dense bf16 MFMA
 
+# HBM traffic per launch in MiB (read, written) of each segment's kernels at the default
+# workload (65536 tokens), from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy;
+# source: profiles/training_step_cfg5_hbm_traffic.txt.  Keys: (layer index, segment).
+MEASURED_TRAFFIC_MIB = {
+    (0, "quantize_x"): (128.0 + 128.1, 0.1 + 32.0),      # abs-max pass + code pass
+    (1, "quantize_x"): (512.0 + 512.1, 0.1 + 128.0),
+    (0, "quantize_w"): (4.0 + 4.2, 0.1 + 1.5),
+    (1, "quantize_w"): (4.0 + 4.1, 0.0 + 1.5),
+    (0, "fwd_gemm"): (1.0 + 40.7, 1.0 + 514.0),          # fragment re-order + contraction
+    (1, "fwd_gemm"): (1.0 + 150.6, 1.0 + 129.1),
+    (0, "bwd_dx"): (2.0 + 572.9, 2.0 + 128.0),
+    (1, "bwd_dx"): (2.0 + 151.6, 2.0 + 512.0),
+    (0, "bwd_dw"): (546.5 + 64.1, 164.6 + 4.0),          # slab partials + fold
+    (1, "bwd_dw"): (258.4 + 64.1, 156.8 + 4.0),
+}
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -38,7 +54,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=50,
                     help="untimed steps; the card needs a few tens of milliseconds of load to reach its steady clocks")
     ap.add_argument("--tokens", type=int, default=65536, help="rows of the activation tensors")
-    ap.add_argument("--cpu-rows", type=int, default=8192, help="row sample the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=24576, help="row sample the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy of 1 GiB (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -149,16 +165,42 @@ def main():
         # backward contractions run on bf16 MFMA (codes exact in bf16, float operand split hi/lo)
         return dict(bound="mfma", achieved=mnk2 / ms / 1e9, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s")
 
+    def seg_traffic(li, name):
+        """Measured HBM bytes per launch (profiles/), or None away from the profiled workload."""
+        if args.tokens != 65536:
+            return None
+        rd, wr = MEASURED_TRAFFIC_MIB[(li, name)]
+        return (rd + wr) * 1048576.0
+
     kernels = {}
     for (li, name), ms in seg_ms.items():
+        c = layers[li]["c"]
         r = seg_roofline(li, name)
         r["frac"] = r["achieved"] / r["peak"]
         r["ms"] = ms
-        kernels[f"{layers[li]['c'].name}.{name}"] = r
+        tr = seg_traffic(li, name)
+        r["traffic"] = tr
+        if tr is not None:      # measured HBM bytes over measured time, against the 8 TB/s peak
+            r["hbm_gbs_measured_bytes"] = tr / ms / 1e6
+            r["hbm_frac_measured_bytes"] = tr / ms / 1e6 / PEAK_HBM_GBS
+        if name in ("fwd_gemm", "bwd_dx", "bwd_dw"):
+            mnk2 = 2.0 * c.M * c.K * c.N
+            pk = 0.5 if c.bits_w <= 4 else 1.0
+            if name == "fwd_gemm":
+                by, peak = c.M * c.K + c.K * c.N * pk + 4.0 * c.M * c.N, PEAK_INT8_TOPS
+            elif name == "bwd_dx":
+                by, peak = 4.0 * c.M * c.N + c.K * c.N + 4.0 * c.M * c.K, PEAK_BF16_TFLOPS / 2   # two bf16 passes
+            else:
+                by, peak = c.M * c.K + 4.0 * c.M * c.N + 4.0 * c.K * c.N, PEAK_BF16_TFLOPS / 2
+            cap = min(peak, mnk2 / by * PEAK_HBM_GBS / 1e3)      # T(FL)OP/s the roofline allows
+            r["tops"] = mnk2 / ms / 1e9
+            r["pct_of_mfma_peak_for_dtype"] = 100.0 * r["tops"] / (PEAK_INT8_TOPS if name == "fwd_gemm" else PEAK_BF16_TFLOPS)
+            r["pct_of_roofline_cap"] = 100.0 * r["tops"] / cap
+        kernels[f"{c.name}.{name}"] = r
     dom_key = max(seg_ms, key=lambda k: seg_ms[k])
     roof = dict(seg_roofline(*dom_key))
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = seg_traffic(*dom_key)
     roof["kernel"] = f"{layers[dom_key[0]]['c'].name}.{dom_key[1]}"
     roof["avg_ms"] = seg_ms[dom_key]
 
