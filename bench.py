@@ -55,6 +55,8 @@ def main():
                     help="untimed steps; the card needs a few tens of milliseconds of load to reach its steady clocks")
     ap.add_argument("--tokens", type=int, default=65536, help="rows of the activation tensors")
     ap.add_argument("--cpu-rows", type=int, default=24576, help="row sample the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the extra figures of the fused abs-max path (keeps a profile to the timed steps)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy of 1 GiB (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -122,6 +124,42 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     assert int(status.item()) == 0, "non-finite input reported by the library"
+
+    # Extra figures, outside `value`: layer 1 with a Swish epilogue that also emits max|y|, and the
+    # one-pass quantizer of layer 2's input that consumes it, beside their plain counterparts.
+    fused = None
+    if not args.no_extras:
+        L1 = layers[0]
+        c1, sv1 = L1["c"], L1["sv"]
+        y1 = layers[1]["x"]                       # same shape as layer 2's input: reuse the buffer
+        m1 = torch.empty(1, dtype=torch.float32, device="cuda")
+        xq2, s2 = layers[1]["sv"].xq, layers[1]["sv"].s_x
+
+        def timed(fn, n=30):
+            for _ in range(5):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+        fused = {
+            "fwd_swish_ms": timed(lambda: B.aqt_dense_fwd_q(sv1.xq, sv1.s_x, sv1.wq_packed, sv1.s_w, c1.N, c1.bits_x,
+                                                             c1.bits_w, epilogue=B.AQT_EPI_SWISH, y=y1, ws=L1["ws_f"])),
+            "fwd_swish_absmax_ms": timed(lambda: B.aqt_dense_fwd_q_absmax(sv1.xq, sv1.s_x, sv1.wq_packed, sv1.s_w, c1.N,
+                                                                           c1.bits_x, c1.bits_w, epilogue=B.AQT_EPI_SWISH,
+                                                                           y=y1, y_absmax=m1, ws=L1["ws_f"])),
+            "quantize_two_pass_ms": timed(lambda: B.aqt_quantize(y1, 8, B.AQT_AXIS_ALL, q=xq2, scale=s2,
+                                                                 ws=layers[1]["ws_q"], dev_status=status)),
+            "quantize_one_pass_known_absmax_ms": timed(lambda: B.aqt_quantize_with_absmax(y1, 8, m1, q=xq2, scale=s2,
+                                                                                         dev_status=status)),
+            "tensor": [c1.M, c1.N],
+        }
+        by = 5.0 * c1.M * c1.N
+        fused["quantize_one_pass_gbs"] = by / fused["quantize_one_pass_known_absmax_ms"] / 1e6
+        fused["quantize_one_pass_hbm_frac"] = fused["quantize_one_pass_gbs"] / PEAK_HBM_GBS
 
     if args.calibrate_copy:
         # known traffic: 2^28 floats read (1 GiB) and written (1 GiB) by one elementwise kernel
@@ -234,6 +272,7 @@ def main():
         "roofline": roof,
         "cpu_baseline": cpu,
         "kernels": kernels,
+        "fused_producer_absmax": fused,
     }
     print(json.dumps(out))
 

@@ -153,6 +153,33 @@ aqt_status aqt_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq_pa
                            void *stream);
 
 /*
+ * Producer-side abs-max for a chain of quantized layers.  The next layer's
+ * activation quantizer (Fig. 2, per tensor) needs m = max|y| of this layer's
+ * output before it can emit a single code; computing m where y is produced
+ * saves that quantizer its first pass over y.
+ * As aqt_dense_fwd_q (without acc_out), and additionally
+ *   *y_absmax = max over all outputs of |y|   (device float, after bias / epilogue;
+ *               for GLU over the [M,N/2] outputs).  Exactly the maximum of the
+ *               values written to y; Inf or NaN in y gives Inf or NaN here.
+ * The word is cleared by the call itself.
+ */
+aqt_status aqt_dense_fwd_q_absmax(const int8_t *xq, const float *s_x, const void *wq_packed,
+                                  const float *s_w, int64_t M, int64_t K, int64_t N, int bits_x, int bits_w,
+                                  const float *bias, int epilogue, float *y, float *y_absmax, void *ws,
+                                  size_t ws_bytes, void *stream);
+
+/*
+ * Fig. 2 per tensor with m = max|x| supplied by the caller (device float, >= 0),
+ * e.g. by aqt_dense_fwd_q_absmax: scale = m / qmax, codes as in aqt_quantize, one
+ * pass over x.  Bit-identical to aqt_quantize(axis = AQT_AXIS_ALL) when m is the
+ * true maximum; a smaller m saturates codes at +-qmax (clip_mask then has zeros),
+ * a non-finite or negative m sets *dev_status to AQT_ERR_NONFINITE.
+ */
+aqt_status aqt_quantize_with_absmax(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bits,
+                                    const float *absmax, int8_t *q, float *scale, uint32_t *clip_mask,
+                                    void *stream, int32_t *dev_status);
+
+/*
  * The training forward: quantizes x per tensor and w per output channel inside
  * the call (weights are trained from scratch, so they are re-quantized every
  * step, Sec. 2.2), then runs aqt_dense_fwd_q.  Bit-identical to calling

@@ -24,7 +24,8 @@ AQT_OP_QUANTIZE, AQT_OP_QUANTIZE_WEIGHTS, AQT_OP_DENSE_FWD, AQT_OP_DENSE_FWD_Q, 
 # every symbol include/aqt.h declares
 SYMBOLS = ["aqt_status_string", "aqt_last_hip_error", "aqt_version", "aqt_workspace_bytes",
            "aqt_packed_weight_bytes", "aqt_quantize", "aqt_quantize_with_scale", "aqt_quantize_weights",
-           "aqt_unpack_weights", "aqt_dense_fwd_q", "aqt_dense_fwd", "aqt_dense_bwd"]
+           "aqt_unpack_weights", "aqt_dense_fwd_q", "aqt_dense_fwd_q_absmax", "aqt_quantize_with_absmax",
+           "aqt_dense_fwd", "aqt_dense_bwd"]
 
 
 class AqtError(RuntimeError):
@@ -68,6 +69,9 @@ def lib() -> ctypes.CDLL:
         L.aqt_unpack_weights.argtypes = [_vp, _i64, _i64, _int, _vp, _vp]
         L.aqt_dense_fwd_q.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _vp,
                                       _vp, _sz, _vp]
+        L.aqt_dense_fwd_q_absmax.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp,
+                                             _vp, _vp, _sz, _vp]
+        L.aqt_quantize_with_absmax.argtypes = [_vp, _i64, _i64, _i64, _int, _vp, _vp, _vp, _vp, _vp, _vp]
         L.aqt_dense_fwd.argtypes = [_vp, _vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp,
                                     ctypes.POINTER(aqt_saved), _vp, _sz, _vp, _vp]
         L.aqt_dense_bwd.argtypes = [_vp, ctypes.POINTER(aqt_saved), _i64, _i64, _i64, _int, _int, _vp, _vp, _vp,
@@ -194,6 +198,38 @@ def aqt_dense_fwd_q(xq, s_x, wq_packed, s_w, N: int, bits_x: int, bits_w: int, *
                                _ptr(bias), epilogue, _ptr(y), _ptr(acc_out), _ptr(ws), ws.numel(), _stream())
     _check(st, "aqt_dense_fwd_q")
     return y, acc_out
+
+
+def aqt_dense_fwd_q_absmax(xq, s_x, wq_packed, s_w, N: int, bits_x: int, bits_w: int, *, bias=None,
+                           epilogue: int = AQT_EPI_NONE, y=None, y_absmax=None, ws=None):
+    """aqt_dense_fwd_q_absmax: returns (y float32, y_absmax float32 [1])."""
+    _dev(xq, torch.int8, "xq")
+    M, K = xq.shape
+    if ws is None:
+        ws = workspace(aqt_workspace_bytes(AQT_OP_DENSE_FWD_Q, M, K, N, bits_x, bits_w))
+    y = torch.empty((M, _out_cols(N, epilogue)), dtype=torch.float32, device=xq.device) if y is None else y
+    y_absmax = torch.empty(1, dtype=torch.float32, device=xq.device) if y_absmax is None else y_absmax
+    st = lib().aqt_dense_fwd_q_absmax(_ptr(xq), _ptr(s_x), _ptr(wq_packed), _ptr(s_w), M, K, N, bits_x, bits_w,
+                                      _ptr(bias), epilogue, _ptr(y), _ptr(y_absmax), _ptr(ws), ws.numel(),
+                                      _stream())
+    _check(st, "aqt_dense_fwd_q_absmax")
+    return y, y_absmax
+
+
+def aqt_quantize_with_absmax(x, bits: int, absmax, *, q=None, scale=None, clip_mask=None, want_mask=False,
+                             dev_status=None):
+    """aqt_quantize_with_absmax: returns (q int8, scale float32 [1], clip_mask or None)."""
+    _dev(x, torch.float32, "x")
+    _dev(absmax, torch.float32, "absmax")
+    rows, cols = x.shape
+    q = torch.empty((rows, cols), dtype=torch.int8, device=x.device) if q is None else q
+    scale = torch.empty(1, dtype=torch.float32, device=x.device) if scale is None else scale
+    if want_mask and clip_mask is None:
+        clip_mask = torch.empty(_words(rows * cols), dtype=torch.int32, device=x.device)
+    st = lib().aqt_quantize_with_absmax(_ptr(x), rows, cols, cols, bits, _ptr(absmax), _ptr(q), _ptr(scale),
+                                        _ptr(clip_mask), _stream(), _ptr(dev_status))
+    _check(st, "aqt_quantize_with_absmax")
+    return q, scale, clip_mask
 
 
 class Saved:

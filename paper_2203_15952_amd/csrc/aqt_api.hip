@@ -137,8 +137,31 @@ aqt_status aqt_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq_pa
   if (epilogue == AQT_EPI_GLU && (N % 2)) return AQT_ERR_UNSUPPORTED;
   if (!acc_fits(K, bits_x, bits_w)) return AQT_ERR_UNSUPPORTED;
   if (!ws || ws_bytes < fwd_q_workspace_bytes(K, N)) return AQT_ERR_WORKSPACE;
-  return launch_dense_fwd_q(xq, s_x, wq_packed, s_w, M, K, N, bits_w, bias, epilogue, y, acc_out, ws,
+  return launch_dense_fwd_q(xq, s_x, wq_packed, s_w, M, K, N, bits_w, bias, epilogue, y, acc_out, nullptr, ws,
                             static_cast<hipStream_t>(stream));
+}
+
+aqt_status aqt_dense_fwd_q_absmax(const int8_t *xq, const float *s_x, const void *wq_packed, const float *s_w,
+                                  int64_t M, int64_t K, int64_t N, int bits_x, int bits_w, const float *bias,
+                                  int epilogue, float *y, float *y_absmax, void *ws, size_t ws_bytes,
+                                  void *stream) {
+  if (!xq || !s_x || !wq_packed || !s_w || !y || !y_absmax || !shape_ok(M, K) || N < 1) return AQT_ERR_INVALID_ARG;
+  if (epilogue != AQT_EPI_NONE && epilogue != AQT_EPI_SWISH && epilogue != AQT_EPI_GLU) return AQT_ERR_INVALID_ARG;
+  if (!bits_ok(bits_x) || !bits_ok(bits_w)) return AQT_ERR_UNSUPPORTED;
+  if (epilogue == AQT_EPI_GLU && (N % 2)) return AQT_ERR_UNSUPPORTED;
+  if (!acc_fits(K, bits_x, bits_w)) return AQT_ERR_UNSUPPORTED;
+  if (!ws || ws_bytes < fwd_q_workspace_bytes(K, N)) return AQT_ERR_WORKSPACE;
+  return launch_dense_fwd_q(xq, s_x, wq_packed, s_w, M, K, N, bits_w, bias, epilogue, y, nullptr,
+                            reinterpret_cast<uint32_t *>(y_absmax), ws, static_cast<hipStream_t>(stream));
+}
+
+aqt_status aqt_quantize_with_absmax(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bits,
+                                    const float *absmax, int8_t *q, float *scale, uint32_t *clip_mask,
+                                    void *stream, int32_t *dev_status) {
+  if (!x || !absmax || !q || !scale || !shape_ok(rows, cols) || ldx < cols) return AQT_ERR_INVALID_ARG;
+  if (!bits_ok(bits)) return AQT_ERR_UNSUPPORTED;
+  return launch_quantize_with_absmax(x, rows, cols, ldx, bits, reinterpret_cast<const uint32_t *>(absmax), q, scale,
+                                     clip_mask, static_cast<hipStream_t>(stream), dev_status);
 }
 
 aqt_status aqt_dense_fwd(const float *x, const float *w, int64_t M, int64_t K, int64_t N, int bits_x, int bits_w,
@@ -160,7 +183,7 @@ aqt_status aqt_dense_fwd(const float *x, const float *w, int64_t M, int64_t K, i
                           f.partials, st, dev_status));
   AQT_TRY(launch_quantize_weights(w, K, N, bits_w, wq, s_w, saved ? saved->wq_kn : nullptr,
                                   saved ? saved->mask_w : nullptr, f.wpart, st, dev_status));
-  return launch_dense_fwd_q(xq, s_x, wq, s_w, M, K, N, bits_w, bias, epilogue, y, nullptr, f.wfrag, st);
+  return launch_dense_fwd_q(xq, s_x, wq, s_w, M, K, N, bits_w, bias, epilogue, y, nullptr, nullptr, f.wfrag, st);
 }
 
 aqt_status aqt_dense_bwd(const float *dy, const aqt_saved *saved, int64_t M, int64_t K, int64_t N, int bits_x,

@@ -38,6 +38,9 @@ __host__ __device__ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 
 aqt_status launch_quantize(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bits, int axis,
                            int8_t *q, float *scale, uint32_t *mask, float *partials, hipStream_t st,
                            int32_t *dev_status);
+aqt_status launch_quantize_with_absmax(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bits,
+                                       const uint32_t *absmax_bits, int8_t *q, float *scale, uint32_t *mask,
+                                       hipStream_t st, int32_t *dev_status);
 aqt_status launch_quantize_with_scale(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bits,
                                       int axis, const float *scale, int8_t *q, uint32_t *mask,
                                       hipStream_t st);
@@ -51,8 +54,8 @@ aqt_status launch_unpack_weights(const void *wq_packed, int64_t K, int64_t N, in
 // ---- forward contraction (gemm_fwd.hip) -----------------------------------------
 aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq_packed,
                               const float *s_w, int64_t M, int64_t K, int64_t N, int bits_w,
-                              const float *bias, int epilogue, float *y, int32_t *acc_out, void *ws,
-                              hipStream_t st);
+                              const float *bias, int epilogue, float *y, int32_t *acc_out, uint32_t *y_absmax,
+                              void *ws, hipStream_t st);
 size_t fwd_q_workspace_bytes(int64_t K, int64_t N);
 
 // ---- straight-through backward (gemm_bwd.hip) -------------------------------------

@@ -29,10 +29,22 @@ __device__ __forceinline__ int weight_code(const uint8_t *__restrict__ wq, int64
   return static_cast<int8_t>(wq[n * row_bytes + k]);
 }
 
+// max|y| as an unsigned maximum over bit patterns (non-negative floats order like
+// their bits; NaN and Inf come out on top, which is how the consumer learns of them).
+// The word only grows, so a stale read can only cause a redundant atomic.
+__device__ __forceinline__ void note_absmax(uint32_t *y_absmax, uint32_t bits) {
+  if (bits > *reinterpret_cast<volatile uint32_t *>(y_absmax)) atomicMax(y_absmax, bits);
+}
+
+__global__ void zero_word_kernel(uint32_t *p) {
+  if (threadIdx.x == 0) *p = 0u;
+}
+
 __global__ __launch_bounds__(kThreads) void dense_fwd_general_kernel(
     const int8_t *__restrict__ xq, const float *__restrict__ s_x, const uint8_t *__restrict__ wq,
     const float *__restrict__ s_w, int64_t M, int64_t K, int64_t N, int packed,
-    const float *__restrict__ bias, int epilogue, float *__restrict__ y, int32_t *__restrict__ acc_out) {
+    const float *__restrict__ bias, int epilogue, float *__restrict__ y, int32_t *__restrict__ acc_out,
+    uint32_t *__restrict__ y_absmax) {
   const int64_t ncols = (epilogue == AQT_EPI_GLU) ? N / 2 : N;
   const int64_t idx = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
   if (idx >= M * ncols) return;
@@ -55,6 +67,7 @@ __global__ __launch_bounds__(kThreads) void dense_fwd_general_kernel(
   else if (epilogue == AQT_EPI_SWISH) out = swish_f32(v[0]);
   else out = v[0] * sigmoid_f32(v[1]);
   y[m * ncols + j] = out;
+  if (y_absmax) note_absmax(y_absmax, __float_as_uint(out) & 0x7FFFFFFFu);
 }
 
 // ---- tuned MFMA kernel --------------------------------------------------------------
@@ -127,7 +140,8 @@ template <int TM, int TN, bool SHIFT4, int EPI>
 __global__ __launch_bounds__(kThreads, 2) void dense_fwd_mfma_kernel(
     const int8_t *__restrict__ xq, const float *__restrict__ s_x, const v4i *__restrict__ wfrag,
     const float *__restrict__ s_w, int M, int K, int N, const float *__restrict__ bias,
-    float *__restrict__ y, int32_t *__restrict__ acc_out, int tiles_m, int tiles_n) {
+    float *__restrict__ y, int32_t *__restrict__ acc_out, uint32_t *__restrict__ y_absmax, int tiles_m,
+    int tiles_n) {
   constexpr int BM = 64 * TM, BN = 64 * TN;
   constexpr int NA = BM * (kBK / 16) / kThreads;   // 16-byte pieces of activations per thread per stage
   __shared__ __attribute__((aligned(1024))) uint8_t sA0[BM * kBK], sA1[BM * kBK];
@@ -285,6 +299,7 @@ __global__ __launch_bounds__(kThreads, 2) void dense_fwd_mfma_kernel(
     }
   }
   float *ybase = y + static_cast<int64_t>(m0) * out_cols;
+  uint32_t amax = 0u;   // running max|out| of this lane, as a bit pattern
 #pragma unroll
   for (int j = 0; j < TN; j += JS) {
     const int n_a = chan_of_block(wn * TN + j) + lr;   // for GLU: the value channel = output column
@@ -315,19 +330,26 @@ __global__ __launch_bounds__(kThreads, 2) void dense_fwd_mfma_kernel(
         }
         // written once, read by another kernel much later: stream it past the caches
         __builtin_nontemporal_store(out, ybase + (i * 32 + 8 * (r >> 2) + (r & 3)) * out_cols + lane_off);
+        amax = max(amax, __float_as_uint(out) & 0x7FFFFFFFu);
       }
     }
+  }
+  if (y_absmax) {   // uniform: one atomic per wavefront, and only if it can raise the word
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) amax = max(amax, static_cast<uint32_t>(__shfl_xor(static_cast<int>(amax), off)));
+    if (lane == 0) note_absmax(y_absmax, amax);
   }
 }
 
 template <int TM, int TN, bool SHIFT4, int EPI>
 aqt_status launch_mfma(const int8_t *xq, const float *s_x, const v4i *wfrag, const float *s_w, int64_t M,
-                       int64_t K, int64_t N, const float *bias, float *y, int32_t *acc_out, hipStream_t st) {
+                       int64_t K, int64_t N, const float *bias, float *y, int32_t *acc_out, uint32_t *y_absmax,
+                       hipStream_t st) {
   constexpr int BM = 64 * TM, BN = 64 * TN;
   auto kern = dense_fwd_mfma_kernel<TM, TN, SHIFT4, EPI>;
   const int tiles_m = static_cast<int>(cdiv(M, BM)), tiles_n = static_cast<int>(N / BN);
   kern<<<tiles_m * tiles_n, kThreads, 0, st>>>(xq, s_x, wfrag, s_w, static_cast<int>(M), static_cast<int>(K),
-                                               static_cast<int>(N), bias, y, acc_out, tiles_m, tiles_n);
+                                               static_cast<int>(N), bias, y, acc_out, y_absmax, tiles_m, tiles_n);
   AQT_HIP(hipGetLastError());
   return AQT_OK;
 }
@@ -335,11 +357,11 @@ aqt_status launch_mfma(const int8_t *xq, const float *s_x, const v4i *wfrag, con
 template <int TM, int TN, bool SHIFT4>
 aqt_status launch_mfma_epi(int epilogue, const int8_t *xq, const float *s_x, const v4i *wfrag, const float *s_w,
                            int64_t M, int64_t K, int64_t N, const float *bias, float *y, int32_t *acc_out,
-                           hipStream_t st) {
+                           uint32_t *y_absmax, hipStream_t st) {
   switch (epilogue) {
-    case AQT_EPI_NONE: return launch_mfma<TM, TN, SHIFT4, AQT_EPI_NONE>(xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, st);
-    case AQT_EPI_SWISH: return launch_mfma<TM, TN, SHIFT4, AQT_EPI_SWISH>(xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, st);
-    default: return launch_mfma<TM, TN, SHIFT4, AQT_EPI_GLU>(xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, st);
+    case AQT_EPI_NONE: return launch_mfma<TM, TN, SHIFT4, AQT_EPI_NONE>(xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, st);
+    case AQT_EPI_SWISH: return launch_mfma<TM, TN, SHIFT4, AQT_EPI_SWISH>(xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, st);
+    default: return launch_mfma<TM, TN, SHIFT4, AQT_EPI_GLU>(xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, st);
   }
 }
 
@@ -349,8 +371,12 @@ size_t fwd_q_workspace_bytes(int64_t K, int64_t N) { return align_up(static_cast
 
 aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq_packed, const float *s_w,
                               int64_t M, int64_t K, int64_t N, int bits_w, const float *bias, int epilogue,
-                              float *y, int32_t *acc_out, void *ws, hipStream_t st) {
+                              float *y, int32_t *acc_out, uint32_t *y_absmax, void *ws, hipStream_t st) {
   const bool packed = packed4(bits_w);
+  if (y_absmax) {
+    zero_word_kernel<<<1, 64, 0, st>>>(y_absmax);
+    AQT_HIP(hipGetLastError());
+  }
   const bool aligned = (reinterpret_cast<uintptr_t>(xq) % 16 == 0) &&
                        (reinterpret_cast<uintptr_t>(wq_packed) % 16 == 0) && ws &&
                        (reinterpret_cast<uintptr_t>(ws) % 16 == 0);
@@ -371,17 +397,17 @@ aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq
       AQT_HIP(hipGetLastError());
       const bool wide = (nn % unit_wide == 0) && cdiv(M, 128) * (N / 256) >= 512;
       if (wide) {
-        return packed ? launch_mfma_epi<2, 4, true>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, st)
-                      : launch_mfma_epi<2, 4, false>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, st);
+        return packed ? launch_mfma_epi<2, 4, true>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, st)
+                      : launch_mfma_epi<2, 4, false>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, st);
       }
-      return packed ? launch_mfma_epi<2, 2, true>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, st)
-                    : launch_mfma_epi<2, 2, false>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, st);
+      return packed ? launch_mfma_epi<2, 2, true>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, st)
+                    : launch_mfma_epi<2, 2, false>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, st);
     }
   }
   const int64_t ncols = (epilogue == AQT_EPI_GLU) ? N / 2 : N;
   dense_fwd_general_kernel<<<static_cast<int>(cdiv(M * ncols, kThreads)), kThreads, 0, st>>>(
       xq, s_x, static_cast<const uint8_t *>(wq_packed), s_w, M, K, N, packed ? 1 : 0, bias, epilogue, y,
-      acc_out);
+      acc_out, y_absmax);
   AQT_HIP(hipGetLastError());
   return AQT_OK;
 }

@@ -392,6 +392,29 @@ aqt_status launch_quantize(const float *x, int64_t rows, int64_t cols, int64_t l
   return launch_quantize_with_scale(x, rows, cols, ldx, bits, axis, scale, q, mask, st);
 }
 
+// Per tensor with the abs-max already known (its bit pattern in device memory): the
+// single word stands in for the array of per-block maxima, so this is pass 2 alone.
+aqt_status launch_quantize_with_absmax(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bits,
+                                       const uint32_t *absmax_bits, int8_t *q, float *scale, uint32_t *mask,
+                                       hipStream_t st, int32_t *dev_status) {
+  const int qmax = qmax_of(bits);
+  const int64_t n = rows * cols;
+  const bool flat = (ldx == cols) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) &&
+                    (reinterpret_cast<uintptr_t>(q) % 4 == 0);
+  if (flat && !mask) {
+    int g = grid_for(n / 4, kThreads * 4, 2048);
+    const int64_t per4 = cdiv(cdiv(n / 4, g), kThreads) * kThreads;
+    g = static_cast<int>(per4 > 0 ? cdiv(n / 4, per4) : 1);
+    if (g < 1) g = 1;
+    quantize_flat_kernel<<<g, kThreads, 0, st>>>(x, n, per4, absmax_bits, 1, qmax, q, scale, dev_status);
+    AQT_HIP(hipGetLastError());
+    return AQT_OK;
+  }
+  finish_scale_all_kernel<<<1, kThreads, 0, st>>>(absmax_bits, 1, qmax, scale, dev_status);
+  AQT_HIP(hipGetLastError());
+  return launch_quantize_with_scale(x, rows, cols, ldx, bits, AQT_AXIS_ALL, scale, q, mask, st);
+}
+
 aqt_status launch_quantize_with_scale(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bits,
                                       int axis, const float *scale, int8_t *q, uint32_t *mask,
                                       hipStream_t st) {

@@ -288,6 +288,72 @@ def test_argument_errors_on_device_buffers():
     assert e.value.status == B.AQT_ERR_WORKSPACE
 
 
+# ----------------------------------------------------------------------------
+# producer-side abs-max and the one-pass quantizer that consumes it
+# ----------------------------------------------------------------------------
+ABSMAX_CASES = [
+    # M, K, N, bits_w, epilogue, bias
+    (300, 128, 256, 4, 1, True),        # tuned kernel, ragged M (shifted tile recomputes rows), Swish
+    (200, 256, 512, 8, 2, True),        # tuned kernel, GLU: the maximum is over the gated outputs
+    (4100, 384, 384, 4, 0, False),      # several tiles, the output spans more than one quantizer block
+    (37, 50, 23, 4, 1, True),           # general kernel
+    (1, 1, 1, 8, 0, False),
+]
+
+
+@pytest.mark.parametrize("M,K,N,bw,epi,with_bias", ABSMAX_CASES)
+def test_fused_absmax_feeds_one_pass_quantizer(M, K, N, bw, epi, with_bias):
+    say("fused absmax", M, K, N, bw, epi, with_bias)
+    c = inputs.small_case(77 + M + N, M, K, N, 8, bw, epi, with_bias=with_bias, with_dy=False)
+    bias = None if c.bias is None else dev(c.bias)
+    xq, s_x, _ = B.aqt_quantize(dev(c.x), 8, B.AQT_AXIS_ALL)
+    wq, s_w, _, _ = B.aqt_quantize_weights(dev(c.w), bw)
+    y_ref, _ = B.aqt_dense_fwd_q(xq, s_x, wq, s_w, N, 8, bw, bias=bias, epilogue=epi)
+    y, m = B.aqt_dense_fwd_q_absmax(xq, s_x, wq, s_w, N, 8, bw, bias=bias, epilogue=epi)
+    y_h = host(y)
+    np.testing.assert_array_equal(y_h, host(y_ref))                 # same outputs as the plain entry point
+    assert host(m)[0] == np.abs(y_h).max()                          # the definition, on the very buffer written
+    # the next layer's quantizer: one pass with the known maximum == the oracle on the same float32 buffer
+    for bits in (8, 4):
+        status = B.new_status()
+        q, s, mask = B.aqt_quantize_with_absmax(y, bits, m, want_mask=(M * N < 100000), dev_status=status)
+        q_ref, s_ref = oracle.quantize(y_h, bits, oracle.AXIS_ALL)
+        np.testing.assert_array_equal(host(s), s_ref)
+        np.testing.assert_array_equal(host(q), q_ref)
+        assert host(status)[0] == 0
+        q2, s2, _ = B.aqt_quantize(y, bits, B.AQT_AXIS_ALL)
+        np.testing.assert_array_equal(host(q2), host(q))
+        np.testing.assert_array_equal(host(s2), host(s))
+        if mask is not None:
+            assert unpack_mask(host(mask), M * N).all() or s_ref[0] == 0
+
+
+def test_quantize_with_absmax_edge_cases():
+    say("quantize with absmax edge cases")
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((33, 65)).astype(np.float32)
+    x_d = dev(x)
+    # a maximum that is too small saturates; codes and mask follow the external-scale oracle
+    m_small = np.float32(np.abs(x).max() / 2)
+    status = B.new_status()
+    q, s, mask = B.aqt_quantize_with_absmax(x_d, 8, dev(np.array([m_small], np.float32)), want_mask=True,
+                                            dev_status=status)
+    s_ref = np.array([m_small / np.float32(127)], np.float32)
+    q_ref, mask_ref = oracle.quantize_with_scale(x, 8, oracle.AXIS_ALL, s_ref)
+    np.testing.assert_array_equal(host(s), s_ref)
+    np.testing.assert_array_equal(host(q), q_ref)
+    np.testing.assert_array_equal(unpack_mask(host(mask), x.size), mask_ref.reshape(-1))
+    assert host(status)[0] == 0 and (mask_ref == 0).any()
+    # zero maximum: scale 0, codes 0
+    q, s, _ = B.aqt_quantize_with_absmax(x_d, 8, dev(np.zeros(1, np.float32)))
+    assert host(s)[0] == 0 and not host(q).any()
+    # non-finite and negative maxima are reported
+    for bad in (np.inf, np.nan, -1.0):
+        status = B.new_status()
+        B.aqt_quantize_with_absmax(x_d, 8, dev(np.array([bad], np.float32)), dev_status=status)
+        assert host(status)[0] == B.AQT_ERR_NONFINITE
+
+
 # 128 x 256 tiles are used once there are at least 512 of them
 WIDE_TILE_CASES = [
     # M, K, N, bits_x, bits_w, epilogue
@@ -373,3 +439,21 @@ def test_training_step_full_size():
     for c in inputs.config5():
         run_full_size_case(c, backward=True)
         torch.cuda.empty_cache()
+
+
+def test_fused_absmax_full_size_chain():
+    # layer 1 of the training-step configuration with a Swish epilogue, its output quantized
+    # for layer 2 in one pass: the launch configuration the benchmark's extra figures time
+    c = inputs.config5()[0]
+    say("fused absmax full size", c.M, c.K, c.N)
+    xq, s_x, _ = B.aqt_quantize(dev(c.x), 8, B.AQT_AXIS_ALL)
+    wq, s_w, _, _ = B.aqt_quantize_weights(dev(c.w), 4)
+    y, m = B.aqt_dense_fwd_q_absmax(xq, s_x, wq, s_w, c.N, 8, 4, epilogue=B.AQT_EPI_SWISH)
+    status = B.new_status()
+    q, s, _ = B.aqt_quantize_with_absmax(y, 8, m, dev_status=status)
+    y_h = host(y)
+    assert host(m)[0] == np.abs(y_h).max()
+    q_ref, s_ref = oracle.quantize(y_h, 8, oracle.AXIS_ALL)
+    np.testing.assert_array_equal(host(s), s_ref)
+    np.testing.assert_array_equal(host(q), q_ref)
+    assert host(status)[0] == 0
