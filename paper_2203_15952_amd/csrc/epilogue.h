@@ -5,11 +5,17 @@
 
 namespace aqt {
 
-// Logistic function evaluated on the side where exp cannot overflow.
+// Logistic function.  One exp, of -|v| so that it cannot overflow, and one reciprocal
+// of d = 1 + e, which lies in [1, 2]: the hardware estimate (1 ulp) plus one Newton
+// step is within half an ulp there and needs none of the scaling an IEEE divide
+// does.  Both signs take the same instructions, so mixed-sign wavefronts do not
+// pay for two branches.  Total error stays under 4e-7 relative.
 __device__ __forceinline__ float sigmoid_f32(float v) {
-  if (v >= 0.0f) return 1.0f / (1.0f + expf(-v));
-  const float e = expf(v);
-  return e / (1.0f + e);
+  const float e = expf(-fabsf(v));
+  const float d = 1.0f + e;
+  float r = __builtin_amdgcn_rcpf(d);
+  r = fmaf(fmaf(-d, r, 1.0f), r, r);
+  return (v >= 0.0f) ? r : e * r;
 }
 
 __device__ __forceinline__ float swish_f32(float v) { return v * sigmoid_f32(v); }
