@@ -157,6 +157,13 @@ def main():
                                                                                          dev_status=status)),
             "tensor": [c1.M, c1.N],
         }
+        # the training forward as ONE call (quantize x, quantize + pack w, contraction), per layer;
+        # layer 2 runs on the Swish output written above, which is what a chained block feeds it
+        ws_fused = [B.workspace(B.aqt_workspace_bytes(B.AQT_OP_DENSE_FWD, L["c"].M, L["c"].K, L["c"].N)) for L in layers]
+        fused["dense_fwd_one_call_ms"] = [
+            timed(lambda L=L, w=w: B.aqt_dense_fwd(L["x"], L["w"], L["c"].bits_x, L["c"].bits_w, y=L["y"], saved=L["sv"],
+                                                   ws=w, dev_status=status))
+            for L, w in zip(layers, ws_fused)]
         by = 5.0 * c1.M * c1.N
         fused["quantize_one_pass_gbs"] = by / fused["quantize_one_pass_known_absmax_ms"] / 1e6
         fused["quantize_one_pass_hbm_frac"] = fused["quantize_one_pass_gbs"] / PEAK_HBM_GBS

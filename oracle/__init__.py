@@ -128,6 +128,38 @@ def dense_fwd_q(xq, s_x, wq_kn, s_w, bias=None, epilogue: int = EPI_NONE):
     return dict(acc=acc, y=y, pre=pre)
 
 
+def dense_fwd_wonly(x, wq_kn, s_w, bias=None, epilogue: int = EPI_NONE):
+    """Weight-only forward (float32 activations x de-quantized integer weights).
+    Returns dict(y f64, pre f64, mag f64)."""
+    x, wq_kn, s_w = _f32(x), _i8(wq_kn), _f32(s_w)
+    M, K = x.shape
+    K2, N = wq_kn.shape
+    assert K == K2 and s_w.size == N
+    bias = None if bias is None else _f32(bias)
+    y = np.empty((M, _out_cols(N, epilogue)), np.float64)
+    pre = np.empty((M, N), np.float64)
+    mag = np.empty((M, N), np.float64)
+    rc = _c().oracle_dense_fwd_wonly(_p(x), _p(wq_kn), _p(s_w), ctypes.c_int64(M), ctypes.c_int64(K),
+                                     ctypes.c_int64(N), _p(bias), epilogue, _p(y), _p(pre), _p(mag))
+    if rc:
+        raise ValueError(f"oracle_dense_fwd_wonly rc={rc}")
+    return dict(y=y, pre=pre, mag=mag)
+
+
+def dense_fwd_wonly_sampled(x, wq_kn, s_w, idx_m, idx_n, bias=None):
+    """Weight-only pre-activation values and term magnitudes at sampled positions."""
+    x, wq_kn, s_w = _f32(x), _i8(wq_kn), _f32(s_w)
+    K, N = wq_kn.shape
+    bias = None if bias is None else _f32(bias)
+    im = np.ascontiguousarray(idx_m, np.int64)
+    inn = np.ascontiguousarray(idx_n, np.int64)
+    pre = np.empty(im.size, np.float64)
+    mag = np.empty(im.size, np.float64)
+    _c().oracle_dense_fwd_wonly_sampled(_p(x), _p(wq_kn), _p(s_w), ctypes.c_int64(K), ctypes.c_int64(N),
+                                        _p(bias), _p(im), _p(inn), ctypes.c_int64(im.size), _p(pre), _p(mag))
+    return pre, mag
+
+
 def dense_fwd(x, w, bits_x: int, bits_w: int, bias=None, epilogue: int = EPI_NONE):
     """Whole forward layer.  Returns dict(xq, s_x, wq, s_w, acc, y, pre)."""
     x, w = _f32(x), _f32(w)

@@ -16,6 +16,8 @@
  *   oracle_dense_fwd*     Sec. 1 and Sec. 2.2: quantize both operands, multiply
  *                         as integers, de-quantize by multiplying with the
  *                         scales.
+ *   oracle_dense_fwd_wonly*  Sec. 4.1, configurations I8W / I4W: integer weights
+ *                         de-quantized to float32, float32 activations.
  *   oracle_dense_bwd      Fig. 2's stop_gradient on the scale; the rounding is
  *                         passed straight through (the paper does not state it,
  *                         straight-through is the standard reading of QAT).
@@ -31,7 +33,10 @@
  * integer-valued special case against an int64 library matmul, power-of-two
  * equivariance, an independent binary32-emulating brute force, the method's
  * error bound against the float product, gradients against a library float64
- * matmul of the de-quantized operands, hand-packed bytes).  The paper prints
+ * matmul of the de-quantized operands, hand-packed bytes; the weight-only forward
+ * by a hand-worked example, one-hot activations, agreement with the integer path
+ * on activations that are exact multiples of a power-of-two scale, and the
+ * half-step bound against the float product).  The paper prints
  * no worked numeric example, so no pin comes from printed values.
  */
 #include <math.h>
@@ -211,6 +216,70 @@ int oracle_dense_fwd_q(const int8_t *xq, float s_x, const int8_t *wq_kn, const f
     free(v);
   }
   return overflow ? 3 : 0;
+}
+
+/*
+ * Weight-only modes (Sec. 4.1, configurations I8W / I4W: integer weights, float32
+ * activations; the weights are converted back to float for the product).
+ * x [M,K] float32, wq_kn [K,N] codes, s_w [N], bias nullable [N].
+ * The de-quantized weight is the float32 number w^[k,n] = s_w[n] * (float)wq[k,n]
+ * (one float32 rounding, as a float32 graph would hold it); the product with x is
+ * then evaluated in double, so what is returned is the exact value a float32
+ * matmul of x and w^ approximates.  y [M,N] doubles ([M,N/2] for GLU), pre
+ * (nullable) [M,N] the value before the activation, mag (nullable) [M,N] the sum of
+ * the magnitudes of the terms, the yardstick for a float contraction.
+ */
+int oracle_dense_fwd_wonly(const float *x, const int8_t *wq_kn, const float *s_w,
+                           int64_t M, int64_t K, int64_t N, const float *bias, int epilogue,
+                           double *y, double *pre, double *mag) {
+  if (epilogue == ORACLE_EPI_GLU && (N % 2)) return 2;
+#pragma omp parallel for schedule(static)
+  for (int64_t m = 0; m < M; ++m) {
+    double *v = (double *)malloc((size_t)N * sizeof(double));
+    for (int64_t n = 0; n < N; ++n) {
+      double s = 0.0, sa = 0.0;
+      for (int64_t k = 0; k < K; ++k) {
+        const float wdq = s_w[n] * (float)wq_kn[k * N + n];   /* one binary32 rounding */
+        double t = (double)x[m * K + k] * (double)wdq;
+        s += t;
+        sa += fabs(t);
+      }
+      if (bias) s += (double)bias[n];
+      v[n] = s;
+      if (pre) pre[m * N + n] = s;
+      if (mag) mag[m * N + n] = sa + (bias ? fabs((double)bias[n]) : 0.0);
+    }
+    if (epilogue == ORACLE_EPI_NONE) {
+      for (int64_t n = 0; n < N; ++n) y[m * N + n] = v[n];
+    } else if (epilogue == ORACLE_EPI_SWISH) {
+      for (int64_t n = 0; n < N; ++n) y[m * N + n] = v[n] * sigmoid64(v[n]);
+    } else {
+      const int64_t h = N / 2;
+      for (int64_t j = 0; j < h; ++j) y[m * h + j] = v[j] * sigmoid64(v[j + h]);
+    }
+    free(v);
+  }
+  return 0;
+}
+
+void oracle_dense_fwd_wonly_sampled(const float *x, const int8_t *wq_kn, const float *s_w,
+                                    int64_t K, int64_t N, const float *bias,
+                                    const int64_t *idx_m, const int64_t *idx_n, int64_t count,
+                                    double *pre, double *mag) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < count; ++i) {
+    int64_t m = idx_m[i], n = idx_n[i];
+    double s = 0.0, sa = 0.0;
+    for (int64_t k = 0; k < K; ++k) {
+      const float wdq = s_w[n] * (float)wq_kn[k * N + n];
+      double t = (double)x[m * K + k] * (double)wdq;
+      s += t;
+      sa += fabs(t);
+    }
+    if (bias) s += (double)bias[n];
+    pre[i] = s;
+    mag[i] = sa + (bias ? fabs((double)bias[n]) : 0.0);
+  }
 }
 
 /*

@@ -7,6 +7,8 @@ by multiplying with the scale, no zero point), Sec. 1 (integer matmul; training
 forward equals serving forward), Table 1 (model sizes => half a byte per int4
 parameter).
 """
+import math
+
 import numpy as np
 import pytest
 from scipy.special import expit
@@ -446,3 +448,90 @@ def test_sampled_variants_against_library_matmul():
     xh = xq.astype(np.float64) * float(s_x)
     np.testing.assert_allclose(dw, (xh.T @ dy.astype(np.float64))[ik, inn], rtol=1e-11, atol=1e-15)
     np.testing.assert_allclose(dwa, (np.abs(xh).T @ np.abs(dy.astype(np.float64)))[ik, inn], rtol=1e-11)
+
+
+# ----------------------------------------------------------------------------
+# Weight-only modes (Sec. 4.1: I8W / I4W, integer weights x float32 activations)
+# ----------------------------------------------------------------------------
+def test_weight_only_hand_worked_example():
+    # w^ = s_w * wq = [[0.5, -0.5], [1.5, 0], [-3.5, 1.25]]
+    x = np.array([[1, 2, -1], [0.5, 0, 4]], F)
+    wq = np.array([[1, -2], [3, 0], [-7, 5]], np.int8)
+    s_w = np.array([0.5, 0.25], F)
+    bias = np.array([1, -1], F)
+    r = oracle.dense_fwd_wonly(x, wq, s_w)
+    np.testing.assert_array_equal(r["pre"], [[7.0, -1.75], [-13.75, 4.75]])
+    np.testing.assert_array_equal(r["y"], r["pre"])
+    np.testing.assert_array_equal(r["mag"], [[7.0, 1.75], [14.25, 5.25]])
+    r = oracle.dense_fwd_wonly(x, wq, s_w, bias)
+    np.testing.assert_array_equal(r["pre"], [[8.0, -2.75], [-12.75, 3.75]])
+    np.testing.assert_array_equal(r["mag"], [[8.0, 2.75], [15.25, 6.25]])
+    r = oracle.dense_fwd_wonly(x, wq, s_w, bias, oracle.EPI_SWISH)
+    assert r["y"][0, 0] == pytest.approx(8.0 / (1.0 + math.exp(-8.0)), rel=1e-15)
+    assert r["y"][1, 0] == pytest.approx(-12.75 / (1.0 + math.exp(12.75)), rel=1e-15)
+    r = oracle.dense_fwd_wonly(x, wq, s_w, bias, oracle.EPI_GLU)      # value = channel 0, gate = channel 1
+    assert r["y"].shape == (2, 1)
+    assert r["y"][0, 0] == pytest.approx(8.0 / (1.0 + math.exp(2.75)), rel=1e-15)
+    assert r["y"][1, 0] == pytest.approx(-12.75 / (1.0 + math.exp(-3.75)), rel=1e-15)
+
+
+def test_weight_only_one_hot_rows_read_out_the_dequantized_weight():
+    # x = identity: row k of the output is row k of w^ = the float32 product s_w[n] * wq[k,n];
+    # a transposed operand or a scale indexed by the wrong axis cannot pass
+    rng = np.random.default_rng(21)
+    K, N = 7, 5
+    wq = rng.integers(-7, 8, (K, N)).astype(np.int8)
+    s_w = rng.uniform(0.01, 0.3, N).astype(F)
+    r = oracle.dense_fwd_wonly(np.eye(K, dtype=F), wq, s_w)
+    expect = (s_w[None, :] * wq.astype(F)).astype(np.float64)       # one float32 rounding per weight
+    np.testing.assert_array_equal(r["pre"], expect)
+    np.testing.assert_array_equal(r["mag"], np.abs(expect))
+    # zero activations leave the bias
+    bias = rng.standard_normal(N).astype(F)
+    r = oracle.dense_fwd_wonly(np.zeros((3, K), F), wq, s_w, bias)
+    np.testing.assert_array_equal(r["pre"], np.broadcast_to(bias.astype(np.float64), (3, N)))
+
+
+def test_weight_only_agrees_with_the_integer_path_on_exactly_representable_activations():
+    # When x is itself s_x * xq with power-of-two scales everywhere, nothing rounds in either
+    # function and the two separately written contractions must give the same numbers.
+    rng = np.random.default_rng(22)
+    M, K, N = 11, 40, 9
+    xq = rng.integers(-127, 128, (M, K)).astype(np.int8)
+    wq = rng.integers(-7, 8, (K, N)).astype(np.int8)
+    s_x = F(2.0 ** -5)
+    s_w = (2.0 ** rng.integers(-6, 0, N)).astype(F)
+    bias = rng.standard_normal(N).astype(F)
+    x = (xq.astype(F) * s_x).astype(F)
+    for epi in (oracle.EPI_NONE, oracle.EPI_SWISH, oracle.EPI_GLU) if N % 2 == 0 else (oracle.EPI_NONE, oracle.EPI_SWISH):
+        a = oracle.dense_fwd_wonly(x, wq, s_w, bias, epi)
+        b = oracle.dense_fwd_q(xq, s_x, wq, s_w, bias, epi)
+        np.testing.assert_allclose(a["pre"], b["pre"], rtol=1e-14, atol=0)
+        np.testing.assert_allclose(a["y"], b["y"], rtol=1e-13, atol=0)
+    # general scales: the only difference is the float32 rounding of each de-quantized weight
+    s_w2 = rng.uniform(0.01, 0.2, N).astype(F)
+    a = oracle.dense_fwd_wonly(x, wq, s_w2)
+    b = oracle.dense_fwd_q(xq, s_x, wq, s_w2)
+    assert (np.abs(a["pre"] - b["pre"]) <= 2.0 ** -24 * a["mag"]).all()
+    assert (a["pre"] != b["pre"]).any()
+
+
+def test_weight_only_half_step_bound_and_sampled_variant():
+    # Per weight |w - w^| <= s_w / 2 (abs-max scaling never clips), so the weight-only output is
+    # within sum_k |x| * s_w[n] / 2 of the float product; int8 weights are 18 times closer than int4.
+    c = inputs.small_case(23, 20, 48, 12, 8, 4, with_dy=False)
+    x64, w64 = c.x.astype(np.float64), c.w.astype(np.float64)
+    errs = {}
+    for bits in (8, 4):
+        wq, s_w = oracle.quantize(c.w, bits, 0)
+        r = oracle.dense_fwd_wonly(c.x, wq, s_w)
+        err = np.abs(r["pre"] - x64 @ w64)
+        bound = np.abs(x64).sum(axis=1)[:, None] * (s_w.astype(np.float64) / 2)[None, :]
+        assert (err <= bound * (1 + 1e-6)).all()
+        errs[bits] = err.mean()
+        rng = np.random.default_rng(bits)
+        im, inn = rng.integers(0, c.M, 30), rng.integers(0, c.N, 30)
+        pre, mag = oracle.dense_fwd_wonly_sampled(c.x, wq, s_w, im, inn)
+        np.testing.assert_array_equal(pre, r["pre"][im, inn])
+        np.testing.assert_array_equal(mag, r["mag"][im, inn])
+    assert errs[8] < errs[4] / 8
