@@ -164,6 +164,14 @@ def main():
             timed(lambda L=L, w=w: B.aqt_dense_fwd(L["x"], L["w"], L["c"].bits_x, L["c"].bits_w, y=L["y"], saved=L["sv"],
                                                    ws=w, dev_status=status))
             for L, w in zip(layers, ws_fused)]
+        # weight-only modes (float32 activations x int4 weights) on both layer shapes; the
+        # contraction is two bf16 MFMA passes over a hi/lo split of x
+        ws_wo = [B.workspace(B.aqt_workspace_bytes(B.AQT_OP_DENSE_FWD_WONLY, L["c"].M, L["c"].K, L["c"].N)) for L in layers]
+        wo_ms = [timed(lambda L=L, w=w: B.aqt_dense_fwd_wonly(L["x"], L["sv"].wq_packed, L["sv"].s_w, L["c"].N,
+                                                              L["c"].bits_w, y=L["y"], ws=w))
+                 for L, w in zip(layers, ws_wo)]
+        fused["weight_only_fwd_ms"] = wo_ms
+        fused["weight_only_fwd_tflops"] = [2.0 * L["c"].M * L["c"].K * L["c"].N / ms / 1e9 for L, ms in zip(layers, wo_ms)]
         by = 5.0 * c1.M * c1.N
         fused["quantize_one_pass_gbs"] = by / fused["quantize_one_pass_known_absmax_ms"] / 1e6
         fused["quantize_one_pass_hbm_frac"] = fused["quantize_one_pass_gbs"] / PEAK_HBM_GBS
@@ -279,7 +287,7 @@ def main():
         "roofline": roof,
         "cpu_baseline": cpu,
         "kernels": kernels,
-        "fused_producer_absmax": fused,
+        "extras": fused,
     }
     print(json.dumps(out))
 

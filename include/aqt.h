@@ -62,6 +62,7 @@ typedef int aqt_status;
 #define AQT_OP_DENSE_FWD 2
 #define AQT_OP_DENSE_FWD_Q 3
 #define AQT_OP_DENSE_BWD 4
+#define AQT_OP_DENSE_FWD_WONLY 5
 
 /* What the forward keeps for the backward.  All caller-owned device buffers. */
 typedef struct aqt_saved {
@@ -178,6 +179,21 @@ aqt_status aqt_dense_fwd_q_absmax(const int8_t *xq, const float *s_x, const void
 aqt_status aqt_quantize_with_absmax(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bits,
                                     const float *absmax, int8_t *q, float *scale, uint32_t *clip_mask,
                                     void *stream, int32_t *dev_status);
+
+/*
+ * Weight-only modes (Sec. 4.1, configurations I8W and I4W: integer weights,
+ * float32 activations; the weights are turned back into floats for the product):
+ *   v[m,n] = (sum_k x[m,k] * wq[k,n]) * s_w[n] (+ bias[n]);  y = v | swish(v) | glu(v)
+ *   x [M,K] float32; wq_packed, s_w as produced by aqt_quantize_weights; y float32
+ *   [M,N] ([M,N/2] for GLU).
+ * A float contraction: x is split into two bf16 terms (16 significant bits), the codes
+ * are exact in bf16, accumulation is float32; every output lies within 1e-4 of the
+ * sum of the magnitudes of its terms from the exact value (typically 1e-6).
+ * Needs aqt_workspace_bytes(AQT_OP_DENSE_FWD_WONLY, ., K, N, ., .) of workspace.
+ */
+aqt_status aqt_dense_fwd_wonly(const float *x, const void *wq_packed, const float *s_w, int64_t M, int64_t K,
+                               int64_t N, int bits_w, const float *bias, int epilogue, float *y, void *ws,
+                               size_t ws_bytes, void *stream);
 
 /*
  * The training forward: quantizes x per tensor and w per output channel inside

@@ -19,13 +19,13 @@ LIB_PATH = os.path.join(_PKG, "libaqt.so")
 AQT_OK, AQT_ERR_INVALID_ARG, AQT_ERR_UNSUPPORTED, AQT_ERR_WORKSPACE, AQT_ERR_HIP, AQT_ERR_NONFINITE = range(6)
 AQT_AXIS_ALL, AQT_AXIS_ROWS, AQT_AXIS_COLS = -1, 0, 1
 AQT_EPI_NONE, AQT_EPI_SWISH, AQT_EPI_GLU = 0, 1, 2
-AQT_OP_QUANTIZE, AQT_OP_QUANTIZE_WEIGHTS, AQT_OP_DENSE_FWD, AQT_OP_DENSE_FWD_Q, AQT_OP_DENSE_BWD = range(5)
+AQT_OP_QUANTIZE, AQT_OP_QUANTIZE_WEIGHTS, AQT_OP_DENSE_FWD, AQT_OP_DENSE_FWD_Q, AQT_OP_DENSE_BWD, AQT_OP_DENSE_FWD_WONLY = range(6)
 
 # every symbol include/aqt.h declares
 SYMBOLS = ["aqt_status_string", "aqt_last_hip_error", "aqt_version", "aqt_workspace_bytes",
            "aqt_packed_weight_bytes", "aqt_quantize", "aqt_quantize_with_scale", "aqt_quantize_weights",
            "aqt_unpack_weights", "aqt_dense_fwd_q", "aqt_dense_fwd_q_absmax", "aqt_quantize_with_absmax",
-           "aqt_dense_fwd", "aqt_dense_bwd"]
+           "aqt_dense_fwd_wonly", "aqt_dense_fwd", "aqt_dense_bwd"]
 
 
 class AqtError(RuntimeError):
@@ -72,6 +72,7 @@ def lib() -> ctypes.CDLL:
         L.aqt_dense_fwd_q_absmax.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp,
                                              _vp, _vp, _sz, _vp]
         L.aqt_quantize_with_absmax.argtypes = [_vp, _i64, _i64, _i64, _int, _vp, _vp, _vp, _vp, _vp, _vp]
+        L.aqt_dense_fwd_wonly.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _int, _vp, _int, _vp, _vp, _sz, _vp]
         L.aqt_dense_fwd.argtypes = [_vp, _vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp,
                                     ctypes.POINTER(aqt_saved), _vp, _sz, _vp, _vp]
         L.aqt_dense_bwd.argtypes = [_vp, ctypes.POINTER(aqt_saved), _i64, _i64, _i64, _int, _int, _vp, _vp, _vp,
@@ -230,6 +231,20 @@ def aqt_quantize_with_absmax(x, bits: int, absmax, *, q=None, scale=None, clip_m
                                         _ptr(clip_mask), _stream(), _ptr(dev_status))
     _check(st, "aqt_quantize_with_absmax")
     return q, scale, clip_mask
+
+
+def aqt_dense_fwd_wonly(x, wq_packed, s_w, N: int, bits_w: int, *, bias=None, epilogue: int = AQT_EPI_NONE,
+                        y=None, ws=None):
+    """aqt_dense_fwd_wonly: float32 activations x integer weights; returns y float32."""
+    _dev(x, torch.float32, "x")
+    M, K = x.shape
+    if ws is None:
+        ws = workspace(aqt_workspace_bytes(AQT_OP_DENSE_FWD_WONLY, M, K, N, 8, bits_w))
+    y = torch.empty((M, _out_cols(N, epilogue)), dtype=torch.float32, device=x.device) if y is None else y
+    st = lib().aqt_dense_fwd_wonly(_ptr(x), _ptr(wq_packed), _ptr(s_w), M, K, N, bits_w, _ptr(bias), epilogue,
+                                   _ptr(y), _ptr(ws), ws.numel(), _stream())
+    _check(st, "aqt_dense_fwd_wonly")
+    return y
 
 
 class Saved:

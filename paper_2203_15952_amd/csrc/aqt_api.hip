@@ -80,6 +80,7 @@ size_t aqt_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int bits_x, 
   switch (op) {
     case AQT_OP_QUANTIZE: return kMaxPartials * sizeof(float);
     case AQT_OP_QUANTIZE_WEIGHTS: return N >= 1 ? weight_ws_bytes(N) : 0;
+    case AQT_OP_DENSE_FWD_WONLY: return (K >= 1 && N >= 1) ? fwd_wonly_workspace_bytes(K, N) : 0;
     case AQT_OP_DENSE_FWD_Q: return (K >= 1 && N >= 1) ? fwd_q_workspace_bytes(K, N) : 0;
     case AQT_OP_DENSE_FWD:
       if (!shape_ok(M, K) || N < 1 || !bits_ok(bits_w)) return 0;
@@ -153,6 +154,18 @@ aqt_status aqt_dense_fwd_q_absmax(const int8_t *xq, const float *s_x, const void
   if (!ws || ws_bytes < fwd_q_workspace_bytes(K, N)) return AQT_ERR_WORKSPACE;
   return launch_dense_fwd_q(xq, s_x, wq_packed, s_w, M, K, N, bits_w, bias, epilogue, y, nullptr,
                             reinterpret_cast<uint32_t *>(y_absmax), ws, static_cast<hipStream_t>(stream));
+}
+
+aqt_status aqt_dense_fwd_wonly(const float *x, const void *wq_packed, const float *s_w, int64_t M, int64_t K,
+                               int64_t N, int bits_w, const float *bias, int epilogue, float *y, void *ws,
+                               size_t ws_bytes, void *stream) {
+  if (!x || !wq_packed || !s_w || !y || !shape_ok(M, K) || N < 1) return AQT_ERR_INVALID_ARG;
+  if (epilogue != AQT_EPI_NONE && epilogue != AQT_EPI_SWISH && epilogue != AQT_EPI_GLU) return AQT_ERR_INVALID_ARG;
+  if (!bits_ok(bits_w)) return AQT_ERR_UNSUPPORTED;
+  if (epilogue == AQT_EPI_GLU && (N % 2)) return AQT_ERR_UNSUPPORTED;
+  if (!ws || ws_bytes < fwd_wonly_workspace_bytes(K, N)) return AQT_ERR_WORKSPACE;
+  return launch_dense_fwd_wonly(x, wq_packed, s_w, M, K, N, bits_w, bias, epilogue, y, ws,
+                                static_cast<hipStream_t>(stream));
 }
 
 aqt_status aqt_quantize_with_absmax(const float *x, int64_t rows, int64_t cols, int64_t ldx, int bits,

@@ -13,9 +13,14 @@
 // v_mfma_f32_32x32x16_bf16 passes accumulate code*hi + code*lo in float32.
 // Every product is exact in float32, so the only other error is the float32
 // accumulation itself.
+//
+// The weight-only forward (Sec. 4.1, configurations I8W / I4W: float32
+// activations, integer weights) is the same kind of contraction and runs on the
+// dX tile program:  y = act((x . wq) * s_w + bias).
 #include <type_traits>
 
 #include "aqt_internal.h"
+#include "epilogue.h"
 
 namespace aqt {
 namespace {
@@ -113,8 +118,10 @@ __global__ __launch_bounds__(kThreads) void bwd_dbias_fold_kernel(const double *
 // 16*ks + 8*lk .. +7 of row 32*jb + lr, i.e. exactly what that lane feeds to
 // v_mfma_f32_32x32x16_bf16.  A fragment is 1 KB, fragments are ordered
 // [jb][ks], so a wavefront fetches one with a single fully coalesced 16-byte-per-lane load.
+// With `packed` the input rows hold two int4 codes per byte (low nibble first), the
+// layout of the forward weight operand for bits_w <= 4.
 __global__ __launch_bounds__(kThreads) void codes_to_bf16_frag_kernel(const int8_t *__restrict__ codes, int K,
-                                                                      int N, v4i *__restrict__ out) {
+                                                                      int N, int packed, v4i *__restrict__ out) {
   const int64_t pieces = static_cast<int64_t>(K) * (N / 8);   // one 16-byte piece per (row, 8 channels)
   const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
   const int ksteps = N / 16;
@@ -124,12 +131,18 @@ __global__ __launch_bounds__(kThreads) void codes_to_bf16_frag_kernel(const int8
     const int64_t frag = i >> 6;
     const int ks = static_cast<int>(frag % ksteps), jb = static_cast<int>(frag / ksteps);
     const int k = 32 * jb + (lane & 31), n = 16 * ks + 8 * (lane >> 5);
-    const v2i c = *reinterpret_cast<const v2i *>(codes + static_cast<int64_t>(k) * N + n);
     float f[8];
+    if (packed) {
+      const uint32_t w = *reinterpret_cast<const uint32_t *>(codes + static_cast<int64_t>(k) * (N >> 1) + (n >> 1));
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      f[e] = static_cast<float>(static_cast<int8_t>(static_cast<uint32_t>(c.x) >> (8 * e)));
-      f[4 + e] = static_cast<float>(static_cast<int8_t>(static_cast<uint32_t>(c.y) >> (8 * e)));
+      for (int e = 0; e < 8; ++e) f[e] = static_cast<float>(static_cast<int>(w << (28 - 4 * e)) >> 28);
+    } else {
+      const v2i c = *reinterpret_cast<const v2i *>(codes + static_cast<int64_t>(k) * N + n);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        f[e] = static_cast<float>(static_cast<int8_t>(static_cast<uint32_t>(c.x) >> (8 * e)));
+        f[4 + e] = static_cast<float>(static_cast<int8_t>(static_cast<uint32_t>(c.y) >> (8 * e)));
+      }
     }
     v4i o;
     o.x = pack_bf16(f[0], f[1]); o.y = pack_bf16(f[2], f[3]);
@@ -183,11 +196,22 @@ constexpr int waitcnt_imm(int vm, int lgkm) {
   return (vm & 0xF) | ((vm >> 4) << 14) | (7 << 4) | ((lgkm & 0xF) << 8);
 }
 
-template <int TM, int TN, bool MASKED>
-__global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
+// The same tile program serves the weight-only forward (integer weights, float32
+// activations): there the float operand is x, the contraction runs over the fan-in,
+// the codes are the forward weight operand, nothing is scaled on the way in, and the
+// epilogue applies the per-channel scale, the bias and the activation.
+//   MODE 0 / 1 : dX without / with a clip mask
+//   MODE 2 + e : weight-only forward with epilogue e (none, Swish, GLU)
+// Names follow dX: `dy` is the float operand [M,N], N the contraction length, K the
+// number of output columns (for GLU: value and gate channels together).
+template <int TM, int TN, int MODE>
+__device__ __forceinline__ void f32_codes_tile(
     const float *__restrict__ dy, const v4i *__restrict__ wq_frag, const float *__restrict__ s_w,
-    const float *__restrict__ s_x, const uint32_t *__restrict__ mask_x, int M, int K, int N,
-    float *__restrict__ dx, int tiles_m, int tiles_c) {
+    const float *__restrict__ s_x, const uint32_t *__restrict__ mask_x, const float *__restrict__ bias, int M,
+    int K, int N, float *__restrict__ dx, int tiles_m, int tiles_c) {
+  constexpr bool MASKED = (MODE == 1);
+  constexpr bool WONLY = (MODE >= 2);
+  constexpr int EPI = WONLY ? MODE - 2 : AQT_EPI_NONE;
   constexpr int BM = 64 * TM, BC = 64 * TN;
   constexpr int kABytes = 2 * BM * kRowB;  // dy hi image, then dy lo image
   constexpr int NA = 2 * TM;               // float4 of dy per thread per stage
@@ -208,7 +232,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
   const int lr = lane & 31, lk = lane >> 5;
 
   float4 ra[2][NA];
-  float4 rs;
+  float4 rs = {1.0f, 1.0f, 1.0f, 1.0f};
 
   // dy: a tile-uniform base (moves with the stage) plus small per-thread byte
   // offsets that stay fixed, so the loads can use scalar-base addressing.
@@ -225,10 +249,21 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
   // codes: fragment (jb, ks) starts at ((jb * N/16) + ks) * 64 pieces of 16 bytes;
   // this wavefront's column j-block is jb0 + j, a stage covers ks = 2*stage, 2*stage + 1.
   const int ksteps = N / 16;
-  const v4i *b_lane = wq_frag + (static_cast<int64_t>(c0 / 32 + wn * TN) * ksteps) * 64 + lane;
   const int b_jstep = ksteps * 64;
+  // First output channel of this wavefront's column block j.  A GLU tile pairs value
+  // and gate channel blocks (even j: value, odd j: gate) so both meet in one lane.
+  auto chan_of = [&](int j) -> int {
+    const int cb = wn * TN + j;
+    if (EPI == AQT_EPI_GLU) return ((cb & 1) ? (K >> 1) : 0) + bc * (BC / 2) + (cb >> 1) * 32;
+    return c0 + cb * 32;
+  };
+  const v4i *b_lane = wq_frag + (static_cast<int64_t>(chan_of(0) / 32) * ksteps) * 64 + lane;
+  // block j relative to block 0, in units of one block's fragments
+  auto b_rel = [&](int j) -> int { return (EPI == AQT_EPI_GLU) ? (j & 1) * (K >> 6) + (j >> 1) : j; };
 
-  auto load_s = [&](int n0) { rs = *reinterpret_cast<const float4 *>(s_base + n0 * 4 + gs); };
+  auto load_s = [&](int n0) {
+    if (!WONLY) rs = *reinterpret_cast<const float4 *>(s_base + n0 * 4 + gs);
+  };
   auto load_a = [&](int set, int n0) {
 #pragma unroll
     for (int i = 0; i < NA; ++i)
@@ -237,8 +272,13 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
   auto store_a = [&](int set, int i, uint8_t *slot) {
     v2i hi, lo;
     uint32_t h, l;
-    split_bf16(ra[set][i].x * rs.x, ra[set][i].y * rs.y, h, l); hi.x = h; lo.x = l;
-    split_bf16(ra[set][i].z * rs.z, ra[set][i].w * rs.w, h, l); hi.y = h; lo.y = l;
+    if (WONLY) {
+      split_bf16(ra[set][i].x, ra[set][i].y, h, l); hi.x = h; lo.x = l;
+      split_bf16(ra[set][i].z, ra[set][i].w, h, l); hi.y = h; lo.y = l;
+    } else {
+      split_bf16(ra[set][i].x * rs.x, ra[set][i].y * rs.y, h, l); hi.x = h; lo.x = l;
+      split_bf16(ra[set][i].z * rs.z, ra[set][i].w * rs.w, h, l); hi.y = h; lo.y = l;
+    }
     *reinterpret_cast<v2i *>(slot + offa0 + i * 32 * kRowB) = hi;
     *reinterpret_cast<v2i *>(slot + BM * kRowB + offa0 + i * 32 * kRowB) = lo;
   };
@@ -264,7 +304,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
   // codes fragments: one register set per (stage parity, fragment step)
   v4i fb[2][2][TN];
   auto load_b = [&](int par, int kk, int j, int stage) {
-    fb[par][kk][j] = b_lane[static_cast<int64_t>(j) * b_jstep + (2 * stage + kk) * 64];
+    fb[par][kk][j] = b_lane[static_cast<int64_t>(b_rel(j)) * b_jstep + (2 * stage + kk) * 64];
   };
   // MFMA number q of a half stage, q in [0, 2*P): all hi products first, then all
   // lo products, so that consecutive MFMAs never share an accumulator and each dy
@@ -349,6 +389,38 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
   // tile, register r holds row 8*(r/4) + 4*(lane/32) + r%4; 32 lanes write 128
   // contiguous bytes.  Addresses are a uniform tile base plus one 32-bit lane offset;
   // the row and tile steps are compile-time multiples of K folded into the base.
+  if (WONLY) {
+    // de-quantize with the channel's scale, add the bias, apply the activation
+    const int out_cols = (EPI == AQT_EPI_GLU) ? (K >> 1) : K;
+    constexpr int JS = (EPI == AQT_EPI_GLU) ? 2 : 1;
+    float *ybase = dx + static_cast<int64_t>(m0) * out_cols;
+    const int row_l = wm * 32 * TM + 4 * lk;
+#pragma unroll
+    for (int j = 0; j < TN; j += JS) {
+      const int n_a = chan_of(j) + lr;   // for GLU: the value channel = output column
+      const float sc_a = s_w[n_a];
+      const float bias_a = bias ? bias[n_a] : 0.0f;
+      float sc_b = 0.0f, bias_b = 0.0f;
+      if (EPI == AQT_EPI_GLU) {
+        const int n_b = chan_of(j + 1) + lr;
+        sc_b = s_w[n_b];
+        bias_b = bias ? bias[n_b] : 0.0f;
+      }
+      const int lane_off = row_l * out_cols + n_a;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float v = acc[i][j][r] * sc_a + bias_a;
+          float o;
+          if (EPI == AQT_EPI_NONE) o = v;
+          else if (EPI == AQT_EPI_SWISH) o = swish_f32(v);
+          else o = v * sigmoid_f32(acc[i][j + (JS - 1)][r] * sc_b + bias_b);
+          __builtin_nontemporal_store(o, ybase + (i * 32 + 8 * (r >> 2) + (r & 3)) * out_cols + lane_off);
+        }
+    }
+    return;
+  }
   float *obase = dx + static_cast<int64_t>(m0) * K + c0;
   const int lane_off = (wm * 32 * TM + 4 * lk) * K + wn * 32 * TN + lr;
   if (MASKED) {
@@ -376,6 +448,23 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
           __builtin_nontemporal_store((keep != 0.0f) ? acc[i][j][r] : 0.0f, obase + row_off + j * 32 + lane_off);
       }
   }
+}
+
+template <int TM, int TN, bool MASKED>
+__global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
+    const float *__restrict__ dy, const v4i *__restrict__ wq_frag, const float *__restrict__ s_w,
+    const float *__restrict__ s_x, const uint32_t *__restrict__ mask_x, int M, int K, int N,
+    float *__restrict__ dx, int tiles_m, int tiles_c) {
+  f32_codes_tile<TM, TN, MASKED ? 1 : 0>(dy, wq_frag, s_w, s_x, mask_x, nullptr, M, K, N, dx, tiles_m, tiles_c);
+}
+
+// Weight-only forward (Sec. 4.1, I8W / I4W): y = act((x . wq) * s_w + bias), x float32 [M,K],
+// codes in fragment order over [N][K].
+template <int TM, int TN, int EPI>
+__global__ __launch_bounds__(kThreads, 2) void dense_fwd_wonly_mfma_kernel(
+    const float *__restrict__ x, const v4i *__restrict__ wq_frag, const float *__restrict__ s_w,
+    const float *__restrict__ bias, int M, int K, int N, float *__restrict__ y, int tiles_m, int tiles_c) {
+  f32_codes_tile<TM, TN, 2 + EPI>(x, wq_frag, s_w, nullptr, nullptr, bias, M, N, K, y, tiles_m, tiles_c);
 }
 
 // =====================================================================================
@@ -687,7 +776,88 @@ aqt_status launch_dw(const float *dy, const aqt_saved *sv, int64_t M, int64_t K,
   return AQT_OK;
 }
 
+// Weight-only forward for any shape: one thread per output, the de-quantized weight
+// rounded to float32 as a float graph would hold it, products summed in float64.
+__global__ __launch_bounds__(kThreads) void dense_fwd_wonly_general_kernel(
+    const float *__restrict__ x, const uint8_t *__restrict__ wq, const float *__restrict__ s_w, int64_t M,
+    int64_t K, int64_t N, int packed, const float *__restrict__ bias, int epilogue, float *__restrict__ y) {
+  const int64_t ncols = (epilogue == AQT_EPI_GLU) ? N / 2 : N;
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  if (idx >= M * ncols) return;
+  const int64_t m = idx / ncols, j = idx - m * ncols;
+  const int64_t row_bytes = packed ? (K + 1) / 2 : K;
+  const int parts = (epilogue == AQT_EPI_GLU) ? 2 : 1;
+  float v[2];
+  for (int p = 0; p < parts; ++p) {
+    const int64_t n = j + p * ncols;
+    double s = 0.0;
+    for (int64_t k = 0; k < K; ++k) {
+      int c;
+      if (packed) {
+        const uint32_t b = wq[n * row_bytes + (k >> 1)];
+        c = static_cast<int>(((k & 1) ? (b >> 4) : (b & 0xFu)) << 28) >> 28;
+      } else {
+        c = static_cast<int8_t>(wq[n * row_bytes + k]);
+      }
+      s += static_cast<double>(x[m * K + k]) * static_cast<double>(s_w[n] * static_cast<float>(c));
+    }
+    float t = static_cast<float>(s);
+    if (bias) t = t + bias[n];
+    v[p] = t;
+  }
+  float out;
+  if (epilogue == AQT_EPI_NONE) out = v[0];
+  else if (epilogue == AQT_EPI_SWISH) out = swish_f32(v[0]);
+  else out = v[0] * sigmoid_f32(v[1]);
+  y[m * ncols + j] = out;
+}
+
+template <int TM, int TN>
+aqt_status launch_wonly(const float *x, const v4i *frag, const float *s_w, const float *bias, int epilogue,
+                        int64_t M, int64_t K, int64_t N, float *y, hipStream_t st) {
+  constexpr int BM = 64 * TM, BC = 64 * TN;
+  const int tiles_m = static_cast<int>(cdiv(M, BM)), tiles_c = static_cast<int>(N / BC);
+  auto kern = (epilogue == AQT_EPI_NONE)    ? dense_fwd_wonly_mfma_kernel<TM, TN, AQT_EPI_NONE>
+              : (epilogue == AQT_EPI_SWISH) ? dense_fwd_wonly_mfma_kernel<TM, TN, AQT_EPI_SWISH>
+                                            : dense_fwd_wonly_mfma_kernel<TM, TN, AQT_EPI_GLU>;
+  kern<<<tiles_m * tiles_c, kThreads, 0, st>>>(x, frag, s_w, bias, static_cast<int>(M), static_cast<int>(K),
+                                                  static_cast<int>(N), y, tiles_m, tiles_c);
+  AQT_HIP(hipGetLastError());
+  return AQT_OK;
+}
+
 }  // namespace
+
+size_t fwd_wonly_workspace_bytes(int64_t K, int64_t N) { return align_up(static_cast<size_t>(K) * N * 2, 256); }
+
+aqt_status launch_dense_fwd_wonly(const float *x, const void *wq_packed, const float *s_w, int64_t M, int64_t K,
+                                  int64_t N, int bits_w, const float *bias, int epilogue, float *y, void *ws,
+                                  hipStream_t st) {
+  const bool packed = packed4(bits_w);
+  const bool fits32 = M < (int64_t(1) << 30) / (K > N ? K : N);
+  const bool aligned = reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(wq_packed) % 8 == 0 &&
+                       ws && reinterpret_cast<uintptr_t>(ws) % 16 == 0;
+  // column tiles of 128 channels (64 value + 64 gate channels for GLU), 256 when there are enough of them
+  const int64_t nn = (epilogue == AQT_EPI_GLU) ? N / 2 : N;
+  const int64_t unit = (epilogue == AQT_EPI_GLU) ? 64 : 128;
+  if (fits32 && aligned && M >= 128 && K % kSN == 0 && nn % unit == 0) {
+    v4i *frag = static_cast<v4i *>(ws);
+    const int64_t pieces = N * (K / 8);
+    int g = static_cast<int>(cdiv(pieces, kThreads));
+    if (g > 2048) g = 2048;
+    codes_to_bf16_frag_kernel<<<g, kThreads, 0, st>>>(static_cast<const int8_t *>(wq_packed), static_cast<int>(N),
+                                                      static_cast<int>(K), packed ? 1 : 0, frag);
+    AQT_HIP(hipGetLastError());
+    const bool wide = (nn % (2 * unit) == 0) && cdiv(M, 128) * (N / 256) >= 512;
+    if (wide) return launch_wonly<2, 4>(x, frag, s_w, bias, epilogue, M, K, N, y, st);
+    return launch_wonly<2, 2>(x, frag, s_w, bias, epilogue, M, K, N, y, st);
+  }
+  const int64_t ncols = (epilogue == AQT_EPI_GLU) ? N / 2 : N;
+  dense_fwd_wonly_general_kernel<<<static_cast<int>(cdiv(M * ncols, kThreads)), kThreads, 0, st>>>(
+      x, static_cast<const uint8_t *>(wq_packed), s_w, M, K, N, packed ? 1 : 0, bias, epilogue, y);
+  AQT_HIP(hipGetLastError());
+  return AQT_OK;
+}
 
 size_t bwd_workspace_bytes(int64_t M, int64_t K, int64_t N) { return plan_bwd(M, K, N).total; }
 
@@ -704,7 +874,7 @@ aqt_status launch_dense_bwd(const float *dy, const aqt_saved *sv, int64_t M, int
       const int64_t pieces = K * (N / 8);
       int g = static_cast<int>(cdiv(pieces, kThreads));
       if (g > 2048) g = 2048;
-      codes_to_bf16_frag_kernel<<<g, kThreads, 0, st>>>(sv->wq_kn, static_cast<int>(K), static_cast<int>(N), wq_frag);
+      codes_to_bf16_frag_kernel<<<g, kThreads, 0, st>>>(sv->wq_kn, static_cast<int>(K), static_cast<int>(N), 0, wq_frag);
       AQT_HIP(hipGetLastError());
       if (p.dx_wide) AQT_TRY((launch_dx<2, 4>(dy, wq_frag, sv, M, K, N, dx, st)));
       else AQT_TRY((launch_dx<2, 2>(dy, wq_frag, sv, M, K, N, dx, st)));

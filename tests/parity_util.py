@@ -56,3 +56,21 @@ def check_grad(g_gpu, g_ref, g_abs, what):
     assert err.max() <= REL_G * np.abs(g_ref).max() + TINY, f"{what}: max-norm error {err.max()}"
     bad = err > REL_G * g_abs + TINY
     assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} elements outside 1e-4 of sum|terms|"
+
+
+def check_float_forward(y_gpu, ora, epilogue):
+    """Weight-only forward: a float contraction, so the pre-activation value is held to the
+    gradient bar (1e-4 of the sum of the magnitudes of its terms) and activations propagate
+    that tolerance through their derivatives.  ora: dict(pre, y, mag) from the oracle."""
+    y = np.asarray(y_gpu, dtype=np.float64)
+    pre, tol_v = ora["pre"], REL_G * ora["mag"] + TINY
+    if epilogue == 0:
+        bad = np.abs(y - pre) > tol_v
+    elif epilogue == 1:
+        bad = np.abs(y - ora["y"]) > REL_Y * np.abs(ora["y"]) + 1.1 * tol_v
+    else:
+        h = pre.shape[1] // 2
+        a, g = pre[:, :h], pre[:, h:]
+        tol = REL_Y * np.abs(ora["y"]) + sigmoid(g) * tol_v[:, :h] + 0.25 * np.abs(a) * tol_v[:, h:] + TINY
+        bad = np.abs(y - ora["y"]) > tol
+    assert not bad.any(), f"{bad.sum()} of {bad.size} outputs outside tolerance"

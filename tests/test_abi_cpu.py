@@ -87,6 +87,9 @@ def test_argument_errors_are_synchronous_and_touch_no_gpu(L):
     assert L.aqt_quantize_with_absmax(one, 4, 4, 4, 8, none, one, one, none, none, none) == B.AQT_ERR_INVALID_ARG
     assert L.aqt_quantize_with_absmax(one, 4, 4, 3, 8, one, one, one, none, none, none) == B.AQT_ERR_INVALID_ARG
     assert L.aqt_quantize_with_absmax(one, 4, 4, 4, 9, one, one, one, none, none, none) == B.AQT_ERR_UNSUPPORTED
+    assert L.aqt_dense_fwd_wonly(one, one, none, 4, 4, 4, 4, none, 0, one, one, 1 << 20, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_dense_fwd_wonly(one, one, one, 4, 4, 5, 4, none, B.AQT_EPI_GLU, one, one, 1 << 20, none) == B.AQT_ERR_UNSUPPORTED
+    assert L.aqt_dense_fwd_wonly(one, one, one, 4, 4, 4, 4, none, 0, one, none, 0, none) == B.AQT_ERR_WORKSPACE
     assert L.aqt_dense_fwd(one, one, 4, 4, 4, 8, 4, none, 0, one, None, none, 0, none, none) == B.AQT_ERR_WORKSPACE
     assert L.aqt_dense_fwd(one, none, 4, 4, 4, 8, 4, none, 0, one, None, one, 1 << 30, none, none) == B.AQT_ERR_INVALID_ARG
     sv = B.aqt_saved(None, None, None, None, None, None, None)

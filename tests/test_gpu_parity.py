@@ -8,7 +8,7 @@ import torch
 import oracle
 from paper_2203_15952_amd import binding as B
 from paper_2203_15952_amd import inputs
-from parity_util import check_forward, check_grad, unpack_mask
+from parity_util import check_float_forward, check_forward, check_grad, unpack_mask
 
 pytestmark = pytest.mark.gpu
 F = np.float32
@@ -352,6 +352,64 @@ def test_quantize_with_absmax_edge_cases():
         status = B.new_status()
         B.aqt_quantize_with_absmax(x_d, 8, dev(np.array([bad], np.float32)), dev_status=status)
         assert host(status)[0] == B.AQT_ERR_NONFINITE
+
+
+# ----------------------------------------------------------------------------
+# weight-only modes: float32 activations x integer weights
+# ----------------------------------------------------------------------------
+WONLY_CASES = [
+    # M, K, N, bits_w, epilogue, bias       (which kernel it lands on)
+    (256, 256, 1024, 4, 0, False),   # tuned kernel, 128 x 128 tiles, packed int4 weights
+    (300, 96, 256, 8, 1, True),      # ragged M, int8 weights, Swish, three contraction stages
+    (200, 64, 512, 4, 2, True),      # GLU: value and gate blocks in one tile
+    (200, 160, 256, 8, 2, False),
+    (37, 50, 23, 4, 0, True),        # general kernel
+    (37, 51, 24, 8, 2, True),
+    (3, 1, 2, 4, 1, False),
+]
+
+
+@pytest.mark.parametrize("M,K,N,bw,epi,with_bias", WONLY_CASES)
+def test_dense_fwd_weight_only_against_oracle(M, K, N, bw, epi, with_bias):
+    say("dense fwd weight-only", M, K, N, bw, epi, with_bias)
+    c = inputs.small_case(91 + M + K + N, M, K, N, 8, bw, epi, with_bias=with_bias, with_dy=False)
+    wq_ref, sw_ref = oracle.quantize(c.w, bw, 0)
+    ora = oracle.dense_fwd_wonly(c.x, wq_ref, sw_ref, c.bias, epi)
+    wq, s_w, wq_kn, _ = B.aqt_quantize_weights(dev(c.w), bw)
+    np.testing.assert_array_equal(host(wq_kn), wq_ref)
+    np.testing.assert_array_equal(host(s_w), sw_ref)
+    y = B.aqt_dense_fwd_wonly(dev(c.x), wq, s_w, N, bw, bias=None if c.bias is None else dev(c.bias), epilogue=epi)
+    check_float_forward(host(y), ora, epi)
+
+
+WONLY_WIDE_CASES = [
+    (16384, 128, 2048, 4, 0),        # 128 x 256 tiles
+    (16500, 96, 1024, 8, 2),         # wide GLU tiles, ragged M
+]
+
+
+@pytest.mark.parametrize("M,K,N,bw,epi", WONLY_WIDE_CASES)
+def test_dense_fwd_weight_only_wide_tiles_sampled(M, K, N, bw, epi):
+    say("dense fwd weight-only wide", M, K, N, bw, epi)
+    c = inputs.small_case(97 + K + N, M, K, N, 8, bw, epi, with_dy=False)
+    wq_ref, sw_ref = oracle.quantize(c.w, bw, 0)
+    wq, s_w, _, _ = B.aqt_quantize_weights(dev(c.w), bw)
+    y_h = host(B.aqt_dense_fwd_wonly(dev(c.x), wq, s_w, N, bw, epilogue=epi))
+    rng = np.random.default_rng(9)
+    out_cols = N // 2 if epi == 2 else N
+    im = np.r_[rng.integers(0, M, 3000), [0, M - 1]]
+    ij = np.r_[rng.integers(0, out_cols, 3000), [0, out_cols - 1]]
+    pre, mag = oracle.dense_fwd_wonly_sampled(c.x, wq_ref, sw_ref, im, ij)
+    got = y_h[im, ij].astype(np.float64)
+    tol_v = 1e-4 * mag + 1e-37
+    if epi == 0:
+        assert (np.abs(got - pre) <= tol_v).all()
+    else:
+        gate, gmag = oracle.dense_fwd_wonly_sampled(c.x, wq_ref, sw_ref, im, ij + out_cols)
+        sg = 1 / (1 + np.exp(-gate))
+        ref = pre * sg
+        tol = 1e-6 * np.abs(ref) + sg * tol_v + 0.25 * np.abs(pre) * (1e-4 * gmag) + 1e-37
+        assert (np.abs(got - ref) <= tol).all()
 
 
 # 128 x 256 tiles are used once there are at least 512 of them
