@@ -676,6 +676,45 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_kernel(
   // columns; addresses are a uniform base plus a 32-bit lane offset plus
   // compile-time multiples of N.
   float *out = partial + static_cast<int64_t>(slab) * K * N + static_cast<int64_t>(r0) * N + c0;
+  if (TC == 2 && TR == 4) {
+    // Written lane by lane the tile would reach HBM as 4- or 8-byte pieces at a 16-byte
+    // stride (the de-interleaved columns), which the memory system turns into several
+    // times the traffic, all of it in the tail of the launch.  So the tile goes through
+    // LDS (free by now) in two halves of 128 rows and leaves as dense 512-byte row
+    // pieces.  Half ih holds the accumulator rows of row blocks i = 2*ih, 2*ih + 1:
+    // tile row k_l = 4*q + (2*wm + ih) with q = (i & 1)*32 + local, local = 8*(r/4) + r%4
+    // + 4*lk; the four LDS arrays serve as four chunks of 32 rows x 128 floats, chunk
+    // (wm, i & 1).  This wavefront's two column blocks are the adjacent tile columns
+    // 4*lr + 2*wn and + 1.
+    __syncthreads();   // every wavefront is done reading operand fragments
+#pragma unroll
+    for (int ih = 0; ih < 2; ++ih) {
+#pragma unroll
+      for (int ii = 0; ii < 2; ++ii) {
+        const int i = 2 * ih + ii;
+        uint8_t *chunk = wm ? (ii ? sD1 : sD0) : (ii ? sC1 : sC0);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int local = 8 * (r >> 2) + (r & 3) + 4 * lk;
+          v2f pr = {acc[i][0][r], acc[i][1][r]};
+          *reinterpret_cast<v2f *>(chunk + local * 512 + (4 * lr + 2 * wn) * 4) = pr;
+        }
+      }
+      __syncthreads();
+      // 32 threads per row: 128 rows x 32 float4 = 16 float4 per thread
+#pragma unroll
+      for (int p = 0; p < 16; ++p) {
+        const int ch = p >> 2;                       // chunk = (wm, i & 1) of the rows it holds
+        const int local = (t >> 5) + 8 * (p & 3);
+        const uint8_t *chunk = (ch >> 1) ? ((ch & 1) ? sD1 : sD0) : ((ch & 1) ? sC1 : sC0);
+        const float4 v = *reinterpret_cast<const float4 *>(chunk + local * 512 + (t & 31) * 16);
+        const int k_l = 4 * ((ch & 1) * 32 + local) + 2 * (ch >> 1) + ih;
+        *reinterpret_cast<float4 *>(out + k_l * N + (t & 31) * 4) = v;
+      }
+      if (ih == 0) __syncthreads();
+    }
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < TC; ++j) {
     const int rho_c = wn * 32 * TC + j * 32 + lr;
