@@ -38,12 +38,12 @@ MEASURED_TRAFFIC_MIB = {
     (1, "quantize_x"): (512.0 + 512.1, 0.1 + 128.0),
     (0, "quantize_w"): (4.0 + 4.2, 0.1 + 1.5),
     (1, "quantize_w"): (4.0 + 4.1, 0.0 + 1.5),
-    (0, "fwd_gemm"): (1.0 + 40.7, 1.0 + 514.0),          # fragment re-order + contraction
-    (1, "fwd_gemm"): (1.0 + 150.6, 1.0 + 129.1),
-    (0, "bwd_dx"): (2.0 + 572.9, 2.0 + 128.0),
-    (1, "bwd_dx"): (2.0 + 151.6, 2.0 + 512.0),
-    (0, "bwd_dw"): (546.5 + 64.1, 164.6 + 4.0),          # slab partials + fold
-    (1, "bwd_dw"): (258.4 + 64.1, 156.8 + 4.0),
+    (0, "fwd_gemm"): (1.0 + 41.2, 1.0 + 515.8),          # fragment re-order + contraction
+    (1, "fwd_gemm"): (1.0 + 151.9, 1.0 + 130.1),
+    (0, "bwd_dx"): (2.0 + 573.0, 2.0 + 128.0),
+    (1, "bwd_dx"): (2.0 + 151.1, 2.0 + 512.0),
+    (0, "bwd_dw"): (544.2 + 64.1, 64.0 + 4.0),           # slab partials + fold
+    (1, "bwd_dw"): (256.2 + 64.1, 64.0 + 4.0),
 }
 
 
