@@ -242,13 +242,43 @@ constexpr int kWCols = 32;
 constexpr int kWChunk = 64;
 
 __global__ __launch_bounds__(kThreads) void wabsmax_partial_kernel(const float *__restrict__ w, int64_t K,
-                                                                   int64_t N, int64_t rows_per_slab,
+                                                                   int64_t N, int64_t rows_per_slab, int vec4,
                                                                    uint32_t *__restrict__ part) {
-  __shared__ uint32_t sm[4][64];
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  const int64_t n = static_cast<int64_t>(blockIdx.x) * 64 + tx;
+  __shared__ uint32_t sm[16][64];
   const int64_t k0 = static_cast<int64_t>(blockIdx.y) * rows_per_slab;
   const int64_t k1 = min(K, k0 + rows_per_slab);
+  if (vec4) {
+    // 16 column groups of 4 x 16 row lanes; four independent 16-byte loads in flight per
+    // thread (the matrix is small, so the pass is bound by load latency, not bandwidth)
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int64_t n = static_cast<int64_t>(blockIdx.x) * 64 + tx * 4;
+    uint32_t m0 = 0, m1 = 0, m2 = 0, m3 = 0;
+    if (n < N) {
+      const float4 zero = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      for (int64_t k = k0 + ty; k < k1; k += 64) {
+        const float4 a = *reinterpret_cast<const float4 *>(w + k * N + n);
+        const float4 b = (k + 16 < k1) ? *reinterpret_cast<const float4 *>(w + (k + 16) * N + n) : zero;
+        const float4 c = (k + 32 < k1) ? *reinterpret_cast<const float4 *>(w + (k + 32) * N + n) : zero;
+        const float4 d = (k + 48 < k1) ? *reinterpret_cast<const float4 *>(w + (k + 48) * N + n) : zero;
+        m0 = max(max(m0, abs_bits(a.x)), max(max(abs_bits(b.x), abs_bits(c.x)), abs_bits(d.x)));
+        m1 = max(max(m1, abs_bits(a.y)), max(max(abs_bits(b.y), abs_bits(c.y)), abs_bits(d.y)));
+        m2 = max(max(m2, abs_bits(a.z)), max(max(abs_bits(b.z), abs_bits(c.z)), abs_bits(d.z)));
+        m3 = max(max(m3, abs_bits(a.w)), max(max(abs_bits(b.w), abs_bits(c.w)), abs_bits(d.w)));
+      }
+    }
+    sm[ty][tx * 4 + 0] = m0; sm[ty][tx * 4 + 1] = m1; sm[ty][tx * 4 + 2] = m2; sm[ty][tx * 4 + 3] = m3;
+    __syncthreads();
+    if (threadIdx.x < 64) {
+      const int64_t nn = static_cast<int64_t>(blockIdx.x) * 64 + threadIdx.x;
+      uint32_t m = 0;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) m = max(m, sm[j][threadIdx.x]);
+      if (nn < N) part[static_cast<int64_t>(blockIdx.y) * N + nn] = m;
+    }
+    return;
+  }
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int64_t n = static_cast<int64_t>(blockIdx.x) * 64 + tx;
   uint32_t m = 0;
   if (n < N)
     for (int64_t k = k0 + ty; k < k1; k += 4) m = max(m, abs_bits(w[k * N + n]));
@@ -438,7 +468,8 @@ aqt_status launch_quantize_weights(const float *w, int64_t K, int64_t N, int bit
   const int64_t rows_per_slab = cdiv(K, slabs);
   slabs = cdiv(K, rows_per_slab);
   dim3 g1(static_cast<unsigned>(cdiv(N, 64)), static_cast<unsigned>(slabs));
-  wabsmax_partial_kernel<<<g1, kThreads, 0, st>>>(w, K, N, rows_per_slab, part);
+  const int vec4 = (N % 4 == 0) && (reinterpret_cast<uintptr_t>(w) % 16 == 0);
+  wabsmax_partial_kernel<<<g1, kThreads, 0, st>>>(w, K, N, rows_per_slab, vec4, part);
   AQT_HIP(hipGetLastError());
   dim3 g2(static_cast<unsigned>(cdiv(N, kWCols)), static_cast<unsigned>(cdiv(K, kWChunk)));
   quantize_weights_kernel<<<g2, kThreads, 0, st>>>(w, K, N, qmax_of(bits_w), packed4(bits_w) ? 1 : 0, part,
