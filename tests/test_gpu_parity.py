@@ -244,9 +244,10 @@ def test_dense_bwd_against_oracle(M, K, N, bx, bw):
     check_grad(host(db), g["dbias"], np.abs(c.dy.astype(np.float64)).sum(0), "dbias")
 
 
-def test_dense_bwd_masks_and_zero_groups():
-    say("dense bwd masks")
-    M, K, N = 96, 64, 48
+@pytest.mark.parametrize("M,K,N", [(96, 64, 48),        # general kernels
+                                   (300, 256, 128)])     # masked variants of the tuned dX and dW kernels
+def test_dense_bwd_masks_and_zero_groups(M, K, N):
+    say("dense bwd masks", M, K, N)
     c = inputs.small_case(61, M, K, N, 8, 4)
     c.w[:, 5] = 0
     # externally supplied, too small scales make both masks non-trivial
@@ -272,6 +273,53 @@ def test_dense_bwd_masks_and_zero_groups():
     B.aqt_dense_fwd(dev(c.x), dev(c.w), 8, 4, saved=sv2)
     _, dw2, _ = B.aqt_dense_bwd(dev(c.dy), sv2, 8, 4, want_dx=False)
     assert (host(dw2)[:, 5] == 0).all() and host(dw2)[:, 4].any()
+
+
+def test_backward_is_bit_reproducible_and_stream_ordered():
+    # dW folds its slabs in a fixed order: two runs give identical bits; the same work
+    # enqueued on a side stream (the stream argument of the C ABI) gives them too
+    say("bwd reproducible / side stream")
+    M, K, N = 4096, 512, 256
+    c = inputs.small_case(71, M, K, N, 8, 4)
+    sv = B.Saved(M, K, N, 4)
+    x_d, w_d, dy_d = dev(c.x), dev(c.w), dev(c.dy)
+    y1 = B.aqt_dense_fwd(x_d, w_d, 8, 4, saved=sv)
+    dx1, dw1, _ = B.aqt_dense_bwd(dy_d, sv, 8, 4)
+    dx2, dw2, _ = B.aqt_dense_bwd(dy_d, sv, 8, 4)
+    np.testing.assert_array_equal(host(dw1), host(dw2))
+    np.testing.assert_array_equal(host(dx1), host(dx2))
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        sv3 = B.Saved(M, K, N, 4)
+        y3 = B.aqt_dense_fwd(x_d, w_d, 8, 4, saved=sv3)
+        dx3, dw3, _ = B.aqt_dense_bwd(dy_d, sv3, 8, 4)
+    side.synchronize()
+    np.testing.assert_array_equal(host(y3), host(y1))
+    np.testing.assert_array_equal(host(dw3), host(dw1))
+    np.testing.assert_array_equal(host(dx3), host(dx1))
+
+
+def test_dense_fwd_very_tall_input_indexing():
+    # a million rows: tile bases are 64-bit, lane offsets 32-bit; compare sampled accumulators
+    say("dense fwd tall")
+    M, K, N = (1 << 20) + 5, 128, 128
+    rng = np.random.default_rng(81)
+    xq_h = rng.integers(-127, 128, (M, K), dtype=np.int8)
+    w = (rng.standard_normal((K, N)) / np.sqrt(K)).astype(F)
+    wq_ref, sw_ref = oracle.quantize(w, 4, 0)
+    wq, s_w, _, _ = B.aqt_quantize_weights(dev(w), 4)
+    s_x = np.array([0.03125], F)
+    y, acc = B.aqt_dense_fwd_q(dev(xq_h), dev(s_x), wq, s_w, N, 8, 4, want_acc=True)
+    acc_h, y_h = host(acc), host(y)
+    im = np.r_[rng.integers(0, M, 3000), [0, M - 1, M - 6, 1 << 19]]
+    inn = np.r_[rng.integers(0, N, 3000), [0, N - 1, 5, 77]]
+    a, pre = oracle.dense_fwd_q_sampled(xq_h, s_x[0], wq_ref, sw_ref, im, inn)
+    np.testing.assert_array_equal(acc_h[im, inn], a)
+    assert (np.abs(y_h[im, inn] - pre) <= 1e-6 * np.abs(pre) + 1e-37).all()
+    # the last rows, in full
+    ref = xq_h[-200:].astype(np.int64) @ wq_ref.astype(np.int64)
+    np.testing.assert_array_equal(acc_h[-200:], ref)
 
 
 def test_argument_errors_on_device_buffers():
