@@ -146,12 +146,12 @@ __global__ __launch_bounds__(kThreads, 2) void dense_fwd_mfma_kernel(
   constexpr int NA = BM * (kBK / 16) / kThreads;   // 16-byte pieces of activations per thread per stage
   __shared__ __attribute__((aligned(1024))) uint8_t sA0[BM * kBK], sA1[BM * kBK];
 
-  // Workgroup -> tile.  Consecutive workgroup ids land on different XCDs (8 of
-  // them, each with its own L2); give each XCD a contiguous run of tiles so the
-  // workgroups that share an activation tile also share an L2.
-  int id = blockIdx.x;
-  const int total = tiles_m * tiles_n;
-  if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+  // Workgroup -> tile, row-major over (row tile, column tile).  Consecutive workgroup
+  // ids land on different XCDs, so the column tiles of one row tile run at the same
+  // time on different L2s and each fetches the activation tile itself; measured, that
+  // costs less than what remapping ids to one contiguous run of tiles per XCD loses
+  // on the output side (the tiles in flight then write to eight distant regions).
+  const int id = blockIdx.x;
   const int bm = id / tiles_n, bn = id - bm * tiles_n;
   // A ragged last row tile is shifted up to end at row M: it recomputes a few rows
   // of its neighbour (same values, same addresses) instead of predicating.
