@@ -563,3 +563,32 @@ def test_fused_absmax_full_size_chain():
     np.testing.assert_array_equal(host(s), s_ref)
     np.testing.assert_array_equal(host(q), q_ref)
     assert host(status)[0] == 0
+
+
+def test_quantize_more_than_2_31_elements():
+    # 64-bit indexing in the per-tensor quantizer: a tensor of 2^31 + 4100 floats (8.6 GB) made on
+    # the device; the scale is checked against the definition, the codes on slices (head, the
+    # 2^31 boundary, the ragged tail) against the oracle's element-wise half with that scale
+    say("quantize > 2^31 elements")
+    rows, cols = (1 << 19) + 1, 4100            # cols not a multiple of 4 rows apart: ragged runs
+    n = rows * cols
+    assert n > (1 << 31)
+    g = torch.Generator(device="cuda").manual_seed(5)
+    x = torch.empty((rows, cols), dtype=torch.float32, device="cuda")
+    x.normal_(generator=g)
+    x[rows - 1, cols - 1] = -9.5                # the maximum sits in the very last element
+    status = B.new_status()
+    q, s, _ = B.aqt_quantize(x, 8, B.AQT_AXIS_ALL, dev_status=status)
+    assert host(status)[0] == 0
+    m = np.float32(x.abs().max().item())
+    assert m == np.float32(9.5)
+    s_ref = np.array([m / np.float32(127)], F)
+    np.testing.assert_array_equal(host(s), s_ref)
+    flat_x, flat_q = x.view(-1), q.view(-1)
+    for lo, hi in [(0, 70000), ((1 << 31) - 40000, (1 << 31) + 40000), (n - 70001, n)]:
+        xs = flat_x[lo:hi].cpu().numpy().reshape(1, -1)
+        q_ref, _ = oracle.quantize_with_scale(xs, 8, oracle.AXIS_ALL, s_ref)
+        np.testing.assert_array_equal(flat_q[lo:hi].cpu().numpy().reshape(1, -1), q_ref)
+    assert int(flat_q[n - 1].item()) == -127
+    del x, q
+    torch.cuda.empty_cache()
