@@ -153,9 +153,9 @@ __global__ __launch_bounds__(kThreads) void codes_to_bf16_frag_kernel(const int8
 
 // =====================================================================================
 // dX = (dy * s_w) . wq^T       rows m, columns k, contraction over n
-// Workgroup = 2 x 2 wavefronts, tile (64*TM) x (64*TN), 32 n per stage, two
-// workgroups per CU.  The split operand sits on the short side of the wavefront
-// tile (TM < TN).
+// Workgroup = 2 x WN wavefronts (WN = 2: two workgroups per CU; WN = 4: one), tile
+// (64*TM) x (32*TN*WN), 32 n per stage.  The split operand sits on the short side
+// of the wavefront tile (TM < TN).
 //
 // Data movement, chosen around what bounds this kernel on gfx950: LDS bandwidth
 // (about 64 bytes per clock and CU for 16-byte reads), not the matrix cores.
@@ -204,7 +204,7 @@ constexpr int waitcnt_imm(int vm, int lgkm) {
 //   MODE 2 + e : weight-only forward with epilogue e (none, Swish, GLU)
 // Names follow dX: `dy` is the float operand [M,N], N the contraction length, K the
 // number of output columns (for GLU: value and gate channels together).
-template <int TM, int TN, int MODE>
+template <int TM, int TN, int MODE, int WN = 2>
 __device__ __forceinline__ void f32_codes_tile(
     const float *__restrict__ dy, const v4i *__restrict__ wq_frag, const float *__restrict__ s_w,
     const float *__restrict__ s_x, const uint32_t *__restrict__ mask_x, const float *__restrict__ bias, int M,
@@ -212,9 +212,14 @@ __device__ __forceinline__ void f32_codes_tile(
   constexpr bool MASKED = (MODE == 1);
   constexpr bool WONLY = (MODE >= 2);
   constexpr int EPI = WONLY ? MODE - 2 : AQT_EPI_NONE;
-  constexpr int BM = 64 * TM, BC = 64 * TN;
+  // Workgroup = 2 x WN wavefronts.  With WN = 4 the float operand tile is staged (and
+  // scaled, split) once for four column wavefronts instead of two, which halves the
+  // loads and the conversion arithmetic per MFMA.
+  constexpr int NTHR = 64 * 2 * WN;        // threads
+  constexpr int RP = NTHR / 8;               // rows staged per pass (8 threads per 32-float row piece)
+  constexpr int BM = 64 * TM, BC = 32 * TN * WN;
   constexpr int kABytes = 2 * BM * kRowB;  // dy hi image, then dy lo image
-  constexpr int NA = 2 * TM;               // float4 of dy per thread per stage
+  constexpr int NA = BM / RP;              // float4 of dy per thread per stage
   constexpr int P = TM * TN;               // MFMA pairs per half stage
   __shared__ __attribute__((aligned(1024))) uint8_t sA0[kABytes], sA1[kABytes];
 
@@ -228,7 +233,7 @@ __device__ __forceinline__ void f32_codes_tile(
 
   const int t = threadIdx.x;
   const int wave = t >> 6, lane = t & 63;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WN, wn = wave % WN;
   const int lr = lane & 31, lk = lane >> 5;
 
   float4 ra[2][NA];
@@ -238,8 +243,8 @@ __device__ __forceinline__ void f32_codes_tile(
   // offsets that stay fixed, so the loads can use scalar-base addressing.
   const char *a_base = reinterpret_cast<const char *>(dy + static_cast<int64_t>(m0) * N);
   const char *s_base = reinterpret_cast<const char *>(s_w);
-  const uint32_t ga0 = static_cast<uint32_t>((t >> 3) * N + (t & 7) * 4) * 4u;  // piece i: + i * 32 rows
-  const uint32_t ga_step = static_cast<uint32_t>(32 * N) * 4u;
+  const uint32_t ga0 = static_cast<uint32_t>((t >> 3) * N + (t & 7) * 4) * 4u;  // piece i: + i * RP rows
+  const uint32_t ga_step = static_cast<uint32_t>(RP * N) * 4u;
   const uint32_t gs = (t & 7) * 16u;
   // LDS offsets: piece i of a thread sits 32 rows below piece 0, which leaves the
   // swizzle bits of the row unchanged.
@@ -279,8 +284,8 @@ __device__ __forceinline__ void f32_codes_tile(
       split_bf16(ra[set][i].x * rs.x, ra[set][i].y * rs.y, h, l); hi.x = h; lo.x = l;
       split_bf16(ra[set][i].z * rs.z, ra[set][i].w * rs.w, h, l); hi.y = h; lo.y = l;
     }
-    *reinterpret_cast<v2i *>(slot + offa0 + i * 32 * kRowB) = hi;
-    *reinterpret_cast<v2i *>(slot + BM * kRowB + offa0 + i * 32 * kRowB) = lo;
+    *reinterpret_cast<v2i *>(slot + offa0 + i * RP * kRowB) = hi;
+    *reinterpret_cast<v2i *>(slot + BM * kRowB + offa0 + i * RP * kRowB) = lo;
   };
 
   v16f acc[TM][TN];
@@ -450,21 +455,21 @@ __device__ __forceinline__ void f32_codes_tile(
   }
 }
 
-template <int TM, int TN, bool MASKED>
-__global__ __launch_bounds__(kThreads, 2) void bwd_dx_mfma_kernel(
+template <int TM, int TN, bool MASKED, int WN = 2>
+__global__ __launch_bounds__(128 * WN, WN == 2 ? 2 : 1) void bwd_dx_mfma_kernel(
     const float *__restrict__ dy, const v4i *__restrict__ wq_frag, const float *__restrict__ s_w,
     const float *__restrict__ s_x, const uint32_t *__restrict__ mask_x, int M, int K, int N,
     float *__restrict__ dx, int tiles_m, int tiles_c) {
-  f32_codes_tile<TM, TN, MASKED ? 1 : 0>(dy, wq_frag, s_w, s_x, mask_x, nullptr, M, K, N, dx, tiles_m, tiles_c);
+  f32_codes_tile<TM, TN, MASKED ? 1 : 0, WN>(dy, wq_frag, s_w, s_x, mask_x, nullptr, M, K, N, dx, tiles_m, tiles_c);
 }
 
 // Weight-only forward (Sec. 4.1, I8W / I4W): y = act((x . wq) * s_w + bias), x float32 [M,K],
 // codes in fragment order over [N][K].
-template <int TM, int TN, int EPI>
-__global__ __launch_bounds__(kThreads, 2) void dense_fwd_wonly_mfma_kernel(
+template <int TM, int TN, int EPI, int WN = 2>
+__global__ __launch_bounds__(128 * WN, WN == 2 ? 2 : 1) void dense_fwd_wonly_mfma_kernel(
     const float *__restrict__ x, const v4i *__restrict__ wq_frag, const float *__restrict__ s_w,
     const float *__restrict__ bias, int M, int K, int N, float *__restrict__ y, int tiles_m, int tiles_c) {
-  f32_codes_tile<TM, TN, 2 + EPI>(x, wq_frag, s_w, nullptr, nullptr, bias, M, N, K, y, tiles_m, tiles_c);
+  f32_codes_tile<TM, TN, 2 + EPI, WN>(x, wq_frag, s_w, nullptr, nullptr, bias, M, N, K, y, tiles_m, tiles_c);
 }
 
 // =====================================================================================
@@ -758,6 +763,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dw_fold_kernel(const float *__re
 struct BwdPlan {
   bool dx_mfma, dw_mfma;
   bool dx_wide;    // 128 x 256 tiles (else 128 x 128)
+  bool dx_wide8;   // 128 x 512 tiles, eight wavefronts: the gradient tile is staged once for four column wavefronts
   bool dw_wide;    // 256 x 128 tiles (else 128 x 128)
   int slabs;
   int m_per_slab;
@@ -770,6 +776,7 @@ BwdPlan plan_bwd(int64_t M, int64_t K, int64_t N) {
   // dX: columns are K, contraction N in stages of 32; row tiles of 128 (the last one may be shifted)
   p.dx_mfma = fits32 && (N % kSN == 0) && (K % 128 == 0) && (M >= 128);
   p.dx_wide = (K % 256 == 0) && cdiv(M, 128) * (K / 256) >= 512;
+  p.dx_wide8 = p.dx_wide && (K % 512 == 0) && cdiv(M, 128) * (K / 512) >= 256;
   // dW: tiles over K x N, slabs over M
   p.dw_mfma = fits32 && (K % 256 == 0) && (N % 128 == 0);
   p.dw_wide = true;
@@ -790,13 +797,13 @@ BwdPlan plan_bwd(int64_t M, int64_t K, int64_t N) {
   return p;
 }
 
-template <int TM, int TN>
+template <int TM, int TN, int WN = 2>
 aqt_status launch_dx(const float *dy, const v4i *wq_frag, const aqt_saved *sv, int64_t M, int64_t K, int64_t N,
                      float *dx, hipStream_t st) {
-  constexpr int BM = 64 * TM, BC = 64 * TN;
-  auto kern = sv->mask_x ? bwd_dx_mfma_kernel<TM, TN, true> : bwd_dx_mfma_kernel<TM, TN, false>;
+  constexpr int BM = 64 * TM, BC = 32 * TN * WN;
+  auto kern = sv->mask_x ? bwd_dx_mfma_kernel<TM, TN, true, WN> : bwd_dx_mfma_kernel<TM, TN, false, WN>;
   const int tiles_m = static_cast<int>(cdiv(M, BM)), tiles_c = static_cast<int>(K / BC);
-  kern<<<tiles_m * tiles_c, kThreads, 0, st>>>(dy, wq_frag, sv->s_w, sv->s_x, sv->mask_x, static_cast<int>(M),
+  kern<<<tiles_m * tiles_c, 128 * WN, 0, st>>>(dy, wq_frag, sv->s_w, sv->s_x, sv->mask_x, static_cast<int>(M),
                                                   static_cast<int>(K), static_cast<int>(N), dx, tiles_m, tiles_c);
   AQT_HIP(hipGetLastError());
   return AQT_OK;
@@ -851,15 +858,15 @@ __global__ __launch_bounds__(kThreads) void dense_fwd_wonly_general_kernel(
   y[m * ncols + j] = out;
 }
 
-template <int TM, int TN>
+template <int TM, int TN, int WN = 2>
 aqt_status launch_wonly(const float *x, const v4i *frag, const float *s_w, const float *bias, int epilogue,
                         int64_t M, int64_t K, int64_t N, float *y, hipStream_t st) {
-  constexpr int BM = 64 * TM, BC = 64 * TN;
+  constexpr int BM = 64 * TM, BC = 32 * TN * WN;
   const int tiles_m = static_cast<int>(cdiv(M, BM)), tiles_c = static_cast<int>(N / BC);
-  auto kern = (epilogue == AQT_EPI_NONE)    ? dense_fwd_wonly_mfma_kernel<TM, TN, AQT_EPI_NONE>
-              : (epilogue == AQT_EPI_SWISH) ? dense_fwd_wonly_mfma_kernel<TM, TN, AQT_EPI_SWISH>
-                                            : dense_fwd_wonly_mfma_kernel<TM, TN, AQT_EPI_GLU>;
-  kern<<<tiles_m * tiles_c, kThreads, 0, st>>>(x, frag, s_w, bias, static_cast<int>(M), static_cast<int>(K),
+  auto kern = (epilogue == AQT_EPI_NONE)    ? dense_fwd_wonly_mfma_kernel<TM, TN, AQT_EPI_NONE, WN>
+              : (epilogue == AQT_EPI_SWISH) ? dense_fwd_wonly_mfma_kernel<TM, TN, AQT_EPI_SWISH, WN>
+                                            : dense_fwd_wonly_mfma_kernel<TM, TN, AQT_EPI_GLU, WN>;
+  kern<<<tiles_m * tiles_c, 128 * WN, 0, st>>>(x, frag, s_w, bias, static_cast<int>(M), static_cast<int>(K),
                                                   static_cast<int>(N), y, tiles_m, tiles_c);
   AQT_HIP(hipGetLastError());
   return AQT_OK;
@@ -888,6 +895,8 @@ aqt_status launch_dense_fwd_wonly(const float *x, const void *wq_packed, const f
                                                       static_cast<int>(K), packed ? 1 : 0, frag);
     AQT_HIP(hipGetLastError());
     const bool wide = (nn % (2 * unit) == 0) && cdiv(M, 128) * (N / 256) >= 512;
+    const bool wide8 = wide && (nn % (4 * unit) == 0) && cdiv(M, 128) * (N / 512) >= 256;   // eight wavefronts
+    if (wide8) return launch_wonly<2, 4, 4>(x, frag, s_w, bias, epilogue, M, K, N, y, st);
     if (wide) return launch_wonly<2, 4>(x, frag, s_w, bias, epilogue, M, K, N, y, st);
     return launch_wonly<2, 2>(x, frag, s_w, bias, epilogue, M, K, N, y, st);
   }
@@ -915,7 +924,8 @@ aqt_status launch_dense_bwd(const float *dy, const aqt_saved *sv, int64_t M, int
       if (g > 2048) g = 2048;
       codes_to_bf16_frag_kernel<<<g, kThreads, 0, st>>>(sv->wq_kn, static_cast<int>(K), static_cast<int>(N), 0, wq_frag);
       AQT_HIP(hipGetLastError());
-      if (p.dx_wide) AQT_TRY((launch_dx<2, 4>(dy, wq_frag, sv, M, K, N, dx, st)));
+      if (p.dx_wide8) AQT_TRY((launch_dx<2, 4, 4>(dy, wq_frag, sv, M, K, N, dx, st)));
+      else if (p.dx_wide) AQT_TRY((launch_dx<2, 4>(dy, wq_frag, sv, M, K, N, dx, st)));
       else AQT_TRY((launch_dx<2, 2>(dy, wq_frag, sv, M, K, N, dx, st)));
     } else {
       bwd_dx_general_kernel<<<static_cast<int>(cdiv(M * K, kThreads)), kThreads, 0, st>>>(

@@ -275,6 +275,46 @@ def test_dense_bwd_masks_and_zero_groups(M, K, N):
     assert (host(dw2)[:, 5] == 0).all() and host(dw2)[:, 4].any()
 
 
+DX_WIDE_CASES = [
+    # M, K, N, masked        dX tiles need >= 512 (128 x 256) or >= 256 (128 x 512) of them
+    (22016, 768, 64, False),     # 128 x 256 tiles, four wavefronts
+    (16400, 1024, 96, False),    # 128 x 512 tiles, eight wavefronts, ragged M
+    (16384, 512, 64, True),      # the same with a clip mask
+]
+
+
+@pytest.mark.parametrize("M,K,N,masked", DX_WIDE_CASES)
+def test_dense_bwd_dx_wide_tiles_sampled(M, K, N, masked):
+    say("dx wide tiles", M, K, N, masked)
+    c = inputs.small_case(67 + K, M, K, N, 8, 4)
+    sv = B.Saved(M, K, N, 4, masks=masked)
+    if masked:
+        # a scale that is too small for a few elements makes the mask non-trivial
+        s_x = np.array([np.abs(c.x).max() / 127 / 1.5], F)
+        xq_ref, mx_ref = oracle.quantize_with_scale(c.x, 8, oracle.AXIS_ALL, s_x)
+        wq_ref, sw_ref = oracle.quantize(c.w, 4, 0)
+        assert 0 < (mx_ref == 0).sum() < mx_ref.size
+        B.aqt_quantize_with_scale(dev(c.x), 8, B.AQT_AXIS_ALL, dev(s_x), q=sv.xq, clip_mask=sv.mask_x)
+        B.aqt_quantize_weights(dev(c.w), 4, wq_packed=sv.wq_packed, s_w=sv.s_w, wq_kn=sv.wq_kn,
+                               clip_mask_w=sv.mask_w)
+        sv.s_x.copy_(dev(s_x))
+    else:
+        wq_ref, sw_ref = oracle.quantize(c.w, 4, 0)
+        mx_ref = None
+        B.aqt_dense_fwd(dev(c.x), dev(c.w), 8, 4, saved=sv)
+    dx, _, _ = B.aqt_dense_bwd(dev(c.dy), sv, 8, 4, want_dw=False)
+    dx_h = host(dx)
+    rng = np.random.default_rng(3)
+    im = np.r_[rng.integers(0, M, 4000), [0, M - 1, M - 1]]
+    ik = np.r_[rng.integers(0, K, 4000), [0, K - 1, 0]]
+    r, ra = oracle.dense_bwd_dx_sampled(c.dy, wq_ref, sw_ref, im, ik)
+    if masked:
+        r = r * mx_ref[im, ik]
+        assert (dx_h[mx_ref == 0] == 0).all()
+    err = np.abs(dx_h[im, ik] - r)
+    assert (err <= 1e-4 * ra + 1e-37).all() and err.max() <= 1e-4 * np.abs(r).max()
+
+
 def test_backward_is_bit_reproducible_and_stream_ordered():
     # dW folds its slabs in a fixed order: two runs give identical bits; the same work
     # enqueued on a side stream (the stream argument of the C ABI) gives them too
@@ -431,8 +471,9 @@ def test_dense_fwd_weight_only_against_oracle(M, K, N, bw, epi, with_bias):
 
 
 WONLY_WIDE_CASES = [
-    (16384, 128, 2048, 4, 0),        # 128 x 256 tiles
-    (16500, 96, 1024, 8, 2),         # wide GLU tiles, ragged M
+    (16384, 128, 2048, 4, 0),        # 128 x 512 tiles, eight wavefronts
+    (16500, 96, 1024, 8, 2),         # the same with GLU, ragged M
+    (22016, 64, 768, 4, 1),          # 128 x 256 tiles (768 is not a multiple of 512)
 ]
 
 
@@ -452,6 +493,9 @@ def test_dense_fwd_weight_only_wide_tiles_sampled(M, K, N, bw, epi):
     tol_v = 1e-4 * mag + 1e-37
     if epi == 0:
         assert (np.abs(got - pre) <= tol_v).all()
+    elif epi == 1:
+        ref = pre / (1 + np.exp(-pre))
+        assert (np.abs(got - ref) <= 1e-6 * np.abs(ref) + 1.1 * tol_v).all()
     else:
         gate, gmag = oracle.dense_fwd_wonly_sampled(c.x, wq_ref, sw_ref, im, ij + out_cols)
         sg = 1 / (1 + np.exp(-gate))
