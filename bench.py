@@ -42,8 +42,8 @@ MEASURED_TRAFFIC_MIB = {
     (1, "quantize_w"): (4.0 + 4.1, 0.0 + 1.5),
     (0, "fwd_gemm"): (1.0 + 259.8, 1.0 + 520.0),         # fragment re-order + contraction
     (1, "fwd_gemm"): (1.0 + 271.0, 1.0 + 130.1),
-    (0, "bwd_dx"): (2.0 + 573.0, 2.0 + 128.0),
-    (1, "bwd_dx"): (2.0 + 151.1, 2.0 + 512.0),
+    (0, "bwd_dx"): (2.0 + 544.2, 2.0 + 128.2),
+    (1, "bwd_dx"): (2.0 + 201.3, 2.0 + 512.9),
     (0, "bwd_dw"): (544.2 + 64.1, 64.0 + 4.0),           # slab partials + fold
     (1, "bwd_dw"): (256.2 + 64.1, 64.0 + 4.0),
 }
