@@ -293,6 +293,11 @@ def main():
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = seg_traffic(*dom_key)
     roof["kernel"] = f"{layers[dom_key[0]]['c'].name}.{dom_key[1]}"
+    if dom_key[1] in ("bwd_dx", "bwd_dw"):
+        roof["note"] = ("achieved counts the algorithmic 2MNK; the kernel issues 4MNK MFMA flops (bf16 hi/lo split of the "
+                        "float32 operand). Measured limits on this part: about 64 B/clk/CU of operand delivery into "
+                        "registers (LDS and L2 together) caps a 64x128 wavefront tile near 0.65 MFMA utilisation, and "
+                        "the shader clock sits at 1.8-1.9 GHz under these kernels (peak assumes 2.4 GHz)")
     roof["avg_ms"] = seg_ms[dom_key]
 
     cpu = None

@@ -184,7 +184,6 @@ __global__ __launch_bounds__(kThreads) void codes_to_bf16_frag_kernel(const int8
 // =====================================================================================
 constexpr int kSN = 32;      // contraction elements per stage
 constexpr int kRowB = 64;    // LDS row: 32 bf16
-constexpr int kPitch = 80;   // padded row pitch used by the dW kernel
 
 __device__ __forceinline__ int swz(int row) { return (row >> 1) & 3; }
 
@@ -320,7 +319,6 @@ __device__ __forceinline__ void f32_codes_tile(
   };
 
   const int NT = N / kSN;
-  const int last = (NT - 1) * kSN;
   auto stage_idx = [&](int s) { return s < NT - 1 ? s : NT - 1; };
   auto stage_n0 = [&](int s) { return stage_idx(s) * kSN; };
 

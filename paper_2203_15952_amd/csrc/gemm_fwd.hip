@@ -151,6 +151,7 @@ __global__ __launch_bounds__(kThreads, 2) void dense_fwd_mfma_kernel(
   // time on different L2s and each fetches the activation tile itself; measured, that
   // costs less than what remapping ids to one contiguous run of tiles per XCD loses
   // on the output side (the tiles in flight then write to eight distant regions).
+  (void)tiles_m;
   const int id = blockIdx.x;
   const int bm = id / tiles_n, bn = id - bm * tiles_n;
   // A ragged last row tile is shifted up to end at row M: it recomputes a few rows
