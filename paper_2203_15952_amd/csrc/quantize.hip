@@ -385,9 +385,9 @@ aqt_status launch_quantize(const float *x, int64_t rows, int64_t cols, int64_t l
     const bool flat = (ldx == cols) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) &&
                       (reinterpret_cast<uintptr_t>(q) % 4 == 0);
     if (flat && !mask) {
-      // up to 2048 blocks = 8 per CU, each on its own contiguous run of the tensor;
+      // up to 4096 blocks = 16 per CU, each on its own contiguous run of the tensor;
       // every thread keeps four 16-byte loads in flight.
-      int g = grid_for(n / 4, kThreads * 4, 2048);
+      int g = grid_for(n / 4, kThreads * 4, kMaxPartials);
       const int64_t per4 = cdiv(cdiv(n / 4, g), kThreads) * kThreads;
       g = static_cast<int>(per4 > 0 ? cdiv(n / 4, per4) : 1);
       if (g < 1) g = 1;
@@ -432,7 +432,7 @@ aqt_status launch_quantize_with_absmax(const float *x, int64_t rows, int64_t col
   const bool flat = (ldx == cols) && (reinterpret_cast<uintptr_t>(x) % 16 == 0) &&
                     (reinterpret_cast<uintptr_t>(q) % 4 == 0);
   if (flat && !mask) {
-    int g = grid_for(n / 4, kThreads * 4, 2048);
+    int g = grid_for(n / 4, kThreads * 4, kMaxPartials);
     const int64_t per4 = cdiv(cdiv(n / 4, g), kThreads) * kThreads;
     g = static_cast<int>(per4 > 0 ? cdiv(n / 4, per4) : 1);
     if (g < 1) g = 1;
