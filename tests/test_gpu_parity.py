@@ -636,3 +636,29 @@ def test_quantize_more_than_2_31_elements():
     assert int(flat_q[n - 1].item()) == -127
     del x, q
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("bx,bw", [(2, 2), (5, 3), (7, 6), (3, 8)])
+def test_other_bit_widths_forward_and_backward(bx, bw):
+    # Sec. 2.2 gives the rule for 8 and 4 bits; the same rule (qmax = 2^(b-1) - 1) is accepted for
+    # any width in 2..8: codes stay inside [-qmax, qmax], weights up to 4 bits are stored packed
+    say("other bit widths", bx, bw)
+    for (M, K, N) in [(256, 128, 128), (33, 20, 11)]:
+        c = inputs.small_case(100 * bx + bw + M, M, K, N, bx, bw, 0, with_bias=True)
+        ora = oracle.dense_fwd(c.x, c.w, bx, bw, c.bias, 0)
+        qx, qw = (1 << (bx - 1)) - 1, (1 << (bw - 1)) - 1
+        assert np.abs(ora["xq"]).max() == qx and np.abs(ora["wq"]).max() == qw
+        sv = B.Saved(M, K, N, bw)
+        y = B.aqt_dense_fwd(dev(c.x), dev(c.w), bx, bw, bias=dev(c.bias), saved=sv)
+        np.testing.assert_array_equal(host(sv.xq), ora["xq"])
+        np.testing.assert_array_equal(host(sv.wq_kn), ora["wq"])
+        np.testing.assert_array_equal(host(sv.s_x), ora["s_x"])
+        np.testing.assert_array_equal(host(sv.s_w), ora["s_w"])
+        np.testing.assert_array_equal(host(B.aqt_unpack_weights(sv.wq_packed, K, N, bw)), ora["wq"])
+        _, acc = B.aqt_dense_fwd_q(sv.xq, sv.s_x, sv.wq_packed, sv.s_w, N, bx, bw, want_acc=True)
+        np.testing.assert_array_equal(host(acc), ora["acc"])
+        check_forward(host(y), ora, ora["s_x"][0], ora["s_w"], c.bias, 0)
+        g = oracle.dense_bwd(c.dy, ora["xq"], ora["s_x"][0], ora["wq"], ora["s_w"])
+        dx, dw, _ = B.aqt_dense_bwd(dev(c.dy), sv, bx, bw)
+        check_grad(host(dx), g["dx"], g["dx_abs"], "dx")
+        check_grad(host(dw), g["dw"], g["dw_abs"], "dw")
