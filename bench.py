@@ -126,9 +126,16 @@ def main():
             B.aqt_dense_bwd(L["dy"], sv, c.bits_x, c.bits_w, dw=L["dw"], want_dx=False, ws=L["ws_b"])
             mark(5)
 
+    t_w = time.perf_counter()
     for _ in range(args.warmup):
         run_step()
     torch.cuda.synchronize()
+    # The card needs on the order of 100 ms of load to settle at its steady clocks; when the
+    # requested warm-up is shorter than that, keep stepping (untimed) until it has had them.
+    while time.perf_counter() - t_w < 0.15:
+        for _ in range(10):
+            run_step()
+        torch.cuda.synchronize()
 
     # Untimed probe pass with an event around every segment: the per-kernel table, and which
     # segment dominates.  (Twelve event records per step cost about 3 % of a step, so the timed
