@@ -54,6 +54,9 @@ def test_workspace_sizes_are_shape_functions(L):
     f = B.aqt_workspace_bytes(B.AQT_OP_DENSE_FWD, 12800, 512, 2048, 8, 4)
     assert f >= 12800 * 512 + 2048 * 256 + 2048 * 4 + q
     assert B.aqt_workspace_bytes(B.AQT_OP_DENSE_BWD, 65536, 512, 2048) > 0
+    assert B.aqt_workspace_bytes(B.AQT_OP_DENSE_FWD_Q, 1, 512, 2048) >= 512 * 2048          # int8 fragments
+    assert B.aqt_workspace_bytes(B.AQT_OP_DENSE_FWD_WONLY, 1, 512, 2048) >= 2 * 512 * 2048  # bf16 fragments
+    assert B.aqt_workspace_bytes(B.AQT_OP_QUANTIZE_WEIGHTS, 1, 512, 2048) >= 16 * 2048 * 4   # slab maxima
     assert B.aqt_workspace_bytes(99, 1, 1, 1) == 0
     assert B.aqt_workspace_bytes(B.AQT_OP_DENSE_FWD, 0, 512, 2048, 8, 4) == 0
 
