@@ -300,6 +300,10 @@ def main():
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = seg_traffic(*dom_key)
     roof["kernel"] = f"{layers[dom_key[0]]['c'].name}.{dom_key[1]}"
+    roof["launches"] = {"quantize_x": "abs-max pass + code pass", "quantize_w": "slab maxima + quantize/pack",
+                        "fwd_gemm": "fragment re-order (about 5 us) + contraction",
+                        "bwd_dx": "fragment re-order (about 4 us) + contraction",
+                        "bwd_dw": "contraction + slab fold (about 12 us)"}[dom_key[1]]
     if dom_key[1] in ("bwd_dx", "bwd_dw"):
         roof["note"] = ("achieved counts the algorithmic 2MNK; the kernel issues 4MNK MFMA flops (bf16 hi/lo split of the "
                         "float32 operand). Measured limits on this part: about 64 B/clk/CU of operand delivery into "
