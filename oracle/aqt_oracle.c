@@ -305,8 +305,11 @@ int oracle_dense_fwd(const float *x, const float *w, int64_t M, int64_t K, int64
  *   dx[m,k] = mask_x[m,k] * sum_n dy[m,n] * s_w[n] * wq[k,n]
  *   dw[k,n] = mask_w[k,n] * s_x * sum_m xq[m,k] * dy[m,n]
  *   dbias[n] = sum_m dy[m,n]
- * mask_x / mask_w: nullable byte masks (NULL = all ones).  Any of dx, dw, dbias
- * may be NULL.  dx_abs / dw_abs (nullable) receive the sum of the magnitudes
+ * mask_x / mask_w: nullable byte masks.  A NULL mask stands for the mask abs-max
+ * scaling produces: 1 wherever the group's scale is non-zero, 0 where it is zero
+ * (Fig. 2's divide_no_nan passes no gradient through a zero scale; with a
+ * non-zero scale the rounded value never leaves [-qmax, qmax], so nothing else
+ * is ever masked).  Any of dx, dw, dbias may be NULL.  dx_abs / dw_abs (nullable) receive the sum of the magnitudes
  * of the terms, the yardstick a condition-aware comparison needs.
  */
 void oracle_dense_bwd(const float *dy, const int8_t *xq, float s_x, const uint8_t *mask_x,
@@ -323,7 +326,7 @@ void oracle_dense_bwd(const float *dy, const int8_t *xq, float s_x, const uint8_
           s += t;
           sa += fabs(t);
         }
-        double g = (mask_x && !mask_x[m * K + k]) ? 0.0 : 1.0;
+        double g = mask_x ? (mask_x[m * K + k] ? 1.0 : 0.0) : (s_x != 0.0f ? 1.0 : 0.0);
         dx[m * K + k] = g * s;
         if (dx_abs) dx_abs[m * K + k] = sa;
       }
@@ -338,7 +341,7 @@ void oracle_dense_bwd(const float *dy, const int8_t *xq, float s_x, const uint8_
           s += t;
           sa += fabs(t);
         }
-        double g = (mask_w && !mask_w[k * N + n]) ? 0.0 : 1.0;
+        double g = mask_w ? (mask_w[k * N + n] ? 1.0 : 0.0) : (s_w[n] != 0.0f ? 1.0 : 0.0);
         dw[k * N + n] = g * (double)s_x * s;
         if (dw_abs) dw_abs[k * N + n] = fabs((double)s_x) * sa;
       }

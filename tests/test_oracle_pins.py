@@ -423,6 +423,19 @@ def test_masks_gate_gradients_and_zero_groups():
     assert g2["dx"][1, 3] == 0
     keep = mx2.astype(bool)
     np.testing.assert_array_equal(g2["dx"][keep], g["dx"][keep])
+    # no mask given = the mask abs-max scaling produces: zero where the group's scale is zero
+    # (divide_no_nan in Fig. 2 passes no gradient), one elsewhere.  Expected values from a
+    # float64 library matmul of the operands, with the zero-scale channel blanked by hand.
+    g3 = oracle.dense_bwd(dy, xq, s_x[0], wq, s_w)
+    dw_lib = float(s_x[0]) * (xq.astype(np.float64).T @ dy.astype(np.float64))
+    assert (dw_lib[:, 2] != 0).any()               # the bilinear form alone would not give zero here
+    dw_lib[:, 2] = 0
+    np.testing.assert_allclose(g3["dw"], dw_lib, rtol=1e-12, atol=0)
+    dx_lib = (dy.astype(np.float64) * s_w.astype(np.float64)) @ wq.astype(np.float64).T
+    np.testing.assert_allclose(g3["dx"], dx_lib, rtol=1e-12, atol=1e-300)
+    # a zero activation scale (all-zero activations) passes nothing to dx, but dw's mask is the weights'
+    g4 = oracle.dense_bwd(dy, np.zeros_like(xq), 0.0, wq, s_w)
+    assert not g4["dx"].any() and (dx_lib != 0).any()
 
 
 # ----------------------------------------------------------------------------
