@@ -144,7 +144,8 @@ aqt_status aqt_unpack_weights(const void *wq_packed, int64_t K, int64_t N, int b
  *   xq [M,K] int8; s_x device scalar; wq_packed as aqt_packed_weight_bytes();
  *   s_w [N]; bias nullable [N]; y [M,N] float32 ([M,N/2] for GLU);
  *   acc_out nullable [M,N] int32, the raw accumulators.
- * Requires K * qmax_x * qmax_w < 2^31 / 16 (else AQT_ERR_UNSUPPORTED).
+ * Requires K * qmax_x * qmax_w < 2^31, and < 2^31 / 16 for bits_w <= 4 (packed codes are
+ * expanded to 16 * code on their way into the matrix cores); else AQT_ERR_UNSUPPORTED.
  * Needs aqt_workspace_bytes(AQT_OP_DENSE_FWD_Q, M, K, N, ., .) of workspace (K*N
  * bytes: the weight codes re-ordered for the matrix cores, rewritten per call).
  */

@@ -41,9 +41,10 @@ FwdWorkspace carve_fwd(void *ws, int64_t M, int64_t K, int64_t N, int bits_w) {
 
 bool shape_ok(int64_t a, int64_t b) { return a >= 1 && b >= 1; }
 
-// int32 accumulation must hold 16 * K * qmax_x * qmax_w (the int4 path carries a factor 16).
+// The int32 accumulator must hold K * qmax_x * qmax_w; packed (<= 4 bit) weights enter the
+// matrix cores as 16 * code, so their sums carry a factor 16 until the final shift.
 bool acc_fits(int64_t K, int bits_x, int bits_w) {
-  const int64_t lim = (int64_t(1) << 31) / 16;
+  const int64_t lim = (int64_t(1) << 31) / (packed4(bits_w) ? 16 : 1);
   return K * qmax_of(bits_x) * qmax_of(bits_w) < lim;
 }
 

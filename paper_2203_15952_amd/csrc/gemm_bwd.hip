@@ -762,7 +762,6 @@ struct BwdPlan {
   bool dx_mfma, dw_mfma;
   bool dx_wide;    // 128 x 256 tiles (else 128 x 128)
   bool dx_wide8;   // 128 x 512 tiles, eight wavefronts: the gradient tile is staged once for four column wavefronts
-  bool dw_wide;    // 256 x 128 tiles (else 128 x 128)
   int slabs;
   int m_per_slab;
   size_t off_bf, off_part, off_bias, total;
@@ -775,9 +774,8 @@ BwdPlan plan_bwd(int64_t M, int64_t K, int64_t N) {
   p.dx_mfma = fits32 && (N % kSN == 0) && (K % 128 == 0) && (M >= 128);
   p.dx_wide = (K % 256 == 0) && cdiv(M, 128) * (K / 256) >= 512;
   p.dx_wide8 = p.dx_wide && (K % 512 == 0) && cdiv(M, 128) * (K / 512) >= 256;
-  // dW: tiles over K x N, slabs over M
+  // dW: 256 x 128 tiles over K x N, slabs over M
   p.dw_mfma = fits32 && (K % 256 == 0) && (N % 128 == 0);
-  p.dw_wide = true;
   const int64_t tiles = p.dw_mfma ? (K / 256) * (N / 128) : 1;
   int64_t slabs = p.dw_mfma ? cdiv(512, tiles) : 1;
   if (slabs > 64) slabs = 64;
@@ -912,7 +910,9 @@ aqt_status launch_dense_bwd(const float *dy, const aqt_saved *sv, int64_t M, int
   (void)ws_bytes;
   const BwdPlan p = plan_bwd(M, K, N);
   uint8_t *base = static_cast<uint8_t *>(ws);
-  const bool dy_aligned = reinterpret_cast<uintptr_t>(dy) % 16 == 0;
+  // 16-byte vector accesses on dy and on the buffers carved from the workspace (their
+  // offsets are multiples of 256); anything else takes the general kernels
+  const bool dy_aligned = reinterpret_cast<uintptr_t>(dy) % 16 == 0 && reinterpret_cast<uintptr_t>(ws) % 16 == 0;
   if (dx) {
     if (p.dx_mfma && dy_aligned && reinterpret_cast<uintptr_t>(sv->s_w) % 16 == 0 &&
         reinterpret_cast<uintptr_t>(sv->wq_kn) % 8 == 0) {

@@ -81,7 +81,12 @@ def test_argument_errors_are_synchronous_and_touch_no_gpu(L):
     assert L.aqt_dense_fwd_q(one, one, one, one, 4, 4, 5, 8, 4, none, B.AQT_EPI_GLU, one, none, none, 0, none) == B.AQT_ERR_UNSUPPORTED
     assert L.aqt_dense_fwd_q(one, one, one, one, 4, 4, 4, 8, 4, none, 3, one, none, none, 0, none) == B.AQT_ERR_INVALID_ARG
     assert L.aqt_dense_fwd_q(one, one, one, one, 4, 200000, 4, 8, 4, none, 0, one, none, none, 0, none) == B.AQT_ERR_UNSUPPORTED
-    assert L.aqt_dense_fwd_q(one, one, one, one, 4, 9000, 4, 8, 8, none, 0, one, none, none, 0, none) == B.AQT_ERR_UNSUPPORTED
+    # int8 weights are not expanded, so the factor 16 does not apply to them: K = 9000 fits (the call
+    # then fails on its missing workspace), K = 140000 does not
+    assert L.aqt_dense_fwd_q(one, one, one, one, 4, 9000, 4, 8, 8, none, 0, one, none, none, 0, none) == B.AQT_ERR_WORKSPACE
+    assert L.aqt_dense_fwd_q(one, one, one, one, 4, 140000, 4, 8, 8, none, 0, one, none, none, 0, none) == B.AQT_ERR_UNSUPPORTED
+    assert L.aqt_dense_fwd_q(one, one, one, one, 4, 9000, 4, 8, 4, none, 0, one, none, none, 0, none) == B.AQT_ERR_WORKSPACE
+    assert L.aqt_dense_fwd_q(one, one, one, one, 4, 160000, 4, 8, 4, none, 0, one, none, none, 0, none) == B.AQT_ERR_UNSUPPORTED
     assert L.aqt_dense_fwd_q(one, one, one, one, 4, 4, 4, 8, 4, none, 0, one, none, none, 0, none) == B.AQT_ERR_WORKSPACE
     assert L.aqt_dense_fwd_q(one, one, one, one, 4, 4, 4, 8, 4, none, 0, one, none, one, 8, none) == B.AQT_ERR_WORKSPACE
     assert L.aqt_dense_fwd_q_absmax(one, one, one, one, 4, 4, 4, 8, 4, none, 0, one, none, one, 1 << 20, none) == B.AQT_ERR_INVALID_ARG

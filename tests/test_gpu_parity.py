@@ -8,7 +8,7 @@ import torch
 import oracle
 from paper_2203_15952_amd import binding as B
 from paper_2203_15952_amd import inputs
-from parity_util import check_float_forward, check_forward, check_grad, unpack_mask
+from parity_util import REL_F, check_float_forward, check_forward, check_grad, unpack_mask
 
 pytestmark = pytest.mark.gpu
 F = np.float32
@@ -205,6 +205,10 @@ def test_dense_fwd_big_tiles_sampled():
     np.testing.assert_array_equal(host(wq_kn), ora_wq)
     y, acc = B.aqt_dense_fwd_q(xq, s_x, wq, s_w, N, 8, 4, want_acc=True)
     acc_h, y_h = host(acc), host(y)
+    rows = tile_rows(M)
+    ora = oracle.dense_fwd_q(ora_xq[rows], ora_sx[0], ora_wq, ora_sw)
+    np.testing.assert_array_equal(acc_h[rows], ora["acc"])
+    check_forward(y_h[rows], ora, ora_sx[0], ora_sw, None, 0)
     # an int64 library matmul of the codes on a row slab, plus scattered samples
     rows = np.r_[0:64, 8000:8064, M - 64:M]
     ref = ora_xq[rows].astype(np.int64) @ ora_wq.astype(np.int64)
@@ -268,10 +272,14 @@ def test_dense_bwd_masks_and_zero_groups(M, K, N):
     check_grad(dx_h, g["dx"], g["dx_abs"], "dx")
     check_grad(dw_h, g["dw"], g["dw_abs"], "dw")
     assert (dx_h[mx_ref == 0] == 0).all() and (dw_h[mw_ref == 0] == 0).all()
-    # NULL masks mean "scale is non-zero": the zero channel still gets no gradient
+    # no masks given: "scale is non-zero" on both sides, the zero channel still gets no gradient
     sv2 = B.Saved(M, K, N, 4)
     B.aqt_dense_fwd(dev(c.x), dev(c.w), 8, 4, saved=sv2)
-    _, dw2, _ = B.aqt_dense_bwd(dev(c.dy), sv2, 8, 4, want_dx=False)
+    ora2 = oracle.dense_fwd(c.x, c.w, 8, 4)
+    g2 = oracle.dense_bwd(c.dy, ora2["xq"], ora2["s_x"][0], ora2["wq"], ora2["s_w"])
+    dx2, dw2, _ = B.aqt_dense_bwd(dev(c.dy), sv2, 8, 4)
+    check_grad(host(dx2), g2["dx"], g2["dx_abs"], "dx")
+    check_grad(host(dw2), g2["dw"], g2["dw_abs"], "dw")
     assert (host(dw2)[:, 5] == 0).all() and host(dw2)[:, 4].any()
 
 
@@ -313,6 +321,19 @@ def test_dense_bwd_dx_wide_tiles_sampled(M, K, N, masked):
         assert (dx_h[mx_ref == 0] == 0).all()
     err = np.abs(dx_h[im, ik] - r)
     assert (err <= 1e-4 * ra + 1e-37).all() and err.max() <= 1e-4 * np.abs(r).max()
+    # whole row tiles: the first, one in the middle, and the last one (shifted up when M is ragged)
+    rows = tile_rows(M)
+    xq_rows = np.zeros((rows.size, K), np.int8)     # unused by dX
+    g = oracle.dense_bwd(c.dy[rows], xq_rows, 1.0, wq_ref, sw_ref, None if mx_ref is None else mx_ref[rows], None,
+                         want_dw=False, want_dbias=False)
+    check_grad(dx_h[rows], g["dx"], g["dx_abs"], "dx tiles")
+
+
+def tile_rows(M, BM=128):
+    """Rows of the first row tile, of one in the middle, and the last 2 * BM rows (the last
+    tile, shifted up to end at row M when M is ragged, and what it overlaps)."""
+    mid = (M // BM // 2) * BM
+    return np.unique(np.r_[0:BM, mid:mid + BM, max(0, M - 2 * BM):M])
 
 
 def test_backward_is_bit_reproducible_and_stream_ordered():
@@ -490,9 +511,10 @@ def test_dense_fwd_weight_only_wide_tiles_sampled(M, K, N, bw, epi):
     ij = np.r_[rng.integers(0, out_cols, 3000), [0, out_cols - 1]]
     pre, mag = oracle.dense_fwd_wonly_sampled(c.x, wq_ref, sw_ref, im, ij)
     got = y_h[im, ij].astype(np.float64)
-    tol_v = 1e-4 * mag + 1e-37
+    tol_v = REL_F * mag + 1e-37
     if epi == 0:
         assert (np.abs(got - pre) <= tol_v).all()
+        assert np.abs(got - pre).max() <= REL_F * np.abs(pre).max()
     elif epi == 1:
         ref = pre / (1 + np.exp(-pre))
         assert (np.abs(got - ref) <= 1e-6 * np.abs(ref) + 1.1 * tol_v).all()
@@ -500,8 +522,32 @@ def test_dense_fwd_weight_only_wide_tiles_sampled(M, K, N, bw, epi):
         gate, gmag = oracle.dense_fwd_wonly_sampled(c.x, wq_ref, sw_ref, im, ij + out_cols)
         sg = 1 / (1 + np.exp(-gate))
         ref = pre * sg
-        tol = 1e-6 * np.abs(ref) + sg * tol_v + 0.25 * np.abs(pre) * (1e-4 * gmag) + 1e-37
+        tol = 1e-6 * np.abs(ref) + sg * tol_v + 0.25 * np.abs(pre) * (REL_F * gmag) + 1e-37
         assert (np.abs(got - ref) <= tol).all()
+    # whole row tiles against the full oracle on those rows
+    rows = tile_rows(M)
+    ora = oracle.dense_fwd_wonly(c.x[rows], wq_ref, sw_ref, None, epi)
+    check_float_forward(y_h[rows], ora, epi)
+
+
+@pytest.mark.parametrize("layer", [0, 1])
+def test_dense_fwd_weight_only_training_step_shapes(layer):
+    # the two shapes the benchmark times this entry point on (16 and 64 contraction stages of 32)
+    c = inputs.config5()[layer]
+    say("dense fwd weight-only full size", c.M, c.K, c.N)
+    wq_ref, sw_ref = oracle.quantize(c.w, c.bits_w, 0)
+    wq, s_w, _, _ = B.aqt_quantize_weights(dev(c.w), c.bits_w)
+    y_h = host(B.aqt_dense_fwd_wonly(dev(c.x), wq, s_w, c.N, c.bits_w))
+    rng = np.random.default_rng(19)
+    im = np.r_[rng.integers(0, c.M, 4000), [0, c.M - 1]]
+    ij = np.r_[rng.integers(0, c.N, 4000), [0, c.N - 1]]
+    pre, mag = oracle.dense_fwd_wonly_sampled(c.x, wq_ref, sw_ref, im, ij)
+    err = np.abs(y_h[im, ij] - pre)
+    assert (err <= REL_F * mag + 1e-37).all() and err.max() <= REL_F * np.abs(pre).max()
+    say("   max err / bound:", float((err / (REL_F * mag + 1e-37)).max()))
+    rows = tile_rows(c.M)
+    ora = oracle.dense_fwd_wonly(c.x[rows], wq_ref, sw_ref, None, 0)
+    check_float_forward(y_h[rows], ora, 0)
 
 
 # 128 x 256 tiles are used once there are at least 512 of them
@@ -523,7 +569,7 @@ def test_dense_fwd_wide_tiles_sampled(M, K, N, bx, bw, epi):
 # the paper-shaped configurations at full size, in the launch configuration the
 # benchmark times: quantizers compared in full, contractions on sampled outputs
 # ----------------------------------------------------------------------------
-def run_full_size_case(c, n_samples=3000, backward=False):
+def run_full_size_case(c, n_samples=3000, backward=False, full_dw=False):
     say("full size", c.name, c.M, c.K, c.N, c.bits_x, c.bits_w, c.epilogue)
     xq_ref, sx_ref = oracle.quantize(c.x, c.bits_x, oracle.AXIS_ALL)
     wq_ref, sw_ref = oracle.quantize(c.w, c.bits_w, 0)
@@ -563,6 +609,12 @@ def run_full_size_case(c, n_samples=3000, backward=False):
         ref = pre * sg
         tol = 1e-6 * np.abs(ref) + sg * tol_v + 0.25 * np.abs(pre) * (1e-6 * np.abs(gate)) + 1e-37
         assert (np.abs(got - ref) <= tol).all()
+    # whole row tiles (first, middle, last): accumulators and outputs in full
+    rows = tile_rows(c.M)
+    ora = oracle.dense_fwd_q(xq_ref[rows], sx_ref[0], wq_ref, sw_ref, None, c.epilogue)
+    np.testing.assert_array_equal(acc_h[rows], ora["acc"])
+    check_forward(y_h[rows], ora, sx_ref[0], sw_ref, None, c.epilogue)
+    del acc_h
     if backward:
         dy_d = dev(c.dy)
         dx, dw, _ = B.aqt_dense_bwd(dy_d, sv, c.bits_x, c.bits_w)
@@ -577,6 +629,11 @@ def run_full_size_case(c, n_samples=3000, backward=False):
         err = np.abs(dw_h[ik2, in2] - r)
         assert (err <= 1e-4 * ra + 1e-37).all() and err.max() <= 1e-4 * np.abs(r).max()
         say("   bwd max err / 1e-4 bound:", float((err / (1e-4 * ra + 1e-37)).max()))
+        g = oracle.dense_bwd(c.dy[rows], xq_ref[rows], sx_ref[0], wq_ref, sw_ref, want_dw=False, want_dbias=False)
+        check_grad(dx_h[rows], g["dx"], g["dx_abs"], "dx tiles")
+        if full_dw:      # every element of dW, all slabs and tiles
+            g = oracle.dense_bwd(c.dy, xq_ref, sx_ref[0], wq_ref, sw_ref, want_dx=False, want_dbias=False)
+            check_grad(dw_h, g["dw"], g["dw_abs"], "dw in full")
 
 
 @pytest.mark.parametrize("cfg", [2, 3, 4])
@@ -587,7 +644,7 @@ def test_conformer_configs_full_size(cfg):
 
 def test_training_step_full_size():
     for c in inputs.config5():
-        run_full_size_case(c, backward=True)
+        run_full_size_case(c, backward=True, full_dw=True)
         torch.cuda.empty_cache()
 
 
