@@ -47,6 +47,7 @@ typedef int aqt_status;
 #define AQT_ERR_WORKSPACE 3   /* ws is NULL or smaller than aqt_workspace_bytes()         */
 #define AQT_ERR_HIP 4         /* a HIP call failed; see aqt_last_hip_error()              */
 #define AQT_ERR_NONFINITE 5   /* only ever written to *dev_status by a kernel             */
+#define AQT_ERR_SCRATCH 6     /* aqt_dense_fwd_q_static: K * N exceeds the static scratch */
 
 /* `axis` names the REDUCED axes, as the `axis` argument of Fig. 2 does. */
 #define AQT_AXIS_ALL (-1) /* one scale for the whole tensor (activations)              */
@@ -153,6 +154,25 @@ aqt_status aqt_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq_pa
                            int64_t M, int64_t K, int64_t N, int bits_x, int bits_w, const float *bias,
                            int epilogue, float *y, int32_t *acc_out, void *ws, size_t ws_bytes,
                            void *stream);
+
+/*
+ * aqt_dense_fwd_q for callers that cannot allocate or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments (without acc_out and the workspace), same kernels, bit-identical y.
+ * The scratch the contraction needs (the weight codes re-ordered for the matrix
+ * cores, K * N bytes) lives in a static device array of AQT_STATIC_SCRATCH_BYTES
+ * inside the library, one copy per GPU, held until the process ends; the call
+ * allocates and frees nothing.  K * N above that size returns AQT_ERR_SCRATCH and
+ * enqueues nothing.  The device the stream belongs to must be current.  All calls
+ * on one GPU share the array (it keeps the last call's contents, every call
+ * rewrites the part it reads): calls that overlap in time on one GPU, e.g. on two
+ * streams, race; order them.
+ */
+#define AQT_STATIC_SCRATCH_BYTES (4u << 20) /* 4 MiB: up to K * N = 2048 * 2048 */
+size_t aqt_static_scratch_bytes(void);
+aqt_status aqt_dense_fwd_q_static(const int8_t *xq, const float *s_x, const void *wq_packed,
+                                  const float *s_w, int64_t M, int64_t K, int64_t N, int bits_x, int bits_w,
+                                  const float *bias, int epilogue, float *y, void *stream);
 
 /*
  * Producer-side abs-max for a chain of quantized layers.  The next layer's

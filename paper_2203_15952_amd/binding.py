@@ -16,7 +16,7 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libaqt.so")
 
-AQT_OK, AQT_ERR_INVALID_ARG, AQT_ERR_UNSUPPORTED, AQT_ERR_WORKSPACE, AQT_ERR_HIP, AQT_ERR_NONFINITE = range(6)
+AQT_OK, AQT_ERR_INVALID_ARG, AQT_ERR_UNSUPPORTED, AQT_ERR_WORKSPACE, AQT_ERR_HIP, AQT_ERR_NONFINITE, AQT_ERR_SCRATCH = range(7)
 AQT_AXIS_ALL, AQT_AXIS_ROWS, AQT_AXIS_COLS = -1, 0, 1
 AQT_EPI_NONE, AQT_EPI_SWISH, AQT_EPI_GLU = 0, 1, 2
 AQT_OP_QUANTIZE, AQT_OP_QUANTIZE_WEIGHTS, AQT_OP_DENSE_FWD, AQT_OP_DENSE_FWD_Q, AQT_OP_DENSE_BWD, AQT_OP_DENSE_FWD_WONLY = range(6)
@@ -25,7 +25,8 @@ AQT_OP_QUANTIZE, AQT_OP_QUANTIZE_WEIGHTS, AQT_OP_DENSE_FWD, AQT_OP_DENSE_FWD_Q, 
 SYMBOLS = ["aqt_status_string", "aqt_last_hip_error", "aqt_version", "aqt_workspace_bytes",
            "aqt_packed_weight_bytes", "aqt_quantize", "aqt_quantize_with_scale", "aqt_quantize_weights",
            "aqt_unpack_weights", "aqt_dense_fwd_q", "aqt_dense_fwd_q_absmax", "aqt_quantize_with_absmax",
-           "aqt_dense_fwd_wonly", "aqt_dense_fwd", "aqt_dense_bwd"]
+           "aqt_dense_fwd_wonly", "aqt_dense_fwd", "aqt_dense_bwd", "aqt_dense_fwd_q_static",
+           "aqt_static_scratch_bytes"]
 
 
 class AqtError(RuntimeError):
@@ -71,6 +72,8 @@ def lib() -> ctypes.CDLL:
                                       _vp, _sz, _vp]
         L.aqt_dense_fwd_q_absmax.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp,
                                              _vp, _vp, _sz, _vp]
+        L.aqt_dense_fwd_q_static.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _vp]
+        L.aqt_static_scratch_bytes.restype = _sz
         L.aqt_quantize_with_absmax.argtypes = [_vp, _i64, _i64, _i64, _int, _vp, _vp, _vp, _vp, _vp, _vp]
         L.aqt_dense_fwd_wonly.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _int, _vp, _int, _vp, _vp, _sz, _vp]
         L.aqt_dense_fwd.argtypes = [_vp, _vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp,
@@ -199,6 +202,22 @@ def aqt_dense_fwd_q(xq, s_x, wq_packed, s_w, N: int, bits_x: int, bits_w: int, *
                                _ptr(bias), epilogue, _ptr(y), _ptr(acc_out), _ptr(ws), ws.numel(), _stream())
     _check(st, "aqt_dense_fwd_q")
     return y, acc_out
+
+
+def aqt_static_scratch_bytes() -> int:
+    return int(lib().aqt_static_scratch_bytes())
+
+
+def aqt_dense_fwd_q_static(xq, s_x, wq_packed, s_w, N: int, bits_x: int, bits_w: int, *, bias=None,
+                           epilogue: int = AQT_EPI_NONE, y):
+    """aqt_dense_fwd_q_static: the caller passes every buffer, the call allocates nothing."""
+    _dev(xq, torch.int8, "xq")
+    _dev(y, torch.float32, "y")
+    M, K = xq.shape
+    st = lib().aqt_dense_fwd_q_static(_ptr(xq), _ptr(s_x), _ptr(wq_packed), _ptr(s_w), M, K, N, bits_x, bits_w,
+                                      _ptr(bias), epilogue, _ptr(y), _stream())
+    _check(st, "aqt_dense_fwd_q_static")
+    return y
 
 
 def aqt_dense_fwd_q_absmax(xq, s_x, wq_packed, s_w, N: int, bits_x: int, bits_w: int, *, bias=None,

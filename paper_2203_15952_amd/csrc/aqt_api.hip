@@ -63,6 +63,7 @@ const char *aqt_status_string(aqt_status s) {
     case AQT_ERR_WORKSPACE: return "workspace missing or too small";
     case AQT_ERR_HIP: return "HIP runtime error";
     case AQT_ERR_NONFINITE: return "non-finite input";
+    case AQT_ERR_SCRATCH: return "shape needs more scratch than the library's static buffer holds";
     default: return "unknown status";
   }
 }
@@ -142,6 +143,25 @@ aqt_status aqt_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq_pa
   return launch_dense_fwd_q(xq, s_x, wq_packed, s_w, M, K, N, bits_w, bias, epilogue, y, acc_out, nullptr, ws,
                             static_cast<hipStream_t>(stream));
 }
+
+aqt_status aqt_dense_fwd_q_static(const int8_t *xq, const float *s_x, const void *wq_packed, const float *s_w,
+                                  int64_t M, int64_t K, int64_t N, int bits_x, int bits_w, const float *bias,
+                                  int epilogue, float *y, void *stream) {
+  if (!xq || !s_x || !wq_packed || !s_w || !y || !shape_ok(M, K) || N < 1) return AQT_ERR_INVALID_ARG;
+  if (epilogue != AQT_EPI_NONE && epilogue != AQT_EPI_SWISH && epilogue != AQT_EPI_GLU) return AQT_ERR_INVALID_ARG;
+  if (!bits_ok(bits_x) || !bits_ok(bits_w)) return AQT_ERR_UNSUPPORTED;
+  if (epilogue == AQT_EPI_GLU && (N % 2)) return AQT_ERR_UNSUPPORTED;
+  if (!acc_fits(K, bits_x, bits_w)) return AQT_ERR_UNSUPPORTED;
+  if (K > static_cast<int64_t>(AQT_STATIC_SCRATCH_BYTES) / N ||
+      fwd_q_workspace_bytes(K, N) > static_cast<size_t>(AQT_STATIC_SCRATCH_BYTES))
+    return AQT_ERR_SCRATCH;
+  void *ws = nullptr;
+  AQT_TRY(static_scratch_address(&ws));
+  return launch_dense_fwd_q(xq, s_x, wq_packed, s_w, M, K, N, bits_w, bias, epilogue, y, nullptr, nullptr, ws,
+                            static_cast<hipStream_t>(stream));
+}
+
+size_t aqt_static_scratch_bytes(void) { return AQT_STATIC_SCRATCH_BYTES; }
 
 aqt_status aqt_dense_fwd_q_absmax(const int8_t *xq, const float *s_x, const void *wq_packed, const float *s_w,
                                   int64_t M, int64_t K, int64_t N, int bits_x, int bits_w, const float *bias,

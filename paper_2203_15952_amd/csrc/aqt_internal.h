@@ -57,6 +57,7 @@ aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq
                               const float *bias, int epilogue, float *y, int32_t *acc_out, uint32_t *y_absmax,
                               void *ws, hipStream_t st);
 size_t fwd_q_workspace_bytes(int64_t K, int64_t N);
+aqt_status static_scratch_address(void **out);   // the library's own scratch array on the current device
 size_t fwd_wonly_workspace_bytes(int64_t K, int64_t N);
 aqt_status launch_dense_fwd_wonly(const float *x, const void *wq_packed, const float *s_w, int64_t M, int64_t K,
                                   int64_t N, int bits_w, const float *bias, int epilogue, float *y, void *ws,

@@ -5,10 +5,17 @@
 //
 // The tuned kernel is described where it is defined; shapes it does not cover take
 // a one-thread-per-output kernel with identical results.
+#include <mutex>
 #include <type_traits>
 
 #include "aqt_internal.h"
 #include "epilogue.h"
+
+// Scratch of the entry point that allocates nothing (aqt_dense_fwd_q_static): the weight
+// codes in MFMA-fragment order, K * N bytes.  Every GPU the library runs on holds its own
+// copy of this array at its own address until the process ends.  In host code the name
+// is only a handle for hipGetSymbolAddress; kernels are given the address that call returns.
+static __device__ __align__(256) uint8_t scratch[AQT_STATIC_SCRATCH_BYTES];
 
 namespace aqt {
 namespace {
@@ -369,6 +376,25 @@ aqt_status launch_mfma_epi(int epilogue, const int8_t *xq, const float *s_x, con
 }  // namespace
 
 size_t fwd_q_workspace_bytes(int64_t K, int64_t N) { return align_up(static_cast<size_t>(K) * N, 256); }
+
+// Device address of `scratch` on the current device, looked up once per device.
+aqt_status static_scratch_address(void **out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void *addr[kMaxDevices] = {};
+  int dev = 0;
+  AQT_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return AQT_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!addr[dev]) {
+    void *p = nullptr;
+    AQT_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return AQT_ERR_HIP;
+    addr[dev] = p;
+  }
+  *out = addr[dev];
+  return AQT_OK;
+}
 
 aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq_packed, const float *s_w,
                               int64_t M, int64_t K, int64_t N, int bits_w, const float *bias, int epilogue,

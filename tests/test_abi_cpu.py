@@ -33,8 +33,8 @@ def test_every_declared_symbol_is_exported(L):
 
 
 def test_status_strings_and_version(L):
-    seen = {L.aqt_status_string(i).decode() for i in range(6)}
-    assert len(seen) == 6 and "ok" in seen
+    seen = {L.aqt_status_string(i).decode() for i in range(7)}
+    assert len(seen) == 7 and "ok" in seen
     assert L.aqt_status_string(99).decode() == "unknown status"
     assert L.aqt_version() >= 100
 

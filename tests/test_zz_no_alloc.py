@@ -1,0 +1,75 @@
+"""The entry point that allocates nothing (aqt_dense_fwd_q_static, scratch in a static device
+array inside the library) against aqt_dense_fwd_q with a caller workspace: same kernels, so
+the outputs must be identical bit for bit, and both within the forward bar of the CPU oracle.
+Two calls in a row, the second on a smaller layer (the array keeps the first call's contents)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2203_15952_amd import binding as B
+from paper_2203_15952_amd import inputs
+from parity_util import check_forward
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def test_static_scratch_forward_two_calls_in_a_row():
+    cases = [(1000, 512, 1024, 8, 4, B.AQT_EPI_SWISH),    # tuned kernel, 512 KiB of scratch
+             (300, 128, 256, 8, 8, B.AQT_EPI_GLU),        # smaller layer right after: 32 KiB
+             (37, 50, 23, 8, 4, B.AQT_EPI_NONE)]          # a shape the general kernel takes (no scratch)
+    prepared = []
+    for i, (M, K, N, bx, bw, epi) in enumerate(cases):
+        print("static scratch case", M, K, N, bx, bw, epi, flush=True)
+        c = inputs.small_case(300 + i, M, K, N, bx, bw, epi, with_bias=True, with_dy=False)
+        ora = oracle.dense_fwd(c.x, c.w, bx, bw, c.bias, epi)
+        xq, s_x, _ = B.aqt_quantize(dev(c.x), bx, B.AQT_AXIS_ALL)
+        wq, s_w, _, _ = B.aqt_quantize_weights(dev(c.w), bw)
+        bias = dev(c.bias)
+        y_ws, _ = B.aqt_dense_fwd_q(xq, s_x, wq, s_w, N, bx, bw, bias=bias, epilogue=epi)
+        y = torch.empty_like(y_ws)
+        prepared.append((c, ora, xq, s_x, wq, s_w, bias, y_ws, y))
+    torch.cuda.synchronize()
+    # Round 0 looks the array up and makes the runtime load every kernel the three shapes use
+    # (which takes device memory of its own); round 1 must then leave the free memory alone.
+    for rnd in range(2):
+        free_before = torch.cuda.mem_get_info()[0]
+        for (M, K, N, bx, bw, epi), (c, ora, xq, s_x, wq, s_w, bias, y_ws, y) in zip(cases, prepared):
+            y.fill_(float("nan"))
+            B.aqt_dense_fwd_q_static(xq, s_x, wq, s_w, N, bx, bw, bias=bias, epilogue=epi, y=y)
+        torch.cuda.synchronize()
+        if rnd == 1:
+            assert torch.cuda.mem_get_info()[0] >= free_before, "device memory was allocated by the calls"
+    for (M, K, N, bx, bw, epi), (c, ora, xq, s_x, wq, s_w, bias, y_ws, y) in zip(cases, prepared):
+        np.testing.assert_array_equal(host(y), host(y_ws))
+        check_forward(host(y), ora, ora["s_x"][0], ora["s_w"], c.bias, epi)
+
+
+def test_static_scratch_rejects_layers_beyond_its_size():
+    limit = B.aqt_static_scratch_bytes()
+    assert limit == 4 << 20
+    K, N = 2048, 2048 + 128                      # K * N just above the array
+    one = torch.zeros(1, dtype=torch.float32, device="cuda")
+    xq = torch.zeros((128, K), dtype=torch.int8, device="cuda")
+    wq = torch.zeros(B.aqt_packed_weight_bytes(K, N, 4), dtype=torch.uint8, device="cuda")
+    s_w = torch.ones(N, dtype=torch.float32, device="cuda")
+    y = torch.full((128, N), 7.0, dtype=torch.float32, device="cuda")
+    with pytest.raises(B.AqtError) as e:
+        B.aqt_dense_fwd_q_static(xq, one, wq, s_w, N, 8, 4, y=y)
+    assert e.value.status == B.AQT_ERR_SCRATCH
+    assert (host(y) == 7.0).all()                # nothing was enqueued
+    # exactly at the limit is accepted
+    N = 2048
+    wq = torch.zeros(B.aqt_packed_weight_bytes(K, N, 4), dtype=torch.uint8, device="cuda")
+    y = torch.full((128, N), 7.0, dtype=torch.float32, device="cuda")
+    B.aqt_dense_fwd_q_static(xq, one, wq, s_w[:N].contiguous(), N, 8, 4, y=y)
+    assert (host(y) == 0.0).all()
