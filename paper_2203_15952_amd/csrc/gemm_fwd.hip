@@ -78,27 +78,28 @@ __global__ __launch_bounds__(kThreads) void dense_fwd_general_kernel(
 }
 
 // ---- tuned MFMA kernel --------------------------------------------------------------
-// What bounds this kernel on gfx950 is operand delivery, not the matrix cores: an
-// int8 32x32x32 MFMA eats 2 KB of operands per 32 cycles, LDS delivers about 64
-// bytes per clock and CU for 16-byte reads, and the K=512 layers are bound by
-// writing their float32 output anyway.  Hence:
-//   * The weights never touch LDS.  A small pre-kernel rewrites the forward weight
-//     operand ([N][K] int8 or [N][K/2] packed int4) into MFMA-fragment order --
-//     expanding int4 nibbles c to the byte 16*c on the way (a shift and a mask, the
-//     sign comes for free) -- and every wavefront pulls its 1 KB fragments straight
-//     from L2 with one coalesced load each, one stage ahead, into registers that
-//     are refilled in place.  The accumulator is shifted back by 4 at the end,
-//     which is exact because every partial sum is a multiple of 16.
-//   * The activations (the HBM stream) go global -> registers (two alternating
-//     sets, a full stage in flight) -> LDS (two slots, 128-byte rows, 16-byte chunks
-//     XOR-swizzled with the row) -> fragments refilled in place.
-//   * Workgroup = 2 x 2 wavefronts, tile (64*TM) x (64*TN) with TM < TN so that LDS
-//     reads per MFMA are 1/TN KB; 128 fan-in bytes per stage = 4 MFMA steps; one
-//     barrier per stage; two workgroups per CU.  All non-MFMA work is cut into
-//     pieces slotted between MFMAs; the loop body is branch-free (loads past the
-//     end are clamped to the last stage).
+// What bounds this kernel on gfx950 is operand delivery into vector registers (LDS
+// reads and loads from L2 share about 64 bytes per clock and CU), not the matrix
+// cores: an int8 32x32x32 MFMA eats 2 KB of operands per 32 cycles.  Hence:
+//   * Weights stay packed all the way into registers.  A small pre-kernel re-orders
+//     the forward weight operand into MFMA-fragment order; int4 weights remain two
+//     codes per byte there (half the bytes to deliver), and the wavefront expands
+//     them to the byte 16*c with a shift and two masks per eight codes right before
+//     use (the sign comes for free).  The accumulator is shifted back by 4 at the
+//     end, exact because every partial sum is a multiple of 16.  Fragments come
+//     straight from L2 with one coalesced 1 KB load each, about two stages ahead.
+//   * Activations (the HBM stream) never pass through registers on their way in:
+//     global_load_lds writes 16 bytes per lane directly into LDS (three slots of one
+//     stage each, 128-byte rows, 16-byte chunks XOR-swizzled with the row; the swizzle
+//     is applied on the global-address side because the LDS side of such a load is
+//     linear in the lane id).  Fragments are read from LDS and refilled in place.
+//   * Workgroup = 2 x 2 wavefronts, tile (64*TM) x (64*TN) with TM < TN; 128 fan-in
+//     bytes per stage = 4 MFMA steps; one barrier per stage; two workgroups per CU.
+//     All non-MFMA work is cut into pieces slotted between MFMAs; the loop body is
+//     branch-free (loads past the end are clamped to the last stage).
 constexpr int kBK = 128;     // fan-in bytes per stage
 constexpr int kKK = 4;       // MFMA steps (32 fan-in each) per stage
+constexpr int kSlots = 3;    // LDS slots, one stage of activations each
 
 #define AQT_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
@@ -106,61 +107,97 @@ constexpr int waitcnt_imm(int vm, int lgkm) {   // s_waitcnt immediate, gfx9 lay
   return (vm & 0xF) | ((vm >> 4) << 14) | (7 << 4) | ((lgkm & 0xF) << 8);
 }
 
-// int4 -> int8 (times 16): eight nibbles of one dword, fan-in order c0..c7, become
-// the two dwords {16c0,16c1,16c2,16c3} and {16c4,..,16c7}.
-__device__ __forceinline__ void unpack8(uint32_t w, uint32_t &d0, uint32_t &d1) {
-  const uint32_t lo = (w << 4) & 0xF0F0F0F0u;  // bytes: c0 c2 c4 c6 (each times 16)
-  const uint32_t hi = w & 0xF0F0F0F0u;         // bytes: c1 c3 c5 c7
-  // v_perm_b32 picks bytes out of {hi (selectors 4..7), lo (selectors 0..3)}
-  d0 = __builtin_amdgcn_perm(hi, lo, 0x05010400u);  // lo.b0 hi.b0 lo.b1 hi.b1
-  d1 = __builtin_amdgcn_perm(hi, lo, 0x07030602u);  // lo.b2 hi.b2 lo.b3 hi.b3
+// Eight int4 codes of one dword in the fragment-ordered layout (byte b: low nibble =
+// code b, high nibble = code 4 + b) -> the dwords {16c0..16c3} and {16c4..16c7}.
+__device__ __forceinline__ v4i expand16(uint32_t wa, uint32_t wb) {
+  v4i o;
+  o.x = static_cast<int>((wa << 4) & 0xF0F0F0F0u);
+  o.y = static_cast<int>(wa & 0xF0F0F0F0u);
+  o.z = static_cast<int>((wb << 4) & 0xF0F0F0F0u);
+  o.w = static_cast<int>(wb & 0xF0F0F0F0u);
+  return o;
 }
 
-// Forward weight operand -> MFMA-fragment order.  Fragment (nb, ks) covers channels
-// 32*nb .. +31 and fan-in 32*ks .. +31; inside it lane (lk*32 + lr) owns the 16
-// consecutive fan-in positions 32*ks + 16*lk .. +15 of channel 32*nb + lr, i.e.
-// what that lane feeds to v_mfma_i32_32x32x32_i8.  Fragments are ordered [nb][ks].
+// Canonical packed dword (nibble e = code e, i.e. low nibble first) -> fragment-ordered dword.
+__device__ __forceinline__ uint32_t regroup_nibbles(uint32_t w) {
+  uint32_t t = 0;
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    const uint32_t lo = (w >> (4 * b)) & 0xFu, hi = (w >> (4 * (4 + b))) & 0xFu;
+    t |= (lo | (hi << 4)) << (8 * b);
+  }
+  return t;
+}
+
+// Forward weight operand -> MFMA-fragment order.
+// int8 weights: fragment (nb, ks) covers channels 32*nb .. +31 and fan-in 32*ks .. +31;
+// inside it lane (lk*32 + lr) owns the 16 consecutive fan-in positions 32*ks + 16*lk ..
+// +15 of channel 32*nb + lr, i.e. what that lane feeds to v_mfma_i32_32x32x32_i8.
+// Fragments are ordered [nb][ks], 1 KB each.
+// Packed int4 weights: a 1 KB fragment (nb, kp) covers the two steps ks = 2*kp, 2*kp + 1;
+// lane (lk*32 + lr) owns two dwords per step (16 codes, regrouped for expand16), step
+// 2*kp first.  Fragments are ordered [nb][kp].
 __global__ __launch_bounds__(kThreads) void weights_to_frag_kernel(const uint8_t *__restrict__ wq, int K, int N,
                                                                    int packed, v4i *__restrict__ out) {
-  const int64_t pieces = static_cast<int64_t>(N) * (K / 16);
   const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+  if (packed) {
+    const int64_t pieces = static_cast<int64_t>(N) * (K / 32);
+    const int kpairs = K / 64;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < pieces; i += stride) {
+      const int lane = static_cast<int>(i & 63);
+      const int64_t frag = i >> 6;
+      const int kp = static_cast<int>(frag % kpairs), nb = static_cast<int>(frag / kpairs);
+      const int n = 32 * nb + (lane & 31), k = 64 * kp + 16 * (lane >> 5);
+      const uint8_t *row = wq + static_cast<int64_t>(n) * (K >> 1);
+      const uint2 w0 = *reinterpret_cast<const uint2 *>(row + (k >> 1));          // step 2*kp
+      const uint2 w1 = *reinterpret_cast<const uint2 *>(row + ((k + 32) >> 1));   // step 2*kp + 1
+      v4i o;
+      o.x = static_cast<int>(regroup_nibbles(w0.x)); o.y = static_cast<int>(regroup_nibbles(w0.y));
+      o.z = static_cast<int>(regroup_nibbles(w1.x)); o.w = static_cast<int>(regroup_nibbles(w1.y));
+      out[i] = o;
+    }
+    return;
+  }
+  const int64_t pieces = static_cast<int64_t>(N) * (K / 16);
   const int ksteps = K / 32;
   for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < pieces; i += stride) {
     const int lane = static_cast<int>(i & 63);
     const int64_t frag = i >> 6;
     const int ks = static_cast<int>(frag % ksteps), nb = static_cast<int>(frag / ksteps);
     const int n = 32 * nb + (lane & 31), k = 32 * ks + 16 * (lane >> 5);
-    v4i o;
-    if (packed) {
-      const uint2 w = *reinterpret_cast<const uint2 *>(wq + static_cast<int64_t>(n) * (K >> 1) + (k >> 1));
-      uint32_t d0, d1;
-      unpack8(w.x, d0, d1); o.x = d0; o.y = d1;
-      unpack8(w.y, d0, d1); o.z = d0; o.w = d1;
-    } else {
-      o = *reinterpret_cast<const v4i *>(wq + static_cast<int64_t>(n) * K + k);
-    }
-    out[i] = o;
+    out[i] = *reinterpret_cast<const v4i *>(wq + static_cast<int64_t>(n) * K + k);
   }
 }
 
-template <int TM, int TN, bool SHIFT4, int EPI>
+template <int TM, int TN, bool PACKED, int EPI>
 __global__ __launch_bounds__(kThreads, 2) void dense_fwd_mfma_kernel(
     const int8_t *__restrict__ xq, const float *__restrict__ s_x, const v4i *__restrict__ wfrag,
     const float *__restrict__ s_w, int M, int K, int N, const float *__restrict__ bias,
     float *__restrict__ y, int32_t *__restrict__ acc_out, uint32_t *__restrict__ y_absmax, int tiles_m,
     int tiles_n) {
+  constexpr bool SHIFT4 = PACKED;
   constexpr int BM = 64 * TM, BN = 64 * TN;
-  constexpr int NA = BM * (kBK / 16) / kThreads;   // 16-byte pieces of activations per thread per stage
-  __shared__ __attribute__((aligned(1024))) uint8_t sA0[BM * kBK], sA1[BM * kBK];
+  constexpr int kSlotBytes = BM * kBK;
+  constexpr int NL = BM * (kBK / 16) / kThreads;   // direct 1 KB loads per wavefront per stage
+  __shared__ __attribute__((aligned(1024))) uint8_t sA[kSlots * kSlotBytes];
 
-  // Workgroup -> tile, row-major over (row tile, column tile).  Consecutive workgroup
-  // ids land on different XCDs, so the column tiles of one row tile run at the same
-  // time on different L2s and each fetches the activation tile itself; measured, that
-  // costs less than what remapping ids to one contiguous run of tiles per XCD loses
-  // on the output side (the tiles in flight then write to eight distant regions).
-  (void)tiles_m;
+  // Workgroup -> tile.  Consecutive workgroup ids land on different XCDs (each with its
+  // own L2).  Ids i, i + 8, i + 16, .. run on one XCD next to each other in time, so they
+  // walk the column tiles of ONE row strip (its activations then come from HBM once
+  // and from that L2 afterwards), while the row strips in flight stay neighbours, so
+  // the output being written is one compact region.
   const int id = blockIdx.x;
-  const int bm = id / tiles_n, bn = id - bm * tiles_n;
+  int bm, bn;
+  {
+    const int grp = 8 * tiles_n, full = (tiles_m / 8) * grp;
+    if (id < full) {
+      bm = (id / grp) * 8 + (id & 7);
+      bn = (id % grp) >> 3;
+    } else {
+      bm = (tiles_m / 8) * 8 + (id - full) / tiles_n;
+      bn = (id - full) % tiles_n;
+    }
+  }
   // A ragged last row tile is shifted up to end at row M: it recomputes a few rows
   // of its neighbour (same values, same addresses) instead of predicating.
   const int m0 = min(bm * BM, M - BM);
@@ -177,35 +214,44 @@ __global__ __launch_bounds__(kThreads, 2) void dense_fwd_mfma_kernel(
     return bn * BN + cb * 32;
   };
 
-  // ---- activations: global -> registers -> LDS ----
-  v4i ra[2][NA];
+  // ---- activations: global -> LDS, directly ----
+  // Load number i of wavefront w fills the LDS bytes [(w*NL + i) KB, +1 KB) of a slot, lane l
+  // the 16 bytes at l*16 in there: row r = (w*NL + i)*8 + l/8, chunk slot l%8, which holds
+  // global chunk (l%8) ^ (r & 7) of that row (r & 7 == (l/8) & 7).
   const char *a_base = reinterpret_cast<const char *>(xq + static_cast<int64_t>(m0) * K);
-  const uint32_t ga0 = static_cast<uint32_t>((t >> 3) * K + (t & 7) * 16);   // piece i: + i * 32 rows
-  const uint32_t ga_step = static_cast<uint32_t>(32 * K);
-  const int rowa = t >> 3;
-  const int offa0 = rowa * kBK + (((t & 7) ^ (rowa & 7)) << 4);             // + i * 32 rows keeps row & 7
-  auto load_a = [&](int set, int k0) {
+  const uint32_t ga0 = static_cast<uint32_t>((wave * NL * 8 + (lane >> 3)) * K + (((lane & 7) ^ ((lane >> 3) & 7)) << 4));
+  const uint32_t ga_step = static_cast<uint32_t>(8 * K);
+  auto issue_a = [&](int slot_off, int k0) {
 #pragma unroll
-    for (int i = 0; i < NA; ++i) ra[set][i] = *reinterpret_cast<const v4i *>(a_base + k0 + ga0 + i * ga_step);
-  };
-  auto store_a = [&](int set, int i, uint8_t *slot) {
-    *reinterpret_cast<v4i *>(slot + offa0 + i * 32 * kBK) = ra[set][i];
+    for (int i = 0; i < NL; ++i)
+      __builtin_amdgcn_global_load_lds(
+          reinterpret_cast<const __attribute__((address_space(1))) void *>(
+              reinterpret_cast<uintptr_t>(a_base + k0 + ga0 + i * ga_step)),
+          reinterpret_cast<__attribute__((address_space(3))) void *>(
+              static_cast<uint32_t>(reinterpret_cast<uintptr_t>(sA)) + slot_off + (wave * NL + i) * 1024),
+          16, 0, 0);
   };
   // fragments of the activations: row lr of row tile i, 16-byte chunk (2*kk + lk) ^ (lr & 7)
   const int a_row = (wm * 32 * TM + lr) * kBK;
   v4i fa[TM];
-  auto read_a = [&](const uint8_t *slot, int kk, int i) {
-    fa[i] = *reinterpret_cast<const v4i *>(slot + a_row + i * 32 * kBK + (((2 * kk + lk) ^ (lr & 7)) << 4));
+  auto read_a = [&](int slot_off, int kk, int i) {
+    fa[i] = *reinterpret_cast<const v4i *>(sA + slot_off + a_row + i * 32 * kBK + (((2 * kk + lk) ^ (lr & 7)) << 4));
   };
 
   // ---- weights: fragments straight from L2 ----
-  const int ksteps = K / 32;
+  // raw[q][j]: int8 weights: the fragment of step q of the stage in flight, refilled in
+  // place for the next stage; packed weights: four pair slots = two stages, stage s lives
+  // in slots 2*(s%2), 2*(s%2) + 1 and a slot is refilled for stage s + 2 as soon as its
+  // second step has been expanded.  ub[kk % 2][j]: expanded fragments (packed only).
+  constexpr int FR = PACKED ? kKK / 2 : kKK;   // fragments per column block and stage
+  const int frags_per_blk = K / (PACKED ? 64 : 32);
   const v4i *b_blk[TN];   // uniform: fragment row of column block j
 #pragma unroll
   for (int j = 0; j < TN; ++j)
-    b_blk[j] = wfrag + static_cast<int64_t>(chan_of_block(wn * TN + j) / 32) * ksteps * 64;
-  v4i fb[kKK][TN];
-  auto load_b = [&](int kk, int j, int stage) { fb[kk][j] = (b_blk[j] + (stage * kKK + kk) * 64)[lane]; };
+    b_blk[j] = wfrag + static_cast<int64_t>(chan_of_block(wn * TN + j) / 32) * frags_per_blk * 64;
+  v4i raw[4][TN];
+  v4i ub[2][TN];
+  auto load_raw = [&](int slot, int j, int frag_no) { raw[slot][j] = (b_blk[j] + frag_no * 64)[lane]; };
 
   v16i acc[TM][TN];
 #pragma unroll
@@ -219,61 +265,80 @@ __global__ __launch_bounds__(kThreads, 2) void dense_fwd_mfma_kernel(
   auto stage_idx = [&](int s) { return s < NS - 1 ? s : NS - 1; };
 
   // ---- prologue ----
-  load_a(0, 0);
+  int off_cur = 0, off_nxt = kSlotBytes, off_fill = 2 * kSlotBytes;
+  issue_a(off_cur, 0);
 #pragma unroll
-  for (int kk = 0; kk < kKK; ++kk)
+  for (int q = 0; q < FR; ++q)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) load_b(kk, j, 0);
+    for (int j = 0; j < TN; ++j) load_raw(q, j, q);
+  issue_a(off_nxt, stage_idx(1) * kBK);
+  if (PACKED) {
 #pragma unroll
-  for (int i = 0; i < NA; ++i) store_a(0, i, sA0);
-  load_a(1, stage_idx(1) * kBK);
-  __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
+    for (int q = 0; q < FR; ++q)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) load_raw(FR + q, j, stage_idx(1) * FR + q);
+  }
+  AQT_SCHED_FENCE();
+  // stage 0 (activations and weights) has landed; stage 1 may still be in flight
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(NL + (PACKED ? FR * TN : 0), 0));
   __builtin_amdgcn_s_barrier();
 #pragma unroll
-  for (int i = 0; i < TM; ++i) read_a(sA0, 0, i);
+  for (int i = 0; i < TM; ++i) read_a(off_cur, 0, i);
+  if (PACKED) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) ub[0][j] = expand16(raw[0][j].x, raw[0][j].y);
+  }
 
-  // One stage; PAR = s % 2 is a compile-time constant (register sets, LDS slots).
+  // One stage; PAR = s % 2 is a compile-time constant (register slots).
   // MFMA q = i*TN + j of a step: row tile i uses its activation fragment in TN
-  // consecutive MFMAs and is refilled right after; weight fragment j is last used
-  // by row tile TM-1 and is refilled (for the next stage, same step) right after.
+  // consecutive MFMAs and is refilled right after.  Between MFMA pairs: packed weights
+  // expand one fragment of the next step (and, when that empties a pair slot, refill it
+  // for the stage after next); int8 weights refill a fragment right after its last use.
   auto stage = [&](auto par, int s) {
     constexpr int PAR = decltype(par)::value;
-    uint8_t *cur = PAR ? sA1 : sA0;
-    uint8_t *nxt = PAR ? sA0 : sA1;
-    const int s1 = stage_idx(s + 1);
-    load_a(PAR, stage_idx(s + 2) * kBK);   // set PAR was written to LDS one stage ago
+    const int s1 = stage_idx(s + 1), s2 = stage_idx(s + 2);
+    issue_a(off_fill, s2 * kBK);   // that slot was last read one stage ago, before the barrier all have passed
     AQT_SCHED_FENCE();
 #pragma unroll
     for (int kk = 0; kk < kKK; ++kk) {
       if (kk == kKK - 1) {
-        // next stage fully staged by everybody before its first fragments are read
-        __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
+        // next stage's activations have landed (everything issued before this stage began has),
+        // own LDS reads of the current slot are done
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm(NL + (PACKED ? 2 * TN : 3 * TN), 0));
         __builtin_amdgcn_s_barrier();
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[kk][j], acc[i][j], 0, 0, 0);
+          if (PACKED) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], ub[kk & 1][j], acc[i][j], 0, 0, 0);
+          else acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], raw[kk][j], acc[i][j], 0, 0, 0);
           if (j & 1) {
             AQT_SCHED_FENCE();
-            if (i == TM - 1) { load_b(kk, j - 1, s1); load_b(kk, j, s1); }
-            // stage s + 1 into the other slot during steps 0 and 1
-            if (kk < 2) {
-              constexpr int PER = (NA + 2 * TM * TN / 2 - 1) / (2 * TM * TN / 2);
-              const int slot_no = (kk * TM + i) * (TN / 2) + (j >> 1);
-#pragma unroll
-              for (int c = slot_no * PER; c < (slot_no + 1) * PER && c < NA; ++c) store_a(PAR ^ 1, c, nxt);
+            if (PACKED) {
+              const int jj = i * (TN / 2) + (j >> 1);   // one fragment of the next step per gap
+              if (jj < TN) {
+                // step kk + 1 lives in pair slot (kk + 1) / 2 of this stage; step 0 of the next stage in its slot 0
+                constexpr int P0 = 2 * PAR, P1 = 2 * PAR + 1, Q0 = 2 * (PAR ^ 1);
+                if (kk == 0) { ub[1][jj] = expand16(raw[P0][jj].z, raw[P0][jj].w); load_raw(P0, jj, s2 * FR); }
+                if (kk == 1) ub[0][jj] = expand16(raw[P1][jj].x, raw[P1][jj].y);
+                if (kk == 2) { ub[1][jj] = expand16(raw[P1][jj].z, raw[P1][jj].w); load_raw(P1, jj, s2 * FR + 1); }
+                if (kk == 3) ub[0][jj] = expand16(raw[Q0][jj].x, raw[Q0][jj].y);
+              }
+            } else if (i == TM - 1) {
+              load_raw(kk, j - 1, s1 * FR + kk);
+              load_raw(kk, j, s1 * FR + kk);
             }
             AQT_SCHED_FENCE();
           }
         }
         // row tile i done for this step: refill its fragment for the next step
-        if (kk < kKK - 1) read_a(cur, kk + 1, i);
-        else read_a(nxt, 0, i);
+        if (kk < kKK - 1) read_a(off_cur, kk + 1, i);
+        else read_a(off_nxt, 0, i);
         AQT_SCHED_FENCE();
       }
     }
+    const int o = off_cur; off_cur = off_nxt; off_nxt = off_fill; off_fill = o;
   };
 
   int s = 0;
@@ -282,6 +347,8 @@ __global__ __launch_bounds__(kThreads, 2) void dense_fwd_mfma_kernel(
     stage(std::integral_constant<int, 1>{}, s + 1);
   }
   if (s < NS) stage(std::integral_constant<int, 0>{}, s);
+  // the clamped loads of the last stages are still writing LDS: drain them before the wavefront can end
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
 
   // ---- epilogue: registers -> HBM ----
   // Lane holds output column (lane % 32) of each 32 x 32 tile; register r holds
@@ -416,7 +483,7 @@ aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq
     const int64_t unit = (epilogue == AQT_EPI_GLU) ? 64 : 128;
     if (nn % unit == 0) {
       v4i *wfrag = static_cast<v4i *>(ws);
-      const int64_t pieces = N * (K / 16);
+      const int64_t pieces = N * (K / (packed ? 32 : 16));
       int g = static_cast<int>(cdiv(pieces, kThreads));
       if (g > 2048) g = 2048;
       weights_to_frag_kernel<<<g, kThreads, 0, st>>>(static_cast<const uint8_t *>(wq_packed), static_cast<int>(K),
