@@ -250,3 +250,60 @@ def dense_bwd_dw_sampled(dy, xq, s_x, idx_k, idx_n):
                                      ctypes.c_int64(M), ctypes.c_int64(K), ctypes.c_int64(N),
                                      _p(idx_k), _p(idx_n), ctypes.c_int64(cnt), _p(dw), _p(dwa))
     return dw, dwa
+
+
+def epilogue_dact(pre, epilogue: int):
+    """Derivative factors of the activation: dv[m,n] = dout[m, n mod out_cols] * dact[m,n]."""
+    pre = np.ascontiguousarray(pre, np.float64)
+    M, N = pre.shape
+    dact = np.empty((M, N), np.float64)
+    rc = _c().oracle_epilogue_dact(_p(pre), ctypes.c_int64(M), ctypes.c_int64(N), epilogue, _p(dact))
+    if rc:
+        raise ValueError(f"oracle_epilogue_dact rc={rc}")
+    return dact
+
+
+def dense_bwd_epi(dout, pre, epilogue: int, xq, s_x, wq_kn, s_w, mask_x=None, mask_w=None,
+                  want_dx=True, want_dw=True, want_dbias=True):
+    """Straight-through backward through the activation, float64.
+    Returns dict(dx, dw, dbias, dx_abs, dw_abs, dv)."""
+    dout, xq, wq_kn, s_w = _f32(dout), _i8(xq), _i8(wq_kn), _f32(s_w)
+    pre = np.ascontiguousarray(pre, np.float64)
+    M, N = pre.shape
+    K = xq.shape[1]
+    assert dout.shape == (M, _out_cols(N, epilogue)) and wq_kn.shape == (K, N)
+    mx = None if mask_x is None else np.ascontiguousarray(mask_x, np.uint8)
+    mw = None if mask_w is None else np.ascontiguousarray(mask_w, np.uint8)
+    dx = np.empty((M, K), np.float64) if want_dx else None
+    dxa = np.empty((M, K), np.float64) if want_dx else None
+    dw = np.empty((K, N), np.float64) if want_dw else None
+    dwa = np.empty((K, N), np.float64) if want_dw else None
+    db = np.empty(N, np.float64) if want_dbias else None
+    dv = np.empty((M, N), np.float64)
+    rc = _c().oracle_dense_bwd_epi(_p(dout), _p(pre), epilogue, _p(xq), ctypes.c_float(float(s_x)), _p(mx),
+                                   _p(wq_kn), _p(s_w), _p(mw), ctypes.c_int64(M), ctypes.c_int64(K),
+                                   ctypes.c_int64(N), _p(dx), _p(dw), _p(db), _p(dxa), _p(dwa), _p(dv))
+    if rc:
+        raise ValueError(f"oracle_dense_bwd_epi rc={rc}")
+    return dict(dx=dx, dw=dw, dbias=db, dx_abs=dxa, dw_abs=dwa, dv=dv)
+
+
+def layernorm(x, gamma=None, beta=None, eps: float = 1e-6):
+    """Per-row layer normalisation in float64 (biased variance)."""
+    x = _f32(x)
+    M, D = x.shape
+    g = None if gamma is None else _f32(gamma)
+    b = None if beta is None else _f32(beta)
+    y = np.empty((M, D), np.float64)
+    _c().oracle_layernorm(_p(x), ctypes.c_int64(M), ctypes.c_int64(D), _p(g), _p(b), ctypes.c_double(eps), _p(y))
+    return y
+
+
+def fake_matmul_f32(xq, wq_kn):
+    """Product of the codes carried and accumulated in float32 (the "fake quantization" arithmetic)."""
+    xq, wq_kn = _i8(xq), _i8(wq_kn)
+    M, K = xq.shape
+    N = wq_kn.shape[1]
+    out = np.empty((M, N), np.float32)
+    _c().oracle_fake_matmul_f32(_p(xq), _p(wq_kn), ctypes.c_int64(M), ctypes.c_int64(K), ctypes.c_int64(N), _p(out))
+    return out

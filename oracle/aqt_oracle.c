@@ -21,6 +21,18 @@
  *   oracle_dense_bwd      Fig. 2's stop_gradient on the scale; the rounding is
  *                         passed straight through (the paper does not state it,
  *                         straight-through is the standard reading of QAT).
+ *   oracle_epilogue_dact, oracle_dense_bwd_epi
+ *                         the same backward through the layer's activation
+ *                         (Swish of the feed-forward module, GLU of the
+ *                         convolution module, Sec. 3.2's Conformer blocks): the
+ *                         chain rule with the textbook derivatives.
+ *   oracle_layernorm      the normalisation in front of the feed-forward module
+ *                         (Sec. 3.2's Conformer; per token over the model width,
+ *                         biased variance), float64; not part of the paper's
+ *                         method, glue of the chained block.
+ *   oracle_fake_matmul_f32  Sec. 1 / Sec. 2.2: "fake" quantization carries the integer
+ *                         codes in float32 and multiplies them with float
+ *                         operations; sums that need more than 24 bits are rounded.
  *
  * Arithmetic: the quantizer is binary32, one rounding per operation, because
  * the paper's listing is float32 TensorFlow and the codes depend on it.  The
@@ -36,7 +48,13 @@
  * matmul of the de-quantized operands, hand-packed bytes; the weight-only forward
  * by a hand-worked example, one-hot activations, agreement with the integer path
  * on activations that are exact multiples of a power-of-two scale, and the
- * half-step bound against the float product).  The paper prints
+ * half-step bound against the float product; the activation derivatives by
+ * closed-form values and central differences of the activation alone, the
+ * backward through the activation by central differences of the de-quantized
+ * layer in float64 numpy; the normalisation by a hand-worked row, zero mean and
+ * unit variance of its rows, and numpy; the float32-emulated product by equality
+ * with the integer product while sums fit 24 bits and a hand-worked sum that does
+ * not).  The paper prints
  * no worked numeric example, so no pin comes from printed values.
  */
 #include <math.h>
@@ -312,17 +330,17 @@ int oracle_dense_fwd(const float *x, const float *w, int64_t M, int64_t K, int64
  * is ever masked).  Any of dx, dw, dbias may be NULL.  dx_abs / dw_abs (nullable) receive the sum of the magnitudes
  * of the terms, the yardstick a condition-aware comparison needs.
  */
-void oracle_dense_bwd(const float *dy, const int8_t *xq, float s_x, const uint8_t *mask_x,
-                      const int8_t *wq_kn, const float *s_w, const uint8_t *mask_w,
-                      int64_t M, int64_t K, int64_t N,
-                      double *dx, double *dw, double *dbias, double *dx_abs, double *dw_abs) {
+static void dense_bwd_core(const double *dy, const int8_t *xq, float s_x, const uint8_t *mask_x,
+                           const int8_t *wq_kn, const float *s_w, const uint8_t *mask_w,
+                           int64_t M, int64_t K, int64_t N,
+                           double *dx, double *dw, double *dbias, double *dx_abs, double *dw_abs) {
   if (dx) {
 #pragma omp parallel for schedule(static)
     for (int64_t m = 0; m < M; ++m)
       for (int64_t k = 0; k < K; ++k) {
         double s = 0.0, sa = 0.0;
         for (int64_t n = 0; n < N; ++n) {
-          double t = (double)dy[m * N + n] * (double)s_w[n] * (double)wq_kn[k * N + n];
+          double t = dy[m * N + n] * (double)s_w[n] * (double)wq_kn[k * N + n];
           s += t;
           sa += fabs(t);
         }
@@ -337,7 +355,7 @@ void oracle_dense_bwd(const float *dy, const int8_t *xq, float s_x, const uint8_
       for (int64_t n = 0; n < N; ++n) {
         double s = 0.0, sa = 0.0;
         for (int64_t m = 0; m < M; ++m) {
-          double t = (double)xq[m * K + k] * (double)dy[m * N + n];
+          double t = (double)xq[m * K + k] * dy[m * N + n];
           s += t;
           sa += fabs(t);
         }
@@ -349,10 +367,125 @@ void oracle_dense_bwd(const float *dy, const int8_t *xq, float s_x, const uint8_
   if (dbias) {
     for (int64_t n = 0; n < N; ++n) {
       double s = 0.0;
-      for (int64_t m = 0; m < M; ++m) s += (double)dy[m * N + n];
+      for (int64_t m = 0; m < M; ++m) s += dy[m * N + n];
       dbias[n] = s;
     }
   }
+}
+
+void oracle_dense_bwd(const float *dy, const int8_t *xq, float s_x, const uint8_t *mask_x,
+                      const int8_t *wq_kn, const float *s_w, const uint8_t *mask_w,
+                      int64_t M, int64_t K, int64_t N,
+                      double *dx, double *dw, double *dbias, double *dx_abs, double *dw_abs) {
+  double *d = (double *)malloc((size_t)M * (size_t)N * sizeof(double));
+  for (int64_t i = 0; i < M * N; ++i) d[i] = (double)dy[i];
+  dense_bwd_core(d, xq, s_x, mask_x, wq_kn, s_w, mask_w, M, K, N, dx, dw, dbias, dx_abs, dw_abs);
+  free(d);
+}
+
+/*
+ * Derivative factors of the layer's activation with respect to the value v it is
+ * applied to (v = de-quantized product + bias), float64:
+ *   none : dact[m,n] = 1
+ *   Swish: out = v s(v), s the logistic function:  dact = s(v) (1 + v (1 - s(v)))
+ *   GLU  : out[m,j] = a s(g), a = v[m,j], g = v[m,j+N/2]:
+ *          dact[m,j] = s(g)   (d out / d a),   dact[m,j+N/2] = a s(g) (1 - s(g))   (d out / d g)
+ * so that d v[m,n] = d out[m, n mod out_cols] * dact[m,n] in every case.
+ * pre and dact are [M,N].
+ */
+int oracle_epilogue_dact(const double *pre, int64_t M, int64_t N, int epilogue, double *dact) {
+  if (epilogue == ORACLE_EPI_GLU && (N % 2)) return 2;
+  const int64_t h = N / 2;
+  for (int64_t m = 0; m < M; ++m)
+    for (int64_t n = 0; n < N; ++n) {
+      double v = pre[m * N + n], d;
+      if (epilogue == ORACLE_EPI_NONE) {
+        d = 1.0;
+      } else if (epilogue == ORACLE_EPI_SWISH) {
+        double sg = sigmoid64(v);
+        d = sg * (1.0 + v * (1.0 - sg));
+      } else if (n < h) {
+        d = sigmoid64(pre[m * N + n + h]);
+      } else {
+        double sg = sigmoid64(v);
+        d = pre[m * N + n - h] * sg * (1.0 - sg);
+      }
+      dact[m * N + n] = d;
+    }
+  return 0;
+}
+
+/*
+ * Straight-through backward through the activation: dout is the gradient with
+ * respect to the layer's output ([M,N], or [M,N/2] for GLU), pre [M,N] the value
+ * the activation was applied to.  The gradient with respect to that value,
+ * dv = dout * dact (chain rule), then takes the place of dy in oracle_dense_bwd.
+ * dv_out (nullable) [M,N] receives it.
+ */
+int oracle_dense_bwd_epi(const float *dout, const double *pre, int epilogue,
+                         const int8_t *xq, float s_x, const uint8_t *mask_x,
+                         const int8_t *wq_kn, const float *s_w, const uint8_t *mask_w,
+                         int64_t M, int64_t K, int64_t N,
+                         double *dx, double *dw, double *dbias, double *dx_abs, double *dw_abs,
+                         double *dv_out) {
+  double *dact = (double *)malloc((size_t)M * (size_t)N * sizeof(double));
+  int rc = oracle_epilogue_dact(pre, M, N, epilogue, dact);
+  if (rc) { free(dact); return rc; }
+  const int64_t oc = (epilogue == ORACLE_EPI_GLU) ? N / 2 : N;
+  for (int64_t m = 0; m < M; ++m)
+    for (int64_t n = 0; n < N; ++n) dact[m * N + n] *= (double)dout[m * oc + (n % oc)];
+  if (dv_out) memcpy(dv_out, dact, (size_t)M * (size_t)N * sizeof(double));
+  dense_bwd_core(dact, xq, s_x, mask_x, wq_kn, s_w, mask_w, M, K, N, dx, dw, dbias, dx_abs, dw_abs);
+  free(dact);
+  return 0;
+}
+
+/*
+ * Layer normalisation of each row of x [M,D] over its D entries, float64:
+ * mean and biased variance of the row, y = (x - mean) / sqrt(var + eps) * gamma + beta;
+ * gamma / beta nullable (1 / 0).
+ */
+void oracle_layernorm(const float *x, int64_t M, int64_t D, const float *gamma, const float *beta,
+                      double eps, double *y) {
+#pragma omp parallel for schedule(static)
+  for (int64_t m = 0; m < M; ++m) {
+    double mean = 0.0, var = 0.0;
+    for (int64_t d = 0; d < D; ++d) mean += (double)x[m * D + d];
+    mean /= (double)D;
+    for (int64_t d = 0; d < D; ++d) {
+      double c = (double)x[m * D + d] - mean;
+      var += c * c;
+    }
+    var /= (double)D;
+    const double r = 1.0 / sqrt(var + eps);
+    for (int64_t d = 0; d < D; ++d) {
+      double v = ((double)x[m * D + d] - mean) * r;
+      if (gamma) v *= (double)gamma[d];
+      if (beta) v += (double)beta[d];
+      y[m * D + d] = v;
+    }
+  }
+}
+
+/*
+ * "Fake" quantization's product (Sec. 1, Sec. 2.2): the integer codes are carried
+ * as float32 numbers and multiplied and added with float32 operations, one
+ * rounding per operation, summed in order of k.  Equal to the integer product
+ * as long as every partial sum fits the 24-bit significand; beyond that the
+ * sums are rounded.  out [M,N] float32.
+ */
+void oracle_fake_matmul_f32(const int8_t *xq, const int8_t *wq_kn, int64_t M, int64_t K, int64_t N,
+                            float *out) {
+#pragma omp parallel for schedule(static)
+  for (int64_t m = 0; m < M; ++m)
+    for (int64_t n = 0; n < N; ++n) {
+      float a = 0.0f;
+      for (int64_t k = 0; k < K; ++k) {
+        float p = (float)xq[m * K + k] * (float)wq_kn[k * N + n];   /* exact: |p| <= 127 * 127 */
+        a = a + p;                                                 /* one binary32 rounding */
+      }
+      out[m * N + n] = a;
+    }
 }
 
 /*

@@ -30,6 +30,14 @@ int oracle_dense_fwd(const float *x, const float *w, int64_t M, int64_t K, int64
 void oracle_dense_bwd(const float *dy, const int8_t *xq, float s_x, const uint8_t *mask_x, const int8_t *wq_kn,
                       const float *s_w, const uint8_t *mask_w, int64_t M, int64_t K, int64_t N, double *dx,
                       double *dw, double *dbias, double *dx_abs, double *dw_abs);
+int oracle_epilogue_dact(const double *pre, int64_t M, int64_t N, int epilogue, double *dact);
+int oracle_dense_bwd_epi(const float *dout, const double *pre, int epilogue, const int8_t *xq, float s_x,
+                         const uint8_t *mask_x, const int8_t *wq_kn, const float *s_w, const uint8_t *mask_w,
+                         int64_t M, int64_t K, int64_t N, double *dx, double *dw, double *dbias, double *dx_abs,
+                         double *dw_abs, double *dv_out);
+void oracle_layernorm(const float *x, int64_t M, int64_t D, const float *gamma, const float *beta, double eps,
+                      double *y);
+void oracle_fake_matmul_f32(const int8_t *xq, const int8_t *wq_kn, int64_t M, int64_t K, int64_t N, float *out);
 void oracle_dense_fwd_q_sampled(const int8_t *xq, float s_x, const int8_t *wq_kn, const float *s_w, int64_t K,
                                 int64_t N, const float *bias, const int64_t *idx_m, const int64_t *idx_n,
                                 int64_t count, int64_t *acc, double *pre);
@@ -104,6 +112,30 @@ static void one_shape(int64_t M, int64_t K, int64_t N, int bits_x, int bits_w) {
   oracle_dense_bwd(dy, xq, s_x[0], NULL, wq, s_w, NULL, M, K, N, dx, dw, NULL, NULL, NULL);
   if (N > 1) for (int64_t k = 0; k < K; ++k) CHECK(dw[k * N + 1] == 0.0); /* zero scale passes no gradient */
   oracle_dense_bwd(dy, xq, s_x[0], NULL, wq, s_w, NULL, M, K, N, NULL, NULL, db, NULL, NULL);
+
+  /* backward through the activations, the normalisation, the float32-emulated product */
+  double *dv = need(sizeof(double) * M * N), *dact = need(sizeof(double) * M * N);
+  CHECK(oracle_dense_fwd_q(xq, s_x[0], wq, s_w, M, K, N, bias, 0, acc, y, pre) == 0);
+  for (int epi = 0; epi < 3; ++epi) {
+    if (epi == 2 && (N % 2)) {
+      CHECK(oracle_epilogue_dact(pre, M, N, epi, dact) == 2);
+      continue;
+    }
+    CHECK(oracle_epilogue_dact(pre, M, N, epi, dact) == 0);
+    /* dy doubles as dout: [M,N] covers [M,N/2] */
+    CHECK(oracle_dense_bwd_epi(dy, pre, epi, xq, s_x[0], mx, wq, s_w, mw, M, K, N, dx, dw, db, dxa, dwa, dv) == 0);
+    CHECK(oracle_dense_bwd_epi(dy, pre, epi, xq, s_x[0], NULL, wq, s_w, NULL, M, K, N, dx, NULL, NULL, NULL, NULL, NULL) == 0);
+  }
+  double *ln = need(sizeof(double) * M * K);
+  float *gam = need(sizeof(float) * K);
+  for (int64_t i = 0; i < K; ++i) gam[i] = 1.0f + 0.1f * next_unit();
+  oracle_layernorm(x, M, K, NULL, NULL, 1e-6, ln);
+  oracle_layernorm(x, M, K, gam, gam, 1e-6, ln);
+  float *fk = need(sizeof(float) * M * N);
+  oracle_fake_matmul_f32(xq, wq, M, K, N, fk);
+  CHECK(oracle_dense_fwd_q(xq, s_x[0], wq, s_w, M, K, N, NULL, 0, acc, y, pre) == 0);
+  for (int64_t i = 0; i < M * N; ++i) CHECK((int32_t)fk[i] == acc[i]);   /* small K: sums fit 24 bits */
+  free(dv); free(dact); free(ln); free(gam); free(fk);
 
   const int64_t cnt = 5;
   int64_t im[5], in[5], ik[5];

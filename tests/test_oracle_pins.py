@@ -548,3 +548,130 @@ def test_weight_only_half_step_bound_and_sampled_variant():
         np.testing.assert_array_equal(pre, r["pre"][im, inn])
         np.testing.assert_array_equal(mag, r["mag"][im, inn])
     assert errs[8] < errs[4] / 8
+
+
+# ----------------------------------------------------------------------------
+# Backward through the activation (Swish / GLU of the Conformer modules)
+# ----------------------------------------------------------------------------
+def test_activation_derivatives_closed_forms_and_central_differences():
+    # hand-picked points: swish'(0) = 1/2; swish' -> 1 for large v and -> 0 for very negative v;
+    # swish has its minimum where 1 + v (1 - s(v)) = 0, i.e. at v = -1.27846454276...
+    v = np.array([[0.0, 40.0, -40.0, -1.2784645427610738]])
+    d = oracle.epilogue_dact(v, oracle.EPI_SWISH)[0]
+    assert d[0] == 0.5 and abs(d[1] - 1.0) < 1e-15 and abs(d[2]) < 1e-15 and abs(d[3]) < 1e-15
+    # GLU out = a s(g): at g = 0, d/da = 1/2 and d/dg = a/4; columns [a0, a1 | g0, g1]
+    pre = np.array([[3.0, -2.0, 0.0, 0.0]])
+    d = oracle.epilogue_dact(pre, oracle.EPI_GLU)[0]
+    np.testing.assert_array_equal(d, [0.5, 0.5, 0.75, -0.5])
+    np.testing.assert_array_equal(oracle.epilogue_dact(pre, oracle.EPI_NONE), np.ones((1, 4)))
+    # central differences of the activation alone, written out in numpy float64
+    rng = np.random.default_rng(40)
+    pre = rng.standard_normal((5, 8)) * 3
+    sig = lambda t: 1 / (1 + np.exp(-t))
+    swish = lambda t: t * sig(t)
+    glu = lambda t: t[:, :4] * sig(t[:, 4:])
+    h = 1e-5
+    fd = (swish(pre + h) - swish(pre - h)) / (2 * h)
+    np.testing.assert_allclose(oracle.epilogue_dact(pre, oracle.EPI_SWISH), fd, rtol=0, atol=1e-9)
+    dact = oracle.epilogue_dact(pre, oracle.EPI_GLU)
+    for j in range(8):
+        e = np.zeros((5, 8)); e[:, j] = h
+        fdj = (glu(pre + e) - glu(pre - e)) / (2 * h)       # only output column j mod 4 moves
+        np.testing.assert_allclose(dact[:, j], fdj[:, j % 4], rtol=0, atol=1e-9)
+
+
+@pytest.mark.parametrize("epi", [oracle.EPI_SWISH, oracle.EPI_GLU])
+def test_backward_through_activation_against_central_differences_of_the_dequantized_layer(epi):
+    # The loss L = sum(dout * act(x^ w^ + b)) is smooth in the de-quantized operands x^ = s_x xq,
+    # w^ = s_w wq; the straight-through gradients are its partial derivatives.
+    rng = np.random.default_rng(41 + epi)
+    M, K, N = 4, 6, 8
+    c = inputs.small_case(41, M, K, N, 8, 4, epi, with_bias=True)
+    f = oracle.dense_fwd(c.x, c.w, 8, 4, c.bias, epi)
+    oc = N // 2 if epi == oracle.EPI_GLU else N
+    dout = rng.standard_normal((M, oc)).astype(F)
+    g = oracle.dense_bwd_epi(dout, f["pre"], epi, f["xq"], f["s_x"][0], f["wq"], f["s_w"])
+    xh = f["xq"].astype(np.float64) * float(f["s_x"][0])
+    wh = f["wq"].astype(np.float64) * f["s_w"].astype(np.float64)[None, :]
+    b = c.bias.astype(np.float64)
+    sig = lambda t: 1 / (1 + np.exp(-t))
+
+    def loss(xa, wa, ba):
+        v = xa @ wa + ba
+        out = v * sig(v) if epi == oracle.EPI_SWISH else v[:, :oc] * sig(v[:, oc:])
+        return float((out * dout).sum())
+    h = 1e-6
+    for (m, k) in [(0, 0), (3, 5), (2, 1)]:
+        e = np.zeros_like(xh); e[m, k] = h
+        fd = (loss(xh + e, wh, b) - loss(xh - e, wh, b)) / (2 * h)
+        assert g["dx"][m, k] == pytest.approx(fd, rel=1e-6, abs=1e-8)
+    for (k, n) in [(0, 0), (5, 7), (2, 4), (1, 3)]:
+        e = np.zeros_like(wh); e[k, n] = h
+        fd = (loss(xh, wh + e, b) - loss(xh, wh - e, b)) / (2 * h)
+        assert g["dw"][k, n] == pytest.approx(fd, rel=1e-6, abs=1e-8)
+    for n in (0, N - 1):
+        e = np.zeros_like(b); e[n] = h
+        fd = (loss(xh, wh, b + e) - loss(xh, wh, b - e)) / (2 * h)
+        assert g["dbias"][n] == pytest.approx(fd, rel=1e-6, abs=1e-8)
+    # with no activation the new entry is the old one
+    f0 = oracle.dense_fwd(c.x, c.w, 8, 4, c.bias, 0)
+    dy = rng.standard_normal((M, N)).astype(F)
+    g0 = oracle.dense_bwd_epi(dy, f0["pre"], 0, f0["xq"], f0["s_x"][0], f0["wq"], f0["s_w"])
+    g1 = oracle.dense_bwd(dy, f0["xq"], f0["s_x"][0], f0["wq"], f0["s_w"])
+    for key in ("dx", "dw", "dbias"):
+        np.testing.assert_array_equal(g0[key], g1[key])
+
+
+# ----------------------------------------------------------------------------
+# Layer normalisation in front of the feed-forward module
+# ----------------------------------------------------------------------------
+def test_layernorm_hand_worked_rows_and_invariants():
+    # two-element row [a, b]: mean (a+b)/2, biased variance ((a-b)/2)^2 -> y = +-d / sqrt(d^2 + eps), d = (a-b)/2
+    x = np.array([[3.0, 1.0], [5.0, 5.0]], F)
+    y = oracle.layernorm(x, eps=1e-6)
+    r = 1.0 / np.sqrt(1.0 + 1e-6)
+    np.testing.assert_allclose(y, [[r, -r], [0.0, 0.0]], rtol=1e-15, atol=0)
+    # gamma / beta act per column after the normalisation
+    y2 = oracle.layernorm(x, gamma=np.array([2.0, 3.0], F), beta=np.array([0.5, -1.0], F), eps=1e-6)
+    np.testing.assert_allclose(y2, [[2 * r + 0.5, -3 * r - 1.0], [0.5, -1.0]], rtol=1e-15)
+    rng = np.random.default_rng(42)
+    x = (rng.standard_normal((7, 512)) * 3 + 1).astype(F)
+    y = oracle.layernorm(x, eps=1e-6)
+    assert np.abs(y.mean(1)).max() < 1e-12
+    np.testing.assert_allclose(y.var(1), x.astype(np.float64).var(1) / (x.astype(np.float64).var(1) + 1e-6), rtol=1e-12)
+    # shift invariance, and the numpy formula
+    np.testing.assert_allclose(oracle.layernorm(x.astype(np.float64) * 0 + x + F(8.0)), y, rtol=0, atol=2e-5)   # shifted rows, float32 inputs
+    xd = x.astype(np.float64)
+    ref = (xd - xd.mean(1, keepdims=True)) / np.sqrt(xd.var(1, keepdims=True) + 1e-6)
+    np.testing.assert_allclose(y, ref, rtol=1e-12, atol=1e-14)
+
+
+# ----------------------------------------------------------------------------
+# "Fake" quantization arithmetic: integers carried in float32 (Sec. 1, Sec. 2.2)
+# ----------------------------------------------------------------------------
+def test_fake_float32_product_equals_integers_until_24_bits_then_rounds():
+    rng = np.random.default_rng(43)
+    # K * 127 * 127 < 2^24  <=>  K <= 1040: every partial sum is an exactly representable integer
+    K = 1040
+    xq = rng.integers(-127, 128, (6, K)).astype(np.int8)
+    wq = rng.integers(-127, 128, (K, 5)).astype(np.int8)
+    xq[0, :], wq[:, 0] = 127, 127                       # the largest possible sum
+    exact = xq.astype(np.int64) @ wq.astype(np.int64)
+    fake = oracle.fake_matmul_f32(xq, wq)
+    assert exact.max() == K * 127 * 127 < 2 ** 24
+    np.testing.assert_array_equal(fake.astype(np.int64), exact)
+    # hand-worked case beyond 24 bits: 1041 terms of 127*127 = 16129 reach 16790289 > 2^24 = 16777216;
+    # float32 spacing there is 2, so the last (odd) sum is rounded to even: 16790288
+    xq = np.full((1, 1041), 127, np.int8)
+    wq = np.full((1041, 1), 127, np.int8)
+    fake = oracle.fake_matmul_f32(xq, wq)
+    assert (xq.astype(np.int64) @ wq.astype(np.int64)).item() == 16790289
+    assert float(fake[0, 0]) == 16790288.0
+    # in general the float32 sums stay within K roundings of the exact integers
+    K = 4096
+    xq = rng.integers(-127, 128, (8, K)).astype(np.int8)
+    wq = rng.integers(100, 128, (K, 8)).astype(np.int8)
+    xq[:] = np.abs(xq)                                  # same-sign terms: sums of about 2^25
+    exact = xq.astype(np.int64) @ wq.astype(np.int64)
+    fake = oracle.fake_matmul_f32(xq, wq).astype(np.float64)
+    assert (fake != exact).any() and np.abs(fake - exact).max() <= K * 2.0 ** -24 * exact.max()
