@@ -136,6 +136,7 @@ static void one_shape(int64_t M, int64_t K, int64_t N, int bits_x, int bits_w) {
   CHECK(oracle_dense_fwd_q(xq, s_x[0], wq, s_w, M, K, N, NULL, 0, acc, y, pre) == 0);
   for (int64_t i = 0; i < M * N; ++i) CHECK((int32_t)fk[i] == acc[i]);   /* small K: sums fit 24 bits */
   free(dv); free(dact); free(ln); free(gam); free(fk);
+  oracle_dense_bwd(dy, xq, s_x[0], NULL, wq, s_w, NULL, M, K, N, dx, NULL, NULL, NULL, NULL);
 
   const int64_t cnt = 5;
   int64_t im[5], in[5], ik[5];
