@@ -64,6 +64,10 @@ typedef int aqt_status;
 #define AQT_OP_DENSE_FWD_Q 3
 #define AQT_OP_DENSE_BWD 4
 #define AQT_OP_DENSE_FWD_WONLY 5
+#define AQT_OP_DENSE_BWD_EPI 6         /* aqt_dense_bwd with an activation: M, K, N            */
+#define AQT_OP_LAYERNORM_QUANTIZE 7    /* M rows; K = row length; N unused                     */
+#define AQT_OP_FFN_FWD 8               /* M tokens, K = model width D, N = inner width H       */
+#define AQT_OP_FFN_BWD 9
 
 /* What the forward keeps for the backward.  All caller-owned device buffers. */
 typedef struct aqt_saved {
@@ -74,6 +78,8 @@ typedef struct aqt_saved {
   int8_t *wq_kn;     /* [K,N] weight codes in the layout of W (backward operand)        */
   float *s_w;        /* [N]   weight scales                                             */
   uint32_t *mask_w;  /* nullable: ceil(K*N/32) words over W's [K,N] order               */
+  float *dact;       /* nullable: [M,N] derivative factors of the activation (Swish / GLU);  */
+                     /* written by the forward when given, required by the backward then   */
 } aqt_saved;
 
 const char *aqt_status_string(aqt_status s); /* host, static storage */
@@ -231,12 +237,18 @@ aqt_status aqt_dense_fwd(const float *x, const float *w, int64_t M, int64_t K, i
                          void *ws, size_t ws_bytes, void *stream, int32_t *dev_status);
 
 /*
- * Straight-through backward of v = (s_x xq)(s_w wq) + bias with the scales held
- * constant (Fig. 2, stop_gradient):
- *   dx[m,k]  = mask_x[m,k] * sum_n (dy[m,n] * s_w[n]) * wq[k,n]
- *   dw[k,n]  = mask_w[k,n] * s_x * sum_m xq[m,k] * dy[m,n]
- *   dbias[n] = sum_m dy[m,n]
- * dy is the gradient with respect to v (epilogue AQT_EPI_NONE).  Any of dx, dw,
+ * Straight-through backward of out = act(v), v = (s_x xq)(s_w wq) + bias, with the scales
+ * held constant (Fig. 2, stop_gradient):
+ *   dv[m,n]  = dy[m, n mod out_cols] * dact[m,n]      (dv = dy when epilogue is AQT_EPI_NONE)
+ *   dx[m,k]  = mask_x[m,k] * sum_n (dv[m,n] * s_w[n]) * wq[k,n]
+ *   dw[k,n]  = mask_w[k,n] * s_x * sum_m xq[m,k] * dv[m,n]
+ *   dbias[n] = sum_m dv[m,n]
+ * dy is the gradient with respect to the layer's output: [M,N], or [M,N/2] for GLU.
+ * With an activation (the Swish of the Conformer feed-forward module, the GLU of its
+ * convolution module, Sec. 3.2) saved->dact must hold the factors the forward wrote:
+ *   Swish: dact = s(v) (1 + v (1 - s(v)));   GLU: dact[m,j] = s(g), dact[m,j+N/2] = a s(g) (1 - s(g)),
+ * s the logistic function, a / g the value / gate halves of v; the workspace is then
+ * aqt_workspace_bytes(AQT_OP_DENSE_BWD_EPI, ...).  Any of dx, dw,
  * dbias may be NULL to skip it.  A NULL mask means "1 where the group's scale
  * is non-zero", which is what abs-max scaling always produces.  Results are
  * float32; the contractions run as two bf16 MFMA passes over a hi/lo split of
@@ -244,8 +256,106 @@ aqt_status aqt_dense_fwd(const float *x, const float *w, int64_t M, int64_t K, i
  * Uses saved->xq, s_x, wq_kn, s_w and the masks.
  */
 aqt_status aqt_dense_bwd(const float *dy, const aqt_saved *saved, int64_t M, int64_t K, int64_t N,
-                         int bits_x, int bits_w, float *dx, float *dw, float *dbias, void *ws,
+                         int bits_x, int bits_w, int epilogue, float *dx, float *dw, float *dbias, void *ws,
                          size_t ws_bytes, void *stream);
+
+/*
+ * Layer normalisation of every row of x [M,D] (mean and biased variance over the row,
+ * y = (x - mean) / sqrt(var + eps) * gamma + beta, float32; gamma / beta nullable) fused
+ * with the per-tensor quantizer of Fig. 2 applied to y: the normalisation in front of the
+ * Conformer feed-forward module (Sec. 3.2) feeds a quantized layer, so y itself is never
+ * written.  Pass 1 takes the row statistics and max|y|; pass 2 re-forms y (same
+ * arithmetic, same bits) and emits codes and scale exactly as aqt_quantize would on y.
+ *   q [M,D] int8 and scale [1]: nullable together (then only y_out is produced);
+ *   y_out nullable [M,D]: the normalised values themselves (for checking, or for a
+ *   float consumer);  row_stats nullable [M,2]: mean and 1/sqrt(var + eps) per row.
+ */
+aqt_status aqt_layernorm_quantize(const float *x, int64_t M, int64_t D, const float *gamma, const float *beta,
+                                  float eps, int bits, int8_t *q, float *scale, float *y_out, float *row_stats,
+                                  void *ws, size_t ws_bytes, void *stream, int32_t *dev_status);
+
+/*
+ * The product of the codes as "fake" quantization computes it on hardware without integer
+ * matrix units (Sec. 1, Sec. 2.2): codes carried in float32, float32 multiply-accumulate
+ * (the float32 matrix cores).  out[m,n] = sum_k float(xq[m,k]) * float(wq_kn[k,n]), exact
+ * while every partial sum fits the 24-bit significand (K * qmax_x * qmax_w < 2^24), rounded
+ * beyond.  A comparator for the native integer product of aqt_dense_fwd_q, not a path
+ * of the layer.  xq [M,K], wq_kn [K,N] int8, out [M,N] float32.
+ */
+aqt_status aqt_fake_matmul_f32(const int8_t *xq, const int8_t *wq_kn, int64_t M, int64_t K, int64_t N,
+                               float *out, void *stream);
+
+/*
+ * Per-layer precision (Sec. 4.1: configurations I8W, I4W, I8WA, I4WI8A, I4WA; Sec. 4.2 /
+ * Table 2: int4 on chosen layers, int8 on the rest).  bits_x = 0 means float32
+ * activations (the weight-only modes).
+ */
+typedef struct aqt_dense_policy {
+  int bits_w; /* 2..8 */
+  int bits_x; /* 2..8, or 0 = float32 activations */
+} aqt_dense_policy;
+
+/* The eight dense layers of one Conformer encoder layer (Sec. 3.2). */
+typedef struct aqt_layer_policy {
+  aqt_dense_policy ffn1_in, ffn1_out; /* first feed-forward module                           */
+  aqt_dense_policy attn_qkv, attn_out; /* self-attention projections                          */
+  aqt_dense_policy conv_pw1, conv_pw2; /* pointwise convolutions of the convolution module    */
+  aqt_dense_policy ffn2_in, ffn2_out; /* second feed-forward module                          */
+} aqt_layer_policy;
+
+#define AQT_POLICY_ALL 0              /* every layer at bits_w (Table 2: E1 int8, E3 int4)       */
+#define AQT_POLICY_EXCEPT_FIRST_LAST 1 /* first and last encoder layer stay int8 (E6)              */
+#define AQT_POLICY_EXCEPT_ATTENTION 2  /* self-attention projections stay int8 (E7)                */
+#define AQT_POLICY_FIRST_K 3           /* only the first k encoder layers get bits_w (E8 - E13)    */
+
+/*
+ * Fill out[0..n_layers) (host memory) with one of Table 2's patterns: layers the pattern
+ * selects get bits_w weights, all others int8 weights; every layer gets bits_x activations.
+ * k is only used by AQT_POLICY_FIRST_K.
+ */
+aqt_status aqt_policy_preset(int pattern, int n_layers, int k, int bits_w, int bits_x, aqt_layer_policy *out);
+
+/*
+ * Bytes the quantized weights of n_layers encoder layers take under a policy (packed codes
+ * plus one float32 scale per output channel; model width d_model, feed-forward width d_ff):
+ * the model-size side of Table 2's trade-off.  Host computation.
+ */
+size_t aqt_policy_weight_bytes(const aqt_layer_policy *policy, int n_layers, int64_t d_model, int64_t d_ff);
+
+/* What the feed-forward module keeps for its backward.  Caller-owned device buffers. */
+typedef struct aqt_ffn_saved {
+  aqt_saved l1;     /* first layer  [M,D] x [D,H]; l1.dact [M,H] required for aqt_ffn_bwd         */
+  aqt_saved l2;     /* second layer [M,H] x [H,D]                                                 */
+  float *h;         /* [M,H] output of the first layer after Swish                                */
+  float *xn;        /* [M,D] normalised input in float32: required when policy[0].bits_x == 0     */
+  float *row_stats; /* nullable [M,2]: mean and reciprocal standard deviation of every input row */
+} aqt_ffn_saved;
+
+/*
+ * The Conformer feed-forward module (Sec. 3.2) on quantized layers, as one call:
+ *   xn = layernorm(x);  h = swish(dense(xn, w1) + b1);  y = dense(h, w2) + b2
+ * with each dense layer at its policy[i] precision (policy[0]: first layer, policy[1]:
+ * second).  Integer activations: the normalisation is fused with the first quantizer
+ * (aqt_layernorm_quantize), the first contraction emits max|h| and the second quantizer
+ * runs in one pass (aqt_dense_fwd_q_absmax, aqt_quantize_with_absmax).  Float32
+ * activations (bits_x = 0) take aqt_dense_fwd_wonly.
+ *   x [M,D]; w1 [D,H], b1 nullable [H]; w2 [H,D], b2 nullable [D]; y [M,D].
+ */
+aqt_status aqt_ffn_fwd(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps,
+                       const float *w1, const float *b1, const float *w2, const float *b2, int64_t M, int64_t D,
+                       int64_t H, const aqt_dense_policy *policy, float *y, const aqt_ffn_saved *saved, void *ws,
+                       size_t ws_bytes, void *stream, int32_t *dev_status);
+
+/*
+ * Straight-through backward of aqt_ffn_fwd down to the normalised input:
+ *   dxn [M,D] (gradient with respect to layernorm(x)), dw1 [D,H], db1 [H], dw2 [H,D], db2 [D];
+ * any of them may be NULL.  Needs integer activations in both layers (a weight-only layer's
+ * weight gradient contracts two float tensors, which this library does not do) and the
+ * buffers aqt_ffn_fwd filled.  The normalisation's own backward is left to the caller.
+ */
+aqt_status aqt_ffn_bwd(const float *dy, const aqt_ffn_saved *saved, int64_t M, int64_t D, int64_t H,
+                       const aqt_dense_policy *policy, float *dxn, float *dw1, float *db1, float *dw2,
+                       float *db2, void *ws, size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -19,14 +19,17 @@ LIB_PATH = os.path.join(_PKG, "libaqt.so")
 AQT_OK, AQT_ERR_INVALID_ARG, AQT_ERR_UNSUPPORTED, AQT_ERR_WORKSPACE, AQT_ERR_HIP, AQT_ERR_NONFINITE, AQT_ERR_SCRATCH = range(7)
 AQT_AXIS_ALL, AQT_AXIS_ROWS, AQT_AXIS_COLS = -1, 0, 1
 AQT_EPI_NONE, AQT_EPI_SWISH, AQT_EPI_GLU = 0, 1, 2
-AQT_OP_QUANTIZE, AQT_OP_QUANTIZE_WEIGHTS, AQT_OP_DENSE_FWD, AQT_OP_DENSE_FWD_Q, AQT_OP_DENSE_BWD, AQT_OP_DENSE_FWD_WONLY = range(6)
+(AQT_OP_QUANTIZE, AQT_OP_QUANTIZE_WEIGHTS, AQT_OP_DENSE_FWD, AQT_OP_DENSE_FWD_Q, AQT_OP_DENSE_BWD,
+ AQT_OP_DENSE_FWD_WONLY, AQT_OP_DENSE_BWD_EPI, AQT_OP_LAYERNORM_QUANTIZE, AQT_OP_FFN_FWD, AQT_OP_FFN_BWD) = range(10)
+AQT_POLICY_ALL, AQT_POLICY_EXCEPT_FIRST_LAST, AQT_POLICY_EXCEPT_ATTENTION, AQT_POLICY_FIRST_K = range(4)
 
 # every symbol include/aqt.h declares
 SYMBOLS = ["aqt_status_string", "aqt_last_hip_error", "aqt_version", "aqt_workspace_bytes",
            "aqt_packed_weight_bytes", "aqt_quantize", "aqt_quantize_with_scale", "aqt_quantize_weights",
            "aqt_unpack_weights", "aqt_dense_fwd_q", "aqt_dense_fwd_q_absmax", "aqt_quantize_with_absmax",
            "aqt_dense_fwd_wonly", "aqt_dense_fwd", "aqt_dense_bwd", "aqt_dense_fwd_q_static",
-           "aqt_static_scratch_bytes"]
+           "aqt_static_scratch_bytes", "aqt_layernorm_quantize", "aqt_fake_matmul_f32", "aqt_policy_preset",
+           "aqt_policy_weight_bytes", "aqt_ffn_fwd", "aqt_ffn_bwd"]
 
 
 class AqtError(RuntimeError):
@@ -41,7 +44,21 @@ class AqtError(RuntimeError):
 class aqt_saved(ctypes.Structure):
     _fields_ = [("xq", ctypes.c_void_p), ("s_x", ctypes.c_void_p), ("mask_x", ctypes.c_void_p),
                 ("wq_packed", ctypes.c_void_p), ("wq_kn", ctypes.c_void_p), ("s_w", ctypes.c_void_p),
-                ("mask_w", ctypes.c_void_p)]
+                ("mask_w", ctypes.c_void_p), ("dact", ctypes.c_void_p)]
+
+
+class aqt_dense_policy(ctypes.Structure):
+    _fields_ = [("bits_w", ctypes.c_int), ("bits_x", ctypes.c_int)]
+
+
+class aqt_layer_policy(ctypes.Structure):
+    _fields_ = [(n, aqt_dense_policy) for n in ("ffn1_in", "ffn1_out", "attn_qkv", "attn_out", "conv_pw1",
+                                                "conv_pw2", "ffn2_in", "ffn2_out")]
+
+
+class aqt_ffn_saved(ctypes.Structure):
+    _fields_ = [("l1", aqt_saved), ("l2", aqt_saved), ("h", ctypes.c_void_p), ("xn", ctypes.c_void_p),
+                ("row_stats", ctypes.c_void_p)]
 
 
 _lib = None
@@ -78,8 +95,19 @@ def lib() -> ctypes.CDLL:
         L.aqt_dense_fwd_wonly.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _int, _vp, _int, _vp, _vp, _sz, _vp]
         L.aqt_dense_fwd.argtypes = [_vp, _vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp,
                                     ctypes.POINTER(aqt_saved), _vp, _sz, _vp, _vp]
-        L.aqt_dense_bwd.argtypes = [_vp, ctypes.POINTER(aqt_saved), _i64, _i64, _i64, _int, _int, _vp, _vp, _vp,
-                                    _vp, _sz, _vp]
+        L.aqt_dense_bwd.argtypes = [_vp, ctypes.POINTER(aqt_saved), _i64, _i64, _i64, _int, _int, _int, _vp, _vp,
+                                    _vp, _vp, _sz, _vp]
+        L.aqt_layernorm_quantize.argtypes = [_vp, _i64, _i64, _vp, _vp, ctypes.c_float, _int, _vp, _vp, _vp, _vp,
+                                             _vp, _sz, _vp, _vp]
+        L.aqt_fake_matmul_f32.argtypes = [_vp, _vp, _i64, _i64, _i64, _vp, _vp]
+        L.aqt_policy_preset.argtypes = [_int, _int, _int, _int, _int, ctypes.POINTER(aqt_layer_policy)]
+        L.aqt_policy_weight_bytes.restype = _sz
+        L.aqt_policy_weight_bytes.argtypes = [ctypes.POINTER(aqt_layer_policy), _int, _i64, _i64]
+        L.aqt_ffn_fwd.argtypes = [_vp, _vp, _vp, ctypes.c_float, _vp, _vp, _vp, _vp, _i64, _i64, _i64,
+                                  ctypes.POINTER(aqt_dense_policy), _vp, ctypes.POINTER(aqt_ffn_saved), _vp, _sz,
+                                  _vp, _vp]
+        L.aqt_ffn_bwd.argtypes = [_vp, ctypes.POINTER(aqt_ffn_saved), _i64, _i64, _i64,
+                                  ctypes.POINTER(aqt_dense_policy), _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
         for name in SYMBOLS:
             getattr(L, name)  # AttributeError if the library lacks a declared entry point
         _lib = L
@@ -269,8 +297,10 @@ def aqt_dense_fwd_wonly(x, wq_packed, s_w, N: int, bits_w: int, *, bias=None, ep
 class Saved:
     """Device buffers the forward keeps for the backward, plus their aqt_saved view."""
 
-    def __init__(self, M: int, K: int, N: int, bits_w: int, device="cuda", masks: bool = False):
+    def __init__(self, M: int, K: int, N: int, bits_w: int, device="cuda", masks: bool = False,
+                 dact: bool = False):
         self.M, self.K, self.N, self.bits_w = M, K, N, bits_w
+        self.dact = torch.empty((M, N), dtype=torch.float32, device=device) if dact else None
         self.xq = torch.empty((M, K), dtype=torch.int8, device=device)
         self.s_x = torch.empty(1, dtype=torch.float32, device=device)
         self.wq_packed = torch.empty(aqt_packed_weight_bytes(K, N, bits_w), dtype=torch.uint8, device=device)
@@ -284,7 +314,7 @@ class Saved:
         def a(t):
             return None if t is None else t.data_ptr()
         self.c = aqt_saved(a(self.xq), a(self.s_x), a(self.mask_x), a(self.wq_packed), a(self.wq_kn),
-                           a(self.s_w), a(self.mask_w))
+                           a(self.s_w), a(self.mask_w), a(self.dact))
         return self
 
 
@@ -305,11 +335,13 @@ def aqt_dense_fwd(x, w, bits_x: int, bits_w: int, *, bias=None, epilogue: int = 
     return y
 
 
-def aqt_dense_bwd(dy, saved: Saved, bits_x: int, bits_w: int, *, dx=None, dw=None, dbias=None,
-                  want_dx=True, want_dw=True, want_dbias=False, ws=None):
-    """aqt_dense_bwd: returns (dx [M,K], dw [K,N], dbias [N]); skipped outputs are None."""
+def aqt_dense_bwd(dy, saved: Saved, bits_x: int, bits_w: int, *, epilogue: int = AQT_EPI_NONE, dx=None, dw=None,
+                  dbias=None, want_dx=True, want_dw=True, want_dbias=False, ws=None):
+    """aqt_dense_bwd: returns (dx [M,K], dw [K,N], dbias [N]); skipped outputs are None.
+    dy is the gradient with respect to the layer's output ([M,N/2] for GLU)."""
     _dev(dy, torch.float32, "dy")
-    M, N = dy.shape
+    M = dy.shape[0]
+    N = saved.N
     K = saved.K
     if want_dx and dx is None:
         dx = torch.empty((M, K), dtype=torch.float32, device=dy.device)
@@ -318,8 +350,96 @@ def aqt_dense_bwd(dy, saved: Saved, bits_x: int, bits_w: int, *, dx=None, dw=Non
     if want_dbias and dbias is None:
         dbias = torch.empty(N, dtype=torch.float32, device=dy.device)
     if ws is None:
-        ws = workspace(aqt_workspace_bytes(AQT_OP_DENSE_BWD, M, K, N, bits_x, bits_w), dy.device)
-    st = lib().aqt_dense_bwd(_ptr(dy), ctypes.byref(saved.c), M, K, N, bits_x, bits_w, _ptr(dx), _ptr(dw),
+        op = AQT_OP_DENSE_BWD if epilogue == AQT_EPI_NONE else AQT_OP_DENSE_BWD_EPI
+        ws = workspace(aqt_workspace_bytes(op, M, K, N, bits_x, bits_w), dy.device)
+    st = lib().aqt_dense_bwd(_ptr(dy), ctypes.byref(saved.c), M, K, N, bits_x, bits_w, epilogue, _ptr(dx), _ptr(dw),
                              _ptr(dbias), _ptr(ws), ws.numel(), _stream())
     _check(st, "aqt_dense_bwd")
     return dx, dw, dbias
+
+
+def aqt_layernorm_quantize(x, bits: int = 8, *, gamma=None, beta=None, eps: float = 1e-6, quantize=True,
+                           want_y=False, want_stats=False, ws=None, dev_status=None):
+    """aqt_layernorm_quantize: returns (q int8 or None, scale or None, y float32 or None, row_stats or None)."""
+    _dev(x, torch.float32, "x")
+    M, D = x.shape
+    q = torch.empty((M, D), dtype=torch.int8, device=x.device) if quantize else None
+    scale = torch.empty(1, dtype=torch.float32, device=x.device) if quantize else None
+    y = torch.empty((M, D), dtype=torch.float32, device=x.device) if want_y else None
+    stats = torch.empty((M, 2), dtype=torch.float32, device=x.device) if want_stats else None
+    ws = workspace(aqt_workspace_bytes(AQT_OP_LAYERNORM_QUANTIZE, M, D, 1), x.device) if ws is None else ws
+    st = lib().aqt_layernorm_quantize(_ptr(x), M, D, _ptr(gamma), _ptr(beta), eps, bits, _ptr(q), _ptr(scale),
+                                      _ptr(y), _ptr(stats), _ptr(ws), ws.numel(), _stream(), _ptr(dev_status))
+    _check(st, "aqt_layernorm_quantize")
+    return q, scale, y, stats
+
+
+def aqt_fake_matmul_f32(xq, wq_kn, *, out=None):
+    """aqt_fake_matmul_f32: product of the codes carried and accumulated in float32."""
+    _dev(xq, torch.int8, "xq")
+    _dev(wq_kn, torch.int8, "wq_kn")
+    M, K = xq.shape
+    N = wq_kn.shape[1]
+    out = torch.empty((M, N), dtype=torch.float32, device=xq.device) if out is None else out
+    st = lib().aqt_fake_matmul_f32(_ptr(xq), _ptr(wq_kn), M, K, N, _ptr(out), _stream())
+    _check(st, "aqt_fake_matmul_f32")
+    return out
+
+
+def aqt_policy_preset(pattern: int, n_layers: int, k: int, bits_w: int, bits_x: int):
+    """aqt_policy_preset: returns a ctypes array of n_layers aqt_layer_policy (host memory, no GPU)."""
+    arr = (aqt_layer_policy * n_layers)()
+    st = lib().aqt_policy_preset(pattern, n_layers, k, bits_w, bits_x, arr)
+    _check(st, "aqt_policy_preset")
+    return arr
+
+
+def aqt_policy_weight_bytes(policy, n_layers: int, d_model: int, d_ff: int) -> int:
+    return int(lib().aqt_policy_weight_bytes(policy, n_layers, d_model, d_ff))
+
+
+class FfnSaved:
+    """Device buffers of the feed-forward module (aqt_ffn_fwd / aqt_ffn_bwd) and their aqt_ffn_saved view."""
+
+    def __init__(self, M: int, D: int, H: int, policy, device="cuda"):
+        (bw1, bx1), (bw2, bx2) = policy
+        self.M, self.D, self.H = M, D, H
+        self.l1 = Saved(M, D, H, bw1, device, dact=True)
+        self.l2 = Saved(M, H, D, bw2, device)
+        self.h = torch.empty((M, H), dtype=torch.float32, device=device)
+        self.xn = torch.empty((M, D), dtype=torch.float32, device=device)
+        self.row_stats = torch.empty((M, 2), dtype=torch.float32, device=device)
+        self.policy = (aqt_dense_policy * 2)(aqt_dense_policy(bw1, bx1), aqt_dense_policy(bw2, bx2))
+        self.c = aqt_ffn_saved(self.l1.c, self.l2.c, self.h.data_ptr(), self.xn.data_ptr(), self.row_stats.data_ptr())
+
+
+def aqt_ffn_fwd(x, w1, b1, w2, b2, saved: FfnSaved, *, gamma=None, beta=None, eps: float = 1e-6, y=None, ws=None,
+                dev_status=None):
+    """aqt_ffn_fwd: y = dense(swish(dense(layernorm(x), w1) + b1), w2) + b2 at the saved policy's precisions."""
+    _dev(x, torch.float32, "x")
+    M, D = x.shape
+    H = w1.shape[1]
+    y = torch.empty((M, D), dtype=torch.float32, device=x.device) if y is None else y
+    ws = workspace(aqt_workspace_bytes(AQT_OP_FFN_FWD, M, D, H), x.device) if ws is None else ws
+    st = lib().aqt_ffn_fwd(_ptr(x), _ptr(gamma), _ptr(beta), eps, _ptr(w1), _ptr(b1), _ptr(w2), _ptr(b2), M, D, H,
+                           saved.policy, _ptr(y), ctypes.byref(saved.c), _ptr(ws), ws.numel(), _stream(),
+                           _ptr(dev_status))
+    _check(st, "aqt_ffn_fwd")
+    return y
+
+
+def aqt_ffn_bwd(dy, saved: FfnSaved, *, want_db=True, ws=None):
+    """aqt_ffn_bwd: returns (dxn [M,D], dw1 [D,H], db1 [H] or None, dw2 [H,D], db2 [D] or None)."""
+    _dev(dy, torch.float32, "dy")
+    M, D, H = saved.M, saved.D, saved.H
+    dev = dy.device
+    dxn = torch.empty((M, D), dtype=torch.float32, device=dev)
+    dw1 = torch.empty((D, H), dtype=torch.float32, device=dev)
+    dw2 = torch.empty((H, D), dtype=torch.float32, device=dev)
+    db1 = torch.empty(H, dtype=torch.float32, device=dev) if want_db else None
+    db2 = torch.empty(D, dtype=torch.float32, device=dev) if want_db else None
+    ws = workspace(aqt_workspace_bytes(AQT_OP_FFN_BWD, M, D, H), dev) if ws is None else ws
+    st = lib().aqt_ffn_bwd(_ptr(dy), ctypes.byref(saved.c), M, D, H, saved.policy, _ptr(dxn), _ptr(dw1), _ptr(db1),
+                           _ptr(dw2), _ptr(db2), _ptr(ws), ws.numel(), _stream())
+    _check(st, "aqt_ffn_bwd")
+    return dxn, dw1, db1, dw2, db2

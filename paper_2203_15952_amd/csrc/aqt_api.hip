@@ -41,6 +41,44 @@ FwdWorkspace carve_fwd(void *ws, int64_t M, int64_t K, int64_t N, int bits_w) {
 
 bool shape_ok(int64_t a, int64_t b) { return a >= 1 && b >= 1; }
 
+struct FfnWorkspace {
+  void *ln;          // layer-normalisation scratch
+  uint32_t *wpart1;  // per-channel slab maxima, first / second weight matrix
+  uint32_t *wpart2;
+  void *wfrag1;      // weights in MFMA-fragment order (also large enough for the weight-only forward)
+  void *wfrag2;
+  float *h_absmax;   // max|h| emitted by the first contraction
+  size_t total;
+};
+
+FfnWorkspace carve_ffn_fwd(void *ws, int64_t M, int64_t D, int64_t H) {
+  FfnWorkspace f;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    uint8_t *p = ws ? static_cast<uint8_t *>(ws) + off : nullptr;
+    off += align_up(bytes, 256);
+    return p;
+  };
+  f.ln = take(layernorm_ws_bytes(M));
+  f.wpart1 = reinterpret_cast<uint32_t *>(take(weight_ws_bytes(H)));
+  f.wpart2 = reinterpret_cast<uint32_t *>(take(weight_ws_bytes(D)));
+  const size_t frag = fwd_wonly_workspace_bytes(D, H);   // 2 bytes per weight covers both forward kinds
+  f.wfrag1 = take(frag);
+  f.wfrag2 = take(frag);
+  f.h_absmax = reinterpret_cast<float *>(take(sizeof(float)));
+  f.total = off;
+  return f;
+}
+
+// Backward of the feed-forward module: one dense-backward workspace large enough for either
+// layer, reused, plus the gradient with respect to h, [M,H].
+size_t ffn_bwd_ws(int64_t M, int64_t D, int64_t H) {
+  const size_t a = bwd_workspace_bytes(M, D, H), b = bwd_workspace_bytes(M, H, D);
+  return (a > b ? a : b) + align_up(static_cast<size_t>(M) * H * sizeof(float), 256);
+}
+
+bool policy_ok(const aqt_dense_policy &p) { return bits_ok(p.bits_w) && (p.bits_x == 0 || bits_ok(p.bits_x)); }
+
 // The int32 accumulator must hold K * qmax_x * qmax_w; packed (<= 4 bit) weights enter the
 // matrix cores as 16 * code, so their sums carry a factor 16 until the final shift.
 bool acc_fits(int64_t K, int bits_x, int bits_w) {
@@ -90,6 +128,16 @@ size_t aqt_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int bits_x, 
     case AQT_OP_DENSE_BWD:
       if (!shape_ok(M, K) || N < 1) return 0;
       return bwd_workspace_bytes(M, K, N);
+    case AQT_OP_DENSE_BWD_EPI:
+      if (!shape_ok(M, K) || N < 1) return 0;
+      return bwd_workspace_bytes(M, K, N) + align_up(static_cast<size_t>(M) * N * sizeof(float), 256);
+    case AQT_OP_LAYERNORM_QUANTIZE: return M >= 1 ? layernorm_ws_bytes(M) : 0;
+    case AQT_OP_FFN_FWD:
+      if (!shape_ok(M, K) || N < 1) return 0;
+      return carve_ffn_fwd(nullptr, M, K, N).total;
+    case AQT_OP_FFN_BWD:
+      if (!shape_ok(M, K) || N < 1) return 0;
+      return ffn_bwd_ws(M, K, N);
     default: return 0;
   }
 }
@@ -217,20 +265,162 @@ aqt_status aqt_dense_fwd(const float *x, const float *w, int64_t M, int64_t K, i
                           f.partials, st, dev_status));
   AQT_TRY(launch_quantize_weights(w, K, N, bits_w, wq, s_w, saved ? saved->wq_kn : nullptr,
                                   saved ? saved->mask_w : nullptr, f.wpart, st, dev_status));
-  return launch_dense_fwd_q(xq, s_x, wq, s_w, M, K, N, bits_w, bias, epilogue, y, nullptr, nullptr, f.wfrag, st);
+  return launch_dense_fwd_q(xq, s_x, wq, s_w, M, K, N, bits_w, bias, epilogue, y, nullptr, nullptr, f.wfrag, st,
+                            saved ? saved->dact : nullptr);
 }
 
 aqt_status aqt_dense_bwd(const float *dy, const aqt_saved *saved, int64_t M, int64_t K, int64_t N, int bits_x,
-                         int bits_w, float *dx, float *dw, float *dbias, void *ws, size_t ws_bytes,
+                         int bits_w, int epilogue, float *dx, float *dw, float *dbias, void *ws, size_t ws_bytes,
                          void *stream) {
   if (!dy || !saved || !shape_ok(M, K) || N < 1) return AQT_ERR_INVALID_ARG;
+  if (epilogue != AQT_EPI_NONE && epilogue != AQT_EPI_SWISH && epilogue != AQT_EPI_GLU) return AQT_ERR_INVALID_ARG;
   if (!bits_ok(bits_x) || !bits_ok(bits_w)) return AQT_ERR_UNSUPPORTED;
+  if (epilogue == AQT_EPI_GLU && (N % 2)) return AQT_ERR_UNSUPPORTED;
   if (!saved->s_x || !saved->s_w) return AQT_ERR_INVALID_ARG;
   if (dx && !saved->wq_kn) return AQT_ERR_INVALID_ARG;
   if (dw && !saved->xq) return AQT_ERR_INVALID_ARG;
-  const size_t need = bwd_workspace_bytes(M, K, N);
+  if (epilogue != AQT_EPI_NONE && !saved->dact) return AQT_ERR_INVALID_ARG;
+  const size_t core = bwd_workspace_bytes(M, K, N);
+  const size_t need = core + (epilogue != AQT_EPI_NONE ? align_up(static_cast<size_t>(M) * N * sizeof(float), 256) : 0);
   if (!ws || ws_bytes < need) return AQT_ERR_WORKSPACE;
-  return launch_dense_bwd(dy, saved, M, K, N, dx, dw, dbias, ws, ws_bytes, static_cast<hipStream_t>(stream));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const float *dv = dy;
+  if (epilogue != AQT_EPI_NONE) {
+    // chain rule through the activation first: dv = dy * dact, [M,N], behind the core workspace
+    float *buf = reinterpret_cast<float *>(static_cast<uint8_t *>(ws) + core);
+    AQT_TRY(launch_dact_mul(dy, saved->dact, M, N, epilogue == AQT_EPI_GLU ? N / 2 : N, buf, st));
+    dv = buf;
+  }
+  return launch_dense_bwd(dv, saved, M, K, N, dx, dw, dbias, ws, core, st);
+}
+
+aqt_status aqt_layernorm_quantize(const float *x, int64_t M, int64_t D, const float *gamma, const float *beta,
+                                  float eps, int bits, int8_t *q, float *scale, float *y_out, float *row_stats,
+                                  void *ws, size_t ws_bytes, void *stream, int32_t *dev_status) {
+  if (!x || !shape_ok(M, D) || !(eps >= 0.0f)) return AQT_ERR_INVALID_ARG;
+  if ((q == nullptr) != (scale == nullptr)) return AQT_ERR_INVALID_ARG;
+  if (!q && !y_out) return AQT_ERR_INVALID_ARG;
+  if (q && !bits_ok(bits)) return AQT_ERR_UNSUPPORTED;
+  if (!ws || ws_bytes < layernorm_ws_bytes(M)) return AQT_ERR_WORKSPACE;
+  return launch_layernorm_quantize(x, M, D, gamma, beta, eps, bits, q, scale, y_out, row_stats, ws,
+                                   static_cast<hipStream_t>(stream), dev_status);
+}
+
+aqt_status aqt_fake_matmul_f32(const int8_t *xq, const int8_t *wq_kn, int64_t M, int64_t K, int64_t N, float *out,
+                               void *stream) {
+  if (!xq || !wq_kn || !out || !shape_ok(M, K) || N < 1) return AQT_ERR_INVALID_ARG;
+  if (M >= (int64_t(1) << 31) / (K > N ? K : N) || cdiv(M, 128) > 65535) return AQT_ERR_UNSUPPORTED;
+  return launch_fake_matmul_f32(xq, wq_kn, M, K, N, out, static_cast<hipStream_t>(stream));
+}
+
+aqt_status aqt_policy_preset(int pattern, int n_layers, int k, int bits_w, int bits_x, aqt_layer_policy *out) {
+  if (!out || n_layers < 1) return AQT_ERR_INVALID_ARG;
+  if (pattern < AQT_POLICY_ALL || pattern > AQT_POLICY_FIRST_K) return AQT_ERR_INVALID_ARG;
+  if (!bits_ok(bits_w) || !(bits_x == 0 || bits_ok(bits_x))) return AQT_ERR_UNSUPPORTED;
+  if (pattern == AQT_POLICY_FIRST_K && (k < 0 || k > n_layers)) return AQT_ERR_INVALID_ARG;
+  const aqt_dense_policy low = {bits_w, bits_x}, base = {8, bits_x};   // Table 2: int8 for what is not selected
+  for (int l = 0; l < n_layers; ++l) {
+    bool sel = true;
+    if (pattern == AQT_POLICY_EXCEPT_FIRST_LAST) sel = (l != 0 && l != n_layers - 1);
+    if (pattern == AQT_POLICY_FIRST_K) sel = (l < k);
+    const aqt_dense_policy p = sel ? low : base;
+    aqt_layer_policy &o = out[l];
+    o.ffn1_in = o.ffn1_out = o.conv_pw1 = o.conv_pw2 = o.ffn2_in = o.ffn2_out = p;
+    o.attn_qkv = o.attn_out = (pattern == AQT_POLICY_EXCEPT_ATTENTION) ? base : p;
+  }
+  return AQT_OK;
+}
+
+size_t aqt_policy_weight_bytes(const aqt_layer_policy *policy, int n_layers, int64_t d_model, int64_t d_ff) {
+  if (!policy || n_layers < 1 || d_model < 1 || d_ff < 1) return 0;
+  size_t total = 0;
+  auto add = [&](const aqt_dense_policy &p, int64_t K, int64_t N) {
+    total += aqt_packed_weight_bytes(K, N, p.bits_w) + static_cast<size_t>(N) * sizeof(float);
+  };
+  for (int l = 0; l < n_layers; ++l) {
+    const aqt_layer_policy &p = policy[l];
+    if (!policy_ok(p.ffn1_in) || !policy_ok(p.ffn1_out) || !policy_ok(p.attn_qkv) || !policy_ok(p.attn_out) ||
+        !policy_ok(p.conv_pw1) || !policy_ok(p.conv_pw2) || !policy_ok(p.ffn2_in) || !policy_ok(p.ffn2_out))
+      return 0;
+    add(p.ffn1_in, d_model, d_ff);  add(p.ffn1_out, d_ff, d_model);
+    add(p.attn_qkv, d_model, 3 * d_model);  add(p.attn_out, d_model, d_model);
+    add(p.conv_pw1, d_model, 2 * d_model);  add(p.conv_pw2, d_model, d_model);
+    add(p.ffn2_in, d_model, d_ff);  add(p.ffn2_out, d_ff, d_model);
+  }
+  return total;
+}
+
+aqt_status aqt_ffn_fwd(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps, const float *w1,
+                       const float *b1, const float *w2, const float *b2, int64_t M, int64_t D, int64_t H,
+                       const aqt_dense_policy *policy, float *y, const aqt_ffn_saved *saved, void *ws,
+                       size_t ws_bytes, void *stream, int32_t *dev_status) {
+  if (!x || !w1 || !w2 || !y || !policy || !saved || !shape_ok(M, D) || H < 1 || !(ln_eps >= 0.0f))
+    return AQT_ERR_INVALID_ARG;
+  const aqt_dense_policy p1 = policy[0], p2 = policy[1];
+  if (!policy_ok(p1) || !policy_ok(p2)) return AQT_ERR_UNSUPPORTED;
+  const aqt_saved &l1 = saved->l1, &l2 = saved->l2;
+  if (!saved->h || !l1.wq_packed || !l1.s_w || !l2.wq_packed || !l2.s_w) return AQT_ERR_INVALID_ARG;
+  if (p1.bits_x ? (!l1.xq || !l1.s_x) : !saved->xn) return AQT_ERR_INVALID_ARG;
+  if (p2.bits_x && (!l2.xq || !l2.s_x)) return AQT_ERR_INVALID_ARG;
+  if (p1.bits_x && !acc_fits(D, p1.bits_x, p1.bits_w)) return AQT_ERR_UNSUPPORTED;
+  if (p2.bits_x && !acc_fits(H, p2.bits_x, p2.bits_w)) return AQT_ERR_UNSUPPORTED;
+  FfnWorkspace f = carve_ffn_fwd(ws, M, D, H);
+  if (!ws || ws_bytes < f.total) return AQT_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  // normalisation (+ first quantizer), first weights, first contraction with Swish
+  AQT_TRY(launch_quantize_weights(w1, D, H, p1.bits_w, l1.wq_packed, l1.s_w, l1.wq_kn, l1.mask_w, f.wpart1, st,
+                                  dev_status));
+  const bool want_absmax = p2.bits_x != 0;
+  if (p1.bits_x) {
+    AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, saved->xn,
+                                      saved->row_stats, f.ln, st, dev_status));
+    AQT_TRY(launch_dense_fwd_q(l1.xq, l1.s_x, l1.wq_packed, l1.s_w, M, D, H, p1.bits_w, b1, AQT_EPI_SWISH, saved->h,
+                               nullptr, want_absmax ? reinterpret_cast<uint32_t *>(f.h_absmax) : nullptr, f.wfrag1,
+                               st, l1.dact));
+  } else {
+    AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, 8, nullptr, nullptr, saved->xn,
+                                      saved->row_stats, f.ln, st, dev_status));
+    AQT_TRY(launch_dense_fwd_wonly(saved->xn, l1.wq_packed, l1.s_w, M, D, H, p1.bits_w, b1, AQT_EPI_SWISH, saved->h,
+                                   f.wfrag1, st));
+  }
+  // second quantizer (one pass when the producer emitted max|h|), second weights, second contraction
+  AQT_TRY(launch_quantize_weights(w2, H, D, p2.bits_w, l2.wq_packed, l2.s_w, l2.wq_kn, l2.mask_w, f.wpart2, st,
+                                  dev_status));
+  if (p2.bits_x) {
+    if (p1.bits_x) {
+      AQT_TRY(launch_quantize_with_absmax(saved->h, M, H, H, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),
+                                          l2.xq, l2.s_x, l2.mask_x, st, dev_status));
+    } else {
+      AQT_TRY(launch_quantize(saved->h, M, H, H, p2.bits_x, AQT_AXIS_ALL, l2.xq, l2.s_x, l2.mask_x,
+                              static_cast<float *>(f.ln), st, dev_status));
+    }
+    return launch_dense_fwd_q(l2.xq, l2.s_x, l2.wq_packed, l2.s_w, M, H, D, p2.bits_w, b2, AQT_EPI_NONE, y, nullptr,
+                              nullptr, f.wfrag2, st);
+  }
+  return launch_dense_fwd_wonly(saved->h, l2.wq_packed, l2.s_w, M, H, D, p2.bits_w, b2, AQT_EPI_NONE, y, f.wfrag2, st);
+}
+
+aqt_status aqt_ffn_bwd(const float *dy, const aqt_ffn_saved *saved, int64_t M, int64_t D, int64_t H,
+                       const aqt_dense_policy *policy, float *dxn, float *dw1, float *db1, float *dw2, float *db2,
+                       void *ws, size_t ws_bytes, void *stream) {
+  if (!dy || !saved || !policy || !shape_ok(M, D) || H < 1) return AQT_ERR_INVALID_ARG;
+  if (!policy_ok(policy[0]) || !policy_ok(policy[1])) return AQT_ERR_UNSUPPORTED;
+  if (policy[0].bits_x == 0 || policy[1].bits_x == 0) return AQT_ERR_UNSUPPORTED;
+  const aqt_saved &l1 = saved->l1, &l2 = saved->l2;
+  if (!l1.s_x || !l1.s_w || !l2.s_x || !l2.s_w || !l2.wq_kn || !l1.dact) return AQT_ERR_INVALID_ARG;
+  if ((dxn && !l1.wq_kn) || (dw1 && !l1.xq) || (dw2 && !l2.xq)) return AQT_ERR_INVALID_ARG;
+  if (!ws || ws_bytes < ffn_bwd_ws(M, D, H)) return AQT_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const size_t a = bwd_workspace_bytes(M, D, H), b = bwd_workspace_bytes(M, H, D);
+  const size_t core = a > b ? a : b;
+  float *dh = reinterpret_cast<float *>(static_cast<uint8_t *>(ws) + core);
+  // second layer (no activation): gradient with respect to h, dw2, db2
+  AQT_TRY(launch_dense_bwd(dy, &l2, M, H, D, dh, dw2, db2, ws, core, st));
+  if (!dxn && !dw1 && !db1) return AQT_OK;
+  // through the Swish, in place, then the first layer
+  AQT_TRY(launch_dact_mul(dh, l1.dact, M, H, H, dh, st));
+  return launch_dense_bwd(dh, &l1, M, D, H, dxn, dw1, db1, ws, core, st);
 }
 
 }  // extern "C"

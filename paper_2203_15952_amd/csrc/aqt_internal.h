@@ -55,7 +55,7 @@ aqt_status launch_unpack_weights(const void *wq_packed, int64_t K, int64_t N, in
 aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq_packed,
                               const float *s_w, int64_t M, int64_t K, int64_t N, int bits_w,
                               const float *bias, int epilogue, float *y, int32_t *acc_out, uint32_t *y_absmax,
-                              void *ws, hipStream_t st);
+                              void *ws, hipStream_t st, float *dact = nullptr);
 size_t fwd_q_workspace_bytes(int64_t K, int64_t N);
 aqt_status static_scratch_address(void **out);   // the library's own scratch array on the current device
 size_t fwd_wonly_workspace_bytes(int64_t K, int64_t N);
@@ -68,5 +68,15 @@ size_t bwd_workspace_bytes(int64_t M, int64_t K, int64_t N);
 aqt_status launch_dense_bwd(const float *dy, const aqt_saved *sv, int64_t M, int64_t K, int64_t N,
                             float *dx, float *dw, float *dbias, void *ws, size_t ws_bytes,
                             hipStream_t st);
+
+// ---- block pieces (block.hip) -----------------------------------------------------------
+size_t layernorm_ws_bytes(int64_t M);
+aqt_status launch_layernorm_quantize(const float *x, int64_t M, int64_t D, const float *gamma, const float *beta,
+                                     float eps, int bits, int8_t *q, float *scale, float *y_out, float *row_stats,
+                                     void *ws, hipStream_t st, int32_t *dev_status);
+aqt_status launch_dact_mul(const float *dout, const float *dact, int64_t M, int64_t N, int64_t oc, float *dv,
+                           hipStream_t st);
+aqt_status launch_fake_matmul_f32(const int8_t *xq, const int8_t *wq_kn, int64_t M, int64_t K, int64_t N, float *out,
+                                  hipStream_t st);
 
 }  // namespace aqt

@@ -1,0 +1,268 @@
+// Pieces around the quantized dense layer that a Conformer block needs (arxiv 2203.15952,
+// Sec. 3.2: feed-forward module = normalisation, Linear, Swish, Linear; Sec. 4.2 / Table 2:
+// which layers run at which precision):
+//   * layer normalisation fused with the per-tensor abs-max quantizer of Fig. 2, so the
+//     normalised tensor is never written in float32,
+//   * the chain-rule factor of the activation applied to an upstream gradient,
+//   * the float32-emulated ("fake", Sec. 1) product of the integer codes on the float32
+//     matrix cores, as a comparator for the native integer product,
+//   * per-layer precision policies and the feed-forward module as one call.
+#include "aqt_internal.h"
+
+namespace aqt {
+namespace {
+
+constexpr int kThreads = 256;
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_max_u(uint32_t v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const uint32_t o = static_cast<uint32_t>(__shfl_xor(static_cast<int>(v), off, 64));
+    v = v > o ? v : o;
+  }
+  return v;
+}
+
+// One normalised value; both passes evaluate exactly this expression (no contraction), so
+// the codes of pass 2 are codes of the very values whose maximum pass 1 took.
+__device__ __forceinline__ float ln_value(float x, float mean, float rstd, const float *gamma, const float *beta,
+                                          int64_t c) {
+  float t = (x - mean) * rstd;
+  if (gamma) t = t * gamma[c];
+  if (beta) t = t + beta[c];
+  return t;
+}
+
+// Pass 1: one wavefront per row.  Row mean and biased variance in float32 (lane partial
+// sums, then a fixed shuffle tree: the same bits on every run), rstd = 1 / sqrt(var + eps),
+// and the largest |normalised value| of everything this block handled.
+__global__ __launch_bounds__(kThreads) void ln_stats_kernel(const float *__restrict__ x, int64_t M, int64_t D,
+                                                            const float *__restrict__ gamma,
+                                                            const float *__restrict__ beta, float eps,
+                                                            float *__restrict__ stats, uint32_t *__restrict__ partial) {
+  __shared__ uint32_t sm[4];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  uint32_t amax = 0u;
+  for (int64_t m = static_cast<int64_t>(blockIdx.x) * 4 + wave; m < M; m += static_cast<int64_t>(gridDim.x) * 4) {
+    const float *row = x + m * D;
+    float s = 0.0f;
+    for (int64_t c = lane; c < D; c += 64) s += row[c];
+    const float mean = wave_sum(s) / static_cast<float>(D);
+    float v = 0.0f;
+    for (int64_t c = lane; c < D; c += 64) {
+      const float d = row[c] - mean;
+      v += d * d;
+    }
+    const float var = wave_sum(v) / static_cast<float>(D);
+    const float rstd = 1.0f / sqrtf(var + eps);
+    if (lane == 0) {
+      stats[2 * m] = mean;
+      stats[2 * m + 1] = rstd;
+    }
+    for (int64_t c = lane; c < D; c += 64)
+      amax = max(amax, __float_as_uint(ln_value(row[c], mean, rstd, gamma, beta, c)) & 0x7FFFFFFFu);
+  }
+  amax = wave_max_u(amax);
+  if (lane == 0) sm[wave] = amax;
+  __syncthreads();
+  if (threadIdx.x == 0) partial[blockIdx.x] = max(max(sm[0], sm[1]), max(sm[2], sm[3]));
+}
+
+// Pass 2: fold the block maxima into the scale (Fig. 2: max / qmax), recompute the normalised
+// values from x and the stored row statistics, quantize (divide, + 0.5, floor), write codes
+// and, when asked, the float32 values themselves.
+__global__ __launch_bounds__(kThreads) void ln_quantize_kernel(const float *__restrict__ x, int64_t M, int64_t D,
+                                                               const float *__restrict__ gamma,
+                                                               const float *__restrict__ beta,
+                                                               const float *__restrict__ stats,
+                                                               const uint32_t *__restrict__ partial, int nparts,
+                                                               int qmax, int8_t *__restrict__ q,
+                                                               float *__restrict__ scale, float *__restrict__ y_out,
+                                                               int32_t *dev_status) {
+  __shared__ uint32_t sm[4];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  uint32_t mx = 0u;
+  for (int i = threadIdx.x; i < nparts; i += kThreads) mx = max(mx, partial[i]);
+  mx = wave_max_u(mx);
+  if (lane == 0) sm[wave] = mx;
+  __syncthreads();
+  mx = max(max(sm[0], sm[1]), max(sm[2], sm[3]));
+  const float fq = static_cast<float>(qmax);
+  const float s = __uint_as_float(mx) / fq;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if (scale) scale[0] = s;
+    if (mx >= 0x7F800000u && dev_status) *dev_status = AQT_ERR_NONFINITE;
+  }
+  for (int64_t m = static_cast<int64_t>(blockIdx.x) * 4 + wave; m < M; m += static_cast<int64_t>(gridDim.x) * 4) {
+    const float *row = x + m * D;
+    const float mean = stats[2 * m], rstd = stats[2 * m + 1];
+    for (int64_t c = lane; c < D; c += 64) {
+      const float v = ln_value(row[c], mean, rstd, gamma, beta, c);
+      if (y_out) y_out[m * D + c] = v;
+      if (q) {
+        const float t = (s == 0.0f) ? 0.0f : v / s;
+        float r = floorf(t + 0.5f);
+        r = fminf(fmaxf(r, -fq), fq);
+        q[m * D + c] = static_cast<int8_t>(static_cast<int>(r));
+      }
+    }
+  }
+}
+
+// dv[m,n] = dout[m, n mod oc] * dact[m,n]  (chain rule through the activation)
+__global__ __launch_bounds__(kThreads) void dact_mul_kernel(const float *__restrict__ dout,
+                                                            const float *__restrict__ dact, int64_t M, int64_t N,
+                                                            int64_t oc, float *__restrict__ dv) {
+  const int64_t total = M * N;
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < total; i += stride) {
+    const int64_t m = i / N, n = i - m * N;
+    dv[i] = dout[m * oc + (n < oc ? n : n - oc)] * dact[i];
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void dact_mul4_kernel(const v4f *__restrict__ dout, const v4f *__restrict__ dact,
+                                                             int64_t M, int64_t N4, int64_t oc4,
+                                                             v4f *__restrict__ dv) {
+  const int64_t total = M * N4;
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < total; i += stride) {
+    const int64_t m = i / N4, n = i - m * N4;
+    const v4f a = __builtin_nontemporal_load(dout + m * oc4 + (n < oc4 ? n : n - oc4));
+    const v4f b = __builtin_nontemporal_load(dact + i);
+    const v4f o = {a.x * b.x, a.y * b.y, a.z * b.z, a.w * b.w};
+    dv[i] = o;
+  }
+}
+
+// ---- the float32-emulated product of the codes ------------------------------------------
+// "Fake" quantization on hardware without integer matrix units: the codes are converted to
+// float32 and multiplied and accumulated by float32 matrix instructions
+// (v_mfma_f32_32x32x2_f32).  Every product is exact; the sums are exact while they fit the
+// 24-bit significand and are rounded beyond.  Tile 128 x 128 per workgroup (four
+// wavefronts of 64 x 64), 32 fan-in per stage staged through LDS as bytes.
+typedef float v16f __attribute__((ext_vector_type(16)));
+constexpr int kFK = 32;
+
+__global__ __launch_bounds__(kThreads) void fake_matmul_f32_kernel(const int8_t *__restrict__ xq,
+                                                                   const int8_t *__restrict__ wq_kn, int M, int K,
+                                                                   int N, float *__restrict__ out) {
+  __shared__ int8_t sA[128][kFK + 4];   // [row][k], padded
+  __shared__ int8_t sB[kFK][128 + 4];   // [k][col]
+  const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
+  const int wm = wave >> 1, wn = wave & 1, lr = lane & 31, lk = lane >> 5;
+  const int m0 = blockIdx.y * 128, n0 = blockIdx.x * 128;
+  v16f acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+  for (int k0 = 0; k0 < K; k0 += kFK) {
+    // 128 x 32 bytes of codes: thread t loads row t/2, 16 bytes
+    {
+      const int r = t >> 1, c = (t & 1) * 16;
+      const int gm = m0 + r;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int gk = k0 + c + e;
+        sA[r][c + e] = (gm < M && gk < K) ? xq[static_cast<int64_t>(gm) * K + gk] : static_cast<int8_t>(0);
+      }
+    }
+    {
+      const int r = t >> 3, c = (t & 7) * 16;
+      const int gk = k0 + r;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int gn = n0 + c + e;
+        sB[r][c + e] = (gk < K && gn < N) ? wq_kn[static_cast<int64_t>(gk) * N + gn] : static_cast<int8_t>(0);
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < kFK; kk += 2) {
+      float a[2], b[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) a[i] = static_cast<float>(sA[wm * 64 + i * 32 + lr][kk + lk]);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) b[j] = static_cast<float>(sB[kk + lk][wn * 64 + j * 32 + lr]);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+        const int n = n0 + wn * 64 + j * 32 + lr;
+        if (m < M && n < N) out[static_cast<int64_t>(m) * N + n] = acc[i][j][r];
+      }
+}
+
+int grid_cap(int64_t items, int per_block, int cap) {
+  int64_t g = cdiv(items, per_block);
+  if (g < 1) g = 1;
+  if (g > cap) g = cap;
+  return static_cast<int>(g);
+}
+
+}  // namespace
+
+size_t layernorm_ws_bytes(int64_t M) {
+  return align_up(kMaxPartials * sizeof(uint32_t), 256) + align_up(static_cast<size_t>(M) * 2 * sizeof(float), 256);
+}
+
+aqt_status launch_layernorm_quantize(const float *x, int64_t M, int64_t D, const float *gamma, const float *beta,
+                                     float eps, int bits, int8_t *q, float *scale, float *y_out, float *row_stats,
+                                     void *ws, hipStream_t st, int32_t *dev_status) {
+  uint32_t *partial = static_cast<uint32_t *>(ws);
+  float *stats = row_stats ? row_stats
+                           : reinterpret_cast<float *>(static_cast<uint8_t *>(ws) +
+                                                       align_up(kMaxPartials * sizeof(uint32_t), 256));
+  const int g = grid_cap(M, 4, 2048);
+  ln_stats_kernel<<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, eps, stats, partial);
+  AQT_HIP(hipGetLastError());
+  ln_quantize_kernel<<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, stats, partial, g, q ? qmax_of(bits) : 1, q, scale,
+                                             y_out, dev_status);
+  AQT_HIP(hipGetLastError());
+  return AQT_OK;
+}
+
+aqt_status launch_dact_mul(const float *dout, const float *dact, int64_t M, int64_t N, int64_t oc, float *dv,
+                           hipStream_t st) {
+  const bool vec = (N % 4 == 0) && (oc % 4 == 0) && reinterpret_cast<uintptr_t>(dout) % 16 == 0 &&
+                   reinterpret_cast<uintptr_t>(dact) % 16 == 0 && reinterpret_cast<uintptr_t>(dv) % 16 == 0;
+  if (vec) {
+    dact_mul4_kernel<<<grid_cap(M * N / 4, kThreads * 4, 4096), kThreads, 0, st>>>(
+        reinterpret_cast<const v4f *>(dout), reinterpret_cast<const v4f *>(dact), M, N / 4, oc / 4,
+        reinterpret_cast<v4f *>(dv));
+  } else {
+    dact_mul_kernel<<<grid_cap(M * N, kThreads * 4, 4096), kThreads, 0, st>>>(dout, dact, M, N, oc, dv);
+  }
+  AQT_HIP(hipGetLastError());
+  return AQT_OK;
+}
+
+aqt_status launch_fake_matmul_f32(const int8_t *xq, const int8_t *wq_kn, int64_t M, int64_t K, int64_t N, float *out,
+                                  hipStream_t st) {
+  dim3 grid(static_cast<unsigned>(cdiv(N, 128)), static_cast<unsigned>(cdiv(M, 128)));
+  fake_matmul_f32_kernel<<<grid, kThreads, 0, st>>>(xq, wq_kn, static_cast<int>(M), static_cast<int>(K),
+                                                    static_cast<int>(N), out);
+  AQT_HIP(hipGetLastError());
+  return AQT_OK;
+}
+
+}  // namespace aqt

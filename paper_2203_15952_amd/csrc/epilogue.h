@@ -20,6 +20,12 @@ __device__ __forceinline__ float sigmoid_f32(float v) {
 
 __device__ __forceinline__ float swish_f32(float v) { return v * sigmoid_f32(v); }
 
+// Derivative factors for the backward through the activation, given sg = sigmoid of the
+// argument the logistic function was applied to:
+//   d swish(v) / dv = sg (1 + v (1 - sg));   d (a sigmoid(g)) / dg = a sg (1 - sg)
+__device__ __forceinline__ float swish_dact_f32(float v, float sg) { return sg * (1.0f + v * (1.0f - sg)); }
+__device__ __forceinline__ float glu_gate_dact_f32(float a, float sg) { return a * sg * (1.0f - sg); }
+
 // Sec. 2.2: de-quantize by multiplying with the scales.  sc = s_x * s_w[n],
 // rounded once; the int32 -> float32 conversion rounds to nearest even.
 __device__ __forceinline__ float dequant_f32(int acc, float sc) { return static_cast<float>(acc) * sc; }

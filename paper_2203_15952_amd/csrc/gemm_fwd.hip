@@ -51,7 +51,7 @@ __global__ __launch_bounds__(kThreads) void dense_fwd_general_kernel(
     const int8_t *__restrict__ xq, const float *__restrict__ s_x, const uint8_t *__restrict__ wq,
     const float *__restrict__ s_w, int64_t M, int64_t K, int64_t N, int packed,
     const float *__restrict__ bias, int epilogue, float *__restrict__ y, int32_t *__restrict__ acc_out,
-    uint32_t *__restrict__ y_absmax) {
+    uint32_t *__restrict__ y_absmax, float *__restrict__ dact) {
   const int64_t ncols = (epilogue == AQT_EPI_GLU) ? N / 2 : N;
   const int64_t idx = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
   if (idx >= M * ncols) return;
@@ -70,9 +70,20 @@ __global__ __launch_bounds__(kThreads) void dense_fwd_general_kernel(
     v[p] = t;
   }
   float out;
-  if (epilogue == AQT_EPI_NONE) out = v[0];
-  else if (epilogue == AQT_EPI_SWISH) out = swish_f32(v[0]);
-  else out = v[0] * sigmoid_f32(v[1]);
+  if (epilogue == AQT_EPI_NONE) {
+    out = v[0];
+  } else if (epilogue == AQT_EPI_SWISH) {
+    const float sg = sigmoid_f32(v[0]);
+    out = v[0] * sg;
+    if (dact) dact[m * N + j] = swish_dact_f32(v[0], sg);
+  } else {
+    const float sg = sigmoid_f32(v[1]);
+    out = v[0] * sg;
+    if (dact) {
+      dact[m * N + j] = sg;
+      dact[m * N + j + ncols] = glu_gate_dact_f32(v[0], sg);
+    }
+  }
   y[m * ncols + j] = out;
   if (y_absmax) note_absmax(y_absmax, __float_as_uint(out) & 0x7FFFFFFFu);
 }
@@ -173,8 +184,8 @@ template <int TM, int TN, bool PACKED, int EPI>
 __global__ __launch_bounds__(kThreads, 2) void dense_fwd_mfma_kernel(
     const int8_t *__restrict__ xq, const float *__restrict__ s_x, const v4i *__restrict__ wfrag,
     const float *__restrict__ s_w, int M, int K, int N, const float *__restrict__ bias,
-    float *__restrict__ y, int32_t *__restrict__ acc_out, uint32_t *__restrict__ y_absmax, int tiles_m,
-    int tiles_n) {
+    float *__restrict__ y, int32_t *__restrict__ acc_out, uint32_t *__restrict__ y_absmax,
+    float *__restrict__ dact, int tiles_m, int tiles_n) {
   constexpr bool SHIFT4 = PACKED;
   constexpr int BM = 64 * TM, BN = 64 * TN;
   constexpr int kSlotBytes = BM * kBK;
@@ -387,21 +398,33 @@ __global__ __launch_bounds__(kThreads, 2) void dense_fwd_mfma_kernel(
       bias_b = bias ? bias[n_b] : 0.0f;
     }
     const int lane_off = row_l * out_cols + n_a;
+    // the activation's derivative factors, [M,N], for the backward (when asked for)
+    float *dbase = dact + static_cast<int64_t>(m0) * N;
+    const int lane_off_d = row_l * N + n_a;
+    const int gate_step = (EPI == AQT_EPI_GLU) ? (N >> 1) : 0;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int a0 = SHIFT4 ? (acc[i][j][r] >> 4) : acc[i][j][r];
         const float v = dequant_f32(a0, sc_a) + bias_a;   // adding a zero bias changes nothing
+        const int row_d = (i * 32 + 8 * (r >> 2) + (r & 3)) * N;
         float out;
         if (EPI == AQT_EPI_NONE) {
           out = v;
         } else if (EPI == AQT_EPI_SWISH) {
-          out = swish_f32(v);
+          const float sg = sigmoid_f32(v);
+          out = v * sg;
+          if (dact) __builtin_nontemporal_store(swish_dact_f32(v, sg), dbase + row_d + lane_off_d);
         } else {
           const int a1 = SHIFT4 ? (acc[i][j + (JS - 1)][r] >> 4) : acc[i][j + (JS - 1)][r];
           const float g = dequant_f32(a1, sc_b) + bias_b;
-          out = v * sigmoid_f32(g);
+          const float sg = sigmoid_f32(g);
+          out = v * sg;
+          if (dact) {
+            __builtin_nontemporal_store(sg, dbase + row_d + lane_off_d);
+            __builtin_nontemporal_store(glu_gate_dact_f32(v, sg), dbase + row_d + lane_off_d + gate_step);
+          }
         }
         // written once, read by another kernel much later: stream it past the caches
         __builtin_nontemporal_store(out, ybase + (i * 32 + 8 * (r >> 2) + (r & 3)) * out_cols + lane_off);
@@ -419,12 +442,12 @@ __global__ __launch_bounds__(kThreads, 2) void dense_fwd_mfma_kernel(
 template <int TM, int TN, bool SHIFT4, int EPI>
 aqt_status launch_mfma(const int8_t *xq, const float *s_x, const v4i *wfrag, const float *s_w, int64_t M,
                        int64_t K, int64_t N, const float *bias, float *y, int32_t *acc_out, uint32_t *y_absmax,
-                       hipStream_t st) {
+                       float *dact, hipStream_t st) {
   constexpr int BM = 64 * TM, BN = 64 * TN;
   auto kern = dense_fwd_mfma_kernel<TM, TN, SHIFT4, EPI>;
   const int tiles_m = static_cast<int>(cdiv(M, BM)), tiles_n = static_cast<int>(N / BN);
   kern<<<tiles_m * tiles_n, kThreads, 0, st>>>(xq, s_x, wfrag, s_w, static_cast<int>(M), static_cast<int>(K),
-                                               static_cast<int>(N), bias, y, acc_out, y_absmax, tiles_m, tiles_n);
+                                               static_cast<int>(N), bias, y, acc_out, y_absmax, dact, tiles_m, tiles_n);
   AQT_HIP(hipGetLastError());
   return AQT_OK;
 }
@@ -432,11 +455,11 @@ aqt_status launch_mfma(const int8_t *xq, const float *s_x, const v4i *wfrag, con
 template <int TM, int TN, bool SHIFT4>
 aqt_status launch_mfma_epi(int epilogue, const int8_t *xq, const float *s_x, const v4i *wfrag, const float *s_w,
                            int64_t M, int64_t K, int64_t N, const float *bias, float *y, int32_t *acc_out,
-                           uint32_t *y_absmax, hipStream_t st) {
+                           uint32_t *y_absmax, float *dact, hipStream_t st) {
   switch (epilogue) {
-    case AQT_EPI_NONE: return launch_mfma<TM, TN, SHIFT4, AQT_EPI_NONE>(xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, st);
-    case AQT_EPI_SWISH: return launch_mfma<TM, TN, SHIFT4, AQT_EPI_SWISH>(xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, st);
-    default: return launch_mfma<TM, TN, SHIFT4, AQT_EPI_GLU>(xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, st);
+    case AQT_EPI_NONE: return launch_mfma<TM, TN, SHIFT4, AQT_EPI_NONE>(xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, dact, st);
+    case AQT_EPI_SWISH: return launch_mfma<TM, TN, SHIFT4, AQT_EPI_SWISH>(xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, dact, st);
+    default: return launch_mfma<TM, TN, SHIFT4, AQT_EPI_GLU>(xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, dact, st);
   }
 }
 
@@ -465,7 +488,8 @@ aqt_status static_scratch_address(void **out) {
 
 aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq_packed, const float *s_w,
                               int64_t M, int64_t K, int64_t N, int bits_w, const float *bias, int epilogue,
-                              float *y, int32_t *acc_out, uint32_t *y_absmax, void *ws, hipStream_t st) {
+                              float *y, int32_t *acc_out, uint32_t *y_absmax, void *ws, hipStream_t st,
+                              float *dact) {
   const bool packed = packed4(bits_w);
   if (y_absmax) {
     zero_word_kernel<<<1, 64, 0, st>>>(y_absmax);
@@ -491,17 +515,17 @@ aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq
       AQT_HIP(hipGetLastError());
       const bool wide = (nn % unit_wide == 0) && cdiv(M, 128) * (N / 256) >= 512;
       if (wide) {
-        return packed ? launch_mfma_epi<2, 4, true>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, st)
-                      : launch_mfma_epi<2, 4, false>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, st);
+        return packed ? launch_mfma_epi<2, 4, true>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, dact, st)
+                      : launch_mfma_epi<2, 4, false>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, dact, st);
       }
-      return packed ? launch_mfma_epi<2, 2, true>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, st)
-                    : launch_mfma_epi<2, 2, false>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, st);
+      return packed ? launch_mfma_epi<2, 2, true>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, dact, st)
+                    : launch_mfma_epi<2, 2, false>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, dact, st);
     }
   }
   const int64_t ncols = (epilogue == AQT_EPI_GLU) ? N / 2 : N;
   dense_fwd_general_kernel<<<static_cast<int>(cdiv(M * ncols, kThreads)), kThreads, 0, st>>>(
       xq, s_x, static_cast<const uint8_t *>(wq_packed), s_w, M, K, N, packed ? 1 : 0, bias, epilogue, y,
-      acc_out, y_absmax);
+      acc_out, y_absmax, dact);
   AQT_HIP(hipGetLastError());
   return AQT_OK;
 }

@@ -100,8 +100,58 @@ def test_argument_errors_are_synchronous_and_touch_no_gpu(L):
     assert L.aqt_dense_fwd_wonly(one, one, one, 4, 4, 4, 4, none, 0, one, none, 0, none) == B.AQT_ERR_WORKSPACE
     assert L.aqt_dense_fwd(one, one, 4, 4, 4, 8, 4, none, 0, one, None, none, 0, none, none) == B.AQT_ERR_WORKSPACE
     assert L.aqt_dense_fwd(one, none, 4, 4, 4, 8, 4, none, 0, one, None, one, 1 << 30, none, none) == B.AQT_ERR_INVALID_ARG
-    sv = B.aqt_saved(None, None, None, None, None, None, None)
-    assert L.aqt_dense_bwd(one, ctypes.byref(sv), 4, 4, 4, 8, 4, one, one, none, one, 1 << 30, none) == B.AQT_ERR_INVALID_ARG
-    assert L.aqt_dense_bwd(one, None, 4, 4, 4, 8, 4, one, one, none, one, 1 << 30, none) == B.AQT_ERR_INVALID_ARG
-    sv = B.aqt_saved(256, 256, None, 256, 256, 256, None)
-    assert L.aqt_dense_bwd(one, ctypes.byref(sv), 4, 4, 4, 8, 4, one, one, none, none, 0, none) == B.AQT_ERR_WORKSPACE
+    sv = B.aqt_saved(None, None, None, None, None, None, None, None)
+    assert L.aqt_dense_bwd(one, ctypes.byref(sv), 4, 4, 4, 8, 4, 0, one, one, none, one, 1 << 30, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_dense_bwd(one, None, 4, 4, 4, 8, 4, 0, one, one, none, one, 1 << 30, none) == B.AQT_ERR_INVALID_ARG
+    sv = B.aqt_saved(256, 256, None, 256, 256, 256, None, None)
+    assert L.aqt_dense_bwd(one, ctypes.byref(sv), 4, 4, 4, 8, 4, 0, one, one, none, none, 0, none) == B.AQT_ERR_WORKSPACE
+    # an activation needs the saved derivative factors, and a workspace that also holds dv
+    assert L.aqt_dense_bwd(one, ctypes.byref(sv), 4, 4, 4, 8, 4, B.AQT_EPI_SWISH, one, one, none, one, 1 << 30, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_dense_bwd(one, ctypes.byref(sv), 4, 4, 5, 8, 4, B.AQT_EPI_GLU, one, one, none, one, 1 << 30, none) == B.AQT_ERR_UNSUPPORTED
+    assert B.aqt_workspace_bytes(B.AQT_OP_DENSE_BWD_EPI, 100, 64, 32) >= B.aqt_workspace_bytes(B.AQT_OP_DENSE_BWD, 100, 64, 32) + 100 * 32 * 4
+    # layer normalisation, float32-emulated product, feed-forward module: argument checks
+    assert L.aqt_layernorm_quantize(none, 4, 4, none, none, 1e-6, 8, one, one, none, none, one, 1 << 20, none, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_layernorm_quantize(one, 4, 4, none, none, 1e-6, 8, one, none, none, none, one, 1 << 20, none, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_layernorm_quantize(one, 4, 4, none, none, 1e-6, 9, one, one, none, none, one, 1 << 20, none, none) == B.AQT_ERR_UNSUPPORTED
+    assert L.aqt_layernorm_quantize(one, 4, 4, none, none, 1e-6, 8, one, one, none, none, none, 0, none, none) == B.AQT_ERR_WORKSPACE
+    assert L.aqt_fake_matmul_f32(one, none, 4, 4, 4, one, none) == B.AQT_ERR_INVALID_ARG
+    fs = B.aqt_ffn_saved()
+    pol = (B.aqt_dense_policy * 2)(B.aqt_dense_policy(4, 8), B.aqt_dense_policy(4, 8))
+    assert L.aqt_ffn_fwd(one, none, none, 1e-6, one, none, one, none, 4, 4, 4, pol, one, ctypes.byref(fs), one, 1 << 30, none, none) == B.AQT_ERR_INVALID_ARG
+    bad = (B.aqt_dense_policy * 2)(B.aqt_dense_policy(9, 8), B.aqt_dense_policy(4, 8))
+    assert L.aqt_ffn_fwd(one, none, none, 1e-6, one, none, one, none, 4, 4, 4, bad, one, ctypes.byref(fs), one, 1 << 30, none, none) == B.AQT_ERR_UNSUPPORTED
+    wo = (B.aqt_dense_policy * 2)(B.aqt_dense_policy(4, 0), B.aqt_dense_policy(4, 8))
+    assert L.aqt_ffn_bwd(one, ctypes.byref(fs), 4, 4, 4, wo, one, one, none, one, none, one, 1 << 30, none) == B.AQT_ERR_UNSUPPORTED
+    assert B.aqt_workspace_bytes(B.AQT_OP_FFN_FWD, 128, 512, 2048) > 0 and B.aqt_workspace_bytes(B.AQT_OP_FFN_BWD, 128, 512, 2048) > 128 * 2048 * 4
+
+
+def test_precision_policies_follow_table_2_patterns(L):
+    # Table 2: int4 on the selected layers, int8 on the rest; E6 spares the first and last layer, E7 the
+    # self-attention projections, E8 - E13 take the first k layers
+    n = 6
+    names = ("ffn1_in", "ffn1_out", "attn_qkv", "attn_out", "conv_pw1", "conv_pw2", "ffn2_in", "ffn2_out")
+
+    def bits_w(p):
+        return [[getattr(l, nm).bits_w for nm in names] for l in p]
+    allp = B.aqt_policy_preset(B.AQT_POLICY_ALL, n, 0, 4, 8)
+    assert bits_w(allp) == [[4] * 8] * n and all(getattr(l, nm).bits_x == 8 for l in allp for nm in names)
+    e6 = B.aqt_policy_preset(B.AQT_POLICY_EXCEPT_FIRST_LAST, n, 0, 4, 8)
+    assert bits_w(e6) == [[8] * 8] + [[4] * 8] * (n - 2) + [[8] * 8]
+    e7 = B.aqt_policy_preset(B.AQT_POLICY_EXCEPT_ATTENTION, n, 0, 4, 8)
+    assert bits_w(e7) == [[4, 4, 8, 8, 4, 4, 4, 4]] * n
+    e10 = B.aqt_policy_preset(B.AQT_POLICY_FIRST_K, n, 3, 4, 0)
+    assert bits_w(e10) == [[4] * 8] * 3 + [[8] * 8] * 3 and e10[0].ffn1_in.bits_x == 0
+    with pytest.raises(B.AqtError):
+        B.aqt_policy_preset(B.AQT_POLICY_FIRST_K, n, n + 1, 4, 8)
+    with pytest.raises(B.AqtError):
+        B.aqt_policy_preset(7, n, 0, 4, 8)
+    # model-size side of the trade-off: half a byte per int4 weight, one byte per int8 weight, 4 bytes per scale
+    d, ff = 512, 2048
+    per_layer_weights = 4 * d * ff + 3 * d * d + d * d + 2 * d * d + d * d
+    per_layer_scales = 4 * (2 * ff + 2 * d + 3 * d + d + 2 * d + d)
+    i8 = B.aqt_policy_weight_bytes(B.aqt_policy_preset(B.AQT_POLICY_ALL, n, 0, 8, 8), n, d, ff)
+    i4 = B.aqt_policy_weight_bytes(allp, n, d, ff)
+    assert i8 == n * (per_layer_weights + per_layer_scales) and i4 == n * (per_layer_weights // 2 + per_layer_scales)
+    sizes = [B.aqt_policy_weight_bytes(B.aqt_policy_preset(B.AQT_POLICY_FIRST_K, n, k, 4, 8), n, d, ff) for k in range(n + 1)]
+    assert sizes[0] == i8 and sizes[-1] == i4 and all(a > b for a, b in zip(sizes, sizes[1:]))   # E8 .. E13 shrink monotonically
+    assert i4 < B.aqt_policy_weight_bytes(e7, n, d, ff) < i8
