@@ -35,6 +35,9 @@ PEAK_BF16_TFLOPS = 2500.0    # dense bf16 MFMA
 # HBM traffic per launch in MiB (read, written) of each segment's kernels at the default
 # workload (65536 tokens), from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy;
 # source: profiles/training_step_cfg5_hbm_traffic.txt.  Keys: (layer index, segment).
+# The figures belong to the kernels of library version PROFILED_VERSION; any other build
+# (a tile variant changed, a kernel rewritten) reports traffic as null instead of stale numbers.
+PROFILED_VERSION = 0
 MEASURED_TRAFFIC_MIB = {
     (0, "quantize_x"): (128.0 + 128.1, 0.1 + 32.0),      # abs-max pass + code pass
     (1, "quantize_x"): (512.0 + 512.1, 0.1 + 128.0),
@@ -67,6 +70,8 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=24576, help="row sample the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the extra figures of the fused abs-max path (keeps a profile to the timed steps)")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the per-layer figures of the forward-only configurations (12800-token shapes)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy of 1 GiB (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -228,6 +233,88 @@ def main():
         fused["quantize_one_pass_gbs"] = by / fused["quantize_one_pass_known_absmax_ms"] / 1e6
         fused["quantize_one_pass_hbm_frac"] = fused["quantize_one_pass_gbs"] / PEAK_HBM_GBS
 
+    def timed_loop(fn, n=30, warm=5):
+        for _ in range(warm):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    # The forward-only configurations (single layer; feed-forward, self-attention and convolution
+    # module layers at 12800 tokens): per quantized layer the contraction alone, the activation
+    # quantizer alone and the training forward as one call.  Not part of `value`.
+    per_config = None
+    if not args.no_configs:
+        per_config = {}
+        for cfg in (1, 2, 3, 4):
+            for c in inputs.CONFIGS[cfg]():
+                x_d, w_d = torch.from_numpy(c.x).cuda(), torch.from_numpy(c.w).cuda()
+                sv = B.Saved(c.M, c.K, c.N, c.bits_w)
+                oc = c.N // 2 if c.epilogue == B.AQT_EPI_GLU else c.N
+                y_d = torch.empty((c.M, oc), dtype=torch.float32, device="cuda")
+                ws_q = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_QUANTIZE, c.M, c.K, 1))
+                ws_f = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_DENSE_FWD_Q, c.M, c.K, c.N))
+                ws_d = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_DENSE_FWD, c.M, c.K, c.N, c.bits_x, c.bits_w))
+                B.aqt_dense_fwd(x_d, w_d, c.bits_x, c.bits_w, epilogue=c.epilogue, y=y_d, saved=sv, ws=ws_d,
+                                dev_status=status)
+                q_ms = timed_loop(lambda: B.aqt_quantize(x_d, c.bits_x, B.AQT_AXIS_ALL, q=sv.xq, scale=sv.s_x, ws=ws_q,
+                                                         dev_status=status))
+                g_ms = timed_loop(lambda: B.aqt_dense_fwd_q(sv.xq, sv.s_x, sv.wq_packed, sv.s_w, c.N, c.bits_x, c.bits_w,
+                                                            epilogue=c.epilogue, y=y_d, ws=ws_f))
+                f_ms = timed_loop(lambda: B.aqt_dense_fwd(x_d, w_d, c.bits_x, c.bits_w, epilogue=c.epilogue, y=y_d,
+                                                          saved=sv, ws=ws_d, dev_status=status))
+                mnk2 = 2.0 * c.M * c.K * c.N
+                pk = 0.5 if c.bits_w <= 4 else 1.0
+                by = c.M * c.K + c.K * c.N * pk + 4.0 * c.M * oc
+                cap = min(PEAK_INT8_TOPS, mnk2 / by * PEAK_HBM_GBS / 1e3)
+                tops = mnk2 / g_ms / 1e9
+                qby = 5.0 * c.M * c.K
+                per_config[c.name] = {
+                    "shape_MKN": [c.M, c.K, c.N], "bits_x_w": [c.bits_x, c.bits_w], "epilogue": c.epilogue,
+                    "gemm_ms": g_ms, "tops": tops, "pct_int8_peak": 100.0 * tops / PEAK_INT8_TOPS,
+                    "roofline_cap_tops": cap, "pct_roofline_cap": 100.0 * tops / cap,
+                    "quantize_x_ms": q_ms, "quantize_x_gbs_5B_per_elem": qby / q_ms / 1e6,
+                    "quantize_x_hbm_frac_5B_per_elem": qby / q_ms / 1e6 / PEAK_HBM_GBS,
+                    "dense_fwd_one_call_ms": f_ms}
+                del x_d, w_d, sv, y_d, ws_q, ws_f, ws_d
+        torch.cuda.empty_cache()
+
+    if fused is not None:
+        # the feed-forward module of the 12800-token configuration as one call (normalisation fused with
+        # the first quantizer, max|h| from the first contraction, one-pass second quantizer), forward and
+        # straight-through backward down to the normalised input
+        Mf, Df, Hf = 12800, 512, 2048
+        gen = torch.Generator(device="cuda").manual_seed(2)
+        xf = torch.randn((Mf, Df), device="cuda", generator=gen)
+        w1f = torch.randn((Df, Hf), device="cuda", generator=gen) / Df ** 0.5
+        w2f = torch.randn((Hf, Df), device="cuda", generator=gen) / Hf ** 0.5
+        dyf = torch.randn((Mf, Df), device="cuda", generator=gen) * 0.1
+        fsv = B.FfnSaved(Mf, Df, Hf, ((4, 8), (4, 8)))
+        yf = torch.empty((Mf, Df), dtype=torch.float32, device="cuda")
+        ws_ff = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_FFN_FWD, Mf, Df, Hf))
+        ws_fb = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_FFN_BWD, Mf, Df, Hf))
+        fused["ffn_module_fwd_ms"] = timed_loop(lambda: B.aqt_ffn_fwd(xf, w1f, None, w2f, None, fsv, y=yf, ws=ws_ff,
+                                                                      dev_status=status))
+        fused["ffn_module_bwd_ms"] = timed_loop(lambda: B.aqt_ffn_bwd(dyf, fsv, want_db=False, ws=ws_fb))
+        fused["ffn_module_shape_MDH"] = [Mf, Df, Hf]
+        # native integer product against its float32 emulation ("fake" quantization's arithmetic, Sec. 1) on
+        # the 2048 -> 512 layer of the training step: same codes, int8 matrix cores vs float32 matrix cores
+        L2 = layers[1]
+        c2, sv2 = L2["c"], L2["sv"]
+        wq8 = sv2.wq_kn.t().contiguous().view(torch.uint8).reshape(-1)      # int8 codes, fan-in contiguous
+        s1 = torch.ones(c2.N, dtype=torch.float32, device="cuda")
+        fo = torch.empty((c2.M, c2.N), dtype=torch.float32, device="cuda")
+        native_ms = timed_loop(lambda: B.aqt_dense_fwd_q(sv2.xq, sv2.s_x, wq8, s1, c2.N, 8, 8, y=L2["y"], ws=L2["ws_f"]),
+                               n=20)
+        fake_ms = timed_loop(lambda: B.aqt_fake_matmul_f32(sv2.xq, sv2.wq_kn, out=fo), n=5, warm=2)
+        fused["native_int8_vs_fake_f32"] = {"shape_MKN": [c2.M, c2.K, c2.N], "native_int8_ms": native_ms,
+                                            "fake_f32_ms": fake_ms, "fake_over_native": fake_ms / native_ms}
+        del xf, w1f, w2f, dyf, fsv, yf, ws_ff, ws_fb, fo
+
     if args.calibrate_copy:
         # known traffic: 2^28 floats read (1 GiB) and written (1 GiB) by one elementwise kernel
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -265,7 +352,7 @@ def main():
 
     def seg_traffic(li, name):
         """Measured HBM bytes per launch (profiles/), or None away from the profiled workload."""
-        if args.tokens != 65536:
+        if args.tokens != 65536 or B.lib().aqt_version() != PROFILED_VERSION:
             return None
         rd, wr = MEASURED_TRAFFIC_MIB[(li, name)]
         return (rd + wr) * 1048576.0
@@ -306,9 +393,7 @@ def main():
                         "bwd_dw": "contraction + slab fold (about 12 us)"}[dom_key[1]]
     if dom_key[1] in ("bwd_dx", "bwd_dw"):
         roof["note"] = ("achieved counts the algorithmic 2MNK; the kernel issues 4MNK MFMA flops (bf16 hi/lo split of the "
-                        "float32 operand). Measured limits on this part: about 64 B/clk/CU of operand delivery into "
-                        "registers (LDS and L2 together) caps a 64x128 wavefront tile near 0.65 MFMA utilisation, and "
-                        "the shader clock sits at 1.8-1.9 GHz under these kernels (peak assumes 2.4 GHz)")
+                        "float32 operand), so frac = 0.5 would be every matrix-core cycle busy at the peak's clock")
     roof["avg_ms"] = seg_ms[dom_key]
 
     cpu = None
@@ -341,6 +426,7 @@ def main():
         "roofline": roof,
         "cpu_baseline": cpu,
         "kernels": kernels,
+        "configs": per_config,
         "extras": fused,
     }
     print(json.dumps(out))

@@ -501,7 +501,6 @@ aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq
   const bool sizes_fit = M < (int64_t(1) << 31) / (K > N ? K : N);  // 32-bit tile arithmetic inside
   if (aligned && sizes_fit && K % kBK == 0 && M >= 128) {
     // The column tile must divide N (N/2 for GLU, whose tile holds value and gate halves).
-    // 128 x 256 tiles once there are enough of them to fill the chip, else 128 x 128.
     const int64_t nn = (epilogue == AQT_EPI_GLU) ? N / 2 : N;
     const int64_t unit_wide = (epilogue == AQT_EPI_GLU) ? 128 : 256;
     const int64_t unit = (epilogue == AQT_EPI_GLU) ? 64 : 128;
@@ -513,7 +512,10 @@ aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq
       weights_to_frag_kernel<<<g, kThreads, 0, st>>>(static_cast<const uint8_t *>(wq_packed), static_cast<int>(K),
                                                      static_cast<int>(N), packed ? 1 : 0, wfrag);
       AQT_HIP(hipGetLastError());
-      const bool wide = (nn % unit_wide == 0) && cdiv(M, 128) * (N / 256) >= 512;
+      // 128 x 256 tiles need several rounds of them on the 512 workgroup slots to pay off (measured:
+      // from about 2000 tiles at a fan-in of 512, from about 400 when the main loop is long), else 128 x 128
+      const int64_t wide_tiles = cdiv(M, 128) * (N / 256);
+      const bool wide = (nn % unit_wide == 0) && wide_tiles >= (K >= 1024 ? 384 : 2048);
       if (wide) {
         return packed ? launch_mfma_epi<2, 4, true>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, dact, st)
                       : launch_mfma_epi<2, 4, false>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, dact, st);

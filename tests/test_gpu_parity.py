@@ -193,9 +193,9 @@ def test_dense_fwd_against_oracle(M, K, N, bx, bw, epi, with_bias):
 
 
 def test_dense_fwd_big_tiles_sampled():
-    # 256 x 256 tiles need >= 512 of them; compare sampled accumulators and outputs
+    # the wide tiles; compare whole row tiles and sampled accumulators and outputs
     say("dense fwd big tiles")
-    M, K, N = 16384, 256, 2048
+    M, K, N = 16384, 1024, 2048
     c = inputs.small_case(41, M, K, N, 8, 4, 0, with_dy=False)
     ora_xq, ora_sx = oracle.quantize(c.x, 8, oracle.AXIS_ALL)
     ora_wq, ora_sw = oracle.quantize(c.w, 4, 0)
@@ -550,12 +550,13 @@ def test_dense_fwd_weight_only_training_step_shapes(layer):
     check_float_forward(y_h[rows], ora, 0)
 
 
-# 128 x 256 tiles are used once there are at least 512 of them
+# 128 x 256 tiles are used from about 400 of them at a fan-in of 1024 or more (2048 below that)
 WIDE_TILE_CASES = [
     # M, K, N, bits_x, bits_w, epilogue
-    (16384, 128, 1024, 8, 8, 2),     # GLU, value and gate halves in one tile, a single stage
-    (16500, 384, 1024, 8, 4, 1),     # ragged M (shifted last row tile), Swish, three stages
-    (16384, 256, 2048, 4, 4, 0),     # int4 x int4
+    (16384, 1024, 1024, 8, 8, 2),    # GLU, value and gate halves in one tile, int8 weights
+    (16500, 1152, 1024, 8, 4, 1),    # ragged M (shifted last row tile), Swish, nine stages
+    (16384, 1024, 2048, 4, 4, 0),    # int4 x int4
+    (33000, 128, 2048, 8, 4, 0),     # a single stage, ragged M, many tiles at a short fan-in
 ]
 
 
