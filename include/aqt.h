@@ -181,6 +181,22 @@ aqt_status aqt_dense_fwd_q_static(const int8_t *xq, const float *s_x, const void
                                   const float *bias, int epilogue, float *y, void *stream);
 
 /*
+ * Serving with static weights: re-order the forward operand for the matrix cores once
+ * (aqt_prepare_weights, into a caller buffer of aqt_prepared_weight_bytes()), then run
+ * the contraction of Sec. 1 / Sec. 2.2 on it as often as needed with no workspace and no
+ * per-call re-ordering pass.  Same arithmetic and bit-identical y as aqt_dense_fwd_q.
+ * Needs a shape the matrix-core kernel takes: K a multiple of 128, N a multiple of 128
+ * (N/2 a multiple of 64 for GLU), M >= 128; otherwise AQT_ERR_UNSUPPORTED (use
+ * aqt_dense_fwd_q).  aqt_prepared_weight_bytes() is 0 for such shapes.  Packed (<= 4 bit)
+ * weights stay two codes per byte in the prepared operand.
+ */
+size_t aqt_prepared_weight_bytes(int64_t K, int64_t N, int bits_w);
+aqt_status aqt_prepare_weights(const void *wq_packed, int64_t K, int64_t N, int bits_w, void *wprep, void *stream);
+aqt_status aqt_dense_fwd_q_prepared(const int8_t *xq, const float *s_x, const void *wprep, const float *s_w,
+                                    int64_t M, int64_t K, int64_t N, int bits_x, int bits_w, const float *bias,
+                                    int epilogue, float *y, void *stream);
+
+/*
  * Producer-side abs-max for a chain of quantized layers.  The next layer's
  * activation quantizer (Fig. 2, per tensor) needs m = max|y| of this layer's
  * output before it can emit a single code; computing m where y is produced

@@ -29,7 +29,8 @@ SYMBOLS = ["aqt_status_string", "aqt_last_hip_error", "aqt_version", "aqt_worksp
            "aqt_unpack_weights", "aqt_dense_fwd_q", "aqt_dense_fwd_q_absmax", "aqt_quantize_with_absmax",
            "aqt_dense_fwd_wonly", "aqt_dense_fwd", "aqt_dense_bwd", "aqt_dense_fwd_q_static",
            "aqt_static_scratch_bytes", "aqt_layernorm_quantize", "aqt_fake_matmul_f32", "aqt_policy_preset",
-           "aqt_policy_weight_bytes", "aqt_ffn_fwd", "aqt_ffn_bwd"]
+           "aqt_policy_weight_bytes", "aqt_ffn_fwd", "aqt_ffn_bwd", "aqt_prepared_weight_bytes",
+           "aqt_prepare_weights", "aqt_dense_fwd_q_prepared"]
 
 
 class AqtError(RuntimeError):
@@ -91,6 +92,10 @@ def lib() -> ctypes.CDLL:
                                              _vp, _vp, _sz, _vp]
         L.aqt_dense_fwd_q_static.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _vp]
         L.aqt_static_scratch_bytes.restype = _sz
+        L.aqt_prepared_weight_bytes.restype = _sz
+        L.aqt_prepared_weight_bytes.argtypes = [_i64, _i64, _int]
+        L.aqt_prepare_weights.argtypes = [_vp, _i64, _i64, _int, _vp, _vp]
+        L.aqt_dense_fwd_q_prepared.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _vp]
         L.aqt_quantize_with_absmax.argtypes = [_vp, _i64, _i64, _i64, _int, _vp, _vp, _vp, _vp, _vp, _vp]
         L.aqt_dense_fwd_wonly.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _int, _vp, _int, _vp, _vp, _sz, _vp]
         L.aqt_dense_fwd.argtypes = [_vp, _vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp,
@@ -245,6 +250,29 @@ def aqt_dense_fwd_q_static(xq, s_x, wq_packed, s_w, N: int, bits_x: int, bits_w:
     st = lib().aqt_dense_fwd_q_static(_ptr(xq), _ptr(s_x), _ptr(wq_packed), _ptr(s_w), M, K, N, bits_x, bits_w,
                                       _ptr(bias), epilogue, _ptr(y), _stream())
     _check(st, "aqt_dense_fwd_q_static")
+    return y
+
+
+def aqt_prepare_weights(wq_packed, K: int, N: int, bits_w: int):
+    """aqt_prepare_weights: the forward operand re-ordered once for the matrix cores."""
+    nbytes = int(lib().aqt_prepared_weight_bytes(K, N, bits_w))
+    if nbytes == 0:
+        raise AqtError(AQT_ERR_UNSUPPORTED, "aqt_prepared_weight_bytes")
+    wprep = torch.empty(nbytes, dtype=torch.uint8, device=wq_packed.device)
+    st = lib().aqt_prepare_weights(_ptr(wq_packed), K, N, bits_w, _ptr(wprep), _stream())
+    _check(st, "aqt_prepare_weights")
+    return wprep
+
+
+def aqt_dense_fwd_q_prepared(xq, s_x, wprep, s_w, N: int, bits_x: int, bits_w: int, *, bias=None,
+                             epilogue: int = AQT_EPI_NONE, y=None):
+    """aqt_dense_fwd_q_prepared: the serving forward on a prepared weight operand, no workspace."""
+    _dev(xq, torch.int8, "xq")
+    M, K = xq.shape
+    y = torch.empty((M, _out_cols(N, epilogue)), dtype=torch.float32, device=xq.device) if y is None else y
+    st = lib().aqt_dense_fwd_q_prepared(_ptr(xq), _ptr(s_x), _ptr(wprep), _ptr(s_w), M, K, N, bits_x, bits_w,
+                                        _ptr(bias), epilogue, _ptr(y), _stream())
+    _check(st, "aqt_dense_fwd_q_prepared")
     return y
 
 

@@ -211,6 +211,35 @@ aqt_status aqt_dense_fwd_q_static(const int8_t *xq, const float *s_x, const void
 
 size_t aqt_static_scratch_bytes(void) { return AQT_STATIC_SCRATCH_BYTES; }
 
+size_t aqt_prepared_weight_bytes(int64_t K, int64_t N, int bits_w) {
+  if (!shape_ok(K, N) || !bits_ok(bits_w) || K % 128 != 0 || N % 128 != 0) return 0;
+  return static_cast<size_t>(K) * N / (packed4(bits_w) ? 2 : 1);
+}
+
+aqt_status aqt_prepare_weights(const void *wq_packed, int64_t K, int64_t N, int bits_w, void *wprep, void *stream) {
+  if (!wq_packed || !wprep || !shape_ok(K, N)) return AQT_ERR_INVALID_ARG;
+  if (!bits_ok(bits_w)) return AQT_ERR_UNSUPPORTED;
+  if (K % 128 != 0 || N % 128 != 0) return AQT_ERR_UNSUPPORTED;
+  if (reinterpret_cast<uintptr_t>(wq_packed) % 16 != 0 || reinterpret_cast<uintptr_t>(wprep) % 16 != 0)
+    return AQT_ERR_INVALID_ARG;
+  return launch_prepare_weights(wq_packed, K, N, bits_w, wprep, static_cast<hipStream_t>(stream));
+}
+
+aqt_status aqt_dense_fwd_q_prepared(const int8_t *xq, const float *s_x, const void *wprep, const float *s_w,
+                                    int64_t M, int64_t K, int64_t N, int bits_x, int bits_w, const float *bias,
+                                    int epilogue, float *y, void *stream) {
+  if (!xq || !s_x || !wprep || !s_w || !y || !shape_ok(M, K) || N < 1) return AQT_ERR_INVALID_ARG;
+  if (epilogue != AQT_EPI_NONE && epilogue != AQT_EPI_SWISH && epilogue != AQT_EPI_GLU) return AQT_ERR_INVALID_ARG;
+  if (!bits_ok(bits_x) || !bits_ok(bits_w)) return AQT_ERR_UNSUPPORTED;
+  if (epilogue == AQT_EPI_GLU && (N % 2)) return AQT_ERR_UNSUPPORTED;
+  if (!acc_fits(K, bits_x, bits_w)) return AQT_ERR_UNSUPPORTED;
+  if (!fwd_q_takes_fragments(M, K, N, epilogue)) return AQT_ERR_UNSUPPORTED;
+  if (reinterpret_cast<uintptr_t>(xq) % 16 != 0 || reinterpret_cast<uintptr_t>(wprep) % 16 != 0)
+    return AQT_ERR_INVALID_ARG;
+  return launch_dense_fwd_q(xq, s_x, nullptr, s_w, M, K, N, bits_w, bias, epilogue, y, nullptr, nullptr,
+                            const_cast<void *>(wprep), static_cast<hipStream_t>(stream), nullptr, true);
+}
+
 aqt_status aqt_dense_fwd_q_absmax(const int8_t *xq, const float *s_x, const void *wq_packed, const float *s_w,
                                   int64_t M, int64_t K, int64_t N, int bits_x, int bits_w, const float *bias,
                                   int epilogue, float *y, float *y_absmax, void *ws, size_t ws_bytes,
@@ -263,10 +292,13 @@ aqt_status aqt_dense_fwd(const float *x, const float *w, int64_t M, int64_t K, i
   float *s_w = (saved && saved->s_w) ? saved->s_w : f.s_w;
   AQT_TRY(launch_quantize(x, M, K, K, bits_x, AQT_AXIS_ALL, xq, s_x, saved ? saved->mask_x : nullptr,
                           f.partials, st, dev_status));
+  // when the matrix-core kernel takes the shape, the weight quantizer emits its operand in fragment order itself
+  const bool frag = fwd_q_takes_fragments(M, K, N, epilogue) && reinterpret_cast<uintptr_t>(xq) % 16 == 0 &&
+                    reinterpret_cast<uintptr_t>(f.wfrag) % 16 == 0;
   AQT_TRY(launch_quantize_weights(w, K, N, bits_w, wq, s_w, saved ? saved->wq_kn : nullptr,
-                                  saved ? saved->mask_w : nullptr, f.wpart, st, dev_status));
+                                  saved ? saved->mask_w : nullptr, f.wpart, st, dev_status, frag ? f.wfrag : nullptr));
   return launch_dense_fwd_q(xq, s_x, wq, s_w, M, K, N, bits_w, bias, epilogue, y, nullptr, nullptr, f.wfrag, st,
-                            saved ? saved->dact : nullptr);
+                            saved ? saved->dact : nullptr, frag);
 }
 
 aqt_status aqt_dense_bwd(const float *dy, const aqt_saved *saved, int64_t M, int64_t K, int64_t N, int bits_x,
@@ -369,15 +401,19 @@ aqt_status aqt_ffn_fwd(const float *x, const float *ln_gamma, const float *ln_be
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   // normalisation (+ first quantizer), first weights, first contraction with Swish
+  const bool frag1 = p1.bits_x && fwd_q_takes_fragments(M, D, H, AQT_EPI_SWISH) &&
+                     reinterpret_cast<uintptr_t>(l1.xq) % 16 == 0;
+  const bool frag2 = p2.bits_x && fwd_q_takes_fragments(M, H, D, AQT_EPI_NONE) &&
+                     reinterpret_cast<uintptr_t>(l2.xq) % 16 == 0;
   AQT_TRY(launch_quantize_weights(w1, D, H, p1.bits_w, l1.wq_packed, l1.s_w, l1.wq_kn, l1.mask_w, f.wpart1, st,
-                                  dev_status));
+                                  dev_status, frag1 ? f.wfrag1 : nullptr));
   const bool want_absmax = p2.bits_x != 0;
   if (p1.bits_x) {
     AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, saved->xn,
                                       saved->row_stats, f.ln, st, dev_status));
     AQT_TRY(launch_dense_fwd_q(l1.xq, l1.s_x, l1.wq_packed, l1.s_w, M, D, H, p1.bits_w, b1, AQT_EPI_SWISH, saved->h,
                                nullptr, want_absmax ? reinterpret_cast<uint32_t *>(f.h_absmax) : nullptr, f.wfrag1,
-                               st, l1.dact));
+                               st, l1.dact, frag1));
   } else {
     AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, 8, nullptr, nullptr, saved->xn,
                                       saved->row_stats, f.ln, st, dev_status));
@@ -386,7 +422,7 @@ aqt_status aqt_ffn_fwd(const float *x, const float *ln_gamma, const float *ln_be
   }
   // second quantizer (one pass when the producer emitted max|h|), second weights, second contraction
   AQT_TRY(launch_quantize_weights(w2, H, D, p2.bits_w, l2.wq_packed, l2.s_w, l2.wq_kn, l2.mask_w, f.wpart2, st,
-                                  dev_status));
+                                  dev_status, frag2 ? f.wfrag2 : nullptr));
   if (p2.bits_x) {
     if (p1.bits_x) {
       AQT_TRY(launch_quantize_with_absmax(saved->h, M, H, H, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),
@@ -396,7 +432,7 @@ aqt_status aqt_ffn_fwd(const float *x, const float *ln_gamma, const float *ln_be
                               static_cast<float *>(f.ln), st, dev_status));
     }
     return launch_dense_fwd_q(l2.xq, l2.s_x, l2.wq_packed, l2.s_w, M, H, D, p2.bits_w, b2, AQT_EPI_NONE, y, nullptr,
-                              nullptr, f.wfrag2, st);
+                              nullptr, f.wfrag2, st, nullptr, frag2);
   }
   return launch_dense_fwd_wonly(saved->h, l2.wq_packed, l2.s_w, M, H, D, p2.bits_w, b2, AQT_EPI_NONE, y, f.wfrag2, st);
 }

@@ -46,7 +46,7 @@ aqt_status launch_quantize_with_scale(const float *x, int64_t rows, int64_t cols
                                       hipStream_t st);
 aqt_status launch_quantize_weights(const float *w, int64_t K, int64_t N, int bits_w, void *wq_packed,
                                    float *s_w, int8_t *wq_kn, uint32_t *mask_w, uint32_t *part,
-                                   hipStream_t st, int32_t *dev_status);
+                                   hipStream_t st, int32_t *dev_status, void *wfrag = nullptr);
 inline size_t weight_ws_bytes(int64_t N) { return align_up(static_cast<size_t>(kWeightSlabs) * N * 4, 256); }
 aqt_status launch_unpack_weights(const void *wq_packed, int64_t K, int64_t N, int bits_w,
                                  int8_t *codes_kn, hipStream_t st);
@@ -55,7 +55,12 @@ aqt_status launch_unpack_weights(const void *wq_packed, int64_t K, int64_t N, in
 aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq_packed,
                               const float *s_w, int64_t M, int64_t K, int64_t N, int bits_w,
                               const float *bias, int epilogue, float *y, int32_t *acc_out, uint32_t *y_absmax,
-                              void *ws, hipStream_t st, float *dact = nullptr);
+                              void *ws, hipStream_t st, float *dact = nullptr, bool ws_is_prepared = false);
+// True when the matrix-core kernel takes the shape (then its weight operand may be handed over
+// already in fragment order: from the weight quantizer, or from launch_prepare_weights).
+bool fwd_q_takes_fragments(int64_t M, int64_t K, int64_t N, int epilogue);
+aqt_status launch_prepare_weights(const void *wq_packed, int64_t K, int64_t N, int bits_w, void *wprep,
+                                  hipStream_t st);
 size_t fwd_q_workspace_bytes(int64_t K, int64_t N);
 aqt_status static_scratch_address(void **out);   // the library's own scratch array on the current device
 size_t fwd_wonly_workspace_bytes(int64_t K, int64_t N);

@@ -486,44 +486,55 @@ aqt_status static_scratch_address(void **out) {
   return AQT_OK;
 }
 
+bool fwd_q_takes_fragments(int64_t M, int64_t K, int64_t N, int epilogue) {
+  const bool sizes_fit = M < (int64_t(1) << 31) / (K > N ? K : N);  // 32-bit tile arithmetic inside
+  // The column tile must divide N (N/2 for GLU, whose tile holds value and gate halves).
+  const int64_t nn = (epilogue == AQT_EPI_GLU) ? N / 2 : N;
+  const int64_t unit = (epilogue == AQT_EPI_GLU) ? 64 : 128;
+  return sizes_fit && K % kBK == 0 && M >= 128 && nn % unit == 0;
+}
+
+aqt_status launch_prepare_weights(const void *wq_packed, int64_t K, int64_t N, int bits_w, void *wprep,
+                                  hipStream_t st) {
+  const bool packed = packed4(bits_w);
+  const int64_t pieces = N * (K / (packed ? 32 : 16));
+  int g = static_cast<int>(cdiv(pieces, kThreads));
+  if (g > 2048) g = 2048;
+  weights_to_frag_kernel<<<g, kThreads, 0, st>>>(static_cast<const uint8_t *>(wq_packed), static_cast<int>(K),
+                                                 static_cast<int>(N), packed ? 1 : 0, static_cast<v4i *>(wprep));
+  AQT_HIP(hipGetLastError());
+  return AQT_OK;
+}
+
 aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq_packed, const float *s_w,
                               int64_t M, int64_t K, int64_t N, int bits_w, const float *bias, int epilogue,
                               float *y, int32_t *acc_out, uint32_t *y_absmax, void *ws, hipStream_t st,
-                              float *dact) {
+                              float *dact, bool ws_is_prepared) {
   const bool packed = packed4(bits_w);
   if (y_absmax) {
     zero_word_kernel<<<1, 64, 0, st>>>(y_absmax);
     AQT_HIP(hipGetLastError());
   }
-  const bool aligned = (reinterpret_cast<uintptr_t>(xq) % 16 == 0) &&
-                       (reinterpret_cast<uintptr_t>(wq_packed) % 16 == 0) && ws &&
-                       (reinterpret_cast<uintptr_t>(ws) % 16 == 0);
-  const bool sizes_fit = M < (int64_t(1) << 31) / (K > N ? K : N);  // 32-bit tile arithmetic inside
-  if (aligned && sizes_fit && K % kBK == 0 && M >= 128) {
-    // The column tile must divide N (N/2 for GLU, whose tile holds value and gate halves).
+  const bool aligned = (reinterpret_cast<uintptr_t>(xq) % 16 == 0) && ws &&
+                       (reinterpret_cast<uintptr_t>(ws) % 16 == 0) &&
+                       (ws_is_prepared || reinterpret_cast<uintptr_t>(wq_packed) % 16 == 0);
+  if (aligned && fwd_q_takes_fragments(M, K, N, epilogue)) {
     const int64_t nn = (epilogue == AQT_EPI_GLU) ? N / 2 : N;
     const int64_t unit_wide = (epilogue == AQT_EPI_GLU) ? 128 : 256;
-    const int64_t unit = (epilogue == AQT_EPI_GLU) ? 64 : 128;
-    if (nn % unit == 0) {
-      v4i *wfrag = static_cast<v4i *>(ws);
-      const int64_t pieces = N * (K / (packed ? 32 : 16));
-      int g = static_cast<int>(cdiv(pieces, kThreads));
-      if (g > 2048) g = 2048;
-      weights_to_frag_kernel<<<g, kThreads, 0, st>>>(static_cast<const uint8_t *>(wq_packed), static_cast<int>(K),
-                                                     static_cast<int>(N), packed ? 1 : 0, wfrag);
-      AQT_HIP(hipGetLastError());
-      // 128 x 256 tiles need several rounds of them on the 512 workgroup slots to pay off (measured:
-      // from about 2000 tiles at a fan-in of 512, from about 400 when the main loop is long), else 128 x 128
-      const int64_t wide_tiles = cdiv(M, 128) * (N / 256);
-      const bool wide = (nn % unit_wide == 0) && wide_tiles >= (K >= 1024 ? 384 : 2048);
-      if (wide) {
-        return packed ? launch_mfma_epi<2, 4, true>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, dact, st)
-                      : launch_mfma_epi<2, 4, false>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, dact, st);
-      }
-      return packed ? launch_mfma_epi<2, 2, true>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, dact, st)
-                    : launch_mfma_epi<2, 2, false>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, dact, st);
+    v4i *wfrag = static_cast<v4i *>(ws);
+    if (!ws_is_prepared) AQT_TRY(launch_prepare_weights(wq_packed, K, N, bits_w, ws, st));
+    // 128 x 256 tiles need several rounds of them on the 512 workgroup slots to pay off (measured:
+    // from about 2000 tiles at a fan-in of 512, from about 400 when the main loop is long), else 128 x 128
+    const int64_t wide_tiles = cdiv(M, 128) * (N / 256);
+    const bool wide = (nn % unit_wide == 0) && wide_tiles >= (K >= 1024 ? 384 : 2048);
+    if (wide) {
+      return packed ? launch_mfma_epi<2, 4, true>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, dact, st)
+                    : launch_mfma_epi<2, 4, false>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, dact, st);
     }
+    return packed ? launch_mfma_epi<2, 2, true>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, dact, st)
+                  : launch_mfma_epi<2, 2, false>(epilogue, xq, s_x, wfrag, s_w, M, K, N, bias, y, acc_out, y_absmax, dact, st);
   }
+  if (ws_is_prepared) return AQT_ERR_UNSUPPORTED;   // the general kernel reads the canonical operand
   const int64_t ncols = (epilogue == AQT_EPI_GLU) ? N / 2 : N;
   dense_fwd_general_kernel<<<static_cast<int>(cdiv(M * ncols, kThreads)), kThreads, 0, st>>>(
       xq, s_x, static_cast<const uint8_t *>(wq_packed), s_w, M, K, N, packed ? 1 : 0, bias, epilogue, y,

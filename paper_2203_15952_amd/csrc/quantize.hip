@@ -291,7 +291,7 @@ __global__ __launch_bounds__(kThreads) void wabsmax_partial_kernel(const float *
 __global__ __launch_bounds__(kThreads) void quantize_weights_kernel(
     const float *__restrict__ w, int64_t K, int64_t N, int qmax, int packed, const uint32_t *__restrict__ part,
     int slabs, uint8_t *__restrict__ wq_packed, float *__restrict__ s_w, int8_t *__restrict__ wq_kn,
-    uint32_t *__restrict__ mask_w, int32_t *dev_status) {
+    uint32_t *__restrict__ mask_w, int32_t *dev_status, uint4 *__restrict__ wfrag) {
   __shared__ int8_t tile[kWCols][kWChunk + 4];
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
   const int64_t n0 = static_cast<int64_t>(blockIdx.x) * kWCols;
@@ -340,6 +340,46 @@ __global__ __launch_bounds__(kThreads) void quantize_weights_kernel(
     } else {
       const int64_t k = k0 + jb;
       if (k < K) wq_packed[nn * row_bytes + k] = static_cast<uint8_t>(tile[rn][jb]);
+    }
+  }
+  // The same tile once more in the order the forward contraction's matrix-core fragments
+  // want it (see weights_to_frag_kernel in gemm_fwd.hip for the layout), so that the
+  // forward needs no re-ordering pass of its own.  Only requested for whole tiles
+  // (N % 32 == 0, K % 64 == 0).  This block's tile is exactly one packed fragment (32
+  // channels x two 32-deep steps) or two int8 fragments.
+  if (wfrag) {
+    const int lane = threadIdx.x & 63, lr = lane & 31, lk = lane >> 5;
+    if (packed) {
+      if (threadIdx.x < 64) {
+        uint32_t d[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {          // dword q: step q / 2, codes 8 * (q % 2) .. + 7 of this lane's 16
+          const int kb = 32 * (q >> 1) + 16 * lk + 8 * (q & 1);
+          uint32_t t = 0;
+#pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            const uint32_t lo = static_cast<uint32_t>(tile[lr][kb + b]) & 0xFu;
+            const uint32_t hi = static_cast<uint32_t>(tile[lr][kb + 4 + b]) & 0xFu;
+            t |= (lo | (hi << 4)) << (8 * b);
+          }
+          d[q] = t;
+        }
+        const int64_t frag = static_cast<int64_t>(blockIdx.x) * (K / 64) + blockIdx.y;
+        wfrag[frag * 64 + lane] = make_uint4(d[0], d[1], d[2], d[3]);
+      }
+    } else if (threadIdx.x < 128) {
+      const int h = threadIdx.x >> 6;           // which of the tile's two steps
+      uint32_t d[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        uint32_t t = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+          t |= (static_cast<uint32_t>(tile[lr][32 * h + 16 * lk + 4 * q + b]) & 0xFFu) << (8 * b);
+        d[q] = t;
+      }
+      const int64_t frag = static_cast<int64_t>(blockIdx.x) * (K / 32) + 2 * blockIdx.y + h;
+      wfrag[frag * 64 + lane] = make_uint4(d[0], d[1], d[2], d[3]);
     }
   }
 }
@@ -457,7 +497,9 @@ aqt_status launch_quantize_with_scale(const float *x, int64_t rows, int64_t cols
 
 aqt_status launch_quantize_weights(const float *w, int64_t K, int64_t N, int bits_w, void *wq_packed,
                                    float *s_w, int8_t *wq_kn, uint32_t *mask_w, uint32_t *part, hipStream_t st,
-                                   int32_t *dev_status) {
+                                   int32_t *dev_status, void *wfrag) {
+  if (wfrag && (N % kWCols != 0 || K % kWChunk != 0 || reinterpret_cast<uintptr_t>(wfrag) % 16 != 0))
+    return AQT_ERR_INVALID_ARG;
   if (mask_w) {
     const int64_t words = cdiv(K * N, 32);
     zero_words_kernel<<<grid_for(words, kThreads, 1024), kThreads, 0, st>>>(mask_w, words);
@@ -474,7 +516,7 @@ aqt_status launch_quantize_weights(const float *w, int64_t K, int64_t N, int bit
   dim3 g2(static_cast<unsigned>(cdiv(N, kWCols)), static_cast<unsigned>(cdiv(K, kWChunk)));
   quantize_weights_kernel<<<g2, kThreads, 0, st>>>(w, K, N, qmax_of(bits_w), packed4(bits_w) ? 1 : 0, part,
                                                    static_cast<int>(slabs), static_cast<uint8_t *>(wq_packed),
-                                                   s_w, wq_kn, mask_w, dev_status);
+                                                   s_w, wq_kn, mask_w, dev_status, static_cast<uint4 *>(wfrag));
   AQT_HIP(hipGetLastError());
   return AQT_OK;
 }

@@ -192,6 +192,28 @@ def test_dense_fwd_against_oracle(M, K, N, bx, bw, epi, with_bias):
     np.testing.assert_array_equal(host(y2), host(y))
 
 
+@pytest.mark.parametrize("M,K,N,bw,epi", [(300, 128, 256, 4, 1), (200, 256, 512, 8, 2), (16500, 1152, 1024, 4, 0),
+                                          (12800, 512, 2048, 4, 1)])
+def test_prepared_weights_serving_path(M, K, N, bw, epi):
+    # weights re-ordered once, then the contraction without workspace: bit-identical to aqt_dense_fwd_q
+    say("prepared weights", M, K, N, bw, epi)
+    c = inputs.small_case(131 + M + N, M, K, N, 8, bw, epi, with_bias=True, with_dy=False)
+    bias = dev(c.bias)
+    xq, s_x, _ = B.aqt_quantize(dev(c.x), 8, B.AQT_AXIS_ALL)
+    wq, s_w, _, _ = B.aqt_quantize_weights(dev(c.w), bw)
+    y_ref, _ = B.aqt_dense_fwd_q(xq, s_x, wq, s_w, N, 8, bw, bias=bias, epilogue=epi)
+    wprep = B.aqt_prepare_weights(wq, K, N, bw)
+    assert wprep.numel() == K * N // (2 if bw <= 4 else 1)
+    for _ in range(2):
+        y = B.aqt_dense_fwd_q_prepared(xq, s_x, wprep, s_w, N, 8, bw, bias=bias, epilogue=epi)
+        np.testing.assert_array_equal(host(y), host(y_ref))
+    # shapes the matrix-core kernel does not take are refused
+    assert B.lib().aqt_prepared_weight_bytes(100, 256, bw) == 0
+    with pytest.raises(B.AqtError) as e:
+        B.aqt_dense_fwd_q_prepared(xq[:100].contiguous(), s_x, wprep, s_w, N, 8, bw)
+    assert e.value.status == B.AQT_ERR_UNSUPPORTED
+
+
 def test_dense_fwd_big_tiles_sampled():
     # the wide tiles; compare whole row tiles and sampled accumulators and outputs
     say("dense fwd big tiles")
