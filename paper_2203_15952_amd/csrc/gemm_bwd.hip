@@ -493,18 +493,30 @@ __global__ __launch_bounds__(128 * WN, WN == 2 ? 2 : 1) void dense_fwd_wonly_mfm
 // Rows past M (only in the last slab) are read from row M-1 and their codes are
 // zeroed, so the loop body stays branch-free.
 // =====================================================================================
-template <int TR, int TC, bool RAGGED>  // tile is (64*TR) k-rows x (64*TC) n-columns; 32 m per stage
-__global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_kernel(
+// Workgroup = 2 x WNW wavefronts (WNW = 2: 256 x 128 tile, two workgroups per compute unit;
+// WNW = 4: 256 x 256 tile, one workgroup of eight wavefronts per compute unit).  Two
+// independent workgroups on a compute unit do not stay level: the older one is served first
+// and the younger finishes its slab alone at about half the matrix pipe's rate (measured: 318 k
+// against 407 k cycles for the two slabs of a pair).  Eight wavefronts behind one barrier
+// cannot drift apart, so the wide form is used whenever the channel count allows it.
+template <int TR, int TC, bool RAGGED, int WNW>  // tile is (64*TR) k-rows x (32*TC*WNW) n-columns; 32 m per stage
+__global__ __launch_bounds__(128 * WNW, WNW == 2 ? 2 : 1) void bwd_dw_mfma_kernel(
     const int8_t *__restrict__ xq, const float *__restrict__ dy, int M, int K, int N, int m_per_slab,
     float *__restrict__ partial, int tiles_r, int tiles_c) {
-  constexpr int BR = 64 * TR, BC = 64 * TC;
+  constexpr int NT = 128 * WNW;               // threads
+  constexpr int BR = 64 * TR, BC = 32 * TC * WNW;
   constexpr int SM = 32;
   constexpr int GA = BR / 4, GB = BC / 4;   // 4-column groups per tile edge
   constexpr int P = TR * TC;                // MFMA pairs per half stage (2*TR*TC MFMAs)
-  static_assert(BR == 256 && BC == 128, "the gather pattern below is written for 256 x 128 tiles");
-  // Two slots, each a codes image and a dy hi/lo image pair.
-  __shared__ __attribute__((aligned(1024))) uint8_t sC0[BR * kRowB], sC1[BR * kRowB];
-  __shared__ __attribute__((aligned(1024))) uint8_t sD0[2 * BC * kRowB], sD1[2 * BC * kRowB];
+  constexpr int RC = SM / (NT / 64);        // rows of m of the codes one thread gathers: 8 or 4
+  static_assert(BR == 256 && P == 8 && NT / GB == 8, "the gather pattern below is written for 256-row tiles");
+  // Two slots, each a codes image and a dy hi/lo image pair; after the main loop the same
+  // memory stages the output tile.
+  constexpr int kCBytes = BR * kRowB, kDBytes = 2 * BC * kRowB;
+  __shared__ __attribute__((aligned(1024))) uint8_t smem[2 * (kCBytes + kDBytes)];
+  uint8_t *const sC0 = smem, *const sC1 = smem + kCBytes;
+  uint8_t *const sD0 = smem + 2 * kCBytes, *const sD1 = smem + 2 * kCBytes + kDBytes;
+  static_assert(2 * (kCBytes + kDBytes) >= 64 * BC * 4, "the output staging image must fit");
 
   // Workgroup -> (slab, tile).  All tiles of a slab read the same rows of xq and dy,
   // so a slab should live on one XCD (one L2) at one time: consecutive workgroup ids
@@ -523,13 +535,13 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_kernel(
 
   const int t = threadIdx.x;
   const int wave = t >> 6, lane = t & 63;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WNW, wn = wave % WNW;
   const int lr = lane & 31, lk = lane >> 5;
 
-  // gather units: codes (g = t % 64: 4 k, mg = t / 64: 8 m); gradients (h = t % 32: 4 n, ms = t / 32: 4 m)
+  // gather units: codes (g = t % 64: 4 k, mg = t / 64: RC m); gradients (h = t % GB: 4 n, ms = t / GB: 4 m)
   const int g = t & 63, mg = t >> 6;
-  const int h = t & 31, ms = t >> 5;
-  uint32_t rx[2][8];
+  const int h = t % GB, ms = t / GB;
+  uint32_t rx[2][RC];
   float4 ry[2][4];
 
   // Slab-uniform bases plus 32-bit offsets (a slab spans at most m_per_slab rows).
@@ -537,13 +549,13 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_kernel(
   const char *y_slab = reinterpret_cast<const char *>(dy + static_cast<int64_t>(m_begin) * N + c0);
   const int m_last = M - 1 - m_begin;      // last valid row, slab-relative
   // RAGGED (M not a multiple of 32): rows past M are read from row M-1 and their codes zeroed.
-  const uint32_t gx0 = static_cast<uint32_t>(mg * 8 * K + 4 * g);
+  const uint32_t gx0 = static_cast<uint32_t>(mg * RC * K + 4 * g);
   const uint32_t gy0 = static_cast<uint32_t>(ms * 4 * N + 4 * h) * 4u;
   auto load_global = [&](int set, int mrel0) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < RC; ++i) {
       if (RAGGED) {
-        const int mrel = mrel0 + mg * 8 + i;
+        const int mrel = mrel0 + mg * RC + i;
         const int mc = min(mrel, m_last);
         const uint32_t v = *reinterpret_cast<const uint32_t *>(x_slab + static_cast<uint32_t>(mc * K + 4 * g));
         rx[set][i] = mrel <= m_last ? v : 0u;
@@ -562,18 +574,25 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_kernel(
     }
   };
   // LDS write offsets (row rho = b*G + g, swizzled 16-byte chunk); b adds whole multiples of
-  // 32 rows, which leaves the swizzle bits unchanged.
-  const int offc0 = g * kRowB + ((mg ^ swz(g)) << 4);
+  // 32 rows, which leaves the swizzle bits unchanged.  A thread's piece of codes is RC bf16
+  // along m: a whole chunk (RC = 8) or half of one (RC = 4).
+  const int offc0 = g * kRowB + ((((mg * RC) >> 3) ^ swz(g)) << 4) + ((mg * RC) & 7) * 2;
   const int offd0 = h * kRowB + (((ms >> 1) ^ swz(h)) << 4) + (ms & 1) * 8;
   auto store_codes = [&](int set, int b, uint8_t *sC) {
-    // byte b of the eight dwords -> eight bf16 along m
-    float f[8];
+    // byte b of the RC dwords -> RC bf16 along m
+    float f[RC];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) f[i] = static_cast<float>(static_cast<int8_t>(rx[set][i] >> (8 * b)));
-    v4i a;
-    a.x = pack_bf16(f[0], f[1]); a.y = pack_bf16(f[2], f[3]);
-    a.z = pack_bf16(f[4], f[5]); a.w = pack_bf16(f[6], f[7]);
-    *reinterpret_cast<v4i *>(sC + offc0 + b * GA * kRowB) = a;
+    for (int i = 0; i < RC; ++i) f[i] = static_cast<float>(static_cast<int8_t>(rx[set][i] >> (8 * b)));
+    if (RC == 8) {
+      v4i a;
+      a.x = pack_bf16(f[0], f[1]); a.y = pack_bf16(f[2], f[3]);
+      a.z = pack_bf16(f[4 % RC], f[5 % RC]); a.w = pack_bf16(f[6 % RC], f[7 % RC]);
+      *reinterpret_cast<v4i *>(sC + offc0 + b * GA * kRowB) = a;
+    } else {
+      v2i a;
+      a.x = pack_bf16(f[0], f[1]); a.y = pack_bf16(f[2], f[3]);
+      *reinterpret_cast<v2i *>(sC + offc0 + b * GA * kRowB) = a;
+    }
   };
   auto store_dy = [&](int set, int b, uint8_t *sD) {
     // component b of the four float4 -> hi/lo bf16 along m
@@ -675,61 +694,45 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dw_mfma_kernel(
   }
   if (s < stages) stage(std::integral_constant<int, 0>{}, s);
 
-  // ---- epilogue: partial tile -> workspace.  Undo the de-interleaving of rows and
-  // columns; addresses are a uniform base plus a 32-bit lane offset plus
-  // compile-time multiples of N.
+  // ---- epilogue: partial tile -> workspace.
+  // Written lane by lane the tile would reach HBM as 4-byte pieces at a 16-byte stride (the
+  // de-interleaved columns), which the memory system turns into several times the traffic,
+  // all of it in the tail of the launch.  So the tile goes through LDS (free by now) and
+  // leaves as whole rows.  Accumulator row rho = wm*128 + i*32 + local (local = 8*(r/4) +
+  // r%4 + 4*lk) is tile row 4*(rho % 64) + rho / 64 and accumulator column rho_c =
+  // wn*32*TC + j*32 + lr is tile column 4*(rho_c % GB) + rho_c / GB (the de-interleaving of
+  // the staging).  Pass p (0..3) moves the 64 tile rows 4*q + p: they belong to the
+  // wavefronts with wm = p / 2 and their row blocks i = 2*(p % 2), 2*(p % 2) + 1, q = (i % 2)*32 + local.
   float *out = partial + static_cast<int64_t>(slab) * K * N + static_cast<int64_t>(r0) * N + c0;
-  if (TC == 2 && TR == 4) {
-    // Written lane by lane the tile would reach HBM as 4- or 8-byte pieces at a 16-byte
-    // stride (the de-interleaved columns), which the memory system turns into several
-    // times the traffic, all of it in the tail of the launch.  So the tile goes through
-    // LDS (free by now) in two halves of 128 rows and leaves as dense 512-byte row
-    // pieces.  Half ih holds the accumulator rows of row blocks i = 2*ih, 2*ih + 1:
-    // tile row k_l = 4*q + (2*wm + ih) with q = (i & 1)*32 + local, local = 8*(r/4) + r%4
-    // + 4*lk; the four LDS arrays serve as four chunks of 32 rows x 128 floats, chunk
-    // (wm, i & 1).  This wavefront's two column blocks are the adjacent tile columns
-    // 4*lr + 2*wn and + 1.
-    __syncthreads();   // every wavefront is done reading operand fragments
+  float *img = reinterpret_cast<float *>(smem);   // [64][BC]
 #pragma unroll
-    for (int ih = 0; ih < 2; ++ih) {
+  for (int p = 0; p < 4; ++p) {
+    __syncthreads();   // operand fragments (p = 0) or the previous pass's rows have been read by everybody
+    if (wm == (p >> 1)) {
 #pragma unroll
       for (int ii = 0; ii < 2; ++ii) {
-        const int i = 2 * ih + ii;
-        uint8_t *chunk = wm ? (ii ? sD1 : sD0) : (ii ? sC1 : sC0);
+        const int i = 2 * (p & 1) + ii;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int local = 8 * (r >> 2) + (r & 3) + 4 * lk;
-          v2f pr = {acc[i][0][r], acc[i][1][r]};
-          *reinterpret_cast<v2f *>(chunk + local * 512 + (4 * lr + 2 * wn) * 4) = pr;
+        for (int j = 0; j < TC; ++j) {
+          const int rho_c = wn * 32 * TC + j * 32 + lr;
+          const int n_l = 4 * (rho_c % GB) + rho_c / GB;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int q = ii * 32 + 8 * (r >> 2) + (r & 3) + 4 * lk;
+            img[q * BC + n_l] = acc[i][j][r];
+          }
         }
       }
-      __syncthreads();
-      // 32 threads per row: 128 rows x 32 float4 = 16 float4 per thread
-#pragma unroll
-      for (int p = 0; p < 16; ++p) {
-        const int ch = p >> 2;                       // chunk = (wm, i & 1) of the rows it holds
-        const int local = (t >> 5) + 8 * (p & 3);
-        const uint8_t *chunk = (ch >> 1) ? ((ch & 1) ? sD1 : sD0) : ((ch & 1) ? sC1 : sC0);
-        const float4 v = *reinterpret_cast<const float4 *>(chunk + local * 512 + (t & 31) * 16);
-        const int k_l = 4 * ((ch & 1) * 32 + local) + 2 * (ch >> 1) + ih;
-        *reinterpret_cast<float4 *>(out + k_l * N + (t & 31) * 4) = v;
-      }
-      if (ih == 0) __syncthreads();
     }
-    return;
-  }
+    __syncthreads();
+    // 64 rows x BC floats as float4: BC/4 threads per row
 #pragma unroll
-  for (int j = 0; j < TC; ++j) {
-    const int rho_c = wn * 32 * TC + j * 32 + lr;
-    const int n_l = 4 * (rho_c % GB) + rho_c / GB;
-#pragma unroll
-    for (int i = 0; i < TR; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int rho_r = wm * 32 * TR + i * 32 + 8 * (r >> 2) + (r & 3) + 4 * lk;
-        const int k_l = 4 * (rho_r % GA) + rho_r / GA;
-        out[k_l * N + n_l] = acc[i][j][r];
-      }
+    for (int it = 0; it < 64 * (BC / 4) / NT; ++it) {
+      const int idx = t + it * NT;
+      const int q = idx / (BC / 4), c4 = idx % (BC / 4);
+      const float4 v = *reinterpret_cast<const float4 *>(img + q * BC + c4 * 4);
+      *reinterpret_cast<float4 *>(out + (4 * q + p) * N + c4 * 4) = v;
+    }
   }
 }
 
@@ -762,6 +765,7 @@ struct BwdPlan {
   bool dx_mfma, dw_mfma;
   bool dx_wide;    // 128 x 256 tiles (else 128 x 128)
   bool dx_wide8;   // 128 x 512 tiles, eight wavefronts: the gradient tile is staged once for four column wavefronts
+  bool dw_wide8;   // dW on 256 x 256 tiles, eight wavefronts
   int slabs;
   int m_per_slab;
   size_t off_bf, off_part, off_bias, total;
@@ -774,10 +778,12 @@ BwdPlan plan_bwd(int64_t M, int64_t K, int64_t N) {
   p.dx_mfma = fits32 && (N % kSN == 0) && (K % 128 == 0) && (M >= 128);
   p.dx_wide = (K % 256 == 0) && cdiv(M, 128) * (K / 256) >= 512;
   p.dx_wide8 = p.dx_wide && (K % 512 == 0) && cdiv(M, 128) * (K / 512) >= 256;
-  // dW: 256 x 128 tiles over K x N, slabs over M
+  // dW: 256 x 256 tiles (eight wavefronts, one workgroup per compute unit) when N allows, else 256 x 128
+  // (two per compute unit); slabs over M so that the launch fills the chip once
   p.dw_mfma = fits32 && (K % 256 == 0) && (N % 128 == 0);
-  const int64_t tiles = p.dw_mfma ? (K / 256) * (N / 128) : 1;
-  int64_t slabs = p.dw_mfma ? cdiv(512, tiles) : 1;
+  p.dw_wide8 = p.dw_mfma && (N % 256 == 0);
+  const int64_t tiles = p.dw_mfma ? (K / 256) * (N / (p.dw_wide8 ? 256 : 128)) : 1;
+  int64_t slabs = p.dw_mfma ? cdiv(p.dw_wide8 ? 256 : 512, tiles) : 1;
   if (slabs > 64) slabs = 64;
   int64_t per = cdiv(M, slabs);
   per = cdiv(per, 32) * 32;            // whole stages
@@ -805,13 +811,13 @@ aqt_status launch_dx(const float *dy, const v4i *wq_frag, const aqt_saved *sv, i
   return AQT_OK;
 }
 
-template <int TR, int TC>
+template <int TR, int TC, int WNW>
 aqt_status launch_dw(const float *dy, const aqt_saved *sv, int64_t M, int64_t K, int64_t N, const BwdPlan &p,
                      float *partial, hipStream_t st) {
-  constexpr int BR = 64 * TR, BC = 64 * TC;
-  auto kern = (M % 32 == 0) ? bwd_dw_mfma_kernel<TR, TC, false> : bwd_dw_mfma_kernel<TR, TC, true>;
+  constexpr int BR = 64 * TR, BC = 32 * TC * WNW;
+  auto kern = (M % 32 == 0) ? bwd_dw_mfma_kernel<TR, TC, false, WNW> : bwd_dw_mfma_kernel<TR, TC, true, WNW>;
   const int tiles_r = static_cast<int>(K / BR), tiles_c = static_cast<int>(N / BC);
-  kern<<<tiles_r * tiles_c * p.slabs, kThreads, 0, st>>>(sv->xq, dy, static_cast<int>(M), static_cast<int>(K),
+  kern<<<tiles_r * tiles_c * p.slabs, 128 * WNW, 0, st>>>(sv->xq, dy, static_cast<int>(M), static_cast<int>(K),
                                                          static_cast<int>(N), p.m_per_slab, partial, tiles_r,
                                                          tiles_c);
   AQT_HIP(hipGetLastError());
@@ -935,7 +941,8 @@ aqt_status launch_dense_bwd(const float *dy, const aqt_saved *sv, int64_t M, int
     if (p.dw_mfma && dy_aligned && reinterpret_cast<uintptr_t>(sv->xq) % 4 == 0 &&
         reinterpret_cast<uintptr_t>(dw) % 16 == 0) {
       float *partial = reinterpret_cast<float *>(base + p.off_part);
-      AQT_TRY((launch_dw<4, 2>(dy, sv, M, K, N, p, partial, st)));
+      if (p.dw_wide8) AQT_TRY((launch_dw<4, 2, 4>(dy, sv, M, K, N, p, partial, st)));
+      else AQT_TRY((launch_dw<4, 2, 2>(dy, sv, M, K, N, p, partial, st)));
       bwd_dw_fold_kernel<<<static_cast<int>(cdiv(K * N / 4, kThreads)), kThreads, 0, st>>>(
           partial, p.slabs, K * N, N, sv->s_x, sv->s_w, sv->mask_w, dw);
       AQT_HIP(hipGetLastError());
