@@ -14,7 +14,7 @@ from typing import Optional
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libaqt.so")
+LIB_PATH = os.environ.get("AQT_LIB", os.path.join(_PKG, "libaqt.so"))   # AQT_LIB: e.g. the tracing build
 
 AQT_OK, AQT_ERR_INVALID_ARG, AQT_ERR_UNSUPPORTED, AQT_ERR_WORKSPACE, AQT_ERR_HIP, AQT_ERR_NONFINITE, AQT_ERR_SCRATCH = range(7)
 AQT_AXIS_ALL, AQT_AXIS_ROWS, AQT_AXIS_COLS = -1, 0, 1

@@ -6,6 +6,31 @@
 
 #include "aqt.h"
 
+// Per-tile timelines (tracing builds only, -DAQT_TIMELINE; see paper_2203_15952_amd/timeline.py):
+// wavefront 0 of every workgroup stamps the shader clock at its phase boundaries and leaves
+// eight 64-bit words per workgroup in a device array of the translation unit, which an
+// extern "C" accessor copies out.  The product build contains none of this.
+#ifdef AQT_TIMELINE
+#define AQT_TL_SLOTS (1 << 15)
+#define AQT_TL_DECL long long aqt_tl_[5] = {0, 0, 0, 0, 0}
+#define AQT_TL(i) aqt_tl_[i] = __builtin_readcyclecounter()
+#define AQT_TL_WRITE(buf, tag)                                                        \
+  do {                                                                                \
+    if ((threadIdx.x & 63) == 0 && (threadIdx.x >> 6) == 0 && blockIdx.x < AQT_TL_SLOTS) { \
+      unsigned hw_, xcc_;                                                             \
+      asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw_));               \
+      asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc_));             \
+      long long *o_ = (buf) + static_cast<long long>(blockIdx.x) * 8;                 \
+      o_[0] = aqt_tl_[0]; o_[1] = aqt_tl_[1]; o_[2] = aqt_tl_[2]; o_[3] = aqt_tl_[3];  \
+      o_[4] = aqt_tl_[4]; o_[5] = hw_; o_[6] = xcc_; o_[7] = (tag);                    \
+    }                                                                                 \
+  } while (0)
+#else
+#define AQT_TL_DECL
+#define AQT_TL(i)
+#define AQT_TL_WRITE(buf, tag)
+#endif
+
 namespace aqt {
 
 extern thread_local int g_last_hip_error;

@@ -22,6 +22,13 @@
 #include "aqt_internal.h"
 #include "epilogue.h"
 
+#ifdef AQT_TIMELINE
+static __device__ long long g_timeline_bwd[AQT_TL_SLOTS * 8];
+extern "C" int aqt_timeline_bwd(void *dst, size_t bytes) {
+  return static_cast<int>(hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_timeline_bwd), bytes));
+}
+#endif
+
 namespace aqt {
 namespace {
 
@@ -322,6 +329,8 @@ __device__ __forceinline__ void f32_codes_tile(
   auto stage_idx = [&](int s) { return s < NT - 1 ? s : NT - 1; };
   auto stage_n0 = [&](int s) { return stage_idx(s) * kSN; };
 
+  AQT_TL_DECL;
+  AQT_TL(0);
   // ---- prologue: stage 0 staged into slot 0, dy of stage 1 into register set 1,
   //      codes of stage 0 into their register sets ----
   load_s(0);
@@ -381,6 +390,7 @@ __device__ __forceinline__ void f32_codes_tile(
     }
   };
 
+  AQT_TL(1);
   int nt = 0;
   for (; nt + 1 < NT; nt += 2) {
     stage(std::integral_constant<int, 0>{}, nt);
@@ -388,6 +398,7 @@ __device__ __forceinline__ void f32_codes_tile(
   }
   if (nt < NT) stage(std::integral_constant<int, 0>{}, nt);
 
+  AQT_TL(2);
   // ---- epilogue: registers -> HBM.  Lane holds column (lane % 32) of each 32 x 32
   // tile, register r holds row 8*(r/4) + 4*(lane/32) + r%4; 32 lanes write 128
   // contiguous bytes.  Addresses are a uniform tile base plus one 32-bit lane offset;
@@ -451,6 +462,12 @@ __device__ __forceinline__ void f32_codes_tile(
           __builtin_nontemporal_store((keep != 0.0f) ? acc[i][j][r] : 0.0f, obase + row_off + j * 32 + lane_off);
       }
   }
+#ifdef AQT_TIMELINE
+  AQT_TL(3);
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));   // the stores have been acknowledged
+  AQT_TL(4);
+  AQT_TL_WRITE(g_timeline_bwd, bm * 65536 + bc);
+#endif
 }
 
 template <int TM, int TN, bool MASKED, int WN = 2>
@@ -640,6 +657,8 @@ __global__ __launch_bounds__(128 * WNW, WNW == 2 ? 2 : 1) void bwd_dw_mfma_kerne
   const int stages = (m_end - m_begin + SM - 1) / SM;
   auto stage_m = [&](int s) { return (s < stages - 1 ? s : stages - 1) * SM; };   // slab-relative
 
+  AQT_TL_DECL;
+  AQT_TL(0);
   // ---- prologue ----
   load_global(0, stage_m(0));
 #pragma unroll
@@ -687,12 +706,14 @@ __global__ __launch_bounds__(128 * WNW, WNW == 2 ? 2 : 1) void bwd_dw_mfma_kerne
     }
   };
 
+  AQT_TL(1);
   int s = 0;
   for (; s + 1 < stages; s += 2) {
     stage(std::integral_constant<int, 0>{}, s);
     stage(std::integral_constant<int, 1>{}, s + 1);
   }
   if (s < stages) stage(std::integral_constant<int, 0>{}, s);
+  AQT_TL(2);
 
   // ---- epilogue: partial tile -> workspace.
   // Written lane by lane the tile would reach HBM as 4-byte pieces at a 16-byte stride (the
@@ -734,6 +755,12 @@ __global__ __launch_bounds__(128 * WNW, WNW == 2 ? 2 : 1) void bwd_dw_mfma_kerne
       *reinterpret_cast<float4 *>(out + (4 * q + p) * N + c4 * 4) = v;
     }
   }
+#ifdef AQT_TIMELINE
+  AQT_TL(3);
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));   // the stores have been acknowledged
+  AQT_TL(4);
+  AQT_TL_WRITE(g_timeline_bwd, slab * 65536 + tile);
+#endif
 }
 
 // Fold the slabs in order, scale by s_x, apply the mask.

@@ -17,6 +17,13 @@
 // is only a handle for hipGetSymbolAddress; kernels are given the address that call returns.
 static __device__ __align__(256) uint8_t scratch[AQT_STATIC_SCRATCH_BYTES];
 
+#ifdef AQT_TIMELINE
+static __device__ long long g_timeline_fwd[AQT_TL_SLOTS * 8];
+extern "C" int aqt_timeline_fwd(void *dst, size_t bytes) {
+  return static_cast<int>(hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_timeline_fwd), bytes));
+}
+#endif
+
 namespace aqt {
 namespace {
 
@@ -275,6 +282,8 @@ __global__ __launch_bounds__(kThreads, 2) void dense_fwd_mfma_kernel(
   const int NS = K / kBK;
   auto stage_idx = [&](int s) { return s < NS - 1 ? s : NS - 1; };
 
+  AQT_TL_DECL;
+  AQT_TL(0);
   // ---- prologue ----
   int off_cur = 0, off_nxt = kSlotBytes, off_fill = 2 * kSlotBytes;
   issue_a(off_cur, 0);
@@ -300,6 +309,7 @@ __global__ __launch_bounds__(kThreads, 2) void dense_fwd_mfma_kernel(
     for (int j = 0; j < TN; ++j) ub[0][j] = expand16(raw[0][j].x, raw[0][j].y);
   }
 
+  AQT_TL(1);
   // One stage; PAR = s % 2 is a compile-time constant (register slots).
   // MFMA q = i*TN + j of a step: row tile i uses its activation fragment in TN
   // consecutive MFMAs and is refilled right after.  Between MFMA pairs: packed weights
@@ -360,6 +370,7 @@ __global__ __launch_bounds__(kThreads, 2) void dense_fwd_mfma_kernel(
   if (s < NS) stage(std::integral_constant<int, 0>{}, s);
   // the clamped loads of the last stages are still writing LDS: drain them before the wavefront can end
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
+  AQT_TL(2);
 
   // ---- epilogue: registers -> HBM ----
   // Lane holds output column (lane % 32) of each 32 x 32 tile; register r holds
@@ -432,6 +443,12 @@ __global__ __launch_bounds__(kThreads, 2) void dense_fwd_mfma_kernel(
       }
     }
   }
+#ifdef AQT_TIMELINE
+  AQT_TL(3);
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));   // the stores have been acknowledged
+  AQT_TL(4);
+  AQT_TL_WRITE(g_timeline_fwd, bm * 65536 + bn);
+#endif
   if (y_absmax) {   // uniform: one atomic per wavefront, and only if it can raise the word
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) amax = max(amax, static_cast<uint32_t>(__shfl_xor(static_cast<int>(amax), off)));
