@@ -383,6 +383,29 @@ def test_backward_is_bit_reproducible_and_stream_ordered():
     np.testing.assert_array_equal(host(dx3), host(dx1))
 
 
+def test_twenty_runs_give_identical_bytes():
+    # Every kernel is deterministic: integer maxima and integer sums do not depend on order, the float
+    # reductions (dW slabs, column sums, row statistics) are folded in a fixed order, and the only atomics
+    # are maxima and bit-wise ORs.  Twenty runs of each entry point must agree byte for byte.
+    say("determinism x20")
+    M, K, N = 2048, 512, 512
+    c = inputs.small_case(111, M, K, N, 8, 4, 1, with_bias=True)
+    x_d, w_d, dy_d, b_d = dev(c.x), dev(c.w), dev(c.dy), dev(c.bias)
+    first = None
+    for run in range(20):
+        sv = B.Saved(M, K, N, 4, masks=True, dact=True)
+        y = B.aqt_dense_fwd(x_d, w_d, 8, 4, bias=b_d, epilogue=1, saved=sv)
+        _, m = B.aqt_dense_fwd_q_absmax(sv.xq, sv.s_x, sv.wq_packed, sv.s_w, N, 8, 4, bias=b_d, epilogue=1)
+        dx, dw, db = B.aqt_dense_bwd(dy_d, sv, 8, 4, epilogue=1, want_dbias=True)
+        q_ln, s_ln, _, st_ln = B.aqt_layernorm_quantize(x_d, 8, want_stats=True)
+        got = [host(t).tobytes() for t in (sv.xq, sv.s_x, sv.mask_x, sv.wq_packed, sv.wq_kn, sv.s_w, sv.mask_w,
+                                           sv.dact, y, m, dx, dw, db, q_ln, s_ln, st_ln)]
+        if first is None:
+            first = got
+        else:
+            assert got == first, f"run {run} differs from run 0"
+
+
 def test_dense_fwd_very_tall_input_indexing():
     # a million rows: tile bases are 64-bit, lane offsets 32-bit; compare sampled accumulators
     say("dense fwd tall")

@@ -233,12 +233,39 @@ def test_pack_int4_never_emits_minus_eight_and_size():
     np.testing.assert_array_equal(back[:, :K].T, q)
 
 
+def golden():
+    """tests/golden/paper_printed_values.txt: numbers the paper prints, each with its citation."""
+    import os
+    out = {}
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_printed_values.txt")
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = line.split("=")
+            out[k.strip()] = float(v)
+    return out
+
+
 def test_model_size_accounting_matches_table1():
-    # Table 1, Conformer (L): 475 MB float, 139 MB int8, 82 MB int4.  If n MB of
-    # parameters (at 1 B each) are quantized, float->int8 saves 3n and int4 stores
-    # half a byte per parameter: 475 - 3.5 n must land on the int4 row.
-    n = (475 - 139) / 3.0
-    assert abs((475 - 3.5 * n) - 82) <= 1.5
+    # Table 1 (sizes read from the golden file).  If n MB of parameters (at 1 B each) are quantized,
+    # float->int8 saves 3n and int4 stores half a byte per parameter: float - 3.5 n must land on the
+    # int4 row, for the large and the small model and for Table 2's production model.
+    g = golden()
+    for f, i8, i4, slack in ((g["conformer_L_float_mb"], g["conformer_L_int8_mb"], g["conformer_L_int4_mb"], 1.5),
+                             (g["conformer_S_float_mb"], g["conformer_S_int8_mb"], g["conformer_S_int4_mb"], 1.0),
+                             (g["prod_float_mb"], g["prod_int8_mb"], g["prod_int4_mb"], 4.0)):
+        n = (f - i8) / 3.0
+        assert abs((f - 3.5 * n) - i4) <= slack
+    # Table 2, E10: int4 on a fraction of the layers lands between the int4 and int8 sizes, at the
+    # fraction of the weights those layers hold (3 of 7 + 3 of 6 layers of the two encoders: about 46 %)
+    frac = (g["prod_int8_mb"] - g["prod_first3_int4_mb"]) / (g["prod_int8_mb"] - g["prod_int4_mb"])
+    assert 0.3 < frac < 0.6
+    # the divisors of Sec. 2.2 are 2^(b-1) - 1
+    assert g["qmax_int8"] == 2 ** 7 - 1 and g["qmax_int4"] == 2 ** 3 - 1
+    q, s = oracle.quantize(np.array([[g["qmax_int8"], 1.0]], F), 8, oracle.AXIS_ALL)
+    assert s[0] == 1.0 and q.tolist() == [[127, 1]]
+    q, s = oracle.quantize(np.array([[g["qmax_int4"], 1.0]], F), 4, oracle.AXIS_ALL)
+    assert s[0] == 1.0 and q.tolist() == [[7, 1]]
 
 
 # ----------------------------------------------------------------------------
