@@ -307,3 +307,42 @@ def fake_matmul_f32(xq, wq_kn):
     out = np.empty((M, N), np.float32)
     _c().oracle_fake_matmul_f32(_p(xq), _p(wq_kn), ctypes.c_int64(M), ctypes.c_int64(K), ctypes.c_int64(N), _p(out))
     return out
+
+
+def depthwise_conv(x, w, bias=None, pad_left: int = 0, want_abs: bool = False):
+    """Depthwise convolution along time, float64.  x [B,T,C], w [kw,C], zero frames outside an utterance."""
+    x, w = _f32(x), _f32(w)
+    B, T, C = x.shape
+    kw = w.shape[0]
+    b = None if bias is None else _f32(bias)
+    out = np.empty((B, T, C), np.float64)
+    ab = np.empty((B, T, C), np.float64) if want_abs else None
+    _c().oracle_depthwise_conv(_p(x), _p(w), _p(b), ctypes.c_int64(B), ctypes.c_int64(T), ctypes.c_int64(C),
+                               ctypes.c_int64(kw), ctypes.c_int64(pad_left), _p(out), _p(ab))
+    return (out, ab) if want_abs else out
+
+
+def depthwise_conv_bwd(dout, x, w, pad_left: int = 0):
+    """Gradients of depthwise_conv with respect to x, w and bias (float64) and the absolute-term sums."""
+    x, w = _f32(x), _f32(w)
+    dout = np.ascontiguousarray(dout, np.float64)
+    B, T, C = x.shape
+    kw = w.shape[0]
+    dx, dxa = np.empty((B, T, C), np.float64), np.empty((B, T, C), np.float64)
+    dw, dwa = np.empty((kw, C), np.float64), np.empty((kw, C), np.float64)
+    db = np.empty(C, np.float64)
+    _c().oracle_depthwise_conv_bwd(_p(dout), _p(x), _p(w), ctypes.c_int64(B), ctypes.c_int64(T), ctypes.c_int64(C),
+                                   ctypes.c_int64(kw), ctypes.c_int64(pad_left), _p(dx), _p(dw), _p(db), _p(dxa),
+                                   _p(dwa))
+    return dict(dx=dx, dw=dw, dbias=db, dx_abs=dxa, dw_abs=dwa)
+
+
+def affine_swish(v, a=None, b=None):
+    """Per-channel scale and shift, then Swish; returns (out, d out / d v), float64.  v [M,C]."""
+    v = np.ascontiguousarray(v, np.float64)
+    M, C = v.shape
+    aa = None if a is None else _f32(a)
+    bb = None if b is None else _f32(b)
+    out, df = np.empty((M, C), np.float64), np.empty((M, C), np.float64)
+    _c().oracle_affine_swish(_p(v), ctypes.c_int64(M), ctypes.c_int64(C), _p(aa), _p(bb), _p(out), _p(df))
+    return out, df

@@ -30,6 +30,12 @@
  *                         (Sec. 3.2's Conformer; per token over the model width,
  *                         biased variance), float64; not part of the paper's
  *                         method, glue of the chained block.
+ *   oracle_depthwise_conv*, oracle_affine_swish
+ *                         the float layers between the two pointwise convolutions
+ *                         of the convolution module (Sec. 3.2: depthwise kernel 32;
+ *                         Sec. 3.3: causal kernel 15, convolution kernels stay
+ *                         float): the plain definitions and their adjoints, float64;
+ *                         glue of the chained block.
  *   oracle_fake_matmul_f32  Sec. 1 / Sec. 2.2: "fake" quantization carries the integer
  *                         codes in float32 and multiplies them with float
  *                         operations; sums that need more than 24 bits are rounded.
@@ -54,7 +60,10 @@
  * layer in float64 numpy; the normalisation by a hand-worked row, zero mean and
  * unit variance of its rows, and numpy; the float32-emulated product by equality
  * with the integer product while sums fit 24 bits and a hand-worked sum that does
- * not).  The paper prints
+ * not; the depthwise convolution by its impulse response, a hand-worked causal
+ * example, numpy's correlate per channel, the adjoint identity and central
+ * differences for its gradients; the affine + Swish by closed-form values and
+ * central differences).  The paper prints
  * no worked numeric example, so no pin comes from printed values.
  */
 #include <math.h>
@@ -485,6 +494,110 @@ void oracle_fake_matmul_f32(const int8_t *xq, const int8_t *wq_kn, int64_t M, in
         a = a + p;                                                 /* one binary32 rounding */
       }
       out[m * N + n] = a;
+    }
+}
+
+/*
+ * Depthwise convolution along time, the float layer between the two pointwise
+ * convolutions of the Conformer convolution module (Sec. 3.2: kernel size 32;
+ * Sec. 3.3: causal, kernel size 15, and the convolution kernels are not
+ * quantized).  x [B,T,C]: B utterances of T frames, C channels; w [kw,C]; bias
+ * nullable [C].  Frames outside an utterance count as zero:
+ *   out[b,t,c] = bias[c] + sum_j w[j,c] * x[b, t + j - pad_left, c],  0 <= j < kw.
+ * pad_left = kw - 1 makes the layer causal.  float64; out_abs (nullable) gets the
+ * sum of the absolute values of the same terms.
+ */
+void oracle_depthwise_conv(const float *x, const float *w, const float *bias, int64_t B, int64_t T,
+                           int64_t C, int64_t kw, int64_t pad_left, double *out, double *out_abs) {
+#pragma omp parallel for schedule(static)
+  for (int64_t bt = 0; bt < B * T; ++bt) {
+    const int64_t b = bt / T, t = bt % T;
+    for (int64_t c = 0; c < C; ++c) {
+      double a = bias ? (double)bias[c] : 0.0, ab = fabs(a);
+      for (int64_t j = 0; j < kw; ++j) {
+        const int64_t u = t + j - pad_left;
+        if (u < 0 || u >= T) continue;
+        const double p = (double)w[j * C + c] * (double)x[(b * T + u) * C + c];
+        a += p;
+        ab += fabs(p);
+      }
+      out[bt * C + c] = a;
+      if (out_abs) out_abs[bt * C + c] = ab;
+    }
+  }
+}
+
+/*
+ * Gradients of oracle_depthwise_conv for an upstream gradient dout [B,T,C] (float64):
+ *   dx[b,u,c]  = sum_j w[j,c] * dout[b, u - j + pad_left, c]
+ *   dw[j,c]    = sum_{b,t} dout[b,t,c] * x[b, t + j - pad_left, c]
+ *   dbias[c]   = sum_{b,t} dout[b,t,c]
+ * each nullable; dx_abs / dw_abs (nullable) get the sums of absolute terms.
+ */
+void oracle_depthwise_conv_bwd(const double *dout, const float *x, const float *w, int64_t B, int64_t T,
+                               int64_t C, int64_t kw, int64_t pad_left, double *dx, double *dw,
+                               double *dbias, double *dx_abs, double *dw_abs) {
+  if (dx) {
+#pragma omp parallel for schedule(static)
+    for (int64_t bu = 0; bu < B * T; ++bu) {
+      const int64_t b = bu / T, u = bu % T;
+      for (int64_t c = 0; c < C; ++c) {
+        double a = 0.0, ab = 0.0;
+        for (int64_t j = 0; j < kw; ++j) {
+          const int64_t t = u - j + pad_left;
+          if (t < 0 || t >= T) continue;
+          const double p = (double)w[j * C + c] * dout[(b * T + t) * C + c];
+          a += p;
+          ab += fabs(p);
+        }
+        dx[bu * C + c] = a;
+        if (dx_abs) dx_abs[bu * C + c] = ab;
+      }
+    }
+  }
+  if (dw) {
+#pragma omp parallel for schedule(static)
+    for (int64_t jc = 0; jc < kw * C; ++jc) {
+      const int64_t j = jc / C, c = jc % C;
+      double a = 0.0, ab = 0.0;
+      for (int64_t b = 0; b < B; ++b)
+        for (int64_t t = 0; t < T; ++t) {
+          const int64_t u = t + j - pad_left;
+          if (u < 0 || u >= T) continue;
+          const double p = dout[(b * T + t) * C + c] * (double)x[(b * T + u) * C + c];
+          a += p;
+          ab += fabs(p);
+        }
+      dw[jc] = a;
+      if (dw_abs) dw_abs[jc] = ab;
+    }
+  }
+  if (dbias) {
+    for (int64_t c = 0; c < C; ++c) {
+      double a = 0.0;
+      for (int64_t bt = 0; bt < B * T; ++bt) a += dout[bt * C + c];
+      dbias[c] = a;
+    }
+  }
+}
+
+/*
+ * The normalisation after the depthwise convolution in the form it takes once its
+ * statistics are fixed (one scale a[c] and one shift b[c] per channel, both nullable:
+ * 1 and 0), followed by Swish (Sec. 3.2's convolution module):
+ *   n = v * a[c] + b[c];  out = n * sigmoid(n);  dfac = d out / d v = a[c] * swish'(n)
+ * with swish'(n) = s (1 + n (1 - s)), s = sigmoid(n).  float64; out, dfac nullable.
+ */
+void oracle_affine_swish(const double *v, int64_t M, int64_t C, const float *a, const float *b,
+                         double *out, double *dfac) {
+#pragma omp parallel for schedule(static)
+  for (int64_t m = 0; m < M; ++m)
+    for (int64_t c = 0; c < C; ++c) {
+      const double ac = a ? (double)a[c] : 1.0;
+      const double n = v[m * C + c] * ac + (b ? (double)b[c] : 0.0);
+      const double s = sigmoid64(n);
+      if (out) out[m * C + c] = n * s;
+      if (dfac) dfac[m * C + c] = ac * s * (1.0 + n * (1.0 - s));
     }
 }
 

@@ -38,6 +38,13 @@ int oracle_dense_bwd_epi(const float *dout, const double *pre, int epilogue, con
 void oracle_layernorm(const float *x, int64_t M, int64_t D, const float *gamma, const float *beta, double eps,
                       double *y);
 void oracle_fake_matmul_f32(const int8_t *xq, const int8_t *wq_kn, int64_t M, int64_t K, int64_t N, float *out);
+void oracle_depthwise_conv(const float *x, const float *w, const float *bias, int64_t B, int64_t T, int64_t C,
+                           int64_t kw, int64_t pad_left, double *out, double *out_abs);
+void oracle_depthwise_conv_bwd(const double *dout, const float *x, const float *w, int64_t B, int64_t T, int64_t C,
+                               int64_t kw, int64_t pad_left, double *dx, double *dw, double *dbias, double *dx_abs,
+                               double *dw_abs);
+void oracle_affine_swish(const double *v, int64_t M, int64_t C, const float *a, const float *b, double *out,
+                         double *dfac);
 void oracle_dense_fwd_q_sampled(const int8_t *xq, float s_x, const int8_t *wq_kn, const float *s_w, int64_t K,
                                 int64_t N, const float *bias, const int64_t *idx_m, const int64_t *idx_n,
                                 int64_t count, int64_t *acc, double *pre);
@@ -156,6 +163,28 @@ static void one_shape(int64_t M, int64_t K, int64_t N, int bits_x, int bits_w) {
   free(dw); free(dwa); free(db);
 }
 
+/* depthwise convolution, its gradients and the affine + Swish on exactly sized buffers */
+static void one_conv(int64_t B, int64_t T, int64_t C, int64_t kw, int64_t pad_left) {
+  const size_t n = (size_t)(B * T * C);
+  float *x = need(n * sizeof(float)), *w = need((size_t)(kw * C) * sizeof(float)), *b = need((size_t)C * sizeof(float));
+  double *out = need(n * sizeof(double)), *ab = need(n * sizeof(double)), *dx = need(n * sizeof(double));
+  double *dxa = need(n * sizeof(double)), *dw = need((size_t)(kw * C) * sizeof(double));
+  double *dwa = need((size_t)(kw * C) * sizeof(double)), *db = need((size_t)C * sizeof(double));
+  for (size_t i = 0; i < n; ++i) x[i] = next_unit();
+  for (int64_t i = 0; i < kw * C; ++i) w[i] = next_unit();
+  for (int64_t i = 0; i < C; ++i) b[i] = next_unit();
+  oracle_depthwise_conv(x, w, b, B, T, C, kw, pad_left, out, ab);
+  oracle_depthwise_conv(x, w, NULL, B, T, C, kw, pad_left, out, NULL);
+  oracle_depthwise_conv_bwd(out, x, w, B, T, C, kw, pad_left, dx, dw, db, dxa, dwa);
+  oracle_depthwise_conv_bwd(out, x, w, B, T, C, kw, pad_left, dx, NULL, NULL, NULL, NULL);
+  oracle_depthwise_conv_bwd(out, x, w, B, T, C, kw, pad_left, NULL, dw, db, NULL, NULL);
+  oracle_affine_swish(out, B * T, C, b, b, dx, dxa);
+  oracle_affine_swish(out, B * T, C, NULL, NULL, dx, NULL);
+  oracle_affine_swish(out, B * T, C, b, NULL, NULL, dxa);
+  for (size_t i = 0; i < n; ++i) CHECK(isfinite(dx[i]) && isfinite(dxa[i]));
+  free(x); free(w); free(b); free(out); free(ab); free(dx); free(dxa); free(dw); free(dwa); free(db);
+}
+
 int main(void) {
   /* Fig. 2 rounds floor(t + 0.5): with 127 present the scale is exactly 1 */
   const float ties[8] = {127.0f, 0.5f, -0.5f, 1.5f, -1.5f, 2.5f, -2.5f, -127.0f};
@@ -176,6 +205,10 @@ int main(void) {
   one_shape(7, 9, 5, 4, 4);
   one_shape(33, 17, 6, 8, 2);
   one_shape(2, 64, 3, 5, 8);
+  one_conv(1, 1, 1, 1, 0);
+  one_conv(2, 5, 3, 32, 15);
+  one_conv(3, 40, 2, 15, 14);
+  one_conv(1, 9, 4, 4, 0);
   printf("oracle sanitizer run ok\n");
   return 0;
 }

@@ -702,3 +702,101 @@ def test_fake_float32_product_equals_integers_until_24_bits_then_rounds():
     exact = xq.astype(np.int64) @ wq.astype(np.int64)
     fake = oracle.fake_matmul_f32(xq, wq).astype(np.float64)
     assert (fake != exact).any() and np.abs(fake - exact).max() <= K * 2.0 ** -24 * exact.max()
+
+
+# ----------------------------------------------------------------------------
+# Depthwise convolution and the normalisation + Swish behind it (convolution module, Sec. 3.2 / 3.3)
+# ----------------------------------------------------------------------------
+def test_depthwise_conv_hand_worked_causal_example_and_impulse_response():
+    # one channel, T = 4, kernel 3, causal (pad_left = kw - 1): out[t] = w0 x[t-2] + w1 x[t-1] + w2 x[t]
+    x = np.array([1, 2, 3, 4], F).reshape(1, 4, 1)
+    w = np.array([0.5, -1.0, 2.0], F).reshape(3, 1)
+    np.testing.assert_array_equal(oracle.depthwise_conv(x, w, pad_left=2).ravel(), [2.0, 3.0, 4.5, 6.0])
+    # centred (pad_left = 1): out[t] = w0 x[t-1] + w1 x[t] + w2 x[t+1]
+    np.testing.assert_array_equal(oracle.depthwise_conv(x, w, pad_left=1).ravel(), [3.0, 4.5, 6.0, -2.5])
+    np.testing.assert_array_equal(oracle.depthwise_conv(x, w, np.array([10.0], F), pad_left=1).ravel(),
+                                  [13.0, 14.5, 16.0, 7.5])
+    # an impulse at frame t0 of channel c0 puts the reversed kernel of that channel around t0, nothing elsewhere
+    rng = np.random.default_rng(50)
+    B, T, C, kw, pl = 2, 40, 5, 32, 15
+    w = rng.standard_normal((kw, C)).astype(F)
+    for t0 in (0, 7, 39):
+        x = np.zeros((B, T, C), F)
+        x[1, t0, 3] = 1.0
+        out = oracle.depthwise_conv(x, w, pad_left=pl)
+        want = np.zeros((B, T, C))
+        for t in range(T):
+            j = t0 - t + pl
+            if 0 <= j < kw:
+                want[1, t, 3] = w[j, 3]
+        np.testing.assert_array_equal(out, want)
+
+
+def test_depthwise_conv_equals_numpy_correlate_per_channel_and_keeps_utterances_apart():
+    rng = np.random.default_rng(51)
+    for (B, T, C, kw, pl) in [(3, 50, 4, 32, 15), (2, 17, 3, 15, 14), (1, 5, 2, 32, 15), (2, 9, 1, 1, 0)]:
+        x = rng.standard_normal((B, T, C)).astype(F)
+        w = rng.standard_normal((kw, C)).astype(F)
+        bias = rng.standard_normal(C).astype(F)
+        out, ab = oracle.depthwise_conv(x, w, bias, pad_left=pl, want_abs=True)
+        for b in range(B):
+            for c in range(C):
+                padded = np.pad(x[b, :, c].astype(np.float64), (pl, kw - 1 - pl))
+                ref = np.correlate(padded, w[:, c].astype(np.float64), "valid") + np.float64(bias[c])
+                np.testing.assert_allclose(out[b, :, c], ref, rtol=0, atol=1e-13)
+        assert (ab >= np.abs(out) - 1e-12).all()
+        # each utterance alone gives the same frames: nothing crosses an utterance boundary
+        for b in range(B):
+            np.testing.assert_array_equal(oracle.depthwise_conv(x[b:b + 1], w, bias, pad_left=pl)[0], out[b])
+
+
+def test_depthwise_conv_gradients_adjoint_identity_and_central_differences():
+    rng = np.random.default_rng(52)
+    B, T, C, kw, pl = 2, 23, 3, 8, 3
+    x = rng.standard_normal((B, T, C)).astype(F)
+    w = rng.standard_normal((kw, C)).astype(F)
+    dout = rng.standard_normal((B, T, C))
+    g = oracle.depthwise_conv_bwd(dout, x, w, pad_left=pl)
+    out = oracle.depthwise_conv(x, w, pad_left=pl)
+    # the layer is bilinear in (x, w): <out, dout> = <x, dx> = <w, dw>
+    ip = (out * dout).sum()
+    np.testing.assert_allclose((x * g["dx"]).sum(), ip, rtol=1e-12)
+    np.testing.assert_allclose((w * g["dw"]).sum(), ip, rtol=1e-12)
+    np.testing.assert_allclose(g["dbias"], dout.sum((0, 1)), rtol=1e-12)
+    # central differences of L = <conv(x, w) + bias, dout> (float32 operands stepped by exact powers of two)
+    h = F(2.0 ** -6)
+    for (b, t, c) in [(0, 0, 0), (1, 22, 2), (0, 11, 1)]:
+        xp, xm = x.copy(), x.copy()
+        xp[b, t, c] += h
+        xm[b, t, c] -= h
+        fd = ((oracle.depthwise_conv(xp, w, pad_left=pl) - oracle.depthwise_conv(xm, w, pad_left=pl)) * dout).sum()
+        fd /= float(xp[b, t, c]) - float(xm[b, t, c])
+        np.testing.assert_allclose(g["dx"][b, t, c], fd, rtol=1e-9, atol=1e-11)
+    for (j, c) in [(0, 0), (7, 2), (3, 1)]:
+        wp, wm = w.copy(), w.copy()
+        wp[j, c] += h
+        wm[j, c] -= h
+        fd = ((oracle.depthwise_conv(x, wp, pad_left=pl) - oracle.depthwise_conv(x, wm, pad_left=pl)) * dout).sum()
+        fd /= float(wp[j, c]) - float(wm[j, c])
+        np.testing.assert_allclose(g["dw"][j, c], fd, rtol=1e-9, atol=1e-11)
+
+
+def test_affine_swish_closed_forms_and_central_differences():
+    sig1 = 1.0 / (1.0 + np.exp(-1.0))
+    out, df = oracle.affine_swish(np.array([[0.0, 0.0]]), a=np.array([1.0, 2.0], F), b=np.array([0.0, 1.0], F))
+    # n = 0: swish 0, slope 1/2;  n = 1 (a = 2): swish sigmoid(1), slope 2 sigmoid(1) (2 - sigmoid(1))
+    np.testing.assert_allclose(out, [[0.0, sig1]], rtol=1e-15, atol=0)
+    np.testing.assert_allclose(df, [[0.5, 2.0 * sig1 * (2.0 - sig1)]], rtol=1e-15)
+    # far from zero Swish is the identity on the right and zero on the left
+    out, df = oracle.affine_swish(np.array([[40.0], [-40.0]]))
+    np.testing.assert_allclose(out.ravel(), [40.0, 0.0], atol=1e-15)
+    np.testing.assert_allclose(df.ravel(), [1.0, 0.0], atol=1e-15)
+    rng = np.random.default_rng(53)
+    v = rng.standard_normal((6, 4)) * 3
+    a, b = rng.standard_normal(4).astype(F), rng.standard_normal(4).astype(F)
+    out, df = oracle.affine_swish(v, a, b)
+    n = v * a.astype(np.float64) + b.astype(np.float64)
+    np.testing.assert_allclose(out, n / (1.0 + np.exp(-n)), rtol=1e-14)
+    h = 1e-6
+    fd = (oracle.affine_swish(v + h, a, b)[0] - oracle.affine_swish(v - h, a, b)[0]) / (2 * h)
+    np.testing.assert_allclose(df, fd, rtol=1e-7, atol=1e-9)
