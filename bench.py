@@ -306,6 +306,25 @@ def main():
                                                                       dev_status=status))
         fused["ffn_module_bwd_ms"] = timed_loop(lambda: B.aqt_ffn_bwd(dyf, fsv, want_db=False, ws=ws_fb))
         fused["ffn_module_shape_MDH"] = [Mf, Df, Hf]
+        # the convolution module of the 12800-token configuration (32 utterances x 400 frames, width 512,
+        # depthwise kernel 32; int4 then int8 pointwise weights) as one call, and its float middle alone:
+        # depthwise convolution + normalisation + Swish + abs-max in one pass, 8 B/element of HBM traffic
+        Bc, Tc, kwc = 32, 400, 32
+        wdw = torch.randn((kwc, Df), device="cuda", generator=gen) / kwc ** 0.5
+        wp1 = torch.randn((Df, 2 * Df), device="cuda", generator=gen) / Df ** 0.5
+        wp2 = torch.randn((Df, Df), device="cuda", generator=gen) / Df ** 0.5
+        csv = B.ConvSaved(Bc, Tc, Df, ((4, 8), (8, 8)))
+        ws_cf = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_CONV_MODULE_FWD, Mf, Df, kwc))
+        ws_cb = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_CONV_MODULE_BWD, Mf, Df, kwc))
+        fused["conv_module_fwd_ms"] = timed_loop(lambda: B.aqt_conv_module_fwd(
+            xf, wp1, None, wdw, None, wp2, None, csv, pad_left=15, y=yf, ws=ws_cf, dev_status=status))
+        fused["conv_module_bwd_ms"] = timed_loop(lambda: B.aqt_conv_module_bwd(dyf, csv, wdw, pad_left=15, ws=ws_cb))
+        g3 = csv.g.view(Bc, Tc, Df)
+        dw_ms = timed_loop(lambda: B.aqt_depthwise_conv_fwd(g3, wdw, pad_left=15, swish=True, want_absmax=True))
+        fused["depthwise_swish_absmax_fwd_ms"] = dw_ms
+        fused["depthwise_fwd_hbm_frac_8B_per_elem"] = 8.0 * Mf * Df / dw_ms / 1e6 / PEAK_HBM_GBS
+        fused["conv_module_shape_BTDk"] = [Bc, Tc, Df, kwc]
+        del wdw, wp1, wp2, csv, ws_cf, ws_cb, g3
         # native integer product against its float32 emulation ("fake" quantization's arithmetic, Sec. 1) on
         # the 2048 -> 512 layer of the training step: same codes, int8 matrix cores vs float32 matrix cores
         L2 = layers[1]

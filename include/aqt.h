@@ -68,6 +68,9 @@ typedef int aqt_status;
 #define AQT_OP_LAYERNORM_QUANTIZE 7    /* M rows; K = row length; N unused                     */
 #define AQT_OP_FFN_FWD 8               /* M tokens, K = model width D, N = inner width H       */
 #define AQT_OP_FFN_BWD 9
+#define AQT_OP_DEPTHWISE_CONV_BWD 10   /* M = B * T tokens, K = channels C, N = kernel size kw  */
+#define AQT_OP_CONV_MODULE_FWD 11      /* M = B * T tokens, K = model width D, N = kernel size  */
+#define AQT_OP_CONV_MODULE_BWD 12
 
 /* What the forward keeps for the backward.  All caller-owned device buffers. */
 typedef struct aqt_saved {
@@ -372,6 +375,72 @@ aqt_status aqt_ffn_fwd(const float *x, const float *ln_gamma, const float *ln_be
 aqt_status aqt_ffn_bwd(const float *dy, const aqt_ffn_saved *saved, int64_t M, int64_t D, int64_t H,
                        const aqt_dense_policy *policy, float *dxn, float *dw1, float *db1, float *dw2,
                        float *db2, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Depthwise convolution along time, the float layer between the two pointwise convolutions
+ * of the Conformer convolution module (Sec. 3.2: kernel size 32; Sec. 3.3: causal, kernel
+ * size 15; convolution kernels stay unquantized), with what follows it fused in:
+ *   v[b,t,c]   = bias[c] + sum_j w[j,c] * x[b, t + j - pad_left, c]     (frames outside [0,T) are zero)
+ *   n          = v * norm_scale[c] + norm_shift[c]        (the normalisation with fixed statistics)
+ *   out        = swish ? n * sigmoid(n) : n
+ * x, out [B,T,C] (B utterances of T frames, C contiguous); w [kw,C]; bias, norm_scale,
+ * norm_shift nullable [C]; 0 <= pad_left < kw (kw - 1: causal).  dfac nullable [B,T,C]:
+ * d out / d v, what the backward needs.  out_absmax nullable device float: max|out|, cleared
+ * by the call, for aqt_quantize_with_absmax in front of the next quantized layer.
+ */
+aqt_status aqt_depthwise_conv_fwd(const float *x, int64_t B, int64_t T, int64_t C, const float *w, const float *bias,
+                                  int kw, int pad_left, const float *norm_scale, const float *norm_shift, int swish,
+                                  float *out, float *dfac, float *out_absmax, void *stream);
+
+/*
+ * Gradients of aqt_depthwise_conv_fwd for the upstream gradient dout [B,T,C]; with
+ * dv = dout * dfac (dfac nullable: dv = dout):
+ *   dx[b,u,c] = sum_j w[j,c] * dv[b, u - j + pad_left, c];   dw[j,c] = sum_{b,t} dv[b,t,c] * x[b, t + j - pad_left, c];
+ *   dbias[c]  = sum_{b,t} dv[b,t,c].
+ * Any of dx, dw, dbias may be NULL (x is only read for dw).  The sums over tokens are folded
+ * in a fixed order.  Workspace: aqt_workspace_bytes(AQT_OP_DEPTHWISE_CONV_BWD, B*T, C, kw, ., .)
+ * for dw / dbias.  Gradients of norm_scale / norm_shift are not produced.
+ */
+aqt_status aqt_depthwise_conv_bwd(const float *dout, const float *dfac, const float *x, const float *w, int64_t B,
+                                  int64_t T, int64_t C, int kw, int pad_left, float *dx, float *dw, float *dbias,
+                                  void *ws, size_t ws_bytes, void *stream);
+
+/* What the convolution module keeps for its backward.  Caller-owned device buffers. */
+typedef struct aqt_conv_saved {
+  aqt_saved pw1;    /* first pointwise convolution [M,D] x [D,2D] with GLU; pw1.dact [M,2D] for the backward */
+  aqt_saved pw2;    /* second pointwise convolution [M,D] x [D,D]                                            */
+  float *g;         /* [M,D] output of the GLU = input of the depthwise convolution                          */
+  float *s;         /* [M,D] after depthwise convolution, normalisation and Swish                            */
+  float *dfac;      /* nullable [M,D]: d s / d (depthwise result), needed by aqt_conv_module_bwd            */
+  float *row_stats; /* nullable [M,2]: mean and reciprocal standard deviation of every input row             */
+} aqt_conv_saved;
+
+/*
+ * The Conformer convolution module (Sec. 3.2) as one call, M = B * T tokens of width D:
+ *   xn = layernorm(x);  g = glu(dense(xn, w1) + b1);  s = swish(norm(depthwise(g)));  y = dense(s, w2) + b2
+ * The pointwise convolutions are quantized dense layers at policy[0] / policy[1] (integer
+ * activations only); the depthwise convolution and the normalisation behind it stay float32
+ * (Sec. 3.3).  Fused as in aqt_ffn_fwd: normalisation with the first quantizer, and the
+ * depthwise kernel emits max|s| so the second quantizer runs in one pass.
+ *   w1 [D,2D] (value columns first, gate columns second), b1 nullable [2D]; w_dw [kw,D], b_dw,
+ *   norm_scale, norm_shift nullable [D]; w2 [D,D], b2 nullable [D]; y [M,D].
+ */
+aqt_status aqt_conv_module_fwd(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps,
+                               const float *w1, const float *b1, const float *w_dw, const float *b_dw,
+                               const float *norm_scale, const float *norm_shift, const float *w2, const float *b2,
+                               int64_t B, int64_t T, int64_t D, int kw, int pad_left, const aqt_dense_policy *policy,
+                               float *y, const aqt_conv_saved *saved, void *ws, size_t ws_bytes, void *stream,
+                               int32_t *dev_status);
+
+/*
+ * Straight-through backward of aqt_conv_module_fwd down to the normalised input:
+ *   dxn [M,D], dw1 [D,2D], db1 [2D], dw_dw [kw,D], db_dw [D], dw2 [D,D], db2 [D]; any may be NULL.
+ * The normalisation's own backward is left to the caller.
+ */
+aqt_status aqt_conv_module_bwd(const float *dy, const aqt_conv_saved *saved, const float *w_dw, int64_t B, int64_t T,
+                               int64_t D, int kw, int pad_left, const aqt_dense_policy *policy, float *dxn,
+                               float *dw1, float *db1, float *dw_dw, float *db_dw, float *dw2, float *db2, void *ws,
+                               size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -20,7 +20,8 @@ AQT_OK, AQT_ERR_INVALID_ARG, AQT_ERR_UNSUPPORTED, AQT_ERR_WORKSPACE, AQT_ERR_HIP
 AQT_AXIS_ALL, AQT_AXIS_ROWS, AQT_AXIS_COLS = -1, 0, 1
 AQT_EPI_NONE, AQT_EPI_SWISH, AQT_EPI_GLU = 0, 1, 2
 (AQT_OP_QUANTIZE, AQT_OP_QUANTIZE_WEIGHTS, AQT_OP_DENSE_FWD, AQT_OP_DENSE_FWD_Q, AQT_OP_DENSE_BWD,
- AQT_OP_DENSE_FWD_WONLY, AQT_OP_DENSE_BWD_EPI, AQT_OP_LAYERNORM_QUANTIZE, AQT_OP_FFN_FWD, AQT_OP_FFN_BWD) = range(10)
+ AQT_OP_DENSE_FWD_WONLY, AQT_OP_DENSE_BWD_EPI, AQT_OP_LAYERNORM_QUANTIZE, AQT_OP_FFN_FWD, AQT_OP_FFN_BWD,
+ AQT_OP_DEPTHWISE_CONV_BWD, AQT_OP_CONV_MODULE_FWD, AQT_OP_CONV_MODULE_BWD) = range(13)
 AQT_POLICY_ALL, AQT_POLICY_EXCEPT_FIRST_LAST, AQT_POLICY_EXCEPT_ATTENTION, AQT_POLICY_FIRST_K = range(4)
 
 # every symbol include/aqt.h declares
@@ -30,7 +31,8 @@ SYMBOLS = ["aqt_status_string", "aqt_last_hip_error", "aqt_version", "aqt_worksp
            "aqt_dense_fwd_wonly", "aqt_dense_fwd", "aqt_dense_bwd", "aqt_dense_fwd_q_static",
            "aqt_static_scratch_bytes", "aqt_layernorm_quantize", "aqt_fake_matmul_f32", "aqt_policy_preset",
            "aqt_policy_weight_bytes", "aqt_ffn_fwd", "aqt_ffn_bwd", "aqt_prepared_weight_bytes",
-           "aqt_prepare_weights", "aqt_dense_fwd_q_prepared"]
+           "aqt_prepare_weights", "aqt_dense_fwd_q_prepared", "aqt_depthwise_conv_fwd", "aqt_depthwise_conv_bwd",
+           "aqt_conv_module_fwd", "aqt_conv_module_bwd"]
 
 
 class AqtError(RuntimeError):
@@ -60,6 +62,11 @@ class aqt_layer_policy(ctypes.Structure):
 class aqt_ffn_saved(ctypes.Structure):
     _fields_ = [("l1", aqt_saved), ("l2", aqt_saved), ("h", ctypes.c_void_p), ("xn", ctypes.c_void_p),
                 ("row_stats", ctypes.c_void_p)]
+
+
+class aqt_conv_saved(ctypes.Structure):
+    _fields_ = [("pw1", aqt_saved), ("pw2", aqt_saved), ("g", ctypes.c_void_p), ("s", ctypes.c_void_p),
+                ("dfac", ctypes.c_void_p), ("row_stats", ctypes.c_void_p)]
 
 
 _lib = None
@@ -113,6 +120,16 @@ def lib() -> ctypes.CDLL:
                                   _vp, _vp]
         L.aqt_ffn_bwd.argtypes = [_vp, ctypes.POINTER(aqt_ffn_saved), _i64, _i64, _i64,
                                   ctypes.POINTER(aqt_dense_policy), _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+        L.aqt_depthwise_conv_fwd.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _int, _int, _vp, _vp, _int, _vp, _vp,
+                                             _vp, _vp]
+        L.aqt_depthwise_conv_bwd.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp,
+                                             _sz, _vp]
+        L.aqt_conv_module_fwd.argtypes = [_vp, _vp, _vp, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+                                          _i64, _i64, _i64, _int, _int, ctypes.POINTER(aqt_dense_policy), _vp,
+                                          ctypes.POINTER(aqt_conv_saved), _vp, _sz, _vp, _vp]
+        L.aqt_conv_module_bwd.argtypes = [_vp, ctypes.POINTER(aqt_conv_saved), _vp, _i64, _i64, _i64, _int, _int,
+                                          ctypes.POINTER(aqt_dense_policy), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+                                          _sz, _vp]
         for name in SYMBOLS:
             getattr(L, name)  # AttributeError if the library lacks a declared entry point
         _lib = L
@@ -471,3 +488,88 @@ def aqt_ffn_bwd(dy, saved: FfnSaved, *, want_db=True, ws=None):
                            _ptr(dw2), _ptr(db2), _ptr(ws), ws.numel(), _stream())
     _check(st, "aqt_ffn_bwd")
     return dxn, dw1, db1, dw2, db2
+
+
+def aqt_depthwise_conv_fwd(x, w, *, bias=None, pad_left: int = 0, norm_scale=None, norm_shift=None, swish=False,
+                           want_dfac=False, want_absmax=False):
+    """aqt_depthwise_conv_fwd: x [B,T,C], w [kw,C]; returns (out, dfac or None, absmax word or None)."""
+    _dev(x, torch.float32, "x")
+    _dev(w, torch.float32, "w")
+    B, T, C = x.shape
+    kw = w.shape[0]
+    out = torch.empty_like(x)
+    dfac = torch.empty_like(x) if want_dfac else None
+    m = torch.empty(1, dtype=torch.float32, device=x.device) if want_absmax else None
+    st = lib().aqt_depthwise_conv_fwd(_ptr(x), B, T, C, _ptr(w), _ptr(bias), kw, pad_left, _ptr(norm_scale),
+                                      _ptr(norm_shift), int(bool(swish)), _ptr(out), _ptr(dfac), _ptr(m), _stream())
+    _check(st, "aqt_depthwise_conv_fwd")
+    return out, dfac, m
+
+
+def aqt_depthwise_conv_bwd(dout, x, w, *, dfac=None, pad_left: int = 0, want_dx=True, want_dw=True,
+                           want_dbias=True, ws=None):
+    """aqt_depthwise_conv_bwd: returns (dx [B,T,C], dw [kw,C], dbias [C]); skipped outputs are None."""
+    _dev(dout, torch.float32, "dout")
+    B, T, C = dout.shape
+    kw = w.shape[0]
+    dev = dout.device
+    dx = torch.empty_like(dout) if want_dx else None
+    dw = torch.empty((kw, C), dtype=torch.float32, device=dev) if want_dw else None
+    db = torch.empty(C, dtype=torch.float32, device=dev) if want_dbias else None
+    ws = workspace(aqt_workspace_bytes(AQT_OP_DEPTHWISE_CONV_BWD, B * T, C, kw), dev) if ws is None else ws
+    st = lib().aqt_depthwise_conv_bwd(_ptr(dout), _ptr(dfac), _ptr(x), _ptr(w), B, T, C, kw, pad_left, _ptr(dx),
+                                      _ptr(dw), _ptr(db), _ptr(ws), ws.numel(), _stream())
+    _check(st, "aqt_depthwise_conv_bwd")
+    return dx, dw, db
+
+
+class ConvSaved:
+    """Device buffers of the convolution module (aqt_conv_module_fwd / _bwd) and their aqt_conv_saved view."""
+
+    def __init__(self, B: int, T: int, D: int, policy, device="cuda"):
+        (bw1, bx1), (bw2, bx2) = policy
+        M = B * T
+        self.B, self.T, self.D, self.M = B, T, D, M
+        self.pw1 = Saved(M, D, 2 * D, bw1, device, dact=True)
+        self.pw2 = Saved(M, D, D, bw2, device)
+        self.g = torch.empty((M, D), dtype=torch.float32, device=device)
+        self.s = torch.empty((M, D), dtype=torch.float32, device=device)
+        self.dfac = torch.empty((M, D), dtype=torch.float32, device=device)
+        self.row_stats = torch.empty((M, 2), dtype=torch.float32, device=device)
+        self.policy = (aqt_dense_policy * 2)(aqt_dense_policy(bw1, bx1), aqt_dense_policy(bw2, bx2))
+        self.c = aqt_conv_saved(self.pw1.c, self.pw2.c, self.g.data_ptr(), self.s.data_ptr(), self.dfac.data_ptr(),
+                                self.row_stats.data_ptr())
+
+
+def aqt_conv_module_fwd(x, w1, b1, w_dw, b_dw, w2, b2, saved: ConvSaved, *, pad_left: int, gamma=None, beta=None,
+                        eps: float = 1e-6, norm_scale=None, norm_shift=None, y=None, ws=None, dev_status=None):
+    """aqt_conv_module_fwd: layernorm, pointwise + GLU, depthwise + normalisation + Swish, pointwise.  x [B*T,D]."""
+    _dev(x, torch.float32, "x")
+    M, D = x.shape
+    kw = w_dw.shape[0]
+    y = torch.empty((M, D), dtype=torch.float32, device=x.device) if y is None else y
+    ws = workspace(aqt_workspace_bytes(AQT_OP_CONV_MODULE_FWD, M, D, kw), x.device) if ws is None else ws
+    st = lib().aqt_conv_module_fwd(_ptr(x), _ptr(gamma), _ptr(beta), eps, _ptr(w1), _ptr(b1), _ptr(w_dw), _ptr(b_dw),
+                                   _ptr(norm_scale), _ptr(norm_shift), _ptr(w2), _ptr(b2), saved.B, saved.T, D, kw,
+                                   pad_left, saved.policy, _ptr(y), ctypes.byref(saved.c), _ptr(ws), ws.numel(),
+                                   _stream(), _ptr(dev_status))
+    _check(st, "aqt_conv_module_fwd")
+    return y
+
+
+def aqt_conv_module_bwd(dy, saved: ConvSaved, w_dw, *, pad_left: int, ws=None):
+    """aqt_conv_module_bwd: returns dict(dxn, dw1, db1, dw_dw, db_dw, dw2, db2)."""
+    _dev(dy, torch.float32, "dy")
+    M, D = saved.M, saved.D
+    kw = w_dw.shape[0]
+    dev = dy.device
+    f32 = dict(dtype=torch.float32, device=dev)
+    o = dict(dxn=torch.empty((M, D), **f32), dw1=torch.empty((D, 2 * D), **f32), db1=torch.empty(2 * D, **f32),
+             dw_dw=torch.empty((kw, D), **f32), db_dw=torch.empty(D, **f32), dw2=torch.empty((D, D), **f32),
+             db2=torch.empty(D, **f32))
+    ws = workspace(aqt_workspace_bytes(AQT_OP_CONV_MODULE_BWD, M, D, kw), dev) if ws is None else ws
+    st = lib().aqt_conv_module_bwd(_ptr(dy), ctypes.byref(saved.c), _ptr(w_dw), saved.B, saved.T, D, kw, pad_left,
+                                   saved.policy, _ptr(o["dxn"]), _ptr(o["dw1"]), _ptr(o["db1"]), _ptr(o["dw_dw"]),
+                                   _ptr(o["db_dw"]), _ptr(o["dw2"]), _ptr(o["db2"]), _ptr(ws), ws.numel(), _stream())
+    _check(st, "aqt_conv_module_bwd")
+    return o

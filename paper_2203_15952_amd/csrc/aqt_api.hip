@@ -77,6 +77,41 @@ size_t ffn_bwd_ws(int64_t M, int64_t D, int64_t H) {
   return (a > b ? a : b) + align_up(static_cast<size_t>(M) * H * sizeof(float), 256);
 }
 
+// Backward of the convolution module: one dense-backward workspace large enough for either
+// pointwise layer, then the gradients with respect to s and g [M,D] each, the gradient in front
+// of the GLU [M,2D], and the partial sums of the depthwise taps.
+struct ConvBwdWorkspace {
+  size_t core;
+  float *ds, *dg, *dv;
+  void *taps;
+  size_t total;
+};
+
+ConvBwdWorkspace carve_conv_bwd(void *ws, int64_t B, int64_t T, int64_t D, int kw) {
+  ConvBwdWorkspace f;
+  const int64_t M = B * T;
+  const size_t a = bwd_workspace_bytes(M, D, 2 * D), b = bwd_workspace_bytes(M, D, D);
+  f.core = a > b ? a : b;
+  size_t off = f.core;
+  auto take = [&](size_t bytes) {
+    uint8_t *p = ws ? static_cast<uint8_t *>(ws) + off : nullptr;
+    off += align_up(bytes, 256);
+    return p;
+  };
+  const size_t md = static_cast<size_t>(M) * D * sizeof(float);
+  f.ds = reinterpret_cast<float *>(take(md));
+  f.dg = reinterpret_cast<float *>(take(md));
+  f.dv = reinterpret_cast<float *>(take(2 * md));
+  f.taps = take(dwconv_bwd_ws_bytes(D, kw));
+  f.total = off;
+  return f;
+}
+
+bool conv_shape_ok(int64_t B, int64_t T, int64_t C, int kw, int pad_left) {
+  return B >= 1 && T >= 1 && C >= 1 && kw >= 1 && kw <= 4096 && pad_left >= 0 && pad_left < kw &&
+         B <= (int64_t(1) << 40) / T;
+}
+
 bool policy_ok(const aqt_dense_policy &p) { return bits_ok(p.bits_w) && (p.bits_x == 0 || bits_ok(p.bits_x)); }
 
 // The int32 accumulator must hold K * qmax_x * qmax_w; packed (<= 4 bit) weights enter the
@@ -138,6 +173,15 @@ size_t aqt_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int bits_x, 
     case AQT_OP_FFN_BWD:
       if (!shape_ok(M, K) || N < 1) return 0;
       return ffn_bwd_ws(M, K, N);
+    case AQT_OP_DEPTHWISE_CONV_BWD:
+      if (!shape_ok(M, K) || N < 1 || N > 4096) return 0;
+      return dwconv_bwd_ws_bytes(K, static_cast<int>(N));
+    case AQT_OP_CONV_MODULE_FWD:
+      if (!shape_ok(M, K) || N < 1) return 0;
+      return carve_ffn_fwd(nullptr, M, K, 2 * K).total;
+    case AQT_OP_CONV_MODULE_BWD:
+      if (!shape_ok(M, K) || N < 1 || N > 4096) return 0;
+      return carve_conv_bwd(nullptr, 1, M, K, static_cast<int>(N)).total;
     default: return 0;
   }
 }
@@ -457,6 +501,94 @@ aqt_status aqt_ffn_bwd(const float *dy, const aqt_ffn_saved *saved, int64_t M, i
   // through the Swish, in place, then the first layer
   AQT_TRY(launch_dact_mul(dh, l1.dact, M, H, H, dh, st));
   return launch_dense_bwd(dh, &l1, M, D, H, dxn, dw1, db1, ws, core, st);
+}
+
+aqt_status aqt_depthwise_conv_fwd(const float *x, int64_t B, int64_t T, int64_t C, const float *w, const float *bias,
+                                  int kw, int pad_left, const float *norm_scale, const float *norm_shift, int swish,
+                                  float *out, float *dfac, float *out_absmax, void *stream) {
+  if (!x || !w || !out || !conv_shape_ok(B, T, C, kw, pad_left)) return AQT_ERR_INVALID_ARG;
+  return launch_dwconv_fwd(x, w, bias, norm_scale, norm_shift, swish ? 1 : 0, B, T, C, kw, pad_left, out, dfac,
+                           reinterpret_cast<uint32_t *>(out_absmax), static_cast<hipStream_t>(stream));
+}
+
+aqt_status aqt_depthwise_conv_bwd(const float *dout, const float *dfac, const float *x, const float *w, int64_t B,
+                                  int64_t T, int64_t C, int kw, int pad_left, float *dx, float *dw, float *dbias,
+                                  void *ws, size_t ws_bytes, void *stream) {
+  if (!dout || !conv_shape_ok(B, T, C, kw, pad_left)) return AQT_ERR_INVALID_ARG;
+  if ((dx && !w) || (dw && !x)) return AQT_ERR_INVALID_ARG;
+  if ((dw || dbias) && (!ws || ws_bytes < dwconv_bwd_ws_bytes(C, kw))) return AQT_ERR_WORKSPACE;
+  // the bias sum rides with the tap sums and reads x only for the taps; give it a valid pointer
+  return launch_dwconv_bwd(dout, dfac, x ? x : dout, w, B, T, C, kw, pad_left, dx, dw, dbias, ws,
+                           static_cast<hipStream_t>(stream));
+}
+
+aqt_status aqt_conv_module_fwd(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps,
+                               const float *w1, const float *b1, const float *w_dw, const float *b_dw,
+                               const float *norm_scale, const float *norm_shift, const float *w2, const float *b2,
+                               int64_t B, int64_t T, int64_t D, int kw, int pad_left, const aqt_dense_policy *policy,
+                               float *y, const aqt_conv_saved *saved, void *ws, size_t ws_bytes, void *stream,
+                               int32_t *dev_status) {
+  if (!x || !w1 || !w_dw || !w2 || !y || !policy || !saved || !conv_shape_ok(B, T, D, kw, pad_left) ||
+      !(ln_eps >= 0.0f))
+    return AQT_ERR_INVALID_ARG;
+  const aqt_dense_policy p1 = policy[0], p2 = policy[1];
+  if (!policy_ok(p1) || !policy_ok(p2) || p1.bits_x == 0 || p2.bits_x == 0) return AQT_ERR_UNSUPPORTED;
+  const aqt_saved &l1 = saved->pw1, &l2 = saved->pw2;
+  if (!saved->g || !saved->s || !l1.xq || !l1.s_x || !l1.wq_packed || !l1.s_w || !l2.xq || !l2.s_x ||
+      !l2.wq_packed || !l2.s_w)
+    return AQT_ERR_INVALID_ARG;
+  if (!acc_fits(D, p1.bits_x, p1.bits_w) || !acc_fits(D, p2.bits_x, p2.bits_w)) return AQT_ERR_UNSUPPORTED;
+  const int64_t M = B * T;
+  FfnWorkspace f = carve_ffn_fwd(ws, M, D, 2 * D);
+  if (!ws || ws_bytes < f.total) return AQT_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  // normalisation + first quantizer, first pointwise convolution with the GLU
+  const bool frag1 = fwd_q_takes_fragments(M, D, 2 * D, AQT_EPI_GLU) && reinterpret_cast<uintptr_t>(l1.xq) % 16 == 0;
+  const bool frag2 = fwd_q_takes_fragments(M, D, D, AQT_EPI_NONE) && reinterpret_cast<uintptr_t>(l2.xq) % 16 == 0;
+  AQT_TRY(launch_quantize_weights(w1, D, 2 * D, p1.bits_w, l1.wq_packed, l1.s_w, l1.wq_kn, l1.mask_w, f.wpart1, st,
+                                  dev_status, frag1 ? f.wfrag1 : nullptr));
+  AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, nullptr,
+                                    saved->row_stats, f.ln, st, dev_status));
+  AQT_TRY(launch_dense_fwd_q(l1.xq, l1.s_x, l1.wq_packed, l1.s_w, M, D, 2 * D, p1.bits_w, b1, AQT_EPI_GLU, saved->g,
+                             nullptr, nullptr, f.wfrag1, st, l1.dact, frag1));
+  // depthwise convolution, normalisation, Swish; max|s| for the one-pass quantizer
+  AQT_TRY(launch_dwconv_fwd(saved->g, w_dw, b_dw, norm_scale, norm_shift, 1, B, T, D, kw, pad_left, saved->s,
+                            saved->dfac, reinterpret_cast<uint32_t *>(f.h_absmax), st));
+  // second pointwise convolution
+  AQT_TRY(launch_quantize_weights(w2, D, D, p2.bits_w, l2.wq_packed, l2.s_w, l2.wq_kn, l2.mask_w, f.wpart2, st,
+                                  dev_status, frag2 ? f.wfrag2 : nullptr));
+  AQT_TRY(launch_quantize_with_absmax(saved->s, M, D, D, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),
+                                      l2.xq, l2.s_x, l2.mask_x, st, dev_status));
+  return launch_dense_fwd_q(l2.xq, l2.s_x, l2.wq_packed, l2.s_w, M, D, D, p2.bits_w, b2, AQT_EPI_NONE, y, nullptr,
+                            nullptr, f.wfrag2, st, nullptr, frag2);
+}
+
+aqt_status aqt_conv_module_bwd(const float *dy, const aqt_conv_saved *saved, const float *w_dw, int64_t B, int64_t T,
+                               int64_t D, int kw, int pad_left, const aqt_dense_policy *policy, float *dxn,
+                               float *dw1, float *db1, float *dw_dw, float *db_dw, float *dw2, float *db2, void *ws,
+                               size_t ws_bytes, void *stream) {
+  if (!dy || !saved || !w_dw || !policy || !conv_shape_ok(B, T, D, kw, pad_left)) return AQT_ERR_INVALID_ARG;
+  if (!policy_ok(policy[0]) || !policy_ok(policy[1])) return AQT_ERR_UNSUPPORTED;
+  if (policy[0].bits_x == 0 || policy[1].bits_x == 0) return AQT_ERR_UNSUPPORTED;
+  const aqt_saved &l1 = saved->pw1, &l2 = saved->pw2;
+  if (!l1.s_x || !l1.s_w || !l2.s_x || !l2.s_w || !l2.wq_kn || !l1.dact || !saved->dfac || !saved->g)
+    return AQT_ERR_INVALID_ARG;
+  if ((dxn && !l1.wq_kn) || (dw1 && !l1.xq) || (dw2 && !l2.xq)) return AQT_ERR_INVALID_ARG;
+  const int64_t M = B * T;
+  ConvBwdWorkspace f = carve_conv_bwd(ws, B, T, D, kw);
+  if (!ws || ws_bytes < f.total) return AQT_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // second pointwise convolution: gradient with respect to s, dw2, db2
+  AQT_TRY(launch_dense_bwd(dy, &l2, M, D, D, f.ds, dw2, db2, ws, f.core, st));
+  // through Swish and normalisation (dfac), then the depthwise convolution
+  const bool more = dxn || dw1 || db1;
+  AQT_TRY(launch_dwconv_bwd(f.ds, saved->dfac, saved->g, w_dw, B, T, D, kw, pad_left, more ? f.dg : nullptr, dw_dw,
+                            db_dw, f.taps, st));
+  if (!more) return AQT_OK;
+  // through the GLU, then the first pointwise convolution
+  AQT_TRY(launch_dact_mul(f.dg, l1.dact, M, 2 * D, D, f.dv, st));
+  return launch_dense_bwd(f.dv, &l1, M, D, 2 * D, dxn, dw1, db1, ws, f.core, st);
 }
 
 }  // extern "C"

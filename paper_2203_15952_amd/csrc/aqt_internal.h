@@ -109,4 +109,13 @@ aqt_status launch_dact_mul(const float *dout, const float *dact, int64_t M, int6
 aqt_status launch_fake_matmul_f32(const int8_t *xq, const int8_t *wq_kn, int64_t M, int64_t K, int64_t N, float *out,
                                   hipStream_t st);
 
+// ---- depthwise convolution of the convolution module (conv.hip) ---------------------------
+size_t dwconv_bwd_ws_bytes(int64_t C, int kw);
+aqt_status launch_dwconv_fwd(const float *x, const float *w, const float *bias, const float *na, const float *nb,
+                             int swish, int64_t B, int64_t T, int64_t C, int kw, int pad_left, float *out, float *dfac,
+                             uint32_t *absmax, hipStream_t st);
+aqt_status launch_dwconv_bwd(const float *dout, const float *dmul, const float *x, const float *w, int64_t B, int64_t T,
+                             int64_t C, int kw, int pad_left, float *dx, float *dw, float *dbias, void *ws,
+                             hipStream_t st);
+
 }  // namespace aqt

@@ -1,0 +1,35 @@
+"""The depthwise-convolution kernels run on the host, thread by thread, under the address and
+undefined-behaviour sanitizers: every global and LDS access of every launch geometry the GPU tests use is
+checked against exactly sized buffers, and the results against float64 loops in the driver.  The kernels'
+source is taken as it is (HIP headers replaced by a small vocabulary header, launchers cut off)."""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(ROOT, "paper_2203_15952_amd", "csrc")
+
+
+def spliced_source():
+    src = open(os.path.join(CSRC, "conv.hip")).read()
+    epi = open(os.path.join(CSRC, "epilogue.h")).read()
+    epi = epi.replace("#include <hip/hip_runtime.h>", "").replace("#pragma once", "")
+    assert '#include "aqt_internal.h"' in src and '#include "epilogue.h"' in src
+    src = src.replace('#include "aqt_internal.h"', '#include "hip_on_host.h"').replace('#include "epilogue.h"', epi)
+    assert src.count("extern __shared__ float lds[];") == 2
+    src = src.replace("extern __shared__ float lds[];", "AQT_EXTERN_LDS(lds);")
+    src = src[:src.index("aqt_status launch_corr")]          # kernels and geometry helpers only
+    return src + open(os.path.join(HERE, "host_emulation", "conv_driver.cpp")).read()
+
+
+def test_conv_kernels_in_bounds_and_correct_on_host(tmp_path):
+    cpp = tmp_path / "conv_on_host.cpp"
+    cpp.write_text(spliced_source())
+    exe = tmp_path / "conv_on_host"
+    cmd = ["g++", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-static-libasan",
+           "-static-libubsan", "-std=c++20", "-pthread", "-I", os.path.join(HERE, "host_emulation"), str(cpp), "-o", str(exe)]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-3000:]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0")
+    r = subprocess.run([str(exe)], capture_output=True, text=True, env=env, timeout=600)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), (r.stdout[-2000:], r.stderr[-3000:])
