@@ -346,3 +346,19 @@ def affine_swish(v, a=None, b=None):
     out, df = np.empty((M, C), np.float64), np.empty((M, C), np.float64)
     _c().oracle_affine_swish(_p(v), ctypes.c_int64(M), ctypes.c_int64(C), _p(aa), _p(bb), _p(out), _p(df))
     return out, df
+
+
+def attention(qkv, heads: int, left: int = -1, right: int = -1, want_mags: bool = False):
+    """Scaled dot-product self-attention per utterance and head over the frames t - left .. t + right
+    (negative: unlimited), float64.  qkv [B,T,3D] -> ctx [B,T,D] (and the magnitudes the error bounds use)."""
+    qkv = _f32(qkv)
+    B, T, D3 = qkv.shape
+    D = D3 // 3
+    ctx = np.empty((B, T, D), np.float64)
+    smag = np.empty((B, T, heads), np.float64) if want_mags else None
+    vmag = np.empty((B, T, D), np.float64) if want_mags else None
+    rc = _c().oracle_attention(_p(qkv), ctypes.c_int64(B), ctypes.c_int64(T), ctypes.c_int64(D), ctypes.c_int64(heads),
+                               ctypes.c_int64(left), ctypes.c_int64(right), _p(ctx), _p(smag), _p(vmag))
+    if rc:
+        raise ValueError(f"oracle_attention rc={rc}")
+    return (ctx, smag, vmag) if want_mags else ctx

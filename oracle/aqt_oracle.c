@@ -36,6 +36,10 @@
  *                         Sec. 3.3: causal kernel 15, convolution kernels stay
  *                         float): the plain definitions and their adjoints, float64;
  *                         glue of the chained block.
+ *   oracle_attention      scaled dot-product attention with softmax over a window of
+ *                         frames, the float core of the self-attention module
+ *                         (Sec. 3.2: heads; Sec. 3.3: left / right context): the
+ *                         textbook definition in float64; glue of the chained block.
  *   oracle_fake_matmul_f32  Sec. 1 / Sec. 2.2: "fake" quantization carries the integer
  *                         codes in float32 and multiplies them with float
  *                         operations; sums that need more than 24 bits are rounded.
@@ -63,7 +67,8 @@
  * not; the depthwise convolution by its impulse response, a hand-worked causal
  * example, numpy's correlate per channel, the adjoint identity and central
  * differences for its gradients; the affine + Swish by closed-form values and
- * central differences).  The paper prints
+ * central differences; the attention by zero queries (window means), a one-hot
+ * alignment, constant values, the zero-width window and scipy's softmax).  The paper prints
  * no worked numeric example, so no pin comes from printed values.
  */
 #include <math.h>
@@ -599,6 +604,65 @@ void oracle_affine_swish(const double *v, int64_t M, int64_t C, const float *a, 
       if (out) out[m * C + c] = n * s;
       if (dfac) dfac[m * C + c] = ac * s * (1.0 + n * (1.0 - s));
     }
+}
+
+/*
+ * Scaled dot-product self-attention over each utterance, the float core between the
+ * quantized projections of the Conformer's self-attention module (Sec. 3.2: 4 or 8 heads;
+ * Sec. 3.3: a limited left context and, in the non-causal encoder, a limited right context).
+ * qkv [B,T,3D] holds queries, keys and values in three column blocks of width D, head h in
+ * columns h*dh .. (h+1)*dh of each block, dh = D / heads.  For query frame t of utterance b
+ * and head h, over the key frames j of the same utterance with t - left <= j <= t + right
+ * (left / right < 0: no limit on that side):
+ *   s_j = (q_t . k_j) / sqrt(dh);  p = softmax_j(s);  ctx[b,t,h*dh + d] = sum_j p_j v_j[d]
+ * float64.  smag [B,T,heads] (nullable): the largest sum_d |q_d k_jd| / sqrt(dh) over the window;
+ * vmag [B,T,D] (nullable): sum_j p_j |v_j[d]|; both only feed error bounds.
+ */
+int oracle_attention(const float *qkv, int64_t B, int64_t T, int64_t D, int64_t heads, int64_t left,
+                     int64_t right, double *ctx, double *smag, double *vmag) {
+  if (heads < 1 || D % heads) return 2;
+  const int64_t dh = D / heads;
+  const double scale = 1.0 / sqrt((double)dh);
+#pragma omp parallel for schedule(static)
+  for (int64_t bt = 0; bt < B * T; ++bt) {
+    const int64_t b = bt / T, t = bt % T;
+    const int64_t j0 = (left < 0 || t - left < 0) ? 0 : t - left;
+    const int64_t j1 = (right < 0 || t + right > T - 1) ? T - 1 : t + right;
+    double *s = (double *)malloc((size_t)(j1 - j0 + 1) * sizeof(double));
+    for (int64_t h = 0; h < heads; ++h) {
+      const float *q = qkv + bt * 3 * D + h * dh;
+      double mx = -INFINITY, mg = 0.0;
+      for (int64_t j = j0; j <= j1; ++j) {
+        const float *k = qkv + (b * T + j) * 3 * D + D + h * dh;
+        double a = 0.0, ab = 0.0;
+        for (int64_t d = 0; d < dh; ++d) {
+          a += (double)q[d] * (double)k[d];
+          ab += fabs((double)q[d] * (double)k[d]);
+        }
+        s[j - j0] = a * scale;
+        if (s[j - j0] > mx) mx = s[j - j0];
+        if (ab * scale > mg) mg = ab * scale;
+      }
+      double sum = 0.0;
+      for (int64_t j = j0; j <= j1; ++j) {
+        s[j - j0] = exp(s[j - j0] - mx);
+        sum += s[j - j0];
+      }
+      for (int64_t d = 0; d < dh; ++d) {
+        double a = 0.0, ab = 0.0;
+        for (int64_t j = j0; j <= j1; ++j) {
+          const double v = (double)qkv[(b * T + j) * 3 * D + 2 * D + h * dh + d];
+          a += s[j - j0] * v;
+          ab += s[j - j0] * fabs(v);
+        }
+        ctx[bt * D + h * dh + d] = a / sum;
+        if (vmag) vmag[bt * D + h * dh + d] = ab / sum;
+      }
+      if (smag) smag[bt * heads + h] = mg;
+    }
+    free(s);
+  }
+  return 0;
 }
 
 /*

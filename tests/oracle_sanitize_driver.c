@@ -43,6 +43,8 @@ void oracle_depthwise_conv(const float *x, const float *w, const float *bias, in
 void oracle_depthwise_conv_bwd(const double *dout, const float *x, const float *w, int64_t B, int64_t T, int64_t C,
                                int64_t kw, int64_t pad_left, double *dx, double *dw, double *dbias, double *dx_abs,
                                double *dw_abs);
+int oracle_attention(const float *qkv, int64_t B, int64_t T, int64_t D, int64_t heads, int64_t left, int64_t right,
+                     double *ctx, double *smag, double *vmag);
 void oracle_affine_swish(const double *v, int64_t M, int64_t C, const float *a, const float *b, double *out,
                          double *dfac);
 void oracle_dense_fwd_q_sampled(const int8_t *xq, float s_x, const int8_t *wq_kn, const float *s_w, int64_t K,
@@ -185,6 +187,22 @@ static void one_conv(int64_t B, int64_t T, int64_t C, int64_t kw, int64_t pad_le
   free(x); free(w); free(b); free(out); free(ab); free(dx); free(dxa); free(dw); free(dwa); free(db);
 }
 
+/* attention on exactly sized buffers, every kind of window */
+static void one_attention(int64_t B, int64_t T, int64_t D, int64_t heads) {
+  const size_t n = (size_t)(B * T * D);
+  float *qkv = need(3 * n * sizeof(float));
+  double *ctx = need(n * sizeof(double)), *vm = need(n * sizeof(double));
+  double *sm = need((size_t)(B * T * heads) * sizeof(double));
+  for (size_t i = 0; i < 3 * n; ++i) qkv[i] = next_unit();
+  CHECK(oracle_attention(qkv, B, T, D, heads, -1, -1, ctx, sm, vm) == 0);
+  CHECK(oracle_attention(qkv, B, T, D, heads, 0, 0, ctx, NULL, NULL) == 0);
+  CHECK(oracle_attention(qkv, B, T, D, heads, 3, -1, ctx, NULL, vm) == 0);
+  CHECK(oracle_attention(qkv, B, T, D, heads, T + 5, 2, ctx, sm, NULL) == 0);
+  CHECK(oracle_attention(qkv, B, T, D, D + 1, -1, -1, ctx, NULL, NULL) == 2);
+  for (size_t i = 0; i < n; ++i) CHECK(isfinite(ctx[i]));
+  free(qkv); free(ctx); free(vm); free(sm);
+}
+
 int main(void) {
   /* Fig. 2 rounds floor(t + 0.5): with 127 present the scale is exactly 1 */
   const float ties[8] = {127.0f, 0.5f, -0.5f, 1.5f, -1.5f, 2.5f, -2.5f, -127.0f};
@@ -209,6 +227,9 @@ int main(void) {
   one_conv(2, 5, 3, 32, 15);
   one_conv(3, 40, 2, 15, 14);
   one_conv(1, 9, 4, 4, 0);
+  one_attention(1, 1, 1, 1);
+  one_attention(2, 7, 6, 3);
+  one_attention(1, 33, 8, 2);
   printf("oracle sanitizer run ok\n");
   return 0;
 }

@@ -800,3 +800,62 @@ def test_affine_swish_closed_forms_and_central_differences():
     h = 1e-6
     fd = (oracle.affine_swish(v + h, a, b)[0] - oracle.affine_swish(v - h, a, b)[0]) / (2 * h)
     np.testing.assert_allclose(df, fd, rtol=1e-7, atol=1e-9)
+
+
+# ----------------------------------------------------------------------------
+# Self-attention core between the quantized projections (Sec. 3.2 heads, Sec. 3.3 context windows)
+# ----------------------------------------------------------------------------
+def _qkv(rng, B, T, D):
+    return rng.standard_normal((B, T, 3 * D)).astype(F)
+
+
+def test_attention_special_cases_with_known_answers():
+    rng = np.random.default_rng(60)
+    B, T, D, H = 2, 9, 8, 2
+    qkv = _qkv(rng, B, T, D)
+    v = qkv[:, :, 2 * D:].astype(np.float64)
+    # zero queries: every score is 0, the softmax is uniform, the result is the mean of the values in the window
+    z = qkv.copy()
+    z[:, :, :D] = 0
+    np.testing.assert_allclose(oracle.attention(z, H), np.broadcast_to(v.mean(1, keepdims=True), v.shape), rtol=1e-13)
+    got = oracle.attention(z, H, left=2, right=1)
+    for t in range(T):
+        lo, hi = max(0, t - 2), min(T - 1, t + 1)
+        np.testing.assert_allclose(got[:, t], v[:, lo:hi + 1].mean(1), rtol=1e-13)
+    # a window of the frame itself returns the values unchanged; constant values come back whatever the scores
+    np.testing.assert_allclose(oracle.attention(qkv, H, left=0, right=0), v, rtol=1e-14)
+    c = qkv.copy()
+    c[:, :, 2 * D:] = 3.25
+    np.testing.assert_allclose(oracle.attention(c, H, left=3), 3.25, rtol=1e-14)
+    # one-hot alignment: query t is 50 x key (T-1-t) and keys are orthogonal with norm^2 = dh, so the other
+    # scores trail by 50 sqrt(dh) and the result is value T-1-t (to exp(-100)); the heads are independent
+    T2, dh = 4, 4
+    e = np.zeros((1, T2, 3 * dh), F)
+    e[0, :, dh:2 * dh] = 2.0 * np.eye(4, dtype=F)
+    e[0, :, :dh] = 50.0 * e[0, ::-1, dh:2 * dh]
+    e[0, :, 2 * dh:] = rng.standard_normal((T2, dh)).astype(F)
+    np.testing.assert_allclose(oracle.attention(e, 1), e[:, ::-1, 2 * dh:].astype(np.float64), rtol=1e-12, atol=1e-30)
+
+
+def test_attention_equals_scipy_softmax_formula_per_head():
+    from scipy.special import softmax
+    rng = np.random.default_rng(61)
+    B, T, D, H = 2, 13, 12, 3
+    dh = D // H
+    qkv = _qkv(rng, B, T, D)
+    q, k, v = (qkv[:, :, i * D:(i + 1) * D].astype(np.float64).reshape(B, T, H, dh) for i in range(3))
+    for left, right in ((-1, -1), (4, 0), (2, 3), (-1, 1)):
+        s = np.einsum("bthd,bjhd->bhtj", q, k) / np.sqrt(dh)
+        t_i, j_i = np.arange(T)[:, None], np.arange(T)[None, :]
+        ok = np.ones((T, T), bool)
+        if left >= 0:
+            ok &= j_i >= t_i - left
+        if right >= 0:
+            ok &= j_i <= t_i + right
+        s = np.where(ok, s, -np.inf)
+        ref = np.einsum("bhtj,bjhd->bthd", softmax(s, axis=-1), v).reshape(B, T, D)
+        ctx, smag, vmag = oracle.attention(qkv, H, left, right, want_mags=True)
+        np.testing.assert_allclose(ctx, ref, rtol=1e-12, atol=1e-14)
+        assert (vmag >= np.abs(ctx) - 1e-12).all() and (smag >= 0).all()
+    with pytest.raises(ValueError):
+        oracle.attention(qkv, 5)
