@@ -71,6 +71,7 @@ typedef int aqt_status;
 #define AQT_OP_DEPTHWISE_CONV_BWD 10   /* M = B * T tokens, K = channels C, N = kernel size kw  */
 #define AQT_OP_CONV_MODULE_FWD 11      /* M = B * T tokens, K = model width D, N = kernel size  */
 #define AQT_OP_CONV_MODULE_BWD 12
+#define AQT_OP_MHSA_FWD 13             /* M = B * T tokens, K = model width D, N unused        */
 
 /* What the forward keeps for the backward.  All caller-owned device buffers. */
 typedef struct aqt_saved {
@@ -441,6 +442,45 @@ aqt_status aqt_conv_module_bwd(const float *dy, const aqt_conv_saved *saved, con
                                int64_t D, int kw, int pad_left, const aqt_dense_policy *policy, float *dxn,
                                float *dw1, float *db1, float *dw_dw, float *db_dw, float *dw2, float *db2, void *ws,
                                size_t ws_bytes, void *stream);
+
+/*
+ * The float core of the self-attention module (Sec. 3.2: 4 or 8 heads; Sec. 3.3: limited
+ * left and right context): for every utterance b, head h and query frame t, over the key
+ * frames j of the same utterance with t - left_context <= j <= t + right_context (a negative
+ * limit: none on that side),
+ *   p = softmax_j( q_t . k_j / sqrt(dh) ),   ctx[b,t,h*dh + d] = sum_j p_j v_j[d],   dh = D / heads.
+ * qkv [B*T, 3D]: queries, keys, values in three column blocks of width D (the output of the
+ * fused projection), head h in columns h*dh .. (h+1)*dh of each block; ctx [B*T, D].
+ * dh <= 64.  Float32 with an online softmax; the scores are not written anywhere.
+ * ctx_absmax nullable device float: max|ctx|, cleared by the call, for
+ * aqt_quantize_with_absmax in front of the output projection.
+ */
+aqt_status aqt_attention_fwd(const float *qkv, int64_t B, int64_t T, int64_t D, int heads, int left_context,
+                             int right_context, float *ctx, float *ctx_absmax, void *stream);
+
+/* Buffers of the self-attention module.  Caller-owned device memory. */
+typedef struct aqt_mhsa_saved {
+  aqt_saved qkv;    /* fused query / key / value projection [M,D] x [D,3D] */
+  aqt_saved out;    /* output projection [M,D] x [D,D]                     */
+  float *qkv_f;     /* [M,3D] projected queries, keys, values              */
+  float *ctx;       /* [M,D] attention result                              */
+  float *row_stats; /* nullable [M,2]                                      */
+} aqt_mhsa_saved;
+
+/*
+ * The self-attention module (Sec. 3.2) as one call, forward, M = B * T tokens of width D:
+ *   xn = layernorm(x);  qkv = dense(xn, wqkv) + bqkv;  ctx = attention(qkv);  y = dense(ctx, wo) + bo
+ * with the projections as quantized dense layers at policy[0] / policy[1] (integer
+ * activations; Table 2's E7 keeps exactly these two layers at int8) and the attention itself in
+ * float32 (the paper quantizes the layers' weights and inputs, not the score products).
+ * Fused like the other modules: normalisation with the first quantizer, max|ctx| from the
+ * attention kernel for a one-pass second quantizer.  The backward of this module is not part
+ * of the library.
+ */
+aqt_status aqt_mhsa_fwd(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps, const float *wqkv,
+                        const float *bqkv, const float *wo, const float *bo, int64_t B, int64_t T, int64_t D,
+                        int heads, int left_context, int right_context, const aqt_dense_policy *policy, float *y,
+                        const aqt_mhsa_saved *saved, void *ws, size_t ws_bytes, void *stream, int32_t *dev_status);
 
 #ifdef __cplusplus
 }

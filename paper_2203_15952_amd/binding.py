@@ -21,7 +21,7 @@ AQT_AXIS_ALL, AQT_AXIS_ROWS, AQT_AXIS_COLS = -1, 0, 1
 AQT_EPI_NONE, AQT_EPI_SWISH, AQT_EPI_GLU = 0, 1, 2
 (AQT_OP_QUANTIZE, AQT_OP_QUANTIZE_WEIGHTS, AQT_OP_DENSE_FWD, AQT_OP_DENSE_FWD_Q, AQT_OP_DENSE_BWD,
  AQT_OP_DENSE_FWD_WONLY, AQT_OP_DENSE_BWD_EPI, AQT_OP_LAYERNORM_QUANTIZE, AQT_OP_FFN_FWD, AQT_OP_FFN_BWD,
- AQT_OP_DEPTHWISE_CONV_BWD, AQT_OP_CONV_MODULE_FWD, AQT_OP_CONV_MODULE_BWD) = range(13)
+ AQT_OP_DEPTHWISE_CONV_BWD, AQT_OP_CONV_MODULE_FWD, AQT_OP_CONV_MODULE_BWD, AQT_OP_MHSA_FWD) = range(14)
 AQT_POLICY_ALL, AQT_POLICY_EXCEPT_FIRST_LAST, AQT_POLICY_EXCEPT_ATTENTION, AQT_POLICY_FIRST_K = range(4)
 
 # every symbol include/aqt.h declares
@@ -32,7 +32,7 @@ SYMBOLS = ["aqt_status_string", "aqt_last_hip_error", "aqt_version", "aqt_worksp
            "aqt_static_scratch_bytes", "aqt_layernorm_quantize", "aqt_fake_matmul_f32", "aqt_policy_preset",
            "aqt_policy_weight_bytes", "aqt_ffn_fwd", "aqt_ffn_bwd", "aqt_prepared_weight_bytes",
            "aqt_prepare_weights", "aqt_dense_fwd_q_prepared", "aqt_depthwise_conv_fwd", "aqt_depthwise_conv_bwd",
-           "aqt_conv_module_fwd", "aqt_conv_module_bwd"]
+           "aqt_conv_module_fwd", "aqt_conv_module_bwd", "aqt_attention_fwd", "aqt_mhsa_fwd"]
 
 
 class AqtError(RuntimeError):
@@ -67,6 +67,11 @@ class aqt_ffn_saved(ctypes.Structure):
 class aqt_conv_saved(ctypes.Structure):
     _fields_ = [("pw1", aqt_saved), ("pw2", aqt_saved), ("g", ctypes.c_void_p), ("s", ctypes.c_void_p),
                 ("dfac", ctypes.c_void_p), ("row_stats", ctypes.c_void_p)]
+
+
+class aqt_mhsa_saved(ctypes.Structure):
+    _fields_ = [("qkv", aqt_saved), ("out", aqt_saved), ("qkv_f", ctypes.c_void_p), ("ctx", ctypes.c_void_p),
+                ("row_stats", ctypes.c_void_p)]
 
 
 _lib = None
@@ -130,6 +135,10 @@ def lib() -> ctypes.CDLL:
         L.aqt_conv_module_bwd.argtypes = [_vp, ctypes.POINTER(aqt_conv_saved), _vp, _i64, _i64, _i64, _int, _int,
                                           ctypes.POINTER(aqt_dense_policy), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                                           _sz, _vp]
+        L.aqt_attention_fwd.argtypes = [_vp, _i64, _i64, _i64, _int, _int, _int, _vp, _vp, _vp]
+        L.aqt_mhsa_fwd.argtypes = [_vp, _vp, _vp, ctypes.c_float, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int,
+                                   _int, ctypes.POINTER(aqt_dense_policy), _vp, ctypes.POINTER(aqt_mhsa_saved), _vp,
+                                   _sz, _vp, _vp]
         for name in SYMBOLS:
             getattr(L, name)  # AttributeError if the library lacks a declared entry point
         _lib = L
@@ -573,3 +582,46 @@ def aqt_conv_module_bwd(dy, saved: ConvSaved, w_dw, *, pad_left: int, ws=None):
                                    _ptr(o["db_dw"]), _ptr(o["dw2"]), _ptr(o["db2"]), _ptr(ws), ws.numel(), _stream())
     _check(st, "aqt_conv_module_bwd")
     return o
+
+
+def aqt_attention_fwd(qkv, B: int, T: int, heads: int, *, left: int = -1, right: int = -1, want_absmax=False):
+    """aqt_attention_fwd: qkv [B*T, 3D] -> (ctx [B*T, D], absmax word or None)."""
+    _dev(qkv, torch.float32, "qkv")
+    M, D3 = qkv.shape
+    D = D3 // 3
+    ctx = torch.empty((M, D), dtype=torch.float32, device=qkv.device)
+    m = torch.empty(1, dtype=torch.float32, device=qkv.device) if want_absmax else None
+    st = lib().aqt_attention_fwd(_ptr(qkv), B, T, D, heads, left, right, _ptr(ctx), _ptr(m), _stream())
+    _check(st, "aqt_attention_fwd")
+    return ctx, m
+
+
+class MhsaSaved:
+    """Device buffers of the self-attention module (aqt_mhsa_fwd) and their aqt_mhsa_saved view."""
+
+    def __init__(self, B: int, T: int, D: int, policy, device="cuda"):
+        (bw1, bx1), (bw2, bx2) = policy
+        M = B * T
+        self.B, self.T, self.D, self.M = B, T, D, M
+        self.qkv = Saved(M, D, 3 * D, bw1, device)
+        self.out = Saved(M, D, D, bw2, device)
+        self.qkv_f = torch.empty((M, 3 * D), dtype=torch.float32, device=device)
+        self.ctx = torch.empty((M, D), dtype=torch.float32, device=device)
+        self.row_stats = torch.empty((M, 2), dtype=torch.float32, device=device)
+        self.policy = (aqt_dense_policy * 2)(aqt_dense_policy(bw1, bx1), aqt_dense_policy(bw2, bx2))
+        self.c = aqt_mhsa_saved(self.qkv.c, self.out.c, self.qkv_f.data_ptr(), self.ctx.data_ptr(),
+                                self.row_stats.data_ptr())
+
+
+def aqt_mhsa_fwd(x, wqkv, bqkv, wo, bo, saved: MhsaSaved, heads: int, *, left: int = -1, right: int = -1, gamma=None,
+                 beta=None, eps: float = 1e-6, y=None, ws=None, dev_status=None):
+    """aqt_mhsa_fwd: layernorm, fused QKV projection, float attention, output projection.  x [B*T, D]."""
+    _dev(x, torch.float32, "x")
+    M, D = x.shape
+    y = torch.empty((M, D), dtype=torch.float32, device=x.device) if y is None else y
+    ws = workspace(aqt_workspace_bytes(AQT_OP_MHSA_FWD, M, D, 1), x.device) if ws is None else ws
+    st = lib().aqt_mhsa_fwd(_ptr(x), _ptr(gamma), _ptr(beta), eps, _ptr(wqkv), _ptr(bqkv), _ptr(wo), _ptr(bo),
+                            saved.B, saved.T, D, heads, left, right, saved.policy, _ptr(y), ctypes.byref(saved.c),
+                            _ptr(ws), ws.numel(), _stream(), _ptr(dev_status))
+    _check(st, "aqt_mhsa_fwd")
+    return y

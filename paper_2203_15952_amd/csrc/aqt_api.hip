@@ -179,6 +179,9 @@ size_t aqt_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int bits_x, 
     case AQT_OP_CONV_MODULE_FWD:
       if (!shape_ok(M, K) || N < 1) return 0;
       return carve_ffn_fwd(nullptr, M, K, 2 * K).total;
+    case AQT_OP_MHSA_FWD:
+      if (!shape_ok(M, K)) return 0;
+      return carve_ffn_fwd(nullptr, M, K, 3 * K).total;
     case AQT_OP_CONV_MODULE_BWD:
       if (!shape_ok(M, K) || N < 1 || N > 4096) return 0;
       return carve_conv_bwd(nullptr, 1, M, K, static_cast<int>(N)).total;
@@ -589,6 +592,54 @@ aqt_status aqt_conv_module_bwd(const float *dy, const aqt_conv_saved *saved, con
   // through the GLU, then the first pointwise convolution
   AQT_TRY(launch_dact_mul(f.dg, l1.dact, M, 2 * D, D, f.dv, st));
   return launch_dense_bwd(f.dv, &l1, M, D, 2 * D, dxn, dw1, db1, ws, f.core, st);
+}
+
+aqt_status aqt_attention_fwd(const float *qkv, int64_t B, int64_t T, int64_t D, int heads, int left_context,
+                             int right_context, float *ctx, float *ctx_absmax, void *stream) {
+  if (!qkv || !ctx || B < 1 || T < 1 || D < 1 || heads < 1 || D % heads) return AQT_ERR_INVALID_ARG;
+  if (!attention_shape_ok(B, T, D, heads)) return AQT_ERR_UNSUPPORTED;
+  return launch_attention(qkv, B, T, D, heads, left_context, right_context, ctx,
+                          reinterpret_cast<uint32_t *>(ctx_absmax), static_cast<hipStream_t>(stream));
+}
+
+aqt_status aqt_mhsa_fwd(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps, const float *wqkv,
+                        const float *bqkv, const float *wo, const float *bo, int64_t B, int64_t T, int64_t D,
+                        int heads, int left_context, int right_context, const aqt_dense_policy *policy, float *y,
+                        const aqt_mhsa_saved *saved, void *ws, size_t ws_bytes, void *stream, int32_t *dev_status) {
+  if (!x || !wqkv || !wo || !y || !policy || !saved || B < 1 || T < 1 || D < 1 || heads < 1 || D % heads ||
+      !(ln_eps >= 0.0f))
+    return AQT_ERR_INVALID_ARG;
+  if (!attention_shape_ok(B, T, D, heads)) return AQT_ERR_UNSUPPORTED;
+  const aqt_dense_policy p1 = policy[0], p2 = policy[1];
+  if (!policy_ok(p1) || !policy_ok(p2) || p1.bits_x == 0 || p2.bits_x == 0) return AQT_ERR_UNSUPPORTED;
+  const aqt_saved &l1 = saved->qkv, &l2 = saved->out;
+  if (!saved->qkv_f || !saved->ctx || !l1.xq || !l1.s_x || !l1.wq_packed || !l1.s_w || !l2.xq || !l2.s_x ||
+      !l2.wq_packed || !l2.s_w)
+    return AQT_ERR_INVALID_ARG;
+  if (!acc_fits(D, p1.bits_x, p1.bits_w) || !acc_fits(D, p2.bits_x, p2.bits_w)) return AQT_ERR_UNSUPPORTED;
+  const int64_t M = B * T;
+  FfnWorkspace f = carve_ffn_fwd(ws, M, D, 3 * D);
+  if (!ws || ws_bytes < f.total) return AQT_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool frag1 = fwd_q_takes_fragments(M, D, 3 * D, AQT_EPI_NONE) && reinterpret_cast<uintptr_t>(l1.xq) % 16 == 0;
+  const bool frag2 = fwd_q_takes_fragments(M, D, D, AQT_EPI_NONE) && reinterpret_cast<uintptr_t>(l2.xq) % 16 == 0;
+  // normalisation + first quantizer, fused projection of queries, keys and values
+  AQT_TRY(launch_quantize_weights(wqkv, D, 3 * D, p1.bits_w, l1.wq_packed, l1.s_w, l1.wq_kn, l1.mask_w, f.wpart1, st,
+                                  dev_status, frag1 ? f.wfrag1 : nullptr));
+  AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, nullptr,
+                                    saved->row_stats, f.ln, st, dev_status));
+  AQT_TRY(launch_dense_fwd_q(l1.xq, l1.s_x, l1.wq_packed, l1.s_w, M, D, 3 * D, p1.bits_w, bqkv, AQT_EPI_NONE,
+                             saved->qkv_f, nullptr, nullptr, f.wfrag1, st, nullptr, frag1));
+  // attention in float32; max|ctx| for the one-pass quantizer
+  AQT_TRY(launch_attention(saved->qkv_f, B, T, D, heads, left_context, right_context, saved->ctx,
+                           reinterpret_cast<uint32_t *>(f.h_absmax), st));
+  // output projection
+  AQT_TRY(launch_quantize_weights(wo, D, D, p2.bits_w, l2.wq_packed, l2.s_w, l2.wq_kn, l2.mask_w, f.wpart2, st,
+                                  dev_status, frag2 ? f.wfrag2 : nullptr));
+  AQT_TRY(launch_quantize_with_absmax(saved->ctx, M, D, D, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),
+                                      l2.xq, l2.s_x, l2.mask_x, st, dev_status));
+  return launch_dense_fwd_q(l2.xq, l2.s_x, l2.wq_packed, l2.s_w, M, D, D, p2.bits_w, bo, AQT_EPI_NONE, y, nullptr,
+                            nullptr, f.wfrag2, st, nullptr, frag2);
 }
 
 }  // extern "C"

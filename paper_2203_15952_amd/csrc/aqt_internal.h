@@ -118,4 +118,9 @@ aqt_status launch_dwconv_bwd(const float *dout, const float *dmul, const float *
                              int64_t C, int kw, int pad_left, float *dx, float *dw, float *dbias, void *ws,
                              hipStream_t st);
 
+// ---- attention core of the self-attention module (attention.hip) ---------------------------
+bool attention_shape_ok(int64_t B, int64_t T, int64_t D, int heads);
+aqt_status launch_attention(const float *qkv, int64_t B, int64_t T, int64_t D, int heads, int left, int right,
+                            float *ctx, uint32_t *absmax, hipStream_t st);
+
 }  // namespace aqt

@@ -18,6 +18,7 @@
 #define __forceinline__ inline
 #define __restrict__
 #define __launch_bounds__(x)
+#define __shared__ static   /* one copy for the block that is running (blocks run in sequence) */
 struct dim3_ { unsigned x, y, z; };
 static thread_local dim3_ threadIdx, blockIdx, gridDim, blockDim;
 static std::barrier<> *g_bar;
@@ -30,6 +31,9 @@ inline int __shfl_xor(int v, int off, int) {
   g_shfl[threadIdx.x] = v; g_bar->arrive_and_wait();
   int r = g_shfl[threadIdx.x ^ off]; g_bar->arrive_and_wait();
   return r;
+}
+inline float __shfl_xor(float v, int off, int w) {
+  int i; memcpy(&i, &v, 4); i = __shfl_xor(i, off, w); memcpy(&v, &i, 4); return v;
 }
 inline uint32_t __float_as_uint(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
 inline float __uint_as_float(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }

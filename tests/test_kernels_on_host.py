@@ -1,7 +1,7 @@
-"""The depthwise-convolution kernels run on the host, thread by thread, under the address and
-undefined-behaviour sanitizers: every global and LDS access of every launch geometry the GPU tests use is
-checked against exactly sized buffers, and the results against float64 loops in the driver.  The kernels'
-source is taken as it is (HIP headers replaced by a small vocabulary header, launchers cut off)."""
+"""The depthwise-convolution and attention kernels run on the host, thread by thread, under the address
+and undefined-behaviour sanitizers: every global and LDS access of launch geometries like the GPU tests'
+is checked against exactly sized buffers, and the results against float64 loops in the drivers.  The
+kernels' source is taken as it is (HIP headers replaced by a small vocabulary header, launchers cut off)."""
 import os
 import subprocess
 
@@ -22,10 +22,28 @@ def spliced_source():
     return src + open(os.path.join(HERE, "host_emulation", "conv_driver.cpp")).read()
 
 
+def spliced_attention_source():
+    src = open(os.path.join(CSRC, "attention.hip")).read()
+    src = src.replace('#include "aqt_internal.h"', '#include "hip_on_host.h"')
+    vec = "typedef float v4f __attribute__((ext_vector_type(4)));"      # a clang extension; g++ gets a plain struct
+    assert vec in src
+    src = src.replace(vec, "struct alignas(16) v4f { float x, y, z, w; };")
+    src = src[:src.index("}  // namespace\n\nbool attention_shape_ok")]  # kernel and geometry helper only
+    return src + open(os.path.join(HERE, "host_emulation", "attention_driver.cpp")).read()
+
+
 def test_conv_kernels_in_bounds_and_correct_on_host(tmp_path):
-    cpp = tmp_path / "conv_on_host.cpp"
-    cpp.write_text(spliced_source())
-    exe = tmp_path / "conv_on_host"
+    build_and_run(tmp_path, "conv_on_host", spliced_source())
+
+
+def test_attention_kernel_in_bounds_and_correct_on_host(tmp_path):
+    build_and_run(tmp_path, "attention_on_host", spliced_attention_source())
+
+
+def build_and_run(tmp_path, name, source):
+    cpp = tmp_path / (name + ".cpp")
+    cpp.write_text(source)
+    exe = tmp_path / name
     cmd = ["g++", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-static-libasan",
            "-static-libubsan", "-std=c++20", "-pthread", "-I", os.path.join(HERE, "host_emulation"), str(cpp), "-o", str(exe)]
     r = subprocess.run(cmd, capture_output=True, text=True)
