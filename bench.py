@@ -324,7 +324,31 @@ def main():
         fused["depthwise_swish_absmax_fwd_ms"] = dw_ms
         fused["depthwise_fwd_hbm_frac_8B_per_elem"] = 8.0 * Mf * Df / dw_ms / 1e6 / PEAK_HBM_GBS
         fused["conv_module_shape_BTDk"] = [Bc, Tc, Df, kwc]
-        del wdw, wp1, wp2, csv, ws_cf, ws_cb, g3
+        # the self-attention module (fused projection, float attention over whole utterances, output projection,
+        # int8 x int8) and its float core alone; one whole encoder layer under two of Table 2's policies
+        Hh = 8
+        wqkv = torch.randn((Df, 3 * Df), device="cuda", generator=gen) / Df ** 0.5
+        wo = torch.randn((Df, Df), device="cuda", generator=gen) / Df ** 0.5
+        msv = B.MhsaSaved(Bc, Tc, Df, ((8, 8), (8, 8)))
+        ws_m = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_MHSA_FWD, Mf, Df, 1))
+        fused["mhsa_module_fwd_ms"] = timed_loop(lambda: B.aqt_mhsa_fwd(xf, wqkv, None, wo, None, msv, Hh, y=yf, ws=ws_m,
+                                                                        dev_status=status), n=20)
+        att_ms = timed_loop(lambda: B.aqt_attention_fwd(msv.qkv_f, Bc, Tc, Hh, want_absmax=True), n=20)
+        fused["attention_core_fwd_ms"] = att_ms
+        fused["attention_core_tflops_f32"] = 4.0 * Bc * Hh * Tc * Tc * (Df // Hh) / att_ms / 1e9
+        lw = {"ffn1_w1": w1f, "ffn1_w2": w2f, "ffn2_w1": w1f, "ffn2_w2": w2f, "att_wqkv": wqkv, "att_wo": wo,
+              "conv_w1": wp1, "conv_wdw": wdw, "conv_w2": wp2}
+        ws_l = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_CONFORMER_LAYER_FWD, Mf, Df, Hf))
+        layer_ms = {}
+        for name, pattern, bw in (("int8", B.AQT_POLICY_ALL, 8), ("int4_except_attention", B.AQT_POLICY_EXCEPT_ATTENTION, 4)):
+            pol = B.aqt_policy_preset(pattern, 1, 0, bw, 8)[0]
+            lsv = B.LayerSaved(Bc, Tc, Df, Hf, pol)
+            layer_ms[name] = timed_loop(lambda: B.aqt_conformer_layer_fwd(
+                xf, lw, lsv, B=Bc, T=Tc, H=Hf, heads=Hh, kw=kwc, pad_left=15, y=yf, ws=ws_l, dev_status=status), n=10, warm=3)
+            del lsv
+        fused["encoder_layer_fwd_ms"] = layer_ms
+        fused["encoder_layer_shape"] = {"utterances": Bc, "frames": Tc, "d_model": Df, "d_ff": Hf, "heads": Hh, "kernel": kwc}
+        del wdw, wp1, wp2, csv, ws_cf, ws_cb, g3, wqkv, wo, msv, ws_m, ws_l
         # native integer product against its float32 emulation ("fake" quantization's arithmetic, Sec. 1) on
         # the 2048 -> 512 layer of the training step: same codes, int8 matrix cores vs float32 matrix cores
         L2 = layers[1]

@@ -72,6 +72,7 @@ typedef int aqt_status;
 #define AQT_OP_CONV_MODULE_FWD 11      /* M = B * T tokens, K = model width D, N = kernel size  */
 #define AQT_OP_CONV_MODULE_BWD 12
 #define AQT_OP_MHSA_FWD 13             /* M = B * T tokens, K = model width D, N unused        */
+#define AQT_OP_CONFORMER_LAYER_FWD 14  /* M = B * T tokens, K = model width D, N = inner width */
 
 /* What the forward keeps for the backward.  All caller-owned device buffers. */
 typedef struct aqt_saved {
@@ -481,6 +482,50 @@ aqt_status aqt_mhsa_fwd(const float *x, const float *ln_gamma, const float *ln_b
                         const float *bqkv, const float *wo, const float *bo, int64_t B, int64_t T, int64_t D,
                         int heads, int left_context, int right_context, const aqt_dense_policy *policy, float *y,
                         const aqt_mhsa_saved *saved, void *ws, size_t ws_bytes, void *stream, int32_t *dev_status);
+
+/* out[i] = x[i] + alpha * m[i], i < n: the residual connection around a module (float32,
+ * two roundings per element; out may alias x or m). */
+aqt_status aqt_residual_add(const float *x, const float *m, float alpha, float *out, int64_t n, void *stream);
+
+/* Weights of one Conformer encoder layer (Sec. 3.2), device pointers, float32; layouts as in
+ * aqt_ffn_fwd, aqt_mhsa_fwd and aqt_conv_module_fwd.  Every *_ln_*, bias and norm pointer
+ * may be NULL. */
+typedef struct aqt_conformer_layer_weights {
+  const float *ffn1_ln_g, *ffn1_ln_b, *ffn1_w1, *ffn1_b1, *ffn1_w2, *ffn1_b2;
+  const float *att_ln_g, *att_ln_b, *att_wqkv, *att_bqkv, *att_wo, *att_bo;
+  const float *conv_ln_g, *conv_ln_b, *conv_w1, *conv_b1, *conv_wdw, *conv_bdw, *conv_norm_scale,
+      *conv_norm_shift, *conv_w2, *conv_b2;
+  const float *ffn2_ln_g, *ffn2_ln_b, *ffn2_w1, *ffn2_b1, *ffn2_w2, *ffn2_b2;
+  const float *out_ln_g, *out_ln_b;
+} aqt_conformer_layer_weights;
+
+typedef struct aqt_conformer_layer_shape {
+  int64_t B, T, D, H;                 /* utterances, frames, model width, feed-forward width     */
+  int heads, kw, pad_left;            /* attention heads; depthwise kernel size and left padding  */
+  int left_context, right_context;    /* attention window, negative: unlimited                    */
+  float ln_eps;
+} aqt_conformer_layer_shape;
+
+/* Buffers of one encoder layer.  Caller-owned device memory. */
+typedef struct aqt_conformer_layer_saved {
+  aqt_ffn_saved ffn1, ffn2;
+  aqt_mhsa_saved att;
+  aqt_conv_saved conv;
+  float *r1, *r2, *r3, *r4;   /* [M,D] each: the residual stream after each module */
+  float *m;                   /* [M,D] module output before it joins the stream     */
+} aqt_conformer_layer_saved;
+
+/*
+ * One Conformer encoder layer (Sec. 3.2), forward, with every dense layer at the precision
+ * its aqt_layer_policy entry names (Sec. 4.2 / Table 2):
+ *   r1 = x + ffn(x) / 2;  r2 = r1 + mhsa(r1);  r3 = r2 + conv(r2);  r4 = r3 + ffn(r3) / 2;  y = layernorm(r4)
+ * x, y [B*T, D].  Forward only (aqt_mhsa_fwd has no backward); the self-attention and convolution
+ * modules need integer activations.
+ */
+aqt_status aqt_conformer_layer_fwd(const float *x, const aqt_conformer_layer_weights *w,
+                                   const aqt_conformer_layer_shape *shape, const aqt_layer_policy *policy, float *y,
+                                   const aqt_conformer_layer_saved *saved, void *ws, size_t ws_bytes, void *stream,
+                                   int32_t *dev_status);
 
 #ifdef __cplusplus
 }

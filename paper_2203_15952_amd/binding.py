@@ -21,7 +21,8 @@ AQT_AXIS_ALL, AQT_AXIS_ROWS, AQT_AXIS_COLS = -1, 0, 1
 AQT_EPI_NONE, AQT_EPI_SWISH, AQT_EPI_GLU = 0, 1, 2
 (AQT_OP_QUANTIZE, AQT_OP_QUANTIZE_WEIGHTS, AQT_OP_DENSE_FWD, AQT_OP_DENSE_FWD_Q, AQT_OP_DENSE_BWD,
  AQT_OP_DENSE_FWD_WONLY, AQT_OP_DENSE_BWD_EPI, AQT_OP_LAYERNORM_QUANTIZE, AQT_OP_FFN_FWD, AQT_OP_FFN_BWD,
- AQT_OP_DEPTHWISE_CONV_BWD, AQT_OP_CONV_MODULE_FWD, AQT_OP_CONV_MODULE_BWD, AQT_OP_MHSA_FWD) = range(14)
+ AQT_OP_DEPTHWISE_CONV_BWD, AQT_OP_CONV_MODULE_FWD, AQT_OP_CONV_MODULE_BWD, AQT_OP_MHSA_FWD,
+ AQT_OP_CONFORMER_LAYER_FWD) = range(15)
 AQT_POLICY_ALL, AQT_POLICY_EXCEPT_FIRST_LAST, AQT_POLICY_EXCEPT_ATTENTION, AQT_POLICY_FIRST_K = range(4)
 
 # every symbol include/aqt.h declares
@@ -32,7 +33,8 @@ SYMBOLS = ["aqt_status_string", "aqt_last_hip_error", "aqt_version", "aqt_worksp
            "aqt_static_scratch_bytes", "aqt_layernorm_quantize", "aqt_fake_matmul_f32", "aqt_policy_preset",
            "aqt_policy_weight_bytes", "aqt_ffn_fwd", "aqt_ffn_bwd", "aqt_prepared_weight_bytes",
            "aqt_prepare_weights", "aqt_dense_fwd_q_prepared", "aqt_depthwise_conv_fwd", "aqt_depthwise_conv_bwd",
-           "aqt_conv_module_fwd", "aqt_conv_module_bwd", "aqt_attention_fwd", "aqt_mhsa_fwd"]
+           "aqt_conv_module_fwd", "aqt_conv_module_bwd", "aqt_attention_fwd", "aqt_mhsa_fwd",
+           "aqt_residual_add", "aqt_conformer_layer_fwd"]
 
 
 class AqtError(RuntimeError):
@@ -72,6 +74,29 @@ class aqt_conv_saved(ctypes.Structure):
 class aqt_mhsa_saved(ctypes.Structure):
     _fields_ = [("qkv", aqt_saved), ("out", aqt_saved), ("qkv_f", ctypes.c_void_p), ("ctx", ctypes.c_void_p),
                 ("row_stats", ctypes.c_void_p)]
+
+
+LAYER_WEIGHT_NAMES = ("ffn1_ln_g", "ffn1_ln_b", "ffn1_w1", "ffn1_b1", "ffn1_w2", "ffn1_b2",
+                      "att_ln_g", "att_ln_b", "att_wqkv", "att_bqkv", "att_wo", "att_bo",
+                      "conv_ln_g", "conv_ln_b", "conv_w1", "conv_b1", "conv_wdw", "conv_bdw", "conv_norm_scale",
+                      "conv_norm_shift", "conv_w2", "conv_b2",
+                      "ffn2_ln_g", "ffn2_ln_b", "ffn2_w1", "ffn2_b1", "ffn2_w2", "ffn2_b2", "out_ln_g", "out_ln_b")
+
+
+class aqt_conformer_layer_weights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in LAYER_WEIGHT_NAMES]
+
+
+class aqt_conformer_layer_shape(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int64), ("T", ctypes.c_int64), ("D", ctypes.c_int64), ("H", ctypes.c_int64),
+                ("heads", ctypes.c_int), ("kw", ctypes.c_int), ("pad_left", ctypes.c_int),
+                ("left_context", ctypes.c_int), ("right_context", ctypes.c_int), ("ln_eps", ctypes.c_float)]
+
+
+class aqt_conformer_layer_saved(ctypes.Structure):
+    _fields_ = [("ffn1", aqt_ffn_saved), ("ffn2", aqt_ffn_saved), ("att", aqt_mhsa_saved), ("conv", aqt_conv_saved),
+                ("r1", ctypes.c_void_p), ("r2", ctypes.c_void_p), ("r3", ctypes.c_void_p), ("r4", ctypes.c_void_p),
+                ("m", ctypes.c_void_p)]
 
 
 _lib = None
@@ -139,6 +164,11 @@ def lib() -> ctypes.CDLL:
         L.aqt_mhsa_fwd.argtypes = [_vp, _vp, _vp, ctypes.c_float, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int,
                                    _int, ctypes.POINTER(aqt_dense_policy), _vp, ctypes.POINTER(aqt_mhsa_saved), _vp,
                                    _sz, _vp, _vp]
+        L.aqt_residual_add.argtypes = [_vp, _vp, ctypes.c_float, _vp, _i64, _vp]
+        L.aqt_conformer_layer_fwd.argtypes = [_vp, ctypes.POINTER(aqt_conformer_layer_weights),
+                                              ctypes.POINTER(aqt_conformer_layer_shape),
+                                              ctypes.POINTER(aqt_layer_policy), _vp,
+                                              ctypes.POINTER(aqt_conformer_layer_saved), _vp, _sz, _vp, _vp]
         for name in SYMBOLS:
             getattr(L, name)  # AttributeError if the library lacks a declared entry point
         _lib = L
@@ -624,4 +654,54 @@ def aqt_mhsa_fwd(x, wqkv, bqkv, wo, bo, saved: MhsaSaved, heads: int, *, left: i
                             saved.B, saved.T, D, heads, left, right, saved.policy, _ptr(y), ctypes.byref(saved.c),
                             _ptr(ws), ws.numel(), _stream(), _ptr(dev_status))
     _check(st, "aqt_mhsa_fwd")
+    return y
+
+
+def aqt_residual_add(x, m, alpha: float, out=None):
+    """aqt_residual_add: out = x + alpha * m."""
+    _dev(x, torch.float32, "x")
+    _dev(m, torch.float32, "m")
+    out = torch.empty_like(x) if out is None else out
+    _check(lib().aqt_residual_add(_ptr(x), _ptr(m), alpha, _ptr(out), x.numel(), _stream()), "aqt_residual_add")
+    return out
+
+
+class LayerSaved:
+    """Device buffers of one encoder layer (aqt_conformer_layer_fwd) and their aqt_conformer_layer_saved view.
+    policy: an aqt_layer_policy."""
+
+    def __init__(self, B: int, T: int, D: int, H: int, policy, device="cuda"):
+        def pair(a, b):
+            return ((a.bits_w, a.bits_x), (b.bits_w, b.bits_x))
+        M = B * T
+        self.policy = policy
+        self.ffn1 = FfnSaved(M, D, H, pair(policy.ffn1_in, policy.ffn1_out), device)
+        self.ffn2 = FfnSaved(M, D, H, pair(policy.ffn2_in, policy.ffn2_out), device)
+        self.att = MhsaSaved(B, T, D, pair(policy.attn_qkv, policy.attn_out), device)
+        self.conv = ConvSaved(B, T, D, pair(policy.conv_pw1, policy.conv_pw2), device)
+        self.r = [torch.empty((M, D), dtype=torch.float32, device=device) for _ in range(4)]
+        self.m = torch.empty((M, D), dtype=torch.float32, device=device)
+        self.c = aqt_conformer_layer_saved(self.ffn1.c, self.ffn2.c, self.att.c, self.conv.c,
+                                           *[t.data_ptr() for t in self.r], self.m.data_ptr())
+
+
+def aqt_conformer_layer_fwd(x, weights: dict, saved: LayerSaved, *, B: int, T: int, H: int, heads: int, kw: int,
+                            pad_left: int, left: int = -1, right: int = -1, eps: float = 1e-6, y=None, ws=None,
+                            dev_status=None):
+    """aqt_conformer_layer_fwd: weights maps the field names of aqt_conformer_layer_weights to device tensors
+    (missing or None: NULL).  x [B*T, D] -> y [B*T, D]."""
+    _dev(x, torch.float32, "x")
+    M, D = x.shape
+    unknown = set(weights) - set(LAYER_WEIGHT_NAMES)
+    if unknown:
+        raise ValueError(f"unknown weight names {sorted(unknown)}")
+    wc = aqt_conformer_layer_weights(*[None if weights.get(n) is None else weights[n].data_ptr()
+                                       for n in LAYER_WEIGHT_NAMES])
+    sh = aqt_conformer_layer_shape(B, T, D, H, heads, kw, pad_left, left, right, eps)
+    y = torch.empty((M, D), dtype=torch.float32, device=x.device) if y is None else y
+    ws = workspace(aqt_workspace_bytes(AQT_OP_CONFORMER_LAYER_FWD, M, D, H), x.device) if ws is None else ws
+    st = lib().aqt_conformer_layer_fwd(_ptr(x), ctypes.byref(wc), ctypes.byref(sh), ctypes.byref(saved.policy),
+                                       _ptr(y), ctypes.byref(saved.c), _ptr(ws), ws.numel(), _stream(),
+                                       _ptr(dev_status))
+    _check(st, "aqt_conformer_layer_fwd")
     return y

@@ -182,6 +182,12 @@ size_t aqt_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int bits_x, 
     case AQT_OP_MHSA_FWD:
       if (!shape_ok(M, K)) return 0;
       return carve_ffn_fwd(nullptr, M, K, 3 * K).total;
+    case AQT_OP_CONFORMER_LAYER_FWD: {
+      if (!shape_ok(M, K) || N < 1) return 0;
+      size_t a = carve_ffn_fwd(nullptr, M, K, N).total;
+      const size_t b = carve_ffn_fwd(nullptr, M, K, 3 * K).total;   // covers the convolution module's 2 K as well
+      return a > b ? a : b;
+    }
     case AQT_OP_CONV_MODULE_BWD:
       if (!shape_ok(M, K) || N < 1 || N > 4096) return 0;
       return carve_conv_bwd(nullptr, 1, M, K, static_cast<int>(N)).total;
@@ -640,6 +646,46 @@ aqt_status aqt_mhsa_fwd(const float *x, const float *ln_gamma, const float *ln_b
                                       l2.xq, l2.s_x, l2.mask_x, st, dev_status));
   return launch_dense_fwd_q(l2.xq, l2.s_x, l2.wq_packed, l2.s_w, M, D, D, p2.bits_w, bo, AQT_EPI_NONE, y, nullptr,
                             nullptr, f.wfrag2, st, nullptr, frag2);
+}
+
+aqt_status aqt_residual_add(const float *x, const float *m, float alpha, float *out, int64_t n, void *stream) {
+  if (!x || !m || !out || n < 1) return AQT_ERR_INVALID_ARG;
+  return launch_residual_add(x, m, alpha, out, n, static_cast<hipStream_t>(stream));
+}
+
+aqt_status aqt_conformer_layer_fwd(const float *x, const aqt_conformer_layer_weights *w,
+                                   const aqt_conformer_layer_shape *shape, const aqt_layer_policy *policy, float *y,
+                                   const aqt_conformer_layer_saved *saved, void *ws, size_t ws_bytes, void *stream,
+                                   int32_t *dev_status) {
+  if (!x || !w || !shape || !policy || !y || !saved) return AQT_ERR_INVALID_ARG;
+  const aqt_conformer_layer_shape &g = *shape;
+  if (g.B < 1 || g.T < 1 || g.D < 1 || g.H < 1 || g.B > (int64_t(1) << 40) / g.T) return AQT_ERR_INVALID_ARG;
+  if (!saved->r1 || !saved->r2 || !saved->r3 || !saved->r4 || !saved->m) return AQT_ERR_INVALID_ARG;
+  const int64_t M = g.B * g.T, n = M * g.D;
+  if (!ws || ws_bytes < aqt_workspace_bytes(AQT_OP_CONFORMER_LAYER_FWD, M, g.D, g.H, 8, 8)) return AQT_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const aqt_dense_policy pf1[2] = {policy->ffn1_in, policy->ffn1_out}, pa[2] = {policy->attn_qkv, policy->attn_out};
+  const aqt_dense_policy pc[2] = {policy->conv_pw1, policy->conv_pw2}, pf2[2] = {policy->ffn2_in, policy->ffn2_out};
+  // half-step feed-forward module
+  AQT_TRY(aqt_ffn_fwd(x, w->ffn1_ln_g, w->ffn1_ln_b, g.ln_eps, w->ffn1_w1, w->ffn1_b1, w->ffn1_w2, w->ffn1_b2, M, g.D,
+                      g.H, pf1, saved->m, &saved->ffn1, ws, ws_bytes, stream, dev_status));
+  AQT_TRY(launch_residual_add(x, saved->m, 0.5f, saved->r1, n, st));
+  // self-attention module
+  AQT_TRY(aqt_mhsa_fwd(saved->r1, w->att_ln_g, w->att_ln_b, g.ln_eps, w->att_wqkv, w->att_bqkv, w->att_wo, w->att_bo,
+                       g.B, g.T, g.D, g.heads, g.left_context, g.right_context, pa, saved->m, &saved->att, ws, ws_bytes,
+                       stream, dev_status));
+  AQT_TRY(launch_residual_add(saved->r1, saved->m, 1.0f, saved->r2, n, st));
+  // convolution module
+  AQT_TRY(aqt_conv_module_fwd(saved->r2, w->conv_ln_g, w->conv_ln_b, g.ln_eps, w->conv_w1, w->conv_b1, w->conv_wdw,
+                              w->conv_bdw, w->conv_norm_scale, w->conv_norm_shift, w->conv_w2, w->conv_b2, g.B, g.T,
+                              g.D, g.kw, g.pad_left, pc, saved->m, &saved->conv, ws, ws_bytes, stream, dev_status));
+  AQT_TRY(launch_residual_add(saved->r2, saved->m, 1.0f, saved->r3, n, st));
+  // second half-step feed-forward module, final normalisation
+  AQT_TRY(aqt_ffn_fwd(saved->r3, w->ffn2_ln_g, w->ffn2_ln_b, g.ln_eps, w->ffn2_w1, w->ffn2_b1, w->ffn2_w2, w->ffn2_b2,
+                      M, g.D, g.H, pf2, saved->m, &saved->ffn2, ws, ws_bytes, stream, dev_status));
+  AQT_TRY(launch_residual_add(saved->r3, saved->m, 0.5f, saved->r4, n, st));
+  return launch_layernorm_quantize(saved->r4, M, g.D, w->out_ln_g, w->out_ln_b, g.ln_eps, 8, nullptr, nullptr, y,
+                                   nullptr, ws, st, dev_status);
 }
 
 }  // extern "C"

@@ -106,6 +106,7 @@ aqt_status launch_layernorm_quantize(const float *x, int64_t M, int64_t D, const
                                      void *ws, hipStream_t st, int32_t *dev_status);
 aqt_status launch_dact_mul(const float *dout, const float *dact, int64_t M, int64_t N, int64_t oc, float *dv,
                            hipStream_t st);
+aqt_status launch_residual_add(const float *x, const float *m, float alpha, float *out, int64_t n, hipStream_t st);
 aqt_status launch_fake_matmul_f32(const int8_t *xq, const int8_t *wq_kn, int64_t M, int64_t K, int64_t N, float *out,
                                   hipStream_t st);
 

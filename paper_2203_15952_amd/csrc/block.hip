@@ -141,6 +141,24 @@ __global__ __launch_bounds__(kThreads) void dact_mul4_kernel(const v4f *__restri
   }
 }
 
+// out = x + alpha * m (the residual connection around a module); no contraction: two roundings
+__global__ __launch_bounds__(kThreads) void residual_add_kernel(const float *x, const float *m, float alpha, float *out,
+                                                                int64_t n) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < n; i += stride)
+    out[i] = x[i] + alpha * m[i];
+}
+
+__global__ __launch_bounds__(kThreads) void residual_add4_kernel(const v4f *x, const v4f *m, float alpha, v4f *out,
+                                                                 int64_t n4) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < n4; i += stride) {
+    const v4f a = x[i], b = m[i];
+    const v4f o = {a.x + alpha * b.x, a.y + alpha * b.y, a.z + alpha * b.z, a.w + alpha * b.w};
+    out[i] = o;
+  }
+}
+
 // ---- the float32-emulated product of the codes ------------------------------------------
 // "Fake" quantization on hardware without integer matrix units: the codes are converted to
 // float32 and multiplied and accumulated by float32 matrix instructions
@@ -251,6 +269,19 @@ aqt_status launch_dact_mul(const float *dout, const float *dact, int64_t M, int6
         reinterpret_cast<v4f *>(dv));
   } else {
     dact_mul_kernel<<<grid_cap(M * N, kThreads * 4, 4096), kThreads, 0, st>>>(dout, dact, M, N, oc, dv);
+  }
+  AQT_HIP(hipGetLastError());
+  return AQT_OK;
+}
+
+aqt_status launch_residual_add(const float *x, const float *m, float alpha, float *out, int64_t n, hipStream_t st) {
+  const bool vec = (n % 4 == 0) && reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(m) % 16 == 0 &&
+                   reinterpret_cast<uintptr_t>(out) % 16 == 0;
+  if (vec) {
+    residual_add4_kernel<<<grid_cap(n / 4, kThreads * 2, 4096), kThreads, 0, st>>>(
+        reinterpret_cast<const v4f *>(x), reinterpret_cast<const v4f *>(m), alpha, reinterpret_cast<v4f *>(out), n / 4);
+  } else {
+    residual_add_kernel<<<grid_cap(n, kThreads * 4, 4096), kThreads, 0, st>>>(x, m, alpha, out, n);
   }
   AQT_HIP(hipGetLastError());
   return AQT_OK;

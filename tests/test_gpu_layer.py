@@ -1,0 +1,150 @@
+"""One Conformer encoder layer as one call: bit-identical to its modules called in sequence (each of
+which has its own stage-by-stage parity test against the oracle), and, end to end, close to the same
+layer evaluated in float64 without any quantization (compared statistically, as a quantized chain
+must be: a code that flips upstream changes everything downstream a little)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2203_15952_amd import binding as B
+
+pytestmark = pytest.mark.gpu
+F = np.float32
+
+
+def dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+@pytest.mark.parametrize("n,alpha", [(1, 0.5), (1023, 1.0), (4096, 0.5), (12800 * 512, -0.25)])
+def test_residual_add(n, alpha):
+    rng = np.random.default_rng(n)
+    x, m = rng.standard_normal(n).astype(F), rng.standard_normal(n).astype(F)
+    out = B.aqt_residual_add(dev(x), dev(m), alpha)
+    np.testing.assert_array_equal(host(out), x + F(alpha) * m)     # float32 product, then float32 sum
+
+
+def layer_weights(seed, D, H, kw):
+    rng = np.random.default_rng(seed)
+
+    def mat(k, n):
+        return (rng.standard_normal((k, n)) / np.sqrt(k)).astype(F)
+
+    def vec(n, centre=0.0):
+        return (centre + 0.1 * rng.standard_normal(n)).astype(F)
+
+    w = {}
+    for p in ("ffn1", "ffn2"):
+        w.update({f"{p}_ln_g": vec(D, 1.0), f"{p}_ln_b": vec(D), f"{p}_w1": mat(D, H), f"{p}_b1": vec(H),
+                  f"{p}_w2": mat(H, D), f"{p}_b2": vec(D)})
+    w.update(att_ln_g=vec(D, 1.0), att_ln_b=vec(D), att_wqkv=mat(D, 3 * D), att_bqkv=vec(3 * D), att_wo=mat(D, D),
+             att_bo=vec(D))
+    w.update(conv_ln_g=vec(D, 1.0), conv_ln_b=vec(D), conv_w1=mat(D, 2 * D), conv_b1=vec(2 * D),
+             conv_wdw=(rng.standard_normal((kw, D)) / np.sqrt(kw)).astype(F), conv_bdw=vec(D),
+             conv_norm_scale=vec(D, 1.0), conv_norm_shift=vec(D), conv_w2=mat(D, D), conv_b2=vec(D))
+    w.update(out_ln_g=vec(D, 1.0), out_ln_b=vec(D))
+    return w
+
+
+def float_layer(x, w, B_, T, D, heads, kw, pl, left, right):
+    """The same encoder layer in float64 with no quantization anywhere."""
+    f = {k: v.astype(np.float64) for k, v in w.items()}
+
+    def swish(v):
+        return v / (1.0 + np.exp(-v))
+
+    def ffn(r, p):
+        xn = oracle.layernorm(r.astype(F), w[f"{p}_ln_g"], w[f"{p}_ln_b"], 1e-6)
+        return swish(xn @ f[f"{p}_w1"] + f[f"{p}_b1"]) @ f[f"{p}_w2"] + f[f"{p}_b2"]
+
+    r1 = x + 0.5 * ffn(x, "ffn1")
+    xn = oracle.layernorm(r1.astype(F), w["att_ln_g"], w["att_ln_b"], 1e-6)
+    qkv = xn @ f["att_wqkv"] + f["att_bqkv"]
+    ctx = oracle.attention(qkv.astype(F).reshape(B_, T, 3 * D), heads, left, right).reshape(-1, D)
+    r2 = r1 + ctx @ f["att_wo"] + f["att_bo"]
+    xn = oracle.layernorm(r2.astype(F), w["conv_ln_g"], w["conv_ln_b"], 1e-6)
+    pre = xn @ f["conv_w1"] + f["conv_b1"]
+    g = pre[:, :D] / (1.0 + np.exp(-pre[:, D:]))
+    v = oracle.depthwise_conv(g.astype(F).reshape(B_, T, D), w["conv_wdw"], w["conv_bdw"], pad_left=pl).reshape(-1, D)
+    s, _ = oracle.affine_swish(v, w["conv_norm_scale"], w["conv_norm_shift"])
+    r3 = r2 + s @ f["conv_w2"] + f["conv_b2"]
+    r4 = r3 + 0.5 * ffn(r3, "ffn2")
+    return oracle.layernorm(r4.astype(F), w["out_ln_g"], w["out_ln_b"], 1e-6)
+
+
+def run_layer(x_d, wd, policy, B_, T, D, H, heads, kw, pl, left, right):
+    sv = B.LayerSaved(B_, T, D, H, policy)
+    status = B.new_status()
+    y = B.aqt_conformer_layer_fwd(x_d, wd, sv, B=B_, T=T, H=H, heads=heads, kw=kw, pad_left=pl, left=left, right=right,
+                                  dev_status=status)
+    assert host(status)[0] == 0
+    return y, sv
+
+
+def test_conformer_layer_equals_its_modules_in_sequence_and_tracks_the_float_layer():
+    B_, T, D, H, heads, kw, pl, left, right = 6, 150, 256, 1024, 4, 15, 14, 23, 0
+    M = B_ * T
+    say("encoder layer", B_, T, D, H)
+    w = layer_weights(800, D, H, kw)
+    x = np.random.default_rng(801).standard_normal((M, D)).astype(F)
+    wd = {k: dev(v) for k, v in w.items()}
+    x_d = dev(x)
+    ref = float_layer(x.astype(np.float64), w, B_, T, D, heads, kw, pl, left, right)
+    errs = {}
+    for name, pattern, bits_w in (("int8", B.AQT_POLICY_ALL, 8), ("int4 except attention", B.AQT_POLICY_EXCEPT_ATTENTION, 4),
+                                  ("int4", B.AQT_POLICY_ALL, 4)):
+        pol = B.aqt_policy_preset(pattern, 1, 0, bits_w, 8)[0]
+        y, sv = run_layer(x_d, wd, pol, B_, T, D, H, heads, kw, pl, left, right)
+        y_h = host(y)
+        errs[name] = np.linalg.norm(y_h - ref) / np.linalg.norm(ref)
+        say(" ", name, "relative error against the float layer", errs[name])
+        # the same modules one by one
+        def pair(a, b):
+            return ((a.bits_w, a.bits_x), (b.bits_w, b.bits_x))
+        f1 = B.FfnSaved(M, D, H, pair(pol.ffn1_in, pol.ffn1_out))
+        m = B.aqt_ffn_fwd(x_d, wd["ffn1_w1"], wd["ffn1_b1"], wd["ffn1_w2"], wd["ffn1_b2"], f1, gamma=wd["ffn1_ln_g"],
+                          beta=wd["ffn1_ln_b"])
+        r1 = B.aqt_residual_add(x_d, m, 0.5)
+        a = B.MhsaSaved(B_, T, D, pair(pol.attn_qkv, pol.attn_out))
+        m = B.aqt_mhsa_fwd(r1, wd["att_wqkv"], wd["att_bqkv"], wd["att_wo"], wd["att_bo"], a, heads, left=left,
+                           right=right, gamma=wd["att_ln_g"], beta=wd["att_ln_b"])
+        r2 = B.aqt_residual_add(r1, m, 1.0)
+        c = B.ConvSaved(B_, T, D, pair(pol.conv_pw1, pol.conv_pw2))
+        m = B.aqt_conv_module_fwd(r2, wd["conv_w1"], wd["conv_b1"], wd["conv_wdw"], wd["conv_bdw"], wd["conv_w2"],
+                                  wd["conv_b2"], c, pad_left=pl, gamma=wd["conv_ln_g"], beta=wd["conv_ln_b"],
+                                  norm_scale=wd["conv_norm_scale"], norm_shift=wd["conv_norm_shift"])
+        r3 = B.aqt_residual_add(r2, m, 1.0)
+        f2 = B.FfnSaved(M, D, H, pair(pol.ffn2_in, pol.ffn2_out))
+        m = B.aqt_ffn_fwd(r3, wd["ffn2_w1"], wd["ffn2_b1"], wd["ffn2_w2"], wd["ffn2_b2"], f2, gamma=wd["ffn2_ln_g"],
+                          beta=wd["ffn2_ln_b"])
+        r4 = B.aqt_residual_add(r3, m, 0.5)
+        _, _, y2, _ = B.aqt_layernorm_quantize(r4, 8, gamma=wd["out_ln_g"], beta=wd["out_ln_b"], quantize=False,
+                                               want_y=True)
+        np.testing.assert_array_equal(host(y2), y_h)
+        for got, want in zip(sv.r, (r1, r2, r3, r4)):
+            np.testing.assert_array_equal(host(got), host(want))
+    # int8 stays within a few per cent of the float layer; int4 weights cost more, and keeping the attention
+    # projections at int8 (Table 2, E7) recovers part of it
+    assert errs["int8"] < 0.03
+    assert errs["int8"] < errs["int4 except attention"] < errs["int4"] < 0.25
+
+
+def test_conformer_layer_rejects_float_activations_in_attention():
+    B_, T, D, H = 1, 64, 128, 256
+    pol = B.aqt_policy_preset(B.AQT_POLICY_ALL, 1, 0, 4, 0)[0]      # weight-only everywhere
+    w = {k: dev(v) for k, v in layer_weights(1, D, H, 15).items()}
+    sv = B.LayerSaved(B_, T, D, H, pol)
+    with pytest.raises(B.AqtError) as e:
+        B.aqt_conformer_layer_fwd(torch.zeros((B_ * T, D), device="cuda"), w, sv, B=B_, T=T, H=H, heads=2, kw=15,
+                                  pad_left=14)
+    assert e.value.status == B.AQT_ERR_UNSUPPORTED
