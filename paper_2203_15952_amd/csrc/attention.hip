@@ -2,47 +2,52 @@
 // projections (arxiv 2203.15952, Sec. 3.2: 4 or 8 heads; Sec. 3.3: a limited left context
 // and, in the non-causal encoder, a limited right context): for every utterance, head and
 // query frame, softmax over the key frames of the window of the scaled dot products, times
-// the values.  Plain float32 vector arithmetic with an online softmax (running maximum and
-// sum per query, the output rescaled when the maximum moves), so the scores never leave the
-// chip; the largest |result| is reduced on the way out for the quantizer of the output
-// projection (Fig. 2).
+// the values.  Float32 throughout: both contractions run on the float32 matrix cores
+// (v_mfma_f32_32x32x2_f32: exact products, float32 accumulation), with an online softmax
+// (running maximum and sum per query, the output rescaled when the maximum moves), so the
+// scores never leave the chip; the largest |result| is reduced on the way out for the
+// quantizer of the output projection (Fig. 2).
 //
 // qkv [B*T, 3D]: queries, keys, values in three column blocks of width D, head h in columns
-// h*dh .. (h+1)*dh of each.  A workgroup owns 64 query frames of one utterance and head and
-// walks the key frames of their windows 64 at a time: queries, keys and values sit in LDS
-// (rows of 68 floats: 16-byte aligned and conflict-free for the access patterns below), a
-// thread forms 4 x 4 blocks: queries 4 ty .. 4 ty + 3 against keys tx, tx + 16, tx + 32,
-// tx + 48 for the scores, the same queries against head columns 4 tx .. 4 tx + 3 for the
-// output.  The probabilities pass through the LDS block the keys held.
+// h*dh .. (h+1)*dh of each.  A workgroup owns 128 query frames of one utterance and head, a
+// wavefront 32 of them, and all walk the key frames of their windows 64 at a time.  Both
+// products are formed transposed, so that a lane owns one query from start to end:
+//   S^T (64 keys x 32 queries) = K Q_w^T   A operand: keys from LDS; B operand: the wavefront's
+//                                          queries, held in 32 registers per lane for the whole kernel
+//   a lane then holds 32 scores of ITS query: maximum, exponentials and sum are lane-local (one
+//   exchange with the other half of the wavefront per step)
+//   O^T (64 x 32 queries) += V^T P^T       B operand: the probabilities, exactly where the first
+//                                          product left them; A operand: values from LDS
+// so the probabilities never leave the registers and the running maximum, the rescaling of O
+// and the final division need no cross-lane traffic.  An MFMA step contracts two positions,
+// lane half lk supplying the second index lk: key and query rows are stored "parity-major"
+// along the head (even positions, then odd ones) so that each lane finds its 32 values
+// contiguous and fetches them 16 bytes at a time; in the second product the step (nb, r) pairs
+// the keys 32 nb + 8 (r / 4) + r % 4 and that + 4, which is where the accumulator layout of
+// the first product put them.  LDS rows are 68 floats: 16-byte aligned, and rows map to
+// different banks.  The result leaves through LDS as whole rows.
 #include "aqt_internal.h"
 
 namespace aqt {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kQ = 64;          // query frames per workgroup
+constexpr int kQ = 128;         // query frames per workgroup (32 per wavefront)
 constexpr int kK = 64;          // key frames per step
 constexpr int kDh = 64;         // widest head a tile holds; narrower heads are padded with zeros
 constexpr int kLd = kDh + 4;    // LDS row stride in floats
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
 struct AttnGeom {
   int64_t B, T, D;
   int heads, dh, left, right;   // left / right < 0: no limit on that side
-  int qtiles;                   // 64-frame query tiles per utterance
-  float scale;                  // 1 / sqrt(dh)
+  int qtiles;                   // 128-frame query tiles per utterance
+  float scale_log2e;            // log2(e) / sqrt(dh): scores are kept in the exponent domain of exp2
 };
 
-__device__ __forceinline__ float group16_max(float v) {
-#pragma unroll
-  for (int off = 8; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-  return v;
-}
-__device__ __forceinline__ float group16_sum(float v) {
-#pragma unroll
-  for (int off = 8; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
-}
+__device__ __forceinline__ int parity_major(int c) { return (c & 1) * 32 + (c >> 1); }
+
 __device__ __forceinline__ uint32_t wave_max_bits(uint32_t v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
@@ -52,13 +57,14 @@ __device__ __forceinline__ uint32_t wave_max_bits(uint32_t v) {
   return v;
 }
 
-// 64 frames x 64 head columns starting at frame row0 and qkv column col0 into dst[frame][col]; frames
-// beyond the utterance and columns beyond the head are zero.  Loads go to clamped, always valid
-// addresses (no branches, sixteen in flight per thread).
+// 64 frames x 64 head columns starting at frame row0 and qkv column col0 into dst[frame][col] (col in
+// parity-major order if asked); frames beyond the utterance and columns beyond the head are zero.
+// Loads go to clamped, always valid addresses (no branches, sixteen in flight per thread).
 __device__ __forceinline__ void stage_tile(float *__restrict__ dst, const float *__restrict__ qkv, const AttnGeom &g,
-                                           int64_t b, int64_t row0, int64_t col0) {
+                                           int64_t b, int64_t row0, int64_t col0, bool permute) {
   const int d = threadIdx.x & 63, r0 = threadIdx.x >> 6;
   const int dd = d < g.dh ? d : g.dh - 1;
+  const int at = permute ? parity_major(d) : d;
   float v[16];
 #pragma unroll
   for (int k = 0; k < 16; ++k) {
@@ -69,18 +75,17 @@ __device__ __forceinline__ void stage_tile(float *__restrict__ dst, const float 
 #pragma unroll
   for (int k = 0; k < 16; ++k) {
     const int r = r0 + 4 * k;
-    dst[r * kLd + d] = (d < g.dh && row0 + r < g.T) ? v[k] : 0.0f;
+    dst[r * kLd + at] = (d < g.dh && row0 + r < g.T) ? v[k] : 0.0f;
   }
 }
 
-__global__ __launch_bounds__(kThreads) void attention_fwd_kernel(const float *__restrict__ qkv, AttnGeom g,
+__global__ __launch_bounds__(kThreads, 2) void attention_fwd_kernel(const float *__restrict__ qkv, AttnGeom g,
                                                                  float *__restrict__ ctx,
                                                                  uint32_t *__restrict__ absmax) {
-  __shared__ float Qs[kQ * kLd];
-  __shared__ float Ks[kK * kLd];   // keys, then the probabilities of the same step
-  __shared__ float Vs[kK * kLd];
-  float *Ps = Ks;
-  const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+  __shared__ __attribute__((aligned(16))) float lds[2 * kK * kLd];
+  float *Ks = lds;              // keys, parity-major along the head
+  float *Vs = lds + kK * kLd;   // values
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 31, lk = lane >> 5;
   int64_t id = blockIdx.x;
   const int qt = static_cast<int>(id % g.qtiles);
   id /= g.qtiles;
@@ -88,123 +93,129 @@ __global__ __launch_bounds__(kThreads) void attention_fwd_kernel(const float *__
   const int64_t b = id / g.heads;
   const int64_t t0 = static_cast<int64_t>(qt) * kQ;
   const int64_t hc = static_cast<int64_t>(h) * g.dh;
-  stage_tile(Qs, qkv, g, b, t0, hc);
+
+  // the wavefront's 32 queries as a B operand: lane (lr, lk) keeps Q[query lr][2 i + lk], i < 32
+  stage_tile(Ks, qkv, g, b, t0, hc, true);
+  stage_tile(Vs, qkv, g, b, t0 + 64, hc, true);
+  __syncthreads();
+  float qf[32];
+  {
+    const float *src = (wave < 2 ? Ks : Vs) + ((wave & 1) * 32 + lr) * kLd + lk * 32;
+#pragma unroll
+    for (int i4 = 0; i4 < 8; ++i4) {
+      const v4f q = *reinterpret_cast<const v4f *>(src + 4 * i4);
+      qf[4 * i4] = q.x; qf[4 * i4 + 1] = q.y; qf[4 * i4 + 2] = q.z; qf[4 * i4 + 3] = q.w;
+    }
+  }
+  const int64_t tw = t0 + wave * 32;          // first query frame of this wavefront
+  const bool active = tw < g.T;               // idle wavefronts of a ragged tile still stage and meet the barriers
+  const int64_t t = tw + lr;                  // this lane's query frame
 
   // key frames any query of this tile may look at
   const int64_t tlast = (t0 + kQ - 1 < g.T ? t0 + kQ - 1 : g.T - 1);
   const int64_t jmin = (g.left < 0 || t0 - g.left < 0) ? 0 : t0 - g.left;
   const int64_t jmax = (g.right < 0 || tlast + g.right > g.T - 1) ? g.T - 1 : tlast + g.right;
+  const int64_t wlo = g.left < 0 ? 0 : t - g.left;                       // this query's window
+  const int64_t whi = (g.right < 0 || t + g.right > g.T - 1) ? g.T - 1 : t + g.right;
 
-  float m[4], l[4], o[4][4];
+  float m = -1e30f, l = 0.0f;   // running maximum (exponent domain of exp2); this lane's share of the running sum
+  v16f o[2];                    // element r: head column 32 blk + 8 (r / 4) + 4 lk + r % 4 of this lane's query
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    m[i] = -1e30f;
-    l[i] = 0.0f;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) o[i][e] = 0.0f;
+  for (int r = 0; r < 16; ++r) {
+    o[0][r] = 0.0f;
+    o[1][r] = 0.0f;
   }
   for (int64_t j0 = jmin / kK * kK; j0 <= jmax; j0 += kK) {
-    __syncthreads();   // the previous step's reads of Ps and Vs are over (first step: Qs is complete after the next barrier)
-    stage_tile(Ks, qkv, g, b, j0, g.D + hc);
-    stage_tile(Vs, qkv, g, b, j0, 2 * g.D + hc);
+    __syncthreads();   // the queries have been taken / the previous step's reads of Ks and Vs are over
+    stage_tile(Ks, qkv, g, b, j0, g.D + hc, true);
+    stage_tile(Vs, qkv, g, b, j0, 2 * g.D + hc, false);
     __syncthreads();
-    // scores of queries 4 ty + i against keys tx + 16 kk
-    float s[4][4];
+    if (active) {
+      // s[nb][r]: score of key j0 + 32 nb + 8 (r / 4) + 4 lk + r % 4 against this lane's query
+      v16f s[2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+      for (int nb = 0; nb < 2; ++nb) {
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) s[i][kk] = 0.0f;
-#pragma unroll 4
-    for (int d4 = 0; d4 < kDh; d4 += 4) {
-      v4f q[4], k[4];
+        for (int r = 0; r < 16; ++r) s[nb][r] = 0.0f;
+        const float *kp = Ks + (nb * 32 + lr) * kLd + lk * 32;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) q[i] = *reinterpret_cast<const v4f *>(&Qs[(ty * 4 + i) * kLd + d4]);
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) k[kk] = *reinterpret_cast<const v4f *>(&Ks[(tx + 16 * kk) * kLd + d4]);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          s[i][kk] = fmaf(q[i].x, k[kk].x, s[i][kk]);
-          s[i][kk] = fmaf(q[i].y, k[kk].y, s[i][kk]);
-          s[i][kk] = fmaf(q[i].z, k[kk].z, s[i][kk]);
-          s[i][kk] = fmaf(q[i].w, k[kk].w, s[i][kk]);
+        for (int i4 = 0; i4 < 8; ++i4) {
+          const v4f k = *reinterpret_cast<const v4f *>(kp + 4 * i4);
+          s[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(k.x, qf[4 * i4], s[nb], 0, 0, 0);
+          s[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(k.y, qf[4 * i4 + 1], s[nb], 0, 0, 0);
+          s[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(k.z, qf[4 * i4 + 2], s[nb], 0, 0, 0);
+          s[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(k.w, qf[4 * i4 + 3], s[nb], 0, 0, 0);
         }
-    }
-    // window, running maximum and sum, probabilities
-    float alpha[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int64_t t = t0 + ty * 4 + i;
-      bool ok[4];
+      }
+      // window, running maximum, probabilities
       float mx = -1e30f;
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const int64_t j = j0 + tx + 16 * kk;
-        ok[kk] = j < g.T && (g.left < 0 || j >= t - g.left) && (g.right < 0 || j <= t + g.right);
-        s[i][kk] *= g.scale;
-        if (ok[kk]) mx = fmaxf(mx, s[i][kk]);
-      }
-      const float mnew = fmaxf(m[i], group16_max(mx));
-      alpha[i] = expf(m[i] - mnew);
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int64_t j = j0 + 32 * nb + 8 * (r >> 2) + 4 * lk + (r & 3);
+          const float x = (j >= wlo && j <= whi) ? s[nb][r] * g.scale_log2e : -1e30f;
+          s[nb][r] = x;
+          mx = fmaxf(mx, x);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float mnew = fmaxf(m, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+      m = mnew;
       float sum = 0.0f;
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        s[i][kk] = ok[kk] ? expf(s[i][kk] - mnew) : 0.0f;
-        sum += s[i][kk];
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float p = s[nb][r] > -1e29f ? __builtin_amdgcn_exp2f(s[nb][r] - mnew) : 0.0f;
+          s[nb][r] = p;
+          sum += p;
+        }
+      l = l * alpha + sum;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        o[0][r] *= alpha;
+        o[1][r] *= alpha;
       }
-      l[i] = l[i] * alpha[i] + group16_sum(sum);
-      m[i] = mnew;
+      // O^T += V^T P^T: step (nb, r) contracts the keys 32 nb + 8 (r / 4) + r % 4 (lk = 0) and that + 4 (lk = 1)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) o[i][e] *= alpha[i];
-    }
-    __syncthreads();   // every score has been formed: the keys may be overwritten
+      for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) Ps[(ty * 4 + i) * kLd + tx + 16 * kk] = s[i][kk];
-    __syncthreads();
-    // output columns 4 tx .. 4 tx + 3 of queries 4 ty + i
-#pragma unroll 4
-    for (int j4 = 0; j4 < kK; j4 += 4) {
-      v4f p[4], v[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) p[i] = *reinterpret_cast<const v4f *>(&Ps[(ty * 4 + i) * kLd + j4]);
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) v[jj] = *reinterpret_cast<const v4f *>(&Vs[(j4 + jj) * kLd + tx * 4]);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        o[i][0] = fmaf(p[i].x, v[0].x, o[i][0]); o[i][1] = fmaf(p[i].x, v[0].y, o[i][1]);
-        o[i][2] = fmaf(p[i].x, v[0].z, o[i][2]); o[i][3] = fmaf(p[i].x, v[0].w, o[i][3]);
-        o[i][0] = fmaf(p[i].y, v[1].x, o[i][0]); o[i][1] = fmaf(p[i].y, v[1].y, o[i][1]);
-        o[i][2] = fmaf(p[i].y, v[1].z, o[i][2]); o[i][3] = fmaf(p[i].y, v[1].w, o[i][3]);
-        o[i][0] = fmaf(p[i].z, v[2].x, o[i][0]); o[i][1] = fmaf(p[i].z, v[2].y, o[i][1]);
-        o[i][2] = fmaf(p[i].z, v[2].z, o[i][2]); o[i][3] = fmaf(p[i].z, v[2].w, o[i][3]);
-        o[i][0] = fmaf(p[i].w, v[3].x, o[i][0]); o[i][1] = fmaf(p[i].w, v[3].y, o[i][1]);
-        o[i][2] = fmaf(p[i].w, v[3].z, o[i][2]); o[i][3] = fmaf(p[i].w, v[3].w, o[i][3]);
-      }
+        for (int r = 0; r < 16; ++r) {
+          const float *vp = Vs + (32 * nb + 8 * (r >> 2) + 4 * lk + (r & 3)) * kLd + lr;
+          o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(vp[0], s[nb][r], o[0], 0, 0, 0);
+          o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(vp[32], s[nb][r], o[1], 0, 0, 0);
+        }
     }
   }
+  // out through LDS, so that rows leave as whole 256-byte pieces
+  __syncthreads();
+  float *ot = lds + wave * 32 * kLd;   // [32 queries][68], this wavefront's own quarter
   uint32_t amax = 0u;
+  if (active) {
+    const float lt = l + __shfl_xor(l, 32, 64);
+    const float inv = lt > 0.0f ? 1.0f / lt : 0.0f;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int64_t t = t0 + ty * 4 + i;
-    if (t < g.T) {
-      const float inv = l[i] > 0.0f ? 1.0f / l[i] : 0.0f;
+    for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int d = tx * 4 + e;
-        if (d < g.dh) {
-          const float r = o[i][e] * inv;
-          ctx[(b * g.T + t) * g.D + hc + d] = r;
-          amax = max(amax, __float_as_uint(r) & 0x7FFFFFFFu);
-        }
+      for (int r4 = 0; r4 < 4; ++r4) {
+        v4f v;
+        v.x = o[blk][4 * r4] * inv; v.y = o[blk][4 * r4 + 1] * inv;
+        v.z = o[blk][4 * r4 + 2] * inv; v.w = o[blk][4 * r4 + 3] * inv;
+        *reinterpret_cast<v4f *>(ot + lr * kLd + 32 * blk + 8 * r4 + 4 * lk) = v;
+      }
+    __builtin_amdgcn_wave_barrier();   // the wavefront's own LDS writes above, its own reads below
+    for (int q = 0; q < 32; ++q) {
+      if (tw + q < g.T && lane < g.dh) {
+        const float v = ot[q * kLd + lane];
+        ctx[(b * g.T + tw + q) * g.D + hc + lane] = v;
+        amax = max(amax, __float_as_uint(v) & 0x7FFFFFFFu);
       }
     }
   }
   if (absmax) {   // uniform: the word only grows, so a stale read can only cost a redundant atomic
     amax = wave_max_bits(amax);
-    if ((tid & 63) == 0 && amax > *reinterpret_cast<volatile uint32_t *>(absmax)) atomicMax(absmax, amax);
+    if (lane == 0 && amax > *reinterpret_cast<volatile uint32_t *>(absmax)) atomicMax(absmax, amax);
   }
 }
 
@@ -217,7 +228,7 @@ AttnGeom attn_geom(int64_t B, int64_t T, int64_t D, int heads, int left, int rig
   g.B = B; g.T = T; g.D = D; g.heads = heads; g.dh = static_cast<int>(D / heads);
   g.left = left; g.right = right;
   g.qtiles = static_cast<int>(cdiv(T, kQ));
-  g.scale = 1.0f / sqrtf(static_cast<float>(g.dh));
+  g.scale_log2e = static_cast<float>(1.4426950408889634 / sqrt(static_cast<double>(g.dh)));
   return g;
 }
 

@@ -35,7 +35,7 @@ static void one(int64_t B, int64_t T, int64_t D, int heads, int left, int right)
 }  // namespace aqt
 int main() {
   using namespace aqt;
-  one(1, 1, 1, 1, -1, -1); one(2, 70, 128, 2, -1, -1); one(1, 130, 72, 2, 23, 0); one(2, 65, 12, 3, 5, 7);
-  one(1, 200, 64, 1, -1, 3); one(1, 64, 36, 1, 0, 0); one(1, 150, 8, 8, 100, 100);
+  one(1, 1, 1, 1, -1, -1); one(1, 70, 128, 2, -1, -1); one(1, 130, 72, 2, 23, 0); one(2, 65, 12, 3, 5, 7);
+  one(1, 140, 64, 1, -1, 3); one(1, 64, 36, 1, 0, 0); one(1, 150, 8, 2, 70, 70);
   printf(bad ? "MISMATCH\n" : "ok\n"); return bad;
 }

@@ -28,6 +28,9 @@ def spliced_attention_source():
     vec = "typedef float v4f __attribute__((ext_vector_type(4)));"      # a clang extension; g++ gets a plain struct
     assert vec in src
     src = src.replace(vec, "struct alignas(16) v4f { float x, y, z, w; };")
+    vec16 = "typedef float v16f __attribute__((ext_vector_type(16)));"                # the shim has its own
+    assert vec16 in src
+    src = src.replace(vec16, "")
     src = src[:src.index("}  // namespace\n\nbool attention_shape_ok")]  # kernel and geometry helper only
     return src + open(os.path.join(HERE, "host_emulation", "attention_driver.cpp")).read()
 
