@@ -18,7 +18,7 @@
 #define __host__
 #define __forceinline__ inline
 #define __restrict__
-#define __launch_bounds__(x)
+#define __launch_bounds__(...)
 #define __shared__ static   /* one copy for the block that is running (blocks run in sequence) */
 struct dim3_ { unsigned x, y, z; };
 static thread_local dim3_ threadIdx, blockIdx, gridDim, blockDim;
