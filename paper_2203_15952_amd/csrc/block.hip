@@ -39,9 +39,22 @@ __device__ __forceinline__ float ln_value(float x, float mean, float rstd, const
   return t;
 }
 
+// A row in registers: lane l keeps the float4 pieces l, l + 64, ... of its row (NV pieces, rows of up to
+// 256 NV floats whose length is a multiple of 4), so each pass reads the row from memory once.
+template <int NV>
+__device__ __forceinline__ void load_row(const float *__restrict__ row, int64_t D, int lane, v4f (&v)[NV]) {
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int64_t c = 4 * (lane + 64 * k);
+    v[k] = c < D ? *reinterpret_cast<const v4f *>(row + c) : v4f{0.0f, 0.0f, 0.0f, 0.0f};
+  }
+}
+
 // Pass 1: one wavefront per row.  Row mean and biased variance in float32 (lane partial
 // sums, then a fixed shuffle tree: the same bits on every run), rstd = 1 / sqrt(var + eps),
 // and the largest |normalised value| of everything this block handled.
+// NV > 0: the row is held in registers (D % 4 == 0, D <= 256 NV, 16-byte aligned rows); NV = 0: any row.
+template <int NV>
 __global__ __launch_bounds__(kThreads) void ln_stats_kernel(const float *__restrict__ x, int64_t M, int64_t D,
                                                             const float *__restrict__ gamma,
                                                             const float *__restrict__ beta, float eps,
@@ -51,22 +64,54 @@ __global__ __launch_bounds__(kThreads) void ln_stats_kernel(const float *__restr
   uint32_t amax = 0u;
   for (int64_t m = static_cast<int64_t>(blockIdx.x) * 4 + wave; m < M; m += static_cast<int64_t>(gridDim.x) * 4) {
     const float *row = x + m * D;
-    float s = 0.0f;
-    for (int64_t c = lane; c < D; c += 64) s += row[c];
-    const float mean = wave_sum(s) / static_cast<float>(D);
-    float v = 0.0f;
-    for (int64_t c = lane; c < D; c += 64) {
-      const float d = row[c] - mean;
-      v += d * d;
+    if constexpr (NV > 0) {
+      v4f v[NV];
+      load_row<NV>(row, D, lane, v);
+      float s = 0.0f;
+#pragma unroll
+      for (int k = 0; k < NV; ++k) s += (v[k].x + v[k].y) + (v[k].z + v[k].w);   // pieces beyond the row are zero
+      const float mean = wave_sum(s) / static_cast<float>(D);
+      float q = 0.0f;
+#pragma unroll
+      for (int k = 0; k < NV; ++k)
+        if (4 * (lane + 64 * k) < D) {
+          const float a = v[k].x - mean, b = v[k].y - mean, c = v[k].z - mean, d = v[k].w - mean;
+          q += (a * a + b * b) + (c * c + d * d);
+        }
+      const float var = wave_sum(q) / static_cast<float>(D);
+      const float rstd = 1.0f / sqrtf(var + eps);
+      if (lane == 0) {
+        stats[2 * m] = mean;
+        stats[2 * m + 1] = rstd;
+      }
+#pragma unroll
+      for (int k = 0; k < NV; ++k) {
+        const int64_t c = 4 * (lane + 64 * k);
+        if (c < D) {
+          amax = max(amax, __float_as_uint(ln_value(v[k].x, mean, rstd, gamma, beta, c)) & 0x7FFFFFFFu);
+          amax = max(amax, __float_as_uint(ln_value(v[k].y, mean, rstd, gamma, beta, c + 1)) & 0x7FFFFFFFu);
+          amax = max(amax, __float_as_uint(ln_value(v[k].z, mean, rstd, gamma, beta, c + 2)) & 0x7FFFFFFFu);
+          amax = max(amax, __float_as_uint(ln_value(v[k].w, mean, rstd, gamma, beta, c + 3)) & 0x7FFFFFFFu);
+        }
+      }
+    } else {
+      float s = 0.0f;
+      for (int64_t c = lane; c < D; c += 64) s += row[c];
+      const float mean = wave_sum(s) / static_cast<float>(D);
+      float v = 0.0f;
+      for (int64_t c = lane; c < D; c += 64) {
+        const float d = row[c] - mean;
+        v += d * d;
+      }
+      const float var = wave_sum(v) / static_cast<float>(D);
+      const float rstd = 1.0f / sqrtf(var + eps);
+      if (lane == 0) {
+        stats[2 * m] = mean;
+        stats[2 * m + 1] = rstd;
+      }
+      for (int64_t c = lane; c < D; c += 64)
+        amax = max(amax, __float_as_uint(ln_value(row[c], mean, rstd, gamma, beta, c)) & 0x7FFFFFFFu);
     }
-    const float var = wave_sum(v) / static_cast<float>(D);
-    const float rstd = 1.0f / sqrtf(var + eps);
-    if (lane == 0) {
-      stats[2 * m] = mean;
-      stats[2 * m + 1] = rstd;
-    }
-    for (int64_t c = lane; c < D; c += 64)
-      amax = max(amax, __float_as_uint(ln_value(row[c], mean, rstd, gamma, beta, c)) & 0x7FFFFFFFu);
   }
   amax = wave_max_u(amax);
   if (lane == 0) sm[wave] = amax;
@@ -74,9 +119,18 @@ __global__ __launch_bounds__(kThreads) void ln_stats_kernel(const float *__restr
   if (threadIdx.x == 0) partial[blockIdx.x] = max(max(sm[0], sm[1]), max(sm[2], sm[3]));
 }
 
+__device__ __forceinline__ int8_t ln_code(float v, float s, float fq) {
+  const float t = (s == 0.0f) ? 0.0f : v / s;
+  float r = floorf(t + 0.5f);
+  r = fminf(fmaxf(r, -fq), fq);
+  return static_cast<int8_t>(static_cast<int>(r));
+}
+
 // Pass 2: fold the block maxima into the scale (Fig. 2: max / qmax), recompute the normalised
 // values from x and the stored row statistics, quantize (divide, + 0.5, floor), write codes
-// and, when asked, the float32 values themselves.
+// and, when asked, the float32 values themselves.  VEC: four columns per lane and access
+// (D % 4 == 0, 16-byte aligned x and y_out, 4-byte aligned q).
+template <bool VEC>
 __global__ __launch_bounds__(kThreads) void ln_quantize_kernel(const float *__restrict__ x, int64_t M, int64_t D,
                                                                const float *__restrict__ gamma,
                                                                const float *__restrict__ beta,
@@ -102,14 +156,26 @@ __global__ __launch_bounds__(kThreads) void ln_quantize_kernel(const float *__re
   for (int64_t m = static_cast<int64_t>(blockIdx.x) * 4 + wave; m < M; m += static_cast<int64_t>(gridDim.x) * 4) {
     const float *row = x + m * D;
     const float mean = stats[2 * m], rstd = stats[2 * m + 1];
-    for (int64_t c = lane; c < D; c += 64) {
-      const float v = ln_value(row[c], mean, rstd, gamma, beta, c);
-      if (y_out) y_out[m * D + c] = v;
-      if (q) {
-        const float t = (s == 0.0f) ? 0.0f : v / s;
-        float r = floorf(t + 0.5f);
-        r = fminf(fmaxf(r, -fq), fq);
-        q[m * D + c] = static_cast<int8_t>(static_cast<int>(r));
+    if constexpr (VEC) {
+      for (int64_t c = 4 * lane; c < D; c += 256) {
+        const v4f xv = *reinterpret_cast<const v4f *>(row + c);
+        v4f y;
+        y.x = ln_value(xv.x, mean, rstd, gamma, beta, c);
+        y.y = ln_value(xv.y, mean, rstd, gamma, beta, c + 1);
+        y.z = ln_value(xv.z, mean, rstd, gamma, beta, c + 2);
+        y.w = ln_value(xv.w, mean, rstd, gamma, beta, c + 3);
+        if (y_out) *reinterpret_cast<v4f *>(y_out + m * D + c) = y;
+        if (q) {
+          const uint32_t b0 = static_cast<uint8_t>(ln_code(y.x, s, fq)), b1 = static_cast<uint8_t>(ln_code(y.y, s, fq));
+          const uint32_t b2 = static_cast<uint8_t>(ln_code(y.z, s, fq)), b3 = static_cast<uint8_t>(ln_code(y.w, s, fq));
+          *reinterpret_cast<uint32_t *>(q + m * D + c) = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
+        }
+      }
+    } else {
+      for (int64_t c = lane; c < D; c += 64) {
+        const float v = ln_value(row[c], mean, rstd, gamma, beta, c);
+        if (y_out) y_out[m * D + c] = v;
+        if (q) q[m * D + c] = ln_code(v, s, fq);
       }
     }
   }
@@ -251,10 +317,16 @@ aqt_status launch_layernorm_quantize(const float *x, int64_t M, int64_t D, const
                            : reinterpret_cast<float *>(static_cast<uint8_t *>(ws) +
                                                        align_up(kMaxPartials * sizeof(uint32_t), 256));
   const int g = grid_cap(M, 4, 2048);
-  ln_stats_kernel<<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, eps, stats, partial);
+  const bool vec = (D % 4 == 0) && reinterpret_cast<uintptr_t>(x) % 16 == 0 &&
+                   (!y_out || reinterpret_cast<uintptr_t>(y_out) % 16 == 0) &&
+                   (!q || reinterpret_cast<uintptr_t>(q) % 4 == 0);
+  if (vec && D <= 512) ln_stats_kernel<2><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, eps, stats, partial);
+  else if (vec && D <= 1024) ln_stats_kernel<4><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, eps, stats, partial);
+  else ln_stats_kernel<0><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, eps, stats, partial);
   AQT_HIP(hipGetLastError());
-  ln_quantize_kernel<<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, stats, partial, g, q ? qmax_of(bits) : 1, q, scale,
-                                             y_out, dev_status);
+  const int qm = q ? qmax_of(bits) : 1;
+  if (vec) ln_quantize_kernel<true><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, stats, partial, g, qm, q, scale, y_out, dev_status);
+  else ln_quantize_kernel<false><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, stats, partial, g, qm, q, scale, y_out, dev_status);
   AQT_HIP(hipGetLastError());
   return AQT_OK;
 }
