@@ -85,6 +85,8 @@ typedef struct aqt_saved {
   uint32_t *mask_w;  /* nullable: ceil(K*N/32) words over W's [K,N] order               */
   float *dact;       /* nullable: [M,N] derivative factors of the activation (Swish / GLU);  */
                      /* written by the forward when given, required by the backward then   */
+  void *wprep;       /* nullable: the forward operand in matrix-core order (aqt_prepare_weights), */
+                     /* read by the module calls of a layer whose policy says weights_ready    */
 } aqt_saved;
 
 const char *aqt_status_string(aqt_status s); /* host, static storage */
@@ -312,8 +314,13 @@ aqt_status aqt_fake_matmul_f32(const int8_t *xq, const int8_t *wq_kn, int64_t M,
  * activations (the weight-only modes).
  */
 typedef struct aqt_dense_policy {
-  int bits_w; /* 2..8 */
-  int bits_x; /* 2..8, or 0 = float32 activations */
+  int bits_w;        /* 2..8 */
+  int bits_x;        /* 2..8, or 0 = float32 activations */
+  int weights_ready; /* 0: the call quantizes the float32 weights it is given (training: they change every step).
+                        1: serving, what you train is what you serve: the layer's aqt_saved already holds
+                        wq_packed and s_w (aqt_quantize_weights) and, if wprep is not NULL, the operand in
+                        matrix-core order (aqt_prepare_weights); the float32 weight pointer is ignored and may
+                        be NULL.  Module calls (aqt_ffn_fwd, aqt_mhsa_fwd, aqt_conv_module_fwd, the layer). */
 } aqt_dense_policy;
 
 /* The eight dense layers of one Conformer encoder layer (Sec. 3.2). */

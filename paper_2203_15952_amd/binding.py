@@ -49,11 +49,11 @@ class AqtError(RuntimeError):
 class aqt_saved(ctypes.Structure):
     _fields_ = [("xq", ctypes.c_void_p), ("s_x", ctypes.c_void_p), ("mask_x", ctypes.c_void_p),
                 ("wq_packed", ctypes.c_void_p), ("wq_kn", ctypes.c_void_p), ("s_w", ctypes.c_void_p),
-                ("mask_w", ctypes.c_void_p), ("dact", ctypes.c_void_p)]
+                ("mask_w", ctypes.c_void_p), ("dact", ctypes.c_void_p), ("wprep", ctypes.c_void_p)]
 
 
 class aqt_dense_policy(ctypes.Structure):
-    _fields_ = [("bits_w", ctypes.c_int), ("bits_x", ctypes.c_int)]
+    _fields_ = [("bits_w", ctypes.c_int), ("bits_x", ctypes.c_int), ("weights_ready", ctypes.c_int)]
 
 
 class aqt_layer_policy(ctypes.Structure):
@@ -384,6 +384,7 @@ class Saved:
     def __init__(self, M: int, K: int, N: int, bits_w: int, device="cuda", masks: bool = False,
                  dact: bool = False):
         self.M, self.K, self.N, self.bits_w = M, K, N, bits_w
+        self.wprep = None
         self.dact = torch.empty((M, N), dtype=torch.float32, device=device) if dact else None
         self.xq = torch.empty((M, K), dtype=torch.int8, device=device)
         self.s_x = torch.empty(1, dtype=torch.float32, device=device)
@@ -398,8 +399,16 @@ class Saved:
         def a(t):
             return None if t is None else t.data_ptr()
         self.c = aqt_saved(a(self.xq), a(self.s_x), a(self.mask_x), a(self.wq_packed), a(self.wq_kn),
-                           a(self.s_w), a(self.mask_w), a(self.dact))
+                           a(self.s_w), a(self.mask_w), a(self.dact), a(self.wprep))
         return self
+
+    def prepare(self, w):
+        """Serving: quantize the float32 weights w [K,N] into this layer's buffers once and, where the shape
+        has one, keep the operand in matrix-core order; module calls with weights_ready = 1 then skip both."""
+        aqt_quantize_weights(w, self.bits_w, wq_packed=self.wq_packed, s_w=self.s_w, wq_kn=self.wq_kn)
+        if int(lib().aqt_prepared_weight_bytes(self.K, self.N, self.bits_w)):
+            self.wprep = aqt_prepare_weights(self.wq_packed, self.K, self.N, self.bits_w)
+        return self.refresh()
 
 
 def aqt_dense_fwd(x, w, bits_x: int, bits_w: int, *, bias=None, epilogue: int = AQT_EPI_NONE, y=None,
@@ -494,7 +503,18 @@ class FfnSaved:
         self.xn = torch.empty((M, D), dtype=torch.float32, device=device)
         self.row_stats = torch.empty((M, 2), dtype=torch.float32, device=device)
         self.policy = (aqt_dense_policy * 2)(aqt_dense_policy(bw1, bx1), aqt_dense_policy(bw2, bx2))
+        self.refresh()
+
+    def refresh(self):
         self.c = aqt_ffn_saved(self.l1.c, self.l2.c, self.h.data_ptr(), self.xn.data_ptr(), self.row_stats.data_ptr())
+        return self
+
+    def prepare(self, w1, w2):
+        """Serving: quantize both weight matrices once; later calls skip the weight quantizers."""
+        self.l1.prepare(w1)
+        self.l2.prepare(w2)
+        self.policy[0].weights_ready = self.policy[1].weights_ready = 1
+        return self.refresh()
 
 
 def aqt_ffn_fwd(x, w1, b1, w2, b2, saved: FfnSaved, *, gamma=None, beta=None, eps: float = 1e-6, y=None, ws=None,
@@ -502,7 +522,7 @@ def aqt_ffn_fwd(x, w1, b1, w2, b2, saved: FfnSaved, *, gamma=None, beta=None, ep
     """aqt_ffn_fwd: y = dense(swish(dense(layernorm(x), w1) + b1), w2) + b2 at the saved policy's precisions."""
     _dev(x, torch.float32, "x")
     M, D = x.shape
-    H = w1.shape[1]
+    H = saved.H
     y = torch.empty((M, D), dtype=torch.float32, device=x.device) if y is None else y
     ws = workspace(aqt_workspace_bytes(AQT_OP_FFN_FWD, M, D, H), x.device) if ws is None else ws
     st = lib().aqt_ffn_fwd(_ptr(x), _ptr(gamma), _ptr(beta), eps, _ptr(w1), _ptr(b1), _ptr(w2), _ptr(b2), M, D, H,
@@ -576,8 +596,19 @@ class ConvSaved:
         self.dfac = torch.empty((M, D), dtype=torch.float32, device=device)
         self.row_stats = torch.empty((M, 2), dtype=torch.float32, device=device)
         self.policy = (aqt_dense_policy * 2)(aqt_dense_policy(bw1, bx1), aqt_dense_policy(bw2, bx2))
+        self.refresh()
+
+    def refresh(self):
         self.c = aqt_conv_saved(self.pw1.c, self.pw2.c, self.g.data_ptr(), self.s.data_ptr(), self.dfac.data_ptr(),
                                 self.row_stats.data_ptr())
+        return self
+
+    def prepare(self, w1, w2):
+        """Serving: quantize both pointwise weight matrices once; later calls skip the weight quantizers."""
+        self.pw1.prepare(w1)
+        self.pw2.prepare(w2)
+        self.policy[0].weights_ready = self.policy[1].weights_ready = 1
+        return self.refresh()
 
 
 def aqt_conv_module_fwd(x, w1, b1, w_dw, b_dw, w2, b2, saved: ConvSaved, *, pad_left: int, gamma=None, beta=None,
@@ -639,8 +670,19 @@ class MhsaSaved:
         self.ctx = torch.empty((M, D), dtype=torch.float32, device=device)
         self.row_stats = torch.empty((M, 2), dtype=torch.float32, device=device)
         self.policy = (aqt_dense_policy * 2)(aqt_dense_policy(bw1, bx1), aqt_dense_policy(bw2, bx2))
+        self.refresh()
+
+    def refresh(self):
         self.c = aqt_mhsa_saved(self.qkv.c, self.out.c, self.qkv_f.data_ptr(), self.ctx.data_ptr(),
                                 self.row_stats.data_ptr())
+        return self
+
+    def prepare(self, wqkv, wo):
+        """Serving: quantize both projection matrices once; later calls skip the weight quantizers."""
+        self.qkv.prepare(wqkv)
+        self.out.prepare(wo)
+        self.policy[0].weights_ready = self.policy[1].weights_ready = 1
+        return self.refresh()
 
 
 def aqt_mhsa_fwd(x, wqkv, bqkv, wo, bo, saved: MhsaSaved, heads: int, *, left: int = -1, right: int = -1, gamma=None,
@@ -681,8 +723,25 @@ class LayerSaved:
         self.conv = ConvSaved(B, T, D, pair(policy.conv_pw1, policy.conv_pw2), device)
         self.r = [torch.empty((M, D), dtype=torch.float32, device=device) for _ in range(4)]
         self.m = torch.empty((M, D), dtype=torch.float32, device=device)
+        self.refresh()
+
+    def refresh(self):
         self.c = aqt_conformer_layer_saved(self.ffn1.c, self.ffn2.c, self.att.c, self.conv.c,
                                            *[t.data_ptr() for t in self.r], self.m.data_ptr())
+        return self
+
+    def prepare(self, weights: dict):
+        """Serving: quantize the eight weight matrices of the layer once (names as in LAYER_WEIGHT_NAMES) and
+        mark every dense layer of the policy weights_ready; later layer calls skip the weight quantizers."""
+        self.ffn1.prepare(weights["ffn1_w1"], weights["ffn1_w2"])
+        self.ffn2.prepare(weights["ffn2_w1"], weights["ffn2_w2"])
+        self.att.prepare(weights["att_wqkv"], weights["att_wo"])
+        self.conv.prepare(weights["conv_w1"], weights["conv_w2"])
+        pol = aqt_layer_policy.from_buffer_copy(self.policy)
+        for name, _ in aqt_layer_policy._fields_:
+            getattr(pol, name).weights_ready = 1
+        self.policy = pol
+        return self.refresh()
 
 
 def aqt_conformer_layer_fwd(x, weights: dict, saved: LayerSaved, *, B: int, T: int, H: int, heads: int, kw: int,

@@ -112,7 +112,33 @@ bool conv_shape_ok(int64_t B, int64_t T, int64_t C, int kw, int pad_left) {
          B <= (int64_t(1) << 40) / T;
 }
 
-bool policy_ok(const aqt_dense_policy &p) { return bits_ok(p.bits_w) && (p.bits_x == 0 || bits_ok(p.bits_x)); }
+bool policy_ok(const aqt_dense_policy &p) {
+  return bits_ok(p.bits_w) && (p.bits_x == 0 || bits_ok(p.bits_x)) && (p.weights_ready == 0 || p.weights_ready == 1);
+}
+
+// The weight side of one dense layer inside a module call.  Training: quantize w now (the quantizer
+// also emits the matrix-core operand into `wfrag` when the contraction kernel takes one).  Serving
+// (weights_ready): nothing to do; the prepared operand of the layer is used if there is one.
+struct WeightSide {
+  void *operand;   // what launch_dense_fwd_q gets as its workspace
+  bool prepared;   // whether it already holds the matrix-core operand
+};
+aqt_status weight_side(const aqt_dense_policy &p, const float *w, const aqt_saved &l, int64_t M, int64_t K, int64_t N,
+                       int epilogue, uint32_t *wpart, void *wfrag, hipStream_t st, int32_t *dev_status,
+                       WeightSide *out) {
+  const bool takes = p.bits_x && fwd_q_takes_fragments(M, K, N, epilogue) && reinterpret_cast<uintptr_t>(l.xq) % 16 == 0;
+  if (p.weights_ready) {
+    const bool have = takes && l.wprep && reinterpret_cast<uintptr_t>(l.wprep) % 16 == 0;
+    out->operand = have ? l.wprep : wfrag;
+    out->prepared = have;
+    return AQT_OK;
+  }
+  if (!w) return AQT_ERR_INVALID_ARG;
+  out->operand = wfrag;
+  out->prepared = takes;
+  return launch_quantize_weights(w, K, N, p.bits_w, l.wq_packed, l.s_w, l.wq_kn, l.mask_w, wpart, st, dev_status,
+                                 takes ? wfrag : nullptr);
+}
 
 // The int32 accumulator must hold K * qmax_x * qmax_w; packed (<= 4 bit) weights enter the
 // matrix cores as 16 * code, so their sums carry a factor 16 until the final shift.
@@ -403,7 +429,7 @@ aqt_status aqt_policy_preset(int pattern, int n_layers, int k, int bits_w, int b
   if (pattern < AQT_POLICY_ALL || pattern > AQT_POLICY_FIRST_K) return AQT_ERR_INVALID_ARG;
   if (!bits_ok(bits_w) || !(bits_x == 0 || bits_ok(bits_x))) return AQT_ERR_UNSUPPORTED;
   if (pattern == AQT_POLICY_FIRST_K && (k < 0 || k > n_layers)) return AQT_ERR_INVALID_ARG;
-  const aqt_dense_policy low = {bits_w, bits_x}, base = {8, bits_x};   // Table 2: int8 for what is not selected
+  const aqt_dense_policy low = {bits_w, bits_x, 0}, base = {8, bits_x, 0};   // Table 2: int8 for what is not selected
   for (int l = 0; l < n_layers; ++l) {
     bool sel = true;
     if (pattern == AQT_POLICY_EXCEPT_FIRST_LAST) sel = (l != 0 && l != n_layers - 1);
@@ -439,8 +465,7 @@ aqt_status aqt_ffn_fwd(const float *x, const float *ln_gamma, const float *ln_be
                        const float *b1, const float *w2, const float *b2, int64_t M, int64_t D, int64_t H,
                        const aqt_dense_policy *policy, float *y, const aqt_ffn_saved *saved, void *ws,
                        size_t ws_bytes, void *stream, int32_t *dev_status) {
-  if (!x || !w1 || !w2 || !y || !policy || !saved || !shape_ok(M, D) || H < 1 || !(ln_eps >= 0.0f))
-    return AQT_ERR_INVALID_ARG;
+  if (!x || !y || !policy || !saved || !shape_ok(M, D) || H < 1 || !(ln_eps >= 0.0f)) return AQT_ERR_INVALID_ARG;
   const aqt_dense_policy p1 = policy[0], p2 = policy[1];
   if (!policy_ok(p1) || !policy_ok(p2)) return AQT_ERR_UNSUPPORTED;
   const aqt_saved &l1 = saved->l1, &l2 = saved->l2;
@@ -454,19 +479,15 @@ aqt_status aqt_ffn_fwd(const float *x, const float *ln_gamma, const float *ln_be
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   // normalisation (+ first quantizer), first weights, first contraction with Swish
-  const bool frag1 = p1.bits_x && fwd_q_takes_fragments(M, D, H, AQT_EPI_SWISH) &&
-                     reinterpret_cast<uintptr_t>(l1.xq) % 16 == 0;
-  const bool frag2 = p2.bits_x && fwd_q_takes_fragments(M, H, D, AQT_EPI_NONE) &&
-                     reinterpret_cast<uintptr_t>(l2.xq) % 16 == 0;
-  AQT_TRY(launch_quantize_weights(w1, D, H, p1.bits_w, l1.wq_packed, l1.s_w, l1.wq_kn, l1.mask_w, f.wpart1, st,
-                                  dev_status, frag1 ? f.wfrag1 : nullptr));
+  WeightSide s1, s2;
+  AQT_TRY(weight_side(p1, w1, l1, M, D, H, AQT_EPI_SWISH, f.wpart1, f.wfrag1, st, dev_status, &s1));
   const bool want_absmax = p2.bits_x != 0;
   if (p1.bits_x) {
     AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, saved->xn,
                                       saved->row_stats, f.ln, st, dev_status));
     AQT_TRY(launch_dense_fwd_q(l1.xq, l1.s_x, l1.wq_packed, l1.s_w, M, D, H, p1.bits_w, b1, AQT_EPI_SWISH, saved->h,
-                               nullptr, want_absmax ? reinterpret_cast<uint32_t *>(f.h_absmax) : nullptr, f.wfrag1,
-                               st, l1.dact, frag1));
+                               nullptr, want_absmax ? reinterpret_cast<uint32_t *>(f.h_absmax) : nullptr, s1.operand,
+                               st, l1.dact, s1.prepared));
   } else {
     AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, 8, nullptr, nullptr, saved->xn,
                                       saved->row_stats, f.ln, st, dev_status));
@@ -474,8 +495,7 @@ aqt_status aqt_ffn_fwd(const float *x, const float *ln_gamma, const float *ln_be
                                    f.wfrag1, st));
   }
   // second quantizer (one pass when the producer emitted max|h|), second weights, second contraction
-  AQT_TRY(launch_quantize_weights(w2, H, D, p2.bits_w, l2.wq_packed, l2.s_w, l2.wq_kn, l2.mask_w, f.wpart2, st,
-                                  dev_status, frag2 ? f.wfrag2 : nullptr));
+  AQT_TRY(weight_side(p2, w2, l2, M, H, D, AQT_EPI_NONE, f.wpart2, f.wfrag2, st, dev_status, &s2));
   if (p2.bits_x) {
     if (p1.bits_x) {
       AQT_TRY(launch_quantize_with_absmax(saved->h, M, H, H, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),
@@ -485,7 +505,7 @@ aqt_status aqt_ffn_fwd(const float *x, const float *ln_gamma, const float *ln_be
                               static_cast<float *>(f.ln), st, dev_status));
     }
     return launch_dense_fwd_q(l2.xq, l2.s_x, l2.wq_packed, l2.s_w, M, H, D, p2.bits_w, b2, AQT_EPI_NONE, y, nullptr,
-                              nullptr, f.wfrag2, st, nullptr, frag2);
+                              nullptr, s2.operand, st, nullptr, s2.prepared);
   }
   return launch_dense_fwd_wonly(saved->h, l2.wq_packed, l2.s_w, M, H, D, p2.bits_w, b2, AQT_EPI_NONE, y, f.wfrag2, st);
 }
@@ -537,8 +557,7 @@ aqt_status aqt_conv_module_fwd(const float *x, const float *ln_gamma, const floa
                                int64_t B, int64_t T, int64_t D, int kw, int pad_left, const aqt_dense_policy *policy,
                                float *y, const aqt_conv_saved *saved, void *ws, size_t ws_bytes, void *stream,
                                int32_t *dev_status) {
-  if (!x || !w1 || !w_dw || !w2 || !y || !policy || !saved || !conv_shape_ok(B, T, D, kw, pad_left) ||
-      !(ln_eps >= 0.0f))
+  if (!x || !w_dw || !y || !policy || !saved || !conv_shape_ok(B, T, D, kw, pad_left) || !(ln_eps >= 0.0f))
     return AQT_ERR_INVALID_ARG;
   const aqt_dense_policy p1 = policy[0], p2 = policy[1];
   if (!policy_ok(p1) || !policy_ok(p2) || p1.bits_x == 0 || p2.bits_x == 0) return AQT_ERR_UNSUPPORTED;
@@ -553,24 +572,21 @@ aqt_status aqt_conv_module_fwd(const float *x, const float *ln_gamma, const floa
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   // normalisation + first quantizer, first pointwise convolution with the GLU
-  const bool frag1 = fwd_q_takes_fragments(M, D, 2 * D, AQT_EPI_GLU) && reinterpret_cast<uintptr_t>(l1.xq) % 16 == 0;
-  const bool frag2 = fwd_q_takes_fragments(M, D, D, AQT_EPI_NONE) && reinterpret_cast<uintptr_t>(l2.xq) % 16 == 0;
-  AQT_TRY(launch_quantize_weights(w1, D, 2 * D, p1.bits_w, l1.wq_packed, l1.s_w, l1.wq_kn, l1.mask_w, f.wpart1, st,
-                                  dev_status, frag1 ? f.wfrag1 : nullptr));
+  WeightSide s1, s2;
+  AQT_TRY(weight_side(p1, w1, l1, M, D, 2 * D, AQT_EPI_GLU, f.wpart1, f.wfrag1, st, dev_status, &s1));
   AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, nullptr,
                                     saved->row_stats, f.ln, st, dev_status));
   AQT_TRY(launch_dense_fwd_q(l1.xq, l1.s_x, l1.wq_packed, l1.s_w, M, D, 2 * D, p1.bits_w, b1, AQT_EPI_GLU, saved->g,
-                             nullptr, nullptr, f.wfrag1, st, l1.dact, frag1));
+                             nullptr, nullptr, s1.operand, st, l1.dact, s1.prepared));
   // depthwise convolution, normalisation, Swish; max|s| for the one-pass quantizer
   AQT_TRY(launch_dwconv_fwd(saved->g, w_dw, b_dw, norm_scale, norm_shift, 1, B, T, D, kw, pad_left, saved->s,
                             saved->dfac, reinterpret_cast<uint32_t *>(f.h_absmax), st));
   // second pointwise convolution
-  AQT_TRY(launch_quantize_weights(w2, D, D, p2.bits_w, l2.wq_packed, l2.s_w, l2.wq_kn, l2.mask_w, f.wpart2, st,
-                                  dev_status, frag2 ? f.wfrag2 : nullptr));
+  AQT_TRY(weight_side(p2, w2, l2, M, D, D, AQT_EPI_NONE, f.wpart2, f.wfrag2, st, dev_status, &s2));
   AQT_TRY(launch_quantize_with_absmax(saved->s, M, D, D, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),
                                       l2.xq, l2.s_x, l2.mask_x, st, dev_status));
   return launch_dense_fwd_q(l2.xq, l2.s_x, l2.wq_packed, l2.s_w, M, D, D, p2.bits_w, b2, AQT_EPI_NONE, y, nullptr,
-                            nullptr, f.wfrag2, st, nullptr, frag2);
+                            nullptr, s2.operand, st, nullptr, s2.prepared);
 }
 
 aqt_status aqt_conv_module_bwd(const float *dy, const aqt_conv_saved *saved, const float *w_dw, int64_t B, int64_t T,
@@ -612,8 +628,7 @@ aqt_status aqt_mhsa_fwd(const float *x, const float *ln_gamma, const float *ln_b
                         const float *bqkv, const float *wo, const float *bo, int64_t B, int64_t T, int64_t D,
                         int heads, int left_context, int right_context, const aqt_dense_policy *policy, float *y,
                         const aqt_mhsa_saved *saved, void *ws, size_t ws_bytes, void *stream, int32_t *dev_status) {
-  if (!x || !wqkv || !wo || !y || !policy || !saved || B < 1 || T < 1 || D < 1 || heads < 1 || D % heads ||
-      !(ln_eps >= 0.0f))
+  if (!x || !y || !policy || !saved || B < 1 || T < 1 || D < 1 || heads < 1 || D % heads || !(ln_eps >= 0.0f))
     return AQT_ERR_INVALID_ARG;
   if (!attention_shape_ok(B, T, D, heads)) return AQT_ERR_UNSUPPORTED;
   const aqt_dense_policy p1 = policy[0], p2 = policy[1];
@@ -627,25 +642,22 @@ aqt_status aqt_mhsa_fwd(const float *x, const float *ln_gamma, const float *ln_b
   FfnWorkspace f = carve_ffn_fwd(ws, M, D, 3 * D);
   if (!ws || ws_bytes < f.total) return AQT_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const bool frag1 = fwd_q_takes_fragments(M, D, 3 * D, AQT_EPI_NONE) && reinterpret_cast<uintptr_t>(l1.xq) % 16 == 0;
-  const bool frag2 = fwd_q_takes_fragments(M, D, D, AQT_EPI_NONE) && reinterpret_cast<uintptr_t>(l2.xq) % 16 == 0;
   // normalisation + first quantizer, fused projection of queries, keys and values
-  AQT_TRY(launch_quantize_weights(wqkv, D, 3 * D, p1.bits_w, l1.wq_packed, l1.s_w, l1.wq_kn, l1.mask_w, f.wpart1, st,
-                                  dev_status, frag1 ? f.wfrag1 : nullptr));
+  WeightSide s1, s2;
+  AQT_TRY(weight_side(p1, wqkv, l1, M, D, 3 * D, AQT_EPI_NONE, f.wpart1, f.wfrag1, st, dev_status, &s1));
   AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, nullptr,
                                     saved->row_stats, f.ln, st, dev_status));
   AQT_TRY(launch_dense_fwd_q(l1.xq, l1.s_x, l1.wq_packed, l1.s_w, M, D, 3 * D, p1.bits_w, bqkv, AQT_EPI_NONE,
-                             saved->qkv_f, nullptr, nullptr, f.wfrag1, st, nullptr, frag1));
+                             saved->qkv_f, nullptr, nullptr, s1.operand, st, nullptr, s1.prepared));
   // attention in float32; max|ctx| for the one-pass quantizer
   AQT_TRY(launch_attention(saved->qkv_f, B, T, D, heads, left_context, right_context, saved->ctx,
                            reinterpret_cast<uint32_t *>(f.h_absmax), st));
   // output projection
-  AQT_TRY(launch_quantize_weights(wo, D, D, p2.bits_w, l2.wq_packed, l2.s_w, l2.wq_kn, l2.mask_w, f.wpart2, st,
-                                  dev_status, frag2 ? f.wfrag2 : nullptr));
+  AQT_TRY(weight_side(p2, wo, l2, M, D, D, AQT_EPI_NONE, f.wpart2, f.wfrag2, st, dev_status, &s2));
   AQT_TRY(launch_quantize_with_absmax(saved->ctx, M, D, D, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),
                                       l2.xq, l2.s_x, l2.mask_x, st, dev_status));
   return launch_dense_fwd_q(l2.xq, l2.s_x, l2.wq_packed, l2.s_w, M, D, D, p2.bits_w, bo, AQT_EPI_NONE, y, nullptr,
-                            nullptr, f.wfrag2, st, nullptr, frag2);
+                            nullptr, s2.operand, st, nullptr, s2.prepared);
 }
 
 aqt_status aqt_residual_add(const float *x, const float *m, float alpha, float *out, int64_t n, void *stream) {

@@ -148,3 +148,40 @@ def test_conformer_layer_rejects_float_activations_in_attention():
         B.aqt_conformer_layer_fwd(torch.zeros((B_ * T, D), device="cuda"), w, sv, B=B_, T=T, H=H, heads=2, kw=15,
                                   pad_left=14)
     assert e.value.status == B.AQT_ERR_UNSUPPORTED
+
+
+def test_serving_form_on_prepared_weights_equals_the_training_forward():
+    # "what you train is what you serve": with the weights quantized once and kept in matrix-core order, the
+    # layer (and each module) gives the very bits of the call that quantizes its float32 weights every time
+    B_, T, D, H, heads, kw, pl = 4, 160, 256, 1024, 4, 15, 14
+    M = B_ * T
+    say("serving form", B_, T, D, H)
+    w = layer_weights(810, D, H, kw)
+    wd = {k: dev(v) for k, v in w.items()}
+    x_d = dev(np.random.default_rng(811).standard_normal((M, D)).astype(F))
+    for pattern, bits_w in ((B.AQT_POLICY_ALL, 8), (B.AQT_POLICY_EXCEPT_ATTENTION, 4)):
+        pol = B.aqt_policy_preset(pattern, 1, 0, bits_w, 8)[0]
+        y_train, _ = run_layer(x_d, wd, pol, B_, T, D, H, heads, kw, pl, 23, 0)
+        sv = B.LayerSaved(B_, T, D, H, pol).prepare(wd)
+        assert sv.policy.ffn1_in.weights_ready == 1 and sv.ffn1.l1.wprep is not None
+        no_w = {k: v for k, v in wd.items() if k not in ("ffn1_w1", "ffn1_w2", "ffn2_w1", "ffn2_w2", "att_wqkv", "att_wo",
+                                                         "conv_w1", "conv_w2")}
+        for _ in range(2):
+            y_serve = B.aqt_conformer_layer_fwd(x_d, no_w, sv, B=B_, T=T, H=H, heads=heads, kw=kw, pad_left=pl, left=23,
+                                                right=0)
+            np.testing.assert_array_equal(host(y_serve), host(y_train))
+    # a module alone, general-kernel shapes (no prepared operand exists: the packed codes are used as they are)
+    Ms, Ds, Hs = 70, 40, 24
+    rng = np.random.default_rng(812)
+    xs = dev(rng.standard_normal((Ms, Ds)).astype(F))
+    w1, w2 = dev((rng.standard_normal((Ds, Hs)) / 6).astype(F)), dev((rng.standard_normal((Hs, Ds)) / 5).astype(F))
+    a = B.FfnSaved(Ms, Ds, Hs, ((4, 8), (8, 8)))
+    y_a = B.aqt_ffn_fwd(xs, w1, None, w2, None, a)
+    b = B.FfnSaved(Ms, Ds, Hs, ((4, 8), (8, 8))).prepare(w1, w2)
+    assert b.l1.wprep is None
+    y_b = B.aqt_ffn_fwd(xs, None, None, None, None, b)
+    np.testing.assert_array_equal(host(y_b), host(y_a))
+    # training mode without weights is an argument error
+    with pytest.raises(B.AqtError) as e:
+        B.aqt_ffn_fwd(xs, None, None, w2, None, a)
+    assert e.value.status == B.AQT_ERR_INVALID_ARG
