@@ -72,9 +72,28 @@ def main():
     out = {"shape": {"utterances": Bc, "frames": T, "d_model": D, "d_ff": H, "heads": a.heads, "kernel": kw},
            "policy": {"pattern": a.pattern, "bits_w": a.bits_w, "bits_x": a.bits_x},
            "weights": "quantized once (serving)" if a.serving else "quantized in every call (training)", "unit": "ms"}
-    out["encoder_layer_fwd"] = timed(lambda: B.aqt_conformer_layer_fwd(
-        x, w, sv, B=Bc, T=T, H=H, heads=a.heads, kw=kw, pad_left=a.pad_left, left=a.left_context,
-        right=a.right_context, y=y, ws=ws, dev_status=status), a.steps, a.warmup)
+
+    def layer():
+        return B.aqt_conformer_layer_fwd(x, w, sv, B=Bc, T=T, H=H, heads=a.heads, kw=kw, pad_left=a.pad_left,
+                                         left=a.left_context, right=a.right_context, y=y, ws=ws, dev_status=status)
+
+    out["encoder_layer_fwd"] = timed(layer, a.steps, a.warmup)
+    # the same call recorded once into a HIP graph and replayed: the library allocates nothing and launches
+    # only kernels on the caller's stream, so the whole layer is capturable
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(2):
+            layer()
+    torch.cuda.current_stream().wait_stream(side)
+    with torch.cuda.graph(graph):
+        layer()
+    eager = y.clone()
+    graph.replay()
+    torch.cuda.synchronize()
+    out["graph_replay_equals_eager"] = bool(torch.equal(y, eager))
+    out["encoder_layer_fwd_graph_replay"] = timed(graph.replay, a.steps, a.warmup)
     out["ffn_module_fwd"] = timed(lambda: B.aqt_ffn_fwd(x, w["ffn1_w1"], None, w["ffn1_w2"], None, sv.ffn1, y=y, ws=ws,
                                                         dev_status=status), a.steps, a.warmup)
     out["mhsa_module_fwd"] = timed(lambda: B.aqt_mhsa_fwd(x, w["att_wqkv"], None, w["att_wo"], None, sv.att, a.heads,

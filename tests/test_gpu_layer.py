@@ -185,3 +185,47 @@ def test_serving_form_on_prepared_weights_equals_the_training_forward():
     with pytest.raises(B.AqtError) as e:
         B.aqt_ffn_fwd(xs, None, None, w2, None, a)
     assert e.value.status == B.AQT_ERR_INVALID_ARG
+
+
+def test_layer_call_replays_from_a_hip_graph():
+    # the library allocates nothing and only launches kernels on the caller's stream (its counters are cleared
+    # by small kernels, not by memsets), so a whole layer can be recorded once and replayed; every replay is
+    # checked against the eager result, with eager work and synchronisations in between
+    B_, T, D, H, heads, kw, pl = 3, 130, 256, 512, 4, 15, 14
+    M = B_ * T
+    say("layer in a HIP graph", B_, T, D, H)
+    wd = {k: dev(v) for k, v in layer_weights(820, D, H, kw).items()}
+    pol = B.aqt_policy_preset(B.AQT_POLICY_EXCEPT_ATTENTION, 1, 0, 4, 8)[0]
+    sv = B.LayerSaved(B_, T, D, H, pol)
+    rng = np.random.default_rng(821)
+    xs = [dev(rng.standard_normal((M, D)).astype(F)) for _ in range(3)]
+    x_in = torch.empty_like(xs[0])
+    y = torch.empty((M, D), dtype=torch.float32, device="cuda")
+    ws = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_CONFORMER_LAYER_FWD, M, D, H))
+    status = B.new_status()
+
+    def layer():
+        B.aqt_conformer_layer_fwd(x_in, wd, sv, B=B_, T=T, H=H, heads=heads, kw=kw, pad_left=pl, left=23, right=0, y=y,
+                                  ws=ws, dev_status=status)
+
+    eager = []
+    for x in xs:
+        x_in.copy_(x)
+        layer()
+        eager.append(host(y).copy())
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        layer()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        layer()
+    for rep in range(2):
+        for x, want in zip(xs, eager):
+            x_in.copy_(x)
+            graph.replay()
+            np.testing.assert_array_equal(host(y), want)
+            B.aqt_residual_add(x_in, x_in, 0.5)          # unrelated eager work between replays
+            torch.cuda.synchronize()
+    assert host(status)[0] == 0
