@@ -362,3 +362,30 @@ def attention(qkv, heads: int, left: int = -1, right: int = -1, want_mags: bool 
     if rc:
         raise ValueError(f"oracle_attention rc={rc}")
     return (ctx, smag, vmag) if want_mags else ctx
+
+
+def attention_bwd(qkv, dctx, heads: int, left: int = -1, right: int = -1):
+    """Gradient of attention() with respect to qkv for the upstream gradient dctx [B,T,D]; returns
+    (dqkv [B,T,3D] float64, the sums of the magnitudes of the terms)."""
+    qkv = _f32(qkv)
+    B, T, D3 = qkv.shape
+    D = D3 // 3
+    dctx = np.ascontiguousarray(dctx, np.float64).reshape(B, T, D)
+    dqkv, mag = np.empty((B, T, D3), np.float64), np.empty((B, T, D3), np.float64)
+    rc = _c().oracle_attention_bwd(_p(qkv), _p(dctx), ctypes.c_int64(B), ctypes.c_int64(T), ctypes.c_int64(D),
+                                   ctypes.c_int64(heads), ctypes.c_int64(left), ctypes.c_int64(right), _p(dqkv), _p(mag))
+    if rc:
+        raise ValueError(f"oracle_attention_bwd rc={rc}")
+    return dqkv, mag
+
+
+def layernorm_bwd(x, dy, gamma=None, eps: float = 1e-6):
+    """Gradient of layernorm(): returns (dx [M,D], dgamma [D], dbeta [D]), float64."""
+    x = _f32(x)
+    M, D = x.shape
+    dy = np.ascontiguousarray(dy, np.float64)
+    g = None if gamma is None else _f32(gamma)
+    dx, dg, db = np.empty((M, D), np.float64), np.empty(D, np.float64), np.empty(D, np.float64)
+    _c().oracle_layernorm_bwd(_p(x), ctypes.c_int64(M), ctypes.c_int64(D), _p(g), ctypes.c_double(eps), _p(dy), _p(dx),
+                              _p(dg), _p(db))
+    return dx, dg, db

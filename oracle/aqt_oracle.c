@@ -40,6 +40,8 @@
  *                         frames, the float core of the self-attention module
  *                         (Sec. 3.2: heads; Sec. 3.3: left / right context): the
  *                         textbook definition in float64; glue of the chained block.
+ *   oracle_attention_bwd, oracle_layernorm_bwd
+ *                         the chain rule through those two, written out, float64.
  *   oracle_fake_matmul_f32  Sec. 1 / Sec. 2.2: "fake" quantization carries the integer
  *                         codes in float32 and multiplies them with float
  *                         operations; sums that need more than 24 bits are rounded.
@@ -68,7 +70,10 @@
  * example, numpy's correlate per channel, the adjoint identity and central
  * differences for its gradients; the affine + Swish by closed-form values and
  * central differences; the attention by zero queries (window means), a one-hot
- * alignment, constant values, the zero-width window and scipy's softmax).  The paper prints
+ * alignment, constant values, the zero-width window and scipy's softmax; the
+ * backward of attention and normalisation by central differences of their
+ * forward functions, by the zero-width window and by the orthogonality of a
+ * normalised row's gradient to the constant and to the row itself).  The paper prints
  * no worked numeric example, so no pin comes from printed values.
  */
 #include <math.h>
@@ -663,6 +668,111 @@ int oracle_attention(const float *qkv, int64_t B, int64_t T, int64_t D, int64_t 
     free(s);
   }
   return 0;
+}
+
+/*
+ * Gradients of oracle_attention for an upstream gradient dctx [B,T,D] (float64), the chain
+ * rule through softmax and the two products written out:
+ *   dP_tj = dctx_t . v_j;   dS_tj = p_tj (dP_tj - sum_i p_ti dP_ti);
+ *   dq_t = sum_j dS_tj k_j / sqrt(dh);  dk_j = sum_t dS_tj q_t / sqrt(dh);  dv_j = sum_t p_tj dctx_t
+ * dqkv [B,T,3D] in the layout of qkv.  mag (nullable, same shape): the sums of the absolute
+ * values of the terms, with |dS| bounded by p (|dP| + sum_i p_i |dP_i|); only feeds error bounds.
+ */
+int oracle_attention_bwd(const float *qkv, const double *dctx, int64_t B, int64_t T, int64_t D, int64_t heads,
+                         int64_t left, int64_t right, double *dqkv, double *mag) {
+  if (heads < 1 || D % heads) return 2;
+  const int64_t dh = D / heads;
+  const double scale = 1.0 / sqrt((double)dh);
+  memset(dqkv, 0, (size_t)(B * T * 3 * D) * sizeof(double));
+  if (mag) memset(mag, 0, (size_t)(B * T * 3 * D) * sizeof(double));
+#pragma omp parallel for schedule(dynamic)
+  for (int64_t bh = 0; bh < B * heads; ++bh) {
+    const int64_t b = bh / heads, h = bh % heads;
+    double *p = (double *)malloc((size_t)T * sizeof(double));
+    double *dp = (double *)malloc((size_t)T * sizeof(double));
+    for (int64_t t = 0; t < T; ++t) {
+      const int64_t j0 = (left < 0 || t - left < 0) ? 0 : t - left;
+      const int64_t j1 = (right < 0 || t + right > T - 1) ? T - 1 : t + right;
+      const float *q = qkv + (b * T + t) * 3 * D + h * dh;
+      const double *g = dctx + (b * T + t) * D + h * dh;
+      double mx = -INFINITY, sum = 0.0, dd = 0.0, dda = 0.0;
+      for (int64_t j = j0; j <= j1; ++j) {
+        const float *k = qkv + (b * T + j) * 3 * D + D + h * dh;
+        double a = 0.0;
+        for (int64_t d = 0; d < dh; ++d) a += (double)q[d] * (double)k[d];
+        p[j] = a * scale;
+        if (p[j] > mx) mx = p[j];
+      }
+      for (int64_t j = j0; j <= j1; ++j) {
+        p[j] = exp(p[j] - mx);
+        sum += p[j];
+      }
+      for (int64_t j = j0; j <= j1; ++j) {
+        const float *v = qkv + (b * T + j) * 3 * D + 2 * D + h * dh;
+        double a = 0.0;
+        for (int64_t d = 0; d < dh; ++d) a += g[d] * (double)v[d];
+        p[j] /= sum;
+        dp[j] = a;
+        dd += p[j] * a;
+        dda += p[j] * fabs(a);
+      }
+      for (int64_t j = j0; j <= j1; ++j) {
+        const double ds = p[j] * (dp[j] - dd) * scale, dsa = p[j] * (fabs(dp[j]) + dda) * scale;
+        const int64_t qo = (b * T + t) * 3 * D + h * dh, ko = (b * T + j) * 3 * D + D + h * dh, vo = ko + D;
+        for (int64_t d = 0; d < dh; ++d) {
+          dqkv[qo + d] += ds * (double)qkv[ko + d];
+          dqkv[ko + d] += ds * (double)qkv[qo + d];
+          dqkv[vo + d] += p[j] * g[d];
+          if (mag) {
+            mag[qo + d] += dsa * fabs((double)qkv[ko + d]);
+            mag[ko + d] += dsa * fabs((double)qkv[qo + d]);
+            mag[vo + d] += p[j] * fabs(g[d]);
+          }
+        }
+      }
+    }
+    free(p);
+    free(dp);
+  }
+  return 0;
+}
+
+/*
+ * Gradients of oracle_layernorm for an upstream gradient dy [M,D] (float64).  With
+ * xh = (x - mean) / sqrt(var + eps) and g = dy * gamma:
+ *   dx = (g - mean_row(g) - xh mean_row(g xh)) / sqrt(var + eps);  dgamma = sum_m dy xh;  dbeta = sum_m dy
+ * dgamma / dbeta nullable.
+ */
+void oracle_layernorm_bwd(const float *x, int64_t M, int64_t D, const float *gamma, double eps, const double *dy,
+                          double *dx, double *dgamma, double *dbeta) {
+  if (dgamma) memset(dgamma, 0, (size_t)D * sizeof(double));
+  if (dbeta) memset(dbeta, 0, (size_t)D * sizeof(double));
+  for (int64_t m = 0; m < M; ++m) {
+    double mean = 0.0, var = 0.0, mg = 0.0, mgx = 0.0;
+    for (int64_t d = 0; d < D; ++d) mean += (double)x[m * D + d];
+    mean /= (double)D;
+    for (int64_t d = 0; d < D; ++d) {
+      const double c = (double)x[m * D + d] - mean;
+      var += c * c;
+    }
+    var /= (double)D;
+    const double r = 1.0 / sqrt(var + eps);
+    for (int64_t d = 0; d < D; ++d) {
+      const double xh = ((double)x[m * D + d] - mean) * r;
+      const double g = dy[m * D + d] * (gamma ? (double)gamma[d] : 1.0);
+      mg += g;
+      mgx += g * xh;
+      if (dgamma) dgamma[d] += dy[m * D + d] * xh;
+      if (dbeta) dbeta[d] += dy[m * D + d];
+    }
+    mg /= (double)D;
+    mgx /= (double)D;
+    for (int64_t d = 0; d < D; ++d) {
+      const double xh = ((double)x[m * D + d] - mean) * r;
+      const double g = dy[m * D + d] * (gamma ? (double)gamma[d] : 1.0);
+      dx[m * D + d] = (g - mg - xh * mgx) * r;
+    }
+  }
 }
 
 /*

@@ -45,6 +45,10 @@ void oracle_depthwise_conv_bwd(const double *dout, const float *x, const float *
                                double *dw_abs);
 int oracle_attention(const float *qkv, int64_t B, int64_t T, int64_t D, int64_t heads, int64_t left, int64_t right,
                      double *ctx, double *smag, double *vmag);
+int oracle_attention_bwd(const float *qkv, const double *dctx, int64_t B, int64_t T, int64_t D, int64_t heads,
+                         int64_t left, int64_t right, double *dqkv, double *mag);
+void oracle_layernorm_bwd(const float *x, int64_t M, int64_t D, const float *gamma, double eps, const double *dy,
+                          double *dx, double *dgamma, double *dbeta);
 void oracle_affine_swish(const double *v, int64_t M, int64_t C, const float *a, const float *b, double *out,
                          double *dfac);
 void oracle_dense_fwd_q_sampled(const int8_t *xq, float s_x, const int8_t *wq_kn, const float *s_w, int64_t K,
@@ -200,7 +204,15 @@ static void one_attention(int64_t B, int64_t T, int64_t D, int64_t heads) {
   CHECK(oracle_attention(qkv, B, T, D, heads, T + 5, 2, ctx, sm, NULL) == 0);
   CHECK(oracle_attention(qkv, B, T, D, D + 1, -1, -1, ctx, NULL, NULL) == 2);
   for (size_t i = 0; i < n; ++i) CHECK(isfinite(ctx[i]));
-  free(qkv); free(ctx); free(vm); free(sm);
+  double *dq = need(3 * n * sizeof(double)), *mg = need(3 * n * sizeof(double));
+  CHECK(oracle_attention_bwd(qkv, ctx, B, T, D, heads, -1, -1, dq, mg) == 0);
+  CHECK(oracle_attention_bwd(qkv, ctx, B, T, D, heads, 2, 1, dq, NULL) == 0);
+  CHECK(oracle_attention_bwd(qkv, ctx, B, T, D, D + 1, 2, 1, dq, NULL) == 2);
+  for (size_t i = 0; i < 3 * n; ++i) CHECK(isfinite(dq[i]));
+  /* the normalisation's backward on the same buffers: rows of D entries */
+  oracle_layernorm_bwd(qkv, B * T, D, qkv, 1e-6, ctx, vm, dq, mg);
+  oracle_layernorm_bwd(qkv, B * T, D, NULL, 1e-6, ctx, vm, NULL, NULL);
+  free(qkv); free(ctx); free(vm); free(sm); free(dq); free(mg);
 }
 
 int main(void) {

@@ -859,3 +859,65 @@ def test_attention_equals_scipy_softmax_formula_per_head():
         assert (vmag >= np.abs(ctx) - 1e-12).all() and (smag >= 0).all()
     with pytest.raises(ValueError):
         oracle.attention(qkv, 5)
+
+
+# ----------------------------------------------------------------------------
+# Backward of the attention core and of the normalisation
+# ----------------------------------------------------------------------------
+def test_attention_backward_central_differences_and_zero_width_window():
+    rng = np.random.default_rng(62)
+    B, T, D, H = 2, 7, 6, 2
+    qkv = _qkv(rng, B, T, D)
+    dctx = rng.standard_normal((B, T, D))
+    for left, right in ((-1, -1), (2, 0), (1, 3)):
+        dqkv, mag = oracle.attention_bwd(qkv, dctx, H, left, right)
+        assert (mag >= np.abs(dqkv) - 1e-12).all()
+        h = F(2.0 ** -8)
+        for idx in [(0, 0, 0), (1, 3, 4), (0, 6, D + 1), (1, 2, D + 5), (0, 4, 2 * D), (1, 6, 3 * D - 1), (1, 0, 2 * D + 3)]:
+            qp, qm = qkv.copy(), qkv.copy()
+            qp[idx] += h
+            qm[idx] -= h
+            fd = ((oracle.attention(qp, H, left, right) - oracle.attention(qm, H, left, right)) * dctx).sum()
+            fd /= float(qp[idx]) - float(qm[idx])
+            np.testing.assert_allclose(dqkv[idx], fd, rtol=2e-4, atol=1e-6)
+    # a window of the frame itself: ctx = v, so dv = dctx and nothing flows to queries and keys
+    dqkv, _ = oracle.attention_bwd(qkv, dctx, H, 0, 0)
+    np.testing.assert_allclose(dqkv[:, :, 2 * D:], dctx, rtol=1e-14)
+    assert np.abs(dqkv[:, :, :2 * D]).max() < 1e-15
+    # zero queries: uniform weights 1/n; dv_j = sum over the queries that see j of dctx_t / n_t; dk = 0
+    z = qkv.copy()
+    z[:, :, :D] = 0
+    dqkv, _ = oracle.attention_bwd(z, dctx, H, 1, 1)
+    n = np.array([min(T - 1, t + 1) - max(0, t - 1) + 1 for t in range(T)], np.float64)
+    want = np.zeros((B, T, D))
+    for t in range(T):
+        for j in range(max(0, t - 1), min(T - 1, t + 1) + 1):
+            want[:, j] += dctx[:, t] / n[t]
+    np.testing.assert_allclose(dqkv[:, :, 2 * D:], want, rtol=1e-13)
+    assert np.abs(dqkv[:, :, D:2 * D]).max() < 1e-15
+
+
+def test_layernorm_backward_central_differences_and_orthogonality():
+    rng = np.random.default_rng(63)
+    M, D = 4, 9
+    x = (rng.standard_normal((M, D)) * 2 + 1).astype(F)
+    gamma, beta = (1 + 0.3 * rng.standard_normal(D)).astype(F), rng.standard_normal(D).astype(F)
+    dy = rng.standard_normal((M, D))
+    dx, dg, db = oracle.layernorm_bwd(x, dy, gamma, 1e-6)
+    h = F(2.0 ** -7)
+    for idx in [(0, 0), (3, 8), (2, 4)]:
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += h
+        xm[idx] -= h
+        fd = ((oracle.layernorm(xp, gamma, beta, 1e-6) - oracle.layernorm(xm, gamma, beta, 1e-6)) * dy).sum()
+        np.testing.assert_allclose(dx[idx], fd / (float(xp[idx]) - float(xm[idx])), rtol=2e-4, atol=1e-7)
+    xh = oracle.layernorm(x, None, None, 1e-6)
+    np.testing.assert_allclose(dg, (dy * xh).sum(0), rtol=1e-13)
+    np.testing.assert_allclose(db, dy.sum(0), rtol=1e-13)
+    # the gradient of a normalised row is orthogonal to the constant vector, and (up to eps) to the row itself
+    assert np.abs(dx.sum(1)).max() < 1e-12
+    assert np.abs((dx * xh).sum(1)).max() < 1e-5
+    # without gamma
+    dx1, _, _ = oracle.layernorm_bwd(x, dy, None, 1e-6)
+    dx2, _, _ = oracle.layernorm_bwd(x, dy, np.ones(D, F), 1e-6)
+    np.testing.assert_array_equal(dx1, dx2)
