@@ -73,6 +73,7 @@ typedef int aqt_status;
 #define AQT_OP_CONV_MODULE_BWD 12
 #define AQT_OP_MHSA_FWD 13             /* M = B * T tokens, K = model width D, N unused        */
 #define AQT_OP_CONFORMER_LAYER_FWD 14  /* M = B * T tokens, K = model width D, N = inner width */
+#define AQT_OP_ATTENTION_BWD 15        /* M = B * T tokens, K unused, N = heads                */
 
 /* What the forward keeps for the backward.  All caller-owned device buffers. */
 typedef struct aqt_saved {
@@ -462,9 +463,22 @@ aqt_status aqt_conv_module_bwd(const float *dy, const aqt_conv_saved *saved, con
  * dh <= 64.  Float32 with an online softmax; the scores are not written anywhere.
  * ctx_absmax nullable device float: max|ctx|, cleared by the call, for
  * aqt_quantize_with_absmax in front of the output projection.
+ * lse nullable [B*T, heads]: log2 of the softmax's normaliser, in the units the kernel keeps
+ * its scores in (so that p_j = 2^(score_j - lse)); what aqt_attention_bwd needs.
  */
 aqt_status aqt_attention_fwd(const float *qkv, int64_t B, int64_t T, int64_t D, int heads, int left_context,
-                             int right_context, float *ctx, float *ctx_absmax, void *stream);
+                             int right_context, float *ctx, float *ctx_absmax, float *lse, void *stream);
+
+/*
+ * Gradient of aqt_attention_fwd with respect to qkv for the upstream gradient dctx [B*T, D]:
+ * the chain rule through the softmax and the two products, on the float32 matrix cores, the
+ * probabilities formed again from qkv and lse.  qkv, ctx and lse as the forward left them;
+ * dqkv [B*T, 3D] in the layout of qkv, every element written.  Each sum has one fixed order
+ * (no atomics).  Workspace: aqt_workspace_bytes(AQT_OP_ATTENTION_BWD, B*T, ., heads, ., .).
+ */
+aqt_status aqt_attention_bwd(const float *qkv, const float *ctx, const float *dctx, const float *lse, int64_t B,
+                             int64_t T, int64_t D, int heads, int left_context, int right_context, float *dqkv,
+                             void *ws, size_t ws_bytes, void *stream);
 
 /* Buffers of the self-attention module.  Caller-owned device memory. */
 typedef struct aqt_mhsa_saved {
@@ -473,6 +487,7 @@ typedef struct aqt_mhsa_saved {
   float *qkv_f;     /* [M,3D] projected queries, keys, values              */
   float *ctx;       /* [M,D] attention result                              */
   float *row_stats; /* nullable [M,2]                                      */
+  float *lse;       /* nullable [M,heads]: the softmax normalisers, for the backward */
 } aqt_mhsa_saved;
 
 /*

@@ -22,7 +22,7 @@ AQT_EPI_NONE, AQT_EPI_SWISH, AQT_EPI_GLU = 0, 1, 2
 (AQT_OP_QUANTIZE, AQT_OP_QUANTIZE_WEIGHTS, AQT_OP_DENSE_FWD, AQT_OP_DENSE_FWD_Q, AQT_OP_DENSE_BWD,
  AQT_OP_DENSE_FWD_WONLY, AQT_OP_DENSE_BWD_EPI, AQT_OP_LAYERNORM_QUANTIZE, AQT_OP_FFN_FWD, AQT_OP_FFN_BWD,
  AQT_OP_DEPTHWISE_CONV_BWD, AQT_OP_CONV_MODULE_FWD, AQT_OP_CONV_MODULE_BWD, AQT_OP_MHSA_FWD,
- AQT_OP_CONFORMER_LAYER_FWD) = range(15)
+ AQT_OP_CONFORMER_LAYER_FWD, AQT_OP_ATTENTION_BWD) = range(16)
 AQT_POLICY_ALL, AQT_POLICY_EXCEPT_FIRST_LAST, AQT_POLICY_EXCEPT_ATTENTION, AQT_POLICY_FIRST_K = range(4)
 
 # every symbol include/aqt.h declares
@@ -34,7 +34,7 @@ SYMBOLS = ["aqt_status_string", "aqt_last_hip_error", "aqt_version", "aqt_worksp
            "aqt_policy_weight_bytes", "aqt_ffn_fwd", "aqt_ffn_bwd", "aqt_prepared_weight_bytes",
            "aqt_prepare_weights", "aqt_dense_fwd_q_prepared", "aqt_depthwise_conv_fwd", "aqt_depthwise_conv_bwd",
            "aqt_conv_module_fwd", "aqt_conv_module_bwd", "aqt_attention_fwd", "aqt_mhsa_fwd",
-           "aqt_residual_add", "aqt_conformer_layer_fwd"]
+           "aqt_residual_add", "aqt_conformer_layer_fwd", "aqt_attention_bwd"]
 
 
 class AqtError(RuntimeError):
@@ -73,7 +73,7 @@ class aqt_conv_saved(ctypes.Structure):
 
 class aqt_mhsa_saved(ctypes.Structure):
     _fields_ = [("qkv", aqt_saved), ("out", aqt_saved), ("qkv_f", ctypes.c_void_p), ("ctx", ctypes.c_void_p),
-                ("row_stats", ctypes.c_void_p)]
+                ("row_stats", ctypes.c_void_p), ("lse", ctypes.c_void_p)]
 
 
 LAYER_WEIGHT_NAMES = ("ffn1_ln_g", "ffn1_ln_b", "ffn1_w1", "ffn1_b1", "ffn1_w2", "ffn1_b2",
@@ -160,7 +160,8 @@ def lib() -> ctypes.CDLL:
         L.aqt_conv_module_bwd.argtypes = [_vp, ctypes.POINTER(aqt_conv_saved), _vp, _i64, _i64, _i64, _int, _int,
                                           ctypes.POINTER(aqt_dense_policy), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                                           _sz, _vp]
-        L.aqt_attention_fwd.argtypes = [_vp, _i64, _i64, _i64, _int, _int, _int, _vp, _vp, _vp]
+        L.aqt_attention_fwd.argtypes = [_vp, _i64, _i64, _i64, _int, _int, _int, _vp, _vp, _vp, _vp]
+        L.aqt_attention_bwd.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int, _int, _vp, _vp, _sz, _vp]
         L.aqt_mhsa_fwd.argtypes = [_vp, _vp, _vp, ctypes.c_float, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _int,
                                    _int, ctypes.POINTER(aqt_dense_policy), _vp, ctypes.POINTER(aqt_mhsa_saved), _vp,
                                    _sz, _vp, _vp]
@@ -645,16 +646,31 @@ def aqt_conv_module_bwd(dy, saved: ConvSaved, w_dw, *, pad_left: int, ws=None):
     return o
 
 
-def aqt_attention_fwd(qkv, B: int, T: int, heads: int, *, left: int = -1, right: int = -1, want_absmax=False):
-    """aqt_attention_fwd: qkv [B*T, 3D] -> (ctx [B*T, D], absmax word or None)."""
+def aqt_attention_fwd(qkv, B: int, T: int, heads: int, *, left: int = -1, right: int = -1, want_absmax=False,
+                      lse=None):
+    """aqt_attention_fwd: qkv [B*T, 3D] -> (ctx [B*T, D], absmax word or None); lse [B*T, heads] is filled if given."""
     _dev(qkv, torch.float32, "qkv")
     M, D3 = qkv.shape
     D = D3 // 3
     ctx = torch.empty((M, D), dtype=torch.float32, device=qkv.device)
     m = torch.empty(1, dtype=torch.float32, device=qkv.device) if want_absmax else None
-    st = lib().aqt_attention_fwd(_ptr(qkv), B, T, D, heads, left, right, _ptr(ctx), _ptr(m), _stream())
+    st = lib().aqt_attention_fwd(_ptr(qkv), B, T, D, heads, left, right, _ptr(ctx), _ptr(m), _ptr(lse), _stream())
     _check(st, "aqt_attention_fwd")
     return ctx, m
+
+
+def aqt_attention_bwd(qkv, ctx, dctx, lse, B: int, T: int, heads: int, *, left: int = -1, right: int = -1, ws=None):
+    """aqt_attention_bwd: returns dqkv [B*T, 3D]."""
+    _dev(qkv, torch.float32, "qkv")
+    _dev(dctx, torch.float32, "dctx")
+    M, D3 = qkv.shape
+    D = D3 // 3
+    dqkv = torch.empty_like(qkv)
+    ws = workspace(aqt_workspace_bytes(AQT_OP_ATTENTION_BWD, M, 1, heads), qkv.device) if ws is None else ws
+    st = lib().aqt_attention_bwd(_ptr(qkv), _ptr(ctx), _ptr(dctx), _ptr(lse), B, T, D, heads, left, right, _ptr(dqkv),
+                                 _ptr(ws), ws.numel(), _stream())
+    _check(st, "aqt_attention_bwd")
+    return dqkv
 
 
 class MhsaSaved:
@@ -669,12 +685,13 @@ class MhsaSaved:
         self.qkv_f = torch.empty((M, 3 * D), dtype=torch.float32, device=device)
         self.ctx = torch.empty((M, D), dtype=torch.float32, device=device)
         self.row_stats = torch.empty((M, 2), dtype=torch.float32, device=device)
+        self.lse = None        # set to a [M, heads] tensor (and refresh()) to keep what the backward needs
         self.policy = (aqt_dense_policy * 2)(aqt_dense_policy(bw1, bx1), aqt_dense_policy(bw2, bx2))
         self.refresh()
 
     def refresh(self):
         self.c = aqt_mhsa_saved(self.qkv.c, self.out.c, self.qkv_f.data_ptr(), self.ctx.data_ptr(),
-                                self.row_stats.data_ptr())
+                                self.row_stats.data_ptr(), None if self.lse is None else self.lse.data_ptr())
         return self
 
     def prepare(self, wqkv, wo):

@@ -214,6 +214,9 @@ size_t aqt_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int bits_x, 
       const size_t b = carve_ffn_fwd(nullptr, M, K, 3 * K).total;   // covers the convolution module's 2 K as well
       return a > b ? a : b;
     }
+    case AQT_OP_ATTENTION_BWD:
+      if (M < 1 || N < 1) return 0;
+      return attention_bwd_ws_bytes(1, M, static_cast<int>(N));
     case AQT_OP_CONV_MODULE_BWD:
       if (!shape_ok(M, K) || N < 1 || N > 4096) return 0;
       return carve_conv_bwd(nullptr, 1, M, K, static_cast<int>(N)).total;
@@ -617,11 +620,22 @@ aqt_status aqt_conv_module_bwd(const float *dy, const aqt_conv_saved *saved, con
 }
 
 aqt_status aqt_attention_fwd(const float *qkv, int64_t B, int64_t T, int64_t D, int heads, int left_context,
-                             int right_context, float *ctx, float *ctx_absmax, void *stream) {
+                             int right_context, float *ctx, float *ctx_absmax, float *lse, void *stream) {
   if (!qkv || !ctx || B < 1 || T < 1 || D < 1 || heads < 1 || D % heads) return AQT_ERR_INVALID_ARG;
   if (!attention_shape_ok(B, T, D, heads)) return AQT_ERR_UNSUPPORTED;
   return launch_attention(qkv, B, T, D, heads, left_context, right_context, ctx,
-                          reinterpret_cast<uint32_t *>(ctx_absmax), static_cast<hipStream_t>(stream));
+                          reinterpret_cast<uint32_t *>(ctx_absmax), lse, static_cast<hipStream_t>(stream));
+}
+
+aqt_status aqt_attention_bwd(const float *qkv, const float *ctx, const float *dctx, const float *lse, int64_t B,
+                             int64_t T, int64_t D, int heads, int left_context, int right_context, float *dqkv,
+                             void *ws, size_t ws_bytes, void *stream) {
+  if (!qkv || !ctx || !dctx || !lse || !dqkv || B < 1 || T < 1 || D < 1 || heads < 1 || D % heads)
+    return AQT_ERR_INVALID_ARG;
+  if (!attention_shape_ok(B, T, D, heads)) return AQT_ERR_UNSUPPORTED;
+  if (!ws || ws_bytes < attention_bwd_ws_bytes(B, T, heads)) return AQT_ERR_WORKSPACE;
+  return launch_attention_bwd(qkv, ctx, dctx, lse, B, T, D, heads, left_context, right_context, dqkv, ws,
+                              static_cast<hipStream_t>(stream));
 }
 
 aqt_status aqt_mhsa_fwd(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps, const float *wqkv,
@@ -651,7 +665,7 @@ aqt_status aqt_mhsa_fwd(const float *x, const float *ln_gamma, const float *ln_b
                              saved->qkv_f, nullptr, nullptr, s1.operand, st, nullptr, s1.prepared));
   // attention in float32; max|ctx| for the one-pass quantizer
   AQT_TRY(launch_attention(saved->qkv_f, B, T, D, heads, left_context, right_context, saved->ctx,
-                           reinterpret_cast<uint32_t *>(f.h_absmax), st));
+                           reinterpret_cast<uint32_t *>(f.h_absmax), saved->lse, st));
   // output projection
   AQT_TRY(weight_side(p2, wo, l2, M, D, D, AQT_EPI_NONE, f.wpart2, f.wfrag2, st, dev_status, &s2));
   AQT_TRY(launch_quantize_with_absmax(saved->ctx, M, D, D, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),

@@ -122,6 +122,10 @@ aqt_status launch_dwconv_bwd(const float *dout, const float *dmul, const float *
 // ---- attention core of the self-attention module (attention.hip) ---------------------------
 bool attention_shape_ok(int64_t B, int64_t T, int64_t D, int heads);
 aqt_status launch_attention(const float *qkv, int64_t B, int64_t T, int64_t D, int heads, int left, int right,
-                            float *ctx, uint32_t *absmax, hipStream_t st);
+                            float *ctx, uint32_t *absmax, float *lse, hipStream_t st);
+size_t attention_bwd_ws_bytes(int64_t B, int64_t T, int heads);
+aqt_status launch_attention_bwd(const float *qkv, const float *ctx, const float *dctx, const float *lse, int64_t B,
+                                int64_t T, int64_t D, int heads, int left, int right, float *dqkv, void *ws,
+                                hipStream_t st);
 
 }  // namespace aqt

@@ -10,7 +10,7 @@ static void one(int64_t B, int64_t T, int64_t D, int heads, int left, int right)
   uint32_t s = 7u, am = 0;
   for (size_t i = 0; i < 3 * n; ++i) { s = s * 1664525u + 1013904223u; qkv[i] = 2.0f * ((float)(s >> 8) / 8388608.0f - 1.0f); }
   AttnGeom g = attn_geom(B, T, D, heads, left, right);
-  run((unsigned)(g.qtiles * heads * B), 256, 0, [&] { attention_fwd_kernel(qkv, g, ctx, &am); });
+  run((unsigned)(g.qtiles * heads * B), 256, 0, [&] { attention_fwd_kernel(qkv, g, ctx, &am, nullptr); });
   const int dh = (int)(D / heads);
   double worst = 0; float mx = 0;
   std::vector<double> p(T);

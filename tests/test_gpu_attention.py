@@ -148,3 +148,39 @@ def test_mhsa_chain_stage_by_stage(B_, T, D, heads, left, right, policy, outlier
     wp2, s_w2, _, _ = B.aqt_quantize_weights(wo_d, bw2)
     y_b, _ = B.aqt_dense_fwd_q(q_b, sx_b, wp2, s_w2, D, bx2, bw2, bias=bo_d)
     np.testing.assert_array_equal(host(y_b), y_h)
+
+
+@pytest.mark.parametrize("B_,T,D,heads,left,right", ATT_CASES)
+def test_attention_backward(B_, T, D, heads, left, right):
+    from parity_util import check_grad
+    say("attention bwd", B_, T, D, heads, left, right)
+    rng = np.random.default_rng(650 + T + D)
+    M = B_ * T
+    qkv = rng.standard_normal((M, 3 * D)).astype(F)
+    dctx = (0.1 * rng.standard_normal((M, D))).astype(F)
+    qkv_d, dctx_d = dev(qkv), dev(dctx)
+    lse = torch.empty((M, heads), dtype=torch.float32, device="cuda")
+    ctx, _ = B.aqt_attention_fwd(qkv_d, B_, T, heads, left=left, right=right, lse=lse)
+    dqkv = B.aqt_attention_bwd(qkv_d, ctx, dctx_d, lse, B_, T, heads, left=left, right=right)
+    ref, mag = oracle.attention_bwd(qkv.reshape(B_, T, 3 * D), dctx.reshape(B_, T, D), heads, left, right)
+    got = host(dqkv).reshape(B_, T, 3 * D)
+    for name, sl in (("dq", slice(0, D)), ("dk", slice(D, 2 * D)), ("dv", slice(2 * D, 3 * D))):
+        check_grad(got[:, :, sl], ref[:, :, sl], mag[:, :, sl], name)
+    # the forward with lse gives the same ctx as without; the backward has one summation order
+    ctx0, _ = B.aqt_attention_fwd(qkv_d, B_, T, heads, left=left, right=right)
+    np.testing.assert_array_equal(host(ctx0), host(ctx))
+    dqkv2 = B.aqt_attention_bwd(qkv_d, ctx, dctx_d, lse, B_, T, heads, left=left, right=right)
+    np.testing.assert_array_equal(host(dqkv2), host(dqkv))
+    if M <= 400:   # lse is log2 of the sum of exponentials of the scaled scores
+        dh = D // heads
+        q, k = (qkv[:, i * D:(i + 1) * D].astype(np.float64).reshape(B_, T, heads, dh) for i in range(2))
+        sc = np.einsum("bthd,bjhd->bthj", q, k) / np.sqrt(dh)
+        t_i, j_i = np.arange(T)[:, None], np.arange(T)[None, :]
+        ok = np.ones((T, T), bool)
+        if left >= 0:
+            ok &= j_i >= t_i - left
+        if right >= 0:
+            ok &= j_i <= t_i + right
+        sc = np.where(ok[None, :, None, :], sc, -np.inf)
+        want = np.log2(np.exp(sc - sc.max(-1, keepdims=True)).sum(-1)) + sc.max(-1) * np.log2(np.e)
+        np.testing.assert_allclose(host(lse).reshape(B_, T, heads), want, rtol=0, atol=2e-5 * (1 + np.abs(want).max()))

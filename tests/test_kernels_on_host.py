@@ -22,7 +22,7 @@ def spliced_source():
     return src + open(os.path.join(HERE, "host_emulation", "conv_driver.cpp")).read()
 
 
-def spliced_attention_source():
+def spliced_attention_source(driver="attention_driver.cpp"):
     src = open(os.path.join(CSRC, "attention.hip")).read()
     src = src.replace('#include "aqt_internal.h"', '#include "hip_on_host.h"')
     vec = "typedef float v4f __attribute__((ext_vector_type(4)));"      # a clang extension; g++ gets a plain struct
@@ -32,7 +32,7 @@ def spliced_attention_source():
     assert vec16 in src
     src = src.replace(vec16, "")
     src = src[:src.index("}  // namespace\n\nbool attention_shape_ok")]  # kernel and geometry helper only
-    return src + open(os.path.join(HERE, "host_emulation", "attention_driver.cpp")).read()
+    return src + open(os.path.join(HERE, "host_emulation", driver)).read()
 
 
 def test_conv_kernels_in_bounds_and_correct_on_host(tmp_path):
@@ -41,6 +41,10 @@ def test_conv_kernels_in_bounds_and_correct_on_host(tmp_path):
 
 def test_attention_kernel_in_bounds_and_correct_on_host(tmp_path):
     build_and_run(tmp_path, "attention_on_host", spliced_attention_source())
+
+
+def test_attention_backward_kernels_in_bounds_and_correct_on_host(tmp_path):
+    build_and_run(tmp_path, "attention_bwd_on_host", spliced_attention_source("attention_bwd_driver.cpp"))
 
 
 def build_and_run(tmp_path, name, source):
