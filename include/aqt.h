@@ -74,6 +74,9 @@ typedef int aqt_status;
 #define AQT_OP_MHSA_FWD 13             /* M = B * T tokens, K = model width D, N unused        */
 #define AQT_OP_CONFORMER_LAYER_FWD 14  /* M = B * T tokens, K = model width D, N = inner width */
 #define AQT_OP_ATTENTION_BWD 15        /* M = B * T tokens, K unused, N = heads                */
+#define AQT_OP_LAYERNORM_BWD 16        /* M rows; K = row length; N unused                     */
+#define AQT_OP_MHSA_BWD 17             /* M = B * T tokens, K = model width D, N = heads       */
+#define AQT_OP_CONFORMER_LAYER_BWD 18  /* M = B * T tokens, K = model width D, N = inner width (heads <= 64, kernel <= 32 assumed) */
 
 /* What the forward keeps for the backward.  All caller-owned device buffers. */
 typedef struct aqt_saved {
@@ -535,6 +538,7 @@ typedef struct aqt_conformer_layer_saved {
   aqt_conv_saved conv;
   float *r1, *r2, *r3, *r4;   /* [M,D] each: the residual stream after each module */
   float *m;                   /* [M,D] module output before it joins the stream     */
+  float *out_row_stats;       /* nullable [M,2]: statistics of the final normalisation, for the backward */
 } aqt_conformer_layer_saved;
 
 /*
@@ -548,6 +552,49 @@ aqt_status aqt_conformer_layer_fwd(const float *x, const aqt_conformer_layer_wei
                                    const aqt_conformer_layer_shape *shape, const aqt_layer_policy *policy, float *y,
                                    const aqt_conformer_layer_saved *saved, void *ws, size_t ws_bytes, void *stream,
                                    int32_t *dev_status);
+
+/*
+ * Backward of the layer normalisation of aqt_layernorm_quantize (the quantizer behind it passes
+ * gradients straight through): with xh = (x - mean) rstd and g = dy gamma,
+ *   dx = add + (g - mean_row(g) - xh mean_row(g xh)) rstd;   dgamma = sum_m dy xh;   dbeta = sum_m dy.
+ * x, dy, dx [M,D]; row_stats [M,2] as the forward stored them; gamma nullable (ones); add nullable
+ * [M,D]: a gradient to add in (the one arriving over a residual connection); dgamma / dbeta
+ * nullable [D], summed in a fixed order.  Workspace: aqt_workspace_bytes(AQT_OP_LAYERNORM_BWD, M, D, ., ., .).
+ */
+aqt_status aqt_layernorm_bwd(const float *x, const float *row_stats, const float *gamma, const float *dy,
+                             const float *add, int64_t M, int64_t D, float *dx, float *dgamma, float *dbeta,
+                             void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Straight-through backward of aqt_mhsa_fwd down to the normalised input:
+ *   dxn [M,D], dwqkv [D,3D], dbqkv [3D], dwo [D,D], dbo [D]; any may be NULL.
+ * Needs saved->lse and the buffers aqt_mhsa_fwd filled.
+ */
+aqt_status aqt_mhsa_bwd(const float *dy, const aqt_mhsa_saved *saved, int64_t B, int64_t T, int64_t D, int heads,
+                        int left_context, int right_context, const aqt_dense_policy *policy, float *dxn,
+                        float *dwqkv, float *dbqkv, float *dwo, float *dbo, void *ws, size_t ws_bytes, void *stream);
+
+/* Gradients of one encoder layer's weights: the fields of aqt_conformer_layer_weights, writable; NULL = not wanted. */
+typedef struct aqt_conformer_layer_grads {
+  float *ffn1_ln_g, *ffn1_ln_b, *ffn1_w1, *ffn1_b1, *ffn1_w2, *ffn1_b2;
+  float *att_ln_g, *att_ln_b, *att_wqkv, *att_bqkv, *att_wo, *att_bo;
+  float *conv_ln_g, *conv_ln_b, *conv_w1, *conv_b1, *conv_wdw, *conv_bdw, *conv_norm_scale, *conv_norm_shift,
+      *conv_w2, *conv_b2;
+  float *ffn2_ln_g, *ffn2_ln_b, *ffn2_w1, *ffn2_b1, *ffn2_w2, *ffn2_b2;
+  float *out_ln_g, *out_ln_b;
+} aqt_conformer_layer_grads;
+
+/*
+ * Straight-through backward of aqt_conformer_layer_fwd (training form: weights_ready = 0, integer
+ * activations everywhere): dx [M,D] and the weight gradients asked for.  x and w as in the forward
+ * call, saved as it left them (including every row_stats, out_row_stats, att.lse, conv.dfac and the
+ * dact buffers).  conv_norm_scale / conv_norm_shift gradients are not produced (fixed statistics)
+ * and must be NULL.
+ */
+aqt_status aqt_conformer_layer_bwd(const float *dy, const float *x, const aqt_conformer_layer_weights *w,
+                                   const aqt_conformer_layer_shape *shape, const aqt_layer_policy *policy,
+                                   const aqt_conformer_layer_saved *saved, float *dx,
+                                   const aqt_conformer_layer_grads *grads, void *ws, size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -22,7 +22,8 @@ AQT_EPI_NONE, AQT_EPI_SWISH, AQT_EPI_GLU = 0, 1, 2
 (AQT_OP_QUANTIZE, AQT_OP_QUANTIZE_WEIGHTS, AQT_OP_DENSE_FWD, AQT_OP_DENSE_FWD_Q, AQT_OP_DENSE_BWD,
  AQT_OP_DENSE_FWD_WONLY, AQT_OP_DENSE_BWD_EPI, AQT_OP_LAYERNORM_QUANTIZE, AQT_OP_FFN_FWD, AQT_OP_FFN_BWD,
  AQT_OP_DEPTHWISE_CONV_BWD, AQT_OP_CONV_MODULE_FWD, AQT_OP_CONV_MODULE_BWD, AQT_OP_MHSA_FWD,
- AQT_OP_CONFORMER_LAYER_FWD, AQT_OP_ATTENTION_BWD) = range(16)
+ AQT_OP_CONFORMER_LAYER_FWD, AQT_OP_ATTENTION_BWD, AQT_OP_LAYERNORM_BWD, AQT_OP_MHSA_BWD,
+ AQT_OP_CONFORMER_LAYER_BWD) = range(19)
 AQT_POLICY_ALL, AQT_POLICY_EXCEPT_FIRST_LAST, AQT_POLICY_EXCEPT_ATTENTION, AQT_POLICY_FIRST_K = range(4)
 
 # every symbol include/aqt.h declares
@@ -34,7 +35,8 @@ SYMBOLS = ["aqt_status_string", "aqt_last_hip_error", "aqt_version", "aqt_worksp
            "aqt_policy_weight_bytes", "aqt_ffn_fwd", "aqt_ffn_bwd", "aqt_prepared_weight_bytes",
            "aqt_prepare_weights", "aqt_dense_fwd_q_prepared", "aqt_depthwise_conv_fwd", "aqt_depthwise_conv_bwd",
            "aqt_conv_module_fwd", "aqt_conv_module_bwd", "aqt_attention_fwd", "aqt_mhsa_fwd",
-           "aqt_residual_add", "aqt_conformer_layer_fwd", "aqt_attention_bwd"]
+           "aqt_residual_add", "aqt_conformer_layer_fwd", "aqt_attention_bwd",
+           "aqt_layernorm_bwd", "aqt_mhsa_bwd", "aqt_conformer_layer_bwd"]
 
 
 class AqtError(RuntimeError):
@@ -96,7 +98,11 @@ class aqt_conformer_layer_shape(ctypes.Structure):
 class aqt_conformer_layer_saved(ctypes.Structure):
     _fields_ = [("ffn1", aqt_ffn_saved), ("ffn2", aqt_ffn_saved), ("att", aqt_mhsa_saved), ("conv", aqt_conv_saved),
                 ("r1", ctypes.c_void_p), ("r2", ctypes.c_void_p), ("r3", ctypes.c_void_p), ("r4", ctypes.c_void_p),
-                ("m", ctypes.c_void_p)]
+                ("m", ctypes.c_void_p), ("out_row_stats", ctypes.c_void_p)]
+
+
+class aqt_conformer_layer_grads(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in LAYER_WEIGHT_NAMES]
 
 
 _lib = None
@@ -170,6 +176,14 @@ def lib() -> ctypes.CDLL:
                                               ctypes.POINTER(aqt_conformer_layer_shape),
                                               ctypes.POINTER(aqt_layer_policy), _vp,
                                               ctypes.POINTER(aqt_conformer_layer_saved), _vp, _sz, _vp, _vp]
+        L.aqt_layernorm_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
+        L.aqt_mhsa_bwd.argtypes = [_vp, ctypes.POINTER(aqt_mhsa_saved), _i64, _i64, _i64, _int, _int, _int,
+                                   ctypes.POINTER(aqt_dense_policy), _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+        L.aqt_conformer_layer_bwd.argtypes = [_vp, _vp, ctypes.POINTER(aqt_conformer_layer_weights),
+                                              ctypes.POINTER(aqt_conformer_layer_shape),
+                                              ctypes.POINTER(aqt_layer_policy),
+                                              ctypes.POINTER(aqt_conformer_layer_saved), _vp,
+                                              ctypes.POINTER(aqt_conformer_layer_grads), _vp, _sz, _vp]
         for name in SYMBOLS:
             getattr(L, name)  # AttributeError if the library lacks a declared entry point
         _lib = L
@@ -676,7 +690,7 @@ def aqt_attention_bwd(qkv, ctx, dctx, lse, B: int, T: int, heads: int, *, left: 
 class MhsaSaved:
     """Device buffers of the self-attention module (aqt_mhsa_fwd) and their aqt_mhsa_saved view."""
 
-    def __init__(self, B: int, T: int, D: int, policy, device="cuda"):
+    def __init__(self, B: int, T: int, D: int, policy, device="cuda", heads: int = 0):
         (bw1, bx1), (bw2, bx2) = policy
         M = B * T
         self.B, self.T, self.D, self.M = B, T, D, M
@@ -685,7 +699,8 @@ class MhsaSaved:
         self.qkv_f = torch.empty((M, 3 * D), dtype=torch.float32, device=device)
         self.ctx = torch.empty((M, D), dtype=torch.float32, device=device)
         self.row_stats = torch.empty((M, 2), dtype=torch.float32, device=device)
-        self.lse = None        # set to a [M, heads] tensor (and refresh()) to keep what the backward needs
+        # the softmax normalisers, kept for the backward when the head count is given
+        self.lse = torch.empty((M, heads), dtype=torch.float32, device=device) if heads else None
         self.policy = (aqt_dense_policy * 2)(aqt_dense_policy(bw1, bx1), aqt_dense_policy(bw2, bx2))
         self.refresh()
 
@@ -729,14 +744,15 @@ class LayerSaved:
     """Device buffers of one encoder layer (aqt_conformer_layer_fwd) and their aqt_conformer_layer_saved view.
     policy: an aqt_layer_policy."""
 
-    def __init__(self, B: int, T: int, D: int, H: int, policy, device="cuda"):
+    def __init__(self, B: int, T: int, D: int, H: int, policy, device="cuda", heads: int = 0):
         def pair(a, b):
             return ((a.bits_w, a.bits_x), (b.bits_w, b.bits_x))
         M = B * T
         self.policy = policy
         self.ffn1 = FfnSaved(M, D, H, pair(policy.ffn1_in, policy.ffn1_out), device)
         self.ffn2 = FfnSaved(M, D, H, pair(policy.ffn2_in, policy.ffn2_out), device)
-        self.att = MhsaSaved(B, T, D, pair(policy.attn_qkv, policy.attn_out), device)
+        self.att = MhsaSaved(B, T, D, pair(policy.attn_qkv, policy.attn_out), device, heads=heads)
+        self.out_row_stats = torch.empty((M, 2), dtype=torch.float32, device=device)
         self.conv = ConvSaved(B, T, D, pair(policy.conv_pw1, policy.conv_pw2), device)
         self.r = [torch.empty((M, D), dtype=torch.float32, device=device) for _ in range(4)]
         self.m = torch.empty((M, D), dtype=torch.float32, device=device)
@@ -744,7 +760,8 @@ class LayerSaved:
 
     def refresh(self):
         self.c = aqt_conformer_layer_saved(self.ffn1.c, self.ffn2.c, self.att.c, self.conv.c,
-                                           *[t.data_ptr() for t in self.r], self.m.data_ptr())
+                                           *[t.data_ptr() for t in self.r], self.m.data_ptr(),
+                                           self.out_row_stats.data_ptr())
         return self
 
     def prepare(self, weights: dict):
@@ -781,3 +798,56 @@ def aqt_conformer_layer_fwd(x, weights: dict, saved: LayerSaved, *, B: int, T: i
                                        _ptr(dev_status))
     _check(st, "aqt_conformer_layer_fwd")
     return y
+
+
+def aqt_layernorm_bwd(x, row_stats, dy, *, gamma=None, add=None, want_affine=True, ws=None):
+    """aqt_layernorm_bwd: returns (dx [M,D], dgamma [D] or None, dbeta [D] or None)."""
+    _dev(x, torch.float32, "x")
+    _dev(dy, torch.float32, "dy")
+    M, D = x.shape
+    dx = torch.empty_like(x)
+    dg = torch.empty(D, dtype=torch.float32, device=x.device) if want_affine else None
+    db = torch.empty(D, dtype=torch.float32, device=x.device) if want_affine else None
+    ws = workspace(aqt_workspace_bytes(AQT_OP_LAYERNORM_BWD, M, D, 1), x.device) if ws is None else ws
+    st = lib().aqt_layernorm_bwd(_ptr(x), _ptr(row_stats), _ptr(gamma), _ptr(dy), _ptr(add), M, D, _ptr(dx), _ptr(dg),
+                                 _ptr(db), _ptr(ws), ws.numel(), _stream())
+    _check(st, "aqt_layernorm_bwd")
+    return dx, dg, db
+
+
+def aqt_mhsa_bwd(dy, saved: MhsaSaved, heads: int, *, left: int = -1, right: int = -1, ws=None):
+    """aqt_mhsa_bwd: returns dict(dxn, dwqkv, dbqkv, dwo, dbo)."""
+    _dev(dy, torch.float32, "dy")
+    M, D = saved.M, saved.D
+    f32 = dict(dtype=torch.float32, device=dy.device)
+    o = dict(dxn=torch.empty((M, D), **f32), dwqkv=torch.empty((D, 3 * D), **f32), dbqkv=torch.empty(3 * D, **f32),
+             dwo=torch.empty((D, D), **f32), dbo=torch.empty(D, **f32))
+    ws = workspace(aqt_workspace_bytes(AQT_OP_MHSA_BWD, M, D, heads), dy.device) if ws is None else ws
+    st = lib().aqt_mhsa_bwd(_ptr(dy), ctypes.byref(saved.c), saved.B, saved.T, D, heads, left, right, saved.policy,
+                            _ptr(o["dxn"]), _ptr(o["dwqkv"]), _ptr(o["dbqkv"]), _ptr(o["dwo"]), _ptr(o["dbo"]),
+                            _ptr(ws), ws.numel(), _stream())
+    _check(st, "aqt_mhsa_bwd")
+    return o
+
+
+def aqt_conformer_layer_bwd(dy, x, weights: dict, saved: LayerSaved, *, B: int, T: int, H: int, heads: int, kw: int,
+                            pad_left: int, left: int = -1, right: int = -1, eps: float = 1e-6, want=None, ws=None):
+    """aqt_conformer_layer_bwd: returns (dx [B*T, D], dict of weight gradients).  `want`: names of the weights whose
+    gradients are wanted (default: every weight present in `weights` except the fixed normalisation of the
+    convolution module)."""
+    _dev(dy, torch.float32, "dy")
+    M, D = x.shape
+    fixed = ("conv_norm_scale", "conv_norm_shift")
+    want = [n for n in LAYER_WEIGHT_NAMES if weights.get(n) is not None and n not in fixed] if want is None else want
+    grads = {n: torch.empty_like(weights[n]) for n in want}
+    wc = aqt_conformer_layer_weights(*[None if weights.get(n) is None else weights[n].data_ptr()
+                                       for n in LAYER_WEIGHT_NAMES])
+    gc = aqt_conformer_layer_grads(*[grads[n].data_ptr() if n in grads else None for n in LAYER_WEIGHT_NAMES])
+    sh = aqt_conformer_layer_shape(B, T, D, H, heads, kw, pad_left, left, right, eps)
+    dx = torch.empty_like(x)
+    ws = workspace(aqt_workspace_bytes(AQT_OP_CONFORMER_LAYER_BWD, M, D, H), x.device) if ws is None else ws
+    st = lib().aqt_conformer_layer_bwd(_ptr(dy), _ptr(x), ctypes.byref(wc), ctypes.byref(sh),
+                                       ctypes.byref(saved.policy), ctypes.byref(saved.c), _ptr(dx), ctypes.byref(gc),
+                                       _ptr(ws), ws.numel(), _stream())
+    _check(st, "aqt_conformer_layer_bwd")
+    return dx, grads

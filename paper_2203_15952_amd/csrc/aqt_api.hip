@@ -107,10 +107,72 @@ ConvBwdWorkspace carve_conv_bwd(void *ws, int64_t B, int64_t T, int64_t D, int k
   return f;
 }
 
+// Backward of the self-attention module: one dense-backward workspace for either projection, the
+// gradients with respect to ctx [M,D] and qkv [M,3D], the attention backward's row sums.
+struct MhsaBwdWorkspace {
+  size_t core;
+  float *dctx, *dqkv;
+  void *att;
+  size_t total;
+};
+
+MhsaBwdWorkspace carve_mhsa_bwd(void *ws, int64_t M, int64_t D, int heads) {
+  MhsaBwdWorkspace f;
+  const size_t a = bwd_workspace_bytes(M, D, 3 * D), b = bwd_workspace_bytes(M, D, D);
+  f.core = a > b ? a : b;
+  size_t off = f.core;
+  auto take = [&](size_t bytes) {
+    uint8_t *p = ws ? static_cast<uint8_t *>(ws) + off : nullptr;
+    off += align_up(bytes, 256);
+    return p;
+  };
+  const size_t md = static_cast<size_t>(M) * D * sizeof(float);
+  f.dctx = reinterpret_cast<float *>(take(md));
+  f.dqkv = reinterpret_cast<float *>(take(3 * md));
+  f.att = take(attention_bwd_ws_bytes(1, M, heads));
+  f.total = off;
+  return f;
+}
+
+// Backward of the encoder layer: the largest module-backward workspace, then the gradient of the residual
+// stream (two buffers, alternating), a module-input gradient, and the normalisation backward's partials.
+struct LayerBwdWorkspace {
+  size_t module;
+  float *da, *db, *dm;
+  void *ln;
+  size_t total;
+};
+
+size_t conv_bwd_total(int64_t M, int64_t D, int kw);
+
+LayerBwdWorkspace carve_layer_bwd(void *ws, int64_t M, int64_t D, int64_t H, int heads, int kw) {
+  LayerBwdWorkspace f;
+  size_t m = ffn_bwd_ws(M, D, H);
+  const size_t a = carve_mhsa_bwd(nullptr, M, D, heads).total, c = conv_bwd_total(M, D, kw);
+  if (a > m) m = a;
+  if (c > m) m = c;
+  f.module = m;
+  size_t off = m;
+  auto take = [&](size_t bytes) {
+    uint8_t *p = ws ? static_cast<uint8_t *>(ws) + off : nullptr;
+    off += align_up(bytes, 256);
+    return p;
+  };
+  const size_t md = static_cast<size_t>(M) * D * sizeof(float);
+  f.da = reinterpret_cast<float *>(take(md));
+  f.db = reinterpret_cast<float *>(take(md));
+  f.dm = reinterpret_cast<float *>(take(md));
+  f.ln = take(layernorm_bwd_ws_bytes(D));
+  f.total = off;
+  return f;
+}
+
 bool conv_shape_ok(int64_t B, int64_t T, int64_t C, int kw, int pad_left) {
   return B >= 1 && T >= 1 && C >= 1 && kw >= 1 && kw <= 4096 && pad_left >= 0 && pad_left < kw &&
          B <= (int64_t(1) << 40) / T;
 }
+
+size_t conv_bwd_total(int64_t M, int64_t D, int kw) { return carve_conv_bwd(nullptr, 1, M, D, kw).total; }
 
 bool policy_ok(const aqt_dense_policy &p) {
   return bits_ok(p.bits_w) && (p.bits_x == 0 || bits_ok(p.bits_x)) && (p.weights_ready == 0 || p.weights_ready == 1);
@@ -217,6 +279,13 @@ size_t aqt_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int bits_x, 
     case AQT_OP_ATTENTION_BWD:
       if (M < 1 || N < 1) return 0;
       return attention_bwd_ws_bytes(1, M, static_cast<int>(N));
+    case AQT_OP_LAYERNORM_BWD: return (M >= 1 && K >= 1) ? layernorm_bwd_ws_bytes(K) : 0;
+    case AQT_OP_MHSA_BWD:
+      if (!shape_ok(M, K) || N < 1) return 0;
+      return carve_mhsa_bwd(nullptr, M, K, static_cast<int>(N)).total;
+    case AQT_OP_CONFORMER_LAYER_BWD:
+      if (!shape_ok(M, K) || N < 1) return 0;
+      return carve_layer_bwd(nullptr, M, K, N, 64, 32).total;
     case AQT_OP_CONV_MODULE_BWD:
       if (!shape_ok(M, K) || N < 1 || N > 4096) return 0;
       return carve_conv_bwd(nullptr, 1, M, K, static_cast<int>(N)).total;
@@ -711,7 +780,87 @@ aqt_status aqt_conformer_layer_fwd(const float *x, const aqt_conformer_layer_wei
                       M, g.D, g.H, pf2, saved->m, &saved->ffn2, ws, ws_bytes, stream, dev_status));
   AQT_TRY(launch_residual_add(saved->r3, saved->m, 0.5f, saved->r4, n, st));
   return launch_layernorm_quantize(saved->r4, M, g.D, w->out_ln_g, w->out_ln_b, g.ln_eps, 8, nullptr, nullptr, y,
-                                   nullptr, ws, st, dev_status);
+                                   saved->out_row_stats, ws, st, dev_status);
+}
+
+aqt_status aqt_layernorm_bwd(const float *x, const float *row_stats, const float *gamma, const float *dy,
+                             const float *add, int64_t M, int64_t D, float *dx, float *dgamma, float *dbeta,
+                             void *ws, size_t ws_bytes, void *stream) {
+  if (!x || !row_stats || !dy || !dx || !shape_ok(M, D)) return AQT_ERR_INVALID_ARG;
+  if ((dgamma || dbeta) && (!ws || ws_bytes < layernorm_bwd_ws_bytes(D))) return AQT_ERR_WORKSPACE;
+  return launch_layernorm_bwd(x, row_stats, gamma, dy, add, M, D, dx, dgamma, dbeta, ws,
+                              static_cast<hipStream_t>(stream));
+}
+
+aqt_status aqt_mhsa_bwd(const float *dy, const aqt_mhsa_saved *saved, int64_t B, int64_t T, int64_t D, int heads,
+                        int left_context, int right_context, const aqt_dense_policy *policy, float *dxn,
+                        float *dwqkv, float *dbqkv, float *dwo, float *dbo, void *ws, size_t ws_bytes, void *stream) {
+  if (!dy || !saved || !policy || B < 1 || T < 1 || D < 1 || heads < 1 || D % heads) return AQT_ERR_INVALID_ARG;
+  if (!attention_shape_ok(B, T, D, heads)) return AQT_ERR_UNSUPPORTED;
+  if (!policy_ok(policy[0]) || !policy_ok(policy[1]) || policy[0].bits_x == 0 || policy[1].bits_x == 0)
+    return AQT_ERR_UNSUPPORTED;
+  const aqt_saved &l1 = saved->qkv, &l2 = saved->out;
+  if (!saved->lse || !saved->qkv_f || !saved->ctx || !l1.s_x || !l1.s_w || !l2.s_x || !l2.s_w || !l2.wq_kn)
+    return AQT_ERR_INVALID_ARG;
+  if ((dxn && !l1.wq_kn) || (dwqkv && !l1.xq) || (dwo && !l2.xq)) return AQT_ERR_INVALID_ARG;
+  const int64_t M = B * T;
+  MhsaBwdWorkspace f = carve_mhsa_bwd(ws, M, D, heads);
+  if (!ws || ws_bytes < f.total) return AQT_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // output projection: gradient with respect to the attention result
+  AQT_TRY(launch_dense_bwd(dy, &l2, M, D, D, f.dctx, dwo, dbo, ws, f.core, st));
+  if (!dxn && !dwqkv && !dbqkv) return AQT_OK;
+  // attention, then the fused projection
+  AQT_TRY(launch_attention_bwd(saved->qkv_f, saved->ctx, f.dctx, saved->lse, B, T, D, heads, left_context,
+                               right_context, f.dqkv, f.att, st));
+  return launch_dense_bwd(f.dqkv, &l1, M, D, 3 * D, dxn, dwqkv, dbqkv, ws, f.core, st);
+}
+
+aqt_status aqt_conformer_layer_bwd(const float *dy, const float *x, const aqt_conformer_layer_weights *w,
+                                   const aqt_conformer_layer_shape *shape, const aqt_layer_policy *policy,
+                                   const aqt_conformer_layer_saved *saved, float *dx,
+                                   const aqt_conformer_layer_grads *grads, void *ws, size_t ws_bytes, void *stream) {
+  if (!dy || !x || !w || !shape || !policy || !saved || !dx || !grads) return AQT_ERR_INVALID_ARG;
+  const aqt_conformer_layer_shape &g = *shape;
+  if (g.B < 1 || g.T < 1 || g.D < 1 || g.H < 1 || g.B > (int64_t(1) << 40) / g.T) return AQT_ERR_INVALID_ARG;
+  if (grads->conv_norm_scale || grads->conv_norm_shift) return AQT_ERR_UNSUPPORTED;
+  if (!saved->r1 || !saved->r2 || !saved->r3 || !saved->r4 || !saved->out_row_stats || !saved->ffn1.row_stats ||
+      !saved->ffn2.row_stats || !saved->att.row_stats || !saved->conv.row_stats || !w->conv_wdw)
+    return AQT_ERR_INVALID_ARG;
+  if (!conv_shape_ok(g.B, g.T, g.D, g.kw, g.pad_left) || !attention_shape_ok(g.B, g.T, g.D, g.heads))
+    return AQT_ERR_UNSUPPORTED;
+  const int64_t M = g.B * g.T, n = M * g.D;
+  LayerBwdWorkspace f = carve_layer_bwd(ws, M, g.D, g.H, g.heads, g.kw);
+  if (!ws || ws_bytes < f.total) return AQT_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const aqt_dense_policy pf1[2] = {policy->ffn1_in, policy->ffn1_out}, pa[2] = {policy->attn_qkv, policy->attn_out};
+  const aqt_dense_policy pc[2] = {policy->conv_pw1, policy->conv_pw2}, pf2[2] = {policy->ffn2_in, policy->ffn2_out};
+  // final normalisation: gradient of the residual stream r4
+  AQT_TRY(launch_layernorm_bwd(saved->r4, saved->out_row_stats, w->out_ln_g, dy, nullptr, M, g.D, f.da, grads->out_ln_g,
+                               grads->out_ln_b, f.ln, st));
+  // second feed-forward module entered the stream with weight 1/2: r4 = r3 + ffn(r3) / 2
+  AQT_TRY(launch_scale(f.da, 0.5f, f.dm, n, st));
+  AQT_TRY(aqt_ffn_bwd(f.dm, &saved->ffn2, M, g.D, g.H, pf2, f.dm, grads->ffn2_w1, grads->ffn2_b1, grads->ffn2_w2,
+                      grads->ffn2_b2, ws, f.module, stream));
+  AQT_TRY(launch_layernorm_bwd(saved->r3, saved->ffn2.row_stats, w->ffn2_ln_g, f.dm, f.da, M, g.D, f.db,
+                               grads->ffn2_ln_g, grads->ffn2_ln_b, f.ln, st));
+  // convolution module: r3 = r2 + conv(r2)
+  AQT_TRY(aqt_conv_module_bwd(f.db, &saved->conv, w->conv_wdw, g.B, g.T, g.D, g.kw, g.pad_left, pc, f.dm,
+                              grads->conv_w1, grads->conv_b1, grads->conv_wdw, grads->conv_bdw, grads->conv_w2,
+                              grads->conv_b2, ws, f.module, stream));
+  AQT_TRY(launch_layernorm_bwd(saved->r2, saved->conv.row_stats, w->conv_ln_g, f.dm, f.db, M, g.D, f.da,
+                               grads->conv_ln_g, grads->conv_ln_b, f.ln, st));
+  // self-attention module: r2 = r1 + mhsa(r1)
+  AQT_TRY(aqt_mhsa_bwd(f.da, &saved->att, g.B, g.T, g.D, g.heads, g.left_context, g.right_context, pa, f.dm,
+                       grads->att_wqkv, grads->att_bqkv, grads->att_wo, grads->att_bo, ws, f.module, stream));
+  AQT_TRY(launch_layernorm_bwd(saved->r1, saved->att.row_stats, w->att_ln_g, f.dm, f.da, M, g.D, f.db,
+                               grads->att_ln_g, grads->att_ln_b, f.ln, st));
+  // first feed-forward module: r1 = x + ffn(x) / 2
+  AQT_TRY(launch_scale(f.db, 0.5f, f.dm, n, st));
+  AQT_TRY(aqt_ffn_bwd(f.dm, &saved->ffn1, M, g.D, g.H, pf1, f.dm, grads->ffn1_w1, grads->ffn1_b1, grads->ffn1_w2,
+                      grads->ffn1_b2, ws, f.module, stream));
+  return launch_layernorm_bwd(x, saved->ffn1.row_stats, w->ffn1_ln_g, f.dm, f.db, M, g.D, dx, grads->ffn1_ln_g,
+                              grads->ffn1_ln_b, f.ln, st);
 }
 
 }  // extern "C"

@@ -104,6 +104,11 @@ size_t layernorm_ws_bytes(int64_t M);
 aqt_status launch_layernorm_quantize(const float *x, int64_t M, int64_t D, const float *gamma, const float *beta,
                                      float eps, int bits, int8_t *q, float *scale, float *y_out, float *row_stats,
                                      void *ws, hipStream_t st, int32_t *dev_status);
+size_t layernorm_bwd_ws_bytes(int64_t D);
+aqt_status launch_layernorm_bwd(const float *x, const float *stats, const float *gamma, const float *dy,
+                                const float *add, int64_t M, int64_t D, float *dx, float *dgamma, float *dbeta,
+                                void *ws, hipStream_t st);
+aqt_status launch_scale(const float *m, float alpha, float *out, int64_t n, hipStream_t st);
 aqt_status launch_dact_mul(const float *dout, const float *dact, int64_t M, int64_t N, int64_t oc, float *dv,
                            hipStream_t st);
 aqt_status launch_residual_add(const float *x, const float *m, float alpha, float *out, int64_t n, hipStream_t st);

@@ -181,6 +181,146 @@ __global__ __launch_bounds__(kThreads) void ln_quantize_kernel(const float *__re
   }
 }
 
+// Backward of the normalisation.  With xh = (x - mean) rstd (statistics as the forward stored them) and
+// g = dy gamma:  dx = (g - mean_row(g) - xh mean_row(g xh)) rstd (+ add, the gradient arriving over the
+// residual connection), dgamma = sum_m dy xh, dbeta = sum_m dy.  One wavefront per row; each lane keeps
+// column sums for its own columns over the rows its workgroup walks, the four wavefronts are added in LDS
+// in a fixed order and the workgroup leaves one partial per column; ln_bwd_fold_kernel adds the partials
+// in order.  NV as in ln_stats_kernel (NV = 0: any row, one column per lane and step).
+template <int NV>
+__global__ __launch_bounds__(kThreads) void ln_bwd_kernel(const float *__restrict__ x, const float *__restrict__ stats,
+                                                          const float *__restrict__ gamma,
+                                                          const float *__restrict__ dy, const float *__restrict__ add,
+                                                          int64_t M, int64_t D, float *__restrict__ dx,
+                                                          float *__restrict__ part) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const float invD = 1.0f / static_cast<float>(D);
+  if constexpr (NV > 0) {
+    __shared__ v4f sm[4][2][NV][64];
+    v4f ag[NV], ab[NV], gm[NV];
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      ag[k] = ab[k] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+      const int64_t c = 4 * (lane + 64 * k);
+      gm[k] = (gamma && c < D) ? *reinterpret_cast<const v4f *>(gamma + c) : v4f{1.0f, 1.0f, 1.0f, 1.0f};
+    }
+    for (int64_t m = static_cast<int64_t>(blockIdx.x) * 4 + wave; m < M; m += static_cast<int64_t>(gridDim.x) * 4) {
+      v4f xv[NV], gv[NV];
+      load_row<NV>(x + m * D, D, lane, xv);
+      load_row<NV>(dy + m * D, D, lane, gv);
+      const float mean = stats[2 * m], rstd = stats[2 * m + 1];
+      float sg = 0.0f, sgx = 0.0f;
+#pragma unroll
+      for (int k = 0; k < NV; ++k) {
+        const bool in = 4 * (lane + 64 * k) < D;
+        v4f xh;
+        xh.x = (xv[k].x - mean) * rstd; xh.y = (xv[k].y - mean) * rstd;
+        xh.z = (xv[k].z - mean) * rstd; xh.w = (xv[k].w - mean) * rstd;
+        if (!in) xh = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+        ag[k].x += gv[k].x * xh.x; ag[k].y += gv[k].y * xh.y; ag[k].z += gv[k].z * xh.z; ag[k].w += gv[k].w * xh.w;
+        ab[k].x += gv[k].x; ab[k].y += gv[k].y; ab[k].z += gv[k].z; ab[k].w += gv[k].w;
+        gv[k].x *= gm[k].x; gv[k].y *= gm[k].y; gv[k].z *= gm[k].z; gv[k].w *= gm[k].w;      // g = dy gamma
+        sg += (gv[k].x + gv[k].y) + (gv[k].z + gv[k].w);
+        sgx += (gv[k].x * xh.x + gv[k].y * xh.y) + (gv[k].z * xh.z + gv[k].w * xh.w);
+        xv[k] = xh;
+      }
+      const float mg = wave_sum(sg) * invD, mgx = wave_sum(sgx) * invD;
+#pragma unroll
+      for (int k = 0; k < NV; ++k) {
+        const int64_t c = 4 * (lane + 64 * k);
+        if (c < D) {
+          v4f o;
+          o.x = (gv[k].x - mg - xv[k].x * mgx) * rstd; o.y = (gv[k].y - mg - xv[k].y * mgx) * rstd;
+          o.z = (gv[k].z - mg - xv[k].z * mgx) * rstd; o.w = (gv[k].w - mg - xv[k].w * mgx) * rstd;
+          if (add) {
+            const v4f a = *reinterpret_cast<const v4f *>(add + m * D + c);
+            o.x += a.x; o.y += a.y; o.z += a.z; o.w += a.w;
+          }
+          *reinterpret_cast<v4f *>(dx + m * D + c) = o;
+        }
+      }
+    }
+    if (part) {
+#pragma unroll
+      for (int k = 0; k < NV; ++k) {
+        sm[wave][0][k][lane] = ag[k];
+        sm[wave][1][k][lane] = ab[k];
+      }
+      __syncthreads();
+      if (wave < 2) {   // wavefront 0 folds the gamma sums, wavefront 1 the beta sums
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+          const int64_t c = 4 * (lane + 64 * k);
+          if (c < D) {
+            const v4f a = sm[0][wave][k][lane], b = sm[1][wave][k][lane], c2 = sm[2][wave][k][lane], d = sm[3][wave][k][lane];
+            v4f o;
+            o.x = ((a.x + b.x) + c2.x) + d.x; o.y = ((a.y + b.y) + c2.y) + d.y;
+            o.z = ((a.z + b.z) + c2.z) + d.z; o.w = ((a.w + b.w) + c2.w) + d.w;
+            *reinterpret_cast<v4f *>(part + (static_cast<int64_t>(blockIdx.x) * 2 + wave) * D + c) = o;
+          }
+        }
+      }
+    }
+  } else {
+    // any row length: the row statistics of g by two passes over the row, then dx; the column sums are
+    // left to ln_bwd_colsum_kernel
+    for (int64_t m = static_cast<int64_t>(blockIdx.x) * 4 + wave; m < M; m += static_cast<int64_t>(gridDim.x) * 4) {
+      const float mean = stats[2 * m], rstd = stats[2 * m + 1];
+      float sg = 0.0f, sgx = 0.0f;
+      for (int64_t c = lane; c < D; c += 64) {
+        const float g = dy[m * D + c] * (gamma ? gamma[c] : 1.0f), xh = (x[m * D + c] - mean) * rstd;
+        sg += g;
+        sgx += g * xh;
+      }
+      const float mg = wave_sum(sg) * invD, mgx = wave_sum(sgx) * invD;
+      for (int64_t c = lane; c < D; c += 64) {
+        const float g = dy[m * D + c] * (gamma ? gamma[c] : 1.0f), xh = (x[m * D + c] - mean) * rstd;
+        float o = (g - mg - xh * mgx) * rstd;
+        if (add) o += add[m * D + c];
+        dx[m * D + c] = o;
+      }
+    }
+  }
+}
+
+// Any row length: partial column sums of dy xh and dy over a slab of rows, one thread per column.
+__global__ __launch_bounds__(kThreads) void ln_bwd_colsum_kernel(const float *__restrict__ x,
+                                                                 const float *__restrict__ stats,
+                                                                 const float *__restrict__ dy, int64_t M, int64_t D,
+                                                                 int64_t rows_per_slab, float *__restrict__ part) {
+  const int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  if (c >= D) return;
+  const int64_t m0 = static_cast<int64_t>(blockIdx.y) * rows_per_slab;
+  const int64_t m1 = m0 + rows_per_slab < M ? m0 + rows_per_slab : M;
+  float ag = 0.0f, ab = 0.0f;
+  for (int64_t m = m0; m < m1; ++m) {
+    const float g = dy[m * D + c];
+    ag += g * ((x[m * D + c] - stats[2 * m]) * stats[2 * m + 1]);
+    ab += g;
+  }
+  part[(static_cast<int64_t>(blockIdx.y) * 2) * D + c] = ag;
+  part[(static_cast<int64_t>(blockIdx.y) * 2 + 1) * D + c] = ab;
+}
+
+__global__ __launch_bounds__(kThreads) void ln_bwd_fold_kernel(const float *__restrict__ part, int P, int64_t D,
+                                                               float *__restrict__ dgamma, float *__restrict__ dbeta) {
+  const int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+  if (c >= D) return;
+  float ag = 0.0f, ab = 0.0f;
+  for (int p = 0; p < P; ++p) {
+    ag += part[(static_cast<int64_t>(p) * 2) * D + c];
+    ab += part[(static_cast<int64_t>(p) * 2 + 1) * D + c];
+  }
+  if (dgamma) dgamma[c] = ag;
+  if (dbeta) dbeta[c] = ab;
+}
+
+// out = alpha * m
+__global__ __launch_bounds__(kThreads) void scale_kernel(const float *m, float alpha, float *out, int64_t n) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < n; i += stride) out[i] = alpha * m[i];
+}
+
 // dv[m,n] = dout[m, n mod oc] * dact[m,n]  (chain rule through the activation)
 __global__ __launch_bounds__(kThreads) void dact_mul_kernel(const float *__restrict__ dout,
                                                             const float *__restrict__ dact, int64_t M, int64_t N,
@@ -327,6 +467,50 @@ aqt_status launch_layernorm_quantize(const float *x, int64_t M, int64_t D, const
   const int qm = q ? qmax_of(bits) : 1;
   if (vec) ln_quantize_kernel<true><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, stats, partial, g, qm, q, scale, y_out, dev_status);
   else ln_quantize_kernel<false><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, stats, partial, g, qm, q, scale, y_out, dev_status);
+  AQT_HIP(hipGetLastError());
+  return AQT_OK;
+}
+
+constexpr int kLnBwdBlocks = 512;   // workgroups (= column-sum partials) of the normalisation's backward
+
+size_t layernorm_bwd_ws_bytes(int64_t D) {
+  return align_up(static_cast<size_t>(kLnBwdBlocks) * 2 * D * sizeof(float), 256);
+}
+
+aqt_status launch_layernorm_bwd(const float *x, const float *stats, const float *gamma, const float *dy,
+                                const float *add, int64_t M, int64_t D, float *dx, float *dgamma, float *dbeta,
+                                void *ws, hipStream_t st) {
+  const bool want_cols = dgamma || dbeta;
+  float *part = want_cols ? static_cast<float *>(ws) : nullptr;
+  const bool vec = (D % 4 == 0) && D <= 1024 && reinterpret_cast<uintptr_t>(x) % 16 == 0 &&
+                   reinterpret_cast<uintptr_t>(dy) % 16 == 0 && reinterpret_cast<uintptr_t>(dx) % 16 == 0 &&
+                   (!add || reinterpret_cast<uintptr_t>(add) % 16 == 0) &&
+                   (!gamma || reinterpret_cast<uintptr_t>(gamma) % 16 == 0);
+  const int g = grid_cap(M, 4, kLnBwdBlocks);
+  int P = g;
+  if (vec && D <= 512) ln_bwd_kernel<2><<<g, kThreads, 0, st>>>(x, stats, gamma, dy, add, M, D, dx, part);
+  else if (vec) ln_bwd_kernel<4><<<g, kThreads, 0, st>>>(x, stats, gamma, dy, add, M, D, dx, part);
+  else {
+    ln_bwd_kernel<0><<<g, kThreads, 0, st>>>(x, stats, gamma, dy, add, M, D, dx, nullptr);
+    if (want_cols) {
+      AQT_HIP(hipGetLastError());
+      P = static_cast<int>(cdiv(M, 256) < kLnBwdBlocks ? cdiv(M, 256) : kLnBwdBlocks);
+      const int64_t rows = cdiv(M, P);
+      P = static_cast<int>(cdiv(M, rows));
+      dim3 grid(static_cast<unsigned>(cdiv(D, kThreads)), static_cast<unsigned>(P));
+      ln_bwd_colsum_kernel<<<grid, kThreads, 0, st>>>(x, stats, dy, M, D, rows, part);
+    }
+  }
+  AQT_HIP(hipGetLastError());
+  if (want_cols) {
+    ln_bwd_fold_kernel<<<static_cast<unsigned>(cdiv(D, kThreads)), kThreads, 0, st>>>(part, P, D, dgamma, dbeta);
+    AQT_HIP(hipGetLastError());
+  }
+  return AQT_OK;
+}
+
+aqt_status launch_scale(const float *m, float alpha, float *out, int64_t n, hipStream_t st) {
+  scale_kernel<<<grid_cap(n, kThreads * 4, 4096), kThreads, 0, st>>>(m, alpha, out, n);
   AQT_HIP(hipGetLastError());
   return AQT_OK;
 }

@@ -184,3 +184,45 @@ def test_attention_backward(B_, T, D, heads, left, right):
         sc = np.where(ok[None, :, None, :], sc, -np.inf)
         want = np.log2(np.exp(sc - sc.max(-1, keepdims=True)).sum(-1)) + sc.max(-1) * np.log2(np.e)
         np.testing.assert_allclose(host(lse).reshape(B_, T, heads), want, rtol=0, atol=2e-5 * (1 + np.abs(want).max()))
+
+
+@pytest.mark.parametrize("B_,T,D,heads,left,right,policy", [
+    (8, 200, 512, 8, -1, -1, ((8, 8), (8, 8))),
+    (3, 70, 128, 4, 23, 0, ((4, 8), (8, 8))),
+    (2, 19, 24, 2, -1, 2, ((8, 4), (4, 8))),
+])
+def test_mhsa_backward_stage_by_stage(B_, T, D, heads, left, right, policy):
+    from parity_util import check_grad
+    say("mhsa bwd", B_, T, D, heads, left, right, policy)
+    M = B_ * T
+    rng = np.random.default_rng(750 + M)
+    x = rng.standard_normal((M, D)).astype(F)
+    wqkv, bqkv = (rng.standard_normal((D, 3 * D)) / np.sqrt(D)).astype(F), (0.1 * rng.standard_normal(3 * D)).astype(F)
+    wo, bo = (rng.standard_normal((D, D)) / np.sqrt(D)).astype(F), (0.1 * rng.standard_normal(D)).astype(F)
+    dy = (0.1 * rng.standard_normal((M, D))).astype(F)
+    (bw1, bx1), (bw2, bx2) = policy
+    sv = B.MhsaSaved(B_, T, D, policy, heads=heads)
+    B.aqt_mhsa_fwd(dev(x), dev(wqkv), dev(bqkv), dev(wo), dev(bo), sv, heads, left=left, right=right)
+    o = B.aqt_mhsa_bwd(dev(dy), sv, heads, left=left, right=right)
+    # output projection against the oracle on the GPU's own codes
+    xq2, sx2, wq2, sw2 = host(sv.out.xq), host(sv.out.s_x), host(sv.out.wq_kn), host(sv.out.s_w)
+    g2 = oracle.dense_bwd(dy, xq2, sx2[0], wq2, sw2)
+    check_grad(host(o["dwo"]), g2["dw"], g2["dw_abs"], "dwo")
+    check_grad(host(o["dbo"]), g2["dbias"], np.abs(dy.astype(np.float64)).sum(0), "dbo")
+    sv2 = B.Saved(M, D, D, bw2)
+    sv2.xq.copy_(sv.out.xq); sv2.s_x.copy_(sv.out.s_x); sv2.wq_kn.copy_(sv.out.wq_kn); sv2.s_w.copy_(sv.out.s_w)
+    dctx, _, _ = B.aqt_dense_bwd(dev(dy), sv2, bx2, bw2, want_dw=False)
+    dctx_h = host(dctx)
+    check_grad(dctx_h, g2["dx"], g2["dx_abs"], "dctx")
+    # attention: the oracle fed the float32 gradient and projections the GPU used
+    qkv_h = host(sv.qkv_f)
+    dqkv = B.aqt_attention_bwd(sv.qkv_f, sv.ctx, dctx, sv.lse, B_, T, heads, left=left, right=right)
+    ref, mag = oracle.attention_bwd(qkv_h.reshape(B_, T, 3 * D), dctx_h.reshape(B_, T, D), heads, left, right)
+    dqkv_h = host(dqkv)
+    check_grad(dqkv_h, ref.reshape(M, 3 * D), mag.reshape(M, 3 * D), "dqkv")
+    # fused projection
+    xq1, sx1, wq1, sw1 = host(sv.qkv.xq), host(sv.qkv.s_x), host(sv.qkv.wq_kn), host(sv.qkv.s_w)
+    g1 = oracle.dense_bwd(dqkv_h, xq1, sx1[0], wq1, sw1)
+    check_grad(host(o["dxn"]), g1["dx"], g1["dx_abs"], "dxn")
+    check_grad(host(o["dwqkv"]), g1["dw"], g1["dw_abs"], "dwqkv")
+    check_grad(host(o["dbqkv"]), g1["dbias"], np.abs(dqkv_h.astype(np.float64)).sum(0), "dbqkv")

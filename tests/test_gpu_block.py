@@ -278,3 +278,43 @@ def test_ffn_chain_weight_only_policy():
     np.testing.assert_array_equal(host(sv2.l2.xq), xq2)
     wq2b, sw2b = oracle.quantize(w2, 4, 0)
     check_forward(host(y2), oracle.dense_fwd_q(xq2, sx2[0], wq2b, sw2b, b2, 0), sx2[0], sw2b, b2, 0)
+
+
+# ----------------------------------------------------------------------------
+# backward of the normalisation
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("M,D,affine,with_add", [(12800, 512, True, True), (100, 77, True, False), (3, 1, False, True),
+                                                 (257, 1024, True, True), (64, 2048, True, True), (1, 512, False, False),
+                                                 (1000, 144, True, True)])
+def test_layernorm_backward(M, D, affine, with_add):
+    say("layernorm bwd", M, D, affine, with_add)
+    rng = np.random.default_rng(900 + M + D)
+    x = (rng.standard_normal((M, D)) * 2 + 0.5).astype(F)
+    gamma = (1 + 0.2 * rng.standard_normal(D)).astype(F) if affine else None
+    beta = (0.1 * rng.standard_normal(D)).astype(F) if affine else None
+    dy = rng.standard_normal((M, D)).astype(F)
+    add = rng.standard_normal((M, D)).astype(F) if with_add else None
+    _, _, _, stats = B.aqt_layernorm_quantize(dev(x), 8, gamma=None if gamma is None else dev(gamma),
+                                              beta=None if beta is None else dev(beta), want_stats=True)
+    dx, dg, db = B.aqt_layernorm_bwd(dev(x), stats, dev(dy), gamma=None if gamma is None else dev(gamma),
+                                     add=None if add is None else dev(add))
+    rdx, rdg, rdb = oracle.layernorm_bwd(x, dy, gamma, 1e-6)
+    # dx is a difference of three terms: hold it to 1e-5 of the sum of their magnitudes (float32 row sums over D
+    # terms and the forward's own float32 statistics); the column sums to the gradient bar
+    xd = x.astype(np.float64)
+    r = 1.0 / np.sqrt(xd.var(1, keepdims=True) + 1e-6)
+    xh = (xd - xd.mean(1, keepdims=True)) * r
+    g = dy.astype(np.float64) * (1.0 if gamma is None else gamma.astype(np.float64))
+    mag = (np.abs(g) + np.abs(g).mean(1, keepdims=True) + np.abs(xh) * np.abs(g * xh).mean(1, keepdims=True)) * r
+    want = rdx + (0.0 if add is None else add.astype(np.float64))
+    bad = np.abs(host(dx) - want) > 1e-5 * (mag + (0.0 if add is None else np.abs(add))) + 1e-30
+    assert not bad.any(), f"{bad.sum()} of {bad.size} dx outside tolerance"
+    check_grad(host(dg), rdg, (np.abs(dy.astype(np.float64)) * np.abs(xh)).sum(0), "dgamma")
+    check_grad(host(db), rdb, np.abs(dy.astype(np.float64)).sum(0), "dbeta")
+    dx2, dg2, db2 = B.aqt_layernorm_bwd(dev(x), stats, dev(dy), gamma=None if gamma is None else dev(gamma),
+                                        add=None if add is None else dev(add))
+    for p, q in ((dx, dx2), (dg, dg2), (db, db2)):
+        np.testing.assert_array_equal(host(p), host(q))
+    dx3, _, _ = B.aqt_layernorm_bwd(dev(x), stats, dev(dy), gamma=None if gamma is None else dev(gamma),
+                                    add=None if add is None else dev(add), want_affine=False)
+    np.testing.assert_array_equal(host(dx3), host(dx))

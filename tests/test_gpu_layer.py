@@ -83,7 +83,7 @@ def float_layer(x, w, B_, T, D, heads, kw, pl, left, right):
 
 
 def run_layer(x_d, wd, policy, B_, T, D, H, heads, kw, pl, left, right):
-    sv = B.LayerSaved(B_, T, D, H, policy)
+    sv = B.LayerSaved(B_, T, D, H, policy, heads=heads)
     status = B.new_status()
     y = B.aqt_conformer_layer_fwd(x_d, wd, sv, B=B_, T=T, H=H, heads=heads, kw=kw, pad_left=pl, left=left, right=right,
                                   dev_status=status)
@@ -229,3 +229,91 @@ def test_layer_call_replays_from_a_hip_graph():
             B.aqt_residual_add(x_in, x_in, 0.5)          # unrelated eager work between replays
             torch.cuda.synchronize()
     assert host(status)[0] == 0
+
+
+def torch_float_layer(x, w, B_, T, D, heads, kw, pl, left, right):
+    """The encoder layer in float64 PyTorch on the CPU, no quantization, for its gradients by autograd."""
+    import torch.nn.functional as Fn
+
+    def ln(r, p):
+        return Fn.layer_norm(r, (D,), w[f"{p}_ln_g"], w[f"{p}_ln_b"], eps=1e-6)
+
+    def swish(v):
+        return v * torch.sigmoid(v)
+
+    def ffn(r, p):
+        return swish(ln(r, p) @ w[f"{p}_w1"] + w[f"{p}_b1"]) @ w[f"{p}_w2"] + w[f"{p}_b2"]
+
+    dh = D // heads
+    r1 = x + 0.5 * ffn(x, "ffn1")
+    qkv = (ln(r1, "att") @ w["att_wqkv"] + w["att_bqkv"]).reshape(B_, T, 3, heads, dh)
+    sc = torch.einsum("bthd,bjhd->bhtj", qkv[:, :, 0], qkv[:, :, 1]) / dh ** 0.5
+    t_i, j_i = torch.arange(T)[:, None], torch.arange(T)[None, :]
+    ok = torch.ones((T, T), dtype=torch.bool)
+    if left >= 0:
+        ok &= j_i >= t_i - left
+    if right >= 0:
+        ok &= j_i <= t_i + right
+    ctx = torch.einsum("bhtj,bjhd->bthd", torch.softmax(sc.masked_fill(~ok, float("-inf")), -1), qkv[:, :, 2])
+    r2 = r1 + ctx.reshape(-1, D) @ w["att_wo"] + w["att_bo"]
+    pre = ln(r2, "conv") @ w["conv_w1"] + w["conv_b1"]
+    g = (pre[:, :D] * torch.sigmoid(pre[:, D:])).reshape(B_, T, D).transpose(1, 2)            # [B, D, T]
+    v = Fn.conv1d(Fn.pad(g, (pl, kw - 1 - pl)), w["conv_wdw"].t().unsqueeze(1), w["conv_bdw"], groups=D)
+    v = v.transpose(1, 2).reshape(-1, D)
+    r3 = r2 + swish(v * w["conv_norm_scale"] + w["conv_norm_shift"]) @ w["conv_w2"] + w["conv_b2"]
+    r4 = r3 + 0.5 * ffn(r3, "ffn2")
+    return Fn.layer_norm(r4, (D,), w["out_ln_g"], w["out_ln_b"], eps=1e-6)
+
+
+def test_conformer_layer_backward_equals_its_modules_and_tracks_the_float_gradient():
+    B_, T, D, H, heads, kw, pl, left, right = 4, 150, 256, 1024, 4, 15, 14, 23, 0
+    M = B_ * T
+    say("encoder layer bwd", B_, T, D, H)
+    w = layer_weights(830, D, H, kw)
+    rng = np.random.default_rng(831)
+    x = rng.standard_normal((M, D)).astype(F)
+    dy = (0.1 * rng.standard_normal((M, D))).astype(F)
+    wd = {k: dev(v) for k, v in w.items()}
+    x_d, dy_d = dev(x), dev(dy)
+    # float64 reference gradients by autograd (CPU)
+    wt = {k: torch.tensor(v, dtype=torch.float64, requires_grad=True) for k, v in w.items()}
+    xt = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+    torch_float_layer(xt, wt, B_, T, D, heads, kw, pl, left, right).backward(torch.tensor(dy, dtype=torch.float64))
+    errs = {}
+    for name, bits_w in (("int8", 8), ("int4", 4)):
+        pol = B.aqt_policy_preset(B.AQT_POLICY_ALL, 1, 0, bits_w, 8)[0]
+        y, sv = run_layer(x_d, wd, pol, B_, T, D, H, heads, kw, pl, left, right)
+        dx, grads = B.aqt_conformer_layer_bwd(dy_d, x_d, wd, sv, B=B_, T=T, H=H, heads=heads, kw=kw, pad_left=pl,
+                                              left=left, right=right)
+        assert set(grads) == set(w) - {"conv_norm_scale", "conv_norm_shift"}
+
+        def rel(a, b):
+            return float(np.linalg.norm(a - b) / np.linalg.norm(b))
+        e = {"dx": rel(host(dx), xt.grad.numpy())}
+        for k in grads:
+            e[k] = rel(host(grads[k]), wt[k].grad.numpy())
+        errs[name] = e
+        say(" ", name, "dx", round(e["dx"], 4), "worst weight gradient", max(e, key=e.get), round(max(e.values()), 4))
+        # the same backward through the public module calls, bit for bit
+        def pair(a, b):
+            return ((a.bits_w, a.bits_x), (b.bits_w, b.bits_x))
+        dr4, g_o, b_o = B.aqt_layernorm_bwd(sv.r[3], sv.out_row_stats, dy_d, gamma=wd["out_ln_g"])
+        half = B.aqt_residual_add(dr4, dr4, -0.5)                          # dr4 / 2, exactly
+        dxn, dw1, db1, dw2, db2 = B.aqt_ffn_bwd(half, sv.ffn2)
+        dr3, g_f2, _ = B.aqt_layernorm_bwd(sv.r[2], sv.ffn2.row_stats, dxn, gamma=wd["ffn2_ln_g"], add=dr4)
+        c = B.aqt_conv_module_bwd(dr3, sv.conv, wd["conv_wdw"], pad_left=pl)
+        dr2, _, _ = B.aqt_layernorm_bwd(sv.r[1], sv.conv.row_stats, c["dxn"], gamma=wd["conv_ln_g"], add=dr3)
+        a = B.aqt_mhsa_bwd(dr2, sv.att, heads, left=left, right=right)
+        dr1, _, _ = B.aqt_layernorm_bwd(sv.r[0], sv.att.row_stats, a["dxn"], gamma=wd["att_ln_g"], add=dr2)
+        half = B.aqt_residual_add(dr1, dr1, -0.5)
+        dxn1, dw1a, _, _, _ = B.aqt_ffn_bwd(half, sv.ffn1)
+        dx_b, _, _ = B.aqt_layernorm_bwd(x_d, sv.ffn1.row_stats, dxn1, gamma=wd["ffn1_ln_g"], add=dr1)
+        np.testing.assert_array_equal(host(dx_b), host(dx))
+        for got, want in ((grads["out_ln_g"], g_o), (grads["out_ln_b"], b_o), (grads["ffn2_w1"], dw1),
+                          (grads["ffn2_w2"], dw2), (grads["ffn2_ln_g"], g_f2), (grads["conv_wdw"], c["dw_dw"]),
+                          (grads["conv_w1"], c["dw1"]), (grads["att_wqkv"], a["dwqkv"]), (grads["att_bo"], a["dbo"]),
+                          (grads["ffn1_w1"], dw1a)):
+            np.testing.assert_array_equal(host(got), host(want))
+    # straight-through gradients of the int8 layer stay close to the float layer's true gradients; int4 is coarser
+    assert errs["int8"]["dx"] < 0.05 and max(errs["int8"].values()) < 0.10
+    assert errs["int8"]["dx"] < errs["int4"]["dx"] < 0.40
