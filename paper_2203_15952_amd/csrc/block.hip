@@ -306,13 +306,22 @@ __global__ __launch_bounds__(kThreads) void ln_bwd_fold_kernel(const float *__re
                                                                float *__restrict__ dgamma, float *__restrict__ dbeta) {
   const int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
   if (c >= D) return;
-  float ag = 0.0f, ab = 0.0f;
-  for (int p = 0; p < P; ++p) {
-    ag += part[(static_cast<int64_t>(p) * 2) * D + c];
-    ab += part[(static_cast<int64_t>(p) * 2 + 1) * D + c];
+  // four independent running sums per output so that loads overlap; the order of the additions is fixed
+  float ag[4] = {0.0f, 0.0f, 0.0f, 0.0f}, ab[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  int p = 0;
+  for (; p + 4 <= P; p += 4) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      ag[u] += part[(static_cast<int64_t>(p + u) * 2) * D + c];
+      ab[u] += part[(static_cast<int64_t>(p + u) * 2 + 1) * D + c];
+    }
   }
-  if (dgamma) dgamma[c] = ag;
-  if (dbeta) dbeta[c] = ab;
+  for (; p < P; ++p) {
+    ag[0] += part[(static_cast<int64_t>(p) * 2) * D + c];
+    ab[0] += part[(static_cast<int64_t>(p) * 2 + 1) * D + c];
+  }
+  if (dgamma) dgamma[c] = (ag[0] + ag[1]) + (ag[2] + ag[3]);
+  if (dbeta) dbeta[c] = (ab[0] + ab[1]) + (ab[2] + ab[3]);
 }
 
 // out = alpha * m

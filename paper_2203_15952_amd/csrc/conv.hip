@@ -293,8 +293,18 @@ __global__ __launch_bounds__(kThreads) void dwconv_dw_fold_kernel(const float *_
   const int64_t rows = kw + 1;
   const int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
   if (i >= rows * C) return;
-  float s = 0.0f;
-  for (int p = 0; p < P; ++p) s += part[static_cast<int64_t>(p) * rows * C + i];
+  // four independent running sums (partials p = 0, 4, 8, ...; 1, 5, ...; ...) so that loads overlap; the order
+  // of the additions is fixed all the same
+  float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+  int p = 0;
+  for (; p + 4 <= P; p += 4) {
+    s0 += part[static_cast<int64_t>(p) * rows * C + i];
+    s1 += part[static_cast<int64_t>(p + 1) * rows * C + i];
+    s2 += part[static_cast<int64_t>(p + 2) * rows * C + i];
+    s3 += part[static_cast<int64_t>(p + 3) * rows * C + i];
+  }
+  for (; p < P; ++p) s0 += part[static_cast<int64_t>(p) * rows * C + i];
+  const float s = (s0 + s1) + (s2 + s3);
   if (i < static_cast<int64_t>(kw) * C) {
     if (dw) dw[i] = s;
   } else if (dbias) {

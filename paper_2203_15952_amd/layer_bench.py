@@ -66,7 +66,7 @@ def main():
     y = torch.empty((M, D), dtype=torch.float32, device="cuda")
     ws = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_CONFORMER_LAYER_FWD, M, D, H))
     status = B.new_status()
-    sv = B.LayerSaved(Bc, T, D, H, pol)
+    sv = B.LayerSaved(Bc, T, D, H, pol, heads=a.heads)
     if a.serving:
         sv.prepare(w)
     out = {"shape": {"utterances": Bc, "frames": T, "d_model": D, "d_ff": H, "heads": a.heads, "kernel": kw},
@@ -94,6 +94,19 @@ def main():
     torch.cuda.synchronize()
     out["graph_replay_equals_eager"] = bool(torch.equal(y, eager))
     out["encoder_layer_fwd_graph_replay"] = timed(graph.replay, a.steps, a.warmup)
+    if not a.serving:
+        # training: straight-through backward of the whole layer (input gradient and all weight gradients)
+        dy = torch.randn((M, D), device="cuda", generator=gen) * 0.1
+        wsb = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_CONFORMER_LAYER_BWD, M, D, H))
+        layer()
+        out["encoder_layer_bwd"] = timed(lambda: B.aqt_conformer_layer_bwd(
+            dy, x, w, sv, B=Bc, T=T, H=H, heads=a.heads, kw=kw, pad_left=a.pad_left, left=a.left_context,
+            right=a.right_context, ws=wsb), a.steps, a.warmup)
+        dctx = torch.randn((M, D), device="cuda", generator=gen) * 0.1
+        wsa = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_ATTENTION_BWD, M, 1, a.heads))
+        out["attention_core_bwd"] = timed(lambda: B.aqt_attention_bwd(
+            sv.att.qkv_f, sv.att.ctx, dctx, sv.att.lse, Bc, T, a.heads, left=a.left_context, right=a.right_context,
+            ws=wsa), a.steps, a.warmup)
     out["ffn_module_fwd"] = timed(lambda: B.aqt_ffn_fwd(x, w["ffn1_w1"], None, w["ffn1_w2"], None, sv.ffn1, y=y, ws=ws,
                                                         dev_status=status), a.steps, a.warmup)
     out["mhsa_module_fwd"] = timed(lambda: B.aqt_mhsa_fwd(x, w["att_wqkv"], None, w["att_wo"], None, sv.att, a.heads,
