@@ -80,6 +80,30 @@ __device__ __forceinline__ void stage_tile(float *__restrict__ dst, const float 
   }
 }
 
+// The two halves of stage_tile, so that the loads of the next step can be in flight while this step is
+// being computed: sixteen clamped loads into registers, and later the sixteen LDS writes (with the zeros).
+__device__ __forceinline__ void load_tile(float (&v)[16], const float *__restrict__ src, int64_t ld_src,
+                                          const AttnGeom &g, int64_t b, int64_t row0, int64_t col0) {
+  const int d = threadIdx.x & 63, r0 = threadIdx.x >> 6;
+  const int dd = d < g.dh ? d : g.dh - 1;
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    int64_t t = row0 + r0 + 4 * k;
+    t = t < g.T ? t : g.T - 1;
+    v[k] = src[(b * g.T + t) * ld_src + col0 + dd];
+  }
+}
+__device__ __forceinline__ void store_tile(float *__restrict__ dst, const float (&v)[16], const AttnGeom &g,
+                                           int64_t row0, bool permute) {
+  const int d = threadIdx.x & 63, r0 = threadIdx.x >> 6;
+  const int at = permute ? parity_major(d) : d;
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    const int r = r0 + 4 * k;
+    dst[r * kLd + at] = (d < g.dh && row0 + r < g.T) ? v[k] : 0.0f;
+  }
+}
+
 __global__ __launch_bounds__(kThreads, 2) void attention_fwd_kernel(const float *__restrict__ qkv, AttnGeom g,
                                                                  float *__restrict__ ctx,
                                                                  uint32_t *__restrict__ absmax,
@@ -127,11 +151,19 @@ __global__ __launch_bounds__(kThreads, 2) void attention_fwd_kernel(const float 
     o[0][r] = 0.0f;
     o[1][r] = 0.0f;
   }
-  for (int64_t j0 = jmin / kK * kK; j0 <= jmax; j0 += kK) {
+  float kn[16], vn[16];   // keys and values of the next step, on their way from memory while this step computes
+  const int64_t jfirst = jmin / kK * kK;
+  load_tile(kn, qkv, 3 * g.D, g, b, jfirst, g.D + hc);
+  load_tile(vn, qkv, 3 * g.D, g, b, jfirst, 2 * g.D + hc);
+  for (int64_t j0 = jfirst; j0 <= jmax; j0 += kK) {
     __syncthreads();   // the queries have been taken / the previous step's reads of Ks and Vs are over
-    stage_tile(Ks, qkv, 3 * g.D, g, b, j0, g.D + hc, true);
-    stage_tile(Vs, qkv, 3 * g.D, g, b, j0, 2 * g.D + hc, false);
+    store_tile(Ks, kn, g, j0, true);
+    store_tile(Vs, vn, g, j0, false);
     __syncthreads();
+    if (j0 + kK <= jmax) {
+      load_tile(kn, qkv, 3 * g.D, g, b, j0 + kK, g.D + hc);
+      load_tile(vn, qkv, 3 * g.D, g, b, j0 + kK, 2 * g.D + hc);
+    }
     if (active) {
       // s[nb][r]: score of key j0 + 32 nb + 8 (r / 4) + 4 lk + r % 4 against this lane's query
       v16f s[2];
@@ -349,11 +381,19 @@ __global__ __launch_bounds__(kThreads) void attention_bwd_dq_kernel(const float 
     dq[0][r] = 0.0f;
     dq[1][r] = 0.0f;
   }
-  for (int64_t j0 = jmin / kK * kK; j0 <= jmax; j0 += kK) {
+  float kn[16], vn[16];   // keys and values of the next step, in flight while this step computes
+  const int64_t jfirst = jmin / kK * kK;
+  load_tile(kn, qkv, 3 * g.D, g, b, jfirst, g.D + hc);
+  load_tile(vn, qkv, 3 * g.D, g, b, jfirst, 2 * g.D + hc);
+  for (int64_t j0 = jfirst; j0 <= jmax; j0 += kK) {
     __syncthreads();
-    stage_tile(Kp, qkv, 3 * g.D, g, b, j0, g.D + hc, true);
-    stage_tile(Vp, qkv, 3 * g.D, g, b, j0, 2 * g.D + hc, true);
+    store_tile(Kp, kn, g, j0, true);
+    store_tile(Vp, vn, g, j0, true);
     __syncthreads();
+    if (j0 + kK <= jmax) {
+      load_tile(kn, qkv, 3 * g.D, g, b, j0 + kK, g.D + hc);
+      load_tile(vn, qkv, 3 * g.D, g, b, j0 + kK, 2 * g.D + hc);
+    }
     if (active) {
       v16f s[2], dp[2];
       mma_tile_regs(s, Kp, qf, lr, lk);     // S^T: keys x this lane's query
@@ -416,16 +456,24 @@ __global__ __launch_bounds__(kThreads) void attention_bwd_dkv_kernel(const float
     dk[0][r] = 0.0f; dk[1][r] = 0.0f;
     dv[0][r] = 0.0f; dv[1][r] = 0.0f;
   }
-  for (int64_t tq = tmin / kK * kK; tq <= tmax; tq += kK) {
+  float qn[16], gn[16];   // queries and upstream gradient rows of the next step, in flight while this step computes
+  const int64_t tfirst = tmin / kK * kK;
+  load_tile(qn, qkv, 3 * g.D, g, b, tfirst, hc);
+  load_tile(gn, dctx, g.D, g, b, tfirst, hc);
+  for (int64_t tq = tfirst; tq <= tmax; tq += kK) {
     __syncthreads();
-    stage_tile(Qp, qkv, 3 * g.D, g, b, tq, hc, true);
-    stage_tile(Gp, dctx, g.D, g, b, tq, hc, true);
+    store_tile(Qp, qn, g, tq, true);
+    store_tile(Gp, gn, g, tq, true);
     if (tid < kK) {
       const int64_t tt = tq + tid < g.T ? tq + tid : g.T - 1;
       Ls[tid] = lse[(b * g.T + tt) * g.heads + h];
       Ds[tid] = dsum[(b * g.T + tt) * g.heads + h];
     }
     __syncthreads();
+    if (tq + kK <= tmax) {
+      load_tile(qn, qkv, 3 * g.D, g, b, tq + kK, hc);
+      load_tile(gn, dctx, g.D, g, b, tq + kK, hc);
+    }
     if (active) {
       v16f s[2], dp[2];
       mma_tile_regs(s, Qp, kf, lr, lk);     // S: queries x this lane's key
