@@ -317,3 +317,16 @@ def test_conformer_layer_backward_equals_its_modules_and_tracks_the_float_gradie
     # straight-through gradients of the int8 layer stay close to the float layer's true gradients; int4 is coarser
     assert errs["int8"]["dx"] < 0.05 and max(errs["int8"].values()) < 0.10
     assert errs["int8"]["dx"] < errs["int4"]["dx"] < 0.40
+
+
+def test_native_quantization_aware_training_reduces_the_loss_and_serves_what_it_trained():
+    # two encoder layers (the first with int4 weights), Adam on the float32 master weights, gradients from
+    # aqt_conformer_layer_bwd; then the serving form on weights quantized once
+    from paper_2203_15952_amd import train_demo
+    out = train_demo.main(["--steps", "40", "--utterances", "4", "--frames", "96", "--d-model", "128", "--d-ff", "256",
+                           "--heads", "2"])
+    say(out)
+    assert out["device_status"] == 0
+    assert out["loss_last"] < 0.6 * out["loss_first"]
+    assert out["served_equals_trained_bit_for_bit"]
+    assert out["weight_bytes_quantized"] < 0.25 * out["weight_bytes_float32"]
