@@ -181,6 +181,14 @@ bool policy_ok(const aqt_dense_policy &p) {
 // The weight side of one dense layer inside a module call.  Training: quantize w now (the quantizer
 // also emits the matrix-core operand into `wfrag` when the contraction kernel takes one).  Serving
 // (weights_ready): nothing to do; the prepared operand of the layer is used if there is one.
+// A module called inside a layer: its input is x + alpha * m (the residual stream plus the previous module's
+// output), formed by the module's normalisation pass and left in r_out.
+struct ResidualIn {
+  const float *m;
+  float alpha;
+  float *r_out;
+};
+
 struct WeightSide {
   void *operand;   // what launch_dense_fwd_q gets as its workspace
   bool prepared;   // whether it already holds the matrix-core operand
@@ -213,6 +221,133 @@ bool acc_fits(int64_t K, int bits_x, int bits_w) {
 }  // namespace aqt
 
 using namespace aqt;
+
+static aqt_status ffn_fwd_impl(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps, const float *w1,
+                       const float *b1, const float *w2, const float *b2, int64_t M, int64_t D, int64_t H,
+                       const aqt_dense_policy *policy, float *y, const aqt_ffn_saved *saved, void *ws,
+                       size_t ws_bytes, void *stream, int32_t *dev_status, const ResidualIn *res) {
+  if (!x || !y || !policy || !saved || !shape_ok(M, D) || H < 1 || !(ln_eps >= 0.0f)) return AQT_ERR_INVALID_ARG;
+  const aqt_dense_policy p1 = policy[0], p2 = policy[1];
+  if (!policy_ok(p1) || !policy_ok(p2)) return AQT_ERR_UNSUPPORTED;
+  const aqt_saved &l1 = saved->l1, &l2 = saved->l2;
+  if (!saved->h || !l1.wq_packed || !l1.s_w || !l2.wq_packed || !l2.s_w) return AQT_ERR_INVALID_ARG;
+  if (p1.bits_x ? (!l1.xq || !l1.s_x) : !saved->xn) return AQT_ERR_INVALID_ARG;
+  if (p2.bits_x && (!l2.xq || !l2.s_x)) return AQT_ERR_INVALID_ARG;
+  if (p1.bits_x && !acc_fits(D, p1.bits_x, p1.bits_w)) return AQT_ERR_UNSUPPORTED;
+  if (p2.bits_x && !acc_fits(H, p2.bits_x, p2.bits_w)) return AQT_ERR_UNSUPPORTED;
+  FfnWorkspace f = carve_ffn_fwd(ws, M, D, H);
+  if (!ws || ws_bytes < f.total) return AQT_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  // normalisation (+ first quantizer), first weights, first contraction with Swish
+  WeightSide s1, s2;
+  AQT_TRY(weight_side(p1, w1, l1, M, D, H, AQT_EPI_SWISH, f.wpart1, f.wfrag1, st, dev_status, &s1));
+  const bool want_absmax = p2.bits_x != 0;
+  if (p1.bits_x) {
+    AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, saved->xn,
+                                      saved->row_stats, f.ln, st, dev_status, res ? res->m : nullptr,
+                                      res ? res->alpha : 0.0f, res ? res->r_out : nullptr));
+    AQT_TRY(launch_dense_fwd_q(l1.xq, l1.s_x, l1.wq_packed, l1.s_w, M, D, H, p1.bits_w, b1, AQT_EPI_SWISH, saved->h,
+                               nullptr, want_absmax ? reinterpret_cast<uint32_t *>(f.h_absmax) : nullptr, s1.operand,
+                               st, l1.dact, s1.prepared));
+  } else {
+    AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, 8, nullptr, nullptr, saved->xn,
+                                      saved->row_stats, f.ln, st, dev_status, res ? res->m : nullptr,
+                                      res ? res->alpha : 0.0f, res ? res->r_out : nullptr));
+    AQT_TRY(launch_dense_fwd_wonly(saved->xn, l1.wq_packed, l1.s_w, M, D, H, p1.bits_w, b1, AQT_EPI_SWISH, saved->h,
+                                   f.wfrag1, st));
+  }
+  // second quantizer (one pass when the producer emitted max|h|), second weights, second contraction
+  AQT_TRY(weight_side(p2, w2, l2, M, H, D, AQT_EPI_NONE, f.wpart2, f.wfrag2, st, dev_status, &s2));
+  if (p2.bits_x) {
+    if (p1.bits_x) {
+      AQT_TRY(launch_quantize_with_absmax(saved->h, M, H, H, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),
+                                          l2.xq, l2.s_x, l2.mask_x, st, dev_status));
+    } else {
+      AQT_TRY(launch_quantize(saved->h, M, H, H, p2.bits_x, AQT_AXIS_ALL, l2.xq, l2.s_x, l2.mask_x,
+                              static_cast<float *>(f.ln), st, dev_status));
+    }
+    return launch_dense_fwd_q(l2.xq, l2.s_x, l2.wq_packed, l2.s_w, M, H, D, p2.bits_w, b2, AQT_EPI_NONE, y, nullptr,
+                              nullptr, s2.operand, st, nullptr, s2.prepared);
+  }
+  return launch_dense_fwd_wonly(saved->h, l2.wq_packed, l2.s_w, M, H, D, p2.bits_w, b2, AQT_EPI_NONE, y, f.wfrag2, st);
+}
+
+static aqt_status conv_module_fwd_impl(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps,
+                               const float *w1, const float *b1, const float *w_dw, const float *b_dw,
+                               const float *norm_scale, const float *norm_shift, const float *w2, const float *b2,
+                               int64_t B, int64_t T, int64_t D, int kw, int pad_left, const aqt_dense_policy *policy,
+                               float *y, const aqt_conv_saved *saved, void *ws, size_t ws_bytes, void *stream,
+                               int32_t *dev_status, const ResidualIn *res) {
+  if (!x || !w_dw || !y || !policy || !saved || !conv_shape_ok(B, T, D, kw, pad_left) || !(ln_eps >= 0.0f))
+    return AQT_ERR_INVALID_ARG;
+  const aqt_dense_policy p1 = policy[0], p2 = policy[1];
+  if (!policy_ok(p1) || !policy_ok(p2) || p1.bits_x == 0 || p2.bits_x == 0) return AQT_ERR_UNSUPPORTED;
+  const aqt_saved &l1 = saved->pw1, &l2 = saved->pw2;
+  if (!saved->g || !saved->s || !l1.xq || !l1.s_x || !l1.wq_packed || !l1.s_w || !l2.xq || !l2.s_x ||
+      !l2.wq_packed || !l2.s_w)
+    return AQT_ERR_INVALID_ARG;
+  if (!acc_fits(D, p1.bits_x, p1.bits_w) || !acc_fits(D, p2.bits_x, p2.bits_w)) return AQT_ERR_UNSUPPORTED;
+  const int64_t M = B * T;
+  FfnWorkspace f = carve_ffn_fwd(ws, M, D, 2 * D);
+  if (!ws || ws_bytes < f.total) return AQT_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  // normalisation + first quantizer, first pointwise convolution with the GLU
+  WeightSide s1, s2;
+  AQT_TRY(weight_side(p1, w1, l1, M, D, 2 * D, AQT_EPI_GLU, f.wpart1, f.wfrag1, st, dev_status, &s1));
+  AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, nullptr,
+                                    saved->row_stats, f.ln, st, dev_status, res ? res->m : nullptr,
+                                      res ? res->alpha : 0.0f, res ? res->r_out : nullptr));
+  AQT_TRY(launch_dense_fwd_q(l1.xq, l1.s_x, l1.wq_packed, l1.s_w, M, D, 2 * D, p1.bits_w, b1, AQT_EPI_GLU, saved->g,
+                             nullptr, nullptr, s1.operand, st, l1.dact, s1.prepared));
+  // depthwise convolution, normalisation, Swish; max|s| for the one-pass quantizer
+  AQT_TRY(launch_dwconv_fwd(saved->g, w_dw, b_dw, norm_scale, norm_shift, 1, B, T, D, kw, pad_left, saved->s,
+                            saved->dfac, reinterpret_cast<uint32_t *>(f.h_absmax), st));
+  // second pointwise convolution
+  AQT_TRY(weight_side(p2, w2, l2, M, D, D, AQT_EPI_NONE, f.wpart2, f.wfrag2, st, dev_status, &s2));
+  AQT_TRY(launch_quantize_with_absmax(saved->s, M, D, D, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),
+                                      l2.xq, l2.s_x, l2.mask_x, st, dev_status));
+  return launch_dense_fwd_q(l2.xq, l2.s_x, l2.wq_packed, l2.s_w, M, D, D, p2.bits_w, b2, AQT_EPI_NONE, y, nullptr,
+                            nullptr, s2.operand, st, nullptr, s2.prepared);
+}
+
+static aqt_status mhsa_fwd_impl(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps, const float *wqkv,
+                        const float *bqkv, const float *wo, const float *bo, int64_t B, int64_t T, int64_t D,
+                        int heads, int left_context, int right_context, const aqt_dense_policy *policy, float *y,
+                        const aqt_mhsa_saved *saved, void *ws, size_t ws_bytes, void *stream, int32_t *dev_status, const ResidualIn *res) {
+  if (!x || !y || !policy || !saved || B < 1 || T < 1 || D < 1 || heads < 1 || D % heads || !(ln_eps >= 0.0f))
+    return AQT_ERR_INVALID_ARG;
+  if (!attention_shape_ok(B, T, D, heads)) return AQT_ERR_UNSUPPORTED;
+  const aqt_dense_policy p1 = policy[0], p2 = policy[1];
+  if (!policy_ok(p1) || !policy_ok(p2) || p1.bits_x == 0 || p2.bits_x == 0) return AQT_ERR_UNSUPPORTED;
+  const aqt_saved &l1 = saved->qkv, &l2 = saved->out;
+  if (!saved->qkv_f || !saved->ctx || !l1.xq || !l1.s_x || !l1.wq_packed || !l1.s_w || !l2.xq || !l2.s_x ||
+      !l2.wq_packed || !l2.s_w)
+    return AQT_ERR_INVALID_ARG;
+  if (!acc_fits(D, p1.bits_x, p1.bits_w) || !acc_fits(D, p2.bits_x, p2.bits_w)) return AQT_ERR_UNSUPPORTED;
+  const int64_t M = B * T;
+  FfnWorkspace f = carve_ffn_fwd(ws, M, D, 3 * D);
+  if (!ws || ws_bytes < f.total) return AQT_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // normalisation + first quantizer, fused projection of queries, keys and values
+  WeightSide s1, s2;
+  AQT_TRY(weight_side(p1, wqkv, l1, M, D, 3 * D, AQT_EPI_NONE, f.wpart1, f.wfrag1, st, dev_status, &s1));
+  AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, nullptr,
+                                    saved->row_stats, f.ln, st, dev_status, res ? res->m : nullptr,
+                                      res ? res->alpha : 0.0f, res ? res->r_out : nullptr));
+  AQT_TRY(launch_dense_fwd_q(l1.xq, l1.s_x, l1.wq_packed, l1.s_w, M, D, 3 * D, p1.bits_w, bqkv, AQT_EPI_NONE,
+                             saved->qkv_f, nullptr, nullptr, s1.operand, st, nullptr, s1.prepared));
+  // attention in float32; max|ctx| for the one-pass quantizer
+  AQT_TRY(launch_attention(saved->qkv_f, B, T, D, heads, left_context, right_context, saved->ctx,
+                           reinterpret_cast<uint32_t *>(f.h_absmax), saved->lse, st));
+  // output projection
+  AQT_TRY(weight_side(p2, wo, l2, M, D, D, AQT_EPI_NONE, f.wpart2, f.wfrag2, st, dev_status, &s2));
+  AQT_TRY(launch_quantize_with_absmax(saved->ctx, M, D, D, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),
+                                      l2.xq, l2.s_x, l2.mask_x, st, dev_status));
+  return launch_dense_fwd_q(l2.xq, l2.s_x, l2.wq_packed, l2.s_w, M, D, D, p2.bits_w, bo, AQT_EPI_NONE, y, nullptr,
+                            nullptr, s2.operand, st, nullptr, s2.prepared);
+}
 
 extern "C" {
 
@@ -537,49 +672,7 @@ aqt_status aqt_ffn_fwd(const float *x, const float *ln_gamma, const float *ln_be
                        const float *b1, const float *w2, const float *b2, int64_t M, int64_t D, int64_t H,
                        const aqt_dense_policy *policy, float *y, const aqt_ffn_saved *saved, void *ws,
                        size_t ws_bytes, void *stream, int32_t *dev_status) {
-  if (!x || !y || !policy || !saved || !shape_ok(M, D) || H < 1 || !(ln_eps >= 0.0f)) return AQT_ERR_INVALID_ARG;
-  const aqt_dense_policy p1 = policy[0], p2 = policy[1];
-  if (!policy_ok(p1) || !policy_ok(p2)) return AQT_ERR_UNSUPPORTED;
-  const aqt_saved &l1 = saved->l1, &l2 = saved->l2;
-  if (!saved->h || !l1.wq_packed || !l1.s_w || !l2.wq_packed || !l2.s_w) return AQT_ERR_INVALID_ARG;
-  if (p1.bits_x ? (!l1.xq || !l1.s_x) : !saved->xn) return AQT_ERR_INVALID_ARG;
-  if (p2.bits_x && (!l2.xq || !l2.s_x)) return AQT_ERR_INVALID_ARG;
-  if (p1.bits_x && !acc_fits(D, p1.bits_x, p1.bits_w)) return AQT_ERR_UNSUPPORTED;
-  if (p2.bits_x && !acc_fits(H, p2.bits_x, p2.bits_w)) return AQT_ERR_UNSUPPORTED;
-  FfnWorkspace f = carve_ffn_fwd(ws, M, D, H);
-  if (!ws || ws_bytes < f.total) return AQT_ERR_WORKSPACE;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-
-  // normalisation (+ first quantizer), first weights, first contraction with Swish
-  WeightSide s1, s2;
-  AQT_TRY(weight_side(p1, w1, l1, M, D, H, AQT_EPI_SWISH, f.wpart1, f.wfrag1, st, dev_status, &s1));
-  const bool want_absmax = p2.bits_x != 0;
-  if (p1.bits_x) {
-    AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, saved->xn,
-                                      saved->row_stats, f.ln, st, dev_status));
-    AQT_TRY(launch_dense_fwd_q(l1.xq, l1.s_x, l1.wq_packed, l1.s_w, M, D, H, p1.bits_w, b1, AQT_EPI_SWISH, saved->h,
-                               nullptr, want_absmax ? reinterpret_cast<uint32_t *>(f.h_absmax) : nullptr, s1.operand,
-                               st, l1.dact, s1.prepared));
-  } else {
-    AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, 8, nullptr, nullptr, saved->xn,
-                                      saved->row_stats, f.ln, st, dev_status));
-    AQT_TRY(launch_dense_fwd_wonly(saved->xn, l1.wq_packed, l1.s_w, M, D, H, p1.bits_w, b1, AQT_EPI_SWISH, saved->h,
-                                   f.wfrag1, st));
-  }
-  // second quantizer (one pass when the producer emitted max|h|), second weights, second contraction
-  AQT_TRY(weight_side(p2, w2, l2, M, H, D, AQT_EPI_NONE, f.wpart2, f.wfrag2, st, dev_status, &s2));
-  if (p2.bits_x) {
-    if (p1.bits_x) {
-      AQT_TRY(launch_quantize_with_absmax(saved->h, M, H, H, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),
-                                          l2.xq, l2.s_x, l2.mask_x, st, dev_status));
-    } else {
-      AQT_TRY(launch_quantize(saved->h, M, H, H, p2.bits_x, AQT_AXIS_ALL, l2.xq, l2.s_x, l2.mask_x,
-                              static_cast<float *>(f.ln), st, dev_status));
-    }
-    return launch_dense_fwd_q(l2.xq, l2.s_x, l2.wq_packed, l2.s_w, M, H, D, p2.bits_w, b2, AQT_EPI_NONE, y, nullptr,
-                              nullptr, s2.operand, st, nullptr, s2.prepared);
-  }
-  return launch_dense_fwd_wonly(saved->h, l2.wq_packed, l2.s_w, M, H, D, p2.bits_w, b2, AQT_EPI_NONE, y, f.wfrag2, st);
+  return ffn_fwd_impl(x, ln_gamma, ln_beta, ln_eps, w1, b1, w2, b2, M, D, H, policy, y, saved, ws, ws_bytes, stream, dev_status, nullptr);
 }
 
 aqt_status aqt_ffn_bwd(const float *dy, const aqt_ffn_saved *saved, int64_t M, int64_t D, int64_t H,
@@ -629,36 +722,7 @@ aqt_status aqt_conv_module_fwd(const float *x, const float *ln_gamma, const floa
                                int64_t B, int64_t T, int64_t D, int kw, int pad_left, const aqt_dense_policy *policy,
                                float *y, const aqt_conv_saved *saved, void *ws, size_t ws_bytes, void *stream,
                                int32_t *dev_status) {
-  if (!x || !w_dw || !y || !policy || !saved || !conv_shape_ok(B, T, D, kw, pad_left) || !(ln_eps >= 0.0f))
-    return AQT_ERR_INVALID_ARG;
-  const aqt_dense_policy p1 = policy[0], p2 = policy[1];
-  if (!policy_ok(p1) || !policy_ok(p2) || p1.bits_x == 0 || p2.bits_x == 0) return AQT_ERR_UNSUPPORTED;
-  const aqt_saved &l1 = saved->pw1, &l2 = saved->pw2;
-  if (!saved->g || !saved->s || !l1.xq || !l1.s_x || !l1.wq_packed || !l1.s_w || !l2.xq || !l2.s_x ||
-      !l2.wq_packed || !l2.s_w)
-    return AQT_ERR_INVALID_ARG;
-  if (!acc_fits(D, p1.bits_x, p1.bits_w) || !acc_fits(D, p2.bits_x, p2.bits_w)) return AQT_ERR_UNSUPPORTED;
-  const int64_t M = B * T;
-  FfnWorkspace f = carve_ffn_fwd(ws, M, D, 2 * D);
-  if (!ws || ws_bytes < f.total) return AQT_ERR_WORKSPACE;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-
-  // normalisation + first quantizer, first pointwise convolution with the GLU
-  WeightSide s1, s2;
-  AQT_TRY(weight_side(p1, w1, l1, M, D, 2 * D, AQT_EPI_GLU, f.wpart1, f.wfrag1, st, dev_status, &s1));
-  AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, nullptr,
-                                    saved->row_stats, f.ln, st, dev_status));
-  AQT_TRY(launch_dense_fwd_q(l1.xq, l1.s_x, l1.wq_packed, l1.s_w, M, D, 2 * D, p1.bits_w, b1, AQT_EPI_GLU, saved->g,
-                             nullptr, nullptr, s1.operand, st, l1.dact, s1.prepared));
-  // depthwise convolution, normalisation, Swish; max|s| for the one-pass quantizer
-  AQT_TRY(launch_dwconv_fwd(saved->g, w_dw, b_dw, norm_scale, norm_shift, 1, B, T, D, kw, pad_left, saved->s,
-                            saved->dfac, reinterpret_cast<uint32_t *>(f.h_absmax), st));
-  // second pointwise convolution
-  AQT_TRY(weight_side(p2, w2, l2, M, D, D, AQT_EPI_NONE, f.wpart2, f.wfrag2, st, dev_status, &s2));
-  AQT_TRY(launch_quantize_with_absmax(saved->s, M, D, D, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),
-                                      l2.xq, l2.s_x, l2.mask_x, st, dev_status));
-  return launch_dense_fwd_q(l2.xq, l2.s_x, l2.wq_packed, l2.s_w, M, D, D, p2.bits_w, b2, AQT_EPI_NONE, y, nullptr,
-                            nullptr, s2.operand, st, nullptr, s2.prepared);
+  return conv_module_fwd_impl(x, ln_gamma, ln_beta, ln_eps, w1, b1, w_dw, b_dw, norm_scale, norm_shift, w2, b2, B, T, D, kw, pad_left, policy, y, saved, ws, ws_bytes, stream, dev_status, nullptr);
 }
 
 aqt_status aqt_conv_module_bwd(const float *dy, const aqt_conv_saved *saved, const float *w_dw, int64_t B, int64_t T,
@@ -711,36 +775,7 @@ aqt_status aqt_mhsa_fwd(const float *x, const float *ln_gamma, const float *ln_b
                         const float *bqkv, const float *wo, const float *bo, int64_t B, int64_t T, int64_t D,
                         int heads, int left_context, int right_context, const aqt_dense_policy *policy, float *y,
                         const aqt_mhsa_saved *saved, void *ws, size_t ws_bytes, void *stream, int32_t *dev_status) {
-  if (!x || !y || !policy || !saved || B < 1 || T < 1 || D < 1 || heads < 1 || D % heads || !(ln_eps >= 0.0f))
-    return AQT_ERR_INVALID_ARG;
-  if (!attention_shape_ok(B, T, D, heads)) return AQT_ERR_UNSUPPORTED;
-  const aqt_dense_policy p1 = policy[0], p2 = policy[1];
-  if (!policy_ok(p1) || !policy_ok(p2) || p1.bits_x == 0 || p2.bits_x == 0) return AQT_ERR_UNSUPPORTED;
-  const aqt_saved &l1 = saved->qkv, &l2 = saved->out;
-  if (!saved->qkv_f || !saved->ctx || !l1.xq || !l1.s_x || !l1.wq_packed || !l1.s_w || !l2.xq || !l2.s_x ||
-      !l2.wq_packed || !l2.s_w)
-    return AQT_ERR_INVALID_ARG;
-  if (!acc_fits(D, p1.bits_x, p1.bits_w) || !acc_fits(D, p2.bits_x, p2.bits_w)) return AQT_ERR_UNSUPPORTED;
-  const int64_t M = B * T;
-  FfnWorkspace f = carve_ffn_fwd(ws, M, D, 3 * D);
-  if (!ws || ws_bytes < f.total) return AQT_ERR_WORKSPACE;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  // normalisation + first quantizer, fused projection of queries, keys and values
-  WeightSide s1, s2;
-  AQT_TRY(weight_side(p1, wqkv, l1, M, D, 3 * D, AQT_EPI_NONE, f.wpart1, f.wfrag1, st, dev_status, &s1));
-  AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, nullptr,
-                                    saved->row_stats, f.ln, st, dev_status));
-  AQT_TRY(launch_dense_fwd_q(l1.xq, l1.s_x, l1.wq_packed, l1.s_w, M, D, 3 * D, p1.bits_w, bqkv, AQT_EPI_NONE,
-                             saved->qkv_f, nullptr, nullptr, s1.operand, st, nullptr, s1.prepared));
-  // attention in float32; max|ctx| for the one-pass quantizer
-  AQT_TRY(launch_attention(saved->qkv_f, B, T, D, heads, left_context, right_context, saved->ctx,
-                           reinterpret_cast<uint32_t *>(f.h_absmax), saved->lse, st));
-  // output projection
-  AQT_TRY(weight_side(p2, wo, l2, M, D, D, AQT_EPI_NONE, f.wpart2, f.wfrag2, st, dev_status, &s2));
-  AQT_TRY(launch_quantize_with_absmax(saved->ctx, M, D, D, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),
-                                      l2.xq, l2.s_x, l2.mask_x, st, dev_status));
-  return launch_dense_fwd_q(l2.xq, l2.s_x, l2.wq_packed, l2.s_w, M, D, D, p2.bits_w, bo, AQT_EPI_NONE, y, nullptr,
-                            nullptr, s2.operand, st, nullptr, s2.prepared);
+  return mhsa_fwd_impl(x, ln_gamma, ln_beta, ln_eps, wqkv, bqkv, wo, bo, B, T, D, heads, left_context, right_context, policy, y, saved, ws, ws_bytes, stream, dev_status, nullptr);
 }
 
 aqt_status aqt_residual_add(const float *x, const float *m, float alpha, float *out, int64_t n, void *stream) {
@@ -756,31 +791,33 @@ aqt_status aqt_conformer_layer_fwd(const float *x, const aqt_conformer_layer_wei
   const aqt_conformer_layer_shape &g = *shape;
   if (g.B < 1 || g.T < 1 || g.D < 1 || g.H < 1 || g.B > (int64_t(1) << 40) / g.T) return AQT_ERR_INVALID_ARG;
   if (!saved->r1 || !saved->r2 || !saved->r3 || !saved->r4 || !saved->m) return AQT_ERR_INVALID_ARG;
-  const int64_t M = g.B * g.T, n = M * g.D;
+  const int64_t M = g.B * g.T;
   if (!ws || ws_bytes < aqt_workspace_bytes(AQT_OP_CONFORMER_LAYER_FWD, M, g.D, g.H, 8, 8)) return AQT_ERR_WORKSPACE;
-  hipStream_t st = static_cast<hipStream_t>(stream);
   const aqt_dense_policy pf1[2] = {policy->ffn1_in, policy->ffn1_out}, pa[2] = {policy->attn_qkv, policy->attn_out};
   const aqt_dense_policy pc[2] = {policy->conv_pw1, policy->conv_pw2}, pf2[2] = {policy->ffn2_in, policy->ffn2_out};
-  // half-step feed-forward module
-  AQT_TRY(aqt_ffn_fwd(x, w->ffn1_ln_g, w->ffn1_ln_b, g.ln_eps, w->ffn1_w1, w->ffn1_b1, w->ffn1_w2, w->ffn1_b2, M, g.D,
-                      g.H, pf1, saved->m, &saved->ffn1, ws, ws_bytes, stream, dev_status));
-  AQT_TRY(launch_residual_add(x, saved->m, 0.5f, saved->r1, n, st));
-  // self-attention module
-  AQT_TRY(aqt_mhsa_fwd(saved->r1, w->att_ln_g, w->att_ln_b, g.ln_eps, w->att_wqkv, w->att_bqkv, w->att_wo, w->att_bo,
-                       g.B, g.T, g.D, g.heads, g.left_context, g.right_context, pa, saved->m, &saved->att, ws, ws_bytes,
-                       stream, dev_status));
-  AQT_TRY(launch_residual_add(saved->r1, saved->m, 1.0f, saved->r2, n, st));
-  // convolution module
-  AQT_TRY(aqt_conv_module_fwd(saved->r2, w->conv_ln_g, w->conv_ln_b, g.ln_eps, w->conv_w1, w->conv_b1, w->conv_wdw,
-                              w->conv_bdw, w->conv_norm_scale, w->conv_norm_shift, w->conv_w2, w->conv_b2, g.B, g.T,
-                              g.D, g.kw, g.pad_left, pc, saved->m, &saved->conv, ws, ws_bytes, stream, dev_status));
-  AQT_TRY(launch_residual_add(saved->r2, saved->m, 1.0f, saved->r3, n, st));
-  // second half-step feed-forward module, final normalisation
-  AQT_TRY(aqt_ffn_fwd(saved->r3, w->ffn2_ln_g, w->ffn2_ln_b, g.ln_eps, w->ffn2_w1, w->ffn2_b1, w->ffn2_w2, w->ffn2_b2,
-                      M, g.D, g.H, pf2, saved->m, &saved->ffn2, ws, ws_bytes, stream, dev_status));
-  AQT_TRY(launch_residual_add(saved->r3, saved->m, 0.5f, saved->r4, n, st));
-  return launch_layernorm_quantize(saved->r4, M, g.D, w->out_ln_g, w->out_ln_b, g.ln_eps, 8, nullptr, nullptr, y,
-                                   saved->out_row_stats, ws, st, dev_status);
+  // half-step feed-forward module.  From here on the residual connection in front of a module is formed by that
+  // module's normalisation pass: r = r_prev + alpha * (previous module's output), left in saved->r*.
+  AQT_TRY(ffn_fwd_impl(x, w->ffn1_ln_g, w->ffn1_ln_b, g.ln_eps, w->ffn1_w1, w->ffn1_b1, w->ffn1_w2, w->ffn1_b2, M, g.D,
+                       g.H, pf1, saved->m, &saved->ffn1, ws, ws_bytes, stream, dev_status, nullptr));
+  // self-attention module on r1 = x + ffn(x) / 2
+  const ResidualIn in1 = {saved->m, 0.5f, saved->r1};
+  AQT_TRY(mhsa_fwd_impl(x, w->att_ln_g, w->att_ln_b, g.ln_eps, w->att_wqkv, w->att_bqkv, w->att_wo, w->att_bo, g.B, g.T,
+                        g.D, g.heads, g.left_context, g.right_context, pa, saved->m, &saved->att, ws, ws_bytes, stream,
+                        dev_status, &in1));
+  // convolution module on r2 = r1 + mhsa(r1)
+  const ResidualIn in2 = {saved->m, 1.0f, saved->r2};
+  AQT_TRY(conv_module_fwd_impl(saved->r1, w->conv_ln_g, w->conv_ln_b, g.ln_eps, w->conv_w1, w->conv_b1, w->conv_wdw,
+                               w->conv_bdw, w->conv_norm_scale, w->conv_norm_shift, w->conv_w2, w->conv_b2, g.B, g.T,
+                               g.D, g.kw, g.pad_left, pc, saved->m, &saved->conv, ws, ws_bytes, stream, dev_status,
+                               &in2));
+  // second half-step feed-forward module on r3 = r2 + conv(r2)
+  const ResidualIn in3 = {saved->m, 1.0f, saved->r3};
+  AQT_TRY(ffn_fwd_impl(saved->r2, w->ffn2_ln_g, w->ffn2_ln_b, g.ln_eps, w->ffn2_w1, w->ffn2_b1, w->ffn2_w2, w->ffn2_b2,
+                       M, g.D, g.H, pf2, saved->m, &saved->ffn2, ws, ws_bytes, stream, dev_status, &in3));
+  // final normalisation of r4 = r3 + ffn(r3) / 2
+  return launch_layernorm_quantize(saved->r3, M, g.D, w->out_ln_g, w->out_ln_b, g.ln_eps, 8, nullptr, nullptr, y,
+                                   saved->out_row_stats, ws, static_cast<hipStream_t>(stream), dev_status, saved->m,
+                                   0.5f, saved->r4);
 }
 
 aqt_status aqt_layernorm_bwd(const float *x, const float *row_stats, const float *gamma, const float *dy,

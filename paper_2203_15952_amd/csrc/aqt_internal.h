@@ -101,9 +101,11 @@ aqt_status launch_dense_bwd(const float *dy, const aqt_saved *sv, int64_t M, int
 
 // ---- block pieces (block.hip) -----------------------------------------------------------
 size_t layernorm_ws_bytes(int64_t M);
+// res / alpha / sum_out (optional): normalise x + alpha * res instead of x and leave that sum in sum_out
 aqt_status launch_layernorm_quantize(const float *x, int64_t M, int64_t D, const float *gamma, const float *beta,
                                      float eps, int bits, int8_t *q, float *scale, float *y_out, float *row_stats,
-                                     void *ws, hipStream_t st, int32_t *dev_status);
+                                     void *ws, hipStream_t st, int32_t *dev_status, const float *res = nullptr,
+                                     float alpha = 0.0f, float *sum_out = nullptr);
 size_t layernorm_bwd_ws_bytes(int64_t D);
 aqt_status launch_layernorm_bwd(const float *x, const float *stats, const float *gamma, const float *dy,
                                 const float *add, int64_t M, int64_t D, float *dx, float *dgamma, float *dbeta,

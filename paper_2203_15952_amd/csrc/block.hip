@@ -54,11 +54,15 @@ __device__ __forceinline__ void load_row(const float *__restrict__ row, int64_t 
 // sums, then a fixed shuffle tree: the same bits on every run), rstd = 1 / sqrt(var + eps),
 // and the largest |normalised value| of everything this block handled.
 // NV > 0: the row is held in registers (D % 4 == 0, D <= 256 NV, 16-byte aligned rows); NV = 0: any row.
+// When `res` is given the input row is x + alpha * res (the residual connection in front of the module:
+// product, then sum, one rounding each), which is also written to `sum_out` for the second pass and the caller.
 template <int NV>
 __global__ __launch_bounds__(kThreads) void ln_stats_kernel(const float *__restrict__ x, int64_t M, int64_t D,
                                                             const float *__restrict__ gamma,
                                                             const float *__restrict__ beta, float eps,
-                                                            float *__restrict__ stats, uint32_t *__restrict__ partial) {
+                                                            float *__restrict__ stats, uint32_t *__restrict__ partial,
+                                                            const float *__restrict__ res, float alpha,
+                                                            float *__restrict__ sum_out) {
   __shared__ uint32_t sm[4];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   uint32_t amax = 0u;
@@ -67,6 +71,17 @@ __global__ __launch_bounds__(kThreads) void ln_stats_kernel(const float *__restr
     if constexpr (NV > 0) {
       v4f v[NV];
       load_row<NV>(row, D, lane, v);
+      if (res) {
+        v4f rv[NV];
+        load_row<NV>(res + m * D, D, lane, rv);
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+          v[k].x = v[k].x + alpha * rv[k].x; v[k].y = v[k].y + alpha * rv[k].y;
+          v[k].z = v[k].z + alpha * rv[k].z; v[k].w = v[k].w + alpha * rv[k].w;
+          const int64_t c = 4 * (lane + 64 * k);
+          if (c < D) *reinterpret_cast<v4f *>(sum_out + m * D + c) = v[k];
+        }
+      }
       float s = 0.0f;
 #pragma unroll
       for (int k = 0; k < NV; ++k) s += (v[k].x + v[k].y) + (v[k].z + v[k].w);   // pieces beyond the row are zero
@@ -95,6 +110,10 @@ __global__ __launch_bounds__(kThreads) void ln_stats_kernel(const float *__restr
         }
       }
     } else {
+      if (res) {   // any row length: form the sum first, then read it back like any input row
+        for (int64_t c = lane; c < D; c += 64) sum_out[m * D + c] = row[c] + alpha * res[m * D + c];
+        row = sum_out + m * D;
+      }
       float s = 0.0f;
       for (int64_t c = lane; c < D; c += 64) s += row[c];
       const float mean = wave_sum(s) / static_cast<float>(D);
@@ -460,7 +479,8 @@ size_t layernorm_ws_bytes(int64_t M) {
 
 aqt_status launch_layernorm_quantize(const float *x, int64_t M, int64_t D, const float *gamma, const float *beta,
                                      float eps, int bits, int8_t *q, float *scale, float *y_out, float *row_stats,
-                                     void *ws, hipStream_t st, int32_t *dev_status) {
+                                     void *ws, hipStream_t st, int32_t *dev_status, const float *res, float alpha,
+                                     float *sum_out) {
   uint32_t *partial = static_cast<uint32_t *>(ws);
   float *stats = row_stats ? row_stats
                            : reinterpret_cast<float *>(static_cast<uint8_t *>(ws) +
@@ -468,11 +488,13 @@ aqt_status launch_layernorm_quantize(const float *x, int64_t M, int64_t D, const
   const int g = grid_cap(M, 4, 2048);
   const bool vec = (D % 4 == 0) && reinterpret_cast<uintptr_t>(x) % 16 == 0 &&
                    (!y_out || reinterpret_cast<uintptr_t>(y_out) % 16 == 0) &&
-                   (!q || reinterpret_cast<uintptr_t>(q) % 4 == 0);
-  if (vec && D <= 512) ln_stats_kernel<2><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, eps, stats, partial);
-  else if (vec && D <= 1024) ln_stats_kernel<4><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, eps, stats, partial);
-  else ln_stats_kernel<0><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, eps, stats, partial);
+                   (!q || reinterpret_cast<uintptr_t>(q) % 4 == 0) &&
+                   (!res || (reinterpret_cast<uintptr_t>(res) % 16 == 0 && reinterpret_cast<uintptr_t>(sum_out) % 16 == 0));
+  if (vec && D <= 512) ln_stats_kernel<2><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, eps, stats, partial, res, alpha, sum_out);
+  else if (vec && D <= 1024) ln_stats_kernel<4><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, eps, stats, partial, res, alpha, sum_out);
+  else ln_stats_kernel<0><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, eps, stats, partial, res, alpha, sum_out);
   AQT_HIP(hipGetLastError());
+  if (res) x = sum_out;   // the second pass normalises the sum the first pass wrote
   const int qm = q ? qmax_of(bits) : 1;
   if (vec) ln_quantize_kernel<true><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, stats, partial, g, qm, q, scale, y_out, dev_status);
   else ln_quantize_kernel<false><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, stats, partial, g, qm, q, scale, y_out, dev_status);
