@@ -342,9 +342,17 @@ def main():
         layer_ms = {}
         for name, pattern, bw in (("int8", B.AQT_POLICY_ALL, 8), ("int4_except_attention", B.AQT_POLICY_EXCEPT_ATTENTION, 4)):
             pol = B.aqt_policy_preset(pattern, 1, 0, bw, 8)[0]
-            lsv = B.LayerSaved(Bc, Tc, Df, Hf, pol)
+            lsv = B.LayerSaved(Bc, Tc, Df, Hf, pol, heads=Hh)
             layer_ms[name] = timed_loop(lambda: B.aqt_conformer_layer_fwd(
                 xf, lw, lsv, B=Bc, T=Tc, H=Hf, heads=Hh, kw=kwc, pad_left=15, y=yf, ws=ws_l, dev_status=status), n=10, warm=3)
+            if name == "int8":     # training: straight-through backward of the whole layer, and the serving form
+                ws_lb = B.workspace(B.aqt_workspace_bytes(B.AQT_OP_CONFORMER_LAYER_BWD, Mf, Df, Hf))
+                fused["encoder_layer_bwd_ms"] = timed_loop(lambda: B.aqt_conformer_layer_bwd(
+                    dyf, xf, lw, lsv, B=Bc, T=Tc, H=Hf, heads=Hh, kw=kwc, pad_left=15, ws=ws_lb), n=10, warm=3)
+                lsv.prepare(lw)
+                fused["encoder_layer_fwd_serving_ms"] = timed_loop(lambda: B.aqt_conformer_layer_fwd(
+                    xf, lw, lsv, B=Bc, T=Tc, H=Hf, heads=Hh, kw=kwc, pad_left=15, y=yf, ws=ws_l, dev_status=status), n=10, warm=3)
+                del ws_lb
             del lsv
         fused["encoder_layer_fwd_ms"] = layer_ms
         fused["encoder_layer_shape"] = {"utterances": Bc, "frames": Tc, "d_model": Df, "d_ff": Hf, "heads": Hh, "kernel": kwc}
