@@ -500,8 +500,8 @@ typedef struct aqt_mhsa_saved {
  * activations; Table 2's E7 keeps exactly these two layers at int8) and the attention itself in
  * float32 (the paper quantizes the layers' weights and inputs, not the score products).
  * Fused like the other modules: normalisation with the first quantizer, max|ctx| from the
- * attention kernel for a one-pass second quantizer.  The backward of this module is not part
- * of the library.
+ * attention kernel for a one-pass second quantizer.  With saved->lse given, the softmax
+ * normalisers are kept for aqt_mhsa_bwd.
  */
 aqt_status aqt_mhsa_fwd(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps, const float *wqkv,
                         const float *bqkv, const float *wo, const float *bo, int64_t B, int64_t T, int64_t D,
@@ -545,8 +545,9 @@ typedef struct aqt_conformer_layer_saved {
  * One Conformer encoder layer (Sec. 3.2), forward, with every dense layer at the precision
  * its aqt_layer_policy entry names (Sec. 4.2 / Table 2):
  *   r1 = x + ffn(x) / 2;  r2 = r1 + mhsa(r1);  r3 = r2 + conv(r2);  r4 = r3 + ffn(r3) / 2;  y = layernorm(r4)
- * x, y [B*T, D].  Forward only (aqt_mhsa_fwd has no backward); the self-attention and convolution
- * modules need integer activations.
+ * x, y [B*T, D].  The self-attention and convolution modules need integer activations.  For
+ * aqt_conformer_layer_bwd the saved buffers must include every row_stats, out_row_stats, att.lse,
+ * conv.dfac and the dact buffers of the layers with an activation.
  */
 aqt_status aqt_conformer_layer_fwd(const float *x, const aqt_conformer_layer_weights *w,
                                    const aqt_conformer_layer_shape *shape, const aqt_layer_policy *policy, float *y,
