@@ -222,21 +222,33 @@ bool acc_fits(int64_t K, int bits_x, int bits_w) {
 
 using namespace aqt;
 
-static aqt_status ffn_fwd_impl(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps, const float *w1,
-                       const float *b1, const float *w2, const float *b2, int64_t M, int64_t D, int64_t H,
-                       const aqt_dense_policy *policy, float *y, const aqt_ffn_saved *saved, void *ws,
-                       size_t ws_bytes, void *stream, int32_t *dev_status, const ResidualIn *res) {
+// Every argument check of the feed-forward module's forward, so that a caller of several modules can run all of
+// them before the first launch.
+static aqt_status ffn_fwd_check(const float *x, float ln_eps, const float *w1, const float *w2, int64_t M, int64_t D,
+                                int64_t H, const aqt_dense_policy *policy, const float *y, const aqt_ffn_saved *saved,
+                                const void *ws, size_t ws_bytes) {
   if (!x || !y || !policy || !saved || !shape_ok(M, D) || H < 1 || !(ln_eps >= 0.0f)) return AQT_ERR_INVALID_ARG;
   const aqt_dense_policy p1 = policy[0], p2 = policy[1];
   if (!policy_ok(p1) || !policy_ok(p2)) return AQT_ERR_UNSUPPORTED;
   const aqt_saved &l1 = saved->l1, &l2 = saved->l2;
   if (!saved->h || !l1.wq_packed || !l1.s_w || !l2.wq_packed || !l2.s_w) return AQT_ERR_INVALID_ARG;
+  if ((!p1.weights_ready && !w1) || (!p2.weights_ready && !w2)) return AQT_ERR_INVALID_ARG;
   if (p1.bits_x ? (!l1.xq || !l1.s_x) : !saved->xn) return AQT_ERR_INVALID_ARG;
   if (p2.bits_x && (!l2.xq || !l2.s_x)) return AQT_ERR_INVALID_ARG;
   if (p1.bits_x && !acc_fits(D, p1.bits_x, p1.bits_w)) return AQT_ERR_UNSUPPORTED;
   if (p2.bits_x && !acc_fits(H, p2.bits_x, p2.bits_w)) return AQT_ERR_UNSUPPORTED;
+  if (!ws || ws_bytes < carve_ffn_fwd(nullptr, M, D, H).total) return AQT_ERR_WORKSPACE;
+  return AQT_OK;
+}
+
+static aqt_status ffn_fwd_impl(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps, const float *w1,
+                       const float *b1, const float *w2, const float *b2, int64_t M, int64_t D, int64_t H,
+                       const aqt_dense_policy *policy, float *y, const aqt_ffn_saved *saved, void *ws,
+                       size_t ws_bytes, void *stream, int32_t *dev_status, const ResidualIn *res) {
+  AQT_TRY(ffn_fwd_check(x, ln_eps, w1, w2, M, D, H, policy, y, saved, ws, ws_bytes));
+  const aqt_dense_policy p1 = policy[0], p2 = policy[1];
+  const aqt_saved &l1 = saved->l1, &l2 = saved->l2;
   FfnWorkspace f = carve_ffn_fwd(ws, M, D, H);
-  if (!ws || ws_bytes < f.total) return AQT_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   // normalisation (+ first quantizer), first weights, first contraction with Swish
@@ -273,12 +285,10 @@ static aqt_status ffn_fwd_impl(const float *x, const float *ln_gamma, const floa
   return launch_dense_fwd_wonly(saved->h, l2.wq_packed, l2.s_w, M, H, D, p2.bits_w, b2, AQT_EPI_NONE, y, f.wfrag2, st);
 }
 
-static aqt_status conv_module_fwd_impl(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps,
-                               const float *w1, const float *b1, const float *w_dw, const float *b_dw,
-                               const float *norm_scale, const float *norm_shift, const float *w2, const float *b2,
-                               int64_t B, int64_t T, int64_t D, int kw, int pad_left, const aqt_dense_policy *policy,
-                               float *y, const aqt_conv_saved *saved, void *ws, size_t ws_bytes, void *stream,
-                               int32_t *dev_status, const ResidualIn *res) {
+static aqt_status conv_module_fwd_check(const float *x, float ln_eps, const float *w1, const float *w_dw,
+                                        const float *w2, int64_t B, int64_t T, int64_t D, int kw, int pad_left,
+                                        const aqt_dense_policy *policy, const float *y, const aqt_conv_saved *saved,
+                                        const void *ws, size_t ws_bytes) {
   if (!x || !w_dw || !y || !policy || !saved || !conv_shape_ok(B, T, D, kw, pad_left) || !(ln_eps >= 0.0f))
     return AQT_ERR_INVALID_ARG;
   const aqt_dense_policy p1 = policy[0], p2 = policy[1];
@@ -287,10 +297,23 @@ static aqt_status conv_module_fwd_impl(const float *x, const float *ln_gamma, co
   if (!saved->g || !saved->s || !l1.xq || !l1.s_x || !l1.wq_packed || !l1.s_w || !l2.xq || !l2.s_x ||
       !l2.wq_packed || !l2.s_w)
     return AQT_ERR_INVALID_ARG;
+  if ((!p1.weights_ready && !w1) || (!p2.weights_ready && !w2)) return AQT_ERR_INVALID_ARG;
   if (!acc_fits(D, p1.bits_x, p1.bits_w) || !acc_fits(D, p2.bits_x, p2.bits_w)) return AQT_ERR_UNSUPPORTED;
+  if (!ws || ws_bytes < carve_ffn_fwd(nullptr, B * T, D, 2 * D).total) return AQT_ERR_WORKSPACE;
+  return AQT_OK;
+}
+
+static aqt_status conv_module_fwd_impl(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps,
+                               const float *w1, const float *b1, const float *w_dw, const float *b_dw,
+                               const float *norm_scale, const float *norm_shift, const float *w2, const float *b2,
+                               int64_t B, int64_t T, int64_t D, int kw, int pad_left, const aqt_dense_policy *policy,
+                               float *y, const aqt_conv_saved *saved, void *ws, size_t ws_bytes, void *stream,
+                               int32_t *dev_status, const ResidualIn *res) {
+  AQT_TRY(conv_module_fwd_check(x, ln_eps, w1, w_dw, w2, B, T, D, kw, pad_left, policy, y, saved, ws, ws_bytes));
+  const aqt_dense_policy p1 = policy[0], p2 = policy[1];
+  const aqt_saved &l1 = saved->pw1, &l2 = saved->pw2;
   const int64_t M = B * T;
   FfnWorkspace f = carve_ffn_fwd(ws, M, D, 2 * D);
-  if (!ws || ws_bytes < f.total) return AQT_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   // normalisation + first quantizer, first pointwise convolution with the GLU
@@ -312,10 +335,9 @@ static aqt_status conv_module_fwd_impl(const float *x, const float *ln_gamma, co
                             nullptr, s2.operand, st, nullptr, s2.prepared);
 }
 
-static aqt_status mhsa_fwd_impl(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps, const float *wqkv,
-                        const float *bqkv, const float *wo, const float *bo, int64_t B, int64_t T, int64_t D,
-                        int heads, int left_context, int right_context, const aqt_dense_policy *policy, float *y,
-                        const aqt_mhsa_saved *saved, void *ws, size_t ws_bytes, void *stream, int32_t *dev_status, const ResidualIn *res) {
+static aqt_status mhsa_fwd_check(const float *x, float ln_eps, const float *wqkv, const float *wo, int64_t B,
+                                 int64_t T, int64_t D, int heads, const aqt_dense_policy *policy, const float *y,
+                                 const aqt_mhsa_saved *saved, const void *ws, size_t ws_bytes) {
   if (!x || !y || !policy || !saved || B < 1 || T < 1 || D < 1 || heads < 1 || D % heads || !(ln_eps >= 0.0f))
     return AQT_ERR_INVALID_ARG;
   if (!attention_shape_ok(B, T, D, heads)) return AQT_ERR_UNSUPPORTED;
@@ -325,10 +347,21 @@ static aqt_status mhsa_fwd_impl(const float *x, const float *ln_gamma, const flo
   if (!saved->qkv_f || !saved->ctx || !l1.xq || !l1.s_x || !l1.wq_packed || !l1.s_w || !l2.xq || !l2.s_x ||
       !l2.wq_packed || !l2.s_w)
     return AQT_ERR_INVALID_ARG;
+  if ((!p1.weights_ready && !wqkv) || (!p2.weights_ready && !wo)) return AQT_ERR_INVALID_ARG;
   if (!acc_fits(D, p1.bits_x, p1.bits_w) || !acc_fits(D, p2.bits_x, p2.bits_w)) return AQT_ERR_UNSUPPORTED;
+  if (!ws || ws_bytes < carve_ffn_fwd(nullptr, B * T, D, 3 * D).total) return AQT_ERR_WORKSPACE;
+  return AQT_OK;
+}
+
+static aqt_status mhsa_fwd_impl(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps, const float *wqkv,
+                        const float *bqkv, const float *wo, const float *bo, int64_t B, int64_t T, int64_t D,
+                        int heads, int left_context, int right_context, const aqt_dense_policy *policy, float *y,
+                        const aqt_mhsa_saved *saved, void *ws, size_t ws_bytes, void *stream, int32_t *dev_status, const ResidualIn *res) {
+  AQT_TRY(mhsa_fwd_check(x, ln_eps, wqkv, wo, B, T, D, heads, policy, y, saved, ws, ws_bytes));
+  const aqt_dense_policy p1 = policy[0], p2 = policy[1];
+  const aqt_saved &l1 = saved->qkv, &l2 = saved->out;
   const int64_t M = B * T;
   FfnWorkspace f = carve_ffn_fwd(ws, M, D, 3 * D);
-  if (!ws || ws_bytes < f.total) return AQT_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   // normalisation + first quantizer, fused projection of queries, keys and values
   WeightSide s1, s2;
@@ -347,6 +380,51 @@ static aqt_status mhsa_fwd_impl(const float *x, const float *ln_gamma, const flo
                                       l2.xq, l2.s_x, l2.mask_x, st, dev_status));
   return launch_dense_fwd_q(l2.xq, l2.s_x, l2.wq_packed, l2.s_w, M, D, D, p2.bits_w, bo, AQT_EPI_NONE, y, nullptr,
                             nullptr, s2.operand, st, nullptr, s2.prepared);
+}
+
+// Argument checks of the three module backward calls, each in one function so that the layer backward can run all
+// of them before its first launch.
+static aqt_status ffn_bwd_check(const float *dy, const aqt_ffn_saved *saved, int64_t M, int64_t D, int64_t H,
+                                const aqt_dense_policy *policy, const float *dxn, const float *dw1, const float *dw2,
+                                const void *ws, size_t ws_bytes) {
+  if (!dy || !saved || !policy || !shape_ok(M, D) || H < 1) return AQT_ERR_INVALID_ARG;
+  if (!policy_ok(policy[0]) || !policy_ok(policy[1])) return AQT_ERR_UNSUPPORTED;
+  if (policy[0].bits_x == 0 || policy[1].bits_x == 0) return AQT_ERR_UNSUPPORTED;
+  const aqt_saved &l1 = saved->l1, &l2 = saved->l2;
+  if (!l1.s_x || !l1.s_w || !l2.s_x || !l2.s_w || !l2.wq_kn || !l1.dact) return AQT_ERR_INVALID_ARG;
+  if ((dxn && !l1.wq_kn) || (dw1 && !l1.xq) || (dw2 && !l2.xq)) return AQT_ERR_INVALID_ARG;
+  if (!ws || ws_bytes < ffn_bwd_ws(M, D, H)) return AQT_ERR_WORKSPACE;
+  return AQT_OK;
+}
+
+static aqt_status conv_module_bwd_check(const float *dy, const aqt_conv_saved *saved, const float *w_dw, int64_t B,
+                                        int64_t T, int64_t D, int kw, int pad_left, const aqt_dense_policy *policy,
+                                        const float *dxn, const float *dw1, const float *dw2, const void *ws,
+                                        size_t ws_bytes) {
+  if (!dy || !saved || !w_dw || !policy || !conv_shape_ok(B, T, D, kw, pad_left)) return AQT_ERR_INVALID_ARG;
+  if (!policy_ok(policy[0]) || !policy_ok(policy[1])) return AQT_ERR_UNSUPPORTED;
+  if (policy[0].bits_x == 0 || policy[1].bits_x == 0) return AQT_ERR_UNSUPPORTED;
+  const aqt_saved &l1 = saved->pw1, &l2 = saved->pw2;
+  if (!l1.s_x || !l1.s_w || !l2.s_x || !l2.s_w || !l2.wq_kn || !l1.dact || !saved->dfac || !saved->g)
+    return AQT_ERR_INVALID_ARG;
+  if ((dxn && !l1.wq_kn) || (dw1 && !l1.xq) || (dw2 && !l2.xq)) return AQT_ERR_INVALID_ARG;
+  if (!ws || ws_bytes < carve_conv_bwd(nullptr, B, T, D, kw).total) return AQT_ERR_WORKSPACE;
+  return AQT_OK;
+}
+
+static aqt_status mhsa_bwd_check(const float *dy, const aqt_mhsa_saved *saved, int64_t B, int64_t T, int64_t D,
+                                 int heads, const aqt_dense_policy *policy, const float *dxn, const float *dwqkv,
+                                 const float *dwo, const void *ws, size_t ws_bytes) {
+  if (!dy || !saved || !policy || B < 1 || T < 1 || D < 1 || heads < 1 || D % heads) return AQT_ERR_INVALID_ARG;
+  if (!attention_shape_ok(B, T, D, heads)) return AQT_ERR_UNSUPPORTED;
+  if (!policy_ok(policy[0]) || !policy_ok(policy[1]) || policy[0].bits_x == 0 || policy[1].bits_x == 0)
+    return AQT_ERR_UNSUPPORTED;
+  const aqt_saved &l1 = saved->qkv, &l2 = saved->out;
+  if (!saved->lse || !saved->qkv_f || !saved->ctx || !l1.s_x || !l1.s_w || !l2.s_x || !l2.s_w || !l2.wq_kn)
+    return AQT_ERR_INVALID_ARG;
+  if ((dxn && !l1.wq_kn) || (dwqkv && !l1.xq) || (dwo && !l2.xq)) return AQT_ERR_INVALID_ARG;
+  if (!ws || ws_bytes < carve_mhsa_bwd(nullptr, B * T, D, heads).total) return AQT_ERR_WORKSPACE;
+  return AQT_OK;
 }
 
 extern "C" {
@@ -678,13 +756,8 @@ aqt_status aqt_ffn_fwd(const float *x, const float *ln_gamma, const float *ln_be
 aqt_status aqt_ffn_bwd(const float *dy, const aqt_ffn_saved *saved, int64_t M, int64_t D, int64_t H,
                        const aqt_dense_policy *policy, float *dxn, float *dw1, float *db1, float *dw2, float *db2,
                        void *ws, size_t ws_bytes, void *stream) {
-  if (!dy || !saved || !policy || !shape_ok(M, D) || H < 1) return AQT_ERR_INVALID_ARG;
-  if (!policy_ok(policy[0]) || !policy_ok(policy[1])) return AQT_ERR_UNSUPPORTED;
-  if (policy[0].bits_x == 0 || policy[1].bits_x == 0) return AQT_ERR_UNSUPPORTED;
+  AQT_TRY(ffn_bwd_check(dy, saved, M, D, H, policy, dxn, dw1, dw2, ws, ws_bytes));
   const aqt_saved &l1 = saved->l1, &l2 = saved->l2;
-  if (!l1.s_x || !l1.s_w || !l2.s_x || !l2.s_w || !l2.wq_kn || !l1.dact) return AQT_ERR_INVALID_ARG;
-  if ((dxn && !l1.wq_kn) || (dw1 && !l1.xq) || (dw2 && !l2.xq)) return AQT_ERR_INVALID_ARG;
-  if (!ws || ws_bytes < ffn_bwd_ws(M, D, H)) return AQT_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const size_t a = bwd_workspace_bytes(M, D, H), b = bwd_workspace_bytes(M, H, D);
   const size_t core = a > b ? a : b;
@@ -729,16 +802,10 @@ aqt_status aqt_conv_module_bwd(const float *dy, const aqt_conv_saved *saved, con
                                int64_t D, int kw, int pad_left, const aqt_dense_policy *policy, float *dxn,
                                float *dw1, float *db1, float *dw_dw, float *db_dw, float *dw2, float *db2, void *ws,
                                size_t ws_bytes, void *stream) {
-  if (!dy || !saved || !w_dw || !policy || !conv_shape_ok(B, T, D, kw, pad_left)) return AQT_ERR_INVALID_ARG;
-  if (!policy_ok(policy[0]) || !policy_ok(policy[1])) return AQT_ERR_UNSUPPORTED;
-  if (policy[0].bits_x == 0 || policy[1].bits_x == 0) return AQT_ERR_UNSUPPORTED;
+  AQT_TRY(conv_module_bwd_check(dy, saved, w_dw, B, T, D, kw, pad_left, policy, dxn, dw1, dw2, ws, ws_bytes));
   const aqt_saved &l1 = saved->pw1, &l2 = saved->pw2;
-  if (!l1.s_x || !l1.s_w || !l2.s_x || !l2.s_w || !l2.wq_kn || !l1.dact || !saved->dfac || !saved->g)
-    return AQT_ERR_INVALID_ARG;
-  if ((dxn && !l1.wq_kn) || (dw1 && !l1.xq) || (dw2 && !l2.xq)) return AQT_ERR_INVALID_ARG;
   const int64_t M = B * T;
   ConvBwdWorkspace f = carve_conv_bwd(ws, B, T, D, kw);
-  if (!ws || ws_bytes < f.total) return AQT_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   // second pointwise convolution: gradient with respect to s, dw2, db2
   AQT_TRY(launch_dense_bwd(dy, &l2, M, D, D, f.ds, dw2, db2, ws, f.core, st));
@@ -795,6 +862,14 @@ aqt_status aqt_conformer_layer_fwd(const float *x, const aqt_conformer_layer_wei
   if (!ws || ws_bytes < aqt_workspace_bytes(AQT_OP_CONFORMER_LAYER_FWD, M, g.D, g.H, 8, 8)) return AQT_ERR_WORKSPACE;
   const aqt_dense_policy pf1[2] = {policy->ffn1_in, policy->ffn1_out}, pa[2] = {policy->attn_qkv, policy->attn_out};
   const aqt_dense_policy pc[2] = {policy->conv_pw1, policy->conv_pw2}, pf2[2] = {policy->ffn2_in, policy->ffn2_out};
+  // every module's own checks, before the first launch: a call that is going to be refused leaves no buffer half written
+  AQT_TRY(ffn_fwd_check(x, g.ln_eps, w->ffn1_w1, w->ffn1_w2, M, g.D, g.H, pf1, saved->m, &saved->ffn1, ws, ws_bytes));
+  AQT_TRY(mhsa_fwd_check(x, g.ln_eps, w->att_wqkv, w->att_wo, g.B, g.T, g.D, g.heads, pa, saved->m, &saved->att, ws,
+                         ws_bytes));
+  AQT_TRY(conv_module_fwd_check(saved->r1, g.ln_eps, w->conv_w1, w->conv_wdw, w->conv_w2, g.B, g.T, g.D, g.kw,
+                                g.pad_left, pc, saved->m, &saved->conv, ws, ws_bytes));
+  AQT_TRY(ffn_fwd_check(saved->r2, g.ln_eps, w->ffn2_w1, w->ffn2_w2, M, g.D, g.H, pf2, saved->m, &saved->ffn2, ws,
+                        ws_bytes));
   // half-step feed-forward module.  From here on the residual connection in front of a module is formed by that
   // module's normalisation pass: r = r_prev + alpha * (previous module's output), left in saved->r*.
   AQT_TRY(ffn_fwd_impl(x, w->ffn1_ln_g, w->ffn1_ln_b, g.ln_eps, w->ffn1_w1, w->ffn1_b1, w->ffn1_w2, w->ffn1_b2, M, g.D,
@@ -832,17 +907,10 @@ aqt_status aqt_layernorm_bwd(const float *x, const float *row_stats, const float
 aqt_status aqt_mhsa_bwd(const float *dy, const aqt_mhsa_saved *saved, int64_t B, int64_t T, int64_t D, int heads,
                         int left_context, int right_context, const aqt_dense_policy *policy, float *dxn,
                         float *dwqkv, float *dbqkv, float *dwo, float *dbo, void *ws, size_t ws_bytes, void *stream) {
-  if (!dy || !saved || !policy || B < 1 || T < 1 || D < 1 || heads < 1 || D % heads) return AQT_ERR_INVALID_ARG;
-  if (!attention_shape_ok(B, T, D, heads)) return AQT_ERR_UNSUPPORTED;
-  if (!policy_ok(policy[0]) || !policy_ok(policy[1]) || policy[0].bits_x == 0 || policy[1].bits_x == 0)
-    return AQT_ERR_UNSUPPORTED;
+  AQT_TRY(mhsa_bwd_check(dy, saved, B, T, D, heads, policy, dxn, dwqkv, dwo, ws, ws_bytes));
   const aqt_saved &l1 = saved->qkv, &l2 = saved->out;
-  if (!saved->lse || !saved->qkv_f || !saved->ctx || !l1.s_x || !l1.s_w || !l2.s_x || !l2.s_w || !l2.wq_kn)
-    return AQT_ERR_INVALID_ARG;
-  if ((dxn && !l1.wq_kn) || (dwqkv && !l1.xq) || (dwo && !l2.xq)) return AQT_ERR_INVALID_ARG;
   const int64_t M = B * T;
   MhsaBwdWorkspace f = carve_mhsa_bwd(ws, M, D, heads);
-  if (!ws || ws_bytes < f.total) return AQT_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   // output projection: gradient with respect to the attention result
   AQT_TRY(launch_dense_bwd(dy, &l2, M, D, D, f.dctx, dwo, dbo, ws, f.core, st));
@@ -872,6 +940,13 @@ aqt_status aqt_conformer_layer_bwd(const float *dy, const float *x, const aqt_co
   hipStream_t st = static_cast<hipStream_t>(stream);
   const aqt_dense_policy pf1[2] = {policy->ffn1_in, policy->ffn1_out}, pa[2] = {policy->attn_qkv, policy->attn_out};
   const aqt_dense_policy pc[2] = {policy->conv_pw1, policy->conv_pw2}, pf2[2] = {policy->ffn2_in, policy->ffn2_out};
+  // the modules' own checks, before the first launch (f.dm, f.da, f.db stand for the gradients they will be given)
+  AQT_TRY(ffn_bwd_check(f.dm, &saved->ffn2, M, g.D, g.H, pf2, f.dm, grads->ffn2_w1, grads->ffn2_w2, ws, f.module));
+  AQT_TRY(conv_module_bwd_check(f.db, &saved->conv, w->conv_wdw, g.B, g.T, g.D, g.kw, g.pad_left, pc, f.dm,
+                                grads->conv_w1, grads->conv_w2, ws, f.module));
+  AQT_TRY(mhsa_bwd_check(f.da, &saved->att, g.B, g.T, g.D, g.heads, pa, f.dm, grads->att_wqkv, grads->att_wo, ws,
+                         f.module));
+  AQT_TRY(ffn_bwd_check(f.dm, &saved->ffn1, M, g.D, g.H, pf1, f.dm, grads->ffn1_w1, grads->ffn1_w2, ws, f.module));
   // final normalisation: gradient of the residual stream r4
   AQT_TRY(launch_layernorm_bwd(saved->r4, saved->out_row_stats, w->out_ln_g, dy, nullptr, M, g.D, f.da, grads->out_ln_g,
                                grads->out_ln_b, f.ln, st));

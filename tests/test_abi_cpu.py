@@ -125,6 +125,126 @@ def test_argument_errors_are_synchronous_and_touch_no_gpu(L):
     assert B.aqt_workspace_bytes(B.AQT_OP_FFN_FWD, 128, 512, 2048) > 0 and B.aqt_workspace_bytes(B.AQT_OP_FFN_BWD, 128, 512, 2048) > 128 * 2048 * 4
 
 
+def _filled(struct_type, skip=()):
+    """A struct whose pointer fields all hold the same never-dereferenced address (nested structs too)."""
+    st = struct_type()
+    for name, typ in struct_type._fields_:
+        if name in skip:
+            continue
+        if typ is ctypes.c_void_p:
+            setattr(st, name, 256)
+        elif issubclass(typ, ctypes.Structure):
+            setattr(st, name, _filled(typ, skip))
+    return st
+
+
+def test_module_and_layer_argument_errors_are_synchronous(L):
+    one, none, big = ctypes.c_void_p(256), None, 1 << 40
+    i8 = (B.aqt_dense_policy * 2)(B.aqt_dense_policy(8, 8, 0), B.aqt_dense_policy(8, 8, 0))
+    # depthwise convolution: pad_left must lie inside the kernel, the tap gradient needs a workspace
+    assert L.aqt_depthwise_conv_fwd(one, 2, 8, 4, one, none, 3, 3, none, none, 0, one, none, none, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_depthwise_conv_fwd(one, 2, 8, 4, one, none, 0, 0, none, none, 0, one, none, none, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_depthwise_conv_fwd(one, 2, 8, 4, none, none, 3, 1, none, none, 0, one, none, none, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_depthwise_conv_bwd(one, none, none, one, 2, 8, 4, 3, 1, one, one, none, one, big, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_depthwise_conv_bwd(one, none, one, none, 2, 8, 4, 3, 1, one, one, none, one, big, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_depthwise_conv_bwd(one, none, one, one, 2, 8, 4, 3, 1, one, one, none, none, 0, none) == B.AQT_ERR_WORKSPACE
+    assert L.aqt_depthwise_conv_bwd(one, none, one, one, 2, 8, 4, 3, 1, one, one, none, one, 16, none) == B.AQT_ERR_WORKSPACE
+    assert B.aqt_workspace_bytes(B.AQT_OP_DEPTHWISE_CONV_BWD, 16, 4, 3) > 0
+    # attention: the model width must split into heads of at most 64 columns
+    assert L.aqt_attention_fwd(one, 2, 8, 30, 4, -1, -1, one, none, none, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_attention_fwd(one, 2, 8, 32, 0, -1, -1, one, none, none, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_attention_fwd(one, 2, 8, 256, 2, -1, -1, one, none, none, none) == B.AQT_ERR_UNSUPPORTED
+    assert L.aqt_attention_bwd(one, one, one, none, 2, 8, 32, 4, -1, -1, one, one, big, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_attention_bwd(one, one, one, one, 2, 8, 256, 2, -1, -1, one, one, big, none) == B.AQT_ERR_UNSUPPORTED
+    assert L.aqt_attention_bwd(one, one, one, one, 2, 8, 32, 4, -1, -1, one, none, 0, none) == B.AQT_ERR_WORKSPACE
+    assert L.aqt_attention_bwd(one, one, one, one, 2, 8, 32, 4, -1, -1, one, one, 8, none) == B.AQT_ERR_WORKSPACE
+    # residual sum, layer normalisation backward
+    assert L.aqt_residual_add(one, none, 0.5, one, 4, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_residual_add(one, one, 0.5, one, 0, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_layernorm_bwd(one, none, none, one, none, 4, 4, one, none, none, none, 0, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_layernorm_bwd(one, one, none, one, none, 4, 4, one, one, none, none, 0, none) == B.AQT_ERR_WORKSPACE
+    assert L.aqt_layernorm_bwd(one, one, none, one, none, 4, 4, one, none, one, one, 8, none) == B.AQT_ERR_WORKSPACE
+    # convolution module
+    cs = _filled(B.aqt_conv_saved)
+    assert L.aqt_conv_module_fwd(one, none, none, 1e-6, one, none, one, none, none, none, one, none, 2, 8, 4, 3, 3, i8,
+                                 one, ctypes.byref(cs), one, big, none, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_conv_module_fwd(one, none, none, 1e-6, one, none, one, none, none, none, none, none, 2, 8, 4, 3, 1, i8,
+                                 one, ctypes.byref(cs), one, big, none, none) == B.AQT_ERR_INVALID_ARG   # no w2
+    wo = (B.aqt_dense_policy * 2)(B.aqt_dense_policy(8, 0, 0), B.aqt_dense_policy(8, 8, 0))
+    assert L.aqt_conv_module_fwd(one, none, none, 1e-6, one, none, one, none, none, none, one, none, 2, 8, 4, 3, 1, wo,
+                                 one, ctypes.byref(cs), one, big, none, none) == B.AQT_ERR_UNSUPPORTED
+    assert L.aqt_conv_module_fwd(one, none, none, 1e-6, one, none, one, none, none, none, one, none, 2, 8, 4, 3, 1, i8,
+                                 one, ctypes.byref(cs), one, 64, none, none) == B.AQT_ERR_WORKSPACE
+    no_g = _filled(B.aqt_conv_saved, skip=("g",))
+    assert L.aqt_conv_module_fwd(one, none, none, 1e-6, one, none, one, none, none, none, one, none, 2, 8, 4, 3, 1, i8,
+                                 one, ctypes.byref(no_g), one, big, none, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_conv_module_bwd(one, ctypes.byref(no_g), one, 2, 8, 4, 3, 1, i8, one, one, none, one, none, one, none,
+                                 one, big, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_conv_module_bwd(one, ctypes.byref(cs), one, 2, 8, 4, 3, 1, i8, one, one, none, one, none, one, none,
+                                 one, 64, none) == B.AQT_ERR_WORKSPACE
+    # self-attention module
+    ms = _filled(B.aqt_mhsa_saved)
+    assert L.aqt_mhsa_fwd(one, none, none, 1e-6, one, none, one, none, 2, 8, 30, 4, -1, -1, i8, one, ctypes.byref(ms),
+                          one, big, none, none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_mhsa_fwd(one, none, none, 1e-6, one, none, one, none, 2, 8, 256, 2, -1, -1, i8, one, ctypes.byref(ms),
+                          one, big, none, none) == B.AQT_ERR_UNSUPPORTED
+    assert L.aqt_mhsa_fwd(one, none, none, 1e-6, none, none, one, none, 2, 8, 32, 4, -1, -1, i8, one, ctypes.byref(ms),
+                          one, big, none, none) == B.AQT_ERR_INVALID_ARG   # training form without the float weights
+    assert L.aqt_mhsa_fwd(one, none, none, 1e-6, one, none, one, none, 2, 8, 32, 4, -1, -1, i8, one, ctypes.byref(ms),
+                          one, 64, none, none) == B.AQT_ERR_WORKSPACE
+    no_lse = _filled(B.aqt_mhsa_saved, skip=("lse",))
+    assert L.aqt_mhsa_bwd(one, ctypes.byref(no_lse), 2, 8, 32, 4, -1, -1, i8, one, one, none, one, none, one, big,
+                          none) == B.AQT_ERR_INVALID_ARG
+    assert L.aqt_mhsa_bwd(one, ctypes.byref(ms), 2, 8, 32, 4, -1, -1, i8, one, one, none, one, none, one, 64,
+                          none) == B.AQT_ERR_WORKSPACE
+    # encoder layer: everything is checked before the first launch, whichever module the mistake sits in
+    w = _filled(B.aqt_conformer_layer_weights)
+    sv = _filled(B.aqt_conformer_layer_saved)
+    gr = B.aqt_conformer_layer_grads()
+    pol = B.aqt_layer_policy()
+    assert L.aqt_policy_preset(B.AQT_POLICY_ALL, 1, 0, 8, 8, ctypes.byref(pol)) == B.AQT_OK
+
+    def shape(**kw):
+        d = dict(B=2, T=8, D=32, H=64, heads=4, kw=3, pad_left=1, left_context=-1, right_context=-1, ln_eps=1e-6)
+        d.update(kw)
+        return B.aqt_conformer_layer_shape(**d)
+
+    def fwd(shp, weights=w, policy=pol, saved=sv, ws_bytes=big):
+        return L.aqt_conformer_layer_fwd(one, ctypes.byref(weights), ctypes.byref(shp), ctypes.byref(policy), one,
+                                         ctypes.byref(saved), one, ws_bytes, none, none)
+
+    def bwd(shp, weights=w, policy=pol, saved=sv, grads=gr, ws_bytes=big):
+        return L.aqt_conformer_layer_bwd(one, one, ctypes.byref(weights), ctypes.byref(shp), ctypes.byref(policy),
+                                         ctypes.byref(saved), one, ctypes.byref(grads), one, ws_bytes, none)
+
+    assert fwd(shape(T=0)) == B.AQT_ERR_INVALID_ARG
+    assert fwd(shape(heads=5)) == B.AQT_ERR_INVALID_ARG            # the attention module's check
+    assert fwd(shape(D=256, heads=2)) == B.AQT_ERR_UNSUPPORTED
+    assert fwd(shape(pad_left=3)) == B.AQT_ERR_INVALID_ARG         # the convolution module's check
+    assert fwd(shape(), ws_bytes=64) == B.AQT_ERR_WORKSPACE
+    no_w = _filled(B.aqt_conformer_layer_weights, skip=("ffn2_w2",))
+    assert fwd(shape(), weights=no_w) == B.AQT_ERR_INVALID_ARG     # the last module's weights, in training form
+    no_r = _filled(B.aqt_conformer_layer_saved, skip=("r3",))
+    assert fwd(shape(), saved=no_r) == B.AQT_ERR_INVALID_ARG
+    bad = B.aqt_layer_policy()
+    L.aqt_policy_preset(B.AQT_POLICY_ALL, 1, 0, 8, 8, ctypes.byref(bad))
+    bad.conv_pw2 = B.aqt_dense_policy(8, 0, 0)                     # weight-only is a feed-forward-module form
+    assert fwd(shape(), policy=bad) == B.AQT_ERR_UNSUPPORTED
+    assert bwd(shape(T=0)) == B.AQT_ERR_INVALID_ARG
+    assert bwd(shape(D=256, heads=2)) == B.AQT_ERR_UNSUPPORTED
+    assert bwd(shape(), ws_bytes=64) == B.AQT_ERR_WORKSPACE
+    frozen = B.aqt_conformer_layer_grads()
+    frozen.conv_norm_scale = 256                                    # the fixed statistics take no gradient
+    assert bwd(shape(), grads=frozen) == B.AQT_ERR_UNSUPPORTED
+    assert bwd(shape(), saved=no_r) == B.AQT_ERR_INVALID_ARG
+    no_lse = _filled(B.aqt_conformer_layer_saved, skip=("lse",))     # found by the attention module's check ...
+    assert bwd(shape(), saved=no_lse) == B.AQT_ERR_INVALID_ARG
+    no_dact = _filled(B.aqt_conformer_layer_saved, skip=("dact",))   # ... and the feed-forward module's, up front
+    assert bwd(shape(), saved=no_dact) == B.AQT_ERR_INVALID_ARG
+    need = B.aqt_workspace_bytes(B.AQT_OP_CONFORMER_LAYER_FWD, 16, 32, 64)
+    assert need > 0 and fwd(shape(), ws_bytes=need - 1) == B.AQT_ERR_WORKSPACE
+
+
 def test_precision_policies_follow_table_2_patterns(L):
     # Table 2: int4 on the selected layers, int8 on the rest; E6 spares the first and last layer, E7 the
     # self-attention projections, E8 - E13 take the first k layers
