@@ -547,7 +547,8 @@ typedef struct aqt_conformer_layer_saved {
  *   r1 = x + ffn(x) / 2;  r2 = r1 + mhsa(r1);  r3 = r2 + conv(r2);  r4 = r3 + ffn(r3) / 2;  y = layernorm(r4)
  * x, y [B*T, D].  The self-attention and convolution modules need integer activations.  For
  * aqt_conformer_layer_bwd the saved buffers must include every row_stats, out_row_stats, att.lse,
- * conv.dfac and the dact buffers of the layers with an activation.
+ * conv.dfac and the dact buffers of the layers with an activation.  Errors: every module's argument,
+ * policy, buffer and workspace check runs before the first launch, so a refused call has written nothing.
  */
 aqt_status aqt_conformer_layer_fwd(const float *x, const aqt_conformer_layer_weights *w,
                                    const aqt_conformer_layer_shape *shape, const aqt_layer_policy *policy, float *y,
@@ -590,7 +591,7 @@ typedef struct aqt_conformer_layer_grads {
  * activations everywhere): dx [M,D] and the weight gradients asked for.  x and w as in the forward
  * call, saved as it left them (including every row_stats, out_row_stats, att.lse, conv.dfac and the
  * dact buffers).  conv_norm_scale / conv_norm_shift gradients are not produced (fixed statistics)
- * and must be NULL.
+ * and must be NULL.  As in the forward, every check runs before the first launch.
  */
 aqt_status aqt_conformer_layer_bwd(const float *dy, const float *x, const aqt_conformer_layer_weights *w,
                                    const aqt_conformer_layer_shape *shape, const aqt_layer_policy *policy,
