@@ -193,9 +193,14 @@ struct WeightSide {
   void *operand;   // what launch_dense_fwd_q gets as its workspace
   bool prepared;   // whether it already holds the matrix-core operand
 };
+// With a job list the quantizer launch is left to the caller (launch_quantize_weights_group over the list).
+struct WeightJobList {
+  WeightJob job[kWeightJobsMax];
+  int n = 0;
+};
 aqt_status weight_side(const aqt_dense_policy &p, const float *w, const aqt_saved &l, int64_t M, int64_t K, int64_t N,
                        int epilogue, uint32_t *wpart, void *wfrag, hipStream_t st, int32_t *dev_status,
-                       WeightSide *out) {
+                       WeightSide *out, WeightJobList *later = nullptr) {
   const bool takes = p.bits_x && fwd_q_takes_fragments(M, K, N, epilogue) && reinterpret_cast<uintptr_t>(l.xq) % 16 == 0;
   if (p.weights_ready) {
     const bool have = takes && l.wprep && reinterpret_cast<uintptr_t>(l.wprep) % 16 == 0;
@@ -206,8 +211,42 @@ aqt_status weight_side(const aqt_dense_policy &p, const float *w, const aqt_save
   if (!w) return AQT_ERR_INVALID_ARG;
   out->operand = wfrag;
   out->prepared = takes;
+  if (later) {
+    if (later->n >= kWeightJobsMax) return AQT_ERR_INVALID_ARG;
+    later->job[later->n++] = WeightJob{w, K, N, p.bits_w, l.wq_packed, l.s_w, l.wq_kn, l.mask_w, wpart,
+                                       takes ? wfrag : nullptr};
+    return AQT_OK;
+  }
   return launch_quantize_weights(w, K, N, p.bits_w, l.wq_packed, l.s_w, l.wq_kn, l.mask_w, wpart, st, dev_status,
                                  takes ? wfrag : nullptr);
+}
+
+// The weight-side buffers of an encoder layer's eight dense layers, behind the modules' shared workspace: the layer
+// call quantizes all of its matrices in one launch pair before the first module runs.
+struct LayerFwdWorkspace {
+  size_t module;           // bytes the modules share, at the front
+  uint32_t *wpart[8];
+  void *wfrag[8];
+  size_t total;
+};
+LayerFwdWorkspace carve_layer_fwd(void *ws, int64_t M, int64_t D, int64_t H) {
+  LayerFwdWorkspace f;
+  const size_t a = carve_ffn_fwd(nullptr, M, D, H).total, b = carve_ffn_fwd(nullptr, M, D, 3 * D).total;
+  f.module = a > b ? a : b;          // 3 D covers the convolution module's 2 D as well
+  size_t off = f.module;
+  auto take = [&](size_t bytes) {
+    uint8_t *p = ws ? static_cast<uint8_t *>(ws) + off : nullptr;
+    off += align_up(bytes, 256);
+    return p;
+  };
+  // fan-in, fan-out in aqt_layer_policy order
+  const int64_t kn[8][2] = {{D, H}, {H, D}, {D, 3 * D}, {D, D}, {D, 2 * D}, {D, D}, {D, H}, {H, D}};
+  for (int i = 0; i < 8; ++i) {
+    f.wpart[i] = reinterpret_cast<uint32_t *>(take(weight_ws_bytes(kn[i][1])));
+    f.wfrag[i] = take(fwd_wonly_workspace_bytes(kn[i][0], kn[i][1]));
+  }
+  f.total = off;
+  return f;
 }
 
 // The int32 accumulator must hold K * qmax_x * qmax_w; packed (<= 4 bit) weights enter the
@@ -244,7 +283,8 @@ static aqt_status ffn_fwd_check(const float *x, float ln_eps, const float *w1, c
 static aqt_status ffn_fwd_impl(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps, const float *w1,
                        const float *b1, const float *w2, const float *b2, int64_t M, int64_t D, int64_t H,
                        const aqt_dense_policy *policy, float *y, const aqt_ffn_saved *saved, void *ws,
-                       size_t ws_bytes, void *stream, int32_t *dev_status, const ResidualIn *res) {
+                       size_t ws_bytes, void *stream, int32_t *dev_status, const ResidualIn *res,
+    const WeightSide *sides = nullptr) {
   AQT_TRY(ffn_fwd_check(x, ln_eps, w1, w2, M, D, H, policy, y, saved, ws, ws_bytes));
   const aqt_dense_policy p1 = policy[0], p2 = policy[1];
   const aqt_saved &l1 = saved->l1, &l2 = saved->l2;
@@ -253,7 +293,15 @@ static aqt_status ffn_fwd_impl(const float *x, const float *ln_gamma, const floa
 
   // normalisation (+ first quantizer), first weights, first contraction with Swish
   WeightSide s1, s2;
-  AQT_TRY(weight_side(p1, w1, l1, M, D, H, AQT_EPI_SWISH, f.wpart1, f.wfrag1, st, dev_status, &s1));
+  if (sides) {
+    s1 = sides[0];
+    s2 = sides[1];
+  } else {   // both matrices through the weight quantizer in one launch pair
+    WeightJobList jobs;
+    AQT_TRY(weight_side(p1, w1, l1, M, D, H, AQT_EPI_SWISH, f.wpart1, f.wfrag1, st, dev_status, &s1, &jobs));
+    AQT_TRY(weight_side(p2, w2, l2, M, H, D, AQT_EPI_NONE, f.wpart2, f.wfrag2, st, dev_status, &s2, &jobs));
+    AQT_TRY(launch_quantize_weights_group(jobs.job, jobs.n, st, dev_status));
+  }
   const bool want_absmax = p2.bits_x != 0;
   if (p1.bits_x) {
     AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, saved->xn,
@@ -269,8 +317,7 @@ static aqt_status ffn_fwd_impl(const float *x, const float *ln_gamma, const floa
     AQT_TRY(launch_dense_fwd_wonly(saved->xn, l1.wq_packed, l1.s_w, M, D, H, p1.bits_w, b1, AQT_EPI_SWISH, saved->h,
                                    f.wfrag1, st));
   }
-  // second quantizer (one pass when the producer emitted max|h|), second weights, second contraction
-  AQT_TRY(weight_side(p2, w2, l2, M, H, D, AQT_EPI_NONE, f.wpart2, f.wfrag2, st, dev_status, &s2));
+  // second quantizer (one pass when the producer emitted max|h|), second contraction
   if (p2.bits_x) {
     if (p1.bits_x) {
       AQT_TRY(launch_quantize_with_absmax(saved->h, M, H, H, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),
@@ -308,7 +355,8 @@ static aqt_status conv_module_fwd_impl(const float *x, const float *ln_gamma, co
                                const float *norm_scale, const float *norm_shift, const float *w2, const float *b2,
                                int64_t B, int64_t T, int64_t D, int kw, int pad_left, const aqt_dense_policy *policy,
                                float *y, const aqt_conv_saved *saved, void *ws, size_t ws_bytes, void *stream,
-                               int32_t *dev_status, const ResidualIn *res) {
+                               int32_t *dev_status, const ResidualIn *res,
+    const WeightSide *sides = nullptr) {
   AQT_TRY(conv_module_fwd_check(x, ln_eps, w1, w_dw, w2, B, T, D, kw, pad_left, policy, y, saved, ws, ws_bytes));
   const aqt_dense_policy p1 = policy[0], p2 = policy[1];
   const aqt_saved &l1 = saved->pw1, &l2 = saved->pw2;
@@ -318,7 +366,15 @@ static aqt_status conv_module_fwd_impl(const float *x, const float *ln_gamma, co
 
   // normalisation + first quantizer, first pointwise convolution with the GLU
   WeightSide s1, s2;
-  AQT_TRY(weight_side(p1, w1, l1, M, D, 2 * D, AQT_EPI_GLU, f.wpart1, f.wfrag1, st, dev_status, &s1));
+  if (sides) {
+    s1 = sides[0];
+    s2 = sides[1];
+  } else {
+    WeightJobList jobs;
+    AQT_TRY(weight_side(p1, w1, l1, M, D, 2 * D, AQT_EPI_GLU, f.wpart1, f.wfrag1, st, dev_status, &s1, &jobs));
+    AQT_TRY(weight_side(p2, w2, l2, M, D, D, AQT_EPI_NONE, f.wpart2, f.wfrag2, st, dev_status, &s2, &jobs));
+    AQT_TRY(launch_quantize_weights_group(jobs.job, jobs.n, st, dev_status));
+  }
   AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, nullptr,
                                     saved->row_stats, f.ln, st, dev_status, res ? res->m : nullptr,
                                       res ? res->alpha : 0.0f, res ? res->r_out : nullptr));
@@ -328,7 +384,6 @@ static aqt_status conv_module_fwd_impl(const float *x, const float *ln_gamma, co
   AQT_TRY(launch_dwconv_fwd(saved->g, w_dw, b_dw, norm_scale, norm_shift, 1, B, T, D, kw, pad_left, saved->s,
                             saved->dfac, reinterpret_cast<uint32_t *>(f.h_absmax), st));
   // second pointwise convolution
-  AQT_TRY(weight_side(p2, w2, l2, M, D, D, AQT_EPI_NONE, f.wpart2, f.wfrag2, st, dev_status, &s2));
   AQT_TRY(launch_quantize_with_absmax(saved->s, M, D, D, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),
                                       l2.xq, l2.s_x, l2.mask_x, st, dev_status));
   return launch_dense_fwd_q(l2.xq, l2.s_x, l2.wq_packed, l2.s_w, M, D, D, p2.bits_w, b2, AQT_EPI_NONE, y, nullptr,
@@ -356,7 +411,8 @@ static aqt_status mhsa_fwd_check(const float *x, float ln_eps, const float *wqkv
 static aqt_status mhsa_fwd_impl(const float *x, const float *ln_gamma, const float *ln_beta, float ln_eps, const float *wqkv,
                         const float *bqkv, const float *wo, const float *bo, int64_t B, int64_t T, int64_t D,
                         int heads, int left_context, int right_context, const aqt_dense_policy *policy, float *y,
-                        const aqt_mhsa_saved *saved, void *ws, size_t ws_bytes, void *stream, int32_t *dev_status, const ResidualIn *res) {
+                        const aqt_mhsa_saved *saved, void *ws, size_t ws_bytes, void *stream, int32_t *dev_status, const ResidualIn *res,
+    const WeightSide *sides = nullptr) {
   AQT_TRY(mhsa_fwd_check(x, ln_eps, wqkv, wo, B, T, D, heads, policy, y, saved, ws, ws_bytes));
   const aqt_dense_policy p1 = policy[0], p2 = policy[1];
   const aqt_saved &l1 = saved->qkv, &l2 = saved->out;
@@ -365,7 +421,15 @@ static aqt_status mhsa_fwd_impl(const float *x, const float *ln_gamma, const flo
   hipStream_t st = static_cast<hipStream_t>(stream);
   // normalisation + first quantizer, fused projection of queries, keys and values
   WeightSide s1, s2;
-  AQT_TRY(weight_side(p1, wqkv, l1, M, D, 3 * D, AQT_EPI_NONE, f.wpart1, f.wfrag1, st, dev_status, &s1));
+  if (sides) {
+    s1 = sides[0];
+    s2 = sides[1];
+  } else {
+    WeightJobList jobs;
+    AQT_TRY(weight_side(p1, wqkv, l1, M, D, 3 * D, AQT_EPI_NONE, f.wpart1, f.wfrag1, st, dev_status, &s1, &jobs));
+    AQT_TRY(weight_side(p2, wo, l2, M, D, D, AQT_EPI_NONE, f.wpart2, f.wfrag2, st, dev_status, &s2, &jobs));
+    AQT_TRY(launch_quantize_weights_group(jobs.job, jobs.n, st, dev_status));
+  }
   AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, nullptr,
                                     saved->row_stats, f.ln, st, dev_status, res ? res->m : nullptr,
                                       res ? res->alpha : 0.0f, res ? res->r_out : nullptr));
@@ -375,7 +439,6 @@ static aqt_status mhsa_fwd_impl(const float *x, const float *ln_gamma, const flo
   AQT_TRY(launch_attention(saved->qkv_f, B, T, D, heads, left_context, right_context, saved->ctx,
                            reinterpret_cast<uint32_t *>(f.h_absmax), saved->lse, st));
   // output projection
-  AQT_TRY(weight_side(p2, wo, l2, M, D, D, AQT_EPI_NONE, f.wpart2, f.wfrag2, st, dev_status, &s2));
   AQT_TRY(launch_quantize_with_absmax(saved->ctx, M, D, D, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),
                                       l2.xq, l2.s_x, l2.mask_x, st, dev_status));
   return launch_dense_fwd_q(l2.xq, l2.s_x, l2.wq_packed, l2.s_w, M, D, D, p2.bits_w, bo, AQT_EPI_NONE, y, nullptr,
@@ -485,9 +548,7 @@ size_t aqt_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, int bits_x, 
       return carve_ffn_fwd(nullptr, M, K, 3 * K).total;
     case AQT_OP_CONFORMER_LAYER_FWD: {
       if (!shape_ok(M, K) || N < 1) return 0;
-      size_t a = carve_ffn_fwd(nullptr, M, K, N).total;
-      const size_t b = carve_ffn_fwd(nullptr, M, K, 3 * K).total;   // covers the convolution module's 2 K as well
-      return a > b ? a : b;
+      return carve_layer_fwd(nullptr, M, K, N).total;
     }
     case AQT_OP_ATTENTION_BWD:
       if (M < 1 || N < 1) return 0;
@@ -870,25 +931,49 @@ aqt_status aqt_conformer_layer_fwd(const float *x, const aqt_conformer_layer_wei
                                 g.pad_left, pc, saved->m, &saved->conv, ws, ws_bytes));
   AQT_TRY(ffn_fwd_check(saved->r2, g.ln_eps, w->ffn2_w1, w->ffn2_w2, M, g.D, g.H, pf2, saved->m, &saved->ffn2, ws,
                         ws_bytes));
+  // every weight matrix of the layer that is not already in serving form goes through the weight quantizer in one
+  // launch pair; the modules then find their weight side ready
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const LayerFwdWorkspace lw = carve_layer_fwd(ws, M, g.D, g.H);
+  WeightJobList jobs;
+  WeightSide sd[8];
+  const int64_t D = g.D, H = g.H;
+  AQT_TRY(weight_side(pf1[0], w->ffn1_w1, saved->ffn1.l1, M, D, H, AQT_EPI_SWISH, lw.wpart[0], lw.wfrag[0], st,
+                      dev_status, &sd[0], &jobs));
+  AQT_TRY(weight_side(pf1[1], w->ffn1_w2, saved->ffn1.l2, M, H, D, AQT_EPI_NONE, lw.wpart[1], lw.wfrag[1], st,
+                      dev_status, &sd[1], &jobs));
+  AQT_TRY(weight_side(pa[0], w->att_wqkv, saved->att.qkv, M, D, 3 * D, AQT_EPI_NONE, lw.wpart[2], lw.wfrag[2], st,
+                      dev_status, &sd[2], &jobs));
+  AQT_TRY(weight_side(pa[1], w->att_wo, saved->att.out, M, D, D, AQT_EPI_NONE, lw.wpart[3], lw.wfrag[3], st,
+                      dev_status, &sd[3], &jobs));
+  AQT_TRY(weight_side(pc[0], w->conv_w1, saved->conv.pw1, M, D, 2 * D, AQT_EPI_GLU, lw.wpart[4], lw.wfrag[4], st,
+                      dev_status, &sd[4], &jobs));
+  AQT_TRY(weight_side(pc[1], w->conv_w2, saved->conv.pw2, M, D, D, AQT_EPI_NONE, lw.wpart[5], lw.wfrag[5], st,
+                      dev_status, &sd[5], &jobs));
+  AQT_TRY(weight_side(pf2[0], w->ffn2_w1, saved->ffn2.l1, M, D, H, AQT_EPI_SWISH, lw.wpart[6], lw.wfrag[6], st,
+                      dev_status, &sd[6], &jobs));
+  AQT_TRY(weight_side(pf2[1], w->ffn2_w2, saved->ffn2.l2, M, H, D, AQT_EPI_NONE, lw.wpart[7], lw.wfrag[7], st,
+                      dev_status, &sd[7], &jobs));
+  AQT_TRY(launch_quantize_weights_group(jobs.job, jobs.n, st, dev_status));
   // half-step feed-forward module.  From here on the residual connection in front of a module is formed by that
   // module's normalisation pass: r = r_prev + alpha * (previous module's output), left in saved->r*.
   AQT_TRY(ffn_fwd_impl(x, w->ffn1_ln_g, w->ffn1_ln_b, g.ln_eps, w->ffn1_w1, w->ffn1_b1, w->ffn1_w2, w->ffn1_b2, M, g.D,
-                       g.H, pf1, saved->m, &saved->ffn1, ws, ws_bytes, stream, dev_status, nullptr));
+                       g.H, pf1, saved->m, &saved->ffn1, ws, lw.module, stream, dev_status, nullptr, &sd[0]));
   // self-attention module on r1 = x + ffn(x) / 2
   const ResidualIn in1 = {saved->m, 0.5f, saved->r1};
   AQT_TRY(mhsa_fwd_impl(x, w->att_ln_g, w->att_ln_b, g.ln_eps, w->att_wqkv, w->att_bqkv, w->att_wo, w->att_bo, g.B, g.T,
-                        g.D, g.heads, g.left_context, g.right_context, pa, saved->m, &saved->att, ws, ws_bytes, stream,
-                        dev_status, &in1));
+                        g.D, g.heads, g.left_context, g.right_context, pa, saved->m, &saved->att, ws, lw.module, stream,
+                        dev_status, &in1, &sd[2]));
   // convolution module on r2 = r1 + mhsa(r1)
   const ResidualIn in2 = {saved->m, 1.0f, saved->r2};
   AQT_TRY(conv_module_fwd_impl(saved->r1, w->conv_ln_g, w->conv_ln_b, g.ln_eps, w->conv_w1, w->conv_b1, w->conv_wdw,
                                w->conv_bdw, w->conv_norm_scale, w->conv_norm_shift, w->conv_w2, w->conv_b2, g.B, g.T,
-                               g.D, g.kw, g.pad_left, pc, saved->m, &saved->conv, ws, ws_bytes, stream, dev_status,
-                               &in2));
+                               g.D, g.kw, g.pad_left, pc, saved->m, &saved->conv, ws, lw.module, stream, dev_status,
+                               &in2, &sd[4]));
   // second half-step feed-forward module on r3 = r2 + conv(r2)
   const ResidualIn in3 = {saved->m, 1.0f, saved->r3};
   AQT_TRY(ffn_fwd_impl(saved->r2, w->ffn2_ln_g, w->ffn2_ln_b, g.ln_eps, w->ffn2_w1, w->ffn2_b1, w->ffn2_w2, w->ffn2_b2,
-                       M, g.D, g.H, pf2, saved->m, &saved->ffn2, ws, ws_bytes, stream, dev_status, &in3));
+                       M, g.D, g.H, pf2, saved->m, &saved->ffn2, ws, lw.module, stream, dev_status, &in3, &sd[6]));
   // final normalisation of r4 = r3 + ffn(r3) / 2
   return launch_layernorm_quantize(saved->r3, M, g.D, w->out_ln_g, w->out_ln_b, g.ln_eps, 8, nullptr, nullptr, y,
                                    saved->out_row_stats, ws, static_cast<hipStream_t>(stream), dev_status, saved->m,

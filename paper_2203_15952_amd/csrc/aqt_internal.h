@@ -72,6 +72,20 @@ aqt_status launch_quantize_with_scale(const float *x, int64_t rows, int64_t cols
 aqt_status launch_quantize_weights(const float *w, int64_t K, int64_t N, int bits_w, void *wq_packed,
                                    float *s_w, int8_t *wq_kn, uint32_t *mask_w, uint32_t *part,
                                    hipStream_t st, int32_t *dev_status, void *wfrag = nullptr);
+// Several matrices through the weight quantizer in one launch pair (same arithmetic per matrix).
+struct WeightJob {
+  const float *w;
+  int64_t K, N;
+  int bits_w;
+  void *wq_packed;
+  float *s_w;
+  int8_t *wq_kn;       // nullable
+  uint32_t *mask_w;    // nullable
+  uint32_t *part;      // kWeightSlabs x N words of its own
+  void *wfrag;         // nullable
+};
+constexpr int kWeightJobsMax = 8;
+aqt_status launch_quantize_weights_group(const WeightJob *jobs, int n, hipStream_t st, int32_t *dev_status);
 inline size_t weight_ws_bytes(int64_t N) { return align_up(static_cast<size_t>(kWeightSlabs) * N * 4, 256); }
 aqt_status launch_unpack_weights(const void *wq_packed, int64_t K, int64_t N, int bits_w,
                                  int8_t *codes_kn, hipStream_t st);

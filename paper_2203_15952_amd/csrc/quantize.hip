@@ -241,17 +241,17 @@ __global__ __launch_bounds__(kThreads) void quantize_elem_kernel(const float *__
 constexpr int kWCols = 32;
 constexpr int kWChunk = 64;
 
-__global__ __launch_bounds__(kThreads) void wabsmax_partial_kernel(const float *__restrict__ w, int64_t K,
-                                                                   int64_t N, int64_t rows_per_slab, int vec4,
-                                                                   uint32_t *__restrict__ part) {
+__device__ __forceinline__ void wabsmax_partial_body(const float *__restrict__ w, int64_t K, int64_t N,
+                                                     int64_t rows_per_slab, int vec4, uint32_t *__restrict__ part,
+                                                     unsigned bx, unsigned by) {
   __shared__ uint32_t sm[16][64];
-  const int64_t k0 = static_cast<int64_t>(blockIdx.y) * rows_per_slab;
+  const int64_t k0 = static_cast<int64_t>(by) * rows_per_slab;
   const int64_t k1 = min(K, k0 + rows_per_slab);
   if (vec4) {
     // 16 column groups of 4 x 16 row lanes; four independent 16-byte loads in flight per
     // thread (the matrix is small, so the pass is bound by load latency, not bandwidth)
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-    const int64_t n = static_cast<int64_t>(blockIdx.x) * 64 + tx * 4;
+    const int64_t n = static_cast<int64_t>(bx) * 64 + tx * 4;
     uint32_t m0 = 0, m1 = 0, m2 = 0, m3 = 0;
     if (n < N) {
       const float4 zero = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
@@ -269,33 +269,39 @@ __global__ __launch_bounds__(kThreads) void wabsmax_partial_kernel(const float *
     sm[ty][tx * 4 + 0] = m0; sm[ty][tx * 4 + 1] = m1; sm[ty][tx * 4 + 2] = m2; sm[ty][tx * 4 + 3] = m3;
     __syncthreads();
     if (threadIdx.x < 64) {
-      const int64_t nn = static_cast<int64_t>(blockIdx.x) * 64 + threadIdx.x;
+      const int64_t nn = static_cast<int64_t>(bx) * 64 + threadIdx.x;
       uint32_t m = 0;
 #pragma unroll
       for (int j = 0; j < 16; ++j) m = max(m, sm[j][threadIdx.x]);
-      if (nn < N) part[static_cast<int64_t>(blockIdx.y) * N + nn] = m;
+      if (nn < N) part[static_cast<int64_t>(by) * N + nn] = m;
     }
     return;
   }
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  const int64_t n = static_cast<int64_t>(blockIdx.x) * 64 + tx;
+  const int64_t n = static_cast<int64_t>(bx) * 64 + tx;
   uint32_t m = 0;
   if (n < N)
     for (int64_t k = k0 + ty; k < k1; k += 4) m = max(m, abs_bits(w[k * N + n]));
   sm[ty][tx] = m;
   __syncthreads();
   if (ty == 0 && n < N)
-    part[static_cast<int64_t>(blockIdx.y) * N + n] = max(max(sm[0][tx], sm[1][tx]), max(sm[2][tx], sm[3][tx]));
+    part[static_cast<int64_t>(by) * N + n] = max(max(sm[0][tx], sm[1][tx]), max(sm[2][tx], sm[3][tx]));
 }
 
-__global__ __launch_bounds__(kThreads) void quantize_weights_kernel(
+__global__ __launch_bounds__(kThreads) void wabsmax_partial_kernel(const float *__restrict__ w, int64_t K,
+                                                                   int64_t N, int64_t rows_per_slab, int vec4,
+                                                                   uint32_t *__restrict__ part) {
+  wabsmax_partial_body(w, K, N, rows_per_slab, vec4, part, blockIdx.x, blockIdx.y);
+}
+
+__device__ __forceinline__ void quantize_weights_body(
     const float *__restrict__ w, int64_t K, int64_t N, int qmax, int packed, const uint32_t *__restrict__ part,
     int slabs, uint8_t *__restrict__ wq_packed, float *__restrict__ s_w, int8_t *__restrict__ wq_kn,
-    uint32_t *__restrict__ mask_w, int32_t *dev_status, uint4 *__restrict__ wfrag) {
+    uint32_t *__restrict__ mask_w, int32_t *dev_status, uint4 *__restrict__ wfrag, unsigned bx, unsigned by) {
   __shared__ int8_t tile[kWCols][kWChunk + 4];
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-  const int64_t n0 = static_cast<int64_t>(blockIdx.x) * kWCols;
-  const int64_t k0 = static_cast<int64_t>(blockIdx.y) * kWChunk;
+  const int64_t n0 = static_cast<int64_t>(bx) * kWCols;
+  const int64_t k0 = static_cast<int64_t>(by) * kWChunk;
   const int64_t n = n0 + tx;
   const bool live = n < N;
   uint32_t m = 0;
@@ -303,7 +309,7 @@ __global__ __launch_bounds__(kThreads) void quantize_weights_kernel(
     for (int j = 0; j < slabs; ++j) m = max(m, part[static_cast<int64_t>(j) * N + n]);
   const float fq = static_cast<float>(qmax);
   const float s = __uint_as_float(m) / fq;
-  if (blockIdx.y == 0 && ty == 0 && live) {
+  if (by == 0 && ty == 0 && live) {
     s_w[n] = s;
     if (m >= 0x7F800000u && dev_status) *dev_status = AQT_ERR_NONFINITE;
   }
@@ -364,7 +370,7 @@ __global__ __launch_bounds__(kThreads) void quantize_weights_kernel(
           }
           d[q] = t;
         }
-        const int64_t frag = static_cast<int64_t>(blockIdx.x) * (K / 64) + blockIdx.y;
+        const int64_t frag = static_cast<int64_t>(bx) * (K / 64) + by;
         wfrag[frag * 64 + lane] = make_uint4(d[0], d[1], d[2], d[3]);
       }
     } else if (threadIdx.x < 128) {
@@ -378,10 +384,51 @@ __global__ __launch_bounds__(kThreads) void quantize_weights_kernel(
           t |= (static_cast<uint32_t>(tile[lr][32 * h + 16 * lk + 4 * q + b]) & 0xFFu) << (8 * b);
         d[q] = t;
       }
-      const int64_t frag = static_cast<int64_t>(blockIdx.x) * (K / 32) + 2 * blockIdx.y + h;
+      const int64_t frag = static_cast<int64_t>(bx) * (K / 32) + 2 * by + h;
       wfrag[frag * 64 + lane] = make_uint4(d[0], d[1], d[2], d[3]);
     }
   }
+}
+
+__global__ __launch_bounds__(kThreads) void quantize_weights_kernel(
+    const float *__restrict__ w, int64_t K, int64_t N, int qmax, int packed, const uint32_t *__restrict__ part,
+    int slabs, uint8_t *__restrict__ wq_packed, float *__restrict__ s_w, int8_t *__restrict__ wq_kn,
+    uint32_t *__restrict__ mask_w, int32_t *dev_status, uint4 *__restrict__ wfrag) {
+  quantize_weights_body(w, K, N, qmax, packed, part, slabs, wq_packed, s_w, wq_kn, mask_w, dev_status, wfrag,
+                        blockIdx.x, blockIdx.y);
+}
+
+// Several weight matrices in one launch pair: gridDim.z walks the matrices, gridDim.x and .y cover the largest of
+// them, and a block outside its own matrix's grid leaves at once.  The arithmetic per matrix is that of the
+// single-matrix kernels above.
+struct WeightJobDev {
+  const float *w;
+  int64_t K, N, rows_per_slab;
+  int qmax, packed, slabs, vec4;
+  unsigned gx1, gx2, gy2;     // this matrix's own grid: abs-max columns, quantizer columns and fan-in chunks
+  uint32_t *part;
+  uint8_t *wq_packed;
+  float *s_w;
+  int8_t *wq_kn;
+  uint32_t *mask_w;
+  uint4 *wfrag;
+};
+struct WeightJobsDev {
+  WeightJobDev job[kWeightJobsMax];
+};
+
+__global__ __launch_bounds__(kThreads) void wabsmax_partial_group_kernel(const WeightJobsDev jobs) {
+  const WeightJobDev &j = jobs.job[blockIdx.z];
+  if (blockIdx.x >= j.gx1 || blockIdx.y >= static_cast<unsigned>(j.slabs)) return;
+  wabsmax_partial_body(j.w, j.K, j.N, j.rows_per_slab, j.vec4, j.part, blockIdx.x, blockIdx.y);
+}
+
+__global__ __launch_bounds__(kThreads) void quantize_weights_group_kernel(const WeightJobsDev jobs,
+                                                                          int32_t *dev_status) {
+  const WeightJobDev &j = jobs.job[blockIdx.z];
+  if (blockIdx.x >= j.gx2 || blockIdx.y >= j.gy2) return;
+  quantize_weights_body(j.w, j.K, j.N, j.qmax, j.packed, j.part, j.slabs, j.wq_packed, j.s_w, j.wq_kn, j.mask_w,
+                        dev_status, j.wfrag, blockIdx.x, blockIdx.y);
 }
 
 __global__ __launch_bounds__(kThreads) void zero_words_kernel(uint32_t *p, int64_t n) {
@@ -518,6 +565,51 @@ aqt_status launch_quantize_weights(const float *w, int64_t K, int64_t N, int bit
   quantize_weights_kernel<<<g2, kThreads, 0, st>>>(w, K, N, qmax_of(bits_w), packed4(bits_w) ? 1 : 0, part,
                                                    static_cast<int>(slabs), static_cast<uint8_t *>(wq_packed),
                                                    s_w, wq_kn, mask_w, dev_status, static_cast<uint4 *>(wfrag));
+  AQT_HIP(hipGetLastError());
+  return AQT_OK;
+}
+
+aqt_status launch_quantize_weights_group(const WeightJob *jobs, int n, hipStream_t st, int32_t *dev_status) {
+  if (n < 0 || n > kWeightJobsMax) return AQT_ERR_INVALID_ARG;
+  if (n == 0) return AQT_OK;
+  if (n == 1)
+    return launch_quantize_weights(jobs[0].w, jobs[0].K, jobs[0].N, jobs[0].bits_w, jobs[0].wq_packed, jobs[0].s_w,
+                                   jobs[0].wq_kn, jobs[0].mask_w, jobs[0].part, st, dev_status, jobs[0].wfrag);
+  WeightJobsDev d;
+  unsigned gx1 = 0, gy1 = 0, gx2 = 0, gy2 = 0;
+  for (int i = 0; i < n; ++i) {
+    const WeightJob &a = jobs[i];
+    if (!a.w || !a.wq_packed || !a.s_w || !a.part || a.K < 1 || a.N < 1) return AQT_ERR_INVALID_ARG;
+    if (a.wfrag && (a.N % kWCols != 0 || a.K % kWChunk != 0 || reinterpret_cast<uintptr_t>(a.wfrag) % 16 != 0))
+      return AQT_ERR_INVALID_ARG;
+    if (cdiv(a.N, kWCols) > 0x7FFFFFFF || cdiv(a.K, kWChunk) > 65535) return AQT_ERR_UNSUPPORTED;
+    if (a.mask_w) {
+      const int64_t words = cdiv(a.K * a.N, 32);
+      zero_words_kernel<<<grid_for(words, kThreads, 1024), kThreads, 0, st>>>(a.mask_w, words);
+      AQT_HIP(hipGetLastError());
+    }
+    int64_t slabs = cdiv(a.K, 32);
+    if (slabs > kWeightSlabs) slabs = kWeightSlabs;
+    const int64_t rows_per_slab = cdiv(a.K, slabs);
+    slabs = cdiv(a.K, rows_per_slab);
+    WeightJobDev &j = d.job[i];
+    j.w = a.w; j.K = a.K; j.N = a.N; j.rows_per_slab = rows_per_slab;
+    j.qmax = qmax_of(a.bits_w); j.packed = packed4(a.bits_w) ? 1 : 0; j.slabs = static_cast<int>(slabs);
+    j.vec4 = (a.N % 4 == 0) && (reinterpret_cast<uintptr_t>(a.w) % 16 == 0);
+    j.gx1 = static_cast<unsigned>(cdiv(a.N, 64));
+    j.gx2 = static_cast<unsigned>(cdiv(a.N, kWCols));
+    j.gy2 = static_cast<unsigned>(cdiv(a.K, kWChunk));
+    j.part = a.part; j.wq_packed = static_cast<uint8_t *>(a.wq_packed); j.s_w = a.s_w; j.wq_kn = a.wq_kn;
+    j.mask_w = a.mask_w; j.wfrag = static_cast<uint4 *>(a.wfrag);
+    gx1 = j.gx1 > gx1 ? j.gx1 : gx1;
+    gy1 = static_cast<unsigned>(slabs) > gy1 ? static_cast<unsigned>(slabs) : gy1;
+    gx2 = j.gx2 > gx2 ? j.gx2 : gx2;
+    gy2 = j.gy2 > gy2 ? j.gy2 : gy2;
+  }
+  for (int i = n; i < kWeightJobsMax; ++i) d.job[i] = d.job[0];   // never indexed: gridDim.z is n
+  wabsmax_partial_group_kernel<<<dim3(gx1, gy1, static_cast<unsigned>(n)), kThreads, 0, st>>>(d);
+  AQT_HIP(hipGetLastError());
+  quantize_weights_group_kernel<<<dim3(gx2, gy2, static_cast<unsigned>(n)), kThreads, 0, st>>>(d, dev_status);
   AQT_HIP(hipGetLastError());
   return AQT_OK;
 }

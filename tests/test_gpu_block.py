@@ -188,6 +188,7 @@ def rows_of(M):
     (12800, 512, 2048, ((4, 8), (4, 8))),      # the feed-forward configuration: int4 weights, int8 activations
     (1000, 256, 512, ((8, 8), (4, 4))),        # int8 x int8 first, int4 x int4 second; ragged M
     (70, 40, 24, ((4, 8), (8, 8))),            # shapes the general kernels take
+    (33, 27, 22, ((4, 8), (4, 8))),            # odd fan-in under packed codes, widths that are no multiple of 4
 ])
 def test_ffn_chain_stage_by_stage(M, D, H, policy):
     say("ffn chain", M, D, H, policy)
