@@ -304,12 +304,13 @@ static aqt_status ffn_fwd_impl(const float *x, const float *ln_gamma, const floa
   }
   const bool want_absmax = p2.bits_x != 0;
   if (p1.bits_x) {
+    // the normalisation's first pass also clears the word the contraction's epilogue collects max|h| in
+    uint32_t *hmax = want_absmax ? reinterpret_cast<uint32_t *>(f.h_absmax) : nullptr;
     AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, saved->xn,
                                       saved->row_stats, f.ln, st, dev_status, res ? res->m : nullptr,
-                                      res ? res->alpha : 0.0f, res ? res->r_out : nullptr));
+                                      res ? res->alpha : 0.0f, res ? res->r_out : nullptr, hmax));
     AQT_TRY(launch_dense_fwd_q(l1.xq, l1.s_x, l1.wq_packed, l1.s_w, M, D, H, p1.bits_w, b1, AQT_EPI_SWISH, saved->h,
-                               nullptr, want_absmax ? reinterpret_cast<uint32_t *>(f.h_absmax) : nullptr, s1.operand,
-                               st, l1.dact, s1.prepared));
+                               nullptr, hmax, s1.operand, st, l1.dact, s1.prepared, true));
   } else {
     AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, 8, nullptr, nullptr, saved->xn,
                                       saved->row_stats, f.ln, st, dev_status, res ? res->m : nullptr,
@@ -375,14 +376,15 @@ static aqt_status conv_module_fwd_impl(const float *x, const float *ln_gamma, co
     AQT_TRY(weight_side(p2, w2, l2, M, D, D, AQT_EPI_NONE, f.wpart2, f.wfrag2, st, dev_status, &s2, &jobs));
     AQT_TRY(launch_quantize_weights_group(jobs.job, jobs.n, st, dev_status));
   }
+  uint32_t *smax = reinterpret_cast<uint32_t *>(f.h_absmax);   // cleared by the normalisation's first pass
   AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, nullptr,
                                     saved->row_stats, f.ln, st, dev_status, res ? res->m : nullptr,
-                                      res ? res->alpha : 0.0f, res ? res->r_out : nullptr));
+                                    res ? res->alpha : 0.0f, res ? res->r_out : nullptr, smax));
   AQT_TRY(launch_dense_fwd_q(l1.xq, l1.s_x, l1.wq_packed, l1.s_w, M, D, 2 * D, p1.bits_w, b1, AQT_EPI_GLU, saved->g,
                              nullptr, nullptr, s1.operand, st, l1.dact, s1.prepared));
   // depthwise convolution, normalisation, Swish; max|s| for the one-pass quantizer
   AQT_TRY(launch_dwconv_fwd(saved->g, w_dw, b_dw, norm_scale, norm_shift, 1, B, T, D, kw, pad_left, saved->s,
-                            saved->dfac, reinterpret_cast<uint32_t *>(f.h_absmax), st));
+                            saved->dfac, smax, st, true));
   // second pointwise convolution
   AQT_TRY(launch_quantize_with_absmax(saved->s, M, D, D, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),
                                       l2.xq, l2.s_x, l2.mask_x, st, dev_status));
@@ -430,14 +432,15 @@ static aqt_status mhsa_fwd_impl(const float *x, const float *ln_gamma, const flo
     AQT_TRY(weight_side(p2, wo, l2, M, D, D, AQT_EPI_NONE, f.wpart2, f.wfrag2, st, dev_status, &s2, &jobs));
     AQT_TRY(launch_quantize_weights_group(jobs.job, jobs.n, st, dev_status));
   }
+  uint32_t *cmax = reinterpret_cast<uint32_t *>(f.h_absmax);   // cleared by the normalisation's first pass
   AQT_TRY(launch_layernorm_quantize(x, M, D, ln_gamma, ln_beta, ln_eps, p1.bits_x, l1.xq, l1.s_x, nullptr,
                                     saved->row_stats, f.ln, st, dev_status, res ? res->m : nullptr,
-                                      res ? res->alpha : 0.0f, res ? res->r_out : nullptr));
+                                    res ? res->alpha : 0.0f, res ? res->r_out : nullptr, cmax));
   AQT_TRY(launch_dense_fwd_q(l1.xq, l1.s_x, l1.wq_packed, l1.s_w, M, D, 3 * D, p1.bits_w, bqkv, AQT_EPI_NONE,
                              saved->qkv_f, nullptr, nullptr, s1.operand, st, nullptr, s1.prepared));
   // attention in float32; max|ctx| for the one-pass quantizer
-  AQT_TRY(launch_attention(saved->qkv_f, B, T, D, heads, left_context, right_context, saved->ctx,
-                           reinterpret_cast<uint32_t *>(f.h_absmax), saved->lse, st));
+  AQT_TRY(launch_attention(saved->qkv_f, B, T, D, heads, left_context, right_context, saved->ctx, cmax, saved->lse,
+                           st, true));
   // output projection
   AQT_TRY(launch_quantize_with_absmax(saved->ctx, M, D, D, p2.bits_x, reinterpret_cast<const uint32_t *>(f.h_absmax),
                                       l2.xq, l2.s_x, l2.mask_x, st, dev_status));

@@ -94,7 +94,8 @@ aqt_status launch_unpack_weights(const void *wq_packed, int64_t K, int64_t N, in
 aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq_packed,
                               const float *s_w, int64_t M, int64_t K, int64_t N, int bits_w,
                               const float *bias, int epilogue, float *y, int32_t *acc_out, uint32_t *y_absmax,
-                              void *ws, hipStream_t st, float *dact = nullptr, bool ws_is_prepared = false);
+                              void *ws, hipStream_t st, float *dact = nullptr, bool ws_is_prepared = false,
+                              bool absmax_is_zero = false);
 // True when the matrix-core kernel takes the shape (then its weight operand may be handed over
 // already in fragment order: from the weight quantizer, or from launch_prepare_weights).
 bool fwd_q_takes_fragments(int64_t M, int64_t K, int64_t N, int epilogue);
@@ -115,11 +116,13 @@ aqt_status launch_dense_bwd(const float *dy, const aqt_saved *sv, int64_t M, int
 
 // ---- block pieces (block.hip) -----------------------------------------------------------
 size_t layernorm_ws_bytes(int64_t M);
-// res / alpha / sum_out (optional): normalise x + alpha * res instead of x and leave that sum in sum_out
+// res / alpha / sum_out (optional): normalise x + alpha * res instead of x and leave that sum in sum_out.
+// zero_word (optional): a word the first pass clears, e.g. the abs-max word of a producer launched after it
+// (which is then told absmax_is_zero and needs no clearing launch of its own).
 aqt_status launch_layernorm_quantize(const float *x, int64_t M, int64_t D, const float *gamma, const float *beta,
                                      float eps, int bits, int8_t *q, float *scale, float *y_out, float *row_stats,
                                      void *ws, hipStream_t st, int32_t *dev_status, const float *res = nullptr,
-                                     float alpha = 0.0f, float *sum_out = nullptr);
+                                     float alpha = 0.0f, float *sum_out = nullptr, uint32_t *zero_word = nullptr);
 size_t layernorm_bwd_ws_bytes(int64_t D);
 aqt_status launch_layernorm_bwd(const float *x, const float *stats, const float *gamma, const float *dy,
                                 const float *add, int64_t M, int64_t D, float *dx, float *dgamma, float *dbeta,
@@ -135,7 +138,7 @@ aqt_status launch_fake_matmul_f32(const int8_t *xq, const int8_t *wq_kn, int64_t
 size_t dwconv_bwd_ws_bytes(int64_t C, int kw);
 aqt_status launch_dwconv_fwd(const float *x, const float *w, const float *bias, const float *na, const float *nb,
                              int swish, int64_t B, int64_t T, int64_t C, int kw, int pad_left, float *out, float *dfac,
-                             uint32_t *absmax, hipStream_t st);
+                             uint32_t *absmax, hipStream_t st, bool absmax_is_zero = false);
 aqt_status launch_dwconv_bwd(const float *dout, const float *dmul, const float *x, const float *w, int64_t B, int64_t T,
                              int64_t C, int kw, int pad_left, float *dx, float *dw, float *dbias, void *ws,
                              hipStream_t st);
@@ -143,7 +146,7 @@ aqt_status launch_dwconv_bwd(const float *dout, const float *dmul, const float *
 // ---- attention core of the self-attention module (attention.hip) ---------------------------
 bool attention_shape_ok(int64_t B, int64_t T, int64_t D, int heads);
 aqt_status launch_attention(const float *qkv, int64_t B, int64_t T, int64_t D, int heads, int left, int right,
-                            float *ctx, uint32_t *absmax, float *lse, hipStream_t st);
+                            float *ctx, uint32_t *absmax, float *lse, hipStream_t st, bool absmax_is_zero = false);
 size_t attention_bwd_ws_bytes(int64_t B, int64_t T, int heads);
 aqt_status launch_attention_bwd(const float *qkv, const float *ctx, const float *dctx, const float *lse, int64_t B,
                                 int64_t T, int64_t D, int heads, int left, int right, float *dqkv, void *ws,

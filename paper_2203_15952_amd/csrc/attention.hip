@@ -524,9 +524,9 @@ bool attention_shape_ok(int64_t B, int64_t T, int64_t D, int heads) {
 }
 
 aqt_status launch_attention(const float *qkv, int64_t B, int64_t T, int64_t D, int heads, int left, int right,
-                            float *ctx, uint32_t *absmax, float *lse, hipStream_t st) {
+                            float *ctx, uint32_t *absmax, float *lse, hipStream_t st, bool absmax_is_zero) {
   const AttnGeom g = attn_geom(B, T, D, heads, left, right);
-  if (absmax) zero_attn_absmax_kernel<<<1, 64, 0, st>>>(absmax);
+  if (absmax && !absmax_is_zero) zero_attn_absmax_kernel<<<1, 64, 0, st>>>(absmax);
   const int64_t blocks = static_cast<int64_t>(g.qtiles) * heads * B;
   attention_fwd_kernel<<<static_cast<unsigned>(blocks), kThreads, 0, st>>>(qkv, g, ctx, absmax, lse);
   AQT_HIP(hipGetLastError());

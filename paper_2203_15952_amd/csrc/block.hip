@@ -62,9 +62,11 @@ __global__ __launch_bounds__(kThreads) void ln_stats_kernel(const float *__restr
                                                             const float *__restrict__ beta, float eps,
                                                             float *__restrict__ stats, uint32_t *__restrict__ partial,
                                                             const float *__restrict__ res, float alpha,
-                                                            float *__restrict__ sum_out) {
+                                                            float *__restrict__ sum_out,
+                                                            uint32_t *__restrict__ zero_word) {
   __shared__ uint32_t sm[4];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (zero_word && blockIdx.x == 0 && threadIdx.x == 0) *zero_word = 0u;   // for a kernel launched after this one
   uint32_t amax = 0u;
   for (int64_t m = static_cast<int64_t>(blockIdx.x) * 4 + wave; m < M; m += static_cast<int64_t>(gridDim.x) * 4) {
     const float *row = x + m * D;
@@ -480,7 +482,7 @@ size_t layernorm_ws_bytes(int64_t M) {
 aqt_status launch_layernorm_quantize(const float *x, int64_t M, int64_t D, const float *gamma, const float *beta,
                                      float eps, int bits, int8_t *q, float *scale, float *y_out, float *row_stats,
                                      void *ws, hipStream_t st, int32_t *dev_status, const float *res, float alpha,
-                                     float *sum_out) {
+                                     float *sum_out, uint32_t *zero_word) {
   uint32_t *partial = static_cast<uint32_t *>(ws);
   float *stats = row_stats ? row_stats
                            : reinterpret_cast<float *>(static_cast<uint8_t *>(ws) +
@@ -490,9 +492,9 @@ aqt_status launch_layernorm_quantize(const float *x, int64_t M, int64_t D, const
                    (!y_out || reinterpret_cast<uintptr_t>(y_out) % 16 == 0) &&
                    (!q || reinterpret_cast<uintptr_t>(q) % 4 == 0) &&
                    (!res || (reinterpret_cast<uintptr_t>(res) % 16 == 0 && reinterpret_cast<uintptr_t>(sum_out) % 16 == 0));
-  if (vec && D <= 512) ln_stats_kernel<2><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, eps, stats, partial, res, alpha, sum_out);
-  else if (vec && D <= 1024) ln_stats_kernel<4><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, eps, stats, partial, res, alpha, sum_out);
-  else ln_stats_kernel<0><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, eps, stats, partial, res, alpha, sum_out);
+  if (vec && D <= 512) ln_stats_kernel<2><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, eps, stats, partial, res, alpha, sum_out, zero_word);
+  else if (vec && D <= 1024) ln_stats_kernel<4><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, eps, stats, partial, res, alpha, sum_out, zero_word);
+  else ln_stats_kernel<0><<<g, kThreads, 0, st>>>(x, M, D, gamma, beta, eps, stats, partial, res, alpha, sum_out, zero_word);
   AQT_HIP(hipGetLastError());
   if (res) x = sum_out;   // the second pass normalises the sum the first pass wrote
   const int qm = q ? qmax_of(bits) : 1;

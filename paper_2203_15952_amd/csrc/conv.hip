@@ -333,9 +333,9 @@ int dw_partials(const ConvGeom &g) {
 
 aqt_status launch_corr(bool rev, const float *xin, const float *xmul, const float *w, const float *bias,
                        const float *na, const float *nb, int swish, const ConvGeom &g, float *out, float *dfac,
-                       uint32_t *absmax, hipStream_t st) {
+                       uint32_t *absmax, hipStream_t st, bool absmax_is_zero = false) {
   const int pl = rev ? g.kw - 1 - g.pad_left : g.pad_left;
-  if (absmax) zero_absmax_kernel<<<1, 64, 0, st>>>(absmax);
+  if (absmax && !absmax_is_zero) zero_absmax_kernel<<<1, 64, 0, st>>>(absmax);
   const int64_t blocks = static_cast<int64_t>(g.cgroups) * g.tgroups * g.B;
   if (g.kw <= kTapsMax && blocks < (int64_t(1) << 31)) {
     const size_t lds = static_cast<size_t>(kTile + 2 * g.kw - 1) * 64 * sizeof(float);
@@ -361,8 +361,9 @@ size_t dwconv_bwd_ws_bytes(int64_t C, int kw) {
 
 aqt_status launch_dwconv_fwd(const float *x, const float *w, const float *bias, const float *na, const float *nb,
                              int swish, int64_t B, int64_t T, int64_t C, int kw, int pad_left, float *out, float *dfac,
-                             uint32_t *absmax, hipStream_t st) {
-  return launch_corr(false, x, nullptr, w, bias, na, nb, swish, geom(B, T, C, kw, pad_left), out, dfac, absmax, st);
+                             uint32_t *absmax, hipStream_t st, bool absmax_is_zero) {
+  return launch_corr(false, x, nullptr, w, bias, na, nb, swish, geom(B, T, C, kw, pad_left), out, dfac, absmax, st,
+                     absmax_is_zero);
 }
 
 aqt_status launch_dwconv_bwd(const float *dout, const float *dmul, const float *x, const float *w, int64_t B, int64_t T,

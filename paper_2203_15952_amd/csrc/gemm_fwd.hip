@@ -526,9 +526,9 @@ aqt_status launch_prepare_weights(const void *wq_packed, int64_t K, int64_t N, i
 aqt_status launch_dense_fwd_q(const int8_t *xq, const float *s_x, const void *wq_packed, const float *s_w,
                               int64_t M, int64_t K, int64_t N, int bits_w, const float *bias, int epilogue,
                               float *y, int32_t *acc_out, uint32_t *y_absmax, void *ws, hipStream_t st,
-                              float *dact, bool ws_is_prepared) {
+                              float *dact, bool ws_is_prepared, bool absmax_is_zero) {
   const bool packed = packed4(bits_w);
-  if (y_absmax) {
+  if (y_absmax && !absmax_is_zero) {
     zero_word_kernel<<<1, 64, 0, st>>>(y_absmax);
     AQT_HIP(hipGetLastError());
   }
