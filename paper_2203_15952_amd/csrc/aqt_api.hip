@@ -510,7 +510,7 @@ const char *aqt_status_string(aqt_status s) {
 
 int aqt_last_hip_error(void) { return g_last_hip_error; }
 
-int aqt_version(void) { return 200; }
+int aqt_version(void) { return 201; }
 
 size_t aqt_packed_weight_bytes(int64_t K, int64_t N, int bits_w) {
   if (!shape_ok(K, N) || !bits_ok(bits_w)) return 0;

@@ -398,14 +398,14 @@ __global__ __launch_bounds__(kThreads) void quantize_weights_kernel(
                         blockIdx.x, blockIdx.y);
 }
 
-// Several weight matrices in one launch pair: gridDim.z walks the matrices, gridDim.x and .y cover the largest of
-// them, and a block outside its own matrix's grid leaves at once.  The arithmetic per matrix is that of the
+// Several weight matrices in one launch pair: a one-dimensional grid holds every matrix's own blocks one matrix
+// after the other (first1 / first2: where each matrix's blocks start).  The arithmetic per matrix is that of the
 // single-matrix kernels above.
 struct WeightJobDev {
   const float *w;
   int64_t K, N, rows_per_slab;
   int qmax, packed, slabs, vec4;
-  unsigned gx1, gx2, gy2;     // this matrix's own grid: abs-max columns, quantizer columns and fan-in chunks
+  unsigned gx1, gx2;          // this matrix's own grid width: abs-max column blocks, quantizer column blocks
   uint32_t *part;
   uint8_t *wq_packed;
   float *s_w;
@@ -415,20 +415,32 @@ struct WeightJobDev {
 };
 struct WeightJobsDev {
   WeightJobDev job[kWeightJobsMax];
+  unsigned first1[kWeightJobsMax + 1], first2[kWeightJobsMax + 1];   // block offsets; entries from n on: the grid size
+  int n;
 };
 
+// Which matrix a block belongs to (first[] ascends, first[0] = 0, blockIdx.x < first[n]).
+__device__ __forceinline__ int job_of_block(const unsigned *first, int n, unsigned b) {
+  int j = 0;
+#pragma unroll
+  for (int i = 1; i < kWeightJobsMax; ++i) j += (i < n && b >= first[i]) ? 1 : 0;
+  return j;
+}
+
 __global__ __launch_bounds__(kThreads) void wabsmax_partial_group_kernel(const WeightJobsDev jobs) {
-  const WeightJobDev &j = jobs.job[blockIdx.z];
-  if (blockIdx.x >= j.gx1 || blockIdx.y >= static_cast<unsigned>(j.slabs)) return;
-  wabsmax_partial_body(j.w, j.K, j.N, j.rows_per_slab, j.vec4, j.part, blockIdx.x, blockIdx.y);
+  const int ji = job_of_block(jobs.first1, jobs.n, blockIdx.x);
+  const WeightJobDev &j = jobs.job[ji];
+  const unsigned local = blockIdx.x - jobs.first1[ji];
+  wabsmax_partial_body(j.w, j.K, j.N, j.rows_per_slab, j.vec4, j.part, local % j.gx1, local / j.gx1);
 }
 
 __global__ __launch_bounds__(kThreads) void quantize_weights_group_kernel(const WeightJobsDev jobs,
                                                                           int32_t *dev_status) {
-  const WeightJobDev &j = jobs.job[blockIdx.z];
-  if (blockIdx.x >= j.gx2 || blockIdx.y >= j.gy2) return;
+  const int ji = job_of_block(jobs.first2, jobs.n, blockIdx.x);
+  const WeightJobDev &j = jobs.job[ji];
+  const unsigned local = blockIdx.x - jobs.first2[ji];
   quantize_weights_body(j.w, j.K, j.N, j.qmax, j.packed, j.part, j.slabs, j.wq_packed, j.s_w, j.wq_kn, j.mask_w,
-                        dev_status, j.wfrag, blockIdx.x, blockIdx.y);
+                        dev_status, j.wfrag, local % j.gx2, local / j.gx2);
 }
 
 __global__ __launch_bounds__(kThreads) void zero_words_kernel(uint32_t *p, int64_t n) {
@@ -576,13 +588,13 @@ aqt_status launch_quantize_weights_group(const WeightJob *jobs, int n, hipStream
     return launch_quantize_weights(jobs[0].w, jobs[0].K, jobs[0].N, jobs[0].bits_w, jobs[0].wq_packed, jobs[0].s_w,
                                    jobs[0].wq_kn, jobs[0].mask_w, jobs[0].part, st, dev_status, jobs[0].wfrag);
   WeightJobsDev d;
-  unsigned gx1 = 0, gy1 = 0, gx2 = 0, gy2 = 0;
+  uint64_t b1 = 0, b2 = 0;     // blocks so far in the two grids
   for (int i = 0; i < n; ++i) {
     const WeightJob &a = jobs[i];
     if (!a.w || !a.wq_packed || !a.s_w || !a.part || a.K < 1 || a.N < 1) return AQT_ERR_INVALID_ARG;
     if (a.wfrag && (a.N % kWCols != 0 || a.K % kWChunk != 0 || reinterpret_cast<uintptr_t>(a.wfrag) % 16 != 0))
       return AQT_ERR_INVALID_ARG;
-    if (cdiv(a.N, kWCols) > 0x7FFFFFFF || cdiv(a.K, kWChunk) > 65535) return AQT_ERR_UNSUPPORTED;
+    if (cdiv(a.N, kWCols) * cdiv(a.K, kWChunk) > 0x0FFFFFFF) return AQT_ERR_UNSUPPORTED;   // 8 of them stay under 2^31
     if (a.mask_w) {
       const int64_t words = cdiv(a.K * a.N, 32);
       zero_words_kernel<<<grid_for(words, kThreads, 1024), kThreads, 0, st>>>(a.mask_w, words);
@@ -598,18 +610,23 @@ aqt_status launch_quantize_weights_group(const WeightJob *jobs, int n, hipStream
     j.vec4 = (a.N % 4 == 0) && (reinterpret_cast<uintptr_t>(a.w) % 16 == 0);
     j.gx1 = static_cast<unsigned>(cdiv(a.N, 64));
     j.gx2 = static_cast<unsigned>(cdiv(a.N, kWCols));
-    j.gy2 = static_cast<unsigned>(cdiv(a.K, kWChunk));
+    d.first1[i] = static_cast<unsigned>(b1);
+    d.first2[i] = static_cast<unsigned>(b2);
+    b1 += static_cast<uint64_t>(j.gx1) * static_cast<uint64_t>(slabs);
+    b2 += static_cast<uint64_t>(j.gx2) * static_cast<uint64_t>(cdiv(a.K, kWChunk));
     j.part = a.part; j.wq_packed = static_cast<uint8_t *>(a.wq_packed); j.s_w = a.s_w; j.wq_kn = a.wq_kn;
     j.mask_w = a.mask_w; j.wfrag = static_cast<uint4 *>(a.wfrag);
-    gx1 = j.gx1 > gx1 ? j.gx1 : gx1;
-    gy1 = static_cast<unsigned>(slabs) > gy1 ? static_cast<unsigned>(slabs) : gy1;
-    gx2 = j.gx2 > gx2 ? j.gx2 : gx2;
-    gy2 = j.gy2 > gy2 ? j.gy2 : gy2;
   }
-  for (int i = n; i < kWeightJobsMax; ++i) d.job[i] = d.job[0];   // never indexed: gridDim.z is n
-  wabsmax_partial_group_kernel<<<dim3(gx1, gy1, static_cast<unsigned>(n)), kThreads, 0, st>>>(d);
+  for (int i = n; i < kWeightJobsMax; ++i) d.job[i] = d.job[0];   // never selected: job_of_block stops at n
+  for (int i = n; i <= kWeightJobsMax; ++i) {
+    d.first1[i] = static_cast<unsigned>(b1);
+    d.first2[i] = static_cast<unsigned>(b2);
+  }
+  d.n = n;
+  if (b1 > 0x7FFFFFFFu || b2 > 0x7FFFFFFFu) return AQT_ERR_UNSUPPORTED;
+  wabsmax_partial_group_kernel<<<static_cast<unsigned>(b1), kThreads, 0, st>>>(d);
   AQT_HIP(hipGetLastError());
-  quantize_weights_group_kernel<<<dim3(gx2, gy2, static_cast<unsigned>(n)), kThreads, 0, st>>>(d, dev_status);
+  quantize_weights_group_kernel<<<static_cast<unsigned>(b2), kThreads, 0, st>>>(d, dev_status);
   AQT_HIP(hipGetLastError());
   return AQT_OK;
 }
