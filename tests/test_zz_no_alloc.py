@@ -39,15 +39,15 @@ def test_static_scratch_forward_two_calls_in_a_row():
         y = torch.empty_like(y_ws)
         prepared.append((c, ora, xq, s_x, wq, s_w, bias, y_ws, y))
     torch.cuda.synchronize()
-    # Round 0 looks the array up and makes the runtime load every kernel the three shapes use
-    # (which takes device memory of its own); round 1 must then leave the free memory alone.
-    for rnd in range(2):
+    # Pass 0 looks the array up and makes the runtime load every kernel the three shapes use
+    # (which takes device memory of its own); pass 1 must then leave the free memory alone.
+    for pass_no in range(2):
         free_before = torch.cuda.mem_get_info()[0]
         for (M, K, N, bx, bw, epi), (c, ora, xq, s_x, wq, s_w, bias, y_ws, y) in zip(cases, prepared):
             y.fill_(float("nan"))
             B.aqt_dense_fwd_q_static(xq, s_x, wq, s_w, N, bx, bw, bias=bias, epilogue=epi, y=y)
         torch.cuda.synchronize()
-        if rnd == 1:
+        if pass_no == 1:
             assert torch.cuda.mem_get_info()[0] >= free_before, "device memory was allocated by the calls"
     for (M, K, N, bx, bw, epi), (c, ora, xq, s_x, wq, s_w, bias, y_ws, y) in zip(cases, prepared):
         np.testing.assert_array_equal(host(y), host(y_ws))
