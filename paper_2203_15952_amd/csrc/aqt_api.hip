@@ -826,11 +826,11 @@ aqt_status aqt_ffn_bwd(const float *dy, const aqt_ffn_saved *saved, int64_t M, i
   const size_t a = bwd_workspace_bytes(M, D, H), b = bwd_workspace_bytes(M, H, D);
   const size_t core = a > b ? a : b;
   float *dh = reinterpret_cast<float *>(static_cast<uint8_t *>(ws) + core);
-  // second layer (no activation): gradient with respect to h, dw2, db2
-  AQT_TRY(launch_dense_bwd(dy, &l2, M, H, D, dh, dw2, db2, ws, core, st));
-  if (!dxn && !dw1 && !db1) return AQT_OK;
-  // through the Swish, in place, then the first layer
-  AQT_TRY(launch_dact_mul(dh, l1.dact, M, H, H, dh, st));
+  // second layer (no activation): dw2, db2 and the gradient with respect to h, which leaves the kernel already
+  // multiplied by the Swish derivative the first layer's forward stored; then the first layer
+  const bool more = dxn || dw1 || db1;
+  AQT_TRY(launch_dense_bwd(dy, &l2, M, H, D, dh, dw2, db2, ws, core, st, more ? l1.dact : nullptr));
+  if (!more) return AQT_OK;
   return launch_dense_bwd(dh, &l1, M, D, H, dxn, dw1, db1, ws, core, st);
 }
 

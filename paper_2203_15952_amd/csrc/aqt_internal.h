@@ -110,9 +110,10 @@ aqt_status launch_dense_fwd_wonly(const float *x, const void *wq_packed, const f
 
 // ---- straight-through backward (gemm_bwd.hip) -------------------------------------
 size_t bwd_workspace_bytes(int64_t M, int64_t K, int64_t N);
+// dx_factor (optional, [M,K]): dx leaves multiplied elementwise by it (the previous layer's activation derivative)
 aqt_status launch_dense_bwd(const float *dy, const aqt_saved *sv, int64_t M, int64_t K, int64_t N,
                             float *dx, float *dw, float *dbias, void *ws, size_t ws_bytes,
-                            hipStream_t st);
+                            hipStream_t st, const float *dx_factor = nullptr);
 
 // ---- block pieces (block.hip) -----------------------------------------------------------
 size_t layernorm_ws_bytes(int64_t M);

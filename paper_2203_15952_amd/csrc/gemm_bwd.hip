@@ -208,6 +208,8 @@ constexpr int waitcnt_imm(int vm, int lgkm) {
 // epilogue applies the per-channel scale, the bias and the activation.
 //   MODE 0 / 1 : dX without / with a clip mask
 //   MODE 2 + e : weight-only forward with epilogue e (none, Swish, GLU)
+//   MODE 5     : dX without a clip mask, times an elementwise factor [M,K] on the way out (`bias` points at it):
+//                the gradient that reaches the previous layer through its activation, with no pass of its own
 // Names follow dX: `dy` is the float operand [M,N], N the contraction length, K the
 // number of output columns (for GLU: value and gate channels together).
 template <int TM, int TN, int MODE, int WN = 2>
@@ -216,7 +218,8 @@ __device__ __forceinline__ void f32_codes_tile(
     const float *__restrict__ s_x, const uint32_t *__restrict__ mask_x, const float *__restrict__ bias, int M,
     int K, int N, float *__restrict__ dx, int tiles_m, int tiles_c) {
   constexpr bool MASKED = (MODE == 1);
-  constexpr bool WONLY = (MODE >= 2);
+  constexpr bool WONLY = (MODE >= 2 && MODE <= 4);
+  constexpr bool TIMES = (MODE == 5);
   constexpr int EPI = WONLY ? MODE - 2 : AQT_EPI_NONE;
   // Workgroup = 2 x WN wavefronts.  With WN = 4 the float operand tile is staged (and
   // scaled, split) once for four column wavefronts instead of two, which halves the
@@ -450,6 +453,22 @@ __device__ __forceinline__ void f32_codes_tile(
           __builtin_nontemporal_store(mask_bit(mask_x, tile0 + off) ? acc[i][j][r] : 0.0f, obase + off);
         }
       }
+  } else if (TIMES) {
+    const float keep = (s_x[0] != 0.0f) ? 1.0f : 0.0f;
+    const float *fbase = bias + static_cast<int64_t>(m0) * K + c0;   // the factor has dx's layout
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row_off = (i * 32 + 8 * (r >> 2) + (r & 3)) * K;
+        float f[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) f[j] = __builtin_nontemporal_load(fbase + row_off + j * 32 + lane_off);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          __builtin_nontemporal_store((keep != 0.0f) ? acc[i][j][r] * f[j] : 0.0f,
+                                      obase + row_off + j * 32 + lane_off);
+      }
   } else {
     const float keep = (s_x[0] != 0.0f) ? 1.0f : 0.0f;   // NULL mask: "the scale is non-zero"
 #pragma unroll
@@ -476,6 +495,15 @@ __global__ __launch_bounds__(128 * WN, WN == 2 ? 2 : 1) void bwd_dx_mfma_kernel(
     const float *__restrict__ s_x, const uint32_t *__restrict__ mask_x, int M, int K, int N,
     float *__restrict__ dx, int tiles_m, int tiles_c) {
   f32_codes_tile<TM, TN, MASKED ? 1 : 0, WN>(dy, wq_frag, s_w, s_x, mask_x, nullptr, M, K, N, dx, tiles_m, tiles_c);
+}
+
+// dX times an elementwise factor of its own shape (no clip mask).
+template <int TM, int TN, int WN = 2>
+__global__ __launch_bounds__(128 * WN, WN == 2 ? 2 : 1) void bwd_dx_times_mfma_kernel(
+    const float *__restrict__ dy, const v4i *__restrict__ wq_frag, const float *__restrict__ s_w,
+    const float *__restrict__ s_x, const float *__restrict__ factor, int M, int K, int N, float *__restrict__ dx,
+    int tiles_m, int tiles_c) {
+  f32_codes_tile<TM, TN, 5, WN>(dy, wq_frag, s_w, s_x, nullptr, factor, M, K, N, dx, tiles_m, tiles_c);
 }
 
 // Weight-only forward (Sec. 4.1, I8W / I4W): y = act((x . wq) * s_w + bias), x float32 [M,K],
@@ -828,10 +856,17 @@ BwdPlan plan_bwd(int64_t M, int64_t K, int64_t N) {
 
 template <int TM, int TN, int WN = 2>
 aqt_status launch_dx(const float *dy, const v4i *wq_frag, const aqt_saved *sv, int64_t M, int64_t K, int64_t N,
-                     float *dx, hipStream_t st) {
+                     float *dx, hipStream_t st, const float *factor = nullptr) {
   constexpr int BM = 64 * TM, BC = 32 * TN * WN;
-  auto kern = sv->mask_x ? bwd_dx_mfma_kernel<TM, TN, true, WN> : bwd_dx_mfma_kernel<TM, TN, false, WN>;
   const int tiles_m = static_cast<int>(cdiv(M, BM)), tiles_c = static_cast<int>(K / BC);
+  if (factor) {   // the caller has checked that there is no clip mask
+    bwd_dx_times_mfma_kernel<TM, TN, WN><<<tiles_m * tiles_c, 128 * WN, 0, st>>>(
+        dy, wq_frag, sv->s_w, sv->s_x, factor, static_cast<int>(M), static_cast<int>(K), static_cast<int>(N), dx,
+        tiles_m, tiles_c);
+    AQT_HIP(hipGetLastError());
+    return AQT_OK;
+  }
+  auto kern = sv->mask_x ? bwd_dx_mfma_kernel<TM, TN, true, WN> : bwd_dx_mfma_kernel<TM, TN, false, WN>;
   kern<<<tiles_m * tiles_c, 128 * WN, 0, st>>>(dy, wq_frag, sv->s_w, sv->s_x, sv->mask_x, static_cast<int>(M),
                                                   static_cast<int>(K), static_cast<int>(N), dx, tiles_m, tiles_c);
   AQT_HIP(hipGetLastError());
@@ -939,7 +974,8 @@ aqt_status launch_dense_fwd_wonly(const float *x, const void *wq_packed, const f
 size_t bwd_workspace_bytes(int64_t M, int64_t K, int64_t N) { return plan_bwd(M, K, N).total; }
 
 aqt_status launch_dense_bwd(const float *dy, const aqt_saved *sv, int64_t M, int64_t K, int64_t N, float *dx,
-                            float *dw, float *dbias, void *ws, size_t ws_bytes, hipStream_t st) {
+                            float *dw, float *dbias, void *ws, size_t ws_bytes, hipStream_t st,
+                            const float *dx_factor) {
   (void)ws_bytes;
   const BwdPlan p = plan_bwd(M, K, N);
   uint8_t *base = static_cast<uint8_t *>(ws);
@@ -955,13 +991,17 @@ aqt_status launch_dense_bwd(const float *dy, const aqt_saved *sv, int64_t M, int
       if (g > 2048) g = 2048;
       codes_to_bf16_frag_kernel<<<g, kThreads, 0, st>>>(sv->wq_kn, static_cast<int>(K), static_cast<int>(N), 0, wq_frag);
       AQT_HIP(hipGetLastError());
-      if (p.dx_wide8) AQT_TRY((launch_dx<2, 4, 4>(dy, wq_frag, sv, M, K, N, dx, st)));
-      else if (p.dx_wide) AQT_TRY((launch_dx<2, 4>(dy, wq_frag, sv, M, K, N, dx, st)));
-      else AQT_TRY((launch_dx<2, 2>(dy, wq_frag, sv, M, K, N, dx, st)));
+      // the factor rides in the epilogue when there is no clip mask and it can be read like dx is written
+      const float *fused = (dx_factor && !sv->mask_x) ? dx_factor : nullptr;
+      if (p.dx_wide8) AQT_TRY((launch_dx<2, 4, 4>(dy, wq_frag, sv, M, K, N, dx, st, fused)));
+      else if (p.dx_wide) AQT_TRY((launch_dx<2, 4>(dy, wq_frag, sv, M, K, N, dx, st, fused)));
+      else AQT_TRY((launch_dx<2, 2>(dy, wq_frag, sv, M, K, N, dx, st, fused)));
+      if (dx_factor && !fused) AQT_TRY(launch_dact_mul(dx, dx_factor, M, K, K, dx, st));
     } else {
       bwd_dx_general_kernel<<<static_cast<int>(cdiv(M * K, kThreads)), kThreads, 0, st>>>(
           dy, sv->wq_kn, sv->s_w, sv->s_x, sv->mask_x, M, K, N, dx);
       AQT_HIP(hipGetLastError());
+      if (dx_factor) AQT_TRY(launch_dact_mul(dx, dx_factor, M, K, K, dx, st));
     }
   }
   if (dw) {
