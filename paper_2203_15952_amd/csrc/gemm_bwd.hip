@@ -456,19 +456,25 @@ __device__ __forceinline__ void f32_codes_tile(
   } else if (TIMES) {
     const float keep = (s_x[0] != 0.0f) ? 1.0f : 0.0f;
     const float *fbase = bias + static_cast<int64_t>(m0) * K + c0;   // the factor has dx's layout
+    // the main loop's registers are free by now: all factors of a 32-row block are requested before the first is used
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+      float f[16][TN];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row_off = (i * 32 + 8 * (r >> 2) + (r & 3)) * K;
-        float f[TN];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) f[j] = __builtin_nontemporal_load(fbase + row_off + j * 32 + lane_off);
+        for (int j = 0; j < TN; ++j) f[r][j] = __builtin_nontemporal_load(fbase + row_off + j * 32 + lane_off);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row_off = (i * 32 + 8 * (r >> 2) + (r & 3)) * K;
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          __builtin_nontemporal_store((keep != 0.0f) ? acc[i][j][r] * f[j] : 0.0f,
+          __builtin_nontemporal_store((keep != 0.0f) ? acc[i][j][r] * f[r][j] : 0.0f,
                                       obase + row_off + j * 32 + lane_off);
       }
+    }
   } else {
     const float keep = (s_x[0] != 0.0f) ? 1.0f : 0.0f;   // NULL mask: "the scale is non-zero"
 #pragma unroll
